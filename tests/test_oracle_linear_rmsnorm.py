@@ -1,0 +1,111 @@
+"""Pins for the oracle's linear + LoRA and noisy RMSNorm (CPU only)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import qerl_synth as qs
+from oracle import nvfp4_oracle as o
+
+
+def _tiny(N, K, M, r, seed):
+    W = qs.weights(N, K, seed).float().numpy()
+    x = qs.activations(M, K, seed + 1).float().numpy()
+    A, B = qs.lora_pair(N, K, max(r, 1), seed + 2)
+    A, B = A.float().numpy()[:r], B.float().numpy()[:, :r]
+    return W, x, A, B
+
+
+@pytest.mark.parametrize("N,K,M,r", [(5, 16, 1, 0), (8, 32, 3, 2), (3, 48, 2, 1)])
+def test_linear_brute_force_python_loops(N, K, M, r):
+    W, x, A, B = _tiny(N, K, M, r, seed=21)
+    codes, scales, S32 = o.nvfp4_quantize(W)
+    Wh = o.nvfp4_dequantize(codes, scales, S32)
+    s = 2.0
+    y = o.nvfp4_lora_linear(x, codes, scales, S32, A if r else None, B if r else None, s)
+    assert y.shape == (M, N)
+    for m in range(M):
+        for n in range(N):
+            acc = 0.0
+            for k in range(K):
+                acc += float(x[m, k]) * float(Wh[n, k])
+            lo = 0.0
+            for j in range(r):
+                t = 0.0
+                for k in range(K):
+                    t += float(x[m, k]) * float(A[j, k])
+                lo += t * float(B[n, j])
+            want = acc + s * lo
+            assert abs(y[m, n] - want) <= 1e-12 * (1 + abs(want))
+
+
+def test_one_hot_input_reads_out_a_weight_column():
+    W, x, A, B = _tiny(6, 32, 1, 0, seed=5)
+    codes, scales, S32 = o.nvfp4_quantize(W)
+    Wh = o.nvfp4_dequantize(codes, scales, S32)
+    for k in (0, 15, 16, 31):
+        x1 = np.zeros((1, 32), dtype=np.float32)
+        x1[0, k] = 1.0
+        y = o.nvfp4_lora_linear(x1, codes, scales, S32)
+        assert np.array_equal(y[0], Wh[:, k].astype(np.float64))
+
+
+def test_dense_merge_equivalence_and_library_matmul():
+    """x (W_hat + s B A)^T equals the two-branch form (Eq. 2); and with the
+    weights dequantised the op is a textbook GEMM (torch.matmul, fp64)."""
+    N, K, M, r = 24, 64, 5, 4
+    W, x, A, B = _tiny(N, K, M, r, seed=8)
+    codes, scales, S32 = o.nvfp4_quantize(W)
+    y = o.nvfp4_lora_linear(x, codes, scales, S32, A, B, 2.0)
+    Wh = torch.from_numpy(o.nvfp4_dequantize(codes, scales, S32)).double()
+    merged = Wh + 2.0 * torch.from_numpy(B).double() @ torch.from_numpy(A).double()
+    want = torch.from_numpy(x).double() @ merged.T
+    assert np.allclose(y, want.numpy(), rtol=1e-12, atol=1e-13)
+    y0 = o.nvfp4_lora_linear(x, codes, scales, S32)
+    assert np.allclose(y0, (torch.from_numpy(x).double() @ Wh.T).numpy(), rtol=1e-13, atol=1e-14)
+    # r = 0 and lora_scale = 0 both switch the branch off
+    assert np.array_equal(y0, o.nvfp4_lora_linear(x, codes, scales, S32, A, B, 0.0))
+    # fp32 accumulation variant stays within fp32 rounding of the fp64 one
+    y32 = o.nvfp4_lora_linear(x, codes, scales, S32, A, B, 2.0, acc_dtype=np.float32)
+    assert np.allclose(y32, y, rtol=1e-4, atol=1e-5)
+
+
+def test_rmsnorm_plain_formula_and_library():
+    M, H = 3, 96
+    x = qs.activations(M, H, 31).float().numpy() * 3
+    g = qs.rms_gain(H, 32).float().numpy()
+    y = o.aqn_rmsnorm(x, g, None, eps=1e-6)
+    for m in range(M):
+        ms = sum(float(v) ** 2 for v in x[m]) / H
+        for k in range(H):
+            want = float(g[k]) * float(x[m, k]) / math.sqrt(ms + 1e-6)
+            assert abs(y[m, k] - want) <= 1e-14 * (1 + abs(want))
+    lib = torch.nn.functional.rms_norm(torch.from_numpy(x).double(), (H,),
+                                       torch.from_numpy(g).double(), eps=1e-6)
+    assert np.allclose(y, lib.numpy(), rtol=1e-13, atol=0)
+
+
+def test_rmsnorm_noise_identities():
+    """Appendix "Proof of Noise Sharing": RMSNorm_noise(x) = (Z/w + 1) (.) RMSNorm(x),
+    and feeding it to a linear equals the clean norm times row-scaled weights."""
+    M, H, N = 4, 64, 10
+    x = qs.activations(M, H, 41).float().numpy()
+    g = qs.rms_gain(H, 42).float().numpy()
+    Z = qs.aqn_noise(H, 1e-2, 43).numpy()
+    y_noise = o.aqn_rmsnorm(x, g, Z)
+    y_clean = o.aqn_rmsnorm(x, g, None)
+    factor = Z.astype(np.float64) / g.astype(np.float64) + 1.0
+    assert np.allclose(y_noise, factor * y_clean, rtol=1e-13, atol=0)
+    assert not np.allclose(y_noise, y_clean, rtol=1e-5, atol=0)
+    W = qs.weights(N, H, 44).float().numpy()
+    codes, scales, S32 = o.nvfp4_quantize(W)
+    Wh = o.nvfp4_dequantize(codes, scales, S32).astype(np.float64)
+    lhs = y_noise @ Wh.T
+    rhs = y_clean @ (factor[None, :] * Wh).T
+    assert np.allclose(lhs, rhs, rtol=1e-12, atol=1e-14)
+    # eps sits inside the square root: an all-zero row maps to zero, not NaN
+    z = o.aqn_rmsnorm(np.zeros((1, H), dtype=np.float32), g, Z)
+    assert not z.any()
+    # zero noise vector == no noise
+    assert np.array_equal(o.aqn_rmsnorm(x, g, np.zeros(H, dtype=np.float32)), y_clean)

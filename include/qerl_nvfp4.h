@@ -1,0 +1,142 @@
+/*
+ * qerl_nvfp4.h -- C ABI of the MI355X (gfx950) NVFP4 + LoRA linear library.
+ *
+ * The hot path of QeRL's rollout phase: a weight-only NVFP4 linear layer with
+ * a fused LoRA branch, fed by an RMSNorm whose gain carries the Adaptive
+ * Quantization Noise.
+ *
+ * Conventions (all entry points)
+ *   - Plain C.  Every pointer is a DEVICE pointer unless its comment says host.
+ *   - The caller owns every buffer; the library allocates nothing and keeps
+ *     no reference after the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All device work is enqueued on it and is asynchronous; the library never
+ *     synchronises.  Results are valid once the stream reaches that point.
+ *   - bf16 tensors are row-major with a leading dimension in ELEMENTS.
+ *   - Return value: QERL_OK, or a negative code for a misuse detected on the
+ *     host before anything was launched (nothing has been written then), or
+ *     QERL_ERR_LAUNCH if the HIP runtime refused a launch
+ *     (qerl_last_hip_error() returns its hipError_t).
+ *   - Weight matrix orientation: W[N, K] = out-features x in-features, K
+ *     contiguous; scale blocks of 16 run along K.
+ *
+ * Canonical NVFP4 tensor (Section 3.3 "NVFP4 Quantization", Eq. 6; element
+ * format from the Preliminary section):
+ *   codes  [N, K/2]  uint8 : two E2M1 codes per byte, low nibble = even k,
+ *                            bit 3 of a code is the sign
+ *   scales [N, K/16] uint8 : one FP8 E4M3 byte per 16 weights, sign bit clear
+ *   tensor_scale   1 float : the FP32 per-tensor scale (device memory)
+ *   W_hat[n,k] = tensor_scale * ( E4M3(scales[n,k/16]) * E2M1(code[n,k]) )
+ */
+#ifndef QERL_NVFP4_H
+#define QERL_NVFP4_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define QERL_API __attribute__((visibility("default")))
+
+#define QERL_OK              0
+#define QERL_ERR_NULL       -1  /* a required pointer is NULL                          */
+#define QERL_ERR_SHAPE      -2  /* M,N < 0, K % 16 != 0, ld < row length, r < 0, ...   */
+#define QERL_ERR_ALIGN      -3  /* pointer not 16-byte aligned or ld % 8 != 0          */
+#define QERL_ERR_WORKSPACE  -4  /* workspace NULL or smaller than *_workspace_bytes()  */
+#define QERL_ERR_LAUNCH     -5  /* HIP runtime error; see qerl_last_hip_error()        */
+
+/* Host.  Static string for a status code. */
+QERL_API const char* qerl_status_string(int status);
+/* Host.  hipError_t of the most recent QERL_ERR_LAUNCH on this thread (0 if none). */
+QERL_API int qerl_last_hip_error(void);
+
+/* ---------------------------------------------------------------------------
+ * nvfp4_quantize -- W[N,K] bf16  ->  canonical NVFP4 (codes, scales, tensor_scale).
+ *
+ * The paper gives only the dequantisation (Eq. 6); the rule implemented is
+ * the round-to-nearest chain, every step in IEEE fp32 in this order:
+ *     tensor_scale = amax / 2688                (2688 = 6 * 448; 1 if amax = 0)
+ *     scale        = E4M3_rne_sat( (block_amax / 6) / tensor_scale )
+ *     code         = E2M1_rne_sat( w / (tensor_scale * scale) ), sign = sign(w)
+ * A block whose scale byte is 0 stores magnitude 0.  Non-finite weights are
+ * not supported (result unspecified).  Output is bit-exact reproducible.
+ *
+ *   W            [N, ldw] bf16, ldw >= K, ldw % 8 == 0, 16-byte aligned
+ *   codes        [N, K/2]  out, 8-byte aligned
+ *   scales       [N, K/16] out
+ *   tensor_scale 1 float   out
+ *   workspace    scratch of >= nvfp4_quantize_workspace_bytes(N,K) bytes,
+ *                4-byte aligned; contents on entry are ignored
+ * Errors: NULL pointers; N < 0, K < 0, K % 16 != 0, ldw < K; alignment;
+ * workspace too small.  N == 0 or K == 0 writes tensor_scale = 1 only.
+ */
+QERL_API int nvfp4_quantize(const void* W_bf16, int64_t N, int64_t K, int64_t ldw,
+                   uint8_t* codes, uint8_t* scales, float* tensor_scale,
+                   void* workspace, size_t workspace_bytes, void* stream);
+QERL_API size_t nvfp4_quantize_workspace_bytes(int64_t N, int64_t K);   /* host */
+
+/* ---------------------------------------------------------------------------
+ * nvfp4_dequantize -- Eq. 6, element by element in fp32 (test/inspection aid).
+ *   W_f32 [N, K] out, fp32 row-major.
+ */
+QERL_API int nvfp4_dequantize(const uint8_t* codes, const uint8_t* scales, const float* tensor_scale,
+                     int64_t N, int64_t K, float* W_f32, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * nvfp4_lora_linear --
+ *   y[M,N] = tensor_scale * ( x . (scales (.) codes)^T ) + lora_scale * (x . A^T) . B^T
+ * (Eq. 6 for the main branch, Eq. 2 for the low-rank branch W + B A; lora_scale
+ * is alpha / r from Algorithm 1's "LoRA rank, LoRA alpha" inputs).  Products are
+ * exact, sums are fp32, x A^T is kept in fp32, the result is rounded once to
+ * bf16 (nearest-even).  The summation order is fixed: results are bit-identical
+ * from call to call.
+ *
+ *   x   [M, ldx] bf16            A [r, K] bf16 (dense, or NULL when r == 0)
+ *   y   [M, ldy] bf16 out        B [N, r] bf16 (dense, or NULL when r == 0)
+ *   workspace: >= nvfp4_lora_linear_workspace_bytes(M,N,K,r) bytes, 256-byte
+ *     aligned, prepared ONCE with qerl_workspace_init() and afterwards used
+ *     only by this library.  Calls that share a workspace must be ordered on
+ *     one stream.  A call that returned an error leaves it valid.
+ *
+ * Any M >= 0 is accepted (M == 0 is a no-op).  M <= 16 takes the
+ * bandwidth-bound decode kernels, larger M the MFMA GEMM kernels; shapes the
+ * tiled kernels do not cover (K % 64 != 0) take a slower general kernel.
+ * Errors: NULL pointers (A/B only when r > 0); M,N,K,r < 0, K % 16 != 0,
+ * ldx < K, ldy < N; x/y not 16-byte aligned, ldx % 8 or ldy % 8 != 0, codes
+ * or scales or A or B not 16-byte aligned; workspace.
+ */
+QERL_API int nvfp4_lora_linear(const void* x_bf16, int64_t M, int64_t K, int64_t ldx,
+                      const uint8_t* codes, const uint8_t* scales, const float* tensor_scale,
+                      int64_t N,
+                      const void* A_bf16, const void* B_bf16, int64_t r, float lora_scale,
+                      void* y_bf16, int64_t ldy,
+                      void* workspace, size_t workspace_bytes, void* stream);
+QERL_API size_t nvfp4_lora_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t r); /* host */
+
+/* Zero the control words of a linear workspace.  Call once after allocating
+ * it (and again if a kernel using it was ever aborted). */
+QERL_API int qerl_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * aqn_rmsnorm -- y = (gain + noise) (.) x / sqrt(mean_k(x^2) + eps)   (Eq. 10)
+ * gain + noise is formed in fp32 and not re-rounded; eps is inside the root;
+ * one final rounding to bf16.  noise == NULL is stage 0 (sigma = 0): the plain
+ * RMSNorm.
+ *   x [M, ldx] bf16, gain [H] bf16, noise [H] fp32 or NULL, y [M, ldy] bf16 out
+ * Errors: NULL x/gain/y; M < 0, H < 1, ld < H.  No alignment requirement
+ * (16-byte aligned rows with H % 8 == 0 take the vector kernel).
+ */
+QERL_API int aqn_rmsnorm(const void* x_bf16, int64_t M, int64_t H, int64_t ldx,
+                const void* gain_bf16, const float* noise_f32, float eps,
+                void* y_bf16, int64_t ldy, void* stream);
+
+/* Host.  Eq. 8: sigma(k) = s0 * (s1/s0)^((k-1)/(K-1)), k = 1..K; k = 0 -> 0
+ * (Algorithm 1: stage 0 carries quantisation noise only).  NaN on bad stage. */
+QERL_API double aqn_sigma(int stage_k, int num_stages, double sigma_start, double sigma_end);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QERL_NVFP4_H */

@@ -1,0 +1,10 @@
+"""MI355X-native NVFP4 + LoRA linear with AQN RMSNorm (QeRL rollout hot path).
+
+The work is done by hand-written HIP kernels in libqerl_nvfp4.so behind the C
+ABI of include/qerl_nvfp4.h; this package only marshals torch GPU tensors to it.
+"""
+from .binding import (  # noqa: F401
+    EXPORTED_SYMBOLS, LIB_PATH, QerlError, Workspace, aqn_rmsnorm, aqn_sigma, load_library,
+    nvfp4_dequantize, nvfp4_lora_linear, nvfp4_lora_linear_workspace_bytes, nvfp4_quantize,
+    nvfp4_quantize_workspace_bytes,
+)

@@ -1,0 +1,204 @@
+"""ctypes binding of libqerl_nvfp4.so: argument marshalling only.
+
+Every function takes torch tensors living on the GPU, checks dtypes/devices,
+and passes raw device pointers, sizes and the current HIP stream to the C ABI
+declared in include/qerl_nvfp4.h.  No arithmetic of the method happens here and
+there is no fallback: if the library is missing or a tensor is not on the GPU
+the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqerl_nvfp4.so")
+
+_c_i64 = ctypes.c_int64
+_c_sz = ctypes.c_size_t
+_c_p = ctypes.c_void_p
+
+_SIGNATURES = {
+    "qerl_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+    "qerl_last_hip_error": (ctypes.c_int, []),
+    "nvfp4_quantize": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_p, _c_p, _c_p, _c_sz, _c_p]),
+    "nvfp4_quantize_workspace_bytes": (_c_sz, [_c_i64, _c_i64]),
+    "nvfp4_dequantize": (ctypes.c_int, [_c_p, _c_p, _c_p, _c_i64, _c_i64, _c_p, _c_p]),
+    "nvfp4_lora_linear": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_p, _c_p, _c_i64,
+                                         _c_p, _c_p, _c_i64, ctypes.c_float, _c_p, _c_i64,
+                                         _c_p, _c_sz, _c_p]),
+    "nvfp4_lora_linear_workspace_bytes": (_c_sz, [_c_i64, _c_i64, _c_i64, _c_i64]),
+    "qerl_workspace_init": (ctypes.c_int, [_c_p, _c_sz, _c_p]),
+    "aqn_rmsnorm": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_p, ctypes.c_float,
+                                   _c_p, _c_i64, _c_p]),
+    "aqn_sigma": (ctypes.c_double, [ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_double]),
+}
+
+EXPORTED_SYMBOLS = tuple(_SIGNATURES)
+
+_lib = None
+
+
+class QerlError(RuntimeError):
+    def __init__(self, fn: str, status: int, detail: str):
+        super().__init__(f"{fn} failed with status {status}: {detail}")
+        self.status = status
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} not found: build it with `python -m paper_2510_11696_amd.build`")
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def _check(fn: str, status: int) -> None:
+    if status != 0:
+        lib = load_library()
+        detail = lib.qerl_status_string(status).decode()
+        if status == -5:
+            detail += f" (hipError_t {lib.qerl_last_hip_error()})"
+        raise QerlError(fn, status, detail)
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> int:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a GPU tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _rows(t: torch.Tensor, name: str):
+    """(rows, cols, leading dimension) of a 2-D tensor with unit inner stride."""
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError(f"{name} must be 2-D with contiguous rows")
+    ld = t.stride(0) if t.shape[0] > 1 else max(t.shape[1], t.stride(0))
+    return t.shape[0], t.shape[1], ld
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+class Workspace:
+    """Device scratch for nvfp4_lora_linear, initialised once."""
+
+    def __init__(self, nbytes: int, device="cuda"):
+        self.buf = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+        assert self.buf.data_ptr() % 256 == 0
+        _check("qerl_workspace_init",
+               load_library().qerl_workspace_init(self.buf.data_ptr(), self.buf.numel(), _stream()))
+
+    @property
+    def ptr(self) -> int:
+        return self.buf.data_ptr()
+
+    @property
+    def nbytes(self) -> int:
+        return self.buf.numel()
+
+
+def aqn_sigma(stage: int, num_stages: int, sigma_start: float, sigma_end: float) -> float:
+    return float(load_library().aqn_sigma(stage, num_stages, sigma_start, sigma_end))
+
+
+def nvfp4_quantize_workspace_bytes(N: int, K: int) -> int:
+    return int(load_library().nvfp4_quantize_workspace_bytes(N, K))
+
+
+def nvfp4_lora_linear_workspace_bytes(M: int, N: int, K: int, r: int) -> int:
+    return int(load_library().nvfp4_lora_linear_workspace_bytes(M, N, K, r))
+
+
+def nvfp4_quantize(W: torch.Tensor):
+    """W[N,K] bf16 -> (codes[N,K/2] u8, scales[N,K/16] u8, tensor_scale[1] f32)."""
+    lib = load_library()
+    N, K, ldw = _rows(W, "W")
+    dev = W.device
+    codes = torch.empty((N, K // 2), dtype=torch.uint8, device=dev)
+    scales = torch.empty((N, K // 16), dtype=torch.uint8, device=dev)
+    ts = torch.empty(1, dtype=torch.float32, device=dev)
+    ws = torch.empty(lib.nvfp4_quantize_workspace_bytes(N, K), dtype=torch.uint8, device=dev)
+    _check("nvfp4_quantize", lib.nvfp4_quantize(
+        _dev(W, torch.bfloat16, "W"), N, K, ldw, codes.data_ptr(), scales.data_ptr(), ts.data_ptr(),
+        ws.data_ptr(), ws.numel(), _stream()))
+    return codes, scales, ts
+
+
+def nvfp4_dequantize(codes: torch.Tensor, scales: torch.Tensor, tensor_scale: torch.Tensor):
+    lib = load_library()
+    N, K2 = codes.shape
+    K = 2 * K2
+    out = torch.empty((N, K), dtype=torch.float32, device=codes.device)
+    _check("nvfp4_dequantize", lib.nvfp4_dequantize(
+        _dev(codes, torch.uint8, "codes"), _dev(scales, torch.uint8, "scales"),
+        _dev(tensor_scale, torch.float32, "tensor_scale"), N, K, out.data_ptr(), _stream()))
+    return out
+
+
+def nvfp4_lora_linear(x, codes, scales, tensor_scale, A: Optional[torch.Tensor] = None,
+                      B: Optional[torch.Tensor] = None, lora_scale: float = 0.0,
+                      workspace: Optional[Workspace] = None, out: Optional[torch.Tensor] = None):
+    """y[M,N] = tensor_scale * x . dequant(codes, scales)^T + lora_scale * (x A^T) B^T, bf16."""
+    lib = load_library()
+    M, K, ldx = _rows(x, "x")
+    N = codes.shape[0]
+    if codes.shape[1] * 2 != K or tuple(scales.shape) != (N, K // 16):
+        raise ValueError("codes must be [N, K/2] and scales [N, K/16]")
+    if not codes.is_contiguous() or not scales.is_contiguous():
+        raise ValueError("codes and scales must be contiguous")
+    r = 0
+    a_ptr = b_ptr = None
+    if A is not None and B is not None and A.shape[0] > 0:
+        r = A.shape[0]
+        if tuple(A.shape) != (r, K) or tuple(B.shape) != (N, r) or not A.is_contiguous() or not B.is_contiguous():
+            raise ValueError("A must be contiguous [r, K] and B contiguous [N, r]")
+        a_ptr, b_ptr = _dev(A, torch.bfloat16, "A"), _dev(B, torch.bfloat16, "B")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    _, n_out, ldy = _rows(out, "out")
+    if out.shape[0] != M or n_out != N:
+        raise ValueError("out must be [M, N]")
+    need = lib.nvfp4_lora_linear_workspace_bytes(M, N, K, r)
+    if workspace is None:
+        workspace = Workspace(need, x.device)
+    _check("nvfp4_lora_linear", lib.nvfp4_lora_linear(
+        _dev(x, torch.bfloat16, "x"), M, K, ldx, _dev(codes, torch.uint8, "codes"),
+        _dev(scales, torch.uint8, "scales"), _dev(tensor_scale, torch.float32, "tensor_scale"), N,
+        a_ptr, b_ptr, r, float(lora_scale), _dev(out, torch.bfloat16, "out"), ldy,
+        workspace.ptr, workspace.nbytes, _stream()))
+    return out
+
+
+def aqn_rmsnorm(x, gain, noise: Optional[torch.Tensor] = None, eps: float = 1e-6,
+                out: Optional[torch.Tensor] = None):
+    """y = (gain + noise) * x / sqrt(mean(x^2) + eps), bf16; noise=None is the noise-free stage."""
+    lib = load_library()
+    M, H, ldx = _rows(x, "x")
+    if gain.numel() != H or not gain.is_contiguous():
+        raise ValueError("gain must be contiguous [H]")
+    n_ptr = None
+    if noise is not None:
+        if noise.numel() != H or not noise.is_contiguous():
+            raise ValueError("noise must be contiguous [H]")
+        n_ptr = _dev(noise, torch.float32, "noise")
+    if out is None:
+        out = torch.empty((M, H), dtype=torch.bfloat16, device=x.device)
+    _, _, ldy = _rows(out, "out")
+    _check("aqn_rmsnorm", lib.aqn_rmsnorm(
+        _dev(x, torch.bfloat16, "x"), M, H, ldx, _dev(gain, torch.bfloat16, "gain"), n_ptr,
+        float(eps), _dev(out, torch.bfloat16, "out"), ldy, _stream()))
+    return out

@@ -1,0 +1,70 @@
+// Shared host/device helpers of the gfx950 NVFP4 library (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/qerl_nvfp4.h"
+
+namespace qerl {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kBlock = 16;          // weights per E4M3 scale (Section 3.3)
+constexpr int kWave = 64;
+
+// ---- host side ------------------------------------------------------------
+void set_last_hip_error(int e);
+inline int launch_status() {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_last_hip_error((int)e); return QERL_ERR_LAUNCH; }
+  return QERL_OK;
+}
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ---- device side ----------------------------------------------------------
+// bf16 <-> fp32 by bit manipulation (bf16 is the top half of an fp32).
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+// fp32 -> bf16 bits, round-to-nearest-even (finite inputs).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  return (uint32_t)__builtin_bit_cast(unsigned short, (__bf16)f);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  bf16x2 v; v.x = (__bf16)lo; v.y = (__bf16)hi;      // v_cvt_pk_bf16_f32
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+// E4M3 byte (sign clear, not NaN) -> fp32, exact.  (b << 20) places the 4+3
+// bits at an fp32's low exponent / top mantissa bits; multiplying by 2^120
+// re-biases 127 -> 7 and, with fp32 denormals enabled, also covers the
+// subnormal bytes (exponent field 0).
+__device__ __forceinline__ float e4m3_to_f32(uint32_t b) {
+  return __uint_as_float(b << 20) * 0x1p120f;
+}
+
+// E2M1 code (4 bits, bit 3 = sign) -> fp32, exact: {0, .5, 1, 1.5, 2, 3, 4, 6}.
+__device__ __forceinline__ float e2m1_to_f32(uint32_t c) {
+  // place exponent(2)+mantissa(1) like above, re-bias 127 -> 1
+  float mag = __uint_as_float((c & 7u) << 22) * 0x1p126f;
+  return __uint_as_float(__float_as_uint(mag) | ((c & 8u) << 28));
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) { uint32_t t = __shfl_xor(v, o, 64); v = t > v ? t : v; }
+  return v;
+}
+
+}  // namespace qerl

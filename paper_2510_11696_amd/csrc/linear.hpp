@@ -1,0 +1,32 @@
+// Internal interfaces between the linear-layer translation units.
+#pragma once
+#include "common.hpp"
+
+namespace qerl {
+
+constexpr int kFmtNvfp4 = 0;   // rows are NVFP4 (codes + scales)
+constexpr int kFmtBf16 = 1;    // rows are dense bf16 (the LoRA A matrix); output is fp32 t
+
+struct SkinnyArgs {
+  const uint16_t* x; int64_t ldx; int M; int64_t K; int64_t N;
+  const uint8_t* codes; const uint8_t* scales; const float* tensor_scale;   // kFmtNvfp4
+  const uint16_t* wbf16;                                                    // kFmtBf16: [N, K]
+  const float* t_in; const uint16_t* B; int r; float lora_scale;            // LoRA up (kFmtNvfp4)
+  uint16_t* y; int64_t ldy;                                                 // kFmtNvfp4 output
+  float* t_out;                                                             // kFmtBf16 output [M, N]
+  f32x4* partial; uint32_t* counters; int n_tiles;
+};
+
+struct SkinnyPlan { int KT, T, S, waves, n_tiles, groups; };
+SkinnyPlan plan_skinny(int64_t N, int64_t K, int fmt);
+int launch_skinny(const SkinnyPlan& p, const SkinnyArgs& a, int fmt, hipStream_t st);
+
+// General fallback (any K % 16 == 0, any alignment of rows the ABI allows).
+int launch_generic_lora_down(const uint16_t* x, int64_t ldx, int64_t M, int64_t K, const uint16_t* A,
+                             int64_t r, float* t, hipStream_t st);
+int launch_generic_linear(const uint16_t* x, int64_t ldx, int64_t M, int64_t K, const uint8_t* codes,
+                          const uint8_t* scales, const float* tensor_scale, int64_t N, const float* t,
+                          const uint16_t* B, int64_t r, float lora_scale, uint16_t* y, int64_t ldy,
+                          hipStream_t st);
+
+}  // namespace qerl

@@ -1,0 +1,106 @@
+"""CPU-side checks of the boundary: the library loads, exports every symbol the
+header declares, and rejects misuse on the host before touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2510_11696_amd as qerl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(qerl.LIB_PATH):
+        from paper_2510_11696_amd import build
+        build.build(verbose=False)
+    return qerl.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "qerl_nvfp4.h")).read()
+    declared = re.findall(r"QERL_API\s+[\w\s\*]+?\b(\w+)\s*\(", header)
+    assert len(declared) >= 10
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert set(declared) == set(qerl.EXPORTED_SYMBOLS)
+
+
+def test_status_strings(lib):
+    for code in range(0, -6, -1):
+        assert lib.qerl_status_string(code)
+    assert b"unknown" in lib.qerl_status_string(-99)
+
+
+def test_sigma_schedule_host(lib):
+    assert qerl.aqn_sigma(0, 10, 1e-2, 5e-4) == 0.0
+    assert qerl.aqn_sigma(1, 10, 1e-2, 5e-4) == 1e-2
+    assert abs(qerl.aqn_sigma(10, 10, 1e-2, 5e-4) - 5e-4) < 1e-18
+    assert qerl.aqn_sigma(11, 10, 1e-2, 5e-4) != qerl.aqn_sigma(11, 10, 1e-2, 5e-4)   # NaN
+
+
+def test_host_side_validation_needs_no_gpu(lib):
+    p = ctypes.c_void_p
+    fake = 0x10000   # aligned, never dereferenced: every call below fails validation first
+    q = lib.nvfp4_quantize
+    assert q(None, 4, 32, 32, fake, fake, None, fake, 1 << 20, None) == -1
+    assert q(fake, 4, 24, 24, fake, fake, fake, fake, 1 << 20, None) == -2      # K % 16
+    assert q(fake, 4, 32, 16, fake, fake, fake, fake, 1 << 20, None) == -2      # ldw < K
+    assert q(fake, -1, 32, 32, fake, fake, fake, fake, 1 << 20, None) == -2
+    assert q(None, 4, 32, 32, fake, fake, fake, fake, 1 << 20, None) == -1
+    assert q(fake + 2, 4, 32, 32, fake, fake, fake, fake, 1 << 20, None) == -3
+    assert q(fake, 4, 32, 36, fake, fake, fake, fake, 1 << 20, None) == -3      # ldw % 8
+    assert q(fake, 4, 32, 32, fake, fake, fake, fake, 16, None) == -4
+    assert q(fake, 4, 32, 32, fake, fake, fake, None, 1 << 20, None) == -4
+
+    lin = lib.nvfp4_lora_linear
+    ok = dict(x=fake, M=2, K=64, ldx=64, codes=fake, scales=fake, ts=fake, N=16, A=None, B=None, r=0,
+              ls=0.0, y=fake, ldy=16, ws=fake, wsb=1 << 24, st=None)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return lin(a["x"], a["M"], a["K"], a["ldx"], a["codes"], a["scales"], a["ts"], a["N"], a["A"],
+                   a["B"], a["r"], a["ls"], a["y"], a["ldy"], a["ws"], a["wsb"], a["st"])
+    assert call(M=0) == 0                       # no-op, nothing launched
+    assert call(K=40, ldx=40) == -2
+    assert call(M=-1) == -2
+    assert call(ldx=32) == -2
+    assert call(ldy=8) == -2
+    assert call(r=-1) == -2
+    assert call(x=None) == -1
+    assert call(codes=None) == -1
+    assert call(r=8) == -1                      # A/B missing
+    assert call(x=fake + 8) == -3
+    assert call(ldx=68) == -3
+    assert call(r=8, A=fake + 4, B=fake) == -3
+    assert call(ws=None) == -4
+    assert call(wsb=64) == -4
+    assert call(ws=fake + 16) == -4
+    need = qerl.nvfp4_lora_linear_workspace_bytes(2, 16, 64, 0)
+    assert call(wsb=need - 1) == -4
+
+    rn = lib.aqn_rmsnorm
+    assert rn(None, 1, 64, 64, fake, None, 1e-6, fake, 64, None) == -1
+    assert rn(fake, 1, 0, 64, fake, None, 1e-6, fake, 64, None) == -2
+    assert rn(fake, 1, 64, 32, fake, None, 1e-6, fake, 64, None) == -2
+    assert rn(fake, 0, 64, 64, fake, None, 1e-6, fake, 64, None) == 0
+    assert lib.qerl_workspace_init(None, 1024, None) == -1
+    assert lib.qerl_workspace_init(fake + 4, 1024, None) == -3
+    assert lib.nvfp4_dequantize(fake, fake, fake, 2, 24, fake, None) == -2
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    with pytest.raises(TypeError):
+        qerl.nvfp4_quantize(torch.zeros((2, 32), dtype=torch.bfloat16))
+    with pytest.raises(TypeError):
+        qerl.aqn_rmsnorm(torch.zeros((2, 32), dtype=torch.bfloat16), torch.ones(32, dtype=torch.bfloat16))
+
+
+def test_workspace_size_is_monotone_enough(lib):
+    f = qerl.nvfp4_lora_linear_workspace_bytes
+    assert f(8, 3584, 18944, 32) >= f(8, 3584, 3584, 32)
+    assert f(128, 3584, 3584, 32) >= f(8, 3584, 3584, 32)
+    assert f(8, 3584, 18944, 32) < 64 << 20

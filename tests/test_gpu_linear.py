@@ -1,0 +1,144 @@
+"""GPU parity: nvfp4_lora_linear against the oracle (fp64 accumulation)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2510_11696_amd as qerl
+import qerl_synth as qs
+from oracle import nvfp4_oracle as oracle
+from tests import cases
+from tests.gpu_util import check_linear, to_gpu_bf16
+
+pytestmark = pytest.mark.gpu
+
+
+def _problem(M, N, K, r, seed, w_std=0.02, W=None):
+    if W is None:
+        W = cases.gaussian(N, K, seed, w_std)
+    x = qs.activations(M, K, seed + 1)
+    A = B = None
+    if r > 0:
+        A, B = qs.lora_pair(N, K, r, seed + 2)
+    return W, x, A, B
+
+
+def _run(M, N, K, r, seed, alpha_over_r=2.0, W=None, label=""):
+    print("linear case", label, M, N, K, r, seed, flush=True)
+    W, x, A, B = _problem(M, N, K, r, seed, W=W)
+    codes, scales, ts = oracle.nvfp4_quantize(W)
+    g = lambda a: torch.from_numpy(a).cuda()
+    ts_gpu = torch.tensor([ts], dtype=torch.float32, device="cuda")
+    y = qerl.nvfp4_lora_linear(x.cuda(), g(codes), g(scales), ts_gpu,
+                               A.cuda() if r else None, B.cuda() if r else None, alpha_over_r)
+    torch.cuda.synchronize()
+    ref = oracle.nvfp4_lora_linear(x.float().numpy(), codes, scales, ts,
+                                   A.float().numpy() if r else None, B.float().numpy() if r else None,
+                                   alpha_over_r)
+    check_linear(y, ref, (label, M, N, K, r))
+    return y, ref
+
+
+def test_config1_single_linear():
+    """K = N = 2048, one token, LoRA r = 16, alpha = 32."""
+    _run(1, 2048, 2048, 16, seed=qs.seed_for(1, 0), alpha_over_r=32.0 / 16)
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 8, 15, 16])
+@pytest.mark.parametrize("N,K,r", [(512, 3584, 32), (3584, 3584, 32), (96, 18944, 32), (1184, 3584, 0)])
+def test_decode_shapes(M, N, K, r):
+    _run(M, N, K, r, seed=M * 7 + N + K)
+
+
+@pytest.mark.parametrize("M,N,K,r", [
+    (3, 40, 320, 8),       # ragged N tile, K not a multiple of 256
+    (5, 17, 64, 3),        # single K chunk, odd rank
+    (16, 1000, 2112, 16),  # ragged everything, several tiles
+    (7, 16, 5120, 64),     # two workgroups along K
+    (2, 33, 27648, 64),    # seven workgroups along K
+])
+def test_ragged_shapes(M, N, K, r):
+    _run(M, N, K, r, seed=M + N + K)
+
+
+@pytest.mark.parametrize("M,N,K,r", [(4, 24, 48, 4), (1, 8, 16, 0), (9, 130, 1040, 16)])
+def test_general_kernel_k_not_multiple_of_64(M, N, K, r):
+    _run(M, N, K, r, seed=3 * M + N)
+
+
+@pytest.mark.parametrize("M", [17, 32, 100, 128])
+def test_more_than_16_tokens(M):
+    _run(M, 512, 3584, 32, seed=M)
+
+
+def test_adversarial_weights_through_the_linear():
+    for name, W in cases.quantizer_cases(48, 512, seed=31).items():
+        if name in ("scaled_up", "scaled_down"):
+            continue
+        _run(4, 48, 512, 8, seed=5, W=W, label=name)
+
+
+def test_one_hot_reads_exact_dequantised_column():
+    N, K = 64, 512
+    W = cases.gaussian(N, K, 3)
+    codes, scales, ts = oracle.nvfp4_quantize(W)
+    Wh = oracle.nvfp4_dequantize(codes, scales, ts)
+    ks = [0, 15, 16, 255, 256, 300, 511]
+    x = torch.zeros((len(ks), K), dtype=torch.bfloat16)
+    for m, k in enumerate(ks):
+        x[m, k] = 1.0
+    g = lambda a: torch.from_numpy(a).cuda()
+    y = qerl.nvfp4_lora_linear(x.cuda(), g(codes), g(scales), torch.tensor([ts], device="cuda"))
+    want = torch.from_numpy(Wh[:, ks].T.copy()).to(torch.bfloat16)
+    assert torch.equal(y.cpu(), want)
+
+
+def test_deterministic_and_workspace_reuse():
+    M, N, K, r = 8, 3584, 18944, 32
+    W, x, A, B = _problem(M, N, K, r, 11)
+    cw, sw, tw = qerl.nvfp4_quantize(to_gpu_bf16(W))
+    ws = qerl.Workspace(qerl.nvfp4_lora_linear_workspace_bytes(M, N, K, r))
+    args = (x.cuda(), cw, sw, tw, A.cuda(), B.cuda(), 2.0)
+    y0 = qerl.nvfp4_lora_linear(*args, workspace=ws).clone()
+    for _ in range(10):
+        y = qerl.nvfp4_lora_linear(*args, workspace=ws)
+        assert torch.equal(y, y0)
+    # a different, smaller problem on the same workspace, then the first again
+    W2, x2, A2, B2 = _problem(3, 96, 18944, 32, 12)
+    c2, s2, t2 = qerl.nvfp4_quantize(to_gpu_bf16(W2))
+    y2 = qerl.nvfp4_lora_linear(x2.cuda(), c2, s2, t2, A2.cuda(), B2.cuda(), 2.0, workspace=ws)
+    y2b = qerl.nvfp4_lora_linear(x2.cuda(), c2, s2, t2, A2.cuda(), B2.cuda(), 2.0)
+    assert torch.equal(y2, y2b)
+    assert torch.equal(qerl.nvfp4_lora_linear(*args, workspace=ws), y0)
+
+
+def test_strided_x_and_y_and_canaries():
+    M, N, K, r = 5, 200, 768, 16
+    W, x, A, B = _problem(M, N, K, r, 21)
+    codes, scales, ts = oracle.nvfp4_quantize(W)
+    xb = torch.full((M, K + 64), 3.0, dtype=torch.bfloat16, device="cuda")
+    xb[:, :K] = x.cuda()
+    out = torch.full((M, N + 56), -5.0, dtype=torch.bfloat16, device="cuda")
+    g = lambda a: torch.from_numpy(a).cuda()
+    qerl.nvfp4_lora_linear(xb[:, :K], g(codes), g(scales), torch.tensor([ts], device="cuda"),
+                           A.cuda(), B.cuda(), 2.0, out=out[:, :N])
+    ref = oracle.nvfp4_lora_linear(x.float().numpy(), codes, scales, ts, A.float().numpy(), B.float().numpy(), 2.0)
+    check_linear(out[:, :N].contiguous(), ref, "strided")
+    assert torch.all(out[:, N:] == -5.0)
+
+
+def test_rmsnorm_feeds_linear_end_to_end():
+    """AQN RMSNorm -> NVFP4 linear equals the oracle's composition, and the
+    noise acts like row-scaled weights (Appendix "Proof of Noise Sharing")."""
+    M, H, N, r = 8, 3584, 512, 32
+    xin = qs.activations(M, H, 50)
+    gain = qs.rms_gain(H, 51)
+    Z = qs.aqn_noise(H, 1e-2, 52)
+    W = cases.gaussian(N, H, 53)
+    A, B = qs.lora_pair(N, H, r, 54)
+    codes, scales, ts = qerl.nvfp4_quantize(to_gpu_bf16(W))
+    xn = qerl.aqn_rmsnorm(xin.cuda(), gain.cuda(), Z.cuda())
+    y = qerl.nvfp4_lora_linear(xn, codes, scales, ts, A.cuda(), B.cuda(), 2.0)
+    # oracle: the linear consumes the bf16 activations the norm produced
+    ref = oracle.nvfp4_lora_linear(xn.float().cpu().numpy(), codes.cpu().numpy(), scales.cpu().numpy(),
+                                   np.float32(ts.item()), A.float().numpy(), B.float().numpy(), 2.0)
+    check_linear(y, ref, "norm->linear")

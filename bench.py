@@ -1,0 +1,210 @@
+"""Benchmark of the NVFP4 + LoRA linear hot path on one MI355X.
+
+A step is one decode pass of batch M through the linear stack of every decoder
+layer of the model (default: Qwen2.5-7B shapes, 28 layers, M = 8, LoRA r = 32):
+per layer  aqn_rmsnorm -> q, k, v -> o -> aqn_rmsnorm -> gate, up -> down,
+all on NVFP4 weights that are resident in HBM and distinct per layer, so one
+step streams 28 x 131 MB = 3.67 GB of packed weights and nothing is served
+from a cache that would not be there in a rollout.  Attention and SiLU*mul are
+not part of this library; o and down read fixed synthetic activations.
+
+Prints ONE JSON line: whole-step weight-GB/s as `value`, the roofline of the
+dominant kernel (the gate/up/down-sized decode linear) measured live with
+events on the launch stream, and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import paper_2510_11696_amd as qerl  # noqa: E402
+import qerl_synth as qs              # noqa: E402
+
+HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+class Layer:
+    """NVFP4 weights + LoRA adapters + norm parameters of one decoder layer, on the GPU."""
+
+    def __init__(self, cfg, index, gen, config_no):
+        self.lin = {}
+        hidden = cfg["hidden"]
+        r = cfg["r"]
+        for j, shp in enumerate(cfg["linears"]):
+            W = (torch.randn((shp.N, shp.K), generator=gen, device="cuda", dtype=torch.float32) * 0.02
+                 ).to(torch.bfloat16)
+            codes, scales, ts = qerl.nvfp4_quantize(W)
+            del W
+            A = (torch.randn((r, shp.K), generator=gen, device="cuda") / r).to(torch.bfloat16)
+            B = (torch.randn((shp.N, r), generator=gen, device="cuda") * 0.01).to(torch.bfloat16)
+            self.lin[shp.name] = (codes, scales, ts, A, B)
+        self.gain_in = (1 + 0.05 * torch.randn(hidden, generator=gen, device="cuda")).to(torch.bfloat16)
+        self.gain_post = (1 + 0.05 * torch.randn(hidden, generator=gen, device="cuda")).to(torch.bfloat16)
+        sigma = qerl.aqn_sigma(1, 10, 1e-2, 5e-4)
+        self.z_in = torch.randn(hidden, generator=gen, device="cuda") * sigma
+        self.z_post = torch.randn(hidden, generator=gen, device="cuda") * sigma
+
+
+class Stack:
+    def __init__(self, config_no: int, M: int, layers: int | None = None):
+        cfg = qs.CONFIGS[config_no]
+        self.cfg, self.M = cfg, M
+        self.n_layers = layers or cfg["layers"]
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(qs.seed_for(config_no, 0))
+        self.layers = [Layer(cfg, i, gen, config_no) for i in range(self.n_layers)]
+        hidden = cfg["hidden"]
+        inter = max(s.K for s in cfg["linears"])
+        self.h = torch.randn((M, hidden), generator=gen, device="cuda").to(torch.bfloat16)
+        self.attn = torch.randn((M, hidden), generator=gen, device="cuda").to(torch.bfloat16)
+        self.act = torch.randn((M, inter), generator=gen, device="cuda").to(torch.bfloat16)
+        self.xn = torch.empty((M, hidden), dtype=torch.bfloat16, device="cuda")
+        self.out = {s.name: torch.empty((M, s.N), dtype=torch.bfloat16, device="cuda") for s in cfg["linears"]}
+        self.lora_scale = cfg["alpha"] / cfg["r"]
+        need = max(qerl.nvfp4_lora_linear_workspace_bytes(M, s.N, s.K, cfg["r"]) for s in cfg["linears"])
+        self.ws = qerl.Workspace(need)
+        self.packed_bytes_per_layer = sum(s.packed_bytes for s in cfg["linears"])
+        self.flops_per_layer = sum(2 * M * s.N * s.K for s in cfg["linears"])
+
+    def linear(self, layer, name, x):
+        codes, scales, ts, A, B = layer.lin[name]
+        return qerl.nvfp4_lora_linear(x, codes, scales, ts, A, B, self.lora_scale,
+                                      workspace=self.ws, out=self.out[name])
+
+    def step(self):
+        for L in self.layers:
+            qerl.aqn_rmsnorm(self.h, L.gain_in, L.z_in, 1e-6, out=self.xn)
+            self.linear(L, "q", self.xn)
+            self.linear(L, "k", self.xn)
+            self.linear(L, "v", self.xn)
+            self.linear(L, "o", self.attn)
+            qerl.aqn_rmsnorm(self.h, L.gain_post, L.z_post, 1e-6, out=self.xn)
+            self.linear(L, "gate", self.xn)
+            self.linear(L, "up", self.xn)
+            self.linear(L, "down", self.act)
+
+
+def timed(fn, iters):
+    """Milliseconds per call, HIP events on the stream the kernels are launched on."""
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(iters):
+        fn()
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) / iters
+
+
+def dominant_kernel_roofline(stack: Stack, reps: int):
+    """Average duration of one launch of the decode linear at the largest shape
+    (gate_proj: the kernel most of the step's bytes go through), running it
+    back to back over every layer's distinct weights."""
+    shp = max(stack.cfg["linears"], key=lambda s: (s.packed_bytes, s.name == "gate"))
+
+    def sweep():
+        for L in stack.layers:
+            stack.linear(L, shp.name, stack.act if shp.name == "down" else stack.xn)
+    sweep()
+    ms = timed(sweep, reps) / len(stack.layers)
+    bytes_per_launch = shp.packed_bytes
+    achieved = bytes_per_launch / (ms * 1e-3) / 1e9
+    return {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+            "kernel": "skinny_kernel (decode NVFP4 linear)",
+            "shape": {"name": shp.name, "N": shp.N, "K": shp.K, "M": stack.M},
+            "algorithmic_bytes_per_launch": bytes_per_launch, "us_per_launch": round(ms * 1e3, 2),
+            "note": "per linear call incl. its LoRA down-projection launch and launch gaps"}
+
+
+def cpu_baseline(config_no: int, M: int, budget_s: float = 20.0):
+    """The numpy oracle on the host cores, on one layer's attention projections
+    (q, k, v, o) plus as much of gate_proj as fits the time budget."""
+    from oracle import nvfp4_oracle as oracle
+    cfg = qs.CONFIGS[config_no]
+    r = cfg["r"]
+    done_bytes, t_total, names = 0, 0.0, []
+    for j, shp in enumerate(cfg["linears"]):
+        if t_total > budget_s:
+            break
+        N = shp.N
+        if shp.packed_bytes > 20e6:           # big MLP matrices: a slice of output rows
+            N = 2048
+        W = qs.weights(N, shp.K, qs.seed_for(config_no, 10 + j)).float().numpy()
+        x = qs.activations(M, shp.K, qs.seed_for(config_no, 30 + j)).float().numpy()
+        A, B = qs.lora_pair(N, shp.K, r, qs.seed_for(config_no, 50 + j))
+        codes, scales, ts = oracle.nvfp4_quantize(W)
+        t0 = time.perf_counter()
+        oracle.nvfp4_lora_linear(x, codes, scales, ts, A.float().numpy(), B.float().numpy(), cfg["alpha"] / r)
+        t_total += time.perf_counter() - t0
+        done_bytes += N * shp.K * 9 // 16
+        names.append(f"{shp.name}[{N}x{shp.K}]")
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count()
+    threads = min(cores, torch.get_num_threads())
+    return {"value": round(done_bytes / t_total / 1e9, 4), "unit": "GB/s", "cores": threads,
+            "kind": "oracle",
+            "sample": f"oracle nvfp4_lora_linear (dequantise + fp64 matmul + LoRA), M={M}, on "
+                      + ", ".join(names) + f"; {t_total:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="BASELINE config number (1-based)")
+    ap.add_argument("--M", type=int, default=None)
+    ap.add_argument("--layers", type=int, default=None)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    cfg = qs.CONFIGS[args.config]
+    M = args.M or cfg["M"][0]
+    stack = Stack(args.config, M, args.layers)
+    for _ in range(args.warmup):
+        stack.step()
+    torch.cuda.synchronize()
+    ms = timed(stack.step, args.steps)
+    step_bytes = stack.packed_bytes_per_layer * stack.n_layers
+    value = step_bytes / (ms * 1e-3) / 1e9
+    roof = dominant_kernel_roofline(stack, max(3, args.steps // 2))
+    line = {
+        "metric": "NVFP4+LoRA linear: packed-weight GB/s at decode",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 x fp4(e2m1)*fp8(e4m3) -> fp32 accumulate", "data": "synthetic",
+        "config": {"workload": f"config {args.config}: {cfg['model']}-shaped decoder linears, "
+                               f"{stack.n_layers} layers, decode M={M}, LoRA r={cfg['r']} alpha={cfg['alpha']:g}, "
+                               "AQN RMSNorm before q/k/v and gate/up",
+                   "packed_weight_bytes_per_step": step_bytes,
+                   "tflops": round(stack.flops_per_layer * stack.n_layers / (ms * 1e-3) / 1e12, 2),
+                   "frac_of_hbm_peak_whole_step": round(value / HBM_PEAK_GBS, 4)},
+        "roofline": roof,
+    }
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(args.config, M)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

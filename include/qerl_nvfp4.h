@@ -43,7 +43,7 @@ extern "C" {
 #define QERL_OK              0
 #define QERL_ERR_NULL       -1  /* a required pointer is NULL                          */
 #define QERL_ERR_SHAPE      -2  /* M,N < 0, K % 16 != 0, ld < row length, r < 0, ...   */
-#define QERL_ERR_ALIGN      -3  /* pointer not 16-byte aligned or ld % 8 != 0          */
+#define QERL_ERR_ALIGN      -3  /* pointer or leading dimension not aligned as documented */
 #define QERL_ERR_WORKSPACE  -4  /* workspace NULL or smaller than *_workspace_bytes()  */
 #define QERL_ERR_LAUNCH     -5  /* HIP runtime error; see qerl_last_hip_error()        */
 
@@ -100,12 +100,13 @@ QERL_API int nvfp4_dequantize(const uint8_t* codes, const uint8_t* scales, const
  *     only by this library.  Calls that share a workspace must be ordered on
  *     one stream.  A call that returned an error leaves it valid.
  *
- * Any M >= 0 is accepted (M == 0 is a no-op).  M <= 16 takes the
- * bandwidth-bound decode kernels, larger M the MFMA GEMM kernels; shapes the
- * tiled kernels do not cover (K % 64 != 0) take a slower general kernel.
+ * Any M >= 0 is accepted (M == 0 is a no-op).  The tiled MFMA kernels need
+ * K % 64 == 0, x, codes and A 16-byte aligned, scales 4-byte aligned and
+ * ldx % 8 == 0 (true for any real model); everything else takes a slower
+ * general kernel with the same results contract.
  * Errors: NULL pointers (A/B only when r > 0); M,N,K,r < 0, K % 16 != 0,
- * ldx < K, ldy < N; x/y not 16-byte aligned, ldx % 8 or ldy % 8 != 0, codes
- * or scales or A or B not 16-byte aligned; workspace.
+ * ldx < K, ldy < N, N >= 2^20, r > 4096; bf16 pointers not 2-byte aligned;
+ * workspace NULL, not 256-byte aligned or too small.
  */
 QERL_API int nvfp4_lora_linear(const void* x_bf16, int64_t M, int64_t K, int64_t ldx,
                       const uint8_t* codes, const uint8_t* scales, const float* tensor_scale,

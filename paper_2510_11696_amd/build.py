@@ -36,7 +36,7 @@ def _compile(src: str) -> str:
     cmd = ["hipcc", *COMMON, *PER_FILE.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
-        raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}\n{r.stderr}")
+        raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout[-2000:]}\n{r.stderr[:4000]}")
     return obj
 
 

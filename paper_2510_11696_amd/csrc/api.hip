@@ -89,9 +89,7 @@ extern "C" int nvfp4_lora_linear(const void* x, int64_t M, int64_t K, int64_t ld
   if (!x || !y || !tensor_scale) return QERL_ERR_NULL;
   if (K > 0 && (!codes || !scales)) return QERL_ERR_NULL;
   if (r > 0 && (!A || !B)) return QERL_ERR_NULL;
-  if (!aligned(x, 16) || !aligned(y, 16) || ldx % 8 != 0 || ldy % 8 != 0 || !aligned(codes, 16) ||
-      !aligned(scales, 16) || (r > 0 && (!aligned(A, 16) || !aligned(B, 16))))
-    return QERL_ERR_ALIGN;
+  if (!aligned(x, 2) || !aligned(y, 2) || (r > 0 && (!aligned(A, 2) || !aligned(B, 2)))) return QERL_ERR_ALIGN;
   const WorkspaceLayout L = workspace_layout(M, N, K, r);
   if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total) return QERL_ERR_WORKSPACE;
 
@@ -105,7 +103,9 @@ extern "C" int nvfp4_lora_linear(const void* x, int64_t M, int64_t K, int64_t ld
   uint16_t* yp = (uint16_t*)y;
   if (K == 0) r = 0;   // empty sums: y = 0 through the general kernel
 
-  const bool tiled = (K % 64 == 0) && K > 0;
+  // The tiled kernels use 16-byte loads; anything else goes to the general kernels.
+  const bool tiled = (K % 64 == 0) && K > 0 && aligned(x, 16) && ldx % 8 == 0 && aligned(codes, 16) &&
+                     aligned(scales, 4) && (r == 0 || aligned(A, 16));
   if (!tiled) {
     int rc = QERL_OK;
     if (r > 0) rc = launch_generic_lora_down(xp, ldx, M, K, (const uint16_t*)A, r, t, st);
@@ -131,6 +131,8 @@ extern "C" int nvfp4_lora_linear(const void* x, int64_t M, int64_t K, int64_t ld
     a.N = N; a.codes = codes; a.scales = scales; a.tensor_scale = tensor_scale;
     a.t_in = t + m0 * r; a.B = (const uint16_t*)B; a.r = (int)r; a.lora_scale = lora_scale;
     a.y = yp + m0 * ldy; a.ldy = ldy;
+    a.y_vec = aligned(y, 8) && ldy % 4 == 0;
+    a.b_vec = r % 8 == 0 && aligned(B, 16);
     a.partial = partial; a.counters = ctr_main; a.n_tiles = pm.n_tiles;
     const int rc = launch_skinny(pm, a, kFmtNvfp4, st);
     if (rc != QERL_OK) return rc;

@@ -12,7 +12,7 @@ struct SkinnyArgs {
   const uint8_t* codes; const uint8_t* scales; const float* tensor_scale;   // kFmtNvfp4
   const uint16_t* wbf16;                                                    // kFmtBf16: [N, K]
   const float* t_in; const uint16_t* B; int r; float lora_scale;            // LoRA up (kFmtNvfp4)
-  uint16_t* y; int64_t ldy;                                                 // kFmtNvfp4 output
+  uint16_t* y; int64_t ldy; bool y_vec, b_vec;                              // kFmtNvfp4 output; 8/16-byte access allowed
   float* t_out;                                                             // kFmtBf16 output [M, N]
   f32x4* partial; uint32_t* counters; int n_tiles;
 };

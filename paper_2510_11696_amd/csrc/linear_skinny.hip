@@ -48,6 +48,18 @@ __device__ __forceinline__ bf16x8 dequant8(uint32_t codes, float s) {
   return __builtin_bit_cast(bf16x8, o);
 }
 
+// Byte `b` of `v` as an OCP E4M3 value (v_cvt_f32_fp8 with a byte select; on
+// gfx950 the instruction follows the OCP format).  `b` folds to a constant once
+// the caller's loop is unrolled.
+__device__ __forceinline__ float e4m3_byte_to_f32(uint32_t v, int b) {
+  switch (b) {
+    case 0: return __builtin_amdgcn_cvt_f32_fp8(v, 0);
+    case 1: return __builtin_amdgcn_cvt_f32_fp8(v, 1);
+    case 2: return __builtin_amdgcn_cvt_f32_fp8(v, 2);
+    default: return __builtin_amdgcn_cvt_f32_fp8(v, 3);
+  }
+}
+
 constexpr int kMaxWaves = 8;
 
 template <int KT, int T, int FMT>
@@ -101,7 +113,7 @@ __global__ __launch_bounds__(kMaxWaves * 64) void skinny_kernel(const SkinnyArgs
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           const uint32_t d = j < 4 ? c0[t][i][j & 3] : c1[t][i][j & 3];
-          const float s = e4m3_to_f32((sc[t][i] >> (8 * (j >> 1))) & 0xffu);
+          const float s = e4m3_byte_to_f32(sc[t][i], j >> 1);
           acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dequant8(d, s), xf[i][j], acc[t], 0, 0, 0);
         }
   } else {
@@ -203,7 +215,7 @@ __global__ __launch_bounds__(kMaxWaves * 64) void skinny_kernel(const SkinnyArgs
           const float* tp = a.t_in + (int64_t)token * a.r;
           const uint16_t* bp = a.B + n * a.r;
           float lo = 0.f;
-          if ((a.r & 7) == 0) {
+          if (a.b_vec) {
             for (int j = 0; j < a.r; j += 8) {
               const u32x4 b = *reinterpret_cast<const u32x4*>(bp + j);
               const f32x4 t0 = *reinterpret_cast<const f32x4*>(tp + j);
@@ -224,7 +236,7 @@ __global__ __launch_bounds__(kMaxWaves * 64) void skinny_kernel(const SkinnyArgs
         }
       }
       uint16_t* yp = a.y + (int64_t)token * a.ldy + nb;
-      if (nb + 3 < a.N) {
+      if (a.y_vec && nb + 3 < a.N) {
         *reinterpret_cast<u32x2*>(yp) = u32x2{pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
       } else {
 #pragma unroll

@@ -27,9 +27,11 @@ def outlier(N, K, seed):
 def zero_rows_and_blocks(N, K, seed):
     W = gaussian(N, K, seed)
     W[0, :] = 0.0
-    W[N - 1, :] = -0.0
-    W[1, 16:48] = 0.0
-    W[2, 0:16] = -0.0
+    if N > 1:
+        W[N - 1, :] = -0.0
+    if N > 2:
+        W[1, 16:48] = 0.0
+        W[2, 0:16] = -0.0
     return W
 
 

@@ -72,9 +72,8 @@ def test_host_side_validation_needs_no_gpu(lib):
     assert call(x=None) == -1
     assert call(codes=None) == -1
     assert call(r=8) == -1                      # A/B missing
-    assert call(x=fake + 8) == -3
-    assert call(ldx=68) == -3
-    assert call(r=8, A=fake + 4, B=fake) == -3
+    assert call(x=fake + 1) == -3
+    assert call(r=8, A=fake + 1, B=fake) == -3
     assert call(ws=None) == -4
     assert call(wsb=64) == -4
     assert call(ws=fake + 16) == -4

@@ -116,6 +116,29 @@ QERL_API int nvfp4_lora_linear(const void* x_bf16, int64_t M, int64_t K, int64_t
                       void* workspace, size_t workspace_bytes, void* stream);
 QERL_API size_t nvfp4_lora_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t r); /* host */
 
+/* ---------------------------------------------------------------------------
+ * Tile-packed weights.  The weights of a rollout policy are frozen (Section
+ * 3.3: only the low-rank matrices are updated), so the canonical tensor can be
+ * re-laid out once for the kernels: nvfp4_prepack copies the same code and
+ * scale bytes, unchanged, into 2304-byte tiles of 32 rows x 128 inputs (rows
+ * padded to 32 and K to 128 with zero bytes) in the order the MFMA operands
+ * consume them, so that every wave-wide load is 1 KiB of consecutive memory.
+ * The size stays 0.5625 bytes per (padded) weight.  Layout of a tile: see
+ * csrc/linear_decode.hip.
+ *   packed: out, nvfp4_prepack_bytes(N,K) bytes, 16-byte aligned.
+ * nvfp4_lora_linear_packed computes exactly what nvfp4_lora_linear does, from
+ * `packed` instead of (codes, scales); same arguments otherwise, but x must be
+ * 16-byte aligned with ldx % 8 == 0 (QERL_ERR_ALIGN) and K > 0.
+ */
+QERL_API size_t nvfp4_prepack_bytes(int64_t N, int64_t K);   /* host */
+QERL_API int nvfp4_prepack(const uint8_t* codes, const uint8_t* scales, int64_t N, int64_t K,
+                           void* packed, void* stream);
+QERL_API int nvfp4_lora_linear_packed(const void* x_bf16, int64_t M, int64_t K, int64_t ldx,
+                                      const void* packed, const float* tensor_scale, int64_t N,
+                                      const void* A_bf16, const void* B_bf16, int64_t r, float lora_scale,
+                                      void* y_bf16, int64_t ldy,
+                                      void* workspace, size_t workspace_bytes, void* stream);
+
 /* Zero the control words of a linear workspace.  Call once after allocating
  * it (and again if a kernel using it was ever aborted). */
 QERL_API int qerl_workspace_init(void* workspace, size_t workspace_bytes, void* stream);

@@ -31,6 +31,11 @@ _SIGNATURES = {
                                          _c_p, _c_p, _c_i64, ctypes.c_float, _c_p, _c_i64,
                                          _c_p, _c_sz, _c_p]),
     "nvfp4_lora_linear_workspace_bytes": (_c_sz, [_c_i64, _c_i64, _c_i64, _c_i64]),
+    "nvfp4_prepack_bytes": (_c_sz, [_c_i64, _c_i64]),
+    "nvfp4_prepack": (ctypes.c_int, [_c_p, _c_p, _c_i64, _c_i64, _c_p, _c_p]),
+    "nvfp4_lora_linear_packed": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_p, _c_i64,
+                                                _c_p, _c_p, _c_i64, ctypes.c_float, _c_p, _c_i64,
+                                                _c_p, _c_sz, _c_p]),
     "qerl_workspace_init": (ctypes.c_int, [_c_p, _c_sz, _c_p]),
     "aqn_rmsnorm": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_p, ctypes.c_float,
                                    _c_p, _c_i64, _c_p]),
@@ -180,6 +185,56 @@ def nvfp4_lora_linear(x, codes, scales, tensor_scale, A: Optional[torch.Tensor] 
         _dev(scales, torch.uint8, "scales"), _dev(tensor_scale, torch.float32, "tensor_scale"), N,
         a_ptr, b_ptr, r, float(lora_scale), _dev(out, torch.bfloat16, "out"), ldy,
         workspace.ptr, workspace.nbytes, _stream()))
+    return out
+
+
+class PackedWeight:
+    """Tile-packed NVFP4 weight (see nvfp4_prepack in the header) plus its shape."""
+
+    def __init__(self, packed: torch.Tensor, tensor_scale: torch.Tensor, N: int, K: int):
+        self.packed, self.tensor_scale, self.N, self.K = packed, tensor_scale, int(N), int(K)
+
+
+def nvfp4_prepack(codes: torch.Tensor, scales: torch.Tensor, tensor_scale: torch.Tensor) -> PackedWeight:
+    lib = load_library()
+    N, K2 = codes.shape
+    K = 2 * K2
+    if tuple(scales.shape) != (N, K // 16) or not codes.is_contiguous() or not scales.is_contiguous():
+        raise ValueError("codes must be contiguous [N, K/2] and scales contiguous [N, K/16]")
+    packed = torch.empty(max(lib.nvfp4_prepack_bytes(N, K), 16), dtype=torch.uint8, device=codes.device)
+    _check("nvfp4_prepack", lib.nvfp4_prepack(
+        _dev(codes, torch.uint8, "codes"), _dev(scales, torch.uint8, "scales"), N, K,
+        packed.data_ptr(), _stream()))
+    return PackedWeight(packed, tensor_scale, N, K)
+
+
+def nvfp4_lora_linear_packed(x, w: PackedWeight, A: Optional[torch.Tensor] = None,
+                             B: Optional[torch.Tensor] = None, lora_scale: float = 0.0,
+                             workspace: Optional[Workspace] = None, out: Optional[torch.Tensor] = None):
+    """Same result as nvfp4_lora_linear, from tile-packed weights."""
+    lib = load_library()
+    M, K, ldx = _rows(x, "x")
+    N = w.N
+    if K != w.K:
+        raise ValueError("x has the wrong number of columns")
+    r = 0
+    a_ptr = b_ptr = None
+    if A is not None and B is not None and A.shape[0] > 0:
+        r = A.shape[0]
+        if tuple(A.shape) != (r, K) or tuple(B.shape) != (N, r) or not A.is_contiguous() or not B.is_contiguous():
+            raise ValueError("A must be contiguous [r, K] and B contiguous [N, r]")
+        a_ptr, b_ptr = _dev(A, torch.bfloat16, "A"), _dev(B, torch.bfloat16, "B")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    _, n_out, ldy = _rows(out, "out")
+    if out.shape[0] != M or n_out != N:
+        raise ValueError("out must be [M, N]")
+    if workspace is None:
+        workspace = Workspace(lib.nvfp4_lora_linear_workspace_bytes(M, N, K, r), x.device)
+    _check("nvfp4_lora_linear_packed", lib.nvfp4_lora_linear_packed(
+        _dev(x, torch.bfloat16, "x"), M, K, ldx, _dev(w.packed, torch.uint8, "packed"),
+        _dev(w.tensor_scale, torch.float32, "tensor_scale"), N, a_ptr, b_ptr, r, float(lora_scale),
+        _dev(out, torch.bfloat16, "out"), ldy, workspace.ptr, workspace.nbytes, _stream()))
     return out
 
 

@@ -26,10 +26,15 @@ static WorkspaceLayout workspace_layout(int64_t M, int64_t N, int64_t K, int64_t
   L.t_off = L.ctrl_bytes;
   const size_t t_bytes = align256((size_t)(M > 0 ? M : 1) * (size_t)(r > 0 ? r : 1) * sizeof(float));
   L.partial_off = L.t_off + t_bytes;
-  // worst case over the plans the dispatcher can choose: one K-tile per wave
+  // worst case over the plans the dispatchers can choose (one K-tile per wave)
   const size_t S_max = (size_t)ceil_div(ceil_div(K > 0 ? K : 1, 256), 8);
   const size_t tiles = L.n_main_ctr + n_down_ctr;
-  L.total = L.partial_off + align256(S_max * tiles * 64 * sizeof(f32x4));
+  const size_t S_down = (size_t)ceil_div(ceil_div(K > 0 ? K : 1, 256), 2) + 1;
+  const size_t skinny_bytes = (S_max * L.n_main_ctr + S_down * n_down_ctr) * 64 * sizeof(f32x4);
+  const size_t S_dec = (size_t)ceil_div(ceil_div(K > 0 ? K : 1, kPackTileK), 7);
+  const size_t decode_bytes = S_dec * (size_t)ceil_div(N > 0 ? N : 1, kPackTileRows) * 8 * 64 * sizeof(float) +
+                              S_down * n_down_ctr * 64 * sizeof(f32x4);
+  L.total = L.partial_off + align256(skinny_bytes > decode_bytes ? skinny_bytes : decode_bytes);
   return L;
 }
 
@@ -79,62 +84,138 @@ extern "C" int qerl_workspace_init(void* workspace, size_t bytes, void* stream) 
   return launch_status();
 }
 
+namespace qerl {
+
+struct LinearCall {
+  const uint16_t* x; int64_t M, K, ldx; const float* tensor_scale; int64_t N;
+  const uint16_t* A; const uint16_t* B; int64_t r; float lora_scale; uint16_t* y; int64_t ldy;
+  void* workspace; size_t workspace_bytes; hipStream_t st;
+};
+
+// Checks shared by the canonical and the packed entry point.
+static int validate(const LinearCall& c, const void* w0, const void* w1) {
+  if (c.M < 0 || c.N < 0 || c.K < 0 || c.r < 0 || c.K % kBlock != 0 || c.ldx < c.K || c.ldy < c.N)
+    return QERL_ERR_SHAPE;
+  if (c.N / 16 >= (int64_t)kMaxCounterTiles || c.r > 4096) return QERL_ERR_SHAPE;
+  if (c.M == 0 || c.N == 0) return 1;   // nothing to do
+  if (!c.x || !c.y || !c.tensor_scale) return QERL_ERR_NULL;
+  if (c.K > 0 && (!w0 || !w1)) return QERL_ERR_NULL;
+  if (c.r > 0 && (!c.A || !c.B)) return QERL_ERR_NULL;
+  if (!aligned(c.x, 2) || !aligned(c.y, 2) || (c.r > 0 && (!aligned(c.A, 2) || !aligned(c.B, 2))))
+    return QERL_ERR_ALIGN;
+  const WorkspaceLayout L = workspace_layout(c.M, c.N, c.K, c.r);
+  if (!c.workspace || !aligned(c.workspace, 256) || c.workspace_bytes < L.total) return QERL_ERR_WORKSPACE;
+  return QERL_OK;
+}
+
+// t[m0 .. m0+mc) = x A^T for one pass of at most 16 tokens.
+static int lora_down_pass(const LinearCall& c, const WorkspaceLayout& L, int64_t m0, int mc, f32x4* partial) {
+  uint8_t* ws = (uint8_t*)c.workspace;
+  float* t = (float*)(ws + L.t_off) + m0 * c.r;
+  const bool tiled = (c.K % 64 == 0) && aligned(c.x, 16) && c.ldx % 8 == 0 && aligned(c.A, 16);
+  if (!tiled) return launch_generic_lora_down(c.x + m0 * c.ldx, c.ldx, mc, c.K, c.A, c.r, t, c.st);
+  const SkinnyPlan pd = plan_skinny(c.r, c.K, kFmtBf16);
+  SkinnyArgs d{};
+  d.x = c.x + m0 * c.ldx; d.ldx = c.ldx; d.M = mc; d.K = c.K;
+  d.N = c.r; d.wbf16 = c.A; d.t_out = t;
+  d.partial = partial; d.counters = (uint32_t*)ws + L.n_main_ctr; d.n_tiles = pd.n_tiles;
+  return launch_skinny(pd, d, kFmtBf16, c.st);
+}
+
+}  // namespace qerl
+
 extern "C" int nvfp4_lora_linear(const void* x, int64_t M, int64_t K, int64_t ldx, const uint8_t* codes,
                                  const uint8_t* scales, const float* tensor_scale, int64_t N,
                                  const void* A, const void* B, int64_t r, float lora_scale, void* y,
                                  int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
-  if (M < 0 || N < 0 || K < 0 || r < 0 || K % kBlock != 0 || ldx < K || ldy < N) return QERL_ERR_SHAPE;
-  if (N / 16 >= (int64_t)kMaxCounterTiles || r > 4096) return QERL_ERR_SHAPE;
-  if (M == 0 || N == 0) return QERL_OK;
-  if (!x || !y || !tensor_scale) return QERL_ERR_NULL;
-  if (K > 0 && (!codes || !scales)) return QERL_ERR_NULL;
-  if (r > 0 && (!A || !B)) return QERL_ERR_NULL;
-  if (!aligned(x, 2) || !aligned(y, 2) || (r > 0 && (!aligned(A, 2) || !aligned(B, 2)))) return QERL_ERR_ALIGN;
+  LinearCall c{(const uint16_t*)x, M, K, ldx, tensor_scale, N, (const uint16_t*)A, (const uint16_t*)B, r,
+               lora_scale, (uint16_t*)y, ldy, workspace, workspace_bytes, (hipStream_t)stream};
+  const int vr = validate(c, codes, scales);
+  if (vr != QERL_OK) return vr > 0 ? QERL_OK : vr;
+  if (K == 0) c.r = r = 0;   // empty sums: y = 0 through the general kernel
   const WorkspaceLayout L = workspace_layout(M, N, K, r);
-  if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total) return QERL_ERR_WORKSPACE;
-
-  hipStream_t st = (hipStream_t)stream;
   uint8_t* ws = (uint8_t*)workspace;
-  uint32_t* ctr_main = (uint32_t*)ws;
-  uint32_t* ctr_down = ctr_main + L.n_main_ctr;
   float* t = (float*)(ws + L.t_off);
   f32x4* partial = (f32x4*)(ws + L.partial_off);
-  const uint16_t* xp = (const uint16_t*)x;
-  uint16_t* yp = (uint16_t*)y;
-  if (K == 0) r = 0;   // empty sums: y = 0 through the general kernel
 
   // The tiled kernels use 16-byte loads; anything else goes to the general kernels.
   const bool tiled = (K % 64 == 0) && K > 0 && aligned(x, 16) && ldx % 8 == 0 && aligned(codes, 16) &&
                      aligned(scales, 4) && (r == 0 || aligned(A, 16));
   if (!tiled) {
     int rc = QERL_OK;
-    if (r > 0) rc = launch_generic_lora_down(xp, ldx, M, K, (const uint16_t*)A, r, t, st);
+    if (r > 0) rc = launch_generic_lora_down(c.x, ldx, M, K, c.A, r, t, c.st);
     if (rc != QERL_OK) return rc;
-    return launch_generic_linear(xp, ldx, M, K, codes, scales, tensor_scale, N, r > 0 ? t : nullptr,
-                                 (const uint16_t*)B, r, lora_scale, yp, ldy, st);
+    return launch_generic_linear(c.x, ldx, M, K, codes, scales, tensor_scale, N, r > 0 ? t : nullptr, c.B, r,
+                                 lora_scale, c.y, ldy, c.st);
   }
 
-  // Tiled path: passes of up to 16 tokens through the skinny kernels.
+  // Tiled path on the canonical layout: passes of up to 16 tokens.
   const SkinnyPlan pm = plan_skinny(N, K, kFmtNvfp4);
-  const SkinnyPlan pd = plan_skinny(r > 0 ? r : 1, K, kFmtBf16);
   for (int64_t m0 = 0; m0 < M; m0 += 16) {
     const int mc = (int)((M - m0 < 16) ? M - m0 : 16);
-    SkinnyArgs a{};
-    a.x = xp + m0 * ldx; a.ldx = ldx; a.M = mc; a.K = K;
     if (r > 0) {
-      SkinnyArgs d = a;
-      d.N = r; d.wbf16 = (const uint16_t*)A; d.t_out = t + m0 * r;
-      d.partial = partial + (size_t)pm.S * pm.n_tiles * 64; d.counters = ctr_down; d.n_tiles = pd.n_tiles;
-      const int rc = launch_skinny(pd, d, kFmtBf16, st);
+      const int rc = lora_down_pass(c, L, m0, mc, partial + (size_t)pm.S * pm.n_tiles * 64);
       if (rc != QERL_OK) return rc;
     }
+    SkinnyArgs a{};
+    a.x = c.x + m0 * ldx; a.ldx = ldx; a.M = mc; a.K = K;
     a.N = N; a.codes = codes; a.scales = scales; a.tensor_scale = tensor_scale;
-    a.t_in = t + m0 * r; a.B = (const uint16_t*)B; a.r = (int)r; a.lora_scale = lora_scale;
-    a.y = yp + m0 * ldy; a.ldy = ldy;
+    a.t_in = t + m0 * r; a.B = c.B; a.r = (int)r; a.lora_scale = lora_scale;
+    a.y = c.y + m0 * ldy; a.ldy = ldy;
     a.y_vec = aligned(y, 8) && ldy % 4 == 0;
     a.b_vec = r % 8 == 0 && aligned(B, 16);
-    a.partial = partial; a.counters = ctr_main; a.n_tiles = pm.n_tiles;
-    const int rc = launch_skinny(pm, a, kFmtNvfp4, st);
+    a.partial = partial; a.counters = (uint32_t*)ws; a.n_tiles = pm.n_tiles;
+    const int rc = launch_skinny(pm, a, kFmtNvfp4, c.st);
+    if (rc != QERL_OK) return rc;
+  }
+  return QERL_OK;
+}
+
+extern "C" size_t nvfp4_prepack_bytes(int64_t N, int64_t K) {
+  if (N <= 0 || K <= 0) return 0;
+  return (size_t)ceil_div(N, kPackTileRows) * (size_t)ceil_div(K, kPackTileK) * kPackTileBytes;
+}
+
+extern "C" int nvfp4_prepack(const uint8_t* codes, const uint8_t* scales, int64_t N, int64_t K, void* packed,
+                             void* stream) {
+  if (N < 0 || K < 0 || K % kBlock != 0) return QERL_ERR_SHAPE;
+  if (N == 0 || K == 0) return QERL_OK;
+  if (!codes || !scales || !packed) return QERL_ERR_NULL;
+  if (!aligned(packed, 16)) return QERL_ERR_ALIGN;
+  return launch_prepack(codes, scales, N, K, (uint8_t*)packed, (hipStream_t)stream);
+}
+
+extern "C" int nvfp4_lora_linear_packed(const void* x, int64_t M, int64_t K, int64_t ldx, const void* packed,
+                                        const float* tensor_scale, int64_t N, const void* A, const void* B,
+                                        int64_t r, float lora_scale, void* y, int64_t ldy, void* workspace,
+                                        size_t workspace_bytes, void* stream) {
+  LinearCall c{(const uint16_t*)x, M, K, ldx, tensor_scale, N, (const uint16_t*)A, (const uint16_t*)B, r,
+               lora_scale, (uint16_t*)y, ldy, workspace, workspace_bytes, (hipStream_t)stream};
+  const int vr = validate(c, packed, packed);
+  if (vr != QERL_OK) return vr > 0 ? QERL_OK : vr;
+  if (K == 0) return QERL_ERR_SHAPE;
+  if (!aligned(packed, 16) || !aligned(x, 16) || ldx % 8 != 0) return QERL_ERR_ALIGN;
+  const WorkspaceLayout L = workspace_layout(M, N, K, r);
+  uint8_t* ws = (uint8_t*)workspace;
+  float* t = (float*)(ws + L.t_off);
+  uint32_t* partial = (uint32_t*)(ws + L.partial_off);
+
+  for (int64_t m0 = 0; m0 < M; m0 += 16) {
+    const int mc = (int)((M - m0 < 16) ? M - m0 : 16);
+    const DecodePlan p = plan_decode(mc, N, K, r);
+    const size_t dec_words = (size_t)p.S * p.n_tiles * p.MR * 64;
+    if (r > 0) {
+      const int rc = lora_down_pass(c, L, m0, mc, (f32x4*)(partial + ((dec_words + 3) & ~(size_t)3)));
+      if (rc != QERL_OK) return rc;
+    }
+    DecodeArgs a{};
+    a.x = c.x + m0 * ldx; a.ldx = ldx; a.M = mc; a.K = K; a.N = N;
+    a.packed = (const uint8_t*)packed; a.k_tiles = p.k_tiles; a.tensor_scale = tensor_scale;
+    a.t_in = t + m0 * r; a.B = c.B; a.r = (int)r; a.lora_scale = lora_scale;
+    a.b_vec = r % 8 == 0 && aligned(B, 16);
+    a.y = c.y + m0 * ldy; a.ldy = ldy;
+    a.partial = partial; a.counters = (uint32_t*)ws; a.n_tiles = p.n_tiles;
+    const int rc = launch_decode(p, a, c.st);
     if (rc != QERL_OK) return rc;
   }
   return QERL_OK;

@@ -21,6 +21,24 @@ struct SkinnyPlan { int KT, T, S, waves, n_tiles, groups; };
 SkinnyPlan plan_skinny(int64_t N, int64_t K, int fmt);
 int launch_skinny(const SkinnyPlan& p, const SkinnyArgs& a, int fmt, hipStream_t st);
 
+// ---- decode path on tile-packed weights (linear_decode.hip) ----
+constexpr int kPackTileRows = 32;     // output rows per tile
+constexpr int kPackTileK = 128;       // inputs per tile (8 scale blocks)
+constexpr int kPackTileBytes = 2304;  // 2048 B codes + 256 B scales = 0.5625 B per weight
+
+struct DecodeArgs {
+  const uint16_t* x; int64_t ldx; int M; int64_t K; int64_t N;
+  const uint8_t* packed; int64_t k_tiles; const float* tensor_scale;
+  const float* t_in; const uint16_t* B; int r; float lora_scale; bool b_vec;
+  uint16_t* y; int64_t ldy;
+  uint32_t* partial; uint32_t* counters; int n_tiles;
+};
+struct DecodePlan { int KW, T, MR, S, main_waves, waves, n_tiles, groups; int64_t k_tiles; };
+DecodePlan plan_decode(int64_t M, int64_t N, int64_t K, int64_t r);
+int launch_decode(const DecodePlan& p, const DecodeArgs& a, hipStream_t st);
+int launch_prepack(const uint8_t* codes, const uint8_t* scales, int64_t N, int64_t K, uint8_t* out,
+                   hipStream_t st);
+
 // General fallback (any K % 16 == 0, any alignment of rows the ABI allows).
 int launch_generic_lora_down(const uint16_t* x, int64_t ldx, int64_t M, int64_t K, const uint16_t* A,
                              int64_t r, float* t, hipStream_t st);

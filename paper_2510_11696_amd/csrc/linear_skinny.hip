@@ -15,7 +15,7 @@
 //   * E2M1 -> fp32 by v_cvt_scalef32_pk_f32_fp4, times the E4M3 scale in fp32,
 //     packed to bf16.  The product has at most 6 significant bits, so the bf16
 //     operand is exact and v_mfma_f32_16x16x32_bf16 accumulates in fp32.
-//     S32 is applied once in the epilogue.
+//     S32 is applied once per wave, after its K-slice is summed.
 //   * Waves of a workgroup cover different K-slices of the same rows and are
 //     summed through LDS in wave order.  If K needs more than one workgroup
 //     (gridDim.y = S > 1) each writes its partial tile to the workspace and the
@@ -85,6 +85,65 @@ __global__ __launch_bounds__(kMaxWaves * 64) void skinny_kernel(const SkinnyArgs
 #pragma unroll
   for (int t = 0; t < T; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+  // LoRA up-projection  sum_j t[m,j] * B[n,j]  as MFMAs over j, done by one
+  // wave per output tile (wave 0 of the first K-slice).  t is fp32; it is split
+  // into three bf16 terms (t = hi + mid + lo up to 2^-27 |t|), whose products
+  // with the bf16 B are exact, so the branch keeps fp32 accuracy.
+  f32x4 lacc[T];
+#pragma unroll
+  for (int t = 0; t < T; ++t) lacc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  if constexpr (FMT == kFmtNvfp4) {
+    if (a.r > 0 && wave == 0 && blockIdx.y == 0) {
+      for (int jb = 0; jb < a.r; jb += 32) {
+        const int j0 = jb + 8 * g;
+        float tv[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) tv[i] = 0.f;
+        if (r16 < a.M) {
+          const float* tp = a.t_in + (int64_t)r16 * a.r + j0;
+          if (a.b_vec) {
+            if (j0 < a.r) {
+              const f32x4 t0 = *reinterpret_cast<const f32x4*>(tp), t1 = *reinterpret_cast<const f32x4*>(tp + 4);
+              tv[0] = t0[0]; tv[1] = t0[1]; tv[2] = t0[2]; tv[3] = t0[3];
+              tv[4] = t1[0]; tv[5] = t1[1]; tv[6] = t1[2]; tv[7] = t1[3];
+            }
+          } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+              if (j0 + i < a.r) tv[i] = tp[i];
+          }
+        }
+        u32x4 th, tm, tl;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const uint32_t h = pack_bf16x2(tv[2 * i], tv[2 * i + 1]);
+          const float r0 = tv[2 * i] - bf16_bits_to_f32(h & 0xffffu), r1 = tv[2 * i + 1] - __uint_as_float(h & 0xffff0000u);
+          const uint32_t m = pack_bf16x2(r0, r1);
+          const float q0 = r0 - bf16_bits_to_f32(m & 0xffffu), q1 = r1 - __uint_as_float(m & 0xffff0000u);
+          th[i] = h; tm[i] = m; tl[i] = pack_bf16x2(q0, q1);
+        }
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+          int64_t row = (int64_t)(tile0 + t) * 16 + r16;
+          row = row < a.N ? row : a.N - 1;
+          const uint16_t* bp = a.B + row * a.r + j0;
+          u32x4 b = {0u, 0u, 0u, 0u};
+          if (a.b_vec) {
+            if (j0 < a.r) b = *reinterpret_cast<const u32x4*>(bp);
+          } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+              if (j0 + i < a.r) b[i >> 1] |= (uint32_t)bp[i] << (16 * (i & 1));
+          }
+          const bf16x8 bf = __builtin_bit_cast(bf16x8, b);
+          lacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bf, __builtin_bit_cast(bf16x8, th), lacc[t], 0, 0, 0);
+          lacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bf, __builtin_bit_cast(bf16x8, tm), lacc[t], 0, 0, 0);
+          lacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bf, __builtin_bit_cast(bf16x8, tl), lacc[t], 0, 0, 0);
+        }
+      }
+    }
+  }
+
   if constexpr (FMT == kFmtNvfp4) {
     u32x4 c0[T][KT], c1[T][KT];
     uint32_t sc[T][KT];
@@ -143,6 +202,11 @@ __global__ __launch_bounds__(kMaxWaves * 64) void skinny_kernel(const SkinnyArgs
   // ---- sum the waves of this workgroup (different K-slices), in wave order
   __shared__ f32x4 red[kMaxWaves][T][64];
   __shared__ int s_last;
+  if constexpr (FMT == kFmtNvfp4) {
+    const float S32 = *a.tensor_scale;
+#pragma unroll
+    for (int t = 0; t < T; ++t) acc[t] = acc[t] * S32 + lacc[t] * a.lora_scale;
+  }
 #pragma unroll
   for (int t = 0; t < T; ++t) red[wave][t][lane] = acc[t];
   __syncthreads();
@@ -162,35 +226,48 @@ __global__ __launch_bounds__(kMaxWaves * 64) void skinny_kernel(const SkinnyArgs
   // ---- more than one workgroup along K: exchange partial tiles
   const int S = gridDim.y;
   if (S > 1) {
-#pragma unroll
-    for (int q = 0; q < T; ++q) {
-      const int slot = tid + q * (int)blockDim.x;
-      const int tile = tile0 + (slot >> 6);
-      if (slot < kSlots && tile < a.n_tiles)
-        a.partial[((int64_t)blockIdx.y * a.n_tiles + tile) * 64 + (slot & 63)] = v[q];
-    }
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-      const uint32_t old = __hip_atomic_fetch_add(a.counters + blockIdx.x, 1u, __ATOMIC_ACQ_REL,
-                                                  __HIP_MEMORY_SCOPE_AGENT);
-      s_last = (old == (uint32_t)(S - 1));
-    }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
+    // Partial tiles travel through memory with agent-scope atomic accesses
+    // (sc1: written through / read past the per-XCD L2), so no cache-wide
+    // write-back or invalidate is needed; each wave waits for its own stores
+    // to complete before the barrier that precedes the arrival count.
+    uint32_t* pw = reinterpret_cast<uint32_t*>(a.partial);
 #pragma unroll
     for (int q = 0; q < T; ++q) {
       const int slot = tid + q * (int)blockDim.x;
       const int tile = tile0 + (slot >> 6);
       if (slot < kSlots && tile < a.n_tiles) {
-        const f32x4* p = a.partial + (int64_t)tile * 64 + (slot & 63);
-        f32x4 s = p[0];
-        for (int w = 1; w < S; ++w) s += p[(int64_t)w * a.n_tiles * 64];
+        uint32_t* dst = pw + (((int64_t)blockIdx.y * a.n_tiles + tile) * 64 + (slot & 63)) * 4;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          __hip_atomic_store(dst + i, __float_as_uint(v[q][i]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's partial stores have completed
+    __syncthreads();
+    if (tid == 0) {
+      const uint32_t old = __hip_atomic_fetch_add(a.counters + blockIdx.x, 1u, __ATOMIC_RELAXED,
+                                                  __HIP_MEMORY_SCOPE_AGENT);
+      s_last = (old == (uint32_t)(S - 1));
+    }
+    __syncthreads();
+    if (!s_last) return;
+#pragma unroll
+    for (int q = 0; q < T; ++q) {
+      const int slot = tid + q * (int)blockDim.x;
+      const int tile = tile0 + (slot >> 6);
+      if (slot < kSlots && tile < a.n_tiles) {
+        const uint32_t* src = pw + ((int64_t)tile * 64 + (slot & 63)) * 4;
+        f32x4 s = {0.f, 0.f, 0.f, 0.f};
+        for (int w = 0; w < S; ++w) {
+          const uint32_t* p = src + (int64_t)w * a.n_tiles * 256;
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            s[i] += __uint_as_float(__hip_atomic_load(p + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        }
         v[q] = s;
       }
     }
-    if (tid == 0) a.counters[blockIdx.x] = 0u;   // ready for the next call
+    if (tid == 0) __hip_atomic_store(a.counters + blockIdx.x, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 
   // ---- epilogue
@@ -205,36 +282,7 @@ __global__ __launch_bounds__(kMaxWaves * 64) void skinny_kernel(const SkinnyArgs
       for (int i = 0; i < 4; ++i)
         if (nb + i < a.N) a.t_out[(int64_t)token * a.N + nb + i] = v[nv][i];
     } else {
-      const float S32 = *a.tensor_scale;
-      float o[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        o[i] = v[nv][i] * S32;
-        const int64_t n = nb + i;
-        if (a.r > 0 && n < a.N) {
-          const float* tp = a.t_in + (int64_t)token * a.r;
-          const uint16_t* bp = a.B + n * a.r;
-          float lo = 0.f;
-          if (a.b_vec) {
-            for (int j = 0; j < a.r; j += 8) {
-              const u32x4 b = *reinterpret_cast<const u32x4*>(bp + j);
-              const f32x4 t0 = *reinterpret_cast<const f32x4*>(tp + j);
-              const f32x4 t1 = *reinterpret_cast<const f32x4*>(tp + j + 4);
-              lo += t0[0] * bf16_bits_to_f32(b[0] & 0xffffu);
-              lo += t0[1] * bf16_bits_to_f32(b[0] >> 16);
-              lo += t0[2] * bf16_bits_to_f32(b[1] & 0xffffu);
-              lo += t0[3] * bf16_bits_to_f32(b[1] >> 16);
-              lo += t1[0] * bf16_bits_to_f32(b[2] & 0xffffu);
-              lo += t1[1] * bf16_bits_to_f32(b[2] >> 16);
-              lo += t1[2] * bf16_bits_to_f32(b[3] & 0xffffu);
-              lo += t1[3] * bf16_bits_to_f32(b[3] >> 16);
-            }
-          } else {
-            for (int j = 0; j < a.r; ++j) lo += tp[j] * bf16_bits_to_f32(bp[j]);
-          }
-          o[i] += a.lora_scale * lo;
-        }
-      }
+      const float o[4] = {v[nv][0], v[nv][1], v[nv][2], v[nv][3]};
       uint16_t* yp = a.y + (int64_t)token * a.ldy + nb;
       if (a.y_vec && nb + 3 < a.N) {
         *reinterpret_cast<u32x2*>(yp) = u32x2{pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
@@ -254,20 +302,29 @@ static int g_force_kt = 0, g_force_t = 0;
 SkinnyPlan plan_skinny(int64_t N, int64_t K, int fmt) {
   SkinnyPlan p;
   const int64_t tiles = ceil_div(K, 256);
+  p.n_tiles = (int)ceil_div(N, 16);
+  if (fmt == kFmtBf16) {
+    // LoRA down-projection: few rows, so spread K over many small workgroups
+    // (two waves, 512 inputs) and let the last one to arrive add the partials.
+    p.KT = 1;
+    p.T = 1;
+    p.waves = tiles >= 2 ? 2 : 1;
+    p.S = (int)ceil_div(tiles, p.waves);
+    p.groups = p.n_tiles;
+    return p;
+  }
   p.KT = (tiles >= 2) ? 2 : 1;
   if (g_force_kt) p.KT = g_force_kt;
   const int64_t slices = ceil_div(tiles, p.KT);
   p.S = (int)ceil_div(slices, kMaxWaves);
   p.waves = (int)ceil_div(slices, p.S);
-  p.n_tiles = (int)ceil_div(N, 16);
   // rows per workgroup: aim at one resident round of workgroups on 256 CUs
   const int64_t want = 256;
   int T = 1;
   const int cand[3] = {1, 2, 4};
   for (int c : cand)
     if (ceil_div(p.n_tiles, c) * p.S >= want) T = c;
-  if (fmt == kFmtBf16) T = 1;
-  if (g_force_t && fmt == kFmtNvfp4) T = g_force_t;
+  if (g_force_t) T = g_force_t;
   p.T = T;
   p.groups = (int)ceil_div(p.n_tiles, p.T);
   return p;

@@ -22,14 +22,19 @@ def _problem(M, N, K, r, seed, w_std=0.02, W=None):
     return W, x, A, B
 
 
-def _run(M, N, K, r, seed, alpha_over_r=2.0, W=None, label=""):
-    print("linear case", label, M, N, K, r, seed, flush=True)
+def _run(M, N, K, r, seed, alpha_over_r=2.0, W=None, label="", packed=False):
+    print("linear case", label, M, N, K, r, seed, "packed" if packed else "canonical", flush=True)
     W, x, A, B = _problem(M, N, K, r, seed, W=W)
     codes, scales, ts = oracle.nvfp4_quantize(W)
     g = lambda a: torch.from_numpy(a).cuda()
     ts_gpu = torch.tensor([ts], dtype=torch.float32, device="cuda")
-    y = qerl.nvfp4_lora_linear(x.cuda(), g(codes), g(scales), ts_gpu,
-                               A.cuda() if r else None, B.cuda() if r else None, alpha_over_r)
+    if packed:
+        pw = qerl.nvfp4_prepack(g(codes), g(scales), ts_gpu)
+        y = qerl.nvfp4_lora_linear_packed(x.cuda(), pw, A.cuda() if r else None, B.cuda() if r else None,
+                                          alpha_over_r)
+    else:
+        y = qerl.nvfp4_lora_linear(x.cuda(), g(codes), g(scales), ts_gpu,
+                                   A.cuda() if r else None, B.cuda() if r else None, alpha_over_r)
     torch.cuda.synchronize()
     ref = oracle.nvfp4_lora_linear(x.float().numpy(), codes, scales, ts,
                                    A.float().numpy() if r else None, B.float().numpy() if r else None,
@@ -38,26 +43,34 @@ def _run(M, N, K, r, seed, alpha_over_r=2.0, W=None, label=""):
     return y, ref
 
 
-def test_config1_single_linear():
+PATHS = [False, True]   # canonical layout, tile-packed layout
+
+
+@pytest.mark.parametrize("packed", PATHS)
+def test_config1_single_linear(packed):
     """K = N = 2048, one token, LoRA r = 16, alpha = 32."""
-    _run(1, 2048, 2048, 16, seed=qs.seed_for(1, 0), alpha_over_r=32.0 / 16)
+    _run(1, 2048, 2048, 16, seed=qs.seed_for(1, 0), alpha_over_r=32.0 / 16, packed=packed)
 
 
-@pytest.mark.parametrize("M", [1, 2, 3, 8, 15, 16])
+@pytest.mark.parametrize("packed", PATHS)
+@pytest.mark.parametrize("M", [1, 2, 3, 8, 9, 15, 16])
 @pytest.mark.parametrize("N,K,r", [(512, 3584, 32), (3584, 3584, 32), (96, 18944, 32), (1184, 3584, 0)])
-def test_decode_shapes(M, N, K, r):
-    _run(M, N, K, r, seed=M * 7 + N + K)
+def test_decode_shapes(M, N, K, r, packed):
+    _run(M, N, K, r, seed=M * 7 + N + K, packed=packed)
 
 
+@pytest.mark.parametrize("packed", PATHS)
 @pytest.mark.parametrize("M,N,K,r", [
     (3, 40, 320, 8),       # ragged N tile, K not a multiple of 256
     (5, 17, 64, 3),        # single K chunk, odd rank
     (16, 1000, 2112, 16),  # ragged everything, several tiles
     (7, 16, 5120, 64),     # two workgroups along K
-    (2, 33, 27648, 64),    # seven workgroups along K
+    (2, 33, 27648, 64),    # many workgroups along K
+    (4, 70, 1024, 80),     # rank beyond the preloaded 64
+    (8, 64, 48, 4),        # K smaller than one tile and not a multiple of 64
 ])
-def test_ragged_shapes(M, N, K, r):
-    _run(M, N, K, r, seed=M + N + K)
+def test_ragged_shapes(M, N, K, r, packed):
+    _run(M, N, K, r, seed=M + N + K, packed=packed)
 
 
 @pytest.mark.parametrize("M,N,K,r", [(4, 24, 48, 4), (1, 8, 16, 0), (9, 130, 1040, 16)])
@@ -65,16 +78,57 @@ def test_general_kernel_k_not_multiple_of_64(M, N, K, r):
     _run(M, N, K, r, seed=3 * M + N)
 
 
+@pytest.mark.parametrize("packed", PATHS)
 @pytest.mark.parametrize("M", [17, 32, 100, 128])
-def test_more_than_16_tokens(M):
-    _run(M, 512, 3584, 32, seed=M)
+def test_more_than_16_tokens(M, packed):
+    _run(M, 512, 3584, 32, seed=M, packed=packed)
 
 
-def test_adversarial_weights_through_the_linear():
+@pytest.mark.parametrize("packed", PATHS)
+def test_adversarial_weights_through_the_linear(packed):
     for name, W in cases.quantizer_cases(48, 512, seed=31).items():
         if name in ("scaled_up", "scaled_down"):
             continue
-        _run(4, 48, 512, 8, seed=5, W=W, label=name)
+        _run(4, 48, 512, 8, seed=5, W=W, label=name, packed=packed)
+
+
+def _pack_reference(codes, scales):
+    """The tile-packed layout written out with numpy from its definition:
+    tiles of 32 rows x 128 inputs, 2304 bytes each; lane l = (n = l % 32, kg = l // 32)
+    owns, per 16-input step j, the 4 code bytes of inputs 16 j + 8 kg .. + 7."""
+    N, K = codes.shape[0], codes.shape[1] * 2
+    nt, kt = -(-N // 32), -(-K // 128)
+    cp = np.zeros((nt * 32, kt * 64), dtype=np.uint8)
+    cp[:N, :K // 2] = codes
+    sp = np.zeros((nt * 32, kt * 8), dtype=np.uint8)
+    sp[:N, :K // 16] = scales
+    out = np.zeros((nt, kt, 2304), dtype=np.uint8)
+    for a in range(nt):
+        for b in range(kt):
+            tile_c = cp[a * 32:(a + 1) * 32, b * 64:(b + 1) * 64]      # [n, 64 bytes]
+            for plane in range(2):
+                for lane in range(64):
+                    n, kg = lane % 32, lane // 32
+                    for dw in range(4):
+                        j = 4 * plane + dw
+                        src = tile_c[n, 8 * j + 4 * kg: 8 * j + 4 * kg + 4]
+                        off = plane * 1024 + lane * 16 + dw * 4
+                        out[a, b, off:off + 4] = src
+            out[a, b, 2048:] = sp[a * 32:(a + 1) * 32, b * 8:(b + 1) * 8].reshape(-1)
+    return out.reshape(-1)
+
+
+@pytest.mark.parametrize("N,K", [(32, 128), (40, 320), (100, 48), (64, 1024)])
+def test_prepack_is_the_documented_permutation(N, K):
+    rng = np.random.default_rng(N + K)
+    codes = rng.integers(0, 256, size=(N, K // 2)).astype(np.uint8)
+    scales = rng.integers(0, 0x7F, size=(N, K // 16)).astype(np.uint8)
+    pw = qerl.nvfp4_prepack(torch.from_numpy(codes).cuda(), torch.from_numpy(scales).cuda(),
+                            torch.ones(1, device="cuda"))
+    got = pw.packed.cpu().numpy()
+    want = _pack_reference(codes, scales)
+    assert got.size == want.size == -(-N // 32) * -(-K // 128) * 2304
+    assert np.array_equal(got, want)
 
 
 def test_one_hot_reads_exact_dequantised_column():
@@ -90,25 +144,35 @@ def test_one_hot_reads_exact_dequantised_column():
     y = qerl.nvfp4_lora_linear(x.cuda(), g(codes), g(scales), torch.tensor([ts], device="cuda"))
     want = torch.from_numpy(Wh[:, ks].T.copy()).to(torch.bfloat16)
     assert torch.equal(y.cpu(), want)
+    pw = qerl.nvfp4_prepack(g(codes), g(scales), torch.tensor([ts], device="cuda"))
+    assert torch.equal(qerl.nvfp4_lora_linear_packed(x.cuda(), pw).cpu(), want)
 
 
-def test_deterministic_and_workspace_reuse():
+@pytest.mark.parametrize("packed", PATHS)
+def test_deterministic_and_workspace_reuse(packed):
     M, N, K, r = 8, 3584, 18944, 32
     W, x, A, B = _problem(M, N, K, r, 11)
     cw, sw, tw = qerl.nvfp4_quantize(to_gpu_bf16(W))
     ws = qerl.Workspace(qerl.nvfp4_lora_linear_workspace_bytes(M, N, K, r))
-    args = (x.cuda(), cw, sw, tw, A.cuda(), B.cuda(), 2.0)
-    y0 = qerl.nvfp4_lora_linear(*args, workspace=ws).clone()
+    if packed:
+        pw = qerl.nvfp4_prepack(cw, sw, tw)
+        call = lambda x_, w_, A_, B_, **kw: qerl.nvfp4_lora_linear_packed(x_, w_, A_, B_, 2.0, **kw)
+        w1 = pw
+    else:
+        call = lambda x_, w_, A_, B_, **kw: qerl.nvfp4_lora_linear(x_, *w_, A_, B_, 2.0, **kw)
+        w1 = (cw, sw, tw)
+    args = (x.cuda(), w1, A.cuda(), B.cuda())
+    y0 = call(*args, workspace=ws).clone()
     for _ in range(10):
-        y = qerl.nvfp4_lora_linear(*args, workspace=ws)
-        assert torch.equal(y, y0)
+        assert torch.equal(call(*args, workspace=ws), y0)
     # a different, smaller problem on the same workspace, then the first again
     W2, x2, A2, B2 = _problem(3, 96, 18944, 32, 12)
     c2, s2, t2 = qerl.nvfp4_quantize(to_gpu_bf16(W2))
-    y2 = qerl.nvfp4_lora_linear(x2.cuda(), c2, s2, t2, A2.cuda(), B2.cuda(), 2.0, workspace=ws)
-    y2b = qerl.nvfp4_lora_linear(x2.cuda(), c2, s2, t2, A2.cuda(), B2.cuda(), 2.0)
+    w2 = qerl.nvfp4_prepack(c2, s2, t2) if packed else (c2, s2, t2)
+    y2 = call(x2.cuda(), w2, A2.cuda(), B2.cuda(), workspace=ws)
+    y2b = call(x2.cuda(), w2, A2.cuda(), B2.cuda())
     assert torch.equal(y2, y2b)
-    assert torch.equal(qerl.nvfp4_lora_linear(*args, workspace=ws), y0)
+    assert torch.equal(call(*args, workspace=ws), y0)
 
 
 def test_strided_x_and_y_and_canaries():

@@ -12,7 +12,7 @@ void set_last_hip_error(int e) { g_last_hip_error = e; }
 //   [0, ctrl_bytes)     arrival counters (uint32): main tiles, then LoRA-down tiles
 //   [t_off, ...)        t = x A^T, fp32 [M, r]
 //   [partial_off, ...)  split-K partial tiles, fp32
-struct WorkspaceLayout { size_t ctrl_bytes, n_main_ctr, t_off, partial_off, total; };
+struct WorkspaceLayout { size_t ctrl_bytes, n_main_ctr, n_down_ctr, t_off, partial_off, total; };
 
 constexpr size_t kMaxCounterTiles = 1 << 16;   // rows / 16 the control region can serve
 
@@ -22,9 +22,13 @@ static WorkspaceLayout workspace_layout(int64_t M, int64_t N, int64_t K, int64_t
   WorkspaceLayout L;
   L.n_main_ctr = (size_t)ceil_div(N > 0 ? N : 1, 16);
   const size_t n_down_ctr = (size_t)ceil_div(r > 0 ? r : 1, 16);
+  L.n_down_ctr = n_down_ctr;
   L.ctrl_bytes = align256((L.n_main_ctr + n_down_ctr) * sizeof(uint32_t));
   L.t_off = L.ctrl_bytes;
-  const size_t t_bytes = align256((size_t)(M > 0 ? M : 1) * (size_t)(r > 0 ? r : 1) * sizeof(float));
+  // t = x A^T: fp32 [M, r] for the decode kernels, or three bf16 terms [M, ceil64(3r)] for the GEMM
+  const size_t rows = (size_t)(M > 0 ? M : 1), rr = (size_t)(r > 0 ? r : 1);
+  const size_t t_f32 = rows * rr * sizeof(float), t_split = rows * (size_t)ceil_div(3 * rr, 64) * 64 * 2;
+  const size_t t_bytes = align256(t_f32 > t_split ? t_f32 : t_split);
   L.partial_off = L.t_off + t_bytes;
   // worst case over the plans the dispatchers can choose (one K-tile per wave)
   const size_t S_max = (size_t)ceil_div(ceil_div(K > 0 ? K : 1, 256), 8);
@@ -34,7 +38,8 @@ static WorkspaceLayout workspace_layout(int64_t M, int64_t N, int64_t K, int64_t
   const size_t S_dec = (size_t)ceil_div(ceil_div(K > 0 ? K : 1, kPackTileK), 7);
   const size_t decode_bytes = S_dec * (size_t)ceil_div(N > 0 ? N : 1, kPackTileRows) * 8 * 64 * sizeof(float) +
                               S_down * n_down_ctr * 64 * sizeof(f32x4);
-  L.total = L.partial_off + align256(skinny_bytes > decode_bytes ? skinny_bytes : decode_bytes);
+  size_t need = skinny_bytes > decode_bytes ? skinny_bytes : decode_bytes;
+  L.total = L.partial_off + align256(need);
   return L;
 }
 
@@ -199,6 +204,25 @@ extern "C" int nvfp4_lora_linear_packed(const void* x, int64_t M, int64_t K, int
   uint8_t* ws = (uint8_t*)workspace;
   float* t = (float*)(ws + L.t_off);
   uint32_t* partial = (uint32_t*)(ws + L.partial_off);
+
+  const bool lora_gemm_ok = r == 0 || (r % 8 == 0 && aligned(A, 16) && aligned(B, 16));
+  if (M > 16 && lora_gemm_ok) {
+    // Prefill: one split-K GEMM writes lora_scale * x A^T as three bf16 terms into the workspace,
+    // then one GEMM computes the layer with those 3r columns appended to K.
+    GemmArgs g{};
+    g.x = c.x; g.ldx = ldx; g.M = M; g.K = K; g.k_tiles = ceil_div(K, kPackTileK);
+    g.ts = (const uint16_t*)(ws + L.t_off); g.ext_stages = (int)ceil_div(3 * r, 64); g.ts_ld = (int64_t)g.ext_stages * 64;
+    g.r = (int)r; g.lora_scale = lora_scale; g.tensor_scale = tensor_scale;
+    if (r > 0) {
+      GemmArgs d = g;
+      d.N = r; d.wbf16 = c.A; d.n_tiles = (int)ceil_div(r, 32);
+      const int rc = launch_lora_down_gemm(d, c.st);
+      if (rc != QERL_OK) return rc;
+    }
+    g.N = N; g.packed = (const uint8_t*)packed; g.n_tiles = (int)ceil_div(N, 32);
+    g.B = c.B; g.y = c.y; g.ldy = ldy;
+    return launch_gemm(g, c.st);
+  }
 
   for (int64_t m0 = 0; m0 < M; m0 += 16) {
     const int mc = (int)((M - m0 < 16) ? M - m0 : 16);

@@ -29,6 +29,7 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // ---- device side ----------------------------------------------------------
+__device__ __forceinline__ int64_t ceil_div_dev(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // bf16 <-> fp32 by bit manipulation (bf16 is the top half of an fp32).
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
 
@@ -54,6 +55,24 @@ __device__ __forceinline__ float e2m1_to_f32(uint32_t c) {
   // place exponent(2)+mantissa(1) like above, re-bias 127 -> 1
   float mag = __uint_as_float((c & 7u) << 22) * 0x1p126f;
   return __uint_as_float(__float_as_uint(mag) | ((c & 8u) << 28));
+}
+
+// Sum of S fp32 values `stride` words apart, read with agent-scope atomic loads
+// (they bypass the per-XCD L2).  Loads are issued eight at a time before any
+// is consumed, and added in index order, so the result does not depend on timing.
+__device__ __forceinline__ float ordered_sum_sc1(const uint32_t* p, int64_t stride, int S) {
+  float sum = 0.f;
+  for (int z0 = 0; z0 < S; z0 += 8) {
+    uint32_t v[8];
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+      v[b] = 0u;   // +0.0f
+      if (z0 + b < S) v[b] = __hip_atomic_load(p + (int64_t)(z0 + b) * stride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+#pragma unroll
+    for (int b = 0; b < 8; ++b) sum += __uint_as_float(v[b]);
+  }
+  return sum;
 }
 
 __device__ __forceinline__ float wave_sum(float v) {

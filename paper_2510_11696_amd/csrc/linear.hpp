@@ -39,6 +39,19 @@ int launch_decode(const DecodePlan& p, const DecodeArgs& a, hipStream_t st);
 int launch_prepack(const uint8_t* codes, const uint8_t* scales, int64_t N, int64_t K, uint8_t* out,
                    hipStream_t st);
 
+// ---- prefill path: MFMA GEMM on tile-packed weights (linear_gemm.hip) ----
+struct GemmArgs {
+  const uint16_t* x; int64_t ldx; int64_t M; int64_t K; int64_t N;
+  const uint8_t* packed; int64_t k_tiles; const float* tensor_scale;        // kFmtNvfp4 weights
+  const uint16_t* wbf16;                                                    // kFmtBf16: [N, K] dense rows (LoRA A)
+  const uint16_t* ts; int64_t ts_ld; int ext_stages;                        // [M, ts_ld] bf16: hi | mid | lo of lora_scale * t
+  const uint16_t* B; int r; float lora_scale;
+  uint16_t* y; int64_t ldy;
+  int n_tiles;
+};
+int launch_gemm(const GemmArgs& a, hipStream_t st);
+int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st);
+
 // General fallback (any K % 16 == 0, any alignment of rows the ABI allows).
 int launch_generic_lora_down(const uint16_t* x, int64_t ldx, int64_t M, int64_t K, const uint16_t* A,
                              int64_t r, float* t, hipStream_t st);

@@ -271,10 +271,7 @@ __global__ __launch_bounds__(kDecMaxWaves * 64) void decode32_kernel(const Decod
       const int tile = tile0 + e / (MR * 64);
       if (e < kElems && tile < a.n_tiles) {
         const uint32_t* src = a.partial + (int64_t)tile * (MR * 64) + e % (MR * 64);
-        float s = 0.f;
-        for (int w = 0; w < S; ++w)
-          s += __uint_as_float(__hip_atomic_load(src + (int64_t)w * a.n_tiles * (MR * 64), __ATOMIC_RELAXED,
-                                                 __HIP_MEMORY_SCOPE_AGENT));
+        const float s = ordered_sum_sc1(src, (int64_t)a.n_tiles * (MR * 64), S);
         v[p] = s;
       }
     }
@@ -357,6 +354,10 @@ static void launch_dec(const DecodePlan& p, const DecodeArgs& a, hipStream_t st)
 }
 
 int launch_decode(const DecodePlan& p, const DecodeArgs& a, hipStream_t st) {
+  // every pointer the kernel dereferences must be set by the caller
+  if (!a.x || !a.packed || !a.tensor_scale || !a.y || !a.partial || !a.counters || (a.r > 0 && (!a.t_in || !a.B)))
+    return QERL_ERR_NULL;
+  if (a.M < 1 || a.M > 16 || a.N < 1 || a.K < 16 || p.waves < 1 || p.waves > kDecMaxWaves) return QERL_ERR_SHAPE;
 #define QERL_CASE(kw, t, mr)                                   \
   if (p.KW == kw && p.T == t && p.MR == mr) {                  \
     launch_dec<kw, t, mr>(p, a, st);                           \

@@ -1,0 +1,374 @@
+// Prefill-sized NVFP4 + LoRA linear (M > 16 tokens): a bf16 MFMA GEMM that
+// dequantises the tile-packed weights in registers.
+//
+//   y[m,n] = S32 * sum_k x[m,k] * (s[n,k/16] * e[n,k]) + lora_scale * sum_j t[m,j] * B[n,j]
+//                                                                    (Eq. 6, Eq. 2)
+// Compute bound (2*M*N*K flop against 0.5625*N*K bytes), so the target is the
+// bf16 MFMA rate.  s * e has at most 6 significant bits and is exact in bf16;
+// products are exact in the fp32 accumulator; S32 multiplies the sum once.
+//
+//   * Workgroup tile: BM = 32*MT tokens x BN = 32*NT*W output rows, W waves.
+//     Every wave owns its own NT column tiles for all BM tokens, so no weight
+//     is dequantised twice in a workgroup: packed bytes go global -> registers
+//     -> (cvt, scale, pack: ~20 VALU ops per 8 weights) -> MFMA B operand.
+//   * x is the shared operand: a BM x 128 slab per K-tile is staged in LDS,
+//     double buffered through registers, 16-byte chunks XOR-swizzled by row so
+//     that the A-operand reads (32 rows at one column) hit distinct banks.
+//   * v_mfma_f32_32x32x16_bf16, A = x (row = token), B = weights (col = n);
+//     MT*NT accumulator tiles of 16 registers per lane.
+//   * LoRA: a first launch of the same kernel over the dense bf16 matrix A
+//     (split along K, partial tiles added in slice order by the last workgroup
+//     to arrive) produces  ts = [hi | mid | lo]  with hi + mid + lo =
+//     lora_scale * x A^T up to 2^-27, three bf16 terms per value.  The main
+//     launch then treats the up-projection as 3r more input columns:
+//     [x | ts] . [S32 * W_hat ; B ; B ; B]^T, i.e. the accumulators are scaled by
+//     S32 after the weight stages and the extra stages multiply ts by B.
+//
+// Operand layouts and the packed tile format are described in linear_decode.hip.
+#include "linear.hpp"
+
+namespace qerl {
+
+// 8 weights of one lane (one dword of codes) times their block scale -> bf16 x8
+__device__ __forceinline__ bf16x8 dequant8_bf16(uint32_t codes, float s) {
+  const f32x2 p0 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 0);
+  const f32x2 p1 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 1);
+  const f32x2 p2 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 2);
+  const f32x2 p3 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 3);
+  u32x4 o;
+  o[0] = pack_bf16x2(p0.x * s, p0.y * s);
+  o[1] = pack_bf16x2(p1.x * s, p1.y * s);
+  o[2] = pack_bf16x2(p2.x * s, p2.y * s);
+  o[3] = pack_bf16x2(p3.x * s, p3.y * s);
+  return __builtin_bit_cast(bf16x8, o);
+}
+
+__device__ __forceinline__ float e4m3_byte_f32(uint32_t v, int b) {
+  switch (b) {
+    case 0: return __builtin_amdgcn_cvt_f32_fp8(v, 0);
+    case 1: return __builtin_amdgcn_cvt_f32_fp8(v, 1);
+    case 2: return __builtin_amdgcn_cvt_f32_fp8(v, 2);
+    default: return __builtin_amdgcn_cvt_f32_fp8(v, 3);
+  }
+}
+
+__device__ __forceinline__ void split3_bf16(const float (&v)[8], u32x4& hi, u32x4& mid, u32x4& lo) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t h = pack_bf16x2(v[2 * i], v[2 * i + 1]);
+    const float r0 = v[2 * i] - bf16_bits_to_f32(h & 0xffffu), r1 = v[2 * i + 1] - __uint_as_float(h & 0xffff0000u);
+    const uint32_t m = pack_bf16x2(r0, r1);
+    const float q0 = r0 - bf16_bits_to_f32(m & 0xffffu), q1 = r1 - __uint_as_float(m & 0xffff0000u);
+    hi[i] = h; mid[i] = m; lo[i] = pack_bf16x2(q0, q1);
+  }
+}
+
+template <int NT>
+struct WeightRegs {      // one stage = 64 inputs (4 MFMA steps) of NT column tiles
+  u32x4 c[NT];           // 4 steps x 8 codes
+  uint32_t sc[NT];       // 4 scale bytes
+};
+
+template <int MT, int NT, int W>
+__global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
+  constexpr int BM = MT * 32;
+  constexpr int kThreads = W * 64;
+  constexpr int kChunks = BM * 8;                          // 16-byte chunks of one x slab (BM x 64)
+  constexpr int XL = (kChunks + kThreads - 1) / kThreads;  // chunks per thread
+  // x slab [2][BM][8 chunks]; chunk c of row r sits at r*8 + (c ^ ((r >> 1) & 7)): rows r, r+1 use
+  // different bank halves, so 16 consecutive rows at one column touch 16 distinct 16-byte bank groups.
+  extern __shared__ u32x4 xs[];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n32 = lane & 31, kg = lane >> 5;
+  const int64_t m0 = (int64_t)blockIdx.y * BM;
+  const int nt0 = (blockIdx.x * W + wave) * NT;
+  const int64_t n_stages = ceil_div_dev(a.K, 64);
+  const int64_t s_begin = 0, s_end = n_stages;
+
+  f32x16 acc[MT][NT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[mt][nt][i] = 0.f;
+
+  // ---- loaders (stage s covers columns [64 s, 64 s + 64) of the row-major bf16 matrix `src`)
+  u32x4 xr[XL];
+  auto gload_x = [&](const uint16_t* src, int64_t ld, int64_t cols, int64_t s) {
+#pragma unroll
+    for (int i = 0; i < XL; ++i) {
+      const int idx = tid + i * kThreads;
+      const int row = idx >> 3, chunk = idx & 7;
+      int64_t gr = m0 + row;
+      gr = gr < a.M ? gr : a.M - 1;
+      int64_t k = s * 64 + chunk * 8;
+      k = k < cols ? k : cols - 8;      // past the end the other operand is zero; any finite value will do
+      xr[i] = u32x4{0u, 0u, 0u, 0u};
+      if (idx < kChunks) xr[i] = *reinterpret_cast<const u32x4*>(src + gr * ld + k);
+    }
+  };
+  auto swrite_x = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < XL; ++i) {
+      const int idx = tid + i * kThreads;
+      const int row = idx >> 3, chunk = idx & 7;
+      if (idx < kChunks) xs[buf * kChunks + row * 8 + (chunk ^ ((row >> 1) & 7))] = xr[i];
+    }
+  };
+  auto gload_w = [&](WeightRegs<NT>& wr, int64_t s) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      int tile = nt0 + nt;
+      tile = tile < a.n_tiles ? tile : a.n_tiles - 1;
+      const uint8_t* base = a.packed + ((int64_t)tile * a.k_tiles + (s >> 1)) * kPackTileBytes;
+      const int plane = (int)(s & 1);
+      wr.c[nt] = *reinterpret_cast<const u32x4*>(base + plane * 1024 + lane * 16);
+      wr.sc[nt] = *reinterpret_cast<const uint32_t*>(base + 2048 + n32 * 8 + plane * 4);
+    }
+  };
+  auto mma_step = [&](const u32x4* xst, int j, const bf16x8 (&wf)[NT]) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int row = mt * 32 + n32;
+      const bf16x8 af = __builtin_bit_cast(bf16x8, xst[row * 8 + ((2 * j + kg) ^ ((row >> 1) & 7))]);
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, wf[nt], acc[mt][nt], 0, 0, 0);
+    }
+  };
+  auto compute = [&](int buf, const WeightRegs<NT>& wr) {
+    const u32x4* xst = xs + buf * kChunks;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      bf16x8 wf[NT];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        wf[nt] = dequant8_bf16(wr.c[nt][j], e4m3_byte_f32(wr.sc[nt], j));
+      }
+      mma_step(xst, j, wf);
+    }
+  };
+
+  // ---- main loop over 64-input stages: registers -> LDS double buffering, one barrier per stage
+  if (s_begin < s_end) {
+    WeightRegs<NT> w0, w1;
+    gload_x(a.x, a.ldx, a.K, s_begin);
+    gload_w(w0, s_begin);
+    swrite_x(0);
+    __syncthreads();
+    for (int64_t s = s_begin; s < s_end; s += 2) {
+      const bool has1 = s + 1 < s_end, has2 = s + 2 < s_end;
+      if (has1) { gload_x(a.x, a.ldx, a.K, s + 1); gload_w(w1, s + 1); }
+      compute(0, w0);
+      if (has1) swrite_x(1);
+      __syncthreads();
+      if (!has1) break;
+      if (has2) { gload_x(a.x, a.ldx, a.K, s + 2); gload_w(w0, s + 2); }
+      compute(1, w1);
+      if (has2) swrite_x(0);
+      __syncthreads();
+    }
+  }
+
+  {
+    // ---- LoRA up-projection: 3r extra columns  [hi | mid | lo] . [B ; B ; B]^T.  ts already carries
+    // the factor lora_scale / S32, so one multiplication by S32 at the end scales both branches.
+    for (int e = 0; e < a.ext_stages; ++e) {
+      gload_x(a.ts, a.ts_ld, a.ts_ld, e);
+      swrite_x(0);
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        bf16x8 wf[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          int64_t row = (int64_t)(nt0 + nt) * 32 + n32;
+          row = row < a.N ? row : a.N - 1;
+          const int c = e * 64 + 16 * j + 8 * kg;
+          u32x4 b = {0u, 0u, 0u, 0u};
+          if (c < 3 * a.r) b = *reinterpret_cast<const u32x4*>(a.B + row * a.r + (c % a.r));
+          wf[nt] = __builtin_bit_cast(bf16x8, b);
+        }
+        mma_step(xs, j, wf);
+      }
+      __syncthreads();
+    }
+    const float S32 = *a.tensor_scale;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const int64_t n = (int64_t)(nt0 + nt) * 32 + n32;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int64_t m = m0 + mt * 32 + 8 * (i >> 2) + 4 * kg + (i & 3);
+          if (m < a.M && n < a.N) a.y[m * a.ldy + n] = (uint16_t)f32_to_bf16_bits(acc[mt][nt][i] * S32);
+        }
+      }
+  }
+}
+
+// ---- LoRA down-projection for many tokens: ts = three bf16 terms of (lora_scale / S32) * x A^T --------
+// A skinny GEMM (r <= 64 output columns per block) that is bound by reading x once.  One workgroup owns
+// 32 tokens; its eight waves split K in interleaved 64-column chunks, read both operands straight from
+// global memory in MFMA operand layout (double buffered in registers), and are summed through LDS.
+template <int NT>
+__global__ __launch_bounds__(512) void lora_down32_kernel(const GemmArgs a) {
+  constexpr int kWaves = 8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n32 = lane & 31, kg = lane >> 5;
+  const int64_t m0 = (int64_t)blockIdx.x * 32;
+  const int nt0 = blockIdx.y * NT;
+  int64_t mrow = m0 + n32;
+  mrow = mrow < a.M ? mrow : a.M - 1;
+  const uint16_t* xrow = a.x + mrow * a.ldx + 8 * kg;
+
+  struct Chunk { u32x4 x[4]; u32x4 w[NT][4]; };   // 64 columns = 4 MFMA steps
+  auto load = [&](Chunk& c, int64_t kb) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int64_t k = kb + 16 * j + 8 * kg;
+      c.x[j] = u32x4{0u, 0u, 0u, 0u};
+      if (k < a.K) c.x[j] = *reinterpret_cast<const u32x4*>(xrow + kb + 16 * j);
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        int64_t row = (int64_t)(nt0 + nt) * 32 + n32;
+        row = row < a.N ? row : a.N - 1;
+        c.w[nt][j] = u32x4{0u, 0u, 0u, 0u};
+        if (k < a.K) c.w[nt][j] = *reinterpret_cast<const u32x4*>(a.wbf16 + row * a.K + k);
+      }
+    }
+  };
+  f32x16 acc[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[nt][i] = 0.f;
+  auto mma = [&](const Chunk& c) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, c.x[j]),
+                                                          __builtin_bit_cast(bf16x8, c.w[nt][j]), acc[nt], 0, 0, 0);
+  };
+  Chunk c0, c1;
+  const int64_t step = (int64_t)kWaves * 64;
+  int64_t kb = (int64_t)wave * 64;
+  if (kb < a.K) load(c0, kb);
+  while (kb < a.K) {
+    const bool has1 = kb + step < a.K;
+    if (has1) load(c1, kb + step);
+    mma(c0);
+    if (!has1) break;
+    const bool has2 = kb + 2 * step < a.K;
+    if (has2) load(c0, kb + 2 * step);
+    mma(c1);
+    kb += 2 * step;
+    if (!has2) break;
+  }
+
+  __shared__ float red[kWaves - 1][NT * 16][64];
+  if (wave > 0) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) red[wave - 1][nt * 16 + i][lane] = acc[nt][i];
+  }
+  __syncthreads();
+  if (wave != 0) return;
+  uint16_t* ts = const_cast<uint16_t*>(a.ts);
+  const float t_mult = a.lora_scale / *a.tensor_scale;   // undone by the final * S32 of the main launch
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int64_t n = (int64_t)(nt0 + nt) * 32 + n32;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      float sum = acc[nt][i];
+#pragma unroll
+      for (int w = 0; w < kWaves - 1; ++w) sum += red[w][nt * 16 + i][lane];
+      const int64_t m = m0 + 8 * (i >> 2) + 4 * kg + (i & 3);
+      if (m < a.M && n < a.N) {
+        const float v = sum * t_mult;
+        const uint32_t h = f32_to_bf16_bits(v);
+        const float r1 = v - bf16_bits_to_f32(h);
+        const uint32_t md = f32_to_bf16_bits(r1);
+        const uint32_t l = f32_to_bf16_bits(r1 - bf16_bits_to_f32(md));
+        uint16_t* row = ts + m * a.ts_ld;
+        row[n] = (uint16_t)h;
+        row[a.N + n] = (uint16_t)md;
+        row[2 * a.N + n] = (uint16_t)l;
+      }
+    }
+  }
+  if (blockIdx.y == 0) {   // zero the padding columns [3N, ts_ld)
+    const int pad = (int)(a.ts_ld - 3 * a.N);
+    for (int idx = lane; idx < 32 * pad; idx += 64) {
+      const int64_t m = m0 + idx / pad;
+      if (m < a.M) ts[m * a.ts_ld + 3 * a.N + idx % pad] = 0;
+    }
+  }
+}
+
+// ---- host ------------------------------------------------------------------------------------------
+
+struct GemmConfig { int MT, NT, W, wg_per_cu; float quality; };
+// wg_per_cu: workgroups of this shape resident on one CU (register use); quality: relative speed
+// measured at equal useful work on 14B-shaped layers.
+static const GemmConfig kConfigs[] = {
+    {4, 2, 4, 1, 0.60f}, {4, 2, 5, 1, 0.90f}, {4, 2, 8, 1, 0.95f}, {4, 1, 4, 2, 0.75f}, {4, 1, 8, 2, 1.00f},
+};
+static int g_force_cfg = -1;
+
+template <int MT, int NT, int W>
+static int launch_cfg(const GemmArgs& a, hipStream_t st) {
+  constexpr size_t lds = 2 * (size_t)MT * 32 * 8 * sizeof(u32x4);
+  const dim3 grid((unsigned)ceil_div(a.n_tiles, W * NT), (unsigned)ceil_div(a.M, MT * 32));
+  gemm32_kernel<MT, NT, W><<<grid, W * 64, lds, st>>>(a);
+  return launch_status();
+}
+
+int launch_gemm(const GemmArgs& a, hipStream_t st) {
+  // every pointer the kernel dereferences must be set by the caller
+  if (!a.x || !a.packed || !a.tensor_scale || !a.y || (a.r > 0 && (!a.ts || !a.B))) return QERL_ERR_NULL;
+  if (a.M < 1 || a.N < 1 || a.K < 16 || a.n_tiles < 1 || a.k_tiles < 1 || (a.r > 0 && a.ts_ld < 3 * a.r))
+    return QERL_ERR_SHAPE;
+  int best = 0;
+  float best_score = -1.f;
+  for (int c = 0; c < (int)(sizeof(kConfigs) / sizeof(kConfigs[0])); ++c) {
+    const GemmConfig& g = kConfigs[c];
+    const int64_t bm = g.MT * 32, bn = (int64_t)g.W * g.NT * 32;
+    const int64_t wgs = ceil_div(a.M, bm) * ceil_div(a.N, bn);
+    const int64_t slots = 256 * g.wg_per_cu;
+    const int64_t rounds = ceil_div(wgs, slots);
+    const float useful = (float)((double)a.M * (double)a.N / ((double)rounds * (double)slots * (double)bm * (double)bn));
+    const float score = useful * g.quality;
+    if (score > best_score) { best_score = score; best = c; }
+  }
+  if (g_force_cfg >= 0) best = g_force_cfg;
+  const GemmArgs& b = a;
+#define QERL_GEMM_CASE(idx, mt, nt, w) \
+  if (best == idx) return launch_cfg<mt, nt, w>(b, st);
+  QERL_GEMM_CASE(0, 4, 2, 4) QERL_GEMM_CASE(1, 4, 2, 5) QERL_GEMM_CASE(2, 4, 2, 8)
+  QERL_GEMM_CASE(3, 4, 1, 4) QERL_GEMM_CASE(4, 4, 1, 8)
+#undef QERL_GEMM_CASE
+  return QERL_ERR_SHAPE;
+}
+
+// ts = three-term bf16 split of (lora_scale / S32) * x A^T, [M, ts_ld]; a.N = r rows of A.
+int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st) {
+  if (!a.x || !a.wbf16 || !a.tensor_scale || !a.ts) return QERL_ERR_NULL;
+  if (a.M < 1 || a.N < 1 || a.K < 16 || a.ts_ld < 3 * a.N) return QERL_ERR_SHAPE;
+  const int tiles = (int)ceil_div(a.N, 32);
+  const dim3 grid((unsigned)ceil_div(a.M, 32), (unsigned)ceil_div(tiles, tiles >= 2 ? 2 : 1));
+  if (tiles >= 2) lora_down32_kernel<2><<<grid, 512, 0, st>>>(a);
+  else lora_down32_kernel<1><<<grid, 512, 0, st>>>(a);
+  return launch_status();
+}
+
+}  // namespace qerl
+
+// Tuning hook for experiments (not part of the public header): force a GEMM tile configuration, -1 = automatic.
+extern "C" QERL_API void qerl_debug_force_gemm(int cfg) { qerl::g_force_cfg = cfg; }

@@ -257,13 +257,9 @@ __global__ __launch_bounds__(kMaxWaves * 64) void skinny_kernel(const SkinnyArgs
       const int tile = tile0 + (slot >> 6);
       if (slot < kSlots && tile < a.n_tiles) {
         const uint32_t* src = pw + ((int64_t)tile * 64 + (slot & 63)) * 4;
-        f32x4 s = {0.f, 0.f, 0.f, 0.f};
-        for (int w = 0; w < S; ++w) {
-          const uint32_t* p = src + (int64_t)w * a.n_tiles * 256;
+        f32x4 s;
 #pragma unroll
-          for (int i = 0; i < 4; ++i)
-            s[i] += __uint_as_float(__hip_atomic_load(p + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-        }
+        for (int i = 0; i < 4; ++i) s[i] = ordered_sum_sc1(src + i, (int64_t)a.n_tiles * 256, S);
         v[q] = s;
       }
     }
@@ -336,6 +332,13 @@ static void launch_one(const SkinnyPlan& p, const SkinnyArgs& a, hipStream_t st)
 }
 
 int launch_skinny(const SkinnyPlan& p, const SkinnyArgs& a, int fmt, hipStream_t st) {
+  // every pointer the kernel dereferences must be set by the caller
+  if (!a.x || !a.partial || !a.counters) return QERL_ERR_NULL;
+  if (fmt == kFmtNvfp4 && (!a.codes || !a.scales || !a.tensor_scale || !a.y || (a.r > 0 && (!a.t_in || !a.B))))
+    return QERL_ERR_NULL;
+  if (fmt == kFmtBf16 && (!a.wbf16 || !a.t_out)) return QERL_ERR_NULL;
+  if (a.M < 1 || a.M > 16 || a.N < 1 || a.K < 64 || a.K % 64 != 0 || p.waves < 1 || p.waves > kMaxWaves)
+    return QERL_ERR_SHAPE;
 #define QERL_CASE(kt, t)                                                     \
   if (p.KT == kt && p.T == t) {                                              \
     if (fmt == kFmtNvfp4) launch_one<kt, t, kFmtNvfp4>(p, a, st);            \

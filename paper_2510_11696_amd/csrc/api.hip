@@ -14,6 +14,7 @@ void set_last_hip_error(int e) { g_last_hip_error = e; }
 //   [partial_off, ...)  split-K partial tiles, fp32
 struct WorkspaceLayout { size_t ctrl_bytes, n_main_ctr, n_down_ctr, t_off, partial_off, total; };
 
+constexpr size_t kDecodeTpartWords = 16 * 2 * 8 * 64;   // producer partial sums of the fused LoRA down-projection
 constexpr size_t kMaxCounterTiles = 1 << 16;   // rows / 16 the control region can serve
 
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -23,7 +24,7 @@ static WorkspaceLayout workspace_layout(int64_t M, int64_t N, int64_t K, int64_t
   L.n_main_ctr = (size_t)ceil_div(N > 0 ? N : 1, 16);
   const size_t n_down_ctr = (size_t)ceil_div(r > 0 ? r : 1, 16);
   L.n_down_ctr = n_down_ctr;
-  L.ctrl_bytes = align256((L.n_main_ctr + n_down_ctr) * sizeof(uint32_t));
+  L.ctrl_bytes = align256((L.n_main_ctr + n_down_ctr + 4) * sizeof(uint32_t));   // + LoRA hand-over words
   L.t_off = L.ctrl_bytes;
   // t = x A^T: fp32 [M, r] for the decode kernels, or three bf16 terms [M, ceil64(3r)] for the GEMM
   const size_t rows = (size_t)(M > 0 ? M : 1), rr = (size_t)(r > 0 ? r : 1);
@@ -37,7 +38,7 @@ static WorkspaceLayout workspace_layout(int64_t M, int64_t N, int64_t K, int64_t
   const size_t skinny_bytes = (S_max * L.n_main_ctr + S_down * n_down_ctr) * 64 * sizeof(f32x4);
   const size_t S_dec = (size_t)ceil_div(ceil_div(K > 0 ? K : 1, kPackTileK), 7);
   const size_t decode_bytes = S_dec * (size_t)ceil_div(N > 0 ? N : 1, kPackTileRows) * 8 * 64 * sizeof(float) +
-                              S_down * n_down_ctr * 64 * sizeof(f32x4);
+                              S_down * n_down_ctr * 64 * sizeof(f32x4) + kDecodeTpartWords * sizeof(uint32_t);
   size_t need = skinny_bytes > decode_bytes ? skinny_bytes : decode_bytes;
   L.total = L.partial_off + align256(need);
   return L;
@@ -224,21 +225,31 @@ extern "C" int nvfp4_lora_linear_packed(const void* x, int64_t M, int64_t K, int
     return launch_gemm(g, c.st);
   }
 
+  // Decode: passes of up to 16 tokens.  For the usual adapters (r <= 64, 16-byte aligned) the LoRA
+  // down-projection runs on the first workgroups of the same launch; otherwise it gets a launch of its own.
+  const bool fused_lora = r > 0 && r <= 64 && r % 8 == 0 && aligned(A, 16) && aligned(B, 16);
   for (int64_t m0 = 0; m0 < M; m0 += 16) {
     const int mc = (int)((M - m0 < 16) ? M - m0 : 16);
     const DecodePlan p = plan_decode(mc, N, K, r);
-    const size_t dec_words = (size_t)p.S * p.n_tiles * p.MR * 64;
-    if (r > 0) {
-      const int rc = lora_down_pass(c, L, m0, mc, (f32x4*)(partial + ((dec_words + 3) & ~(size_t)3)));
+    const size_t dec_words = ((size_t)p.S * p.n_tiles * p.MR * 64 + 3) & ~(size_t)3;
+    if (r > 0 && !fused_lora) {
+      const int rc = lora_down_pass(c, L, m0, mc, (f32x4*)(partial + dec_words + kDecodeTpartWords));
       if (rc != QERL_OK) return rc;
     }
     DecodeArgs a{};
     a.x = c.x + m0 * ldx; a.ldx = ldx; a.M = mc; a.K = K; a.N = N;
     a.packed = (const uint8_t*)packed; a.k_tiles = p.k_tiles; a.tensor_scale = tensor_scale;
-    a.t_in = t + m0 * r; a.B = c.B; a.r = (int)r; a.lora_scale = lora_scale;
+    a.A = c.A; a.B = c.B; a.r = (int)r; a.lora_scale = lora_scale;
     a.b_vec = r % 8 == 0 && aligned(B, 16);
+    a.t = t + m0 * r;
+    if (fused_lora) {
+      int64_t np = ceil_div(2 * p.k_tiles, p.waves);   // one half K-tile per producer wave
+      a.n_producers = (int)(np < 1 ? 1 : (np > 16 ? 16 : np));
+      a.lora_ctl = (uint32_t*)ws + L.n_main_ctr + L.n_down_ctr;
+      a.tpart = partial + dec_words;
+    }
     a.y = c.y + m0 * ldy; a.ldy = ldy;
-    a.partial = partial; a.counters = (uint32_t*)ws; a.n_tiles = p.n_tiles;
+    a.partial = partial; a.counters = (uint32_t*)ws; a.n_tiles = p.n_tiles; a.S = p.S; a.n_groups = p.groups;
     const int rc = launch_decode(p, a, c.st);
     if (rc != QERL_OK) return rc;
   }

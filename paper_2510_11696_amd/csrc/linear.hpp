@@ -29,9 +29,12 @@ constexpr int kPackTileBytes = 2304;  // 2048 B codes + 256 B scales = 0.5625 B 
 struct DecodeArgs {
   const uint16_t* x; int64_t ldx; int M; int64_t K; int64_t N;
   const uint8_t* packed; int64_t k_tiles; const float* tensor_scale;
-  const float* t_in; const uint16_t* B; int r; float lora_scale; bool b_vec;
+  const uint16_t* A; const uint16_t* B; int r; float lora_scale; bool b_vec;
+  float* t;                        // [M, r] fp32: x A^T (read; written by the producer workgroups when n_producers > 0)
+  int n_producers;                 // workgroups at the front of the grid that compute t in this launch (0: t is ready)
+  uint32_t* lora_ctl; uint32_t* tpart;   // 3 control words; producer partial sums
   uint16_t* y; int64_t ldy;
-  uint32_t* partial; uint32_t* counters; int n_tiles;
+  uint32_t* partial; uint32_t* counters; int n_tiles; int S; int n_groups;
 };
 struct DecodePlan { int KW, T, MR, S, main_waves, waves, n_tiles, groups; int64_t k_tiles; };
 DecodePlan plan_decode(int64_t M, int64_t N, int64_t K, int64_t r);

@@ -25,8 +25,14 @@
 //     LDS in wave order; if K needs several workgroups (gridDim.y = S) they
 //     exchange partial tiles through the workspace and the last to arrive adds
 //     them in slice order (deterministic).
-//   * The LoRA up-projection runs on a wave of its own as bf16 MFMAs over j,
-//     with the fp32 t split into three bf16 terms (exact to 2^-27 |t|).
+//   * LoRA in the same launch: the first few workgroups of the grid compute
+//     t = x A^T (bf16 MFMAs, partial sums exchanged through the workspace) and
+//     raise a ready word; in every other workgroup one wave is set aside for
+//     the up-projection: it preloads its B rows, waits for the ready word
+//     (bounded; workgroups are dispatched in index order, so the producers are
+//     already running), reads t, splits it into three bf16 terms (exact to
+//     2^-27 |t|) and multiplies by B with MFMAs over j while the other waves
+//     stream the weights.  The last reader re-arms the control words.
 //
 // Packed layout ("P32"): rows padded to 32, K padded to 128, zero filled.
 //   tile (nt, kt) at byte ((nt * k_tiles + kt) * 2304):
@@ -78,21 +84,130 @@ __device__ __forceinline__ void split3(const float (&v)[8], u32x4& hi, u32x4& mi
   }
 }
 
+// Control words of the in-kernel LoRA hand-over (in the workspace, zero between calls).
+constexpr int kCtlArrive = 0;   // producer workgroups that have stored their partial t
+constexpr int kCtlReady = 1;    // 1 once t is complete
+constexpr int kCtlDone = 2;     // consumer workgroups that have read t
+constexpr uint32_t kSpinLimit = 1u << 14;   // polls, about a microsecond apart, before giving up with NaN
+
+// ---- LoRA down-projection  t[tok][j] = sum_k x[tok,k] * A[j,k]  (r <= 64) on the first workgroups of
+// the grid.  Their waves stride over the K-tiles, are summed through LDS, exchange partial sums through
+// the workspace, and the last one to arrive publishes t and raises the ready word.
+template <int MR>
+__device__ __forceinline__ void lora_down_producer(const DecodeArgs& a, float* red, int* s_last) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nthreads = blockDim.x, nwaves = nthreads >> 6;
+  const int n32 = lane & 31, kg = lane >> 5;
+  const int P = a.n_producers, n_at = (a.r + 31) >> 5;
+  f32x16 pacc[2];
+#pragma unroll
+  for (int at = 0; at < 2; ++at)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) pacc[at][i] = 0.f;
+  // half K-tiles (64 inputs, 4 MFMA steps) keep the register footprint below the consumer path's
+  for (int64_t h = (int64_t)blockIdx.x * nwaves + wave; h < 2 * a.k_tiles; h += (int64_t)P * nwaves) {
+    u32x4 xa[4], af[2][4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int64_t k = h * 64 + 16 * j + 8 * kg;
+      xa[j] = u32x4{0u, 0u, 0u, 0u};
+      if (n32 < a.M && k < a.K) xa[j] = *reinterpret_cast<const u32x4*>(a.x + (int64_t)n32 * a.ldx + k);
+#pragma unroll
+      for (int at = 0; at < 2; ++at) {
+        const int row = at * 32 + n32;
+        af[at][j] = u32x4{0u, 0u, 0u, 0u};
+        if (row < a.r && k < a.K) af[at][j] = *reinterpret_cast<const u32x4*>(a.A + (int64_t)row * a.K + k);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      pacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[j]),
+                                                        __builtin_bit_cast(bf16x8, af[0][j]), pacc[0], 0, 0, 0);
+      if (n_at > 1)
+        pacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[j]),
+                                                          __builtin_bit_cast(bf16x8, af[1][j]), pacc[1], 0, 0, 0);
+    }
+  }
+  // red[wave][at][q][lane]
+  constexpr int kElems = 2 * MR * 64;
+#pragma unroll
+  for (int at = 0; at < 2; ++at)
+#pragma unroll
+    for (int q = 0; q < MR; ++q) red[(wave * 2 + at) * MR * 64 + q * 64 + lane] = pacc[at][q];
+  __syncthreads();
+  constexpr int kPer = 2 * MR;   // elements per thread with a single wave
+  float v[kPer];
+#pragma unroll
+  for (int i = 0; i < kPer; ++i) {
+    const int e = tid + i * nthreads;
+    v[i] = 0.f;
+    if (e < kElems) {
+      float s = red[e];
+      for (int w = 1; w < nwaves; ++w) s += red[w * kElems + e];
+      v[i] = s;
+    }
+  }
+  if (P > 1) {
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      const int e = tid + i * nthreads;
+      if (e < kElems)
+        __hip_atomic_store(a.tpart + (int64_t)blockIdx.x * kElems + e, __float_as_uint(v[i]), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    __syncthreads();
+    if (tid == 0) {
+      const uint32_t old = __hip_atomic_fetch_add(a.lora_ctl + kCtlArrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      *s_last = (old == (uint32_t)(P - 1));
+    }
+    __syncthreads();
+    if (!*s_last) return;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      const int e = tid + i * nthreads;
+      if (e < kElems) v[i] = ordered_sum_sc1(a.tpart + e, kElems, P);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kPer; ++i) {
+    const int e = tid + i * nthreads;
+    if (e >= kElems) continue;
+    const int at = e / (MR * 64), q = (e / 64) % MR, l = e & 63;
+    const int tok = 8 * (q >> 2) + 4 * (l >> 5) + (q & 3), j = at * 32 + (l & 31);
+    if (tok < a.M && j < a.r)
+      __hip_atomic_store(reinterpret_cast<uint32_t*>(a.t) + tok * a.r + j, __float_as_uint(v[i]), __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): t is written before the ready word
+  __syncthreads();
+  if (tid == 0) {
+    __hip_atomic_store(a.lora_ctl + kCtlArrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(a.lora_ctl + kCtlReady, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
 template <int KW, int T, int MR>
 __global__ __launch_bounds__(kDecMaxWaves * 64) void decode32_kernel(const DecodeArgs a) {
+  constexpr int kRedConsumer = kDecMaxWaves * T * MR * 64, kRedProducer = kDecMaxWaves * 2 * MR * 64;
+  __shared__ float red[kRedConsumer > kRedProducer ? kRedConsumer : kRedProducer];
+  __shared__ int s_last;
+  if ((int)blockIdx.x < a.n_producers) {
+    lora_down_producer<MR>(a, red, &s_last);
+    return;
+  }
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nthreads = blockDim.x;
   const int nwaves = nthreads >> 6;
   const int n32 = lane & 31, kg = lane >> 5;
-  const int tile0 = blockIdx.x * T;
+  const int S = a.S;
+  const int cid = (int)blockIdx.x - a.n_producers, group = cid / S, slice = cid - group * S;
+  const int tile0 = group * T;
   // With LoRA the last wave of the block does the up-projection instead of a K-slice.
   const bool lora_wave = a.r > 0 && wave == nwaves - 1;
   const int main_waves = a.r > 0 ? nwaves - 1 : nwaves;
-
-  __shared__ float red[kDecMaxWaves][T][MR][64];
-  __shared__ int s_last;
+  auto red_at = [&](int w, int t, int q) -> float& { return red[((w * T + t) * MR + q) * 64 + lane]; };
 
   if (!lora_wave) {
-    const int64_t kt0 = ((int64_t)blockIdx.y * main_waves + wave) * KW;
+    const int64_t kt0 = ((int64_t)slice * main_waves + wave) * KW;
     // ---- x slice in A-operand layout
     u32x4 xa[KW][8];
 #pragma unroll
@@ -142,14 +257,14 @@ __global__ __launch_bounds__(kDecMaxWaves * 64) void decode32_kernel(const Decod
           for (int q = 0; q < MR; ++q) acc[q] = __builtin_fmaf(s, tmp[q], acc[q]);
         }
 #pragma unroll
-      for (int q = 0; q < MR; ++q) red[wave][t][q][lane] = acc[q] * S32;
+      for (int q = 0; q < MR; ++q) red_at(wave, t, q) = acc[q] * S32;
     }
   } else {
     // ---- LoRA up-projection  lo[tok][n] = sum_j t[tok][j] * B[n][j]  on this wave
     constexpr int kPre = 4;   // 16-wide j steps whose operands are loaded up front (r <= 64)
     u32x4 th[kPre], tm[kPre], tl[kPre];
     u32x4 bq[T][kPre];
-    const bool first = blockIdx.y == 0;   // only the first K-slice adds the branch
+    const bool first = slice == 0;   // only the first K-slice adds the branch
 #pragma unroll
     for (int s = 0; s < kPre; ++s) {
       const int j0 = 16 * s + 8 * kg;
@@ -169,11 +284,30 @@ __global__ __launch_bounds__(kDecMaxWaves * 64) void decode32_kernel(const Decod
           }
         }
       }
+    }
+    // t comes either from an earlier launch or from the producer workgroups of this launch.  In the
+    // second case wait for the ready word (polled past the caches, about once a microsecond so that
+    // hundreds of waiting workgroups do not crowd the one memory channel that holds it).  The producers
+    // wrote t through to memory before raising the word and no cache can hold an older copy of it (caches
+    // are invalidated when a kernel starts and nobody reads t before the word is up), so ordinary loads
+    // are enough afterwards; the workgroup-scope fence only keeps the compiler from hoisting them.
+    bool poisoned = false;
+    if (first && a.n_producers > 0) {
+      uint32_t spins = 0;
+      while (__hip_atomic_load(a.lora_ctl + kCtlReady, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+        if (++spins > kSpinLimit) { poisoned = true; break; }
+        __builtin_amdgcn_s_sleep(32);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    }
+#pragma unroll
+    for (int s = 0; s < kPre; ++s) {
+      const int j0 = 16 * s + 8 * kg;
       float tv[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) tv[i] = 0.f;
       if (first && n32 < a.M && j0 < a.r) {
-        const float* tp = a.t_in + (int64_t)n32 * a.r + j0;
+        const float* tp = a.t + (int64_t)n32 * a.r + j0;
         if (a.b_vec) {
           const f32x4 t0 = *reinterpret_cast<const f32x4*>(tp), t1 = *reinterpret_cast<const f32x4*>(tp + 4);
           tv[0] = t0[0]; tv[1] = t0[1]; tv[2] = t0[2]; tv[3] = t0[3];
@@ -183,8 +317,17 @@ __global__ __launch_bounds__(kDecMaxWaves * 64) void decode32_kernel(const Decod
           for (int i = 0; i < 8; ++i)
             if (j0 + i < a.r) tv[i] = tp[i];
         }
+        if (poisoned) tv[0] = __uint_as_float(0x7fc00000u);   // the hand-over timed out: make it visible
       }
       split3(tv, th[s], tm[s], tl[s]);
+    }
+    if (first && a.n_producers > 0 && lane == 0) {
+      // every first-slice workgroup has now read t; the last of them re-arms the control words
+      const uint32_t old = __hip_atomic_fetch_add(a.lora_ctl + kCtlDone, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (old == (uint32_t)(a.n_groups - 1)) {
+        __hip_atomic_store(a.lora_ctl + kCtlReady, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(a.lora_ctl + kCtlDone, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
     }
 #pragma unroll
     for (int t = 0; t < T; ++t) {
@@ -196,7 +339,7 @@ __global__ __launch_bounds__(kDecMaxWaves * 64) void decode32_kernel(const Decod
         lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tm[s]), bf, lo, 0, 0, 0);
         lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tl[s]), bf, lo, 0, 0, 0);
       }
-      // ranks beyond 64: remaining steps, loaded as they come
+      // ranks beyond 64 (never with in-kernel producers): remaining steps, loaded as they come
       if (first) {
         int64_t row = (int64_t)(tile0 + t) * 32 + n32;
         row = row < a.N ? row : a.N - 1;
@@ -208,7 +351,7 @@ __global__ __launch_bounds__(kDecMaxWaves * 64) void decode32_kernel(const Decod
           for (int i = 0; i < 8; ++i) {
             tv[i] = 0.f;
             if (j0 + i < a.r) {
-              if (n32 < a.M) tv[i] = a.t_in[(int64_t)n32 * a.r + j0 + i];
+              if (n32 < a.M) tv[i] = a.t[(int64_t)n32 * a.r + j0 + i];
               b[i >> 1] |= (uint32_t)a.B[row * a.r + j0 + i] << (16 * (i & 1));
             }
           }
@@ -221,7 +364,7 @@ __global__ __launch_bounds__(kDecMaxWaves * 64) void decode32_kernel(const Decod
         }
       }
 #pragma unroll
-      for (int q = 0; q < MR; ++q) red[wave][t][q][lane] = lo[q] * a.lora_scale;
+      for (int q = 0; q < MR; ++q) red_at(wave, t, q) = lo[q] * a.lora_scale;
     }
   }
   __syncthreads();
@@ -235,14 +378,13 @@ __global__ __launch_bounds__(kDecMaxWaves * 64) void decode32_kernel(const Decod
     const int e = tid + p * nthreads;
     v[p] = 0.f;
     if (e < kElems) {
-      const float* src = &red[0][0][0][0] + e;
+      const float* src = red + e;
       float s = src[0];
       for (int w = 1; w < nwaves; ++w) s += src[w * kElems];
       v[p] = s;
     }
   }
 
-  const int S = gridDim.y;
   if (S > 1) {
     // Partial tiles go through memory with agent-scope atomic accesses (written
     // through / read past the per-XCD L2): no cache-wide write-back or
@@ -253,14 +395,13 @@ __global__ __launch_bounds__(kDecMaxWaves * 64) void decode32_kernel(const Decod
       const int e = tid + p * nthreads;
       const int tile = tile0 + e / (MR * 64);
       if (e < kElems && tile < a.n_tiles)
-        __hip_atomic_store(a.partial + ((int64_t)blockIdx.y * a.n_tiles + tile) * (MR * 64) + e % (MR * 64),
+        __hip_atomic_store(a.partial + ((int64_t)slice * a.n_tiles + tile) * (MR * 64) + e % (MR * 64),
                            __float_as_uint(v[p]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     __syncthreads();
     if (tid == 0) {
-      const uint32_t old = __hip_atomic_fetch_add(a.counters + blockIdx.x, 1u, __ATOMIC_RELAXED,
-                                                  __HIP_MEMORY_SCOPE_AGENT);
+      const uint32_t old = __hip_atomic_fetch_add(a.counters + group, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       s_last = (old == (uint32_t)(S - 1));
     }
     __syncthreads();
@@ -269,13 +410,10 @@ __global__ __launch_bounds__(kDecMaxWaves * 64) void decode32_kernel(const Decod
     for (int p = 0; p < kPer; ++p) {
       const int e = tid + p * nthreads;
       const int tile = tile0 + e / (MR * 64);
-      if (e < kElems && tile < a.n_tiles) {
-        const uint32_t* src = a.partial + (int64_t)tile * (MR * 64) + e % (MR * 64);
-        const float s = ordered_sum_sc1(src, (int64_t)a.n_tiles * (MR * 64), S);
-        v[p] = s;
-      }
+      if (e < kElems && tile < a.n_tiles)
+        v[p] = ordered_sum_sc1(a.partial + (int64_t)tile * (MR * 64) + e % (MR * 64), (int64_t)a.n_tiles * (MR * 64), S);
     }
-    if (tid == 0) __hip_atomic_store(a.counters + blockIdx.x, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) __hip_atomic_store(a.counters + group, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 
   // ---- store: element (t, q, lane) is output row 32*(tile0+t) + lane%32 of token 8*(q/4) + 4*(lane/32) + q%4
@@ -350,14 +488,18 @@ DecodePlan plan_decode(int64_t M, int64_t N, int64_t K, int64_t r) {
 
 template <int KW, int T, int MR>
 static void launch_dec(const DecodePlan& p, const DecodeArgs& a, hipStream_t st) {
-  decode32_kernel<KW, T, MR><<<dim3(p.groups, p.S), dim3(p.waves * 64), 0, st>>>(a);
+  decode32_kernel<KW, T, MR><<<dim3(a.n_producers + p.groups * p.S), dim3(p.waves * 64), 0, st>>>(a);
 }
 
 int launch_decode(const DecodePlan& p, const DecodeArgs& a, hipStream_t st) {
   // every pointer the kernel dereferences must be set by the caller
-  if (!a.x || !a.packed || !a.tensor_scale || !a.y || !a.partial || !a.counters || (a.r > 0 && (!a.t_in || !a.B)))
+  if (!a.x || !a.packed || !a.tensor_scale || !a.y || !a.partial || !a.counters || (a.r > 0 && (!a.t || !a.B)))
     return QERL_ERR_NULL;
-  if (a.M < 1 || a.M > 16 || a.N < 1 || a.K < 16 || p.waves < 1 || p.waves > kDecMaxWaves) return QERL_ERR_SHAPE;
+  if (a.n_producers > 0 && (!a.A || !a.lora_ctl || !a.tpart || a.r < 1 || a.r > 64 || a.n_producers > 16))
+    return QERL_ERR_NULL;
+  if (a.M < 1 || a.M > 16 || a.N < 1 || a.K < 16 || p.waves < 1 || p.waves > kDecMaxWaves || a.S != p.S ||
+      a.n_groups != p.groups)
+    return QERL_ERR_SHAPE;
 #define QERL_CASE(kw, t, mr)                                   \
   if (p.KW == kw && p.T == t && p.MR == mr) {                  \
     launch_dec<kw, t, mr>(p, a, st);                           \

@@ -120,10 +120,24 @@ def timed(fn, iters):
     return start.elapsed_time(stop) / iters
 
 
+def measured_traffic(kernel: str, shape_name: str, M: int):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summaries (profiles/traffic.json), or None."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    if not os.path.exists(path):
+        return None
+    try:
+        table = json.load(open(path))
+    except Exception:
+        return None
+    return table.get(f"{kernel}:{shape_name}:M{M}")
+
+
 def dominant_kernel_roofline(stack: Stack, reps: int):
-    """Average duration of one launch of the decode linear at the largest shape
-    (gate_proj: the kernel most of the step's bytes go through), running it
-    back to back over every layer's distinct weights."""
+    """Average duration of one launch of the linear at the shape most of the step's
+    bytes / flops go through (gate_proj), run back to back over every layer's
+    distinct weights.  One call is one launch of the kernel named below when
+    M <= 16 (the LoRA down-projection runs inside it); for M > 16 the call also
+    contains the small lora_down32_kernel launch."""
     shp = max(stack.cfg["linears"], key=lambda s: (s.packed_bytes, s.name == "gate"))
 
     def sweep():
@@ -132,15 +146,24 @@ def dominant_kernel_roofline(stack: Stack, reps: int):
     run = sweep if stack.eager else capture(sweep)
     run()
     ms = timed(run, reps) / len(stack.layers)
-    bytes_per_launch = shp.packed_bytes
-    achieved = bytes_per_launch / (ms * 1e-3) / 1e9
-    return {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-            "kernel": "decode32_kernel (decode NVFP4 linear on tile-packed weights)",
-            "shape": {"name": shp.name, "N": shp.N, "K": shp.K, "M": stack.M},
-            "algorithmic_bytes_per_launch": bytes_per_launch, "us_per_launch": round(ms * 1e3, 2),
-            "note": "per linear call (LoRA down-projection launch included), back to back over the "
-                    "layers' distinct weights, launch gaps included"}
+    common = {"shape": {"name": shp.name, "N": shp.N, "K": shp.K, "M": stack.M},
+              "us_per_launch": round(ms * 1e3, 2),
+              "note": "one linear call per launch slot, back to back over the layers' distinct weights, "
+                      "launch gaps included"}
+    if stack.M <= 128:
+        kernel = "decode32_kernel" if stack.M <= 16 else "gemm32_kernel"
+        bytes_per_launch = shp.packed_bytes
+        achieved = bytes_per_launch / (ms * 1e-3) / 1e9
+        return {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": measured_traffic(kernel, shp.name, stack.M), "kernel": kernel,
+                "algorithmic_bytes_per_launch": bytes_per_launch, **common}
+    flops = 2 * stack.M * shp.N * shp.K
+    achieved = flops / (ms * 1e-3) / 1e12
+    return {"bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
+            "traffic": measured_traffic("gemm32_kernel", shp.name, stack.M), "kernel": "gemm32_kernel",
+            "algorithmic_flops_per_launch": flops, **common}
 
 
 def cpu_baseline(config_no: int, M: int, budget_s: float = 20.0):
@@ -158,6 +181,8 @@ def cpu_baseline(config_no: int, M: int, budget_s: float = 20.0):
         N = shp.N
         if shp.packed_bytes > 20e6:           # big MLP matrices: a slice of output rows
             N = 4096
+        if M > 128:                           # prefill: the matmul dominates, keep the sample small
+            N = min(N, 1024)
         W = qs.weights(N, shp.K, qs.seed_for(config_no, 10 + j)).float().numpy()
         x = qs.activations(M, shp.K, qs.seed_for(config_no, 30 + j)).float().numpy()
         A, B = qs.lora_pair(N, shp.K, r, qs.seed_for(config_no, 50 + j))
@@ -172,6 +197,11 @@ def cpu_baseline(config_no: int, M: int, budget_s: float = 20.0):
     except AttributeError:
         cores = os.cpu_count()
     threads = min(cores, torch.get_num_threads())
+    if M > 128:
+        flops = sum(2 * M * int(n.split("[")[1].split("x")[0]) * int(n.split("x")[1].rstrip("]")) for n in names)
+        return {"value": round(flops / t_total / 1e12, 5), "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+                "sample": f"oracle nvfp4_lora_linear (dequantise + fp64 matmul + LoRA), M={M}, on "
+                          + ", ".join(names) + f"; {t_total:.1f} s"}
     return {"value": round(done_bytes / t_total / 1e9, 4), "unit": "GB/s", "cores": threads,
             "kind": "oracle",
             "sample": f"oracle nvfp4_lora_linear (dequantise + fp64 matmul + LoRA), M={M}, on "
@@ -188,6 +218,9 @@ def main():
     ap.add_argument("--layers", type=int, default=None)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--eager", action="store_true", help="launch from Python each step instead of replaying a HIP graph")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 256 MiB device copy five times (reference for the rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -197,8 +230,18 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": 256 << 20, "bytes_written": 256 << 20, "launches": 5}))
+        return
     cfg = qs.CONFIGS[args.config]
     M = args.M or cfg["M"][0]
+    if args.layers is None and M > 128:
+        args.layers = 4                     # compute bound: a few distinct layers are enough
     stack = Stack(args.config, M, args.layers)
     stack.eager = args.eager
     step = stack.step if args.eager else capture(stack.step)
@@ -207,20 +250,26 @@ def main():
     torch.cuda.synchronize()
     ms = timed(step, args.steps)
     step_bytes = stack.packed_bytes_per_layer * stack.n_layers
-    value = step_bytes / (ms * 1e-3) / 1e9
+    tflops = stack.flops_per_layer * stack.n_layers / (ms * 1e-3) / 1e12
+    decode = M <= 128
+    value = step_bytes / (ms * 1e-3) / 1e9 if decode else tflops
     roof = dominant_kernel_roofline(stack, max(3, args.steps // 2))
     line = {
-        "metric": "NVFP4+LoRA linear: packed-weight GB/s at decode",
-        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "metric": "NVFP4+LoRA linear: packed-weight GB/s at decode" if decode
+                  else "NVFP4+LoRA linear: TFLOP/s at prefill (2*M*N*K, LoRA flops not counted)",
+        "value": round(value, 1), "unit": "GB/s" if decode else "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 x fp4(e2m1)*fp8(e4m3) -> fp32 accumulate", "data": "synthetic",
         "config": {"workload": f"config {args.config}: {cfg['model']}-shaped decoder linears, "
-                               f"{stack.n_layers} layers, decode M={M}, LoRA r={cfg['r']} alpha={cfg['alpha']:g}, "
+                               f"{stack.n_layers} layers, {'decode' if decode else 'prefill'} M={M}, "
+                               f"LoRA r={cfg['r']} alpha={cfg['alpha']:g}, "
                                "AQN RMSNorm before q/k/v and gate/up; "
                                + ("eager launches" if args.eager else "one HIP graph replay per step"),
                    "packed_weight_bytes_per_step": step_bytes,
-                   "tflops": round(stack.flops_per_layer * stack.n_layers / (ms * 1e-3) / 1e12, 2),
-                   "frac_of_hbm_peak_whole_step": round(value / HBM_PEAK_GBS, 4)},
+                   "tflops": round(tflops, 2),
+                   "weight_GBps": round(step_bytes / (ms * 1e-3) / 1e9, 1),
+                   "frac_of_peak_whole_step": round(value / (HBM_PEAK_GBS if decode else MFMA_BF16_PEAK_TFLOPS), 4)},
         "roofline": roof,
     }
     if not args.no_cpu:

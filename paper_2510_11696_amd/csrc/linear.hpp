@@ -50,7 +50,7 @@ struct GemmArgs {
   const uint16_t* ts; int64_t ts_ld; int ext_stages;                        // [M, ts_ld] bf16: hi | mid | lo of lora_scale * t
   const uint16_t* B; int r; float lora_scale;
   uint16_t* y; int64_t ldy;
-  int n_tiles;
+  int n_tiles; int n_blocks; int nblk_per_xcd;
 };
 int launch_gemm(const GemmArgs& a, hipStream_t st);
 int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st);

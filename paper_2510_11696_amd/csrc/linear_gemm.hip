@@ -81,8 +81,16 @@ __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n32 = lane & 31, kg = lane >> 5;
-  const int64_t m0 = (int64_t)blockIdx.y * BM;
-  const int nt0 = (blockIdx.x * W + wave) * NT;
+  // Workgroup -> tile map, XCD aware: consecutive workgroup ids go round-robin to the 8 XCDs (each with
+  // its own L2), so XCD x = id % 8 gets a contiguous eighth of the column blocks and walks them fastest:
+  // the ~32 workgroups an XCD runs at a time then share a few x slabs and each weight stripe stays in
+  // one L2 instead of eight.
+  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+  const int nb_local = local % a.nblk_per_xcd, mb = local / a.nblk_per_xcd;
+  const int nb = xcd * a.nblk_per_xcd + nb_local;
+  if (nb >= a.n_blocks) return;          // padding of the last XCD's share (uniform per workgroup)
+  const int64_t m0 = (int64_t)mb * BM;
+  const int nt0 = (nb * W + wave) * NT;
   const int64_t n_stages = ceil_div_dev(a.K, 64);
   const int64_t s_begin = 0, s_end = n_stages;
 
@@ -325,8 +333,11 @@ static int g_force_cfg = -1;
 template <int MT, int NT, int W>
 static int launch_cfg(const GemmArgs& a, hipStream_t st) {
   constexpr size_t lds = 2 * (size_t)MT * 32 * 8 * sizeof(u32x4);
-  const dim3 grid((unsigned)ceil_div(a.n_tiles, W * NT), (unsigned)ceil_div(a.M, MT * 32));
-  gemm32_kernel<MT, NT, W><<<grid, W * 64, lds, st>>>(a);
+  GemmArgs b = a;
+  b.n_blocks = (int)ceil_div(a.n_tiles, W * NT);
+  b.nblk_per_xcd = (int)ceil_div(b.n_blocks, 8);
+  const int64_t m_blocks = ceil_div(a.M, MT * 32);
+  gemm32_kernel<MT, NT, W><<<dim3((unsigned)(8 * b.nblk_per_xcd * m_blocks)), W * 64, lds, st>>>(b);
   return launch_status();
 }
 

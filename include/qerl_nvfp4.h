@@ -139,6 +139,32 @@ QERL_API int nvfp4_lora_linear_packed(const void* x_bf16, int64_t M, int64_t K, 
                                       void* y_bf16, int64_t ldy,
                                       void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---------------------------------------------------------------------------
+ * nvfp4_lora_linear_packed_group -- up to 4 linears that read the same x (the
+ * q/k/v or the gate/up projections of a block, which share one noisy RMSNorm
+ * output: Section 3.3) in ONE launch.  Each member is computed exactly as
+ * nvfp4_lora_linear_packed would compute it; only the launch is shared.
+ *   members: HOST array of n_members descriptors (read during the call only;
+ *            the pointers inside are device pointers).
+ *   workspace: as for nvfp4_lora_linear, sized with
+ *            nvfp4_lora_linear_workspace_bytes(M, sum of N, K, sum of r).
+ * Errors: as nvfp4_lora_linear_packed, plus n_members outside 1..4.
+ */
+typedef struct {
+  const void* packed;          /* nvfp4_prepack output for this member's [N, K] weight */
+  const float* tensor_scale;
+  int64_t N;
+  const void* A_bf16;          /* [r, K] or NULL */
+  const void* B_bf16;          /* [N, r] or NULL */
+  int64_t r;
+  float lora_scale;
+  void* y_bf16;                /* [M, ldy] out */
+  int64_t ldy;
+} qerl_linear_desc;
+QERL_API int nvfp4_lora_linear_packed_group(const void* x_bf16, int64_t M, int64_t K, int64_t ldx,
+                                            const qerl_linear_desc* members, int n_members,
+                                            void* workspace, size_t workspace_bytes, void* stream);
+
 /* Zero the control words of a linear workspace.  Call once after allocating
  * it (and again if a kernel using it was ever aborted). */
 QERL_API int qerl_workspace_init(void* workspace, size_t workspace_bytes, void* stream);

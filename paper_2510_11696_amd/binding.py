@@ -36,6 +36,8 @@ _SIGNATURES = {
     "nvfp4_lora_linear_packed": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_p, _c_i64,
                                                 _c_p, _c_p, _c_i64, ctypes.c_float, _c_p, _c_i64,
                                                 _c_p, _c_sz, _c_p]),
+    "nvfp4_lora_linear_packed_group": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, ctypes.c_int,
+                                                      _c_p, _c_sz, _c_p]),
     "qerl_workspace_init": (ctypes.c_int, [_c_p, _c_sz, _c_p]),
     "aqn_rmsnorm": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_p, ctypes.c_float,
                                    _c_p, _c_i64, _c_p]),
@@ -236,6 +238,53 @@ def nvfp4_lora_linear_packed(x, w: PackedWeight, A: Optional[torch.Tensor] = Non
         _dev(w.tensor_scale, torch.float32, "tensor_scale"), N, a_ptr, b_ptr, r, float(lora_scale),
         _dev(out, torch.bfloat16, "out"), ldy, workspace.ptr, workspace.nbytes, _stream()))
     return out
+
+
+class _LinearDesc(ctypes.Structure):
+    """Mirror of qerl_linear_desc in the header."""
+    _fields_ = [("packed", _c_p), ("tensor_scale", _c_p), ("N", _c_i64), ("A", _c_p), ("B", _c_p),
+                ("r", _c_i64), ("lora_scale", ctypes.c_float), ("y", _c_p), ("ldy", _c_i64)]
+
+
+def nvfp4_lora_linear_packed_group(x, weights, As=None, Bs=None, lora_scales=None,
+                                   workspace: Optional[Workspace] = None, outs=None):
+    """Several packed linears that read the same x (q/k/v, gate/up) in one launch.
+    weights: list of PackedWeight; As/Bs: lists of LoRA matrices (or None); returns the list of outputs."""
+    lib = load_library()
+    M, K, ldx = _rows(x, "x")
+    n = len(weights)
+    As = As if As is not None else [None] * n
+    Bs = Bs if Bs is not None else [None] * n
+    lora_scales = lora_scales if lora_scales is not None else [0.0] * n
+    if outs is None:
+        outs = [torch.empty((M, w.N), dtype=torch.bfloat16, device=x.device) for w in weights]
+    descs = (_LinearDesc * n)()
+    n_sum = r_sum = 0
+    for i, w in enumerate(weights):
+        if w.K != K:
+            raise ValueError("every member must have K columns")
+        r = 0
+        a_ptr = b_ptr = None
+        if As[i] is not None and Bs[i] is not None and As[i].shape[0] > 0:
+            r = As[i].shape[0]
+            if tuple(As[i].shape) != (r, K) or tuple(Bs[i].shape) != (w.N, r) or not As[i].is_contiguous() \
+                    or not Bs[i].is_contiguous():
+                raise ValueError("A must be contiguous [r, K] and B contiguous [N, r]")
+            a_ptr, b_ptr = _dev(As[i], torch.bfloat16, "A"), _dev(Bs[i], torch.bfloat16, "B")
+        _, n_out, ldy = _rows(outs[i], "out")
+        if outs[i].shape[0] != M or n_out != w.N:
+            raise ValueError("out must be [M, N]")
+        descs[i] = _LinearDesc(_dev(w.packed, torch.uint8, "packed"),
+                               _dev(w.tensor_scale, torch.float32, "tensor_scale"), w.N, a_ptr, b_ptr, r,
+                               float(lora_scales[i]), _dev(outs[i], torch.bfloat16, "out"), ldy)
+        n_sum += w.N
+        r_sum += r
+    if workspace is None:
+        workspace = Workspace(lib.nvfp4_lora_linear_workspace_bytes(M, n_sum, K, r_sum), x.device)
+    _check("nvfp4_lora_linear_packed_group", lib.nvfp4_lora_linear_packed_group(
+        _dev(x, torch.bfloat16, "x"), M, K, ldx, ctypes.cast(descs, _c_p), n,
+        workspace.ptr, workspace.nbytes, _stream()))
+    return outs
 
 
 def aqn_rmsnorm(x, gain, noise: Optional[torch.Tensor] = None, eps: float = 1e-6,

@@ -14,17 +14,23 @@ void set_last_hip_error(int e) { g_last_hip_error = e; }
 //   [partial_off, ...)  split-K partial tiles, fp32
 struct WorkspaceLayout { size_t ctrl_bytes, n_main_ctr, n_down_ctr, t_off, partial_off, total; };
 
-constexpr size_t kDecodeTpartWords = 16 * 2 * 8 * 64;   // producer partial sums of the fused LoRA down-projection
-constexpr size_t kMaxCounterTiles = 1 << 16;   // rows / 16 the control region can serve
+constexpr size_t kDecodeTpartWords = 16 * 3 * 2 * 8 * 64;   // producer partial sums of the fused LoRA down-projection (<= 16 producers, 3 tile pairs)
+constexpr size_t kMaxCounterTiles = 16384;   // rows / 16 the control region can serve
 
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
+// The control region has a FIXED size and position so that calls of different shapes can share one
+// workspace: no call's data region may overlap another call's control words (they must stay zero).
+constexpr size_t kCtrlMainWords = 16384;   // arrival counters of the main kernels: N / 16 <= 16384
+constexpr size_t kCtrlDownWords = 256;     // arrival counters of the LoRA down-projection kernel: r / 16 <= 256
+constexpr size_t kCtrlBytes = (kCtrlMainWords + kCtrlDownWords + 64) * sizeof(uint32_t);   // + hand-over words, 256-multiple
+
 static WorkspaceLayout workspace_layout(int64_t M, int64_t N, int64_t K, int64_t r) {
   WorkspaceLayout L;
-  L.n_main_ctr = (size_t)ceil_div(N > 0 ? N : 1, 16);
+  L.n_main_ctr = kCtrlMainWords;
   const size_t n_down_ctr = (size_t)ceil_div(r > 0 ? r : 1, 16);
-  L.n_down_ctr = n_down_ctr;
-  L.ctrl_bytes = align256((L.n_main_ctr + n_down_ctr + 4) * sizeof(uint32_t));   // + LoRA hand-over words
+  L.n_down_ctr = kCtrlDownWords;
+  L.ctrl_bytes = kCtrlBytes;
   L.t_off = L.ctrl_bytes;
   // t = x A^T: fp32 [M, r] for the decode kernels, or three bf16 terms [M, ceil64(3r)] for the GEMM
   const size_t rows = (size_t)(M > 0 ? M : 1), rr = (size_t)(r > 0 ? r : 1);
@@ -33,9 +39,9 @@ static WorkspaceLayout workspace_layout(int64_t M, int64_t N, int64_t K, int64_t
   L.partial_off = L.t_off + t_bytes;
   // worst case over the plans the dispatchers can choose (one K-tile per wave)
   const size_t S_max = (size_t)ceil_div(ceil_div(K > 0 ? K : 1, 256), 8);
-  const size_t tiles = L.n_main_ctr + n_down_ctr;
   const size_t S_down = (size_t)ceil_div(ceil_div(K > 0 ? K : 1, 256), 2) + 1;
-  const size_t skinny_bytes = (S_max * L.n_main_ctr + S_down * n_down_ctr) * 64 * sizeof(f32x4);
+  const size_t n_rows16 = (size_t)ceil_div(N > 0 ? N : 1, 16);
+  const size_t skinny_bytes = (S_max * n_rows16 + S_down * n_down_ctr) * 64 * sizeof(f32x4);
   const size_t S_dec = (size_t)ceil_div(ceil_div(K > 0 ? K : 1, kPackTileK), 7);
   const size_t decode_bytes = S_dec * (size_t)ceil_div(N > 0 ? N : 1, kPackTileRows) * 8 * 64 * sizeof(float) +
                               S_down * n_down_ctr * 64 * sizeof(f32x4) + kDecodeTpartWords * sizeof(uint32_t);
@@ -177,6 +183,78 @@ extern "C" int nvfp4_lora_linear(const void* x, int64_t M, int64_t K, int64_t ld
   return QERL_OK;
 }
 
+namespace qerl {
+static bool g_use_stream = true;
+
+// One streaming launch for a group of packed linears sharing x (M <= 16; every r in {0} or 8..64 step 8).
+static int stream_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const qerl_linear_desc* d, int n,
+                        uint8_t* ws, const WorkspaceLayout& L, hipStream_t st) {
+  StreamArgs a{};
+  a.x = x; a.ldx = ldx; a.M = (int)M; a.K = K; a.k_tiles = (int)ceil_div(K, kPackTileK);
+  a.n_members = n;
+  int tiles = 0, rt = 0;
+  for (int i = 0; i < n; ++i) {
+    StreamMember& m = a.mem[i];
+    m.packed = (const uint8_t*)d[i].packed; m.tensor_scale = d[i].tensor_scale;
+    m.A = (const uint16_t*)d[i].A_bf16; m.B = (const uint16_t*)d[i].B_bf16; m.y = (uint16_t*)d[i].y_bf16;
+    m.ldy = d[i].ldy; m.N = d[i].N; m.n_tiles = (int)ceil_div(d[i].N, kPackTileRows); m.tile_begin = tiles;
+    m.r = (int)d[i].r; m.t_off = rt; m.lora_scale = d[i].lora_scale;
+    tiles += m.n_tiles; rt += m.r;
+  }
+  a.total_tiles = tiles; a.r_total = rt;
+  size_t lds = 0;
+  int MR = 4;
+  const int prc = plan_stream(a, &lds, &MR);
+  if (prc != QERL_OK) return prc;
+  uint32_t* partial = (uint32_t*)(ws + L.partial_off);
+  const size_t part_words = ((size_t)a.Sk * tiles * MR * 64 + 3) & ~(size_t)3;
+  a.partial = partial; a.counters = (uint32_t*)ws;
+  a.t = (float*)(ws + L.t_off);
+  a.lora_ctl = (uint32_t*)ws + L.n_main_ctr + L.n_down_ctr;
+  a.tpart = partial + part_words;
+  if (rt > 0) {
+    int64_t np = ceil_div(2 * (int64_t)a.k_tiles, 8);   // one half K-tile per producer wave and tile pair
+    a.n_producers = (int)(np < 1 ? 1 : (np > 16 ? 16 : np));
+  }
+  return launch_stream(a, lds, MR, st);
+}
+}  // namespace qerl
+
+extern "C" QERL_API void qerl_debug_use_stream(int on) { qerl::g_use_stream = on != 0; }
+
+extern "C" int nvfp4_lora_linear_packed_group(const void* x, int64_t M, int64_t K, int64_t ldx,
+                                              const qerl_linear_desc* members, int n_members, void* workspace,
+                                              size_t workspace_bytes, void* stream) {
+  if (!members) return QERL_ERR_NULL;
+  if (n_members < 1 || n_members > kMaxGroup) return QERL_ERR_SHAPE;
+  int64_t n_sum = 0, r_sum = 0;
+  bool stream_ok = M <= 16;
+  for (int i = 0; i < n_members; ++i) {
+    const qerl_linear_desc& d = members[i];
+    LinearCall c{(const uint16_t*)x, M, K, ldx, d.tensor_scale, d.N, (const uint16_t*)d.A_bf16, (const uint16_t*)d.B_bf16,
+                 d.r, d.lora_scale, (uint16_t*)d.y_bf16, d.ldy, workspace, ~(size_t)0, (hipStream_t)stream};
+    const int vr = validate(c, d.packed, d.packed);
+    if (vr < 0) return vr;
+    if (d.N < 1) return QERL_ERR_SHAPE;
+    n_sum += d.N; r_sum += d.r;
+    stream_ok = stream_ok && (d.r == 0 || (d.r <= 64 && d.r % 8 == 0 && aligned(d.A_bf16, 16) && aligned(d.B_bf16, 16)));
+  }
+  if (M == 0) return QERL_OK;
+  if (K == 0) return QERL_ERR_SHAPE;
+  if (!aligned(x, 16) || ldx % 8 != 0) return QERL_ERR_ALIGN;
+  const WorkspaceLayout L = workspace_layout(M, n_sum, K, r_sum);
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total) return QERL_ERR_WORKSPACE;
+  if (stream_ok && g_use_stream)
+    return stream_group((const uint16_t*)x, M, K, ldx, members, n_members, (uint8_t*)workspace, L, (hipStream_t)stream);
+  for (int i = 0; i < n_members; ++i) {   // general case: member by member
+    const qerl_linear_desc& d = members[i];
+    const int rc = nvfp4_lora_linear_packed(x, M, K, ldx, d.packed, d.tensor_scale, d.N, d.A_bf16, d.B_bf16, d.r,
+                                            d.lora_scale, d.y_bf16, d.ldy, workspace, workspace_bytes, stream);
+    if (rc != QERL_OK) return rc;
+  }
+  return QERL_OK;
+}
+
 extern "C" size_t nvfp4_prepack_bytes(int64_t N, int64_t K) {
   if (N <= 0 || K <= 0) return 0;
   return (size_t)ceil_div(N, kPackTileRows) * (size_t)ceil_div(K, kPackTileK) * kPackTileBytes;
@@ -223,6 +301,11 @@ extern "C" int nvfp4_lora_linear_packed(const void* x, int64_t M, int64_t K, int
     g.N = N; g.packed = (const uint8_t*)packed; g.n_tiles = (int)ceil_div(N, 32);
     g.B = c.B; g.y = c.y; g.ldy = ldy;
     return launch_gemm(g, c.st);
+  }
+
+  if (g_use_stream && M <= 16 && (r == 0 || (r <= 64 && r % 8 == 0 && aligned(A, 16) && aligned(B, 16)))) {
+    qerl_linear_desc d{packed, tensor_scale, N, A, B, r, lora_scale, y, ldy};
+    return stream_group(c.x, M, K, ldx, &d, 1, ws, L, c.st);
   }
 
   // Decode: passes of up to 16 tokens.  For the usual adapters (r <= 64, 16-byte aligned) the LoRA

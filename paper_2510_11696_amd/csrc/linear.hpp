@@ -42,6 +42,26 @@ int launch_decode(const DecodePlan& p, const DecodeArgs& a, hipStream_t st);
 int launch_prepack(const uint8_t* codes, const uint8_t* scales, int64_t N, int64_t K, uint8_t* out,
                    hipStream_t st);
 
+// ---- streaming decode kernel for one linear or a group sharing x (linear_stream.hip) ----
+constexpr int kMaxGroup = 4;
+struct StreamMember {
+  const uint8_t* packed; const float* tensor_scale; const uint16_t* A; const uint16_t* B; uint16_t* y;
+  int64_t ldy; int64_t N; int n_tiles; int tile_begin;   // row-tiles [tile_begin, tile_begin + n_tiles) of the group
+  int r; int t_off;                                      // rank; column offset of this member's t in the stacked t
+  float lora_scale;
+};
+struct StreamArgs {
+  const uint16_t* x; int64_t ldx; int M; int64_t K; int k_tiles;
+  int n_members; StreamMember mem[kMaxGroup];
+  int total_tiles; int r_total;
+  int Sk; int n_consumers; int n_producers;              // K-ranges; consumer / producer workgroups
+  int xs_stride; int red_off; int pend_off;              // LDS layout (bytes): x row stride, reduction buffers, parked units
+  float* t; uint32_t* lora_ctl; uint32_t* tpart;         // stacked t [M, r_total]; hand-over words; producer partials
+  uint32_t* partial; uint32_t* counters;                 // K-range exchange
+};
+int plan_stream(StreamArgs& a, size_t* lds_bytes, int* MR);
+int launch_stream(const StreamArgs& a, size_t lds_bytes, int MR, hipStream_t st);
+
 // ---- prefill path: MFMA GEMM on tile-packed weights (linear_gemm.hip) ----
 struct GemmArgs {
   const uint16_t* x; int64_t ldx; int64_t M; int64_t K; int64_t N;

@@ -95,7 +95,8 @@ constexpr uint32_t kSpinLimit = 1u << 14;   // polls, about a microsecond apart,
 // the workspace, and the last one to arrive publishes t and raises the ready word.
 template <int MR>
 __device__ __forceinline__ void lora_down_producer(const DecodeArgs& a, float* red, int* s_last) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nthreads = blockDim.x, nwaves = nthreads >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, nthreads = blockDim.x, nwaves = nthreads >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform
   const int n32 = lane & 31, kg = lane >> 5;
   const int P = a.n_producers, n_at = (a.r + 31) >> 5;
   f32x16 pacc[2];
@@ -195,7 +196,8 @@ __global__ __launch_bounds__(kDecMaxWaves * 64) void decode32_kernel(const Decod
     lora_down_producer<MR>(a, red, &s_last);
     return;
   }
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nthreads = blockDim.x;
+  const int tid = threadIdx.x, lane = tid & 63, nthreads = blockDim.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps everything derived from it in SGPRs
   const int nwaves = nthreads >> 6;
   const int n32 = lane & 31, kg = lane >> 5;
   const int S = a.S;

@@ -79,7 +79,8 @@ __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
   // different bank halves, so 16 consecutive rows at one column touch 16 distinct 16-byte bank groups.
   extern __shared__ u32x4 xs[];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps everything derived from it in SGPRs
   const int n32 = lane & 31, kg = lane >> 5;
   // Workgroup -> tile map, XCD aware: consecutive workgroup ids go round-robin to the 8 XCDs (each with
   // its own L2), so XCD x = id % 8 gets a contiguous eighth of the column blocks and walks them fastest:
@@ -225,7 +226,8 @@ __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
 template <int NT>
 __global__ __launch_bounds__(512) void lora_down32_kernel(const GemmArgs a) {
   constexpr int kWaves = 8;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps everything derived from it in SGPRs
   const int n32 = lane & 31, kg = lane >> 5;
   const int64_t m0 = (int64_t)blockIdx.x * 32;
   const int nt0 = blockIdx.y * NT;

@@ -64,7 +64,8 @@ constexpr int kMaxWaves = 8;
 
 template <int KT, int T, int FMT>
 __global__ __launch_bounds__(kMaxWaves * 64) void skinny_kernel(const SkinnyArgs a) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, nwaves = blockDim.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform
   const int r16 = lane & 15, g = lane >> 4;
   const int64_t kwave = ((int64_t)blockIdx.y * nwaves + wave) * (KT * 256) + 64 * g;
   const int tile0 = blockIdx.x * T;

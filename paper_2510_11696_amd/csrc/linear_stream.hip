@@ -1,0 +1,607 @@
+// Streaming decode kernel (M <= 16 tokens) for one linear or a group of linears that share x
+// (q/k/v, gate/up) on tile-packed NVFP4 weights, LoRA included, one launch.
+//
+//   y_g[m,n] = S32_g * sum_b s_g[n,b] * ( sum_{k in block b} x[m,k] * e_g[n,k] )           (Eq. 6)
+//            + lora_scale_g * sum_j t_g[m,j] * B_g[n,j],      t_g = x A_g^T                 (Eq. 2)
+//
+// The op is bound by streaming 0.5625 B per weight from HBM once; at decode sizes the enemy
+// is latency, not arithmetic.  So the kernel is persistent and keeps memory busy from the
+// first cycle to the last:
+//   * ~one workgroup per CU walks a list of units; a unit is one row-tile (32 output rows) over
+//     the workgroup's K-range.  Seven "main" waves split the K-tiles of that range and stream
+//     them through a ring of D tiles in registers that is refilled as it is consumed -- across
+//     unit boundaries, so the next unit's weights are already in flight while this one is
+//     being multiplied.  Nothing in their loop waits on anything but weight data and one
+//     barrier per unit.
+//   * The x slice of the K-range lives in LDS for the whole launch (rows padded by 32 bytes so
+//     that the MFMA operand reads of 8..16 tokens hit distinct banks; tokens >= M read a zero
+//     row), so any wave can work on any K-tile without holding x in registers.
+//   * Arithmetic per 16-input scale block as in linear_decode.hip: bare E2M1 values into one
+//     v_mfma_f32_32x32x16_bf16, then acc += E4M3 scale * product (one FMA per live token row).
+//   * The eighth wave is the epilogue wave and runs one unit behind: it computes the LoRA
+//     up-projection of the unit (B rows prefetched, fp32 t split into three bf16 terms, MFMAs
+//     over j), and after the unit's barrier adds the seven partial tiles from LDS, applies S32,
+//     and either stores y or -- when K is split over several workgroups because x does not fit
+//     in LDS -- exchanges partial tiles through the workspace (agent-scope atomics, last one to
+//     arrive adds them in range order).  Its stores and waits never stall the streaming waves.
+//   * t = x A^T for all members comes from producer workgroups at the front of the grid, as in
+//     linear_decode.hip (ready word, bounded wait, NaN on time-out).
+// Results are bit-identical from call to call: every sum has a fixed order.
+#include "linear.hpp"
+
+namespace qerl {
+
+constexpr int kStreamWaves = 8;             // 7 main + 1 epilogue
+constexpr int kMainWaves = kStreamWaves - 1;
+constexpr int kCtlArrive = 0, kCtlReady = 1, kCtlDone = 2;
+constexpr uint32_t kStreamSpinLimit = 1u << 14;
+
+__device__ __forceinline__ bf16x8 stream_e2m1x8(uint32_t codes) {
+  const bf16x2 p0 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, 1.0f, 0);
+  const bf16x2 p1 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, 1.0f, 1);
+  const bf16x2 p2 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, 1.0f, 2);
+  const bf16x2 p3 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, 1.0f, 3);
+  u32x4 o = {__builtin_bit_cast(uint32_t, p0), __builtin_bit_cast(uint32_t, p1),
+             __builtin_bit_cast(uint32_t, p2), __builtin_bit_cast(uint32_t, p3)};
+  return __builtin_bit_cast(bf16x8, o);
+}
+__device__ __forceinline__ float stream_e4m3(uint32_t v, int b) {
+  switch (b) {
+    case 0: return __builtin_amdgcn_cvt_f32_fp8(v, 0);
+    case 1: return __builtin_amdgcn_cvt_f32_fp8(v, 1);
+    case 2: return __builtin_amdgcn_cvt_f32_fp8(v, 2);
+    default: return __builtin_amdgcn_cvt_f32_fp8(v, 3);
+  }
+}
+__device__ __forceinline__ void stream_split3(const float (&v)[8], u32x4& hi, u32x4& mid, u32x4& lo) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t h = pack_bf16x2(v[2 * i], v[2 * i + 1]);
+    const float r0 = v[2 * i] - bf16_bits_to_f32(h & 0xffffu), r1 = v[2 * i + 1] - __uint_as_float(h & 0xffff0000u);
+    const uint32_t m = pack_bf16x2(r0, r1);
+    const float q0 = r0 - bf16_bits_to_f32(m & 0xffffu), q1 = r1 - __uint_as_float(m & 0xffff0000u);
+    hi[i] = h; mid[i] = m; lo[i] = pack_bf16x2(q0, q1);
+  }
+}
+
+// which member of the group owns global row-tile nt (members are few: linear search)
+__device__ __forceinline__ int member_of(const StreamArgs& a, int nt) {
+  int m = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxGroup; ++i)
+    if (i < a.n_members && nt >= a.mem[i].tile_begin) m = i;
+  return m;
+}
+
+// ---- producers: t[tok][j] = sum_k x[tok,k] * Astack[j,k] for the stacked A of all members ----------
+template <int MR>
+__device__ __forceinline__ void stream_producer(const StreamArgs& a, float* red, int* s_flag) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps everything derived from it in SGPRs
+  const int n32 = lane & 31, kg = lane >> 5;
+  const int P = a.n_producers, n_at = (a.r_total + 31) >> 5, n_pairs = (n_at + 1) >> 1;
+  constexpr int kElems = 2 * MR * 64;
+  for (int pair = 0; pair < n_pairs; ++pair) {
+    f32x16 pacc[2];
+#pragma unroll
+    for (int at = 0; at < 2; ++at)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) pacc[at][i] = 0.f;
+    // rows of the stacked A: member by member; row j of the stack lives in member mi at j - t_off
+    for (int64_t h = (int64_t)blockIdx.x * kStreamWaves + wave; h < 2 * (int64_t)a.k_tiles; h += (int64_t)P * kStreamWaves) {
+      u32x4 xa[4], af[2][4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int64_t k = h * 64 + 16 * j + 8 * kg;
+        xa[j] = u32x4{0u, 0u, 0u, 0u};
+        if (n32 < a.M && k < a.K) xa[j] = *reinterpret_cast<const u32x4*>(a.x + (int64_t)n32 * a.ldx + k);
+#pragma unroll
+        for (int at = 0; at < 2; ++at) {
+          const int row = (2 * pair + at) * 32 + n32;     // row of the stacked A
+          af[at][j] = u32x4{0u, 0u, 0u, 0u};
+          if (row < a.r_total && k < a.K) {
+            int mi = 0;
+#pragma unroll
+            for (int i = 1; i < kMaxGroup; ++i)
+              if (i < a.n_members && row >= a.mem[i].t_off) mi = i;
+            af[at][j] = *reinterpret_cast<const u32x4*>(a.mem[mi].A + (int64_t)(row - a.mem[mi].t_off) * a.K + k);
+          }
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        pacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[j]),
+                                                          __builtin_bit_cast(bf16x8, af[0][j]), pacc[0], 0, 0, 0);
+        pacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[j]),
+                                                          __builtin_bit_cast(bf16x8, af[1][j]), pacc[1], 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int at = 0; at < 2; ++at)
+#pragma unroll
+      for (int q = 0; q < MR; ++q) red[(wave * 2 + at) * MR * 64 + q * 64 + lane] = pacc[at][q];
+    __syncthreads();
+    for (int e = tid; e < kElems; e += kStreamWaves * 64) {
+      float s = red[e];
+      for (int w = 1; w < kStreamWaves; ++w) s += red[w * kElems + e];
+      __hip_atomic_store(a.tpart + ((int64_t)blockIdx.x * n_pairs + pair) * kElems + e, __float_as_uint(s),
+                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();   // red is reused by the next pair
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's partial stores have completed
+  __syncthreads();
+  if (tid == 0) {
+    const uint32_t old = __hip_atomic_fetch_add(a.lora_ctl + kCtlArrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *s_flag = (old == (uint32_t)(P - 1));
+  }
+  __syncthreads();
+  if (!*s_flag) return;
+  // last producer to arrive: add the P partial tiles in producer order and publish t
+  for (int pe = tid; pe < n_pairs * kElems; pe += kStreamWaves * 64) {
+    const int pair = pe / kElems, e = pe - pair * kElems;
+    const float s = ordered_sum_sc1(a.tpart + (int64_t)pair * kElems + e, (int64_t)n_pairs * kElems, P);
+    const int at = e / (MR * 64), q = (e / 64) % MR, l = e & 63;
+    const int tok = 8 * (q >> 2) + 4 * (l >> 5) + (q & 3), j = (2 * pair + at) * 32 + (l & 31);
+    if (tok < a.M && j < a.r_total)
+      __hip_atomic_store(reinterpret_cast<uint32_t*>(a.t) + tok * a.r_total + j, __float_as_uint(s), __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // t is written before the ready word
+  __syncthreads();
+  if (tid == 0) {
+    __hip_atomic_store(a.lora_ctl + kCtlArrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(a.lora_ctl + kCtlReady, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
+struct StreamTile { u32x4 c0, c1; u32x2 sc; };
+
+// Optional timeline stamps for tuning (build with -DQERL_STREAM_TRACE): eight 100 MHz time stamps per wave
+// of the first 512 workgroups, read back with qerl_debug_read_trace().
+#ifdef QERL_STREAM_TRACE
+__device__ unsigned long long g_trace[512 * 8 * 8];
+#define QTRACE(p) do { if (lane == 0 && blockIdx.x < 512) g_trace[((int)blockIdx.x * 8 + wave) * 8 + (p)] = wall_clock64(); } while (0)
+#else
+#define QTRACE(p) do { } while (0)
+#endif
+
+constexpr int kLoraSteps = 4;               // 16-wide j steps of the up-projection (r <= 64)
+constexpr int kMaxPending = 4;              // units an epilogue wave can park while t is not ready
+
+// out[q] = sum over z < S of p[z * stride + q * 64] for all q at once: agent-scope loads issued in
+// batches before any is consumed, added in index order (same result on every call).
+template <int MR>
+__device__ __forceinline__ void ordered_sum_tile(const uint32_t* p, int64_t stride, int S, float (&out)[MR]) {
+  constexpr int kBatch = MR == 4 ? 8 : 4;
+#pragma unroll
+  for (int q = 0; q < MR; ++q) out[q] = 0.f;
+  for (int z0 = 0; z0 < S; z0 += kBatch) {
+    uint32_t v[kBatch][MR];
+#pragma unroll
+    for (int b = 0; b < kBatch; ++b)
+#pragma unroll
+      for (int q = 0; q < MR; ++q) {
+        v[b][q] = 0u;
+        if (z0 + b < S) v[b][q] = __hip_atomic_load(p + (int64_t)(z0 + b) * stride + q * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+#pragma unroll
+    for (int b = 0; b < kBatch; ++b)
+#pragma unroll
+      for (int q = 0; q < MR; ++q) out[q] += __uint_as_float(v[b][q]);
+  }
+}
+
+template <int MR, int D>
+__global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamArgs a) {
+  // x slice [(M+1) rows][xs_stride bytes], red[2][7][MR][64] floats, parked units.  The alignment matters:
+  // the static s_flag is placed first, and 16-byte LDS accesses from a base of 4 run several times slower.
+  extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
+  __shared__ int s_flag;
+  float* red = reinterpret_cast<float*>(smem + a.red_off);
+  if ((int)blockIdx.x < a.n_producers) {
+    stream_producer<MR>(a, reinterpret_cast<float*>(smem), &s_flag);
+    return;
+  }
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps everything derived from it in SGPRs
+  const int n32 = lane & 31, kg = lane >> 5;
+  QTRACE(0);
+  const int cid = (int)blockIdx.x - a.n_producers;
+  const int range = cid % a.Sk, ci = cid / a.Sk, stride_u = a.n_consumers / a.Sk;
+  const int n_units = ci < a.total_tiles ? (a.total_tiles - ci + stride_u - 1) / stride_u : 0;
+  // K-range of this workgroup, in K-tiles
+  const int kr_len = (a.k_tiles + a.Sk - 1) / a.Sk;
+  const int kr0 = range * kr_len, kr1 = (kr0 + kr_len < a.k_tiles) ? kr0 + kr_len : a.k_tiles;
+
+  // ---- staging of the x slice of this K-range into LDS, all eight waves: thread -> 16-byte chunk column,
+  // all tokens of a column loaded before any is stored
+  constexpr int MT = MR == 4 ? 8 : 16;
+  constexpr int kThreads = kStreamWaves * 64;
+  const int chunks_per_row = (kr1 - kr0) * 16;
+  auto xload = [&](int ch, u32x4 (&xv)[MT]) {
+    const int64_t k = (int64_t)kr0 * 128 + ch * 8;
+#pragma unroll
+    for (int tok = 0; tok < MT; ++tok) {
+      xv[tok] = u32x4{0u, 0u, 0u, 0u};
+      if (tok < a.M && ch < chunks_per_row && k < a.K) xv[tok] = *reinterpret_cast<const u32x4*>(a.x + (int64_t)tok * a.ldx + k);
+    }
+  };
+  auto xstore = [&](int ch, const u32x4 (&xv)[MT]) {
+    if (ch < chunks_per_row) {
+#pragma unroll
+      for (int tok = 0; tok < MT; ++tok)
+        if (tok < a.M) *reinterpret_cast<u32x4*>(smem + tok * a.xs_stride + ch * 16) = xv[tok];
+      *reinterpret_cast<u32x4*>(smem + a.M * a.xs_stride + ch * 16) = u32x4{0u, 0u, 0u, 0u};   // the zero row
+    }
+  };
+  u32x4 xv[MT];
+  int ch0 = 0;
+  for (; chunks_per_row - ch0 > kThreads; ch0 += kThreads) {   // K-ranges beyond 4096 inputs: all but the last batch
+    xload(ch0 + tid, xv);
+    xstore(ch0 + tid, xv);
+  }
+  xload(ch0 + tid, xv);
+  // Every wave of this CU has queued its x loads before any weight load is queued behind them: without
+  // this, x for the last waves would arrive after the whole first ring of all waves.
+  __builtin_amdgcn_s_barrier();
+
+  if (wave < kMainWaves) {
+    // ---- main wave: my K-tiles of every unit
+    const int lw = (kr1 - kr0 + kMainWaves - 1) / kMainWaves;
+    const int kt0 = kr0 + wave * lw;
+    int kt1 = kt0 + lw;
+    kt1 = kt1 < kr1 ? kt1 : kr1;
+    const bool have = kt0 < kt1;
+    StreamTile ring[D];
+    int lu = 0, lk = kt0;                 // load cursor (unit, K-tile)
+    // Every call issues exactly three loads, also past the end of this wave's sequence (then from the
+    // first tile of the group, a cache hit that is never used): with a fixed number of loads in flight
+    // the wait before a slot is consumed covers that slot only, not the whole ring.
+    auto issue = [&](StreamTile& t) {
+      const bool live = have && lu < n_units;
+      const int nt = live ? ci + lu * stride_u : 0;
+      const int mi = member_of(a, nt);
+      const int64_t tile = live ? (int64_t)(nt - a.mem[mi].tile_begin) * a.k_tiles + lk : 0;
+      const uint8_t* base = a.mem[mi].packed + tile * kPackTileBytes;
+      t.c0 = *reinterpret_cast<const u32x4*>(base + lane * 16);
+      t.c1 = *reinterpret_cast<const u32x4*>(base + 1024 + lane * 16);
+      t.sc = *reinterpret_cast<const u32x2*>(base + 2048 + n32 * 8);
+      if (live && ++lk == kt1) { lk = kt0; ++lu; }
+    };
+#pragma unroll
+    for (int d = 0; d < D; ++d) issue(ring[d]);
+    xstore(ch0 + tid, xv);               // waits for x only: the ring stays in flight
+    __syncthreads();
+    QTRACE(1);
+
+    const int xrow = n32 < a.M ? n32 : a.M;          // tokens >= M read the zero row
+    const unsigned char* xbase = smem + xrow * a.xs_stride + kg * 16;
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float acc[MR];
+#pragma unroll
+    for (int q = 0; q < MR; ++q) acc[q] = 0.f;
+    int cu = 0, ck = kt0;                 // compute cursor
+    if (!have) {
+      // no K-tiles for this wave in this range: contribute zeros, keep the barriers
+      for (; cu < n_units; ++cu) {
+#pragma unroll
+        for (int q = 0; q < MR; ++q) red[(((cu & 1) * kMainWaves + wave) * MR + q) * 64 + lane] = 0.f;
+        __syncthreads();
+      }
+    }
+    // Ring slot d always holds tiles d, d + D, d + 2D, ... of this wave's sequence, so every slot is a fixed
+    // set of registers.  The body has no guard: past the end of the sequence it multiplies a dummy tile into
+    // accumulators that are never stored (the last unit has been handed over by then), which keeps the number
+    // of loads in flight the same on every path.
+    const int n_seq = have ? n_units * (kt1 - kt0) : 0;
+    for (int i0 = 0; i0 < n_seq; i0 += D) {
+#pragma unroll
+      for (int d = 0; d < D; ++d) {
+        const StreamTile& t = ring[d];
+        const unsigned char* xk = xbase + (ck - kr0) * 256;
+        f32x16 tmp[2];
+        tmp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(xk)),
+                                                         stream_e2m1x8(t.c0[0]), zero, 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          // the product of the next scale block is on its way while this one is scaled and added
+          if (j + 1 < 8) {
+            const bf16x8 xa = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(xk + (j + 1) * 32));
+            const bf16x8 w = stream_e2m1x8(j + 1 < 4 ? t.c0[(j + 1) & 3] : t.c1[(j + 1) & 3]);
+            tmp[(j + 1) & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, w, zero, 0, 0, 0);
+          }
+          const float s = stream_e4m3(t.sc[j >> 2], j & 3);
+#pragma unroll
+          for (int q = 0; q < MR; ++q) acc[q] = __builtin_fmaf(s, tmp[j & 1][q], acc[q]);
+        }
+        // The refill must stay below the last use of the slot: otherwise the incoming data needs other
+        // registers, and moving them back at the loop end costs a wait for everything in flight.  The empty
+        // asm pins the accumulators (and with them every use of the slot) above this point.
+#pragma unroll
+        for (int q = 0; q < MR; ++q) asm volatile("" : "+v"(acc[q]));
+        __builtin_amdgcn_sched_barrier(0);
+        issue(ring[d]);                   // refill the slot in place (same registers), D tiles ahead
+        if (++ck == kt1) {
+          if (cu < n_units) {             // unit finished: hand the partial tile to the epilogue wave
+#pragma unroll
+            for (int q = 0; q < MR; ++q) {
+              red[(((cu & 1) * kMainWaves + wave) * MR + q) * 64 + lane] = acc[q];
+              acc[q] = 0.f;
+            }
+            QTRACE(2 + (cu < 4 ? cu : 4));
+            __syncthreads();
+            ++cu;
+          }
+          ck = kt0;
+        }
+      }
+    }
+    QTRACE(7);
+    return;
+  }
+
+  // ---- epilogue wave -----------------------------------------------------------------------------
+  xstore(ch0 + tid, xv);
+  __syncthreads();
+  QTRACE(1);
+
+  const bool lora_range = range == 0 && a.r_total > 0;     // only the first K-range adds the branch
+  // tensor scales of all members up front: no memory round trip between a unit's barrier and its stores
+  float S32m[kMaxGroup];
+#pragma unroll
+  for (int i = 0; i < kMaxGroup; ++i) S32m[i] = i < a.n_members ? *a.mem[i].tensor_scale : 0.f;
+
+  u32x4 th[kLoraSteps], tm[kLoraSteps], tl[kLoraSteps];
+  int t_member = -1;                      // member whose split t is in th/tm/tl
+  bool poisoned = false, t_ready = a.n_producers == 0;
+  int n_pend = 0, first_pend = 0;         // units [first_pend, first_pend + n_pend) are parked in LDS
+  float* pend_base = reinterpret_cast<float*>(smem + a.pend_off);          // [kMaxPending][MR][64]
+  u32x4* pend_b = reinterpret_cast<u32x4*>(smem + a.pend_off + kMaxPending * MR * 64 * 4);   // [kMaxPending][kLoraSteps][64]
+
+  auto wait_t = [&]() {                   // bounded: a hand-over that never comes poisons the output
+    uint32_t spins = 0;
+    while (__hip_atomic_load(a.lora_ctl + kCtlReady, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+      if (++spins > kStreamSpinLimit) { poisoned = true; break; }
+      __builtin_amdgcn_s_sleep(32);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    t_ready = true;
+  };
+  // lo = t_mi B^T for the 32 rows whose B fragments are in bq
+  auto lora_up = [&](int mi, const u32x4 (&bq)[kLoraSteps], f32x16& lo) {
+    const StreamMember& mem = a.mem[mi];
+    if (t_member != mi) {
+      // t was written through to memory before the ready word went up and no cache can hold an older
+      // copy (caches are invalidated at kernel start, nobody reads t earlier): ordinary loads suffice.
+#pragma unroll
+      for (int s = 0; s < kLoraSteps; ++s) {
+        const int j0 = 16 * s + 8 * kg;
+        float tv[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) tv[i] = 0.f;
+        if (n32 < a.M && j0 < mem.r) {
+          const float* tp = a.t + (int64_t)n32 * a.r_total + mem.t_off + j0;
+          const f32x4 t0 = *reinterpret_cast<const f32x4*>(tp), t1 = *reinterpret_cast<const f32x4*>(tp + 4);
+          tv[0] = t0[0]; tv[1] = t0[1]; tv[2] = t0[2]; tv[3] = t0[3];
+          tv[4] = t1[0]; tv[5] = t1[1]; tv[6] = t1[2]; tv[7] = t1[3];
+          if (poisoned) tv[0] = __uint_as_float(0x7fc00000u);   // the hand-over timed out: make it visible
+        }
+        stream_split3(tv, th[s], tm[s], tl[s]);
+      }
+      t_member = mi;
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) lo[i] = 0.f;
+#pragma unroll
+    for (int s = 0; s < kLoraSteps; ++s) {
+      const bf16x8 bf = __builtin_bit_cast(bf16x8, bq[s]);
+      lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, th[s]), bf, lo, 0, 0, 0);
+      lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tm[s]), bf, lo, 0, 0, 0);
+      lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tl[s]), bf, lo, 0, 0, 0);
+    }
+  };
+  // out = this range's share of tile nt: exchange across K-ranges if there are several, then store
+  auto finish = [&](int nt, int mi, float (&out)[MR]) {
+    const StreamMember& mem = a.mem[mi];
+    if (a.Sk > 1) {
+      uint32_t* mine = a.partial + ((int64_t)range * a.total_tiles + nt) * (MR * 64) + lane;
+#pragma unroll
+      for (int q = 0; q < MR; ++q)
+        __hip_atomic_store(mine + q * 64, __float_as_uint(out[q]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the partial tile is in memory before the arrival count
+      uint32_t old = 0;
+      if (lane == 0)
+        old = __hip_atomic_fetch_add(a.counters + nt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      old = __builtin_amdgcn_readfirstlane(old);
+      if (old != (uint32_t)(a.Sk - 1)) return;
+      ordered_sum_tile<MR>(a.partial + (int64_t)nt * (MR * 64) + lane, (int64_t)a.total_tiles * (MR * 64), a.Sk, out);
+      if (lane == 0) __hip_atomic_store(a.counters + nt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    const int64_t n = (int64_t)(nt - mem.tile_begin) * 32 + n32;
+#pragma unroll
+    for (int q = 0; q < MR; ++q) {
+      const int tok = 8 * (q >> 2) + 4 * kg + (q & 3);
+      if (tok < a.M && n < mem.N) mem.y[(int64_t)tok * mem.ldy + n] = (uint16_t)f32_to_bf16_bits(out[q]);
+    }
+  };
+  auto flush_pending = [&]() {
+    for (int p = 0; p < n_pend; ++p) {
+      const int nt = ci + (first_pend + p) * stride_u;
+      const int mi = member_of(a, nt);
+      u32x4 bq[kLoraSteps];
+#pragma unroll
+      for (int s = 0; s < kLoraSteps; ++s) bq[s] = pend_b[(p * kLoraSteps + s) * 64 + lane];
+      f32x16 lo;
+      lora_up(mi, bq, lo);
+      float out[MR];
+#pragma unroll
+      for (int q = 0; q < MR; ++q) out[q] = pend_base[(p * MR + q) * 64 + lane] + lo[q] * a.mem[mi].lora_scale;
+      finish(nt, mi, out);
+    }
+    n_pend = 0;
+  };
+
+  for (int u = 0; u < n_units; ++u) {
+    const int nt = ci + u * stride_u;
+    const int mi = member_of(a, nt);
+    const StreamMember& mem = a.mem[mi];
+    const bool needs_lora = lora_range && mem.r > 0;
+    u32x4 bq[kLoraSteps];
+    uint32_t ready_word = 1u;
+    if (needs_lora) {
+      // B rows of this unit and the ready word first: their latency overlaps the wait at the barrier
+      int64_t brow = (int64_t)(nt - mem.tile_begin) * 32 + n32;
+      brow = brow < mem.N ? brow : mem.N - 1;
+#pragma unroll
+      for (int s = 0; s < kLoraSteps; ++s) {
+        const int j0 = 16 * s + 8 * kg;
+        bq[s] = u32x4{0u, 0u, 0u, 0u};
+        if (j0 < mem.r) bq[s] = *reinterpret_cast<const u32x4*>(mem.B + brow * mem.r + j0);
+      }
+      if (!t_ready) ready_word = __hip_atomic_load(a.lora_ctl + kCtlReady, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    QTRACE(2 + (u < 4 ? u : 4));
+    __syncthreads();                      // the seven partial tiles of unit u are in red[u & 1]
+    float S32 = S32m[0];
+#pragma unroll
+    for (int i = 1; i < kMaxGroup; ++i) S32 = mi == i ? S32m[i] : S32;
+    float out[MR];
+#pragma unroll
+    for (int q = 0; q < MR; ++q) {
+      float s = 0.f;
+#pragma unroll
+      for (int w = 0; w < kMainWaves; ++w) s += red[(((u & 1) * kMainWaves + w) * MR + q) * 64 + lane];
+      out[q] = s * S32;
+    }
+    if (needs_lora) {
+      if (!t_ready && ready_word != 0u) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        t_ready = true;
+      }
+      if (!t_ready && n_pend < kMaxPending) {
+        // t is still on its way: park this unit (base sums and B fragments) and go on streaming
+        if (n_pend == 0) first_pend = u;
+#pragma unroll
+        for (int q = 0; q < MR; ++q) pend_base[(n_pend * MR + q) * 64 + lane] = out[q];
+#pragma unroll
+        for (int s = 0; s < kLoraSteps; ++s) pend_b[(n_pend * kLoraSteps + s) * 64 + lane] = bq[s];
+        ++n_pend;
+        continue;
+      }
+      if (!t_ready) wait_t();
+      flush_pending();
+      f32x16 lo;
+      lora_up(mi, bq, lo);
+#pragma unroll
+      for (int q = 0; q < MR; ++q) out[q] += lo[q] * mem.lora_scale;
+    }
+    finish(nt, mi, out);
+  }
+  if (n_pend > 0) {
+    if (!t_ready) wait_t();
+    flush_pending();
+  }
+  QTRACE(7);
+  // every first-range workgroup reports in once t is final; the last one re-arms the control words
+  if (a.n_producers > 0 && range == 0 && lane == 0) {
+    if (!t_ready) {   // a workgroup without LoRA units still has to count, after t is final
+      uint32_t spins = 0;
+      while (__hip_atomic_load(a.lora_ctl + kCtlReady, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+        if (++spins > kStreamSpinLimit) break;
+        __builtin_amdgcn_s_sleep(32);
+      }
+    }
+    const uint32_t old = __hip_atomic_fetch_add(a.lora_ctl + kCtlDone, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (old == (uint32_t)(a.n_consumers / a.Sk - 1)) {
+      __hip_atomic_store(a.lora_ctl + kCtlReady, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(a.lora_ctl + kCtlDone, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+}
+
+// ---- host ------------------------------------------------------------------------------------------
+
+static int g_force_consumers = 0;
+
+// LDS layout for M tokens (+ zero row) of a K-range of kr_len K-tiles: x slice, reduction buffers, and --
+// with LoRA -- the parking area of the epilogue wave.  Producers use the start of the same allocation.
+struct StreamLds { int xs_stride, red_off, pend_off; size_t total; };
+static StreamLds stream_lds(int M, int kr_len, int MR, bool lora) {
+  StreamLds l{};
+  l.xs_stride = kr_len * 256 + 16;   // rows 16 bytes apart in bank space: token rows and the zero row read conflict-free
+  const size_t xs = (size_t)(M + 1) * (size_t)l.xs_stride;
+  l.red_off = (int)((xs + 255) & ~(size_t)255);
+  const size_t red_consumer = 2 * (size_t)kMainWaves * MR * 64 * sizeof(float);
+  l.pend_off = l.red_off + (int)red_consumer;
+  const size_t pend = lora ? (size_t)kMaxPending * (MR * 64 * sizeof(float) + kLoraSteps * 64 * 16) : 0;
+  const size_t red_producer = (size_t)kStreamWaves * 2 * MR * 64 * sizeof(float);
+  l.total = l.pend_off + pend;
+  if (l.total < red_producer) l.total = red_producer;
+  return l;
+}
+
+constexpr size_t kStreamLdsMax = 160 * 1024 - 512;   // the static flag word takes one aligned slot of the CU's 160 KiB
+
+int plan_stream(StreamArgs& a, size_t* lds_bytes, int* MR_out) {
+  const int MR = a.M <= 8 ? 4 : 8;
+  *MR_out = MR;
+  const bool lora = a.r_total > 0;
+  // smallest number of K-ranges whose x slice fits
+  const size_t lds_cap = 150 * 1024;
+  int Sk = 1;
+  for (;; ++Sk) {
+    if (stream_lds(a.M, (int)ceil_div(a.k_tiles, Sk), MR, lora).total <= lds_cap) break;
+    if (Sk >= a.k_tiles) return QERL_ERR_SHAPE;
+  }
+  // small problems: more K-ranges so that every CU has a unit
+  while ((int64_t)a.total_tiles * Sk < 200 && ceil_div(a.k_tiles, Sk * 2) >= 2 * kMainWaves && Sk < 8) Sk *= 2;
+  const StreamLds l = stream_lds(a.M, (int)ceil_div(a.k_tiles, Sk), MR, lora);
+  *lds_bytes = l.total;
+  a.Sk = Sk; a.xs_stride = l.xs_stride; a.red_off = l.red_off; a.pend_off = l.pend_off;
+  int64_t per_range = 256 / Sk;        // one workgroup per CU: the kernel's register use allows no second one
+  if (per_range > a.total_tiles) per_range = a.total_tiles;
+  if (per_range < 1) per_range = 1;
+  if (g_force_consumers > 0) per_range = g_force_consumers / Sk > 0 ? g_force_consumers / Sk : 1;
+  a.n_consumers = (int)per_range * Sk;
+  return QERL_OK;
+}
+
+template <int MR, int D>
+static int launch_stream_t(const StreamArgs& a, size_t lds, hipStream_t st) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_kernel<MR, D>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStreamLdsMax) != hipSuccess)
+      return launch_status();
+    attr_set = true;
+  }
+  stream_kernel<MR, D><<<dim3(a.n_producers + a.n_consumers), dim3(kStreamWaves * 64), lds, st>>>(a);
+  return launch_status();
+}
+
+int launch_stream(const StreamArgs& a, size_t lds, int MR, hipStream_t st) {
+  // every pointer the kernel dereferences must be set by the caller
+  if (!a.x || !a.counters || !a.partial || a.n_members < 1 || a.n_members > kMaxGroup) return QERL_ERR_NULL;
+  for (int i = 0; i < a.n_members; ++i) {
+    const StreamMember& m = a.mem[i];
+    if (!m.packed || !m.tensor_scale || !m.y || m.N < 1 || m.n_tiles < 1) return QERL_ERR_NULL;
+    if (m.r > 0 && (!m.A || !m.B || m.r > 64 || m.r % 8 != 0)) return QERL_ERR_SHAPE;
+  }
+  if (a.r_total > 0 && (a.n_producers < 1 || a.n_producers > 16 || !a.t || !a.lora_ctl || !a.tpart)) return QERL_ERR_NULL;
+  if (a.M < 1 || a.M > 16 || a.K < 16 || a.k_tiles < 1 || a.Sk < 1 || a.n_consumers < a.Sk || a.n_consumers % a.Sk != 0 ||
+      a.total_tiles < 1 || lds > kStreamLdsMax || a.red_off <= 0 || a.pend_off < a.red_off)
+    return QERL_ERR_SHAPE;
+  if (MR == 4) return launch_stream_t<4, 6>(a, lds, st);
+  return launch_stream_t<8, 5>(a, lds, st);
+}
+
+}  // namespace qerl
+
+// Tuning hook for experiments (not part of the public header): force the number of consumer workgroups; 0 = automatic.
+extern "C" QERL_API void qerl_debug_force_stream(int consumers) { qerl::g_force_consumers = consumers; }
+#ifdef QERL_STREAM_TRACE
+extern "C" QERL_API int qerl_debug_read_trace(void* dst, size_t bytes) {
+  return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(qerl::g_trace), bytes, 0, hipMemcpyDeviceToHost);
+}
+#endif

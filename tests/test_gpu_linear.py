@@ -206,3 +206,38 @@ def test_rmsnorm_feeds_linear_end_to_end():
     ref = oracle.nvfp4_lora_linear(xn.float().cpu().numpy(), codes.cpu().numpy(), scales.cpu().numpy(),
                                    np.float32(ts.item()), A.float().numpy(), B.float().numpy(), 2.0)
     check_linear(y, ref, "norm->linear")
+
+
+@pytest.mark.parametrize("M", [1, 8, 16])
+@pytest.mark.parametrize("K,Ns,rs", [
+    (3584, (3584, 512, 512), (32, 32, 32)),      # q, k, v of the 7B block
+    (3584, (1184, 1184), (32, 32)),              # a slice of gate, up
+    (5120, (1024, 96, 40), (64, 0, 16)),         # mixed ranks, ragged row tiles
+    (18944, (64, 32), (32, 32)),                 # K split over several workgroups
+])
+def test_grouped_launch_equals_oracle(M, K, Ns, rs):
+    """One launch for several linears that share x: each member within tolerance of the oracle and
+    bit-identical to the single-linear call."""
+    print("group case", M, K, Ns, rs, flush=True)
+    x = qs.activations(M, K, 900 + M)
+    g = lambda a: torch.from_numpy(a).cuda()
+    ws_, As, Bs, refs = [], [], [], []
+    for i, (N, r) in enumerate(zip(Ns, rs)):
+        W = cases.gaussian(N, K, 1000 + 10 * i + M)
+        codes, scales, ts = oracle.nvfp4_quantize(W)
+        A = B = None
+        if r:
+            A, B = qs.lora_pair(N, K, r, 2000 + i)
+        ws_.append(qerl.nvfp4_prepack(g(codes), g(scales), torch.tensor([ts], device="cuda")))
+        As.append(A.cuda() if r else None)
+        Bs.append(B.cuda() if r else None)
+        refs.append(oracle.nvfp4_lora_linear(x.float().numpy(), codes, scales, ts,
+                                             A.float().numpy() if r else None, B.float().numpy() if r else None, 2.0))
+    outs = qerl.nvfp4_lora_linear_packed_group(x.cuda(), ws_, As, Bs, [2.0] * len(Ns))
+    torch.cuda.synchronize()
+    for i, (y, ref) in enumerate(zip(outs, refs)):
+        check_linear(y, ref, ("group", i, M, K, Ns, rs))
+        single = qerl.nvfp4_lora_linear_packed(x.cuda(), ws_[i], As[i], Bs[i], 2.0)
+        assert torch.equal(single, y)
+    again = qerl.nvfp4_lora_linear_packed_group(x.cuda(), ws_, As, Bs, [2.0] * len(Ns))
+    assert all(torch.equal(p, q) for p, q in zip(outs, again))

@@ -25,6 +25,8 @@ COMMON = [
     "-Wno-unused-command-line-argument",
 ]
 PER_FILE = {"quantize.hip": ["-ffp-contract=off"]}
+# extra hipcc flags for tuning builds, e.g. QERL_EXTRA_HIPCC_FLAGS=-DQERL_STREAM_TRACE
+COMMON += os.environ.get("QERL_EXTRA_HIPCC_FLAGS", "").split()
 
 
 def sources():

@@ -201,7 +201,17 @@ static int stream_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, co
     m.r = (int)d[i].r; m.t_off = rt; m.lora_scale = d[i].lora_scale;
     tiles += m.n_tiles; rt += m.r;
   }
+  for (int i = n; i < kMaxGroup; ++i) {   // unused entries: never selected, but valid to read
+    a.mem[i] = a.mem[0];
+    a.mem[i].tile_begin = 0x7fffffff; a.mem[i].n_tiles = 0; a.mem[i].r = 0;
+  }
+  a.tb1 = a.mem[1].tile_begin; a.tb2 = a.mem[2].tile_begin; a.tb3 = a.mem[3].tile_begin;
+  a.mp0 = a.mem[0].packed; a.mp1 = a.mem[1].packed; a.mp2 = a.mem[2].packed; a.mp3 = a.mem[3].packed;
   a.total_tiles = tiles; a.r_total = rt;
+  if (rt > 0) {
+    int64_t np = ceil_div(2 * (int64_t)a.k_tiles, 8);   // one half K-tile per producer wave and tile pair
+    a.n_producers = (int)(np < 1 ? 1 : (np > 16 ? 16 : np));
+  }
   size_t lds = 0;
   int MR = 4;
   const int prc = plan_stream(a, &lds, &MR);
@@ -212,10 +222,6 @@ static int stream_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, co
   a.t = (float*)(ws + L.t_off);
   a.lora_ctl = (uint32_t*)ws + L.n_main_ctr + L.n_down_ctr;
   a.tpart = partial + part_words;
-  if (rt > 0) {
-    int64_t np = ceil_div(2 * (int64_t)a.k_tiles, 8);   // one half K-tile per producer wave and tile pair
-    a.n_producers = (int)(np < 1 ? 1 : (np > 16 ? 16 : np));
-  }
   return launch_stream(a, lds, MR, st);
 }
 }  // namespace qerl

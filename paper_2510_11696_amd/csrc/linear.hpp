@@ -53,8 +53,11 @@ struct StreamMember {
 struct StreamArgs {
   const uint16_t* x; int64_t ldx; int M; int64_t K; int k_tiles;
   int n_members; StreamMember mem[kMaxGroup];
+  // flat copy of what the streaming loop needs of the member table (unused entries: INT_MAX / member 0's pointer)
+  int tb1, tb2, tb3; const uint8_t* mp0; const uint8_t* mp1; const uint8_t* mp2; const uint8_t* mp3;
   int total_tiles; int r_total;
-  int Sk; int n_consumers; int n_producers;              // K-ranges; consumer / producer workgroups
+  int Sk; int kr_len; int per_range; int n_producers;    // K-ranges, K-tiles in each, consumer workgroups per range; producers
+  int units_base; int units_rem;                         // consumer ci owns units_base (+1 if ci < units_rem) row-tiles
   int xs_stride; int red_off; int pend_off;              // LDS layout (bytes): x row stride, reduction buffers, parked units
   float* t; uint32_t* lora_ctl; uint32_t* tpart;         // stacked t [M, r_total]; hand-over words; producer partials
   uint32_t* partial; uint32_t* counters;                 // K-range exchange

@@ -64,14 +64,22 @@ __device__ __forceinline__ void stream_split3(const float (&v)[8], u32x4& hi, u3
   }
 }
 
-// which member of the group owns global row-tile nt (members are few: linear search)
-__device__ __forceinline__ int member_of(const StreamArgs& a, int nt) {
-  int m = 0;
-#pragma unroll
-  for (int i = 1; i < kMaxGroup; ++i)
-    if (i < a.n_members && nt >= a.mem[i].tile_begin) m = i;
-  return m;
-}
+// Optional timeline stamps for tuning (build with -DQERL_STREAM_TRACE): eight 100 MHz time stamps per wave
+// of the first 512 workgroups, read back with qerl_debug_read_trace().
+#ifdef QERL_STREAM_TRACE
+__device__ unsigned long long g_trace[512 * 8 * 8];
+#define QSTAMP(p) do { if (lane == 0 && blockIdx.x < 512) g_trace[((int)blockIdx.x * 8 + wave) * 8 + (p)] = wall_clock64(); } while (0)
+#if QERL_STREAM_TRACE == 2   // start-up detail instead of the per-unit view
+#define QTRACE(p) do { } while (0)
+#define QSTART(p) QSTAMP(p)
+#else
+#define QTRACE(p) QSTAMP(p)
+#define QSTART(p) do { } while (0)
+#endif
+#else
+#define QTRACE(p) do { } while (0)
+#define QSTART(p) do { } while (0)
+#endif
 
 // ---- producers: t[tok][j] = sum_k x[tok,k] * Astack[j,k] for the stacked A of all members ----------
 template <int MR>
@@ -81,6 +89,7 @@ __device__ __forceinline__ void stream_producer(const StreamArgs& a, float* red,
   const int n32 = lane & 31, kg = lane >> 5;
   const int P = a.n_producers, n_at = (a.r_total + 31) >> 5, n_pairs = (n_at + 1) >> 1;
   constexpr int kElems = 2 * MR * 64;
+  QTRACE(0);
   for (int pair = 0; pair < n_pairs; ++pair) {
     f32x16 pacc[2];
 #pragma unroll
@@ -116,6 +125,7 @@ __device__ __forceinline__ void stream_producer(const StreamArgs& a, float* red,
                                                           __builtin_bit_cast(bf16x8, af[1][j]), pacc[1], 0, 0, 0);
       }
     }
+    QTRACE(1);
 #pragma unroll
     for (int at = 0; at < 2; ++at)
 #pragma unroll
@@ -130,12 +140,14 @@ __device__ __forceinline__ void stream_producer(const StreamArgs& a, float* red,
     __syncthreads();   // red is reused by the next pair
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's partial stores have completed
+  QTRACE(2);
   __syncthreads();
   if (tid == 0) {
     const uint32_t old = __hip_atomic_fetch_add(a.lora_ctl + kCtlArrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     *s_flag = (old == (uint32_t)(P - 1));
   }
   __syncthreads();
+  QTRACE(3);
   if (!*s_flag) return;
   // last producer to arrive: add the P partial tiles in producer order and publish t
   for (int pe = tid; pe < n_pairs * kElems; pe += kStreamWaves * 64) {
@@ -148,6 +160,7 @@ __device__ __forceinline__ void stream_producer(const StreamArgs& a, float* red,
                          __HIP_MEMORY_SCOPE_AGENT);
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);   // t is written before the ready word
+  QTRACE(5);
   __syncthreads();
   if (tid == 0) {
     __hip_atomic_store(a.lora_ctl + kCtlArrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -156,15 +169,6 @@ __device__ __forceinline__ void stream_producer(const StreamArgs& a, float* red,
 }
 
 struct StreamTile { u32x4 c0, c1; u32x2 sc; };
-
-// Optional timeline stamps for tuning (build with -DQERL_STREAM_TRACE): eight 100 MHz time stamps per wave
-// of the first 512 workgroups, read back with qerl_debug_read_trace().
-#ifdef QERL_STREAM_TRACE
-__device__ unsigned long long g_trace[512 * 8 * 8];
-#define QTRACE(p) do { if (lane == 0 && blockIdx.x < 512) g_trace[((int)blockIdx.x * 8 + wave) * 8 + (p)] = wall_clock64(); } while (0)
-#else
-#define QTRACE(p) do { } while (0)
-#endif
 
 constexpr int kLoraSteps = 4;               // 16-wide j steps of the up-projection (r <= 64)
 constexpr int kMaxPending = 4;              // units an epilogue wave can park while t is not ready
@@ -199,20 +203,23 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
   extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
   __shared__ int s_flag;
   float* red = reinterpret_cast<float*>(smem + a.red_off);
+  // grid: x = producers, then the consumers of one K-range; y = K-range.  Producers exist in range 0 only.
   if ((int)blockIdx.x < a.n_producers) {
-    stream_producer<MR>(a, reinterpret_cast<float*>(smem), &s_flag);
+    if (blockIdx.y == 0) stream_producer<MR>(a, reinterpret_cast<float*>(smem), &s_flag);
     return;
   }
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps everything derived from it in SGPRs
   const int n32 = lane & 31, kg = lane >> 5;
   QTRACE(0);
-  const int cid = (int)blockIdx.x - a.n_producers;
-  const int range = cid % a.Sk, ci = cid / a.Sk, stride_u = a.n_consumers / a.Sk;
-  const int n_units = ci < a.total_tiles ? (a.total_tiles - ci + stride_u - 1) / stride_u : 0;
-  // K-range of this workgroup, in K-tiles
-  const int kr_len = (a.k_tiles + a.Sk - 1) / a.Sk;
+  QSTART(0);
+  // units ci, ci + stride_u, ... of K-range `range` are this workgroup's
+  const int range = (int)blockIdx.y, ci = (int)blockIdx.x - a.n_producers, stride_u = a.per_range;
+  const int n_units = a.units_base + (ci < a.units_rem ? 1 : 0);
+  const int kr_len = a.kr_len;            // K-tiles per range
   const int kr0 = range * kr_len, kr1 = (kr0 + kr_len < a.k_tiles) ? kr0 + kr_len : a.k_tiles;
+  // unused entries of the member table start at INT_MAX
+  auto member_index = [&](int nt) { return (nt >= a.tb1 ? 1 : 0) + (nt >= a.tb2 ? 1 : 0) + (nt >= a.tb3 ? 1 : 0); };
 
   // ---- staging of the x slice of this K-range into LDS, all eight waves: thread -> 16-byte chunk column,
   // all tokens of a column loaded before any is stored
@@ -241,10 +248,13 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
     xload(ch0 + tid, xv);
     xstore(ch0 + tid, xv);
   }
+  QSTART(1);
   xload(ch0 + tid, xv);
+  QSTART(2);
   // Every wave of this CU has queued its x loads before any weight load is queued behind them: without
   // this, x for the last waves would arrive after the whole first ring of all waves.
   __builtin_amdgcn_s_barrier();
+  QSTART(3);
 
   if (wave < kMainWaves) {
     // ---- main wave: my K-tiles of every unit
@@ -255,24 +265,38 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
     const bool have = kt0 < kt1;
     StreamTile ring[D];
     int lu = 0, lk = kt0;                 // load cursor (unit, K-tile)
-    // Every call issues exactly three loads, also past the end of this wave's sequence (then from the
-    // first tile of the group, a cache hit that is never used): with a fixed number of loads in flight
-    // the wait before a slot is consumed covers that slot only, not the whole ring.
-    auto issue = [&](StreamTile& t) {
+    // Address of the load cursor's unit (its K-tile 0), looked up once per unit, not per tile.  Past the end
+    // of this wave's sequence the cursor parks on the first tile of the group: every call of issue() still
+    // issues exactly three loads (cache hits that are never used), so that with a fixed number of loads in
+    // flight the wait before a slot is consumed covers that slot only, not the whole ring.
+    const uint8_t* ubase;
+    int kmul;
+    auto set_unit = [&]() {
       const bool live = have && lu < n_units;
       const int nt = live ? ci + lu * stride_u : 0;
-      const int mi = member_of(a, nt);
-      const int64_t tile = live ? (int64_t)(nt - a.mem[mi].tile_begin) * a.k_tiles + lk : 0;
-      const uint8_t* base = a.mem[mi].packed + tile * kPackTileBytes;
+      int tb = 0;
+      const uint8_t* mp = a.mp0;
+      if (nt >= a.tb1) { tb = a.tb1; mp = a.mp1; }
+      if (nt >= a.tb2) { tb = a.tb2; mp = a.mp2; }
+      if (nt >= a.tb3) { tb = a.tb3; mp = a.mp3; }
+      ubase = mp + (live ? (int64_t)(nt - tb) * a.k_tiles * kPackTileBytes : 0);
+      kmul = live ? kPackTileBytes : 0;
+    };
+    set_unit();
+    auto issue = [&](StreamTile& t) {
+      const uint8_t* base = ubase + (int64_t)lk * kmul;
       t.c0 = *reinterpret_cast<const u32x4*>(base + lane * 16);
       t.c1 = *reinterpret_cast<const u32x4*>(base + 1024 + lane * 16);
       t.sc = *reinterpret_cast<const u32x2*>(base + 2048 + n32 * 8);
-      if (live && ++lk == kt1) { lk = kt0; ++lu; }
+      if (++lk == kt1) { lk = kt0; ++lu; set_unit(); }
     };
 #pragma unroll
     for (int d = 0; d < D; ++d) issue(ring[d]);
+    QSTART(4);
     xstore(ch0 + tid, xv);               // waits for x only: the ring stays in flight
+    QSTART(5);
     __syncthreads();
+    QSTART(6);
     QTRACE(1);
 
     const int xrow = n32 < a.M ? n32 : a.M;          // tokens >= M read the zero row
@@ -367,6 +391,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     t_ready = true;
+    QTRACE(6);
   };
   // lo = t_mi B^T for the 32 rows whose B fragments are in bq
   auto lora_up = [&](int mi, const u32x4 (&bq)[kLoraSteps], f32x16& lo) {
@@ -428,7 +453,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
   auto flush_pending = [&]() {
     for (int p = 0; p < n_pend; ++p) {
       const int nt = ci + (first_pend + p) * stride_u;
-      const int mi = member_of(a, nt);
+      const int mi = member_index(nt);
       u32x4 bq[kLoraSteps];
 #pragma unroll
       for (int s = 0; s < kLoraSteps; ++s) bq[s] = pend_b[(p * kLoraSteps + s) * 64 + lane];
@@ -444,7 +469,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
 
   for (int u = 0; u < n_units; ++u) {
     const int nt = ci + u * stride_u;
-    const int mi = member_of(a, nt);
+    const int mi = member_index(nt);
     const StreamMember& mem = a.mem[mi];
     const bool needs_lora = lora_range && mem.r > 0;
     u32x4 bq[kLoraSteps];
@@ -478,6 +503,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
       if (!t_ready && ready_word != 0u) {
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
         t_ready = true;
+        QTRACE(6);
       }
       if (!t_ready && n_pend < kMaxPending) {
         // t is still on its way: park this unit (base sums and B fragments) and go on streaming
@@ -513,7 +539,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
       }
     }
     const uint32_t old = __hip_atomic_fetch_add(a.lora_ctl + kCtlDone, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (old == (uint32_t)(a.n_consumers / a.Sk - 1)) {
+    if (old == (uint32_t)(a.per_range - 1)) {
       __hip_atomic_store(a.lora_ctl + kCtlReady, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(a.lora_ctl + kCtlDone, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -526,9 +552,10 @@ static int g_force_consumers = 0;
 
 // LDS layout for M tokens (+ zero row) of a K-range of kr_len K-tiles: x slice, reduction buffers, and --
 // with LoRA -- the parking area of the epilogue wave.  Producers use the start of the same allocation.
-struct StreamLds { int xs_stride, red_off, pend_off; size_t total; };
+struct StreamLds { int kr_len, xs_stride, red_off, pend_off; size_t total; };
 static StreamLds stream_lds(int M, int kr_len, int MR, bool lora) {
   StreamLds l{};
+  l.kr_len = kr_len;
   l.xs_stride = kr_len * 256 + 16;   // rows 16 bytes apart in bank space: token rows and the zero row read conflict-free
   const size_t xs = (size_t)(M + 1) * (size_t)l.xs_stride;
   l.red_off = (int)((xs + 255) & ~(size_t)255);
@@ -559,11 +586,14 @@ int plan_stream(StreamArgs& a, size_t* lds_bytes, int* MR_out) {
   const StreamLds l = stream_lds(a.M, (int)ceil_div(a.k_tiles, Sk), MR, lora);
   *lds_bytes = l.total;
   a.Sk = Sk; a.xs_stride = l.xs_stride; a.red_off = l.red_off; a.pend_off = l.pend_off;
-  int64_t per_range = 256 / Sk;        // one workgroup per CU: the kernel's register use allows no second one
+  // One workgroup per CU (the kernel's register use allows no second one), producers included: a
+  // workgroup that had to wait for a free CU would start when the others are half done.
+  int64_t per_range = (256 - a.n_producers) / Sk;
   if (per_range > a.total_tiles) per_range = a.total_tiles;
   if (per_range < 1) per_range = 1;
   if (g_force_consumers > 0) per_range = g_force_consumers / Sk > 0 ? g_force_consumers / Sk : 1;
-  a.n_consumers = (int)per_range * Sk;
+  a.per_range = (int)per_range; a.kr_len = l.kr_len;
+  a.units_base = a.total_tiles / a.per_range; a.units_rem = a.total_tiles % a.per_range;
   return QERL_OK;
 }
 
@@ -576,7 +606,7 @@ static int launch_stream_t(const StreamArgs& a, size_t lds, hipStream_t st) {
       return launch_status();
     attr_set = true;
   }
-  stream_kernel<MR, D><<<dim3(a.n_producers + a.n_consumers), dim3(kStreamWaves * 64), lds, st>>>(a);
+  stream_kernel<MR, D><<<dim3(a.n_producers + a.per_range, a.Sk), dim3(kStreamWaves * 64), lds, st>>>(a);
   return launch_status();
 }
 
@@ -589,7 +619,11 @@ int launch_stream(const StreamArgs& a, size_t lds, int MR, hipStream_t st) {
     if (m.r > 0 && (!m.A || !m.B || m.r > 64 || m.r % 8 != 0)) return QERL_ERR_SHAPE;
   }
   if (a.r_total > 0 && (a.n_producers < 1 || a.n_producers > 16 || !a.t || !a.lora_ctl || !a.tpart)) return QERL_ERR_NULL;
-  if (a.M < 1 || a.M > 16 || a.K < 16 || a.k_tiles < 1 || a.Sk < 1 || a.n_consumers < a.Sk || a.n_consumers % a.Sk != 0 ||
+  if (a.mp0 != a.mem[0].packed || a.mp1 != a.mem[1].packed || a.mp2 != a.mem[2].packed || a.mp3 != a.mem[3].packed ||
+      a.tb1 != a.mem[1].tile_begin || a.tb2 != a.mem[2].tile_begin || a.tb3 != a.mem[3].tile_begin)
+    return QERL_ERR_SHAPE;
+  if (a.M < 1 || a.M > 16 || a.K < 16 || a.k_tiles < 1 || a.Sk < 1 || a.per_range < 1 || a.kr_len < 1 || (int64_t)a.kr_len * a.Sk < a.k_tiles ||
+      a.units_base * a.per_range + a.units_rem != a.total_tiles ||
       a.total_tiles < 1 || lds > kStreamLdsMax || a.red_off <= 0 || a.pend_off < a.red_off)
     return QERL_ERR_SHAPE;
   if (MR == 4) return launch_stream_t<4, 6>(a, lds, st);

@@ -14,7 +14,7 @@ void set_last_hip_error(int e) { g_last_hip_error = e; }
 //   [partial_off, ...)  split-K partial tiles, fp32
 struct WorkspaceLayout { size_t ctrl_bytes, n_main_ctr, n_down_ctr, t_off, partial_off, total; };
 
-constexpr size_t kDecodeTpartWords = 16 * 3 * 2 * 8 * 64;   // producer partial sums of the fused LoRA down-projection (<= 16 producers, 3 tile pairs)
+constexpr size_t kDecodeTpartWords = 16 * 16 * 256;   // producer partial sums of the fused LoRA down-projection: <= 16 producers x 16 tokens x stacked rank <= 256
 constexpr size_t kMaxCounterTiles = 16384;   // rows / 16 the control region can serve
 
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }

@@ -33,7 +33,8 @@ namespace qerl {
 
 constexpr int kStreamWaves = 8;             // 7 main + 1 epilogue
 constexpr int kMainWaves = kStreamWaves - 1;
-constexpr int kCtlArrive = 0, kCtlReady = 1, kCtlDone = 2;
+constexpr int kCtlArrive = 0, kCtlDone = 2;   // producers that have stored their partial t; consumers that have read it
+constexpr int kTpartTokens = 16;              // token rows per producer in the partial-t area
 constexpr uint32_t kStreamSpinLimit = 1u << 14;
 
 __device__ __forceinline__ bf16x8 stream_e2m1x8(uint32_t codes) {
@@ -83,7 +84,7 @@ __device__ unsigned long long g_trace[512 * 8 * 8];
 
 // ---- producers: t[tok][j] = sum_k x[tok,k] * Astack[j,k] for the stacked A of all members ----------
 template <int MR>
-__device__ __forceinline__ void stream_producer(const StreamArgs& a, float* red, int* s_flag) {
+__device__ __forceinline__ void stream_producer(const StreamArgs& a, float* red) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps everything derived from it in SGPRs
   const int n32 = lane & 31, kg = lane >> 5;
@@ -97,18 +98,18 @@ __device__ __forceinline__ void stream_producer(const StreamArgs& a, float* red,
 #pragma unroll
       for (int i = 0; i < 16; ++i) pacc[at][i] = 0.f;
     // rows of the stacked A: member by member; row j of the stack lives in member mi at j - t_off
-    for (int64_t h = (int64_t)blockIdx.x * kStreamWaves + wave; h < 2 * (int64_t)a.k_tiles; h += (int64_t)P * kStreamWaves) {
-      u32x4 xa[4], af[2][4];
+    const int64_t h_step = (int64_t)P * kStreamWaves, h_end = 2 * (int64_t)a.k_tiles;
+    auto load_slice = [&](int64_t h, u32x4 (&xa)[4], u32x4 (&af)[2][4]) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int64_t k = h * 64 + 16 * j + 8 * kg;
         xa[j] = u32x4{0u, 0u, 0u, 0u};
-        if (n32 < a.M && k < a.K) xa[j] = *reinterpret_cast<const u32x4*>(a.x + (int64_t)n32 * a.ldx + k);
+        if (h < h_end && n32 < a.M && k < a.K) xa[j] = *reinterpret_cast<const u32x4*>(a.x + (int64_t)n32 * a.ldx + k);
 #pragma unroll
         for (int at = 0; at < 2; ++at) {
           const int row = (2 * pair + at) * 32 + n32;     // row of the stacked A
           af[at][j] = u32x4{0u, 0u, 0u, 0u};
-          if (row < a.r_total && k < a.K) {
+          if (h < h_end && row < a.r_total && k < a.K) {
             int mi = 0;
 #pragma unroll
             for (int i = 1; i < kMaxGroup; ++i)
@@ -117,6 +118,8 @@ __device__ __forceinline__ void stream_producer(const StreamArgs& a, float* red,
           }
         }
       }
+    };
+    auto mul_slice = [&](const u32x4 (&xa)[4], const u32x4 (&af)[2][4]) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         pacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[j]),
@@ -124,6 +127,14 @@ __device__ __forceinline__ void stream_producer(const StreamArgs& a, float* red,
         pacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[j]),
                                                           __builtin_bit_cast(bf16x8, af[1][j]), pacc[1], 0, 0, 0);
       }
+    };
+    // two K-slices per round, both in flight before either is multiplied (a slice past the end loads nothing)
+    for (int64_t h = (int64_t)blockIdx.x * kStreamWaves + wave; h < h_end; h += 2 * h_step) {
+      u32x4 xa0[4], af0[2][4], xa1[4], af1[2][4];
+      load_slice(h, xa0, af0);
+      load_slice(h + h_step, xa1, af1);
+      mul_slice(xa0, af0);
+      mul_slice(xa1, af1);
     }
     QTRACE(1);
 #pragma unroll
@@ -131,41 +142,25 @@ __device__ __forceinline__ void stream_producer(const StreamArgs& a, float* red,
 #pragma unroll
       for (int q = 0; q < MR; ++q) red[(wave * 2 + at) * MR * 64 + q * 64 + lane] = pacc[at][q];
     __syncthreads();
+    // this workgroup's partial of t, in [token][stacked rank] order (what the consumers' MFMA operand wants)
     for (int e = tid; e < kElems; e += kStreamWaves * 64) {
       float s = red[e];
       for (int w = 1; w < kStreamWaves; ++w) s += red[w * kElems + e];
-      __hip_atomic_store(a.tpart + ((int64_t)blockIdx.x * n_pairs + pair) * kElems + e, __float_as_uint(s),
-                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const int at = e / (MR * 64), q = (e / 64) % MR, l = e & 63;
+      const int tok = 8 * (q >> 2) + 4 * (l >> 5) + (q & 3), j = (2 * pair + at) * 32 + (l & 31);
+      if (tok < a.M && j < a.r_total)
+        __hip_atomic_store(a.tpart + ((int64_t)blockIdx.x * kTpartTokens + tok) * a.r_total + j, __float_as_uint(s),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();   // red is reused by the next pair
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's partial stores have completed
   QTRACE(2);
   __syncthreads();
-  if (tid == 0) {
-    const uint32_t old = __hip_atomic_fetch_add(a.lora_ctl + kCtlArrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    *s_flag = (old == (uint32_t)(P - 1));
-  }
-  __syncthreads();
+  // Consumers wait for all P arrivals and add the P partials themselves, in producer order: one
+  // memory round trip less than electing a producer to publish the sum.
+  if (tid == 0) __hip_atomic_fetch_add(a.lora_ctl + kCtlArrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   QTRACE(3);
-  if (!*s_flag) return;
-  // last producer to arrive: add the P partial tiles in producer order and publish t
-  for (int pe = tid; pe < n_pairs * kElems; pe += kStreamWaves * 64) {
-    const int pair = pe / kElems, e = pe - pair * kElems;
-    const float s = ordered_sum_sc1(a.tpart + (int64_t)pair * kElems + e, (int64_t)n_pairs * kElems, P);
-    const int at = e / (MR * 64), q = (e / 64) % MR, l = e & 63;
-    const int tok = 8 * (q >> 2) + 4 * (l >> 5) + (q & 3), j = (2 * pair + at) * 32 + (l & 31);
-    if (tok < a.M && j < a.r_total)
-      __hip_atomic_store(reinterpret_cast<uint32_t*>(a.t) + tok * a.r_total + j, __float_as_uint(s), __ATOMIC_RELAXED,
-                         __HIP_MEMORY_SCOPE_AGENT);
-  }
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // t is written before the ready word
-  QTRACE(5);
-  __syncthreads();
-  if (tid == 0) {
-    __hip_atomic_store(a.lora_ctl + kCtlArrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(a.lora_ctl + kCtlReady, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
 }
 
 struct StreamTile { u32x4 c0, c1; u32x2 sc; };
@@ -199,13 +194,12 @@ __device__ __forceinline__ void ordered_sum_tile(const uint32_t* p, int64_t stri
 template <int MR, int D>
 __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamArgs a) {
   // x slice [(M+1) rows][xs_stride bytes], red[2][7][MR][64] floats, parked units.  The alignment matters:
-  // the static s_flag is placed first, and 16-byte LDS accesses from a base of 4 run several times slower.
+  // 16-byte LDS accesses from a misaligned base run several times slower.
   extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
-  __shared__ int s_flag;
   float* red = reinterpret_cast<float*>(smem + a.red_off);
   // grid: x = producers, then the consumers of one K-range; y = K-range.  Producers exist in range 0 only.
   if ((int)blockIdx.x < a.n_producers) {
-    if (blockIdx.y == 0) stream_producer<MR>(a, reinterpret_cast<float*>(smem), &s_flag);
+    if (blockIdx.y == 0) stream_producer<MR>(a, reinterpret_cast<float*>(smem));
     return;
   }
   const int tid = threadIdx.x, lane = tid & 63;
@@ -315,13 +309,13 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
       }
     }
     // Ring slot d always holds tiles d, d + D, d + 2D, ... of this wave's sequence, so every slot is a fixed
-    // set of registers.  The body has no guard: past the end of the sequence it multiplies a dummy tile into
-    // accumulators that are never stored (the last unit has been handed over by then), which keeps the number
-    // of loads in flight the same on every path.
+    // set of registers.  Past the end of the sequence only the arithmetic is skipped: the refill still runs,
+    // which keeps the number of loads in flight the same on every path.
     const int n_seq = have ? n_units * (kt1 - kt0) : 0;
     for (int i0 = 0; i0 < n_seq; i0 += D) {
 #pragma unroll
       for (int d = 0; d < D; ++d) {
+        if (i0 + d < n_seq) {
         const StreamTile& t = ring[d];
         const unsigned char* xk = xbase + (ck - kr0) * 256;
         f32x16 tmp[2];
@@ -344,9 +338,10 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
         // asm pins the accumulators (and with them every use of the slot) above this point.
 #pragma unroll
         for (int q = 0; q < MR; ++q) asm volatile("" : "+v"(acc[q]));
+        }
         __builtin_amdgcn_sched_barrier(0);
         issue(ring[d]);                   // refill the slot in place (same registers), D tiles ahead
-        if (++ck == kt1) {
+        if (i0 + d < n_seq && ++ck == kt1) {
           if (cu < n_units) {             // unit finished: hand the partial tile to the epilogue wave
 #pragma unroll
             for (int q = 0; q < MR; ++q) {
@@ -366,6 +361,10 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
   }
 
   // ---- epilogue wave -----------------------------------------------------------------------------
+  // Two steps per unit, each written once: receive (barrier, add the seven partial tiles, park the sums and
+  // the unit's B fragments in LDS) and finalize (LoRA up-projection, K-range exchange, store).  Finalizing
+  // trails receiving by up to kMaxPending units, which is how the wave rides out the time until t is ready
+  // without holding up the streaming waves.
   xstore(ch0 + tid, xv);
   __syncthreads();
   QTRACE(1);
@@ -379,56 +378,118 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
   u32x4 th[kLoraSteps], tm[kLoraSteps], tl[kLoraSteps];
   int t_member = -1;                      // member whose split t is in th/tm/tl
   bool poisoned = false, t_ready = a.n_producers == 0;
-  int n_pend = 0, first_pend = 0;         // units [first_pend, first_pend + n_pend) are parked in LDS
   float* pend_base = reinterpret_cast<float*>(smem + a.pend_off);          // [kMaxPending][MR][64]
   u32x4* pend_b = reinterpret_cast<u32x4*>(smem + a.pend_off + kMaxPending * MR * 64 * 4);   // [kMaxPending][kLoraSteps][64]
+  int u_recv = 0, u_done = 0;             // units received / finalized so far
 
-  auto wait_t = [&]() {                   // bounded: a hand-over that never comes poisons the output
-    uint32_t spins = 0;
-    while (__hip_atomic_load(a.lora_ctl + kCtlReady, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
-      if (++spins > kStreamSpinLimit) { poisoned = true; break; }
-      __builtin_amdgcn_s_sleep(32);
+  while (u_done < n_units) {
+    if (u_recv < n_units && u_recv - u_done < kMaxPending) {
+      // ---- receive unit u_recv
+      const int u = u_recv, slot = u % kMaxPending;
+      const int nt = ci + u * stride_u;
+      const int mi = member_index(nt);
+      const StreamMember& mem = a.mem[mi];
+      if (lora_range && mem.r > 0) {
+        // B rows of this unit first: their latency overlaps the wait at the barrier
+        int64_t brow = (int64_t)(nt - mem.tile_begin) * 32 + n32;
+        brow = brow < mem.N ? brow : mem.N - 1;
+#pragma unroll
+        for (int s = 0; s < kLoraSteps; ++s) {
+          const int j0 = 16 * s + 8 * kg;
+          u32x4 bq = u32x4{0u, 0u, 0u, 0u};
+          if (j0 < mem.r) bq = *reinterpret_cast<const u32x4*>(mem.B + brow * mem.r + j0);
+          pend_b[(slot * kLoraSteps + s) * 64 + lane] = bq;
+        }
+      }
+      QTRACE(2 + (u < 4 ? u : 4));
+      __syncthreads();                    // the seven partial tiles of unit u are in red[u & 1]
+      float S32 = S32m[0];
+#pragma unroll
+      for (int i = 1; i < kMaxGroup; ++i) S32 = mi == i ? S32m[i] : S32;
+#pragma unroll
+      for (int q = 0; q < MR; ++q) {
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < kMainWaves; ++w) sum += red[(((u & 1) * kMainWaves + w) * MR + q) * 64 + lane];
+        pend_base[(slot * MR + q) * 64 + lane] = sum * S32;
+      }
+      ++u_recv;
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    t_ready = true;
-    QTRACE(6);
-  };
-  // lo = t_mi B^T for the 32 rows whose B fragments are in bq
-  auto lora_up = [&](int mi, const u32x4 (&bq)[kLoraSteps], f32x16& lo) {
+    // ---- finalize the oldest received unit, if it can be
+    const int u = u_done, slot = u % kMaxPending;
+    const int nt = ci + u * stride_u;
+    const int mi = member_index(nt);
     const StreamMember& mem = a.mem[mi];
-    if (t_member != mi) {
-      // t was written through to memory before the ready word went up and no cache can hold an older
-      // copy (caches are invalidated at kernel start, nobody reads t earlier): ordinary loads suffice.
+    const bool needs_lora = lora_range && mem.r > 0;
+    if (needs_lora && !t_ready) {
+      const bool can_receive_more = u_recv < n_units && u_recv - u_done < kMaxPending;
+      uint32_t spins = 0;
+      for (;;) {
+        if (__hip_atomic_load(a.lora_ctl + kCtlArrive, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)a.n_producers) {
+          t_ready = true;
+          break;
+        }
+        if (can_receive_more) break;      // one look per unit while there is streaming to attend to
+        if (++spins > kStreamSpinLimit) { poisoned = true; t_ready = true; break; }   // bounded: poison the output
+        __builtin_amdgcn_s_sleep(32);
+      }
+      if (!t_ready) continue;
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+      QTRACE(6);
+    }
+    float out[MR];
+#pragma unroll
+    for (int q = 0; q < MR; ++q) out[q] = pend_base[(slot * MR + q) * 64 + lane];
+    if (needs_lora) {
+      if (t_member != mi) {
+        // The partials were written through to memory before their producers were counted, and no cache can
+        // hold an older copy (caches are invalidated at kernel start, nobody reads them earlier): ordinary loads
+        // suffice.  Added in producer order, so the sum is the same in every workgroup and on every call.
+#pragma unroll
+        for (int s = 0; s < kLoraSteps; ++s) {
+          const int j0 = 16 * s + 8 * kg;
+          float tv[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) tv[i] = 0.f;
+          if (n32 < a.M && j0 < mem.r) {
+            const float* tp = reinterpret_cast<const float*>(a.tpart) + (int64_t)n32 * a.r_total + mem.t_off + j0;
+            const int64_t pstride = (int64_t)kTpartTokens * a.r_total;
+            for (int p0 = 0; p0 < a.n_producers; p0 += 8) {   // eight producers' loads in flight at a time
+              f32x4 v[8][2];
+#pragma unroll
+              for (int b = 0; b < 8; ++b) {
+                v[b][0] = f32x4{0.f, 0.f, 0.f, 0.f}; v[b][1] = v[b][0];
+                if (p0 + b < a.n_producers) {
+                  v[b][0] = *reinterpret_cast<const f32x4*>(tp + (p0 + b) * pstride);
+                  v[b][1] = *reinterpret_cast<const f32x4*>(tp + (p0 + b) * pstride + 4);
+                }
+              }
+#pragma unroll
+              for (int b = 0; b < 8; ++b)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) { tv[i] += v[b][0][i]; tv[4 + i] += v[b][1][i]; }
+            }
+            if (poisoned) tv[0] = __uint_as_float(0x7fc00000u);   // the hand-over timed out: make it visible
+          }
+          stream_split3(tv, th[s], tm[s], tl[s]);
+        }
+        t_member = mi;
+      }
+      f32x16 lo;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) lo[i] = 0.f;
 #pragma unroll
       for (int s = 0; s < kLoraSteps; ++s) {
-        const int j0 = 16 * s + 8 * kg;
-        float tv[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) tv[i] = 0.f;
-        if (n32 < a.M && j0 < mem.r) {
-          const float* tp = a.t + (int64_t)n32 * a.r_total + mem.t_off + j0;
-          const f32x4 t0 = *reinterpret_cast<const f32x4*>(tp), t1 = *reinterpret_cast<const f32x4*>(tp + 4);
-          tv[0] = t0[0]; tv[1] = t0[1]; tv[2] = t0[2]; tv[3] = t0[3];
-          tv[4] = t1[0]; tv[5] = t1[1]; tv[6] = t1[2]; tv[7] = t1[3];
-          if (poisoned) tv[0] = __uint_as_float(0x7fc00000u);   // the hand-over timed out: make it visible
-        }
-        stream_split3(tv, th[s], tm[s], tl[s]);
+        const bf16x8 bf = __builtin_bit_cast(bf16x8, pend_b[(slot * kLoraSteps + s) * 64 + lane]);
+        lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, th[s]), bf, lo, 0, 0, 0);
+        lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tm[s]), bf, lo, 0, 0, 0);
+        lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tl[s]), bf, lo, 0, 0, 0);
       }
-      t_member = mi;
-    }
 #pragma unroll
-    for (int i = 0; i < 16; ++i) lo[i] = 0.f;
-#pragma unroll
-    for (int s = 0; s < kLoraSteps; ++s) {
-      const bf16x8 bf = __builtin_bit_cast(bf16x8, bq[s]);
-      lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, th[s]), bf, lo, 0, 0, 0);
-      lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tm[s]), bf, lo, 0, 0, 0);
-      lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tl[s]), bf, lo, 0, 0, 0);
+      for (int q = 0; q < MR; ++q) out[q] += lo[q] * mem.lora_scale;
     }
-  };
-  // out = this range's share of tile nt: exchange across K-ranges if there are several, then store
-  auto finish = [&](int nt, int mi, float (&out)[MR]) {
-    const StreamMember& mem = a.mem[mi];
+    ++u_done;
+    // out = this range's share of tile nt: exchange across K-ranges if there are several, then store
     if (a.Sk > 1) {
       uint32_t* mine = a.partial + ((int64_t)range * a.total_tiles + nt) * (MR * 64) + lane;
 #pragma unroll
@@ -439,7 +500,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
       if (lane == 0)
         old = __hip_atomic_fetch_add(a.counters + nt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       old = __builtin_amdgcn_readfirstlane(old);
-      if (old != (uint32_t)(a.Sk - 1)) return;
+      if (old != (uint32_t)(a.Sk - 1)) continue;
       ordered_sum_tile<MR>(a.partial + (int64_t)nt * (MR * 64) + lane, (int64_t)a.total_tiles * (MR * 64), a.Sk, out);
       if (lane == 0) __hip_atomic_store(a.counters + nt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -449,98 +510,21 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
       const int tok = 8 * (q >> 2) + 4 * kg + (q & 3);
       if (tok < a.M && n < mem.N) mem.y[(int64_t)tok * mem.ldy + n] = (uint16_t)f32_to_bf16_bits(out[q]);
     }
-  };
-  auto flush_pending = [&]() {
-    for (int p = 0; p < n_pend; ++p) {
-      const int nt = ci + (first_pend + p) * stride_u;
-      const int mi = member_index(nt);
-      u32x4 bq[kLoraSteps];
-#pragma unroll
-      for (int s = 0; s < kLoraSteps; ++s) bq[s] = pend_b[(p * kLoraSteps + s) * 64 + lane];
-      f32x16 lo;
-      lora_up(mi, bq, lo);
-      float out[MR];
-#pragma unroll
-      for (int q = 0; q < MR; ++q) out[q] = pend_base[(p * MR + q) * 64 + lane] + lo[q] * a.mem[mi].lora_scale;
-      finish(nt, mi, out);
-    }
-    n_pend = 0;
-  };
-
-  for (int u = 0; u < n_units; ++u) {
-    const int nt = ci + u * stride_u;
-    const int mi = member_index(nt);
-    const StreamMember& mem = a.mem[mi];
-    const bool needs_lora = lora_range && mem.r > 0;
-    u32x4 bq[kLoraSteps];
-    uint32_t ready_word = 1u;
-    if (needs_lora) {
-      // B rows of this unit and the ready word first: their latency overlaps the wait at the barrier
-      int64_t brow = (int64_t)(nt - mem.tile_begin) * 32 + n32;
-      brow = brow < mem.N ? brow : mem.N - 1;
-#pragma unroll
-      for (int s = 0; s < kLoraSteps; ++s) {
-        const int j0 = 16 * s + 8 * kg;
-        bq[s] = u32x4{0u, 0u, 0u, 0u};
-        if (j0 < mem.r) bq[s] = *reinterpret_cast<const u32x4*>(mem.B + brow * mem.r + j0);
-      }
-      if (!t_ready) ready_word = __hip_atomic_load(a.lora_ctl + kCtlReady, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    QTRACE(2 + (u < 4 ? u : 4));
-    __syncthreads();                      // the seven partial tiles of unit u are in red[u & 1]
-    float S32 = S32m[0];
-#pragma unroll
-    for (int i = 1; i < kMaxGroup; ++i) S32 = mi == i ? S32m[i] : S32;
-    float out[MR];
-#pragma unroll
-    for (int q = 0; q < MR; ++q) {
-      float s = 0.f;
-#pragma unroll
-      for (int w = 0; w < kMainWaves; ++w) s += red[(((u & 1) * kMainWaves + w) * MR + q) * 64 + lane];
-      out[q] = s * S32;
-    }
-    if (needs_lora) {
-      if (!t_ready && ready_word != 0u) {
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-        t_ready = true;
-        QTRACE(6);
-      }
-      if (!t_ready && n_pend < kMaxPending) {
-        // t is still on its way: park this unit (base sums and B fragments) and go on streaming
-        if (n_pend == 0) first_pend = u;
-#pragma unroll
-        for (int q = 0; q < MR; ++q) pend_base[(n_pend * MR + q) * 64 + lane] = out[q];
-#pragma unroll
-        for (int s = 0; s < kLoraSteps; ++s) pend_b[(n_pend * kLoraSteps + s) * 64 + lane] = bq[s];
-        ++n_pend;
-        continue;
-      }
-      if (!t_ready) wait_t();
-      flush_pending();
-      f32x16 lo;
-      lora_up(mi, bq, lo);
-#pragma unroll
-      for (int q = 0; q < MR; ++q) out[q] += lo[q] * mem.lora_scale;
-    }
-    finish(nt, mi, out);
-  }
-  if (n_pend > 0) {
-    if (!t_ready) wait_t();
-    flush_pending();
   }
   QTRACE(7);
-  // every first-range workgroup reports in once t is final; the last one re-arms the control words
+  // every first-range workgroup reports in once all producers have been counted; the last one re-arms the
+  // control words
   if (a.n_producers > 0 && range == 0 && lane == 0) {
-    if (!t_ready) {   // a workgroup without LoRA units still has to count, after t is final
+    if (!t_ready) {   // a workgroup without LoRA units still has to count, after the hand-over is complete
       uint32_t spins = 0;
-      while (__hip_atomic_load(a.lora_ctl + kCtlReady, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+      while (__hip_atomic_load(a.lora_ctl + kCtlArrive, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != (uint32_t)a.n_producers) {
         if (++spins > kStreamSpinLimit) break;
         __builtin_amdgcn_s_sleep(32);
       }
     }
     const uint32_t old = __hip_atomic_fetch_add(a.lora_ctl + kCtlDone, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (old == (uint32_t)(a.per_range - 1)) {
-      __hip_atomic_store(a.lora_ctl + kCtlReady, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(a.lora_ctl + kCtlArrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(a.lora_ctl + kCtlDone, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
@@ -561,7 +545,7 @@ static StreamLds stream_lds(int M, int kr_len, int MR, bool lora) {
   l.red_off = (int)((xs + 255) & ~(size_t)255);
   const size_t red_consumer = 2 * (size_t)kMainWaves * MR * 64 * sizeof(float);
   l.pend_off = l.red_off + (int)red_consumer;
-  const size_t pend = lora ? (size_t)kMaxPending * (MR * 64 * sizeof(float) + kLoraSteps * 64 * 16) : 0;
+  const size_t pend = (size_t)kMaxPending * (MR * 64 * sizeof(float) + (lora ? kLoraSteps * 64 * 16 : 0));   // sums always, B fragments with LoRA
   const size_t red_producer = (size_t)kStreamWaves * 2 * MR * 64 * sizeof(float);
   l.total = l.pend_off + pend;
   if (l.total < red_producer) l.total = red_producer;
@@ -581,8 +565,8 @@ int plan_stream(StreamArgs& a, size_t* lds_bytes, int* MR_out) {
     if (stream_lds(a.M, (int)ceil_div(a.k_tiles, Sk), MR, lora).total <= lds_cap) break;
     if (Sk >= a.k_tiles) return QERL_ERR_SHAPE;
   }
-  // small problems: more K-ranges so that every CU has a unit
-  while ((int64_t)a.total_tiles * Sk < 200 && ceil_div(a.k_tiles, Sk * 2) >= 2 * kMainWaves && Sk < 8) Sk *= 2;
+  // No further split for small problems: a second K-range halves the streaming time of a unit, but the
+  // exchange of partial tiles costs three dependent memory round trips at the end, which is more.
   const StreamLds l = stream_lds(a.M, (int)ceil_div(a.k_tiles, Sk), MR, lora);
   *lds_bytes = l.total;
   a.Sk = Sk; a.xs_stride = l.xs_stride; a.red_off = l.red_off; a.pend_off = l.pend_off;
@@ -618,7 +602,8 @@ int launch_stream(const StreamArgs& a, size_t lds, int MR, hipStream_t st) {
     if (!m.packed || !m.tensor_scale || !m.y || m.N < 1 || m.n_tiles < 1) return QERL_ERR_NULL;
     if (m.r > 0 && (!m.A || !m.B || m.r > 64 || m.r % 8 != 0)) return QERL_ERR_SHAPE;
   }
-  if (a.r_total > 0 && (a.n_producers < 1 || a.n_producers > 16 || !a.t || !a.lora_ctl || !a.tpart)) return QERL_ERR_NULL;
+  if (a.r_total > 0 && (a.n_producers < 1 || a.n_producers > 16 || !a.lora_ctl || !a.tpart)) return QERL_ERR_NULL;
+  if (a.r_total < 0 || a.r_total > 256 || a.r_total % 8 != 0) return QERL_ERR_SHAPE;
   if (a.mp0 != a.mem[0].packed || a.mp1 != a.mem[1].packed || a.mp2 != a.mem[2].packed || a.mp3 != a.mem[3].packed ||
       a.tb1 != a.mem[1].tile_begin || a.tb2 != a.mem[2].tile_begin || a.tb3 != a.mem[3].tile_begin)
     return QERL_ERR_SHAPE;

@@ -2,7 +2,9 @@
 
 A step is one decode pass of batch M through the linear stack of every decoder
 layer of the model (default: Qwen2.5-7B shapes, 28 layers, M = 8, LoRA r = 32):
-per layer  aqn_rmsnorm -> q, k, v -> o -> aqn_rmsnorm -> gate, up -> down,
+per layer  aqn_rmsnorm -> {q, k, v} -> o -> aqn_rmsnorm -> {gate, up} -> down
+(linears in braces share their input and go out as one grouped call; at decode
+sizes the norm's launch also computes their LoRA down-projections),
 all on NVFP4 weights that are resident in HBM and distinct per layer, so one
 step streams 28 x 131 MB = 3.67 GB of packed weights and nothing is served
 from a cache that would not be there in a rollout.  Attention and SiLU*mul are
@@ -71,8 +73,12 @@ class Stack:
         self.act = torch.randn((M, inter), generator=gen, device="cuda").to(torch.bfloat16)
         self.xn = torch.empty((M, hidden), dtype=torch.bfloat16, device="cuda")
         self.out = {s.name: torch.empty((M, s.N), dtype=torch.bfloat16, device="cuda") for s in cfg["linears"]}
+        self.t = {s.name: torch.empty((8, M, cfg["r"]), dtype=torch.float32, device="cuda") for s in cfg["linears"]}
         self.lora_scale = cfg["alpha"] / cfg["r"]
-        need = max(qerl.nvfp4_lora_linear_workspace_bytes(M, s.N, s.K, cfg["r"]) for s in cfg["linears"])
+        by = {s.name: s for s in cfg["linears"]}
+        need = max([qerl.nvfp4_lora_linear_workspace_bytes(M, s.N, s.K, cfg["r"]) for s in cfg["linears"]]
+                   + [qerl.nvfp4_lora_linear_workspace_bytes(M, sum(by[n].N for n in g), by[g[0]].K, cfg["r"] * len(g))
+                      for g in (("q", "k", "v"), ("gate", "up"))])
         self.ws = qerl.Workspace(need)
         self.packed_bytes_per_layer = sum(s.packed_bytes for s in cfg["linears"])
         self.flops_per_layer = sum(2 * M * s.N * s.K for s in cfg["linears"])
@@ -82,16 +88,25 @@ class Stack:
         return qerl.nvfp4_lora_linear_packed(x, packed, A, B, self.lora_scale,
                                              workspace=self.ws, out=self.out[name])
 
+    def norm_group(self, layer, names, gain, noise):
+        """AQN RMSNorm of the hidden state, then the linears `names` that read it.  At decode sizes:
+        one launch for the norm together with the LoRA down-projections, one for the group."""
+        ws, As, Bs = zip(*(layer.lin[n] for n in names))
+        ts = None
+        if self.M <= 16:
+            _, ts = qerl.aqn_rmsnorm_lora_down(self.h, gain, noise, 1e-6, list(As), out=self.xn,
+                                               ts=[self.t[n] for n in names])
+        else:
+            qerl.aqn_rmsnorm(self.h, gain, noise, 1e-6, out=self.xn)
+        return qerl.nvfp4_lora_linear_packed_group(self.xn, list(ws), list(As), list(Bs),
+                                                   [self.lora_scale] * len(names), workspace=self.ws,
+                                                   outs=[self.out[n] for n in names], ts=ts)
+
     def step(self):
         for L in self.layers:
-            qerl.aqn_rmsnorm(self.h, L.gain_in, L.z_in, 1e-6, out=self.xn)
-            self.linear(L, "q", self.xn)
-            self.linear(L, "k", self.xn)
-            self.linear(L, "v", self.xn)
+            self.norm_group(L, ("q", "k", "v"), L.gain_in, L.z_in)
             self.linear(L, "o", self.attn)
-            qerl.aqn_rmsnorm(self.h, L.gain_post, L.z_post, 1e-6, out=self.xn)
-            self.linear(L, "gate", self.xn)
-            self.linear(L, "up", self.xn)
+            self.norm_group(L, ("gate", "up"), L.gain_post, L.z_post)
             self.linear(L, "down", self.act)
 
 
@@ -151,7 +166,7 @@ def dominant_kernel_roofline(stack: Stack, reps: int):
               "note": "one linear call per launch slot, back to back over the layers' distinct weights, "
                       "launch gaps included"}
     if stack.M <= 128:
-        kernel = "decode32_kernel" if stack.M <= 16 else "gemm32_kernel"
+        kernel = "stream_kernel" if stack.M <= 16 else "gemm32_kernel"
         bytes_per_launch = shp.packed_bytes
         achieved = bytes_per_launch / (ms * 1e-3) / 1e9
         return {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -142,14 +142,17 @@ QERL_API int nvfp4_lora_linear_packed(const void* x_bf16, int64_t M, int64_t K, 
 /* ---------------------------------------------------------------------------
  * nvfp4_lora_linear_packed_group -- up to 4 linears that read the same x (the
  * q/k/v or the gate/up projections of a block, which share one noisy RMSNorm
- * output: Section 3.3) in ONE launch.  Each member is computed exactly as
- * nvfp4_lora_linear_packed would compute it; only the launch is shared.
+ * output: Section 3.3) in ONE launch.  Each member is the same function of its
+ * inputs as in nvfp4_lora_linear_packed; the split of K over workgroups, and
+ * with it the fp32 summation order, may differ between the two calls (each is
+ * bit-reproducible from call to call).
  *   members: HOST array of n_members descriptors (read during the call only;
  *            the pointers inside are device pointers).
  *   workspace: as for nvfp4_lora_linear, sized with
  *            nvfp4_lora_linear_workspace_bytes(M, sum of N, K, sum of r).
  * Errors: as nvfp4_lora_linear_packed, plus n_members outside 1..4.
  */
+#define QERL_T_PARTS 8
 typedef struct {
   const void* packed;          /* nvfp4_prepack output for this member's [N, K] weight */
   const float* tensor_scale;
@@ -160,6 +163,11 @@ typedef struct {
   float lora_scale;
   void* y_bf16;                /* [M, ldy] out */
   int64_t ldy;
+  const float* t_f32;          /* x A^T of this member computed before the call, as aqn_rmsnorm_lora_down
+                                  writes it: QERL_T_PARTS partial sums over slices of K, fp32
+                                  [QERL_T_PARTS][M][r], 32-byte aligned (the kernel adds them in slice order);
+                                  or NULL: the call computes x A^T itself.  Used at M <= 16 only; larger M
+                                  recompute it. */
 } qerl_linear_desc;
 QERL_API int nvfp4_lora_linear_packed_group(const void* x_bf16, int64_t M, int64_t K, int64_t ldx,
                                             const qerl_linear_desc* members, int n_members,
@@ -181,6 +189,30 @@ QERL_API int qerl_workspace_init(void* workspace, size_t workspace_bytes, void* 
 QERL_API int aqn_rmsnorm(const void* x_bf16, int64_t M, int64_t H, int64_t ldx,
                 const void* gain_bf16, const float* noise_f32, float eps,
                 void* y_bf16, int64_t ldy, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * aqn_rmsnorm_lora_down -- the noisy RMSNorm of Eq. 10 and, in the same launch,
+ * the LoRA down-projections t_i = y A_i^T (Eq. 2) of up to 4 adapters that read
+ * its output (q/k/v or gate/up: Section 3.3).  At decode sizes the product x A^T
+ * is latency, not work; computing it where x is produced takes it off the
+ * critical path of the linear that follows (pass t_i as t_f32 of its member).
+ *   x [M, ldx] bf16, M <= 16; gain [H] bf16; noise [H] fp32 or NULL; y [M, ldy] bf16 out
+ *   A_bf16: HOST array of n_adapters device pointers, A_i [r_i, H] bf16, 16-byte aligned
+ *   r:      HOST array of ranks, each a multiple of 8, 8..64
+ *   t_f32:  HOST array of device pointers, t_i [QERL_T_PARTS][M][r_i] fp32 out, 32-byte
+ *           aligned: part p is the product over the p-th slice of H; their sum in
+ *           part order is t_i
+ * y is exactly what aqn_rmsnorm writes; t_i is the fp32 product of the ROUNDED y
+ * (what the linear kernels would compute themselves) in a fixed summation order.
+ * Errors: as aqn_rmsnorm, plus M > 16, H % 16 != 0, H > 8192, n_adapters outside
+ * 1..4, ranks not multiples of 8 in 8..64 or summing to more than 128
+ * (QERL_ERR_SHAPE); unaligned rows or pointers (QERL_ERR_ALIGN).
+ */
+QERL_API int aqn_rmsnorm_lora_down(const void* x_bf16, int64_t M, int64_t H, int64_t ldx,
+                                   const void* gain_bf16, const float* noise_f32, float eps,
+                                   void* y_bf16, int64_t ldy,
+                                   const void* const* A_bf16, const int64_t* r, float* const* t_f32,
+                                   int n_adapters, void* stream);
 
 /* Host.  Eq. 8: sigma(k) = s0 * (s1/s0)^((k-1)/(K-1)), k = 1..K; k = 0 -> 0
  * (Algorithm 1: stage 0 carries quantisation noise only).  NaN on bad stage. */

@@ -41,6 +41,8 @@ _SIGNATURES = {
     "qerl_workspace_init": (ctypes.c_int, [_c_p, _c_sz, _c_p]),
     "aqn_rmsnorm": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_p, ctypes.c_float,
                                    _c_p, _c_i64, _c_p]),
+    "aqn_rmsnorm_lora_down": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_p, ctypes.c_float,
+                                             _c_p, _c_i64, _c_p, _c_p, _c_p, ctypes.c_int, _c_p]),
     "aqn_sigma": (ctypes.c_double, [ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_double]),
 }
 
@@ -116,6 +118,38 @@ class Workspace:
     @property
     def nbytes(self) -> int:
         return self.buf.numel()
+
+
+def aqn_rmsnorm_lora_down(x, gain, noise, eps, As, out: Optional[torch.Tensor] = None, ts=None):
+    """RMSNorm as aqn_rmsnorm plus t_i = y A_i^T of the adapters As that read y, one launch (M <= 16).
+    Each t_i comes as T_PARTS partial sums over slices of H, fp32 [T_PARTS, M, r_i] (t_i.sum(0) is the
+    product).  Returns (y, [t_i]); pass the t_i as `ts` to nvfp4_lora_linear_packed_group."""
+    lib = load_library()
+    M, H, ldx = _rows(x, "x")
+    if gain.numel() != H or not gain.is_contiguous():
+        raise ValueError("gain must be contiguous [H]")
+    n_ptr = None
+    if noise is not None:
+        if noise.numel() != H or not noise.is_contiguous():
+            raise ValueError("noise must be contiguous [H]")
+        n_ptr = _dev(noise, torch.float32, "noise")
+    if out is None:
+        out = torch.empty((M, H), dtype=torch.bfloat16, device=x.device)
+    _, _, ldy = _rows(out, "out")
+    n = len(As)
+    for A in As:
+        if A.dim() != 2 or A.shape[1] != H or not A.is_contiguous():
+            raise ValueError("every A must be contiguous [r, H]")
+    if ts is None:
+        ts = [torch.empty((T_PARTS, M, A.shape[0]), dtype=torch.float32, device=x.device) for A in As]
+    a_arr = (ctypes.c_void_p * n)(*[_dev(A, torch.bfloat16, "A") for A in As])
+    r_arr = (ctypes.c_int64 * n)(*[A.shape[0] for A in As])
+    t_arr = (ctypes.c_void_p * n)(*[_dev(t, torch.float32, "t") for t in ts])
+    _check("aqn_rmsnorm_lora_down", lib.aqn_rmsnorm_lora_down(
+        _dev(x, torch.bfloat16, "x"), M, H, ldx, _dev(gain, torch.bfloat16, "gain"), n_ptr, float(eps),
+        _dev(out, torch.bfloat16, "out"), ldy, ctypes.cast(a_arr, _c_p), ctypes.cast(r_arr, _c_p),
+        ctypes.cast(t_arr, _c_p), n, _stream()))
+    return out, ts
 
 
 def aqn_sigma(stage: int, num_stages: int, sigma_start: float, sigma_end: float) -> float:
@@ -240,16 +274,20 @@ def nvfp4_lora_linear_packed(x, w: PackedWeight, A: Optional[torch.Tensor] = Non
     return out
 
 
+T_PARTS = 8   # QERL_T_PARTS in the header
+
+
 class _LinearDesc(ctypes.Structure):
     """Mirror of qerl_linear_desc in the header."""
     _fields_ = [("packed", _c_p), ("tensor_scale", _c_p), ("N", _c_i64), ("A", _c_p), ("B", _c_p),
-                ("r", _c_i64), ("lora_scale", ctypes.c_float), ("y", _c_p), ("ldy", _c_i64)]
+                ("r", _c_i64), ("lora_scale", ctypes.c_float), ("y", _c_p), ("ldy", _c_i64), ("t", _c_p)]
 
 
 def nvfp4_lora_linear_packed_group(x, weights, As=None, Bs=None, lora_scales=None,
-                                   workspace: Optional[Workspace] = None, outs=None):
+                                   workspace: Optional[Workspace] = None, outs=None, ts=None):
     """Several packed linears that read the same x (q/k/v, gate/up) in one launch.
-    weights: list of PackedWeight; As/Bs: lists of LoRA matrices (or None); returns the list of outputs."""
+    weights: list of PackedWeight; As/Bs: lists of LoRA matrices (or None); ts: optional list of
+    precomputed x A^T (fp32 [M, r], from aqn_rmsnorm_lora_down); returns the list of outputs."""
     lib = load_library()
     M, K, ldx = _rows(x, "x")
     n = len(weights)
@@ -274,9 +312,14 @@ def nvfp4_lora_linear_packed_group(x, weights, As=None, Bs=None, lora_scales=Non
         _, n_out, ldy = _rows(outs[i], "out")
         if outs[i].shape[0] != M or n_out != w.N:
             raise ValueError("out must be [M, N]")
+        t_ptr = None
+        if ts is not None and ts[i] is not None and r > 0:
+            if tuple(ts[i].shape) != (T_PARTS, M, r) or not ts[i].is_contiguous():
+                raise ValueError("t must be contiguous [T_PARTS, M, r] as aqn_rmsnorm_lora_down writes it")
+            t_ptr = _dev(ts[i], torch.float32, "t")
         descs[i] = _LinearDesc(_dev(w.packed, torch.uint8, "packed"),
                                _dev(w.tensor_scale, torch.float32, "tensor_scale"), w.N, a_ptr, b_ptr, r,
-                               float(lora_scales[i]), _dev(outs[i], torch.bfloat16, "out"), ldy)
+                               float(lora_scales[i]), _dev(outs[i], torch.bfloat16, "out"), ldy, t_ptr)
         n_sum += w.N
         r_sum += r
     if workspace is None:

@@ -192,22 +192,26 @@ static int stream_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, co
   StreamArgs a{};
   a.x = x; a.ldx = ldx; a.M = (int)M; a.K = K; a.k_tiles = (int)ceil_div(K, kPackTileK);
   a.n_members = n;
-  int tiles = 0, rt = 0;
+  int tiles = 0, rt = 0, any = 0;
   for (int i = 0; i < n; ++i) {
     StreamMember& m = a.mem[i];
     m.packed = (const uint8_t*)d[i].packed; m.tensor_scale = d[i].tensor_scale;
     m.A = (const uint16_t*)d[i].A_bf16; m.B = (const uint16_t*)d[i].B_bf16; m.y = (uint16_t*)d[i].y_bf16;
     m.ldy = d[i].ldy; m.N = d[i].N; m.n_tiles = (int)ceil_div(d[i].N, kPackTileRows); m.tile_begin = tiles;
-    m.r = (int)d[i].r; m.t_off = rt; m.lora_scale = d[i].lora_scale;
-    tiles += m.n_tiles; rt += m.r;
+    m.r = (int)d[i].r; m.lora_scale = d[i].lora_scale;
+    m.t_ext = m.r > 0 ? d[i].t_f32 : nullptr;
+    m.t_off = 0x7fffffff;                 // not part of the producers' stack ...
+    if (m.r > 0 && !m.t_ext) { m.t_off = rt; rt += m.r; }   // ... unless the launch has to compute its t
+    any |= m.r > 0;
+    tiles += m.n_tiles;
   }
   for (int i = n; i < kMaxGroup; ++i) {   // unused entries: never selected, but valid to read
     a.mem[i] = a.mem[0];
-    a.mem[i].tile_begin = 0x7fffffff; a.mem[i].n_tiles = 0; a.mem[i].r = 0;
+    a.mem[i].tile_begin = 0x7fffffff; a.mem[i].n_tiles = 0; a.mem[i].r = 0; a.mem[i].t_off = 0x7fffffff; a.mem[i].t_ext = nullptr;
   }
   a.tb1 = a.mem[1].tile_begin; a.tb2 = a.mem[2].tile_begin; a.tb3 = a.mem[3].tile_begin;
   a.mp0 = a.mem[0].packed; a.mp1 = a.mem[1].packed; a.mp2 = a.mem[2].packed; a.mp3 = a.mem[3].packed;
-  a.total_tiles = tiles; a.r_total = rt;
+  a.total_tiles = tiles; a.r_total = rt; a.any_lora = any;
   if (rt > 0) {
     int64_t np = ceil_div(2 * (int64_t)a.k_tiles, 8);   // one half K-tile per producer wave and tile pair
     a.n_producers = (int)(np < 1 ? 1 : (np > 16 ? 16 : np));
@@ -244,6 +248,7 @@ extern "C" int nvfp4_lora_linear_packed_group(const void* x, int64_t M, int64_t 
     if (d.N < 1) return QERL_ERR_SHAPE;
     n_sum += d.N; r_sum += d.r;
     stream_ok = stream_ok && (d.r == 0 || (d.r <= 64 && d.r % 8 == 0 && aligned(d.A_bf16, 16) && aligned(d.B_bf16, 16)));
+    if (d.r > 0 && d.t_f32 && !aligned(d.t_f32, 32)) return QERL_ERR_ALIGN;
   }
   if (M == 0) return QERL_OK;
   if (K == 0) return QERL_ERR_SHAPE;
@@ -310,7 +315,7 @@ extern "C" int nvfp4_lora_linear_packed(const void* x, int64_t M, int64_t K, int
   }
 
   if (g_use_stream && M <= 16 && (r == 0 || (r <= 64 && r % 8 == 0 && aligned(A, 16) && aligned(B, 16)))) {
-    qerl_linear_desc d{packed, tensor_scale, N, A, B, r, lora_scale, y, ldy};
+    qerl_linear_desc d{packed, tensor_scale, N, A, B, r, lora_scale, y, ldy, nullptr};
     return stream_group(c.x, M, K, ldx, &d, 1, ws, L, c.st);
   }
 

@@ -47,7 +47,8 @@ constexpr int kMaxGroup = 4;
 struct StreamMember {
   const uint8_t* packed; const float* tensor_scale; const uint16_t* A; const uint16_t* B; uint16_t* y;
   int64_t ldy; int64_t N; int n_tiles; int tile_begin;   // row-tiles [tile_begin, tile_begin + n_tiles) of the group
-  int r; int t_off;                                      // rank; column offset of this member's t in the stacked t
+  int r; int t_off;                                      // rank; column offset of this member's t in the stacked t (INT_MAX if t_ext)
+  const float* t_ext;                                    // x A^T computed before the launch, fp32 [QERL_T_PARTS][M][r] partial sums, or null: producers compute it
   float lora_scale;
 };
 struct StreamArgs {
@@ -55,7 +56,7 @@ struct StreamArgs {
   int n_members; StreamMember mem[kMaxGroup];
   // flat copy of what the streaming loop needs of the member table (unused entries: INT_MAX / member 0's pointer)
   int tb1, tb2, tb3; const uint8_t* mp0; const uint8_t* mp1; const uint8_t* mp2; const uint8_t* mp3;
-  int total_tiles; int r_total;
+  int total_tiles; int r_total; int any_lora;            // row-tiles; stacked rank the producers compute; any member with r > 0
   int Sk; int kr_len; int per_range; int n_producers;    // K-ranges, K-tiles in each, consumer workgroups per range; producers
   int units_base; int units_rem;                         // consumer ci owns units_base (+1 if ci < units_rem) row-tiles
   int xs_stride; int red_off; int pend_off;              // LDS layout (bytes): x row stride, reduction buffers, parked units

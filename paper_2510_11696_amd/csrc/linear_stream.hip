@@ -207,9 +207,10 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
   const int n32 = lane & 31, kg = lane >> 5;
   QTRACE(0);
   QSTART(0);
-  // units ci, ci + stride_u, ... of K-range `range` are this workgroup's
-  const int range = (int)blockIdx.y, ci = (int)blockIdx.x - a.n_producers, stride_u = a.per_range;
+  // units u0 .. u0 + n_units - 1 of K-range `range` are this workgroup's
+  const int range = (int)blockIdx.y, ci = (int)blockIdx.x - a.n_producers;
   const int n_units = a.units_base + (ci < a.units_rem ? 1 : 0);
+  const int u0 = ci * a.units_base + (ci < a.units_rem ? ci : a.units_rem);   // consecutive row-tiles: mostly one member per workgroup
   const int kr_len = a.kr_len;            // K-tiles per range
   const int kr0 = range * kr_len, kr1 = (kr0 + kr_len < a.k_tiles) ? kr0 + kr_len : a.k_tiles;
   // unused entries of the member table start at INT_MAX
@@ -267,7 +268,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
     int kmul;
     auto set_unit = [&]() {
       const bool live = have && lu < n_units;
-      const int nt = live ? ci + lu * stride_u : 0;
+      const int nt = live ? u0 + lu : 0;
       int tb = 0;
       const uint8_t* mp = a.mp0;
       if (nt >= a.tb1) { tb = a.tb1; mp = a.mp1; }
@@ -287,7 +288,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
 #pragma unroll
     for (int d = 0; d < D; ++d) issue(ring[d]);
     QSTART(4);
-    xstore(ch0 + tid, xv);               // waits for x only: the ring stays in flight
+    xstore(ch0 + tid, xv);                // waits for x only: the ring stays in flight
     QSTART(5);
     __syncthreads();
     QSTART(6);
@@ -369,7 +370,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
   __syncthreads();
   QTRACE(1);
 
-  const bool lora_range = range == 0 && a.r_total > 0;     // only the first K-range adds the branch
+  const bool lora_range = range == 0 && a.any_lora != 0;   // only the first K-range adds the branch
   // tensor scales of all members up front: no memory round trip between a unit's barrier and its stores
   float S32m[kMaxGroup];
 #pragma unroll
@@ -386,7 +387,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
     if (u_recv < n_units && u_recv - u_done < kMaxPending) {
       // ---- receive unit u_recv
       const int u = u_recv, slot = u % kMaxPending;
-      const int nt = ci + u * stride_u;
+      const int nt = u0 + u;
       const int mi = member_index(nt);
       const StreamMember& mem = a.mem[mi];
       if (lora_range && mem.r > 0) {
@@ -417,11 +418,11 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
     }
     // ---- finalize the oldest received unit, if it can be
     const int u = u_done, slot = u % kMaxPending;
-    const int nt = ci + u * stride_u;
+    const int nt = u0 + u;
     const int mi = member_index(nt);
     const StreamMember& mem = a.mem[mi];
     const bool needs_lora = lora_range && mem.r > 0;
-    if (needs_lora && !t_ready) {
+    if (needs_lora && !t_ready && !mem.t_ext) {
       const bool can_receive_more = u_recv < n_units && u_recv - u_done < kMaxPending;
       uint32_t spins = 0;
       for (;;) {
@@ -451,7 +452,22 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
           float tv[8];
 #pragma unroll
           for (int i = 0; i < 8; ++i) tv[i] = 0.f;
-          if (n32 < a.M && j0 < mem.r) {
+          if (n32 < a.M && j0 < mem.r && mem.t_ext) {
+            // t of this member was computed before the launch, as partial sums over slices of K
+            // [QERL_T_PARTS][M][r]: all loads in flight at once, added in slice order
+            const float* tp = mem.t_ext + (int64_t)n32 * mem.r + j0;
+            const int64_t pstride = (int64_t)a.M * mem.r;
+            f32x4 v[QERL_T_PARTS][2];
+#pragma unroll
+            for (int b = 0; b < QERL_T_PARTS; ++b) {
+              v[b][0] = *reinterpret_cast<const f32x4*>(tp + b * pstride);
+              v[b][1] = *reinterpret_cast<const f32x4*>(tp + b * pstride + 4);
+            }
+#pragma unroll
+            for (int b = 0; b < QERL_T_PARTS; ++b)
+#pragma unroll
+              for (int i = 0; i < 4; ++i) { tv[i] += v[b][0][i]; tv[4 + i] += v[b][1][i]; }
+          } else if (n32 < a.M && j0 < mem.r) {
             const float* tp = reinterpret_cast<const float*>(a.tpart) + (int64_t)n32 * a.r_total + mem.t_off + j0;
             const int64_t pstride = (int64_t)kTpartTokens * a.r_total;
             for (int p0 = 0; p0 < a.n_producers; p0 += 8) {   // eight producers' loads in flight at a time
@@ -532,7 +548,8 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
 
 // ---- host ------------------------------------------------------------------------------------------
 
-static int g_force_consumers = 0;
+static int g_force_ranges = 0;
+static int g_force_depth = 0;
 
 // LDS layout for M tokens (+ zero row) of a K-range of kr_len K-tiles: x slice, reduction buffers, and --
 // with LoRA -- the parking area of the epilogue wave.  Producers use the start of the same allocation.
@@ -557,25 +574,36 @@ constexpr size_t kStreamLdsMax = 160 * 1024 - 512;   // the static flag word tak
 int plan_stream(StreamArgs& a, size_t* lds_bytes, int* MR_out) {
   const int MR = a.M <= 8 ? 4 : 8;
   *MR_out = MR;
-  const bool lora = a.r_total > 0;
-  // smallest number of K-ranges whose x slice fits
+  const bool lora = a.any_lora != 0;
   const size_t lds_cap = 150 * 1024;
-  int Sk = 1;
-  for (;; ++Sk) {
-    if (stream_lds(a.M, (int)ceil_div(a.k_tiles, Sk), MR, lora).total <= lds_cap) break;
-    if (Sk >= a.k_tiles) return QERL_ERR_SHAPE;
+  // Number of K-ranges: at least what makes the x slice fit, and beyond that whatever gives the shortest
+  // critical path -- tiles a main wave multiplies one after the other (about half a microsecond each), plus
+  // the exchange of partial tiles (three dependent memory round trips) once K is split at all.  Never more
+  // ranges than K-tiles / 7: the workspace is sized for that, and a range should feed seven waves.
+  const int sk_limit = (int)ceil_div(a.k_tiles, kMainWaves);
+  const int cus = 256 - a.n_producers;   // one workgroup per CU (the register use allows no second one), producers included
+  int best = 0;
+  double best_cost = 0;
+  for (int Sk = 1; Sk <= sk_limit; ++Sk) {
+    const int kr_len = (int)ceil_div(a.k_tiles, Sk);
+    if (stream_lds(a.M, kr_len, MR, lora).total > lds_cap) continue;
+    if (g_force_ranges > 0 && Sk != g_force_ranges) continue;
+    int64_t per_range = cus / Sk;
+    if (per_range < 1) break;
+    if (per_range > a.total_tiles) per_range = a.total_tiles;
+    const int64_t units = ceil_div(a.total_tiles, per_range), lw = ceil_div(kr_len, kMainWaves);
+    const double cost = 0.5 * (double)(units * lw) + (Sk > 1 ? 3.0 : 0.0);
+    if (best == 0 || cost < best_cost) { best = Sk; best_cost = cost; }
+    if (Sk >= 8 && best != 0) break;
   }
-  // No further split for small problems: a second K-range halves the streaming time of a unit, but the
-  // exchange of partial tiles costs three dependent memory round trips at the end, which is more.
+  if (best == 0) return QERL_ERR_SHAPE;
+  const int Sk = best;
   const StreamLds l = stream_lds(a.M, (int)ceil_div(a.k_tiles, Sk), MR, lora);
   *lds_bytes = l.total;
   a.Sk = Sk; a.xs_stride = l.xs_stride; a.red_off = l.red_off; a.pend_off = l.pend_off;
-  // One workgroup per CU (the kernel's register use allows no second one), producers included: a
-  // workgroup that had to wait for a free CU would start when the others are half done.
-  int64_t per_range = (256 - a.n_producers) / Sk;
+  int64_t per_range = cus / Sk;
   if (per_range > a.total_tiles) per_range = a.total_tiles;
   if (per_range < 1) per_range = 1;
-  if (g_force_consumers > 0) per_range = g_force_consumers / Sk > 0 ? g_force_consumers / Sk : 1;
   a.per_range = (int)per_range; a.kr_len = l.kr_len;
   a.units_base = a.total_tiles / a.per_range; a.units_rem = a.total_tiles % a.per_range;
   return QERL_OK;
@@ -603,6 +631,7 @@ int launch_stream(const StreamArgs& a, size_t lds, int MR, hipStream_t st) {
     if (m.r > 0 && (!m.A || !m.B || m.r > 64 || m.r % 8 != 0)) return QERL_ERR_SHAPE;
   }
   if (a.r_total > 0 && (a.n_producers < 1 || a.n_producers > 16 || !a.lora_ctl || !a.tpart)) return QERL_ERR_NULL;
+  if (a.r_total == 0 && a.n_producers != 0) return QERL_ERR_SHAPE;
   if (a.r_total < 0 || a.r_total > 256 || a.r_total % 8 != 0) return QERL_ERR_SHAPE;
   if (a.mp0 != a.mem[0].packed || a.mp1 != a.mem[1].packed || a.mp2 != a.mem[2].packed || a.mp3 != a.mem[3].packed ||
       a.tb1 != a.mem[1].tile_begin || a.tb2 != a.mem[2].tile_begin || a.tb3 != a.mem[3].tile_begin)
@@ -611,14 +640,17 @@ int launch_stream(const StreamArgs& a, size_t lds, int MR, hipStream_t st) {
       a.units_base * a.per_range + a.units_rem != a.total_tiles ||
       a.total_tiles < 1 || lds > kStreamLdsMax || a.red_off <= 0 || a.pend_off < a.red_off)
     return QERL_ERR_SHAPE;
-  if (MR == 4) return launch_stream_t<4, 6>(a, lds, st);
-  return launch_stream_t<8, 5>(a, lds, st);
+  if (MR == 4 && g_force_depth == 3) return launch_stream_t<4, 3>(a, lds, st);
+  if (MR == 4 && g_force_depth == 6) return launch_stream_t<4, 6>(a, lds, st);
+  if (MR == 4) return launch_stream_t<4, 4>(a, lds, st);
+  return launch_stream_t<8, 4>(a, lds, st);
 }
 
 }  // namespace qerl
 
-// Tuning hook for experiments (not part of the public header): force the number of consumer workgroups; 0 = automatic.
-extern "C" QERL_API void qerl_debug_force_stream(int consumers) { qerl::g_force_consumers = consumers; }
+// Tuning hooks for experiments (not part of the public header): number of K-ranges and ring depth; 0 = automatic.
+extern "C" QERL_API void qerl_debug_force_stream(int ranges) { qerl::g_force_ranges = ranges; }
+extern "C" QERL_API void qerl_debug_force_stream_depth(int d) { qerl::g_force_depth = d; }
 #ifdef QERL_STREAM_TRACE
 extern "C" QERL_API int qerl_debug_read_trace(void* dst, size_t bytes) {
   return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(qerl::g_trace), bytes, 0, hipMemcpyDeviceToHost);

@@ -216,8 +216,9 @@ def test_rmsnorm_feeds_linear_end_to_end():
     (18944, (64, 32), (32, 32)),                 # K split over several workgroups
 ])
 def test_grouped_launch_equals_oracle(M, K, Ns, rs):
-    """One launch for several linears that share x: each member within tolerance of the oracle and
-    bit-identical to the single-linear call."""
+    """One launch for several linears that share x: each member within tolerance of the oracle (the
+    single-linear call may split K differently, so the two agree to rounding, not bit for bit), and the
+    grouped call repeats bit for bit."""
     print("group case", M, K, Ns, rs, flush=True)
     x = qs.activations(M, K, 900 + M)
     g = lambda a: torch.from_numpy(a).cuda()
@@ -238,6 +239,49 @@ def test_grouped_launch_equals_oracle(M, K, Ns, rs):
     for i, (y, ref) in enumerate(zip(outs, refs)):
         check_linear(y, ref, ("group", i, M, K, Ns, rs))
         single = qerl.nvfp4_lora_linear_packed(x.cuda(), ws_[i], As[i], Bs[i], 2.0)
-        assert torch.equal(single, y)
+        check_linear(single, ref, ("single", i, M, K, Ns, rs))
     again = qerl.nvfp4_lora_linear_packed_group(x.cuda(), ws_, As, Bs, [2.0] * len(Ns))
+    assert all(torch.equal(p, q) for p, q in zip(outs, again))
+
+
+@pytest.mark.parametrize("M", [1, 7, 8, 16])
+@pytest.mark.parametrize("H,Ns,rs,sigma", [
+    (3584, (3584, 512, 512), (32, 32, 32), 1e-2),   # q, k, v of the 7B block
+    (3584, (1184, 1184), (32, 32), 5e-4),           # a slice of gate, up
+    (2048, (96, 64), (64, 16), None),               # two rank tiles in one adapter; a partial rank tile; stage 0
+    (4096, (64,), (8,), 1e-2),
+])
+def test_norm_with_lora_down_feeds_grouped_linear(M, H, Ns, rs, sigma):
+    """aqn_rmsnorm_lora_down: y bit-identical to aqn_rmsnorm, t = y A^T within fp32 summation error of
+    the oracle's product, and the grouped linear fed with that t within tolerance of the oracle."""
+    print("norm+down case", M, H, Ns, rs, sigma, flush=True)
+    xin = qs.activations(M, H, 300 + M)
+    gain = qs.rms_gain(H, 301)
+    Z = qs.aqn_noise(H, sigma, 302) if sigma is not None else None
+    g = lambda a: torch.from_numpy(a).cuda()
+    ws_, As, Bs, W_q = [], [], [], []
+    for i, (N, r) in enumerate(zip(Ns, rs)):
+        W = cases.gaussian(N, H, 3000 + 10 * i + M)
+        codes, scales, ts = oracle.nvfp4_quantize(W)
+        A, B = qs.lora_pair(N, H, r, 4000 + i)
+        ws_.append(qerl.nvfp4_prepack(g(codes), g(scales), torch.tensor([ts], device="cuda")))
+        As.append(A.cuda()); Bs.append(B.cuda()); W_q.append((codes, scales, ts, A, B))
+    y_plain = qerl.aqn_rmsnorm(xin.cuda(), gain.cuda(), Z.cuda() if Z is not None else None, 1e-6)
+    y, ts_gpu = qerl.aqn_rmsnorm_lora_down(xin.cuda(), gain.cuda(), Z.cuda() if Z is not None else None, 1e-6, As)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_plain)
+    y64 = y.float().cpu().numpy().astype(np.float64)
+    for (codes, scales, ts, A, B), t_gpu in zip(W_q, ts_gpu):
+        t_ref = y64 @ A.float().numpy().astype(np.float64).T
+        bound = 4 * H * 2.0 ** -24 * (np.abs(y64) @ np.abs(A.float().numpy().astype(np.float64)).T) + 1e-30
+        assert tuple(t_gpu.shape) == (8, M, A.shape[0])
+        assert (np.abs(t_gpu.cpu().numpy().astype(np.float64).sum(0) - t_ref) <= bound).all()
+    outs = qerl.nvfp4_lora_linear_packed_group(y, ws_, As, Bs, [2.0] * len(Ns), ts=ts_gpu)
+    outs_self = qerl.nvfp4_lora_linear_packed_group(y, ws_, As, Bs, [2.0] * len(Ns))
+    torch.cuda.synchronize()
+    for i, ((codes, scales, ts, A, B), out, out_self) in enumerate(zip(W_q, outs, outs_self)):
+        ref = oracle.nvfp4_lora_linear(y.float().cpu().numpy(), codes, scales, ts, A.float().numpy(), B.float().numpy(), 2.0)
+        check_linear(out, ref, ("norm+down -> group", i, M, H, Ns, rs))
+        check_linear(out_self, ref, ("group computing t itself", i, M, H, Ns, rs))
+    again = qerl.nvfp4_lora_linear_packed_group(y, ws_, As, Bs, [2.0] * len(Ns), ts=ts_gpu)
     assert all(torch.equal(p, q) for p, q in zip(outs, again))

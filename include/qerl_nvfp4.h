@@ -202,8 +202,10 @@ QERL_API int aqn_rmsnorm(const void* x_bf16, int64_t M, int64_t H, int64_t ldx,
  *   t_f32:  HOST array of device pointers, t_i [QERL_T_PARTS][M][r_i] fp32 out, 32-byte
  *           aligned: part p is the product over the p-th slice of H; their sum in
  *           part order is t_i
- * y is exactly what aqn_rmsnorm writes; t_i is the fp32 product of the ROUNDED y
- * (what the linear kernels would compute themselves) in a fixed summation order.
+ * y is the function aqn_rmsnorm computes (its mean of squares is summed in another
+ * order, so a rare element may differ from aqn_rmsnorm's by one bf16 unit); t_i
+ * is the fp32 product of the ROUNDED y that this call writes (what the linear
+ * kernels would compute themselves from y) in a fixed summation order.
  * Errors: as aqn_rmsnorm, plus M > 16, H % 16 != 0, H > 8192, n_adapters outside
  * 1..4, ranks not multiples of 8 in 8..64 or summing to more than 128
  * (QERL_ERR_SHAPE); unaligned rows or pointers (QERL_ERR_ALIGN).

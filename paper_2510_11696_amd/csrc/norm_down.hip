@@ -9,10 +9,11 @@
 // to wait for another either.
 //
 // QERL_T_PARTS workgroups of 512 threads; workgroup p owns the p-th slice of K (whole 16-input steps):
-//   1. all of x is read once, rows in registers, and each row's sum of squares is formed exactly as
-//      aqn_rmsnorm forms it (256 threads per row, same element order, same reduction tree), so y is
-//      bit-identical to what aqn_rmsnorm writes;
-//   2. the slice's columns of every row are normalised, rounded, written to y and kept in LDS;
+//   1. wave w reads row w (and w + 8) whole and forms its sum of squares -- one wave per row, so no
+//      exchange between waves; 1 / rms of every row goes to LDS;
+//   2. the slice's columns of every row (requested at the start as well) are normalised, rounded,
+//      written to y and kept in LDS.  y is the function aqn_rmsnorm computes; the mean of squares is
+//      summed in another order, so a rare element can differ from aqn_rmsnorm's by one bf16 unit;
 //   3. the eight waves split the slice's steps: x fragment from LDS, A fragments of all stacked ranks
 //      (requested first thing in the kernel) from registers, one accumulator tile per 32 stacked ranks;
 //   4. the eight waves' tiles are added in wave order and stored as part p of every adapter's t.
@@ -21,7 +22,7 @@
 
 namespace qerl {
 
-constexpr int kNdThreads = 512, kNdWaves = 8, kNdRowThreads = 256;
+constexpr int kNdThreads = 512, kNdWaves = 8;
 constexpr int kNdMaxAdapters = 4;
 constexpr int kNdParts = QERL_T_PARTS;
 constexpr int kNdMaxTiles = 4;             // 32-rank tiles of the stacked adapters: sum of ranks <= 128
@@ -45,57 +46,61 @@ struct NormDownArgs {
   int xs_stride;                           // bytes between token rows of the slice in LDS
 };
 
-// MR: accumulator registers that hold live tokens (4 for M <= 8, 8 for M <= 16); NCH: 16-byte chunks of a row
-// per thread (2: H <= 4096, 4: H <= 8192); NT: 32-rank tiles
-template <int MR, int NCH, int NT>
+// MR: accumulator registers that hold live tokens (4 for M <= 8, 8 for M <= 16); NCL: 16-byte chunks of a row
+// per lane when one wave reads the row (8: H <= 4096, 16: H <= 8192); NT: 32-rank tiles
+template <int MR, int NCL, int NT>
 __global__ __launch_bounds__(kNdThreads) void norm_down_kernel(const NormDownArgs a) {
   extern __shared__ __attribute__((aligned(256))) unsigned char smem[];   // slice of y [(M+1) rows][xs_stride]; red after it
-  __shared__ float s_part[16][4];          // per row: the four wave sums of its 256 threads
-  constexpr int kRowsPerThread = MR == 4 ? 4 : 8;   // rows half, half + 2, ... of this thread's half
+  __shared__ float s_inv[16];              // 1 / rms of every row
+  constexpr int RPW = MR == 4 ? 1 : 2;     // rows per wave for the sums of squares: rows wave, wave + 8
+  constexpr int NQ = MR == 4 ? 2 : 4;      // (row, chunk) items of the slice per thread: 128 chunk slots per row
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int half = wave >> 2, rt = tid & (kNdRowThreads - 1);   // which of two concurrent rows; thread within the row
   const int chunks = (int)(a.H / 8);
   const int n32 = lane & 31, kg = lane >> 5;
   const int part = (int)blockIdx.x;
   const int n_steps = (int)(a.H / 16);
   const int step0 = part * a.steps_per_part;
   const int step1 = step0 + a.steps_per_part < n_steps ? step0 + a.steps_per_part : n_steps;
+  const int c_lo = step0 * 2, nsc = (step1 - step0) * 2;   // 16-byte chunks of the slice: first, count (<= 128)
   NDT(0);
 
-  // ---- 1. read x (requested first: it is needed first) ...
-  u32x4 reg[kRowsPerThread][NCH];
-  float ss[kRowsPerThread];
+  // ---- everything this workgroup reads is requested up front, in the order it is needed:
+  // (a) whole rows for the sums of squares: wave w reads row w (and w + 8), lane l the chunks l, l + 64, ...
+  // (with two long rows per wave the second is read after the first is summed: registers)
+  constexpr bool kSeqRows = RPW * NCL > 16;
+  constexpr int XR = kSeqRows ? 1 : RPW;
+  u32x4 xr[XR][NCL];
+  auto load_row = [&](int p, int slot) {
+    const int row = wave + 8 * p;
 #pragma unroll
-  for (int p = 0; p < kRowsPerThread; ++p) {
-    const int row = 2 * p + half;
-    ss[p] = 0.f;
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      const int c = rt + i * kNdRowThreads;
-      reg[p][i] = u32x4{0u, 0u, 0u, 0u};
-      if (row < a.M && c < chunks) reg[p][i] = reinterpret_cast<const u32x4*>(a.x + (int64_t)row * a.ldx)[c];
+    for (int i = 0; i < NCL; ++i) {
+      const int c = lane + 64 * i;
+      xr[slot][i] = u32x4{0u, 0u, 0u, 0u};
+      if (row < a.M && c < chunks) xr[slot][i] = reinterpret_cast<const u32x4*>(a.x + (int64_t)row * a.ldx)[c];
     }
-  }
-  // gain and noise of the chunks this thread normalises: also requested up front
-  const int c_lo = step0 * 2, c_hi = step1 * 2;          // 16-byte chunks of the slice
+  };
+#pragma unroll
+  for (int p = 0; p < XR; ++p) load_row(p, p);
+  // (b) the slice's chunks of every row with their gain and noise: item = (row, chunk slot), 128 slots per row
   const u32x4* __restrict__ gr = reinterpret_cast<const u32x4*>(a.gain);
   const f32x4* __restrict__ zr = reinterpret_cast<const f32x4*>(a.noise);
-  u32x4 gq[NCH];
-  f32x4 zq[NCH][2];
+  u32x4 xq[NQ], gq[NQ];
+  f32x4 zq[NQ][2];
 #pragma unroll
-  for (int i = 0; i < NCH; ++i) {
-    const int c = rt + i * kNdRowThreads;
-    gq[i] = u32x4{0u, 0u, 0u, 0u};
-    zq[i][0] = f32x4{0.f, 0.f, 0.f, 0.f}; zq[i][1] = zq[i][0];
-    if (c >= c_lo && c < c_hi) {
-      gq[i] = gr[c];
-      if (zr) { zq[i][0] = zr[2 * c]; zq[i][1] = zr[2 * c + 1]; }
+  for (int q = 0; q < NQ; ++q) {
+    const int id = tid + kNdThreads * q, row = id >> 7, cs = id & 127;
+    xq[q] = u32x4{0u, 0u, 0u, 0u}; gq[q] = xq[q];
+    zq[q][0] = f32x4{0.f, 0.f, 0.f, 0.f}; zq[q][1] = zq[q][0];
+    if (row < a.M && cs < nsc) {
+      const int c = c_lo + cs;
+      xq[q] = reinterpret_cast<const u32x4*>(a.x + (int64_t)row * a.ldx)[c];
+      gq[q] = gr[c];
+      if (zr) { zq[q][0] = zr[2 * c]; zq[q][1] = zr[2 * c + 1]; }
     }
   }
-
-  // ---- A fragments of this wave's steps, all rank tiles: requested before x is even looked at (they depend on
-  // nothing), so their latency overlaps the normalisation; behind x, which is needed first.  Wave w takes steps step0 + w, step0 + w + 8, ...
+  // (c) A fragments of this wave's steps, all rank tiles (they depend on nothing, so their latency overlaps
+  // the normalisation).  Wave w takes steps step0 + w, step0 + w + 8, ...
   const uint16_t* arow[NT];
   bool live[NT];
 #pragma unroll
@@ -125,60 +130,49 @@ __global__ __launch_bounds__(kNdThreads) void norm_down_kernel(const NormDownArg
   };
   load_frags(step0 + wave);
 
-  // ... sum of squares per row in aqn_rmsnorm's order
+  // ---- 1. sum of squares of a row: chunks in order per lane, then the lanes (wave_sum); 1 / rms to LDS
 #pragma unroll
-  for (int p = 0; p < kRowsPerThread; ++p) {
+  for (int p = 0; p < RPW; ++p) {
+    const int slot = kSeqRows ? 0 : p;
+    if (kSeqRows && p > 0) load_row(p, 0);
+    float ss = 0.f;
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      if (rt + i * kNdRowThreads < chunks) {
+    for (int i = 0; i < NCL; ++i) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const float lo = bf16_bits_to_f32(reg[p][i][j] & 0xffffu), hi = bf16_bits_to_f32(reg[p][i][j] >> 16);
-          ss[p] += lo * lo;
-          ss[p] += hi * hi;
-        }
+      for (int j = 0; j < 4; ++j) {
+        const float lo = bf16_bits_to_f32(xr[slot][i][j] & 0xffffu), hi = bf16_bits_to_f32(xr[slot][i][j] >> 16);
+        ss += lo * lo;
+        ss += hi * hi;
       }
     }
     if (p == 0) NDT(1);
-    const float ws = wave_sum(ss[p]);
-    if (lane == 0 && 2 * p + half < 16) s_part[2 * p + half][wave & 3] = ws;
+    const float total = wave_sum(ss);
+    if (lane == 0) s_inv[wave + 8 * p] = 1.0f / sqrtf(total / (float)a.H + a.eps);
   }
   __syncthreads();
   NDT(2);
 
   // ---- 2. normalise and round the slice's columns: to y and to LDS (A-operand rows)
-  float inv[kRowsPerThread];
 #pragma unroll
-  for (int p = 0; p < kRowsPerThread; ++p) {
-    const int row = (2 * p + half) & 15;
-    const float total = ((s_part[row][0] + s_part[row][1]) + s_part[row][2]) + s_part[row][3];
-    inv[p] = 1.0f / sqrtf(total / (float)a.H + a.eps);
-  }
+  for (int q = 0; q < NQ; ++q) {
+    const int id = tid + kNdThreads * q, row = id >> 7, cs = id & 127;
+    if (row < a.M && cs < nsc) {
+      const float inv = s_inv[row];
+      const float z[8] = {zq[q][0][0], zq[q][0][1], zq[q][0][2], zq[q][0][3], zq[q][1][0], zq[q][1][1], zq[q][1][2], zq[q][1][3]};
+      u32x4 o;
 #pragma unroll
-  for (int p = 0; p < kRowsPerThread; ++p) {
-    const int row = 2 * p + half;
-    if (row < a.M) {
-#pragma unroll
-      for (int i = 0; i < NCH; ++i) {
-        const int c = rt + i * kNdRowThreads;
-        if (c >= c_lo && c < c_hi) {
-          const float z[8] = {zq[i][0][0], zq[i][0][1], zq[i][0][2], zq[i][0][3], zq[i][1][0], zq[i][1][1], zq[i][1][2], zq[i][1][3]};
-          u32x4 o;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const float ga = bf16_bits_to_f32(gq[i][j] & 0xffffu) + z[2 * j];
-            const float gb = bf16_bits_to_f32(gq[i][j] >> 16) + z[2 * j + 1];
-            const float xa = bf16_bits_to_f32(reg[p][i][j] & 0xffffu), xb = bf16_bits_to_f32(reg[p][i][j] >> 16);
-            o[j] = pack_bf16x2(ga * (xa * inv[p]), gb * (xb * inv[p]));
-          }
-          *reinterpret_cast<u32x4*>(smem + row * a.xs_stride + (c - c_lo) * 16) = o;
-          reinterpret_cast<u32x4*>(a.y + (int64_t)row * a.ldy)[c] = o;
-        }
+      for (int j = 0; j < 4; ++j) {
+        const float ga = bf16_bits_to_f32(gq[q][j] & 0xffffu) + z[2 * j];
+        const float gb = bf16_bits_to_f32(gq[q][j] >> 16) + z[2 * j + 1];
+        const float xa = bf16_bits_to_f32(xq[q][j] & 0xffffu), xb = bf16_bits_to_f32(xq[q][j] >> 16);
+        o[j] = pack_bf16x2(ga * (xa * inv), gb * (xb * inv));
       }
+      *reinterpret_cast<u32x4*>(smem + row * a.xs_stride + cs * 16) = o;
+      reinterpret_cast<u32x4*>(a.y + (int64_t)row * a.ldy)[c_lo + cs] = o;
     }
   }
   NDT(3);
-  for (int c = tid; c < c_hi - c_lo; c += kNdThreads)   // tokens >= M read this zero row
+  for (int c = tid; c < nsc; c += kNdThreads)   // tokens >= M read this zero row
     *reinterpret_cast<u32x4*>(smem + a.M * a.xs_stride + c * 16) = u32x4{0u, 0u, 0u, 0u};
   __syncthreads();
   NDT(4);
@@ -240,25 +234,25 @@ __global__ __launch_bounds__(kNdThreads) void norm_down_kernel(const NormDownArg
 
 using namespace qerl;
 
-template <int MR, int NCH, int NT>
+template <int MR, int NCL, int NT>
 static int launch_norm_down_t(const NormDownArgs& a, size_t lds, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&norm_down_kernel<MR, NCH, NT>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&norm_down_kernel<MR, NCL, NT>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024) != hipSuccess)
       return launch_status();
     attr_set = true;
   }
-  norm_down_kernel<MR, NCH, NT><<<kNdParts, kNdThreads, lds, st>>>(a);
+  norm_down_kernel<MR, NCL, NT><<<kNdParts, kNdThreads, lds, st>>>(a);
   return launch_status();
 }
-template <int MR, int NCH>
+template <int MR, int NCL>
 static int launch_norm_down(const NormDownArgs& a, size_t lds, hipStream_t st) {
   switch (a.n_tiles) {
-    case 1: return launch_norm_down_t<MR, NCH, 1>(a, lds, st);
-    case 2: return launch_norm_down_t<MR, NCH, 2>(a, lds, st);
-    case 3: return launch_norm_down_t<MR, NCH, 3>(a, lds, st);
-    default: return launch_norm_down_t<MR, NCH, 4>(a, lds, st);
+    case 1: return launch_norm_down_t<MR, NCL, 1>(a, lds, st);
+    case 2: return launch_norm_down_t<MR, NCL, 2>(a, lds, st);
+    case 3: return launch_norm_down_t<MR, NCL, 3>(a, lds, st);
+    default: return launch_norm_down_t<MR, NCL, 4>(a, lds, st);
   }
 }
 
@@ -269,7 +263,7 @@ extern "C" int aqn_rmsnorm_lora_down(const void* x, int64_t M, int64_t H, int64_
   if (M < 0 || M > 16 || H < 1 || ldx < H || ldy < H) return QERL_ERR_SHAPE;
   if (n_adapters < 1 || n_adapters > kNdMaxAdapters) return QERL_ERR_SHAPE;
   if (!x || !gain || !y || !A || !r || !t) return QERL_ERR_NULL;
-  if (H % 16 != 0 || H > 8 * kNdRowThreads * 4) return QERL_ERR_SHAPE;
+  if (H % 16 != 0 || H > 8192) return QERL_ERR_SHAPE;
   if (ldx % 8 != 0 || ldy % 8 != 0 || !aligned(x, 16) || !aligned(y, 16) || !aligned(gain, 16) ||
       (noise && !aligned(noise, 16)))
     return QERL_ERR_ALIGN;
@@ -297,9 +291,9 @@ extern "C" int aqn_rmsnorm_lora_down(const void* x, int64_t M, int64_t H, int64_
   const size_t lds = (size_t)(M + 1) * a.xs_stride + (size_t)kNdWaves * a.n_tiles * MR * 64 * sizeof(float);
   if (lds > 128 * 1024) return QERL_ERR_SHAPE;             // cannot happen for H <= 8192; keeps the launch legal
   hipStream_t st = (hipStream_t)stream;
-  const bool wide = H > 8 * kNdRowThreads * 2;
-  if (MR == 4) return wide ? launch_norm_down<4, 4>(a, lds, st) : launch_norm_down<4, 2>(a, lds, st);
-  return wide ? launch_norm_down<8, 4>(a, lds, st) : launch_norm_down<8, 2>(a, lds, st);
+  const bool wide = H > 4096;
+  if (MR == 4) return wide ? launch_norm_down<4, 16>(a, lds, st) : launch_norm_down<4, 8>(a, lds, st);
+  return wide ? launch_norm_down<8, 16>(a, lds, st) : launch_norm_down<8, 8>(a, lds, st);
 }
 
 #ifdef QERL_ND_TRACE

@@ -7,7 +7,7 @@ import paper_2510_11696_amd as qerl
 import qerl_synth as qs
 from oracle import nvfp4_oracle as oracle
 from tests import cases
-from tests.gpu_util import check_linear, to_gpu_bf16
+from tests.gpu_util import bf16_ulp_distance, check_linear, to_gpu_bf16
 
 pytestmark = pytest.mark.gpu
 
@@ -250,9 +250,10 @@ def test_grouped_launch_equals_oracle(M, K, Ns, rs):
     (3584, (1184, 1184), (32, 32), 5e-4),           # a slice of gate, up
     (2048, (96, 64), (64, 16), None),               # two rank tiles in one adapter; a partial rank tile; stage 0
     (4096, (64,), (8,), 1e-2),
+    (5120, (1024, 96), (64, 64), 5e-3),             # rows longer than 4096: the wide variants; 14B / 32B hidden size
 ])
 def test_norm_with_lora_down_feeds_grouped_linear(M, H, Ns, rs, sigma):
-    """aqn_rmsnorm_lora_down: y bit-identical to aqn_rmsnorm, t = y A^T within fp32 summation error of
+    """aqn_rmsnorm_lora_down: y within one bf16 unit of the oracle (as aqn_rmsnorm), t = y A^T within fp32 summation error of
     the oracle's product, and the grouped linear fed with that t within tolerance of the oracle."""
     print("norm+down case", M, H, Ns, rs, sigma, flush=True)
     xin = qs.activations(M, H, 300 + M)
@@ -269,7 +270,11 @@ def test_norm_with_lora_down_feeds_grouped_linear(M, H, Ns, rs, sigma):
     y_plain = qerl.aqn_rmsnorm(xin.cuda(), gain.cuda(), Z.cuda() if Z is not None else None, 1e-6)
     y, ts_gpu = qerl.aqn_rmsnorm_lora_down(xin.cuda(), gain.cuda(), Z.cuda() if Z is not None else None, 1e-6, As)
     torch.cuda.synchronize()
-    assert torch.equal(y, y_plain)
+    # same function as aqn_rmsnorm, other summation order of the mean: within one bf16 unit of the fp64 oracle
+    ref_y = oracle.aqn_rmsnorm(xin.float().numpy(), gain.float().numpy(), Z.numpy() if Z is not None else None, 1e-6)
+    d = bf16_ulp_distance(y, ref_y)
+    assert d.max() <= 1 and (d > 0).mean() < 0.01
+    assert bf16_ulp_distance(y_plain, ref_y).max() <= 1
     y64 = y.float().cpu().numpy().astype(np.float64)
     for (codes, scales, ts, A, B), t_gpu in zip(W_q, ts_gpu):
         t_ref = y64 @ A.float().numpy().astype(np.float64).T

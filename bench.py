@@ -11,8 +11,9 @@ from a cache that would not be there in a rollout.  Attention and SiLU*mul are
 not part of this library; o and down read fixed synthetic activations.
 
 Prints ONE JSON line: whole-step weight-GB/s as `value`, the roofline of the
-dominant kernel (the gate/up/down-sized decode linear) measured live with
-events on the launch stream, and the CPU oracle timed on a bounded sample.
+dominant kernel (at decode sizes the grouped gate_proj + up_proj launch)
+measured live with events on the launch stream, and the CPU oracle timed on a
+bounded sample.
 """
 from __future__ import annotations
 
@@ -148,36 +149,50 @@ def measured_traffic(kernel: str, shape_name: str, M: int):
 
 
 def dominant_kernel_roofline(stack: Stack, reps: int):
-    """Average duration of one launch of the linear at the shape most of the step's
-    bytes / flops go through (gate_proj), run back to back over every layer's
-    distinct weights.  One call is one launch of the kernel named below when
-    M <= 16 (the LoRA down-projection runs inside it); for M > 16 the call also
-    contains the small lora_down32_kernel launch."""
-    shp = max(stack.cfg["linears"], key=lambda s: (s.packed_bytes, s.name == "gate"))
+    """Average duration of one launch of the kernel most of the step's bytes / flops go through, run back
+    to back over every layer's distinct weights.  Decode (M <= 16): the grouped gate_proj + up_proj launch
+    of stream_kernel, fed with the LoRA down-projections the norm's launch left in memory, exactly as in
+    the step.  M > 16: the gate_proj call (the small lora_down32_kernel launch belongs to it)."""
+    by = {s.name: s for s in stack.cfg["linears"]}
+    if stack.M <= 16:
+        names = ("gate", "up")
+        for L in stack.layers[:1]:          # any valid t will do for timing: it only feeds the up-projection
+            stack.norm_group(L, names, L.gain_post, L.z_post)
+        ts = [stack.t[n] for n in names]
 
-    def sweep():
-        for L in stack.layers:
-            stack.linear(L, shp.name, stack.act if shp.name == "down" else stack.xn)
+        def sweep():
+            for L in stack.layers:
+                ws, As, Bs = zip(*(L.lin[n] for n in names))
+                qerl.nvfp4_lora_linear_packed_group(stack.xn, list(ws), list(As), list(Bs),
+                                                    [stack.lora_scale] * len(names), workspace=stack.ws,
+                                                    outs=[stack.out[n] for n in names], ts=ts)
+        shape = {"name": "gate+up", "N": sum(by[n].N for n in names), "K": by["gate"].K, "M": stack.M}
+        bytes_per_launch = sum(by[n].packed_bytes for n in names)
+    else:
+        shp = max(stack.cfg["linears"], key=lambda s: (s.packed_bytes, s.name == "gate"))
+
+        def sweep():
+            for L in stack.layers:
+                stack.linear(L, shp.name, stack.act if shp.name == "down" else stack.xn)
+        shape = {"name": shp.name, "N": shp.N, "K": shp.K, "M": stack.M}
+        bytes_per_launch = shp.packed_bytes
     run = sweep if stack.eager else capture(sweep)
     run()
     ms = timed(run, reps) / len(stack.layers)
-    common = {"shape": {"name": shp.name, "N": shp.N, "K": shp.K, "M": stack.M},
-              "us_per_launch": round(ms * 1e3, 2),
-              "note": "one linear call per launch slot, back to back over the layers' distinct weights, "
-                      "launch gaps included"}
+    common = {"shape": shape, "us_per_launch": round(ms * 1e3, 2),
+              "note": "one call per launch slot, back to back over the layers' distinct weights, launch gaps included"}
     if stack.M <= 128:
         kernel = "stream_kernel" if stack.M <= 16 else "gemm32_kernel"
-        bytes_per_launch = shp.packed_bytes
         achieved = bytes_per_launch / (ms * 1e-3) / 1e9
         return {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": measured_traffic(kernel, shp.name, stack.M), "kernel": kernel,
+                "traffic": measured_traffic(kernel, shape["name"], stack.M), "kernel": kernel,
                 "algorithmic_bytes_per_launch": bytes_per_launch, **common}
-    flops = 2 * stack.M * shp.N * shp.K
+    flops = 2 * stack.M * shape["N"] * shape["K"]
     achieved = flops / (ms * 1e-3) / 1e12
     return {"bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
-            "traffic": measured_traffic("gemm32_kernel", shp.name, stack.M), "kernel": "gemm32_kernel",
+            "traffic": measured_traffic("gemm32_kernel", shape["name"], stack.M), "kernel": "gemm32_kernel",
             "algorithmic_flops_per_launch": flops, **common}
 
 

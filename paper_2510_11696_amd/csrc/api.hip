@@ -199,6 +199,7 @@ static int stream_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, co
     m.A = (const uint16_t*)d[i].A_bf16; m.B = (const uint16_t*)d[i].B_bf16; m.y = (uint16_t*)d[i].y_bf16;
     m.ldy = d[i].ldy; m.N = d[i].N; m.n_tiles = (int)ceil_div(d[i].N, kPackTileRows); m.tile_begin = tiles;
     m.r = (int)d[i].r; m.lora_scale = d[i].lora_scale;
+    m.y_vec = aligned(d[i].y_bf16, 16) && d[i].ldy % 8 == 0;
     m.t_ext = m.r > 0 ? d[i].t_f32 : nullptr;
     m.t_off = 0x7fffffff;                 // not part of the producers' stack ...
     if (m.r > 0 && !m.t_ext) { m.t_off = rt; rt += m.r; }   // ... unless the launch has to compute its t

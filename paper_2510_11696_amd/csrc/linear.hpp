@@ -48,6 +48,7 @@ struct StreamMember {
   const uint8_t* packed; const float* tensor_scale; const uint16_t* A; const uint16_t* B; uint16_t* y;
   int64_t ldy; int64_t N; int n_tiles; int tile_begin;   // row-tiles [tile_begin, tile_begin + n_tiles) of the group
   int r; int t_off;                                      // rank; column offset of this member's t in the stacked t (INT_MAX if t_ext)
+  int y_vec;                                             // y rows allow 16-byte stores (aligned base, ldy % 8 == 0)
   const float* t_ext;                                    // x A^T computed before the launch, fp32 [QERL_T_PARTS][M][r] partial sums, or null: producers compute it
   float lora_scale;
 };
@@ -59,7 +60,7 @@ struct StreamArgs {
   int total_tiles; int r_total; int any_lora;            // row-tiles; stacked rank the producers compute; any member with r > 0
   int Sk; int kr_len; int per_range; int n_producers;    // K-ranges, K-tiles in each, consumer workgroups per range; producers
   int units_base; int units_rem;                         // consumer ci owns units_base (+1 if ci < units_rem) row-tiles
-  int xs_stride; int red_off; int pend_off;              // LDS layout (bytes): x row stride, reduction buffers, parked units
+  int xs_stride; int red_off; int pend_off; int tsum_off;   // LDS layout (bytes): x row stride, reduction buffers, parked units, t of a member
   float* t; uint32_t* lora_ctl; uint32_t* tpart;         // stacked t [M, r_total]; hand-over words; producer partials
   uint32_t* partial; uint32_t* counters;                 // K-range exchange
 };

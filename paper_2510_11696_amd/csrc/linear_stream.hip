@@ -165,6 +165,7 @@ __device__ __forceinline__ void stream_producer(const StreamArgs& a, float* red)
 
 struct StreamTile { u32x4 c0, c1; u32x2 sc; };
 
+constexpr int kRedBufs = 4;                // partial-tile buffers between the main waves and the epilogue wave
 constexpr int kLoraSteps = 4;               // 16-wide j steps of the up-projection (r <= 64)
 constexpr int kMaxPending = 4;              // units an epilogue wave can park while t is not ready
 
@@ -193,9 +194,11 @@ __device__ __forceinline__ void ordered_sum_tile(const uint32_t* p, int64_t stri
 
 template <int MR, int D>
 __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamArgs a) {
-  // x slice [(M+1) rows][xs_stride bytes], red[2][7][MR][64] floats, parked units.  The alignment matters:
+  // x slice [(M+1) rows][xs_stride bytes], red[kRedBufs][7][64][MR] floats, parked units, t of a member.  The alignment matters:
   // 16-byte LDS accesses from a misaligned base run several times slower.
   extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
+  __shared__ StreamMember s_mem[kMaxGroup];
+  __shared__ int s_prod[kRedBufs], s_cons; // per buffer: main waves that have written their partial tile; units taken over by the epilogue wave
   float* red = reinterpret_cast<float*>(smem + a.red_off);
   // grid: x = producers, then the consumers of one K-range; y = K-range.  Producers exist in range 0 only.
   if ((int)blockIdx.x < a.n_producers) {
@@ -246,6 +249,49 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
   QSTART(1);
   xload(ch0 + tid, xv);
   QSTART(2);
+  if (tid < kRedBufs) s_prod[tid] = 0;
+  if (tid == 0) s_cons = 0;
+
+  // ---- what the epilogue wave reads from memory: requested ahead, because a load of that wave queues behind
+  // the whole weight ring of its CU, a latency it must never wait out between one barrier and the next.
+  const bool lora_range = range == 0 && a.any_lora != 0;   // only the first K-range adds the LoRA branch
+  // B rows (32 rows x r of the unit's member): one unit ahead, parked with the unit's sums
+  u32x4 bnext[kLoraSteps];
+  auto request_b = [&](int u) {
+#pragma unroll
+    for (int s = 0; s < kLoraSteps; ++s) bnext[s] = u32x4{0u, 0u, 0u, 0u};
+    if (u < n_units && lora_range) {
+      const int nt = u0 + u;
+      const StreamMember mem = s_mem[member_index(nt)];
+      if (mem.r > 0) {
+        int64_t brow = (int64_t)(nt - mem.tile_begin) * 32 + n32;
+        brow = brow < mem.N ? brow : mem.N - 1;
+#pragma unroll
+        for (int s = 0; s < kLoraSteps; ++s) {
+          const int j0 = 16 * s + 8 * kg;
+          if (j0 < mem.r) bnext[s] = *reinterpret_cast<const u32x4*>(mem.B + brow * mem.r + j0);
+        }
+      }
+    }
+  };
+  // partial sums of t: the first eight parts of 64 groups of four ranks (all there is for 8 tokens x rank 32)
+  f32x4 tq[8];
+  int tq_member = -1;
+  auto request_t = [&](int mi, int e0, int p0) {
+    const StreamMember mem = s_mem[mi];
+    const int r = mem.r, r4 = r >> 2, n4 = a.M * r4;
+    const float* src = mem.t_ext ? mem.t_ext : reinterpret_cast<const float*>(a.tpart) + mem.t_off;
+    const int n_parts = mem.t_ext ? QERL_T_PARTS : a.n_producers;
+    const int64_t row_stride = mem.t_ext ? r : a.r_total;
+    const int64_t part_stride = mem.t_ext ? (int64_t)a.M * r : (int64_t)kTpartTokens * a.r_total;
+    const int e = e0 + lane, tok = e / r4, j4 = e - tok * r4;
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+      tq[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (e < n4 && p0 + b < n_parts)
+        tq[b] = *reinterpret_cast<const f32x4*>(src + (p0 + b) * part_stride + tok * row_stride + 4 * j4);
+    }
+  };
   // Every wave of this CU has queued its x loads before any weight load is queued behind them: without
   // this, x for the last waves would arrive after the whole first ring of all waves.
   __builtin_amdgcn_s_barrier();
@@ -301,14 +347,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
 #pragma unroll
     for (int q = 0; q < MR; ++q) acc[q] = 0.f;
     int cu = 0, ck = kt0;                 // compute cursor
-    if (!have) {
-      // no K-tiles for this wave in this range: contribute zeros, keep the barriers
-      for (; cu < n_units; ++cu) {
-#pragma unroll
-        for (int q = 0; q < MR; ++q) red[(((cu & 1) * kMainWaves + wave) * MR + q) * 64 + lane] = 0.f;
-        __syncthreads();
-      }
-    }
+    // (a wave without K-tiles in this range has nothing to add: the epilogue wave counts the live ones only)
     // Ring slot d always holds tiles d, d + D, d + 2D, ... of this wave's sequence, so every slot is a fixed
     // set of registers.  Past the end of the sequence only the arithmetic is skipped: the refill still runs,
     // which keeps the number of loads in flight the same on every path.
@@ -343,14 +382,22 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
         __builtin_amdgcn_sched_barrier(0);
         issue(ring[d]);                   // refill the slot in place (same registers), D tiles ahead
         if (i0 + d < n_seq && ++ck == kt1) {
-          if (cu < n_units) {             // unit finished: hand the partial tile to the epilogue wave
+          if (cu < n_units) {
+            // Unit finished: hand the partial tile to the epilogue wave through one of kRedBufs buffers and
+            // go on.  No barrier: the waves of a workgroup drift apart freely, and only a buffer that the
+            // epilogue wave has not taken over yet (it is kRedBufs units behind) makes this wave wait.
+            if (cu >= kRedBufs) {
+              while (__hip_atomic_load(&s_cons, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < cu - kRedBufs + 1)
+                __builtin_amdgcn_s_sleep(1);
+            }
+            float* slot = red + (((cu % kRedBufs) * kMainWaves + wave) * 64 + lane) * MR;
 #pragma unroll
-            for (int q = 0; q < MR; ++q) {
-              red[(((cu & 1) * kMainWaves + wave) * MR + q) * 64 + lane] = acc[q];
-              acc[q] = 0.f;
+            for (int q = 0; q < MR; q += 4) {
+              *reinterpret_cast<f32x4*>(slot + q) = f32x4{acc[q], acc[q + 1], acc[q + 2], acc[q + 3]};
+              acc[q] = 0.f; acc[q + 1] = 0.f; acc[q + 2] = 0.f; acc[q + 3] = 0.f;
             }
             QTRACE(2 + (cu < 4 ? cu : 4));
-            __syncthreads();
+            if (lane == 0) __hip_atomic_fetch_add(&s_prod[cu % kRedBufs], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
             ++cu;
           }
           ck = kt0;
@@ -362,6 +409,21 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
   }
 
   // ---- epilogue wave -----------------------------------------------------------------------------
+  // It looks members up by a computed index.  Indexing the kernel arguments that way would be a vector load
+  // from memory per field and unit, each waiting for its turn behind the weight ring; so the table is copied
+  // to LDS once (constant indices: scalar loads) and read from there.
+  if (lane == 0) {
+#pragma unroll
+    for (int i = 0; i < kMaxGroup; ++i) s_mem[i] = a.mem[i];
+  }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  // first requests while the main waves are still queueing their ring: B of the first unit, and t if it was
+  // computed before the launch
+  request_b(0);
+  if (n_units > 0 && lora_range) {
+    const int m0 = member_index(u0);
+    if (s_mem[m0].r > 0 && s_mem[m0].t_ext) { request_t(m0, 0, 0); tq_member = m0; }
+  }
   // Two steps per unit, each written once: receive (barrier, add the seven partial tiles, park the sums and
   // the unit's B fragments in LDS) and finalize (LoRA up-projection, K-range exchange, store).  Finalizing
   // trails receiving by up to kMaxPending units, which is how the wave rides out the time until t is ready
@@ -370,49 +432,102 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
   __syncthreads();
   QTRACE(1);
 
-  const bool lora_range = range == 0 && a.any_lora != 0;   // only the first K-range adds the branch
   // tensor scales of all members up front: no memory round trip between a unit's barrier and its stores
   float S32m[kMaxGroup];
 #pragma unroll
   for (int i = 0; i < kMaxGroup; ++i) S32m[i] = i < a.n_members ? *a.mem[i].tensor_scale : 0.f;
 
+  const int lw_e = (kr1 - kr0 + kMainWaves - 1) / kMainWaves;
+  const int n_live = lw_e > 0 ? (kr1 - kr0 + lw_e - 1) / lw_e : 0;   // main waves that have K-tiles in this range
   u32x4 th[kLoraSteps], tm[kLoraSteps], tl[kLoraSteps];
   int t_member = -1;                      // member whose split t is in th/tm/tl
   bool poisoned = false, t_ready = a.n_producers == 0;
   float* pend_base = reinterpret_cast<float*>(smem + a.pend_off);          // [kMaxPending][MR][64]
   u32x4* pend_b = reinterpret_cast<u32x4*>(smem + a.pend_off + kMaxPending * MR * 64 * 4);   // [kMaxPending][kLoraSteps][64]
   int u_recv = 0, u_done = 0;             // units received / finalized so far
+  int b_wanted = -1;                      // unit whose B rows are to be requested next
+  // t of member mi: its partial sums (QERL_T_PARTS slices of K computed before the launch, or the producers'
+  // partials of this launch) are fetched by the whole wave in one round of loads -- element groups of four,
+  // all parts of a group in flight together -- added in part order, and left in LDS as [token][rank]; from
+  // there each lane takes its MFMA operand rows and splits the fp32 values into three bf16 terms (exact to
+  // 2^-24 relative).  The partials were written through to memory before this wave looks (kernel boundary, or
+  // the producers' count), and no cache can hold an older copy: ordinary loads suffice.
+  float* tsum = reinterpret_cast<float*>(smem + a.tsum_off);               // [M][r] of the current member
+  uint16_t* ytile = reinterpret_cast<uint16_t*>(smem + a.tsum_off + 16 * 64 * 4);   // [16 tokens][32 rows] bf16, output staging
+  auto load_t = [&](int mi) {
+    const StreamMember mem = s_mem[mi];
+    const int r = mem.r, r4 = r >> 2, n4 = a.M * r4;                        // groups of four ranks
+    const int n_parts = mem.t_ext ? QERL_T_PARTS : a.n_producers;
+    for (int e0 = 0; e0 < n4; e0 += 64) {                                   // one group per lane and round
+      f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+      for (int p0 = 0; p0 < n_parts; p0 += 8) {
+        if (!(tq_member == mi && e0 == 0 && p0 == 0)) request_t(mi, e0, p0);   // else: requested at kernel start
+        tq_member = -1;
+#pragma unroll
+        for (int b = 0; b < 8; ++b) sum += tq[b];
+      }
+      if (e0 + lane < n4) *reinterpret_cast<f32x4*>(tsum + 4 * (e0 + lane)) = sum;
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave's LDS writes are done before it reads them back
+#pragma unroll
+    for (int s = 0; s < kLoraSteps; ++s) {
+      const int j0 = 16 * s + 8 * kg;
+      float tv[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) tv[i] = 0.f;
+      if (n32 < a.M && j0 < r) {
+        const f32x4 t0 = *reinterpret_cast<const f32x4*>(tsum + n32 * r + j0);
+        const f32x4 t1 = *reinterpret_cast<const f32x4*>(tsum + n32 * r + j0 + 4);
+        tv[0] = t0[0]; tv[1] = t0[1]; tv[2] = t0[2]; tv[3] = t0[3];
+        tv[4] = t1[0]; tv[5] = t1[1]; tv[6] = t1[2]; tv[7] = t1[3];
+        if (poisoned) tv[0] = __uint_as_float(0x7fc00000u);   // the hand-over timed out: make it visible
+      }
+      stream_split3(tv, th[s], tm[s], tl[s]);
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // ... and read before the next member overwrites them
+    t_member = mi;
+  };
 
   while (u_done < n_units) {
+    if (b_wanted >= 0) { request_b(b_wanted); b_wanted = -1; }
     if (u_recv < n_units && u_recv - u_done < kMaxPending) {
       // ---- receive unit u_recv
       const int u = u_recv, slot = u % kMaxPending;
       const int nt = u0 + u;
       const int mi = member_index(nt);
-      const StreamMember& mem = a.mem[mi];
-      if (lora_range && mem.r > 0) {
-        // B rows of this unit first: their latency overlaps the wait at the barrier
-        int64_t brow = (int64_t)(nt - mem.tile_begin) * 32 + n32;
-        brow = brow < mem.N ? brow : mem.N - 1;
-#pragma unroll
-        for (int s = 0; s < kLoraSteps; ++s) {
-          const int j0 = 16 * s + 8 * kg;
-          u32x4 bq = u32x4{0u, 0u, 0u, 0u};
-          if (j0 < mem.r) bq = *reinterpret_cast<const u32x4*>(mem.B + brow * mem.r + j0);
-          pend_b[(slot * kLoraSteps + s) * 64 + lane] = bq;
-        }
-      }
       QTRACE(2 + (u < 4 ? u : 4));
-      __syncthreads();                    // the seven partial tiles of unit u are in red[u & 1]
+      while (__hip_atomic_load(&s_prod[u % kRedBufs], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < n_live)
+        __builtin_amdgcn_s_sleep(1);      // the live waves' partial tiles of unit u are in red[u % kRedBufs]
+      if (lora_range) {
+#pragma unroll
+        for (int s = 0; s < kLoraSteps; ++s) pend_b[(slot * kLoraSteps + s) * 64 + lane] = bnext[s];
+        b_wanted = u + 1;                 // requested at the end of this round: nothing finalize waits for may queue behind it
+      }
       float S32 = S32m[0];
 #pragma unroll
       for (int i = 1; i < kMaxGroup; ++i) S32 = mi == i ? S32m[i] : S32;
+      {
+        f32x4 part[kMainWaves][MR / 4];
 #pragma unroll
-      for (int q = 0; q < MR; ++q) {
-        float sum = 0.f;
+        for (int w = 0; w < kMainWaves; ++w)
 #pragma unroll
-        for (int w = 0; w < kMainWaves; ++w) sum += red[(((u & 1) * kMainWaves + w) * MR + q) * 64 + lane];
-        pend_base[(slot * MR + q) * 64 + lane] = sum * S32;
+          for (int q4 = 0; q4 < MR / 4; ++q4) {
+            part[w][q4] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (w < n_live) part[w][q4] = *reinterpret_cast<const f32x4*>(red + (((u % kRedBufs) * kMainWaves + w) * 64 + lane) * MR + 4 * q4);
+          }
+#pragma unroll
+        for (int q = 0; q < MR; ++q) {
+          float sum = 0.f;
+#pragma unroll
+          for (int w = 0; w < kMainWaves; ++w) sum += part[w][q >> 2][q & 3];
+          pend_base[(slot * MR + q) * 64 + lane] = sum * S32;
+        }
+      }
+      // the buffer may be written again (its reads above have returned: the sums were formed from them);
+      // its counter goes back to zero before the main waves are told
+      if (lane == 0) {
+        __hip_atomic_store(&s_prod[u % kRedBufs], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        __hip_atomic_store(&s_cons, u + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
       }
       ++u_recv;
     }
@@ -420,7 +535,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
     const int u = u_done, slot = u % kMaxPending;
     const int nt = u0 + u;
     const int mi = member_index(nt);
-    const StreamMember& mem = a.mem[mi];
+    const StreamMember mem = s_mem[mi];
     const bool needs_lora = lora_range && mem.r > 0;
     if (needs_lora && !t_ready && !mem.t_ext) {
       const bool can_receive_more = u_recv < n_units && u_recv - u_done < kMaxPending;
@@ -442,67 +557,21 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
 #pragma unroll
     for (int q = 0; q < MR; ++q) out[q] = pend_base[(slot * MR + q) * 64 + lane];
     if (needs_lora) {
-      if (t_member != mi) {
-        // The partials were written through to memory before their producers were counted, and no cache can
-        // hold an older copy (caches are invalidated at kernel start, nobody reads them earlier): ordinary loads
-        // suffice.  Added in producer order, so the sum is the same in every workgroup and on every call.
+      if (t_member != mi) load_t(mi);
+      f32x16 lh, lm, ll;                  // one chain per bf16 term of t: independent MFMAs back to back
 #pragma unroll
-        for (int s = 0; s < kLoraSteps; ++s) {
-          const int j0 = 16 * s + 8 * kg;
-          float tv[8];
-#pragma unroll
-          for (int i = 0; i < 8; ++i) tv[i] = 0.f;
-          if (n32 < a.M && j0 < mem.r && mem.t_ext) {
-            // t of this member was computed before the launch, as partial sums over slices of K
-            // [QERL_T_PARTS][M][r]: all loads in flight at once, added in slice order
-            const float* tp = mem.t_ext + (int64_t)n32 * mem.r + j0;
-            const int64_t pstride = (int64_t)a.M * mem.r;
-            f32x4 v[QERL_T_PARTS][2];
-#pragma unroll
-            for (int b = 0; b < QERL_T_PARTS; ++b) {
-              v[b][0] = *reinterpret_cast<const f32x4*>(tp + b * pstride);
-              v[b][1] = *reinterpret_cast<const f32x4*>(tp + b * pstride + 4);
-            }
-#pragma unroll
-            for (int b = 0; b < QERL_T_PARTS; ++b)
-#pragma unroll
-              for (int i = 0; i < 4; ++i) { tv[i] += v[b][0][i]; tv[4 + i] += v[b][1][i]; }
-          } else if (n32 < a.M && j0 < mem.r) {
-            const float* tp = reinterpret_cast<const float*>(a.tpart) + (int64_t)n32 * a.r_total + mem.t_off + j0;
-            const int64_t pstride = (int64_t)kTpartTokens * a.r_total;
-            for (int p0 = 0; p0 < a.n_producers; p0 += 8) {   // eight producers' loads in flight at a time
-              f32x4 v[8][2];
-#pragma unroll
-              for (int b = 0; b < 8; ++b) {
-                v[b][0] = f32x4{0.f, 0.f, 0.f, 0.f}; v[b][1] = v[b][0];
-                if (p0 + b < a.n_producers) {
-                  v[b][0] = *reinterpret_cast<const f32x4*>(tp + (p0 + b) * pstride);
-                  v[b][1] = *reinterpret_cast<const f32x4*>(tp + (p0 + b) * pstride + 4);
-                }
-              }
-#pragma unroll
-              for (int b = 0; b < 8; ++b)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) { tv[i] += v[b][0][i]; tv[4 + i] += v[b][1][i]; }
-            }
-            if (poisoned) tv[0] = __uint_as_float(0x7fc00000u);   // the hand-over timed out: make it visible
-          }
-          stream_split3(tv, th[s], tm[s], tl[s]);
-        }
-        t_member = mi;
-      }
-      f32x16 lo;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) lo[i] = 0.f;
+      for (int i = 0; i < 16; ++i) { lh[i] = 0.f; lm[i] = 0.f; ll[i] = 0.f; }
 #pragma unroll
       for (int s = 0; s < kLoraSteps; ++s) {
-        const bf16x8 bf = __builtin_bit_cast(bf16x8, pend_b[(slot * kLoraSteps + s) * 64 + lane]);
-        lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, th[s]), bf, lo, 0, 0, 0);
-        lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tm[s]), bf, lo, 0, 0, 0);
-        lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tl[s]), bf, lo, 0, 0, 0);
+        if (16 * s < mem.r) {
+          const bf16x8 bf = __builtin_bit_cast(bf16x8, pend_b[(slot * kLoraSteps + s) * 64 + lane]);
+          lh = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, th[s]), bf, lh, 0, 0, 0);
+          lm = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tm[s]), bf, lm, 0, 0, 0);
+          ll = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tl[s]), bf, ll, 0, 0, 0);
+        }
       }
 #pragma unroll
-      for (int q = 0; q < MR; ++q) out[q] += lo[q] * mem.lora_scale;
+      for (int q = 0; q < MR; ++q) out[q] += ((lh[q] + lm[q]) + ll[q]) * mem.lora_scale;
     }
     ++u_done;
     // out = this range's share of tile nt: exchange across K-ranges if there are several, then store
@@ -520,11 +589,29 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
       ordered_sum_tile<MR>(a.partial + (int64_t)nt * (MR * 64) + lane, (int64_t)a.total_tiles * (MR * 64), a.Sk, out);
       if (lane == 0) __hip_atomic_store(a.counters + nt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    const int64_t n = (int64_t)(nt - mem.tile_begin) * 32 + n32;
+    const int64_t n0 = (int64_t)(nt - mem.tile_begin) * 32;
+    if (mem.y_vec && n0 + 32 <= mem.N) {
+      // Whole tile, 16-byte aligned rows: transpose through LDS so that the tile leaves in ONE store
+      // instruction (16 bytes per lane) -- every vector memory instruction of this wave waits for its turn
+      // behind the main waves' weight loads.
 #pragma unroll
-    for (int q = 0; q < MR; ++q) {
-      const int tok = 8 * (q >> 2) + 4 * kg + (q & 3);
-      if (tok < a.M && n < mem.N) mem.y[(int64_t)tok * mem.ldy + n] = (uint16_t)f32_to_bf16_bits(out[q]);
+      for (int q = 0; q < MR; ++q) {
+        const int tok = 8 * (q >> 2) + 4 * kg + (q & 3);
+        ytile[tok * 32 + n32] = (uint16_t)f32_to_bf16_bits(out[q]);
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      const int tok = lane >> 2, part = lane & 3;
+      if (tok < a.M) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(ytile + tok * 32 + part * 8);
+        *reinterpret_cast<u32x4*>(mem.y + (int64_t)tok * mem.ldy + n0 + part * 8) = v;
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // read before the next unit overwrites the tile
+    } else {
+#pragma unroll
+      for (int q = 0; q < MR; ++q) {
+        const int tok = 8 * (q >> 2) + 4 * kg + (q & 3);
+        if (tok < a.M && n0 + n32 < mem.N) mem.y[(int64_t)tok * mem.ldy + n0 + n32] = (uint16_t)f32_to_bf16_bits(out[q]);
+      }
     }
   }
   QTRACE(7);
@@ -553,18 +640,20 @@ static int g_force_depth = 0;
 
 // LDS layout for M tokens (+ zero row) of a K-range of kr_len K-tiles: x slice, reduction buffers, and --
 // with LoRA -- the parking area of the epilogue wave.  Producers use the start of the same allocation.
-struct StreamLds { int kr_len, xs_stride, red_off, pend_off; size_t total; };
+struct StreamLds { int kr_len, xs_stride, red_off, pend_off, tsum_off; size_t total; };
 static StreamLds stream_lds(int M, int kr_len, int MR, bool lora) {
   StreamLds l{};
   l.kr_len = kr_len;
   l.xs_stride = kr_len * 256 + 16;   // rows 16 bytes apart in bank space: token rows and the zero row read conflict-free
   const size_t xs = (size_t)(M + 1) * (size_t)l.xs_stride;
   l.red_off = (int)((xs + 255) & ~(size_t)255);
-  const size_t red_consumer = 2 * (size_t)kMainWaves * MR * 64 * sizeof(float);
+  const size_t red_consumer = (size_t)kRedBufs * kMainWaves * MR * 64 * sizeof(float);
   l.pend_off = l.red_off + (int)red_consumer;
   const size_t pend = (size_t)kMaxPending * (MR * 64 * sizeof(float) + (lora ? kLoraSteps * 64 * 16 : 0));   // sums always, B fragments with LoRA
+  l.tsum_off = l.pend_off + (int)pend;
+  const size_t tsum = (size_t)16 * 64 * sizeof(float) + 16 * 32 * 2;               // t of one member (up to 16 tokens x 64 ranks); output tile staging
   const size_t red_producer = (size_t)kStreamWaves * 2 * MR * 64 * sizeof(float);
-  l.total = l.pend_off + pend;
+  l.total = l.tsum_off + tsum;
   if (l.total < red_producer) l.total = red_producer;
   return l;
 }
@@ -600,7 +689,7 @@ int plan_stream(StreamArgs& a, size_t* lds_bytes, int* MR_out) {
   const int Sk = best;
   const StreamLds l = stream_lds(a.M, (int)ceil_div(a.k_tiles, Sk), MR, lora);
   *lds_bytes = l.total;
-  a.Sk = Sk; a.xs_stride = l.xs_stride; a.red_off = l.red_off; a.pend_off = l.pend_off;
+  a.Sk = Sk; a.xs_stride = l.xs_stride; a.red_off = l.red_off; a.pend_off = l.pend_off; a.tsum_off = l.tsum_off;
   int64_t per_range = cus / Sk;
   if (per_range > a.total_tiles) per_range = a.total_tiles;
   if (per_range < 1) per_range = 1;

@@ -169,29 +169,6 @@ constexpr int kRedBufs = 4;                // partial-tile buffers between the m
 constexpr int kLoraSteps = 4;               // 16-wide j steps of the up-projection (r <= 64)
 constexpr int kMaxPending = 4;              // units an epilogue wave can park while t is not ready
 
-// out[q] = sum over z < S of p[z * stride + q * 64] for all q at once: agent-scope loads issued in
-// batches before any is consumed, added in index order (same result on every call).
-template <int MR>
-__device__ __forceinline__ void ordered_sum_tile(const uint32_t* p, int64_t stride, int S, float (&out)[MR]) {
-  constexpr int kBatch = MR == 4 ? 8 : 4;
-#pragma unroll
-  for (int q = 0; q < MR; ++q) out[q] = 0.f;
-  for (int z0 = 0; z0 < S; z0 += kBatch) {
-    uint32_t v[kBatch][MR];
-#pragma unroll
-    for (int b = 0; b < kBatch; ++b)
-#pragma unroll
-      for (int q = 0; q < MR; ++q) {
-        v[b][q] = 0u;
-        if (z0 + b < S) v[b][q] = __hip_atomic_load(p + (int64_t)(z0 + b) * stride + q * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-#pragma unroll
-    for (int b = 0; b < kBatch; ++b)
-#pragma unroll
-      for (int q = 0; q < MR; ++q) out[q] += __uint_as_float(v[b][q]);
-  }
-}
-
 template <int MR, int D>
 __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamArgs a) {
   // x slice [(M+1) rows][xs_stride bytes], red[kRedBufs][7][64][MR] floats, parked units, t of a member.  The alignment matters:
@@ -574,20 +551,15 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
       for (int q = 0; q < MR; ++q) out[q] += ((lh[q] + lm[q]) + ll[q]) * mem.lora_scale;
     }
     ++u_done;
-    // out = this range's share of tile nt: exchange across K-ranges if there are several, then store
+    // out = this range's share of tile nt.  With several K-ranges it goes to the workspace as it is
+    // ([range][tile][lane][MR] fp32) and stream_reduce_kernel, launched behind this kernel, adds the ranges in
+    // order and stores y: no workgroup ever waits for another one's range.
     if (a.Sk > 1) {
-      uint32_t* mine = a.partial + ((int64_t)range * a.total_tiles + nt) * (MR * 64) + lane;
+      float* mine = reinterpret_cast<float*>(a.partial) + (((int64_t)range * a.total_tiles + nt) * 64 + lane) * MR;
 #pragma unroll
-      for (int q = 0; q < MR; ++q)
-        __hip_atomic_store(mine + q * 64, __float_as_uint(out[q]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the partial tile is in memory before the arrival count
-      uint32_t old = 0;
-      if (lane == 0)
-        old = __hip_atomic_fetch_add(a.counters + nt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      old = __builtin_amdgcn_readfirstlane(old);
-      if (old != (uint32_t)(a.Sk - 1)) continue;
-      ordered_sum_tile<MR>(a.partial + (int64_t)nt * (MR * 64) + lane, (int64_t)a.total_tiles * (MR * 64), a.Sk, out);
-      if (lane == 0) __hip_atomic_store(a.counters + nt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      for (int q4 = 0; q4 < MR / 4; ++q4)
+        *reinterpret_cast<f32x4*>(mine + 4 * q4) = f32x4{out[4 * q4], out[4 * q4 + 1], out[4 * q4 + 2], out[4 * q4 + 3]};
+      continue;
     }
     const int64_t n0 = (int64_t)(nt - mem.tile_begin) * 32;
     if (mem.y_vec && n0 + 32 <= mem.N) {
@@ -633,6 +605,51 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
   }
 }
 
+// Second kernel of a launch with several K-ranges: y tile = sum over ranges, in range order, of the
+// partial tiles the epilogue waves left in the workspace.  One wave per row-tile.
+struct ReduceMember { uint16_t* y; int64_t ldy; int64_t N; int tile_begin; };
+struct ReduceArgs { const float* partial; int M, Sk, total_tiles; ReduceMember mem[kMaxGroup]; };
+
+template <int MR>
+__global__ __launch_bounds__(256) void stream_reduce_kernel(const ReduceArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int nt = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (nt >= a.total_tiles) return;
+  int mi = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxGroup; ++i) mi = nt >= a.mem[i].tile_begin ? i : mi;
+  const float* p = a.partial + ((int64_t)nt * 64 + lane) * MR;
+  const int64_t stride = (int64_t)a.total_tiles * 64 * MR;
+  f32x4 acc[MR / 4];
+#pragma unroll
+  for (int q4 = 0; q4 < MR / 4; ++q4) acc[q4] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int z0 = 0; z0 < a.Sk; z0 += 4) {      // four ranges in flight, added in range order
+    f32x4 v[4][MR / 4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int q4 = 0; q4 < MR / 4; ++q4) {
+        v[b][q4] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (z0 + b < a.Sk) v[b][q4] = *reinterpret_cast<const f32x4*>(p + (int64_t)(z0 + b) * stride + 4 * q4);
+      }
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int q4 = 0; q4 < MR / 4; ++q4) acc[q4] += v[b][q4];
+  }
+  uint16_t* y = a.mem[0].y; int64_t ldy = a.mem[0].ldy, N = a.mem[0].N; int tb = a.mem[0].tile_begin;
+#pragma unroll
+  for (int i = 1; i < kMaxGroup; ++i)
+    if (mi == i) { y = a.mem[i].y; ldy = a.mem[i].ldy; N = a.mem[i].N; tb = a.mem[i].tile_begin; }
+  const int n32 = lane & 31, kg = lane >> 5;
+  const int64_t n = (int64_t)(nt - tb) * 32 + n32;
+#pragma unroll
+  for (int q = 0; q < MR; ++q) {
+    const int tok = 8 * (q >> 2) + 4 * kg + (q & 3);
+    if (tok < a.M && n < N) y[(int64_t)tok * ldy + n] = (uint16_t)f32_to_bf16_bits(acc[q >> 2][q & 3]);
+  }
+}
+
 // ---- host ------------------------------------------------------------------------------------------
 
 static int g_force_ranges = 0;
@@ -667,10 +684,12 @@ int plan_stream(StreamArgs& a, size_t* lds_bytes, int* MR_out) {
   const size_t lds_cap = 150 * 1024;
   // Number of K-ranges: at least what makes the x slice fit, and beyond that whatever gives the shortest
   // critical path -- tiles a main wave multiplies one after the other (about half a microsecond each), plus
-  // the exchange of partial tiles (three dependent memory round trips) once K is split at all.  Never more
+  // the second launch that adds the ranges' partial tiles once K is split at all.  A unit cannot take less
+  // than the epilogue wave needs to collect it.  Never more
   // ranges than K-tiles / 7: the workspace is sized for that, and a range should feed seven waves.
   const int sk_limit = (int)ceil_div(a.k_tiles, kMainWaves);
   const int cus = 256 - a.n_producers;   // one workgroup per CU (the register use allows no second one), producers included
+  const double epilogue_us = MR == 4 ? 0.6 : 1.0;
   int best = 0;
   double best_cost = 0;
   for (int Sk = 1; Sk <= sk_limit; ++Sk) {
@@ -681,7 +700,8 @@ int plan_stream(StreamArgs& a, size_t* lds_bytes, int* MR_out) {
     if (per_range < 1) break;
     if (per_range > a.total_tiles) per_range = a.total_tiles;
     const int64_t units = ceil_div(a.total_tiles, per_range), lw = ceil_div(kr_len, kMainWaves);
-    const double cost = 0.5 * (double)(units * lw) + (Sk > 1 ? 3.0 : 0.0);
+    const double per_unit = 0.5 * (double)lw > epilogue_us ? 0.5 * (double)lw : epilogue_us;
+    const double cost = (double)units * per_unit + (Sk > 1 ? 4.0 : 0.0);
     if (best == 0 || cost < best_cost) { best = Sk; best_cost = cost; }
     if (Sk >= 8 && best != 0) break;
   }
@@ -708,6 +728,14 @@ static int launch_stream_t(const StreamArgs& a, size_t lds, hipStream_t st) {
     attr_set = true;
   }
   stream_kernel<MR, D><<<dim3(a.n_producers + a.per_range, a.Sk), dim3(kStreamWaves * 64), lds, st>>>(a);
+  if (a.Sk > 1) {
+    const int rc = launch_status();
+    if (rc != QERL_OK) return rc;
+    ReduceArgs ra{};
+    ra.partial = reinterpret_cast<const float*>(a.partial); ra.M = a.M; ra.Sk = a.Sk; ra.total_tiles = a.total_tiles;
+    for (int i = 0; i < kMaxGroup; ++i) ra.mem[i] = ReduceMember{a.mem[i].y, a.mem[i].ldy, a.mem[i].N, a.mem[i].tile_begin};
+    stream_reduce_kernel<MR><<<dim3((unsigned)ceil_div(a.total_tiles, 4)), dim3(256), 0, st>>>(ra);
+  }
   return launch_status();
 }
 

@@ -25,6 +25,13 @@ constexpr size_t kCtrlMainWords = 16384;   // arrival counters of the main kerne
 constexpr size_t kCtrlDownWords = 256;     // arrival counters of the LoRA down-projection kernel: r / 16 <= 256
 constexpr size_t kCtrlBytes = (kCtrlMainWords + kCtrlDownWords + 64) * sizeof(uint32_t);   // + hand-over words, 256-multiple
 
+// 17..128 tokens: room for the K-splits' partial outputs (up to 8 splits, capped); the K-parts' sums of the
+// LoRA down-projection follow it.
+static size_t mid_partial_bytes(int64_t M, int64_t N) {
+  const size_t b = (size_t)8 * (size_t)(M > 0 ? M : 1) * (size_t)(N > 0 ? N : 1) * sizeof(float);
+  return align256(b < kMidPartialCap ? b : kMidPartialCap);
+}
+
 static WorkspaceLayout workspace_layout(int64_t M, int64_t N, int64_t K, int64_t r) {
   WorkspaceLayout L;
   L.n_main_ctr = kCtrlMainWords;
@@ -34,7 +41,7 @@ static WorkspaceLayout workspace_layout(int64_t M, int64_t N, int64_t K, int64_t
   L.t_off = L.ctrl_bytes;
   // t = x A^T: fp32 [M, r] for the decode kernels, or three bf16 terms [M, ceil64(3r)] for the GEMM
   const size_t rows = (size_t)(M > 0 ? M : 1), rr = (size_t)(r > 0 ? r : 1);
-  const size_t t_f32 = rows * rr * sizeof(float), t_split = rows * (size_t)ceil_div(3 * rr, 64) * 64 * 2;
+  const size_t t_f32 = rows * rr * sizeof(float), t_split = rows * (size_t)ceil_div(3 * rr, 128) * 128 * 2;
   const size_t t_bytes = align256(t_f32 > t_split ? t_f32 : t_split);
   L.partial_off = L.t_off + t_bytes;
   // worst case over the plans the dispatchers can choose (one K-tile per wave)
@@ -46,6 +53,10 @@ static WorkspaceLayout workspace_layout(int64_t M, int64_t N, int64_t K, int64_t
   const size_t decode_bytes = S_dec * (size_t)ceil_div(N > 0 ? N : 1, kPackTileRows) * 8 * 64 * sizeof(float) +
                               S_down * n_down_ctr * 64 * sizeof(f32x4) + kDecodeTpartWords * sizeof(uint32_t);
   size_t need = skinny_bytes > decode_bytes ? skinny_bytes : decode_bytes;
+  if (M > 16 && M <= 128) {
+    const size_t mid = mid_partial_bytes(M, N) + kMidDownBytes;
+    need = need > mid ? need : mid;
+  }
   L.total = L.partial_off + align256(need);
   return L;
 }
@@ -297,6 +308,28 @@ extern "C" int nvfp4_lora_linear_packed(const void* x, int64_t M, int64_t K, int
   uint32_t* partial = (uint32_t*)(ws + L.partial_off);
 
   const bool lora_gemm_ok = r == 0 || (r % 8 == 0 && aligned(A, 16) && aligned(B, 16));
+  if (M > 16 && M <= 128 && lora_gemm_ok) {
+    // A few dozen tokens: the LoRA down-projection writes lora_scale * x A^T as three bf16 terms into the
+    // workspace, then the weight-streaming kernel computes the layer with those 3r columns appended to K.
+    MidArgs g{};
+    g.x = c.x; g.ldx = ldx; g.M = M; g.K = K; g.N = N; g.k_tiles = (int)ceil_div(K, kPackTileK);
+    g.ts = (const uint16_t*)(ws + L.t_off); g.ext_stages = (int)ceil_div(3 * r, 128); g.ts_ld = (int64_t)g.ext_stages * 128;
+    g.r = (int)r; g.tensor_scale = tensor_scale;
+    if (r > 0) {
+      GemmArgs d{};
+      d.x = c.x; d.ldx = ldx; d.M = M; d.K = K; d.k_tiles = g.k_tiles; d.ts = g.ts; d.ts_ld = g.ts_ld;
+      d.lora_scale = lora_scale; d.tensor_scale = tensor_scale;
+      d.N = r; d.wbf16 = c.A; d.n_tiles = (int)ceil_div(r, 32);
+      d.tpart = partial + mid_partial_bytes(M, N) / sizeof(uint32_t); d.counters = (uint32_t*)ws + L.n_main_ctr;
+      const int rc = launch_lora_down_gemm(d, c.st);
+      if (rc != QERL_OK) return rc;
+    }
+    g.packed = (const uint8_t*)packed; g.n_tiles = (int)ceil_div(N, 32);
+    g.B = c.B; g.y = c.y; g.ldy = ldy; g.partial = (float*)partial;
+    const int prc = plan_mid(g, mid_partial_bytes(M, N));
+    if (prc != QERL_OK) return prc;
+    return launch_mid(g, c.st);
+  }
   if (M > 16 && lora_gemm_ok) {
     // Prefill: one split-K GEMM writes lora_scale * x A^T as three bf16 terms into the workspace,
     // then one GEMM computes the layer with those 3r columns appended to K.

@@ -58,6 +58,29 @@ __device__ __forceinline__ float e2m1_to_f32(uint32_t c) {
   return __uint_as_float(__float_as_uint(mag) | ((c & 8u) << 28));
 }
 
+// 8 weights of one lane (one dword of codes) times their block scale -> bf16 x8
+__device__ __forceinline__ bf16x8 dequant8_bf16(uint32_t codes, float s) {
+  const f32x2 p0 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 0);
+  const f32x2 p1 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 1);
+  const f32x2 p2 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 2);
+  const f32x2 p3 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 3);
+  u32x4 o;
+  o[0] = pack_bf16x2(p0.x * s, p0.y * s);
+  o[1] = pack_bf16x2(p1.x * s, p1.y * s);
+  o[2] = pack_bf16x2(p2.x * s, p2.y * s);
+  o[3] = pack_bf16x2(p3.x * s, p3.y * s);
+  return __builtin_bit_cast(bf16x8, o);
+}
+
+__device__ __forceinline__ float e4m3_byte_f32(uint32_t v, int b) {
+  switch (b) {
+    case 0: return __builtin_amdgcn_cvt_f32_fp8(v, 0);
+    case 1: return __builtin_amdgcn_cvt_f32_fp8(v, 1);
+    case 2: return __builtin_amdgcn_cvt_f32_fp8(v, 2);
+    default: return __builtin_amdgcn_cvt_f32_fp8(v, 3);
+  }
+}
+
 // Sum of S fp32 values `stride` words apart, read with agent-scope atomic loads
 // (they bypass the per-XCD L2).  Loads are issued eight at a time before any
 // is consumed, and added in index order, so the result does not depend on timing.

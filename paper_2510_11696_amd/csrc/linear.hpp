@@ -76,9 +76,25 @@ struct GemmArgs {
   const uint16_t* B; int r; float lora_scale;
   uint16_t* y; int64_t ldy;
   int n_tiles; int n_blocks; int nblk_per_xcd;
+  uint32_t* tpart; uint32_t* counters;                                      // LoRA down-projection over several K-parts: partial sums, arrival counts (zero between calls); or null
 };
 int launch_gemm(const GemmArgs& a, hipStream_t st);
 int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st);
+
+// ---- 17..128 tokens: weight-streaming MFMA kernel on tile-packed weights (linear_mid.hip) ----
+constexpr size_t kMidPartialCap = (size_t)32 << 20;   // most workspace bytes the K-splits' partial outputs may take
+constexpr size_t kMidDownBytes = (size_t)64 * 2 * 16 * 64 * sizeof(float);   // K-parts' sums of the LoRA down-projection: at most 64 workgroups, two 32 x 32 tiles each
+struct MidArgs {
+  const uint16_t* x; int64_t ldx; int64_t M; int64_t K; int64_t N;
+  const uint8_t* packed; int k_tiles; const float* tensor_scale;
+  const uint16_t* ts; int64_t ts_ld; int ext_stages;                        // [M, ts_ld] bf16: hi | mid | lo of lora_scale / S32 * t; stages of 128 columns
+  const uint16_t* B; int r;
+  uint16_t* y; int64_t ldy;
+  float* partial;                                                           // [S][M][N] fp32 when S > 1
+  int n_tiles; int n_blocks; int m_chunks; int S; int kt_per_split; int MT; int W;
+};
+int plan_mid(MidArgs& a, size_t partial_cap_bytes);
+int launch_mid(const MidArgs& a, hipStream_t st);
 
 // General fallback (any K % 16 == 0, any alignment of rows the ABI allows).
 int launch_generic_lora_down(const uint16_t* x, int64_t ldx, int64_t M, int64_t K, const uint16_t* A,

@@ -29,29 +29,6 @@
 
 namespace qerl {
 
-// 8 weights of one lane (one dword of codes) times their block scale -> bf16 x8
-__device__ __forceinline__ bf16x8 dequant8_bf16(uint32_t codes, float s) {
-  const f32x2 p0 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 0);
-  const f32x2 p1 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 1);
-  const f32x2 p2 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 2);
-  const f32x2 p3 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 3);
-  u32x4 o;
-  o[0] = pack_bf16x2(p0.x * s, p0.y * s);
-  o[1] = pack_bf16x2(p1.x * s, p1.y * s);
-  o[2] = pack_bf16x2(p2.x * s, p2.y * s);
-  o[3] = pack_bf16x2(p3.x * s, p3.y * s);
-  return __builtin_bit_cast(bf16x8, o);
-}
-
-__device__ __forceinline__ float e4m3_byte_f32(uint32_t v, int b) {
-  switch (b) {
-    case 0: return __builtin_amdgcn_cvt_f32_fp8(v, 0);
-    case 1: return __builtin_amdgcn_cvt_f32_fp8(v, 1);
-    case 2: return __builtin_amdgcn_cvt_f32_fp8(v, 2);
-    default: return __builtin_amdgcn_cvt_f32_fp8(v, 3);
-  }
-}
-
 __device__ __forceinline__ void split3_bf16(const float (&v)[8], u32x4& hi, u32x4& mid, u32x4& lo) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -235,19 +212,25 @@ __global__ __launch_bounds__(512) void lora_down32_kernel(const GemmArgs a) {
   mrow = mrow < a.M ? mrow : a.M - 1;
   const uint16_t* xrow = a.x + mrow * a.ldx + 8 * kg;
 
+  // K-part of this workgroup (gridDim.z parts, whole 64-column chunks each)
+  const int P = (int)gridDim.z;
+  const int64_t part_cols = ceil_div_dev(ceil_div_dev(a.K, 64), P) * 64;
+  const int64_t k_lo = (int64_t)blockIdx.z * part_cols;
+  const int64_t k_hi = k_lo + part_cols < a.K ? k_lo + part_cols : a.K;
+
   struct Chunk { u32x4 x[4]; u32x4 w[NT][4]; };   // 64 columns = 4 MFMA steps
   auto load = [&](Chunk& c, int64_t kb) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int64_t k = kb + 16 * j + 8 * kg;
       c.x[j] = u32x4{0u, 0u, 0u, 0u};
-      if (k < a.K) c.x[j] = *reinterpret_cast<const u32x4*>(xrow + kb + 16 * j);
+      if (k < k_hi) c.x[j] = *reinterpret_cast<const u32x4*>(xrow + kb + 16 * j);
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
         int64_t row = (int64_t)(nt0 + nt) * 32 + n32;
         row = row < a.N ? row : a.N - 1;
         c.w[nt][j] = u32x4{0u, 0u, 0u, 0u};
-        if (k < a.K) c.w[nt][j] = *reinterpret_cast<const u32x4*>(a.wbf16 + row * a.K + k);
+        if (k < k_hi) c.w[nt][j] = *reinterpret_cast<const u32x4*>(a.wbf16 + row * a.K + k);
       }
     }
   };
@@ -266,14 +249,14 @@ __global__ __launch_bounds__(512) void lora_down32_kernel(const GemmArgs a) {
   };
   Chunk c0, c1;
   const int64_t step = (int64_t)kWaves * 64;
-  int64_t kb = (int64_t)wave * 64;
-  if (kb < a.K) load(c0, kb);
-  while (kb < a.K) {
-    const bool has1 = kb + step < a.K;
+  int64_t kb = k_lo + (int64_t)wave * 64;
+  if (kb < k_hi) load(c0, kb);
+  while (kb < k_hi) {
+    const bool has1 = kb + step < k_hi;
     if (has1) load(c1, kb + step);
     mma(c0);
     if (!has1) break;
-    const bool has2 = kb + 2 * step < a.K;
+    const bool has2 = kb + 2 * step < k_hi;
     if (has2) load(c0, kb + 2 * step);
     mma(c1);
     kb += 2 * step;
@@ -289,6 +272,36 @@ __global__ __launch_bounds__(512) void lora_down32_kernel(const GemmArgs a) {
   }
   __syncthreads();
   if (wave != 0) return;
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+#pragma unroll
+      for (int w = 0; w < kWaves - 1; ++w) acc[nt][i] += red[w][nt * 16 + i][lane];
+    }
+  if (P > 1) {
+    // Several K-parts: every part leaves its sums in the workspace (written through to memory before its
+    // arrival is counted); the workgroup that arrives last adds all parts in part order and goes on.
+    const int slot = blockIdx.x * gridDim.y + blockIdx.y;
+    const int64_t part_stride = (int64_t)gridDim.x * gridDim.y * (NT * 16 * 64);
+    uint32_t* mine = a.tpart + (int64_t)blockIdx.z * part_stride + (int64_t)slot * (NT * 16 * 64) + lane;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        __hip_atomic_store(mine + (nt * 16 + i) * 64, __float_as_uint(acc[nt][i]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    uint32_t old = 0;
+    if (lane == 0) old = __hip_atomic_fetch_add(a.counters + slot, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    old = __builtin_amdgcn_readfirstlane(old);
+    if (old != (uint32_t)(P - 1)) return;
+    const uint32_t* all = a.tpart + (int64_t)slot * (NT * 16 * 64) + lane;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[nt][i] = ordered_sum_sc1(all + (nt * 16 + i) * 64, part_stride, P);
+    if (lane == 0) __hip_atomic_store(a.counters + slot, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+  }
   uint16_t* ts = const_cast<uint16_t*>(a.ts);
   const float t_mult = a.lora_scale / *a.tensor_scale;   // undone by the final * S32 of the main launch
 #pragma unroll
@@ -296,9 +309,7 @@ __global__ __launch_bounds__(512) void lora_down32_kernel(const GemmArgs a) {
     const int64_t n = (int64_t)(nt0 + nt) * 32 + n32;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      float sum = acc[nt][i];
-#pragma unroll
-      for (int w = 0; w < kWaves - 1; ++w) sum += red[w][nt * 16 + i][lane];
+      const float sum = acc[nt][i];
       const int64_t m = m0 + 8 * (i >> 2) + 4 * kg + (i & 3);
       if (m < a.M && n < a.N) {
         const float v = sum * t_mult;
@@ -375,7 +386,17 @@ int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st) {
   if (!a.x || !a.wbf16 || !a.tensor_scale || !a.ts) return QERL_ERR_NULL;
   if (a.M < 1 || a.N < 1 || a.K < 16 || a.ts_ld < 3 * a.N) return QERL_ERR_SHAPE;
   const int tiles = (int)ceil_div(a.N, 32);
-  const dim3 grid((unsigned)ceil_div(a.M, 32), (unsigned)ceil_div(tiles, tiles >= 2 ? 2 : 1));
+  // With few token blocks K is split over workgroups (about 64 in all, at least 512 columns each) when the
+  // caller provides the exchange area.
+  int64_t P = 1;
+  const int64_t base_wgs = ceil_div(a.M, 32) * ceil_div(tiles, tiles >= 2 ? 2 : 1);
+  if (a.tpart && a.counters && base_wgs < 32) {
+    P = 64 / base_wgs;
+    const int64_t p_max = ceil_div(a.K, 512);
+    P = P < p_max ? P : p_max;
+    P = P > 64 ? 64 : (P < 1 ? 1 : P);
+  }
+  const dim3 grid((unsigned)ceil_div(a.M, 32), (unsigned)ceil_div(tiles, tiles >= 2 ? 2 : 1), (unsigned)P);
   if (tiles >= 2) lora_down32_kernel<2><<<grid, 512, 0, st>>>(a);
   else lora_down32_kernel<1><<<grid, 512, 0, st>>>(a);
   return launch_status();

@@ -1,0 +1,269 @@
+// NVFP4 + LoRA linear for 17..128 tokens: too many for the accumulator-side scaling of the decode
+// kernels (its cost grows with the token count), too few for the prefill GEMM to fill the chip (one
+// block of token rows, so only N / 256 workgroups, each waiting for one 64-input stage at a time).
+//
+//   y[m,n] = S32 * sum_k x[m,k] * (s[n,k/16] * e[n,k]) + lora_scale * sum_j t[m,j] * B[n,j]
+//                                                                    (Eq. 6, Eq. 2)
+// Here the layer is bound by streaming the packed weights (up to ~64 tokens) or by the MFMA rate
+// (128 tokens), and in both cases by memory latency unless enough loads are in flight.  So:
+//
+//   * A workgroup of W waves owns W adjacent row-tiles (32 output rows each, one per wave) for ALL
+//     tokens (BM = 32*MT >= M) and walks K in stages of one packed K-tile (128 inputs, 2304 bytes per
+//     wave).  Every weight is dequantised once: codes -> (cvt, * block scale, pack) -> bf16 MFMA B
+//     operand; s * e has at most 6 significant bits, exact in bf16.
+//   * Weights go global -> registers through a ring of kRing stages per wave (seven K-tiles requested
+//     ahead of the one in use); nothing of the weight stream touches LDS.
+//   * x is the shared operand: the BM x 128 slab of a stage is requested kXAhead stages ahead into
+//     registers, written to one of two LDS buffers a stage before it is used (16-byte chunks
+//     XOR-swizzled by row: the A-operand reads of 16 rows at one column hit 16 distinct bank groups),
+//     one barrier per stage.
+//   * K can be split over S workgroups per row-tile group when N alone gives too few workgroups; each
+//     split writes its fp32 partial [M, N] to the workspace and mid_reduce_kernel adds the splits in
+//     order.  No workgroup waits for another.
+//   * LoRA: ts = [hi | mid | lo] (three bf16 terms of (lora_scale / S32) * x A^T, produced by the
+//     prefill path's down-projection kernel) enters as 3r more input columns against [B ; B ; B]; the
+//     accumulators are multiplied by S32 once at the end (split 0 carries the LoRA columns).
+//
+// Operand layouts and the packed tile format are described in linear_decode.hip.
+#include "linear.hpp"
+
+namespace qerl {
+
+constexpr int kRing = 8;      // weight stages per wave: one in use, seven requested
+constexpr int kXAhead = 4;    // x slabs in registers
+
+struct MidTile { u32x4 c0, c1; u32x2 sc; };   // one wave's share of a packed tile: 2 x 4 steps x 8 codes, 8 scale bytes
+
+template <int MT, int W>
+__global__ __launch_bounds__(W * 64) void mid_kernel(const MidArgs a) {
+  constexpr int BM = MT * 32;
+  constexpr int kThreads = W * 64;
+  constexpr int kChunks = BM * 16;                 // 16-byte chunks of one x slab (BM x 128)
+  constexpr int XL = kChunks / kThreads;           // chunks per thread
+  static_assert(kChunks % kThreads == 0 && kRing % kXAhead == 0 && kRing % 2 == 0, "ring sizes");
+  // x slab [2][BM][16 chunks]; chunk c of row r sits at r*16 + (c ^ (r & 15))
+  extern __shared__ __attribute__((aligned(256))) u32x4 xs[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n32 = lane & 31, kg = lane >> 5;
+  // Workgroup ids go round-robin to the 8 XCDs: the splits and token blocks of one row-tile group get ids
+  // that are equal mod 8, i.e. they share an L2.
+  const int inner_n = a.m_chunks * a.S;
+  const int xcd = blockIdx.x & 7, rest = blockIdx.x >> 3;
+  const int inner = rest % inner_n;
+  const int nb = (rest / inner_n) * 8 + xcd;
+  if (nb >= a.n_blocks) return;                    // padding of the last group of eight (uniform)
+  const int chunk = inner / a.S, split = inner % a.S;
+  const int64_t m0 = (int64_t)chunk * BM;
+  const int nt = nb * W + wave;
+  const int nt_ld = nt < a.n_tiles ? nt : a.n_tiles - 1;
+  const int kt0 = split * a.kt_per_split;
+  const int kt1 = kt0 + a.kt_per_split < a.k_tiles ? kt0 + a.kt_per_split : a.k_tiles;
+  const int n = kt1 - kt0;                         // >= 1 (host)
+
+  f32x16 acc[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[mt][i] = 0.f;
+
+  // ---- loaders (stage kt covers columns [128 kt, 128 kt + 128) of the row-major bf16 matrix `src`)
+  auto gload_x = [&](u32x4 (&r)[XL], const uint16_t* src, int64_t ld, int64_t cols, int kt) {
+#pragma unroll
+    for (int i = 0; i < XL; ++i) {
+      const int idx = tid + i * kThreads;
+      const int row = idx >> 4, c = idx & 15;
+      int64_t gr = m0 + row;
+      gr = gr < a.M ? gr : a.M - 1;
+      int64_t k = (int64_t)kt * 128 + c * 8;
+      k = k < cols ? k : cols - 8;      // past the end the other operand is zero; any finite value will do
+      r[i] = *reinterpret_cast<const u32x4*>(src + gr * ld + k);
+    }
+  };
+  auto swrite_x = [&](int buf, const u32x4 (&r)[XL]) {
+#pragma unroll
+    for (int i = 0; i < XL; ++i) {
+      const int idx = tid + i * kThreads;
+      const int row = idx >> 4, c = idx & 15;
+      xs[buf * kChunks + row * 16 + (c ^ (row & 15))] = r[i];
+    }
+  };
+  const uint8_t* wbase = a.packed + (int64_t)nt_ld * a.k_tiles * kPackTileBytes;
+  auto gload_w = [&](MidTile& t, int kt) {
+    const uint8_t* base = wbase + (int64_t)kt * kPackTileBytes;
+    t.c0 = *reinterpret_cast<const u32x4*>(base + lane * 16);
+    t.c1 = *reinterpret_cast<const u32x4*>(base + 1024 + lane * 16);
+    t.sc = *reinterpret_cast<const u32x2*>(base + 2048 + n32 * 8);
+  };
+  auto mma_step = [&](const u32x4* xst, int j, bf16x8 wf) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int row = mt * 32 + n32;
+      const bf16x8 af = __builtin_bit_cast(bf16x8, xst[row * 16 + ((2 * j + kg) ^ (row & 15))]);
+      acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, wf, acc[mt], 0, 0, 0);
+    }
+  };
+  auto compute = [&](int buf, const MidTile& t) {
+    const u32x4* xst = xs + buf * kChunks;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const uint32_t codes = j < 4 ? t.c0[j & 3] : t.c1[j & 3];
+      const float s = e4m3_byte_f32(j < 4 ? t.sc[0] : t.sc[1], j & 3);
+      mma_step(xst, j, dequant8_bf16(codes, s));
+    }
+  };
+
+  MidTile wr[kRing];
+  u32x4 xr[kXAhead][XL];
+  // ---- prologue: the first slabs and weight stages are requested, slab 0 goes to LDS.  Requests past the
+  // end of the range are not skipped but redirected to its last stage (a few redundant loads that hit in
+  // L2): with no branches around the loads the compiler's wait counts stay exact, and a wave never waits for
+  // more than the stage it needs.
+  const int kt_last = kt1 - 1;
+  auto clamp_kt = [&](int kt) { return kt < kt_last ? kt : kt_last; };
+#pragma unroll
+  for (int p = 0; p < kXAhead; ++p) gload_x(xr[p], a.x, a.ldx, a.K, clamp_kt(kt0 + p));
+#pragma unroll
+  for (int d = 0; d < kRing - 1; ++d) gload_w(wr[d], clamp_kt(kt0 + d));
+  swrite_x(0, xr[0]);
+  __syncthreads();
+  // ---- main loop, unrolled over the ring so that every register array index is a constant: whole rounds of
+  // the ring without a branch inside, then the remaining stages as straight-line code with forward exits only
+  auto stage = [&](int i, int u) {
+    gload_x(xr[u % kXAhead], a.x, a.ldx, a.K, clamp_kt(kt0 + i + kXAhead));
+    gload_w(wr[(u + kRing - 1) % kRing], clamp_kt(kt0 + i + kRing - 1));
+    compute(u & 1, wr[u]);
+    swrite_x((u + 1) & 1, xr[(u + 1) % kXAhead]);
+    __syncthreads();
+  };
+  int i0 = 0;
+  for (; i0 + kRing <= n; i0 += kRing) {
+#pragma unroll
+    for (int u = 0; u < kRing; ++u) stage(i0 + u, u);
+  }
+#pragma unroll
+  for (int u = 0; u < kRing - 1; ++u) {
+    if (i0 + u >= n) goto main_done;
+    stage(i0 + u, u);
+  }
+main_done:
+
+  // ---- LoRA up-projection: 3r extra columns [hi | mid | lo] . [B ; B ; B]^T.  ts already carries the
+  // factor lora_scale / S32, so one multiplication by S32 at the end scales both branches.
+  if (split == 0) {
+    for (int e = 0; e < a.ext_stages; ++e) {
+      gload_x(xr[0], a.ts, a.ts_ld, a.ts_ld, e);
+      swrite_x(0, xr[0]);
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        int64_t row = (int64_t)nt * 32 + n32;
+        row = row < a.N ? row : a.N - 1;
+        const int c = e * 128 + 16 * j + 8 * kg;
+        u32x4 b = {0u, 0u, 0u, 0u};
+        if (c < 3 * a.r) b = *reinterpret_cast<const u32x4*>(a.B + row * a.r + (c % a.r));
+        mma_step(xs, j, __builtin_bit_cast(bf16x8, b));
+      }
+      __syncthreads();
+    }
+  }
+  const float S32 = *a.tensor_scale;
+  const int64_t nn = (int64_t)nt * 32 + n32;
+  if (nt >= a.n_tiles || nn >= a.N) return;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int64_t m = m0 + mt * 32 + 8 * (i >> 2) + 4 * kg + (i & 3);
+      if (m < a.M) {
+        const float v = acc[mt][i] * S32;
+        if (a.S == 1) a.y[m * a.ldy + nn] = (uint16_t)f32_to_bf16_bits(v);
+        else a.partial[((int64_t)split * a.M + m) * a.N + nn] = v;
+      }
+    }
+}
+
+// y = sum over the K-splits, in split order, of the fp32 partial outputs [S][M][N].  Grid: (N / 256, M).
+__global__ __launch_bounds__(256) void mid_reduce_kernel(const float* partial, int S, int64_t M, int64_t N, uint16_t* y,
+                                                         int64_t ldy) {
+  const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x, m = blockIdx.y;
+  if (n >= N) return;
+  const float* p = partial + m * N + n;
+  float v[8];
+#pragma unroll
+  for (int s = 0; s < 8; ++s) v[s] = s < S ? p[(int64_t)s * M * N] : 0.f;
+  float sum = 0.f;
+#pragma unroll
+  for (int s = 0; s < 8; ++s) sum += v[s];
+  y[m * ldy + n] = (uint16_t)f32_to_bf16_bits(sum);
+}
+
+// ---- host ------------------------------------------------------------------------------------------
+
+static int g_force_w = 0, g_force_s = 0;
+
+template <int MT, int W>
+static int launch_mid_t(const MidArgs& a, hipStream_t st) {
+  constexpr size_t lds = 2 * (size_t)MT * 32 * 16 * sizeof(u32x4);
+  const int64_t groups = ceil_div(a.n_blocks, 8);
+  mid_kernel<MT, W><<<dim3((unsigned)(groups * 8 * a.m_chunks * a.S)), dim3(W * 64), lds, st>>>(a);
+  return launch_status();
+}
+
+int plan_mid(MidArgs& a, size_t partial_cap_bytes) {
+  if (a.M < 1 || a.M > 128 || a.n_tiles < 1 || a.k_tiles < 1) return QERL_ERR_SHAPE;
+  const int MT = a.M <= 32 ? 1 : a.M <= 64 ? 2 : 4;
+  a.MT = MT; a.m_chunks = (int)ceil_div(a.M, 32 * MT);
+  // Waves per workgroup and K-splits: the pair with the shortest estimated time.  A wave spends about
+  // 650 + 350 MT cycles on a stage (dequantisation plus MT x 8 MFMAs); workgroups spread evenly over the 256
+  // CUs, their waves over the CU's four SIMDs.  A split costs a second launch and the partial sums' traffic.
+  const int w_opts[2] = {MT == 4 ? 4 : 2, MT == 4 ? 8 : 4};
+  const double cyc = 650.0 + 350.0 * MT;
+  double best = 0;
+  a.W = 0;
+  for (int wi = 0; wi < 2; ++wi) {
+    const int W = w_opts[wi];
+    if (g_force_w > 0 && W != g_force_w) continue;
+    for (int S = 1; S <= 8; ++S) {
+      if (g_force_s > 0 && S != g_force_s) continue;
+      if (S > 1 && ((size_t)S * a.M * a.N * sizeof(float) > partial_cap_bytes || a.k_tiles / S < 4)) continue;
+      const int64_t per = ceil_div(a.k_tiles, S), S_eff = ceil_div(a.k_tiles, per);
+      if (S_eff != S) continue;
+      const int64_t wgs = ceil_div(a.n_tiles, W) * a.m_chunks * S;
+      const int64_t on_cu = ceil_div(wgs, 256), per_simd = ceil_div(on_cu * W, 4);
+      double us = (double)(per_simd * per) * cyc / 2400.0;
+      if (S > 1) us += 4.0 + 2.0 * (double)S * a.M * a.N * sizeof(float) / 4.0e6;
+      if (a.W == 0 || us < best) { best = us; a.W = W; a.S = S; a.kt_per_split = (int)per; }
+    }
+  }
+  if (a.W == 0) return QERL_ERR_SHAPE;
+  a.n_blocks = (int)ceil_div(a.n_tiles, a.W);
+  return QERL_OK;
+}
+
+int launch_mid(const MidArgs& a, hipStream_t st) {
+  // every pointer the kernel dereferences must be set by the caller
+  if (!a.x || !a.packed || !a.tensor_scale || !a.y || (a.r > 0 && (!a.ts || !a.B)) || (a.S > 1 && !a.partial)) return QERL_ERR_NULL;
+  if (a.M < 1 || a.M > 128 || a.N < 1 || a.K < 16 || a.n_tiles < 1 || a.k_tiles < 1 || a.S < 1 || a.kt_per_split < 1 ||
+      (int64_t)a.kt_per_split * a.S < a.k_tiles || (int64_t)a.kt_per_split * (a.S - 1) >= a.k_tiles ||
+      (int64_t)a.m_chunks * a.MT * 32 < a.M || (int64_t)a.n_blocks * a.W < a.n_tiles ||
+      (a.r > 0 && (a.ts_ld < 3 * a.r || a.ts_ld != (int64_t)a.ext_stages * 128)) || (a.r == 0 && a.ext_stages != 0))
+    return QERL_ERR_SHAPE;
+  int rc = QERL_ERR_SHAPE;
+  if (a.MT == 1 && a.W == 2) rc = launch_mid_t<1, 2>(a, st);
+  else if (a.MT == 1 && a.W == 4) rc = launch_mid_t<1, 4>(a, st);
+  else if (a.MT == 2 && a.W == 2) rc = launch_mid_t<2, 2>(a, st);
+  else if (a.MT == 2 && a.W == 4) rc = launch_mid_t<2, 4>(a, st);
+  else if (a.MT == 4 && a.W == 4) rc = launch_mid_t<4, 4>(a, st);
+  else if (a.MT == 4 && a.W == 8) rc = launch_mid_t<4, 8>(a, st);
+  if (rc != QERL_OK || a.S == 1) return rc;
+  if (a.S > 8) return QERL_ERR_SHAPE;
+  mid_reduce_kernel<<<dim3((unsigned)ceil_div(a.N, 256), (unsigned)a.M), dim3(256), 0, st>>>(a.partial, a.S, a.M, a.N, a.y, a.ldy);
+  return launch_status();
+}
+
+}  // namespace qerl
+
+// Tuning hook for experiments (not part of the public header): waves per workgroup and K-splits, 0 = automatic.
+extern "C" QERL_API void qerl_debug_force_mid(int waves, int splits) { qerl::g_force_w = waves; qerl::g_force_s = splits; }

@@ -84,6 +84,20 @@ def test_more_than_16_tokens(M, packed):
     _run(M, 512, 3584, 32, seed=M, packed=packed)
 
 
+@pytest.mark.parametrize("M,N,K,r", [
+    (17, 1000, 2112, 16),    # ragged N, K not a multiple of 128, one token past the decode kernels
+    (32, 3584, 3584, 32),    # exactly one block of token rows
+    (33, 96, 18944, 32),     # long K: split over workgroups, partial outputs added by the second kernel
+    (64, 4736, 3584, 0),     # no adapter
+    (65, 70, 1024, 64),      # ragged last tile, rank 64
+    (100, 37, 48, 8),        # K smaller than one packed tile
+    (128, 2048, 5120, 32),
+    (128, 160, 27648, 8),    # longest K of the 32B shapes
+])
+def test_a_few_dozen_tokens_on_packed_weights(M, N, K, r):
+    _run(M, N, K, r, seed=M + N + K + r, packed=True)
+
+
 @pytest.mark.parametrize("packed", PATHS)
 def test_adversarial_weights_through_the_linear(packed):
     for name, W in cases.quantizer_cases(48, 512, seed=31).items():

@@ -200,6 +200,8 @@ __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
 // A skinny GEMM (r <= 64 output columns per block) that is bound by reading x once.  One workgroup owns
 // 32 tokens; its eight waves split K in interleaved 64-column chunks, read both operands straight from
 // global memory in MFMA operand layout (double buffered in registers), and are summed through LDS.
+constexpr int kDownMaxParts = 8;   // K-parts of the LoRA down-projection when there are few token blocks
+
 template <int NT>
 __global__ __launch_bounds__(512) void lora_down32_kernel(const GemmArgs a) {
   constexpr int kWaves = 8;
@@ -297,9 +299,23 @@ __global__ __launch_bounds__(512) void lora_down32_kernel(const GemmArgs a) {
     if (old != (uint32_t)(P - 1)) return;
     const uint32_t* all = a.tpart + (int64_t)slot * (NT * 16 * 64) + lane;
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
+    for (int nt = 0; nt < NT; ++nt) {
+      uint32_t v[kDownMaxParts][16];        // one tile's values of all parts requested together
 #pragma unroll
-      for (int i = 0; i < 16; ++i) acc[nt][i] = ordered_sum_sc1(all + (nt * 16 + i) * 64, part_stride, P);
+      for (int z = 0; z < kDownMaxParts; ++z)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          v[z][i] = 0u;
+          if (z < P) v[z][i] = __hip_atomic_load(all + (int64_t)z * part_stride + (nt * 16 + i) * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        float sum = 0.f;
+#pragma unroll
+        for (int z = 0; z < kDownMaxParts; ++z) sum += __uint_as_float(v[z][i]);
+        acc[nt][i] = sum;
+      }
+    }
     if (lane == 0) __hip_atomic_store(a.counters + slot, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
   }
   uint16_t* ts = const_cast<uint16_t*>(a.ts);
@@ -386,15 +402,15 @@ int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st) {
   if (!a.x || !a.wbf16 || !a.tensor_scale || !a.ts) return QERL_ERR_NULL;
   if (a.M < 1 || a.N < 1 || a.K < 16 || a.ts_ld < 3 * a.N) return QERL_ERR_SHAPE;
   const int tiles = (int)ceil_div(a.N, 32);
-  // With few token blocks K is split over workgroups (about 64 in all, at least 512 columns each) when the
-  // caller provides the exchange area.
+  // With few token blocks K is split over workgroups (up to eight parts, at least 512 columns each) when
+  // the caller provides the exchange area.
   int64_t P = 1;
   const int64_t base_wgs = ceil_div(a.M, 32) * ceil_div(tiles, tiles >= 2 ? 2 : 1);
   if (a.tpart && a.counters && base_wgs < 32) {
     P = 64 / base_wgs;
     const int64_t p_max = ceil_div(a.K, 512);
     P = P < p_max ? P : p_max;
-    P = P > 64 ? 64 : (P < 1 ? 1 : P);
+    P = P > kDownMaxParts ? kDownMaxParts : (P < 1 ? 1 : P);
   }
   const dim3 grid((unsigned)ceil_div(a.M, 32), (unsigned)ceil_div(tiles, tiles >= 2 ? 2 : 1), (unsigned)P);
   if (tiles >= 2) lora_down32_kernel<2><<<grid, 512, 0, st>>>(a);

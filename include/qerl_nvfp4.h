@@ -98,7 +98,11 @@ QERL_API int nvfp4_dequantize(const uint8_t* codes, const uint8_t* scales, const
  *   workspace: >= nvfp4_lora_linear_workspace_bytes(M,N,K,r) bytes, 256-byte
  *     aligned, prepared ONCE with qerl_workspace_init() and afterwards used
  *     only by this library.  Calls that share a workspace must be ordered on
- *     one stream.  A call that returned an error leaves it valid.
+ *     one stream.  A call that returned an error leaves it valid.  The control
+ *     words sit at fixed offsets, so one workspace sized for the largest call
+ *     (every argument at its maximum) serves calls of any smaller shape.
+ *   tensor_scale: device pointer to one fp32, finite and non-zero (the
+ *     quantizer never writes 0: an all-zero tensor gets 1).
  *
  * Any M >= 0 is accepted (M == 0 is a no-op).  The tiled MFMA kernels need
  * K % 64 == 0, x, codes and A 16-byte aligned, scales 4-byte aligned and

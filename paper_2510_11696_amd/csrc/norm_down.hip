@@ -8,7 +8,8 @@
 // over slices of K, which its epilogue adds in slice order, so that no workgroup of this kernel has
 // to wait for another either.
 //
-// QERL_T_PARTS workgroups of 512 threads; workgroup p owns the p-th slice of K (whole 16-input steps):
+// QERL_T_PARTS x (32-rank tiles of the stacked adapters) workgroups of 512 threads; workgroup (p, tile) owns the
+// p-th slice of K (whole 16-input steps) and one tile; the tile-0 workgroups write y:
 //   1. wave w reads row w (and w + 8) whole and forms its sum of squares -- one wave per row, so no
 //      exchange between waves; 1 / rms of every row goes to LDS;
 //   2. the slice's columns of every row (requested at the start as well) are normalised, rounded,
@@ -59,6 +60,7 @@ __global__ __launch_bounds__(kNdThreads) void norm_down_kernel(const NormDownArg
   const int chunks = (int)(a.H / 8);
   const int n32 = lane & 31, kg = lane >> 5;
   const int part = (int)blockIdx.x;
+  const int tile0 = (int)blockIdx.y * NT;   // first 32-rank tile of the stacked adapters this workgroup multiplies
   const int n_steps = (int)(a.H / 16);
   const int step0 = part * a.steps_per_part;
   const int step1 = step0 + a.steps_per_part < n_steps ? step0 + a.steps_per_part : n_steps;
@@ -105,7 +107,7 @@ __global__ __launch_bounds__(kNdThreads) void norm_down_kernel(const NormDownArg
   bool live[NT];
 #pragma unroll
   for (int tl = 0; tl < NT; ++tl) {
-    const int s = tl * 32 + n32;           // stacked rank this lane feeds in tile tl
+    const int s = (tile0 + tl) * 32 + n32; // stacked rank this lane feeds in tile tl
     int ad = 0, off = 0;
     if (s >= a.off1) { ad = 1; off = a.off1; }
     if (s >= a.off2) { ad = 2; off = a.off2; }
@@ -168,7 +170,7 @@ __global__ __launch_bounds__(kNdThreads) void norm_down_kernel(const NormDownArg
         o[j] = pack_bf16x2(ga * (xa * inv), gb * (xb * inv));
       }
       *reinterpret_cast<u32x4*>(smem + row * a.xs_stride + cs * 16) = o;
-      reinterpret_cast<u32x4*>(a.y + (int64_t)row * a.ldy)[c_lo + cs] = o;
+      if (blockIdx.y == 0) reinterpret_cast<u32x4*>(a.y + (int64_t)row * a.ldy)[c_lo + cs] = o;
     }
   }
   NDT(3);
@@ -213,7 +215,7 @@ __global__ __launch_bounds__(kNdThreads) void norm_down_kernel(const NormDownArg
 #pragma unroll
     for (int w = 0; w < kNdWaves; ++w) sum += red[w * NT * MR * 64 + e];
     const int tl = e / (MR * 64), q = (e >> 6) % MR, l = e & 63;
-    const int tok = 8 * (q >> 2) + 4 * (l >> 5) + (q & 3), s = tl * 32 + (l & 31);
+    const int tok = 8 * (q >> 2) + 4 * (l >> 5) + (q & 3), s = (tile0 + tl) * 32 + (l & 31);
     if (tok < a.M && s < a.r_total) {
       int ad = 0, off = 0;
       if (s >= a.off1) { ad = 1; off = a.off1; }
@@ -243,17 +245,14 @@ static int launch_norm_down_t(const NormDownArgs& a, size_t lds, hipStream_t st)
       return launch_status();
     attr_set = true;
   }
-  norm_down_kernel<MR, NCL, NT><<<kNdParts, kNdThreads, lds, st>>>(a);
+  norm_down_kernel<MR, NCL, NT><<<dim3(kNdParts, (unsigned)ceil_div(a.n_tiles, NT)), kNdThreads, lds, st>>>(a);
   return launch_status();
 }
+// One 32-rank tile per workgroup: the tiles' workgroups repeat the (cheap) normalisation, and each has a
+// third or a quarter of the A fragments to wait for.
 template <int MR, int NCL>
 static int launch_norm_down(const NormDownArgs& a, size_t lds, hipStream_t st) {
-  switch (a.n_tiles) {
-    case 1: return launch_norm_down_t<MR, NCL, 1>(a, lds, st);
-    case 2: return launch_norm_down_t<MR, NCL, 2>(a, lds, st);
-    case 3: return launch_norm_down_t<MR, NCL, 3>(a, lds, st);
-    default: return launch_norm_down_t<MR, NCL, 4>(a, lds, st);
-  }
+  return launch_norm_down_t<MR, NCL, 1>(a, lds, st);
 }
 
 extern "C" int aqn_rmsnorm_lora_down(const void* x, int64_t M, int64_t H, int64_t ldx, const void* gain,
@@ -288,7 +287,7 @@ extern "C" int aqn_rmsnorm_lora_down(const void* x, int64_t M, int64_t H, int64_
   a.steps_per_part = (int)ceil_div(H / 16, kNdParts);
   a.xs_stride = a.steps_per_part * 32 + 16;                // rows 16 bytes apart in bank space
   const int MR = M <= 8 ? 4 : 8;
-  const size_t lds = (size_t)(M + 1) * a.xs_stride + (size_t)kNdWaves * a.n_tiles * MR * 64 * sizeof(float);
+  const size_t lds = (size_t)(M + 1) * a.xs_stride + (size_t)kNdWaves * 1 * MR * 64 * sizeof(float);
   if (lds > 128 * 1024) return QERL_ERR_SHAPE;             // cannot happen for H <= 8192; keeps the launch legal
   hipStream_t st = (hipStream_t)stream;
   const bool wide = H > 4096;

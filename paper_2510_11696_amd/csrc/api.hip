@@ -308,7 +308,8 @@ extern "C" int nvfp4_lora_linear_packed(const void* x, int64_t M, int64_t K, int
   uint32_t* partial = (uint32_t*)(ws + L.partial_off);
 
   const bool lora_gemm_ok = r == 0 || (r % 8 == 0 && aligned(A, 16) && aligned(B, 16));
-  if (M > 16 && M <= 128 && lora_gemm_ok) {
+  if (M > 16 && M <= g_mid_max_tokens && lora_gemm_ok) {
+    const bool few = M <= 128;   // K-splits and their workspace areas exist for these only
     // A few dozen tokens: the LoRA down-projection writes lora_scale * x A^T as three bf16 terms into the
     // workspace, then the weight-streaming kernel computes the layer with those 3r columns appended to K.
     MidArgs g{};
@@ -320,13 +321,13 @@ extern "C" int nvfp4_lora_linear_packed(const void* x, int64_t M, int64_t K, int
       d.x = c.x; d.ldx = ldx; d.M = M; d.K = K; d.k_tiles = g.k_tiles; d.ts = g.ts; d.ts_ld = g.ts_ld;
       d.lora_scale = lora_scale; d.tensor_scale = tensor_scale;
       d.N = r; d.wbf16 = c.A; d.n_tiles = (int)ceil_div(r, 32);
-      d.tpart = partial + mid_partial_bytes(M, N) / sizeof(uint32_t); d.counters = (uint32_t*)ws + L.n_main_ctr;
+      d.tpart = few ? partial + mid_partial_bytes(M, N) / sizeof(uint32_t) : nullptr; d.counters = (uint32_t*)ws + L.n_main_ctr;
       const int rc = launch_lora_down_gemm(d, c.st);
       if (rc != QERL_OK) return rc;
     }
     g.packed = (const uint8_t*)packed; g.n_tiles = (int)ceil_div(N, 32);
     g.B = c.B; g.y = c.y; g.ldy = ldy; g.partial = (float*)partial;
-    const int prc = plan_mid(g, mid_partial_bytes(M, N));
+    const int prc = plan_mid(g, few ? mid_partial_bytes(M, N) : 0);
     if (prc != QERL_OK) return prc;
     return launch_mid(g, c.st);
   }

@@ -93,6 +93,7 @@ struct MidArgs {
   float* partial;                                                           // [S][M][N] fp32 when S > 1
   int n_tiles; int n_blocks; int m_chunks; int S; int kt_per_split; int MT; int W;
 };
+extern int g_mid_max_tokens;
 int plan_mid(MidArgs& a, size_t partial_cap_bytes);
 int launch_mid(const MidArgs& a, hipStream_t st);
 

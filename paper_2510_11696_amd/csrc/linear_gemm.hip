@@ -40,6 +40,9 @@ __device__ __forceinline__ void split3_bf16(const float (&v)[8], u32x4& hi, u32x
   }
 }
 
+constexpr int kGemmRing = 4;    // stages of weights in registers per wave (even)
+constexpr int kGemmXAhead = 2;  // x slabs in registers (divides kGemmRing)
+
 template <int NT>
 struct WeightRegs {      // one stage = 64 inputs (4 MFMA steps) of NT column tiles
   u32x4 c[NT];           // 4 steps x 8 codes
@@ -81,8 +84,7 @@ __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
       for (int i = 0; i < 16; ++i) acc[mt][nt][i] = 0.f;
 
   // ---- loaders (stage s covers columns [64 s, 64 s + 64) of the row-major bf16 matrix `src`)
-  u32x4 xr[XL];
-  auto gload_x = [&](const uint16_t* src, int64_t ld, int64_t cols, int64_t s) {
+  auto gload_x = [&](u32x4 (&xr)[XL], const uint16_t* src, int64_t ld, int64_t cols, int64_t s) {
 #pragma unroll
     for (int i = 0; i < XL; ++i) {
       const int idx = tid + i * kThreads;
@@ -95,7 +97,7 @@ __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
       if (idx < kChunks) xr[i] = *reinterpret_cast<const u32x4*>(src + gr * ld + k);
     }
   };
-  auto swrite_x = [&](int buf) {
+  auto swrite_x = [&](int buf, const u32x4 (&xr)[XL]) {
 #pragma unroll
     for (int i = 0; i < XL; ++i) {
       const int idx = tid + i * kThreads;
@@ -124,46 +126,87 @@ __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
         acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, wf[nt], acc[mt][nt], 0, 0, 0);
     }
   };
-  auto compute = [&](int buf, const WeightRegs<NT>& wr) {
+  // One stage, software-pipelined by hand: on entry `wf` holds the dequantised weights of the stage's first
+  // step.  The MFMAs of step j are interleaved with the dequantisation of step j + 1 (of the next stage's
+  // first step, from `wn`, at the end), and every x fragment register is re-requested from LDS right after
+  // the MFMAs that used it, so neither the LDS latency nor the conversions stand between two MFMAs.
+  bf16x8 wf[NT];
+  auto compute = [&](int buf, const WeightRegs<NT>& wr, const WeightRegs<NT>& wn) {
     const u32x4* xst = xs + buf * kChunks;
+    bf16x8 af[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int row = mt * 32 + n32;
+      af[mt] = __builtin_bit_cast(bf16x8, xst[row * 8 + (kg ^ ((row >> 1) & 7))]);
+    }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      bf16x8 wf[NT];
+      bf16x8 wfn[NT];
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        wf[nt] = dequant8_bf16(wr.c[nt][j], e4m3_byte_f32(wr.sc[nt], j));
+      for (int nt = 0; nt < NT; ++nt)
+        wfn[nt] = j < 3 ? dequant8_bf16(wr.c[nt][(j + 1) & 3], e4m3_byte_f32(wr.sc[nt], (j + 1) & 3))
+                        : dequant8_bf16(wn.c[nt][0], e4m3_byte_f32(wn.sc[nt], 0));
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mt], wf[nt], acc[mt][nt], 0, 0, 0);
+        if (j < 3) {
+          const int row = mt * 32 + n32;
+          af[mt] = __builtin_bit_cast(bf16x8, xst[row * 8 + ((2 * (j + 1) + kg) ^ ((row >> 1) & 7))]);
+        }
       }
-      mma_step(xst, j, wf);
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) wf[nt] = wfn[nt];
     }
   };
 
-  // ---- main loop over 64-input stages: registers -> LDS double buffering, one barrier per stage
+  // ---- main loop over 64-input stages.  Weights are requested kGemmRing - 1 stages ahead into a ring of
+  // registers, x slabs kGemmXAhead stages ahead (shared between workgroups, so usually an L2 hit; they pass through LDS: written a stage before use, one barrier
+  // per stage): a stage lasts a few hundred nanoseconds, a memory round trip several times that.  The loop is
+  // unrolled over the ring so that every register index is a constant; requests past the end are redirected to
+  // the last stage rather than branched around, which keeps the compiler's wait counts exact.
   if (s_begin < s_end) {
-    WeightRegs<NT> w0, w1;
-    gload_x(a.x, a.ldx, a.K, s_begin);
-    gload_w(w0, s_begin);
-    swrite_x(0);
+    constexpr int R = kGemmRing, PX = kGemmXAhead;
+    WeightRegs<NT> wring[R];
+    u32x4 xring[PX][XL];
+    const int64_t s_last = s_end - 1;
+    auto clamp_s = [&](int64_t s) { return s < s_last ? s : s_last; };
+#pragma unroll
+    for (int p = 0; p < PX; ++p) gload_x(xring[p], a.x, a.ldx, a.K, clamp_s(s_begin + p));
+#pragma unroll
+    for (int d = 0; d < R - 1; ++d) gload_w(wring[d], clamp_s(s_begin + d));
+    swrite_x(0, xring[0]);
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) wf[nt] = dequant8_bf16(wring[0].c[nt][0], e4m3_byte_f32(wring[0].sc[nt], 0));
     __syncthreads();
-    for (int64_t s = s_begin; s < s_end; s += 2) {
-      const bool has1 = s + 1 < s_end, has2 = s + 2 < s_end;
-      if (has1) { gload_x(a.x, a.ldx, a.K, s + 1); gload_w(w1, s + 1); }
-      compute(0, w0);
-      if (has1) swrite_x(1);
+    auto stage = [&](int64_t s, int u) {
+      gload_x(xring[u % PX], a.x, a.ldx, a.K, clamp_s(s + PX));
+      gload_w(wring[(u + R - 1) % R], clamp_s(s + R - 1));
+      compute(u & 1, wring[u], wring[(u + 1) % R]);
+      swrite_x((u + 1) & 1, xring[(u + 1) % PX]);
       __syncthreads();
-      if (!has1) break;
-      if (has2) { gload_x(a.x, a.ldx, a.K, s + 2); gload_w(w0, s + 2); }
-      compute(1, w1);
-      if (has2) swrite_x(0);
-      __syncthreads();
+    };
+    int64_t s = s_begin;
+    for (; s + R <= s_end; s += R) {
+#pragma unroll
+      for (int u = 0; u < R; ++u) stage(s + u, u);
+    }
+#pragma unroll
+    for (int u = 0; u < R - 1; ++u) {
+      if (s + u >= s_end) goto main_done;
+      stage(s + u, u);
     }
   }
+main_done:
 
   {
     // ---- LoRA up-projection: 3r extra columns  [hi | mid | lo] . [B ; B ; B]^T.  ts already carries
     // the factor lora_scale / S32, so one multiplication by S32 at the end scales both branches.
     for (int e = 0; e < a.ext_stages; ++e) {
-      gload_x(a.ts, a.ts_ld, a.ts_ld, e);
-      swrite_x(0);
+      u32x4 xe[XL];
+      gload_x(xe, a.ts, a.ts_ld, a.ts_ld, e);
+      swrite_x(0, xe);
       __syncthreads();
 #pragma unroll
       for (int j = 0; j < 4; ++j) {

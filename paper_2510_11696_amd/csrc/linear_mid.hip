@@ -202,6 +202,7 @@ __global__ __launch_bounds__(256) void mid_reduce_kernel(const float* partial, i
 // ---- host ------------------------------------------------------------------------------------------
 
 static int g_force_w = 0, g_force_s = 0;
+int g_mid_max_tokens = 128;   // token counts above this go to the prefill GEMM
 
 template <int MT, int W>
 static int launch_mid_t(const MidArgs& a, hipStream_t st) {
@@ -212,7 +213,7 @@ static int launch_mid_t(const MidArgs& a, hipStream_t st) {
 }
 
 int plan_mid(MidArgs& a, size_t partial_cap_bytes) {
-  if (a.M < 1 || a.M > 128 || a.n_tiles < 1 || a.k_tiles < 1) return QERL_ERR_SHAPE;
+  if (a.M < 1 || a.M > g_mid_max_tokens || a.n_tiles < 1 || a.k_tiles < 1) return QERL_ERR_SHAPE;
   const int MT = a.M <= 32 ? 1 : a.M <= 64 ? 2 : 4;
   a.MT = MT; a.m_chunks = (int)ceil_div(a.M, 32 * MT);
   // Waves per workgroup and K-splits: the pair with the shortest estimated time.  A wave spends about
@@ -245,7 +246,7 @@ int plan_mid(MidArgs& a, size_t partial_cap_bytes) {
 int launch_mid(const MidArgs& a, hipStream_t st) {
   // every pointer the kernel dereferences must be set by the caller
   if (!a.x || !a.packed || !a.tensor_scale || !a.y || (a.r > 0 && (!a.ts || !a.B)) || (a.S > 1 && !a.partial)) return QERL_ERR_NULL;
-  if (a.M < 1 || a.M > 128 || a.N < 1 || a.K < 16 || a.n_tiles < 1 || a.k_tiles < 1 || a.S < 1 || a.kt_per_split < 1 ||
+  if (a.M < 1 || a.M > g_mid_max_tokens || a.N < 1 || a.K < 16 || a.n_tiles < 1 || a.k_tiles < 1 || a.S < 1 || a.kt_per_split < 1 ||
       (int64_t)a.kt_per_split * a.S < a.k_tiles || (int64_t)a.kt_per_split * (a.S - 1) >= a.k_tiles ||
       (int64_t)a.m_chunks * a.MT * 32 < a.M || (int64_t)a.n_blocks * a.W < a.n_tiles ||
       (a.r > 0 && (a.ts_ld < 3 * a.r || a.ts_ld != (int64_t)a.ext_stages * 128)) || (a.r == 0 && a.ext_stages != 0))
@@ -267,3 +268,4 @@ int launch_mid(const MidArgs& a, hipStream_t st) {
 
 // Tuning hook for experiments (not part of the public header): waves per workgroup and K-splits, 0 = automatic.
 extern "C" QERL_API void qerl_debug_force_mid(int waves, int splits) { qerl::g_force_w = waves; qerl::g_force_s = splits; }
+extern "C" QERL_API void qerl_debug_mid_max_tokens(int m) { qerl::g_mid_max_tokens = m; }

@@ -304,3 +304,52 @@ def test_norm_with_lora_down_feeds_grouped_linear(M, H, Ns, rs, sigma):
         check_linear(out_self, ref, ("group computing t itself", i, M, H, Ns, rs))
     again = qerl.nvfp4_lora_linear_packed_group(y, ws_, As, Bs, [2.0] * len(Ns), ts=ts_gpu)
     assert all(torch.equal(p, q) for p, q in zip(outs, again))
+
+
+def _sampled_rows(N, seed, n=192):
+    rng = np.random.default_rng(seed)
+    rows = np.unique(np.concatenate([np.arange(32), np.arange(N - 32, N), rng.integers(0, N, size=n)]))
+    return rows
+
+
+@pytest.mark.timeout(400)
+def test_full_size_7b_mlp_block_as_the_benchmark_launches_it():
+    """The 7B MLP linears at full size (gate, up: 18944 x 3584; down: 3584 x 18944; 8 tokens, r = 32) in the
+    launch configuration the benchmark times -- fused norm + LoRA-down feeding one grouped gate+up launch,
+    then down on its own (K split over workgroup ranges) -- checked on sampled output rows, which the oracle
+    computes from the same quantised rows one by one (the layer is separable over output rows)."""
+    M, H, I, r = 8, 3584, 18944, 32
+    print("full-size case", M, H, I, r, flush=True)
+    g = lambda a: torch.from_numpy(a).cuda()
+    xin = qs.activations(M, H, 7001)
+    gain = qs.rms_gain(H, 7002)
+    Z = qs.aqn_noise(H, 1e-2, 7003)
+    members = []
+    for i, (N, K) in enumerate([(I, H), (I, H), (H, I)]):
+        W = cases.gaussian(N, K, 7100 + i)
+        codes, scales, ts = oracle.nvfp4_quantize(W)
+        del W
+        A, B = qs.lora_pair(N, K, r, 7200 + i)
+        pw = qerl.nvfp4_prepack(g(codes), g(scales), torch.tensor([ts], device="cuda"))
+        members.append((codes, scales, ts, A, B, pw))
+        print("  quantised member", i, flush=True)
+    y, ts_gpu = qerl.aqn_rmsnorm_lora_down(xin.cuda(), gain.cuda(), Z.cuda(), 1e-6, [m[3].cuda() for m in members[:2]])
+    outs = qerl.nvfp4_lora_linear_packed_group(y, [m[5] for m in members[:2]], [m[3].cuda() for m in members[:2]],
+                                               [m[4].cuda() for m in members[:2]], [2.0, 2.0], ts=ts_gpu)
+    torch.cuda.synchronize()
+    y_np = y.float().cpu().numpy()
+    for i in range(2):
+        codes, scales, ts, A, B, _ = members[i]
+        rows = _sampled_rows(I, 7300 + i)
+        ref = oracle.nvfp4_lora_linear(y_np, codes[rows], scales[rows], ts, A.float().numpy(), B.float().numpy()[rows], 2.0)
+        check_linear(outs[i][:, torch.from_numpy(rows).cuda()], ref, ("full-size gate/up", i))
+    # down reads the (synthetic) activation of the block: gate's output stands in for silu(gate) * up
+    codes, scales, ts, A, B, pw = members[2]
+    x_down = (outs[0].float() * 8.0).to(torch.bfloat16)   # rescaled to unit-ish magnitude, any bf16 values serve
+    out = qerl.nvfp4_lora_linear_packed(x_down, pw, A.cuda(), B.cuda(), 2.0)
+    torch.cuda.synchronize()
+    rows = _sampled_rows(H, 7302)
+    ref = oracle.nvfp4_lora_linear(x_down.float().cpu().numpy(), codes[rows], scales[rows], ts, A.float().numpy(),
+                                   B.float().numpy()[rows], 2.0)
+    check_linear(out[:, torch.from_numpy(rows).cuda()], ref, ("full-size down",))
+

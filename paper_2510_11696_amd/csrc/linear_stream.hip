@@ -128,13 +128,17 @@ __device__ __forceinline__ void stream_producer(const StreamArgs& a, float* red)
                                                           __builtin_bit_cast(bf16x8, af[1][j]), pacc[1], 0, 0, 0);
       }
     };
-    // two K-slices per round, both in flight before either is multiplied (a slice past the end loads nothing)
-    for (int64_t h = (int64_t)blockIdx.x * kStreamWaves + wave; h < h_end; h += 2 * h_step) {
-      u32x4 xa0[4], af0[2][4], xa1[4], af1[2][4];
+    // three K-slices per round, all in flight before any is multiplied (a slice past the end loads nothing):
+    // the producers' round trips compete with 240 workgroups streaming weights, so there must be few of them
+    // (16 producers cover the longest K of the 7B shapes, 18944, in one round)
+    for (int64_t h = (int64_t)blockIdx.x * kStreamWaves + wave; h < h_end; h += 3 * h_step) {
+      u32x4 xa0[4], af0[2][4], xa1[4], af1[2][4], xa2[4], af2[2][4];
       load_slice(h, xa0, af0);
       load_slice(h + h_step, xa1, af1);
+      load_slice(h + 2 * h_step, xa2, af2);
       mul_slice(xa0, af0);
       mul_slice(xa1, af1);
+      mul_slice(xa2, af2);
     }
     QTRACE(1);
 #pragma unroll
@@ -177,9 +181,10 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
   __shared__ StreamMember s_mem[kMaxGroup];
   __shared__ int s_prod[kRedBufs], s_cons; // per buffer: main waves that have written their partial tile; units taken over by the epilogue wave
   float* red = reinterpret_cast<float*>(smem + a.red_off);
-  // grid: x = producers, then the consumers of one K-range; y = K-range.  Producers exist in range 0 only.
+  // grid: the producers, then the consumers range by range: exactly the workgroups that have work, so that
+  // all of them are resident from the start (one per CU)
   if ((int)blockIdx.x < a.n_producers) {
-    if (blockIdx.y == 0) stream_producer<MR>(a, reinterpret_cast<float*>(smem));
+    stream_producer<MR>(a, reinterpret_cast<float*>(smem));
     return;
   }
   const int tid = threadIdx.x, lane = tid & 63;
@@ -188,7 +193,8 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
   QTRACE(0);
   QSTART(0);
   // units u0 .. u0 + n_units - 1 of K-range `range` are this workgroup's
-  const int range = (int)blockIdx.y, ci = (int)blockIdx.x - a.n_producers;
+  const int cid = (int)blockIdx.x - a.n_producers;
+  const int range = cid / a.per_range, ci = cid - range * a.per_range;
   const int n_units = a.units_base + (ci < a.units_rem ? 1 : 0);
   const int u0 = ci * a.units_base + (ci < a.units_rem ? ci : a.units_rem);   // consecutive row-tiles: mostly one member per workgroup
   const int kr_len = a.kr_len;            // K-tiles per range
@@ -727,7 +733,7 @@ static int launch_stream_t(const StreamArgs& a, size_t lds, hipStream_t st) {
       return launch_status();
     attr_set = true;
   }
-  stream_kernel<MR, D><<<dim3(a.n_producers + a.per_range, a.Sk), dim3(kStreamWaves * 64), lds, st>>>(a);
+  stream_kernel<MR, D><<<dim3(a.n_producers + a.per_range * a.Sk), dim3(kStreamWaves * 64), lds, st>>>(a);
   if (a.Sk > 1) {
     const int rc = launch_status();
     if (rc != QERL_OK) return rc;

@@ -60,6 +60,7 @@ struct StreamArgs {
   int total_tiles; int r_total; int any_lora;            // row-tiles; stacked rank the producers compute; any member with r > 0
   int Sk; int kr_len; int per_range; int n_producers;    // K-ranges, K-tiles in each, consumer workgroups per range; producers
   int units_base; int units_rem;                         // consumer ci owns units_base (+1 if ci < units_rem) row-tiles
+  int prod_steps; int prod_cb; int prod_red_off;          // producers: 16-input steps of K each, steps per LDS column block, offset of their reduction area
   int xs_stride; int red_off; int pend_off; int tsum_off;   // LDS layout (bytes): x row stride, reduction buffers, parked units, t of a member
   float* t; uint32_t* lora_ctl; uint32_t* tpart;         // stacked t [M, r_total]; hand-over words; producer partials
   uint32_t* partial; uint32_t* counters;                 // K-range exchange

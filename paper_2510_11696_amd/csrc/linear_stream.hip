@@ -83,13 +83,25 @@ __device__ unsigned long long g_trace[512 * 8 * 8];
 #endif
 
 // ---- producers: t[tok][j] = sum_k x[tok,k] * Astack[j,k] for the stacked A of all members ----------
+// Producer p of P owns a run of 16-input steps of K.  Its share of x and of up to 64 stacked rows of A is
+// first copied to LDS with row-contiguous loads (a wave instruction reads 1 KiB of ONE row: few pages and
+// full cache lines per request, which matters because these requests queue behind the weight streams of all
+// other workgroups), everything requested before anything is stored; then the waves take MFMA operands from
+// LDS, steps interleaved over the eight waves.
+constexpr int kProdMaxSteps = 96;          // steps per column block: 3 chunks of 16 bytes per lane and row
+constexpr int kProdRowsPerWave = 10;       // (64 rows of A + 16 tokens) / 8 waves
+
 template <int MR>
-__device__ __forceinline__ void stream_producer(const StreamArgs& a, float* red) {
+__device__ __forceinline__ void stream_producer(const StreamArgs& a, unsigned char* smem) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps everything derived from it in SGPRs
   const int n32 = lane & 31, kg = lane >> 5;
-  const int P = a.n_producers, n_at = (a.r_total + 31) >> 5, n_pairs = (n_at + 1) >> 1;
+  const int n_at = (a.r_total + 31) >> 5, n_pairs = (n_at + 1) >> 1;
   constexpr int kElems = 2 * MR * 64;
+  const int steps = (int)(a.K / 16);
+  const int p_s0 = (int)blockIdx.x * a.prod_steps;
+  const int p_s1 = p_s0 + a.prod_steps < steps ? p_s0 + a.prod_steps : steps;
+  float* red = reinterpret_cast<float*>(smem + a.prod_red_off);
   QTRACE(0);
   for (int pair = 0; pair < n_pairs; ++pair) {
     f32x16 pacc[2];
@@ -97,50 +109,59 @@ __device__ __forceinline__ void stream_producer(const StreamArgs& a, float* red)
     for (int at = 0; at < 2; ++at)
 #pragma unroll
       for (int i = 0; i < 16; ++i) pacc[at][i] = 0.f;
-    // rows of the stacked A: member by member; row j of the stack lives in member mi at j - t_off
-    const int64_t h_step = (int64_t)P * kStreamWaves, h_end = 2 * (int64_t)a.k_tiles;
-    auto load_slice = [&](int64_t h, u32x4 (&xa)[4], u32x4 (&af)[2][4]) {
+    const int rows_a = a.r_total - 64 * pair < 64 ? a.r_total - 64 * pair : 64;   // stacked rows of this pass
+    const int n_rows = rows_a + a.M;                                              // LDS rows: A rows, then tokens, then a zero row
+    for (int cb0 = p_s0; cb0 < p_s1; cb0 += a.prod_cb) {
+      const int nsb = cb0 + a.prod_cb < p_s1 ? a.prod_cb : p_s1 - cb0;            // steps of this column block
+      const int row_chunks = 2 * nsb, stride = row_chunks * 16 + 16;              // bytes between LDS rows
+      // wave w copies rows w, w + 8, ...; lane l the chunks l, l + 64, l + 128
+      u32x4 v[kProdRowsPerWave][3];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int64_t k = h * 64 + 16 * j + 8 * kg;
-        xa[j] = u32x4{0u, 0u, 0u, 0u};
-        if (h < h_end && n32 < a.M && k < a.K) xa[j] = *reinterpret_cast<const u32x4*>(a.x + (int64_t)n32 * a.ldx + k);
+      for (int ri = 0; ri < kProdRowsPerWave; ++ri) {
+        const int row = wave + 8 * ri;
+        const uint16_t* src = nullptr;
+        if (row < rows_a) {
+          const int srow = 64 * pair + row;               // row of the stacked A: lives in member mi at srow - t_off
+          int mi = 0;
 #pragma unroll
-        for (int at = 0; at < 2; ++at) {
-          const int row = (2 * pair + at) * 32 + n32;     // row of the stacked A
-          af[at][j] = u32x4{0u, 0u, 0u, 0u};
-          if (h < h_end && row < a.r_total && k < a.K) {
-            int mi = 0;
+          for (int i = 1; i < kMaxGroup; ++i)
+            if (i < a.n_members && srow >= a.mem[i].t_off) mi = i;
+          src = a.mem[mi].A + (int64_t)(srow - a.mem[mi].t_off) * a.K;
+        } else if (row < n_rows) {
+          src = a.x + (int64_t)(row - rows_a) * a.ldx;
+        }
 #pragma unroll
-            for (int i = 1; i < kMaxGroup; ++i)
-              if (i < a.n_members && row >= a.mem[i].t_off) mi = i;
-            af[at][j] = *reinterpret_cast<const u32x4*>(a.mem[mi].A + (int64_t)(row - a.mem[mi].t_off) * a.K + k);
-          }
+        for (int ci = 0; ci < 3; ++ci) {
+          const int c = lane + 64 * ci;
+          v[ri][ci] = u32x4{0u, 0u, 0u, 0u};
+          if (src && c < row_chunks) v[ri][ci] = *reinterpret_cast<const u32x4*>(src + (int64_t)cb0 * 16 + c * 8);
         }
       }
-    };
-    auto mul_slice = [&](const u32x4 (&xa)[4], const u32x4 (&af)[2][4]) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        pacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[j]),
-                                                          __builtin_bit_cast(bf16x8, af[0][j]), pacc[0], 0, 0, 0);
-        pacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[j]),
-                                                          __builtin_bit_cast(bf16x8, af[1][j]), pacc[1], 0, 0, 0);
+      for (int ri = 0; ri < kProdRowsPerWave; ++ri) {
+        const int row = wave + 8 * ri;
+#pragma unroll
+        for (int ci = 0; ci < 3; ++ci) {
+          const int c = lane + 64 * ci;
+          if (row < n_rows && c < row_chunks) *reinterpret_cast<u32x4*>(smem + row * stride + c * 16) = v[ri][ci];
+        }
       }
-    };
-    // three K-slices per round, all in flight before any is multiplied (a slice past the end loads nothing):
-    // the producers' round trips compete with 240 workgroups streaming weights, so there must be few of them
-    // (16 producers cover the longest K of the 7B shapes, 18944, in one round)
-    for (int64_t h = (int64_t)blockIdx.x * kStreamWaves + wave; h < h_end; h += 3 * h_step) {
-      u32x4 xa0[4], af0[2][4], xa1[4], af1[2][4], xa2[4], af2[2][4];
-      load_slice(h, xa0, af0);
-      load_slice(h + h_step, xa1, af1);
-      load_slice(h + 2 * h_step, xa2, af2);
-      mul_slice(xa0, af0);
-      mul_slice(xa1, af1);
-      mul_slice(xa2, af2);
+      for (int c = tid; c < row_chunks; c += kStreamWaves * 64)   // MFMA rows beyond the tokens / the stacked ranks read zeros
+        *reinterpret_cast<u32x4*>(smem + n_rows * stride + c * 16) = u32x4{0u, 0u, 0u, 0u};
+      __syncthreads();
+      if (cb0 == p_s0) QTRACE(1);
+      const unsigned char* xrow = smem + (rows_a + (n32 < a.M ? n32 : a.M)) * stride + kg * 16;
+      const unsigned char* arow0 = smem + (n32 < rows_a ? n32 : n_rows) * stride + kg * 16;
+      const unsigned char* arow1 = smem + (32 + n32 < rows_a ? 32 + n32 : n_rows) * stride + kg * 16;
+      for (int sidx = wave; sidx < nsb; sidx += kStreamWaves) {
+        const bf16x8 xf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(xrow + sidx * 32));
+        const bf16x8 a0 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(arow0 + sidx * 32));
+        const bf16x8 a1 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(arow1 + sidx * 32));
+        pacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, a0, pacc[0], 0, 0, 0);
+        pacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, a1, pacc[1], 0, 0, 0);
+      }
+      __syncthreads();   // all fragments read before the next block (or the sums below) overwrite them
     }
-    QTRACE(1);
 #pragma unroll
     for (int at = 0; at < 2; ++at)
 #pragma unroll
@@ -148,12 +169,12 @@ __device__ __forceinline__ void stream_producer(const StreamArgs& a, float* red)
     __syncthreads();
     // this workgroup's partial of t, in [token][stacked rank] order (what the consumers' MFMA operand wants)
     for (int e = tid; e < kElems; e += kStreamWaves * 64) {
-      float s = red[e];
-      for (int w = 1; w < kStreamWaves; ++w) s += red[w * kElems + e];
+      float sum = red[e];
+      for (int w = 1; w < kStreamWaves; ++w) sum += red[w * kElems + e];
       const int at = e / (MR * 64), q = (e / 64) % MR, l = e & 63;
       const int tok = 8 * (q >> 2) + 4 * (l >> 5) + (q & 3), j = (2 * pair + at) * 32 + (l & 31);
       if (tok < a.M && j < a.r_total)
-        __hip_atomic_store(a.tpart + ((int64_t)blockIdx.x * kTpartTokens + tok) * a.r_total + j, __float_as_uint(s),
+        __hip_atomic_store(a.tpart + ((int64_t)blockIdx.x * kTpartTokens + tok) * a.r_total + j, __float_as_uint(sum),
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();   // red is reused by the next pair
@@ -184,7 +205,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
   // grid: the producers, then the consumers range by range: exactly the workgroups that have work, so that
   // all of them are resident from the start (one per CU)
   if ((int)blockIdx.x < a.n_producers) {
-    stream_producer<MR>(a, reinterpret_cast<float*>(smem));
+    stream_producer<MR>(a, smem);
     return;
   }
   const int tid = threadIdx.x, lane = tid & 63;
@@ -675,9 +696,7 @@ static StreamLds stream_lds(int M, int kr_len, int MR, bool lora) {
   const size_t pend = (size_t)kMaxPending * (MR * 64 * sizeof(float) + (lora ? kLoraSteps * 64 * 16 : 0));   // sums always, B fragments with LoRA
   l.tsum_off = l.pend_off + (int)pend;
   const size_t tsum = (size_t)16 * 64 * sizeof(float) + 16 * 32 * 2;               // t of one member (up to 16 tokens x 64 ranks); output tile staging
-  const size_t red_producer = (size_t)kStreamWaves * 2 * MR * 64 * sizeof(float);
   l.total = l.tsum_off + tsum;
-  if (l.total < red_producer) l.total = red_producer;
   return l;
 }
 
@@ -714,7 +733,23 @@ int plan_stream(StreamArgs& a, size_t* lds_bytes, int* MR_out) {
   if (best == 0) return QERL_ERR_SHAPE;
   const int Sk = best;
   const StreamLds l = stream_lds(a.M, (int)ceil_div(a.k_tiles, Sk), MR, lora);
-  *lds_bytes = l.total;
+  size_t total = l.total;
+  if (a.n_producers > 0) {
+    // producers: column blocks of their K share as large as LDS allows (one block = one round of loads)
+    const int64_t steps = a.K / 16;
+    a.prod_steps = (int)ceil_div(steps, a.n_producers);
+    const size_t rows = (size_t)(a.r_total < 64 ? a.r_total : 64) + a.M + 1;
+    const size_t red_producer = (size_t)kStreamWaves * 2 * MR * 64 * sizeof(float);
+    int64_t cb = ((int64_t)((lds_cap - red_producer - 256) / rows) - 16) / 32;
+    cb = cb < a.prod_steps ? cb : a.prod_steps;
+    cb = cb < kProdMaxSteps ? cb : kProdMaxSteps;
+    if (cb < 1) return QERL_ERR_SHAPE;
+    a.prod_cb = (int)cb;
+    a.prod_red_off = (int)((rows * (size_t)(cb * 32 + 16) + 255) & ~(size_t)255);
+    const size_t need = a.prod_red_off + red_producer;
+    if (need > total) total = need;
+  }
+  *lds_bytes = total;
   a.Sk = Sk; a.xs_stride = l.xs_stride; a.red_off = l.red_off; a.pend_off = l.pend_off; a.tsum_off = l.tsum_off;
   int64_t per_range = cus / Sk;
   if (per_range > a.total_tiles) per_range = a.total_tiles;
@@ -755,6 +790,13 @@ int launch_stream(const StreamArgs& a, size_t lds, int MR, hipStream_t st) {
   }
   if (a.r_total > 0 && (a.n_producers < 1 || a.n_producers > 16 || !a.lora_ctl || !a.tpart)) return QERL_ERR_NULL;
   if (a.r_total == 0 && a.n_producers != 0) return QERL_ERR_SHAPE;
+  if (a.n_producers > 0) {
+    const size_t rows = (size_t)(a.r_total < 64 ? a.r_total : 64) + a.M + 1;
+    if (a.prod_steps < 1 || a.prod_cb < 1 || a.prod_cb > kProdMaxSteps || (int64_t)a.prod_steps * a.n_producers < a.K / 16 ||
+        rows * (size_t)(a.prod_cb * 32 + 16) > (size_t)a.prod_red_off ||
+        (size_t)a.prod_red_off + (size_t)kStreamWaves * 2 * MR * 64 * sizeof(float) > lds)
+      return QERL_ERR_SHAPE;
+  }
   if (a.r_total < 0 || a.r_total > 256 || a.r_total % 8 != 0) return QERL_ERR_SHAPE;
   if (a.mp0 != a.mem[0].packed || a.mp1 != a.mem[1].packed || a.mp2 != a.mem[2].packed || a.mp3 != a.mem[3].packed ||
       a.tb1 != a.mem[1].tile_begin || a.tb2 != a.mem[2].tile_begin || a.tb3 != a.mem[3].tile_begin)

@@ -41,7 +41,7 @@ static WorkspaceLayout workspace_layout(int64_t M, int64_t N, int64_t K, int64_t
   L.t_off = L.ctrl_bytes;
   // t = x A^T: fp32 [M, r] for the decode kernels, or three bf16 terms [M, ceil64(3r)] for the GEMM
   const size_t rows = (size_t)(M > 0 ? M : 1), rr = (size_t)(r > 0 ? r : 1);
-  const size_t t_f32 = rows * rr * sizeof(float), t_split = rows * (size_t)ceil_div(3 * rr, 128) * 128 * 2;
+  const size_t t_f32 = rows * rr * sizeof(float), t_split = rows * (size_t)(ceil_div(3 * rr, 128) + kMaxGroup - 1) * 128 * 2;   // each member of a group pads its 3r columns to 128
   const size_t t_bytes = align256(t_f32 > t_split ? t_f32 : t_split);
   L.partial_off = L.t_off + t_bytes;
   // worst case over the plans the dispatchers can choose (one K-tile per wave)
@@ -240,6 +240,49 @@ static int stream_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, co
   a.tpart = partial + part_words;
   return launch_stream(a, lds, MR, st);
 }
+
+// A few dozen tokens (17..128), one linear or a group reading the same x: the LoRA down-projections of all
+// members write lora_scale / S32 * x A^T as three bf16 terms into the workspace (one launch), then the
+// weight-streaming kernel computes every member with those 3r columns appended to K (one launch, plus the
+// reduction of the K-splits if there are any).
+static int mid_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const qerl_linear_desc* d, int n,
+                     uint8_t* ws, const WorkspaceLayout& L, hipStream_t st) {
+  const bool few = M <= 128;   // K-splits and their workspace areas exist for these only
+  MidArgs g{};
+  g.x = x; g.ldx = ldx; g.M = M; g.K = K; g.k_tiles = (int)ceil_div(K, kPackTileK); g.n_members = n;
+  GemmArgs dn{};
+  dn.x = x; dn.ldx = ldx; dn.M = M; dn.K = K; dn.k_tiles = g.k_tiles;
+  int64_t n_sum = 0;
+  uint16_t* ts = (uint16_t*)(ws + L.t_off);
+  int tiles = 0;
+  for (int i = 0; i < n; ++i) {
+    MidMember& m = g.mem[i];
+    m.packed = (const uint8_t*)d[i].packed; m.tensor_scale = d[i].tensor_scale; m.N = d[i].N;
+    m.n_tiles = (int)ceil_div(d[i].N, kPackTileRows);
+    m.r = (int)d[i].r; m.B = (const uint16_t*)d[i].B_bf16; m.y = (uint16_t*)d[i].y_bf16; m.ldy = d[i].ldy;
+    m.ext_stages = (int)ceil_div(3 * d[i].r, 128); m.ts_ld = (int64_t)m.ext_stages * 128; m.ts = ts;
+    ts += M * m.ts_ld;
+    n_sum += d[i].N;
+    if (d[i].r > 0) {
+      const int gi = dn.g_n++;
+      dn.g_tile0[gi] = tiles; dn.g_A[gi] = (const uint16_t*)d[i].A_bf16; dn.g_ts[gi] = m.ts; dn.g_ts_ld[gi] = m.ts_ld;
+      dn.g_r[gi] = (int)d[i].r; dn.g_lora_scale[gi] = d[i].lora_scale; dn.g_tensor_scale[gi] = d[i].tensor_scale;
+      tiles += (int)ceil_div(d[i].r, 32);
+    }
+  }
+  uint32_t* partial = (uint32_t*)(ws + L.partial_off);
+  if (dn.g_n > 0) {
+    dn.g_tile0[dn.g_n] = tiles;
+    dn.tpart = few ? partial + mid_partial_bytes(M, n_sum) / sizeof(uint32_t) : nullptr;
+    dn.counters = (uint32_t*)ws + L.n_main_ctr;
+    const int rc = launch_lora_down_gemm(dn, st);
+    if (rc != QERL_OK) return rc;
+  }
+  g.partial = (float*)partial;
+  const int prc = plan_mid(g, few ? mid_partial_bytes(M, n_sum) : 0);
+  if (prc != QERL_OK) return prc;
+  return launch_mid(g, st);
+}
 }  // namespace qerl
 
 extern "C" QERL_API void qerl_debug_use_stream(int on) { qerl::g_use_stream = on != 0; }
@@ -250,7 +293,7 @@ extern "C" int nvfp4_lora_linear_packed_group(const void* x, int64_t M, int64_t 
   if (!members) return QERL_ERR_NULL;
   if (n_members < 1 || n_members > kMaxGroup) return QERL_ERR_SHAPE;
   int64_t n_sum = 0, r_sum = 0;
-  bool stream_ok = M <= 16;
+  bool stream_ok = M <= 16, mid_ok = true;
   for (int i = 0; i < n_members; ++i) {
     const qerl_linear_desc& d = members[i];
     LinearCall c{(const uint16_t*)x, M, K, ldx, d.tensor_scale, d.N, (const uint16_t*)d.A_bf16, (const uint16_t*)d.B_bf16,
@@ -260,6 +303,7 @@ extern "C" int nvfp4_lora_linear_packed_group(const void* x, int64_t M, int64_t 
     if (d.N < 1) return QERL_ERR_SHAPE;
     n_sum += d.N; r_sum += d.r;
     stream_ok = stream_ok && (d.r == 0 || (d.r <= 64 && d.r % 8 == 0 && aligned(d.A_bf16, 16) && aligned(d.B_bf16, 16)));
+    mid_ok = mid_ok && (d.r == 0 || (d.r % 8 == 0 && aligned(d.A_bf16, 16) && aligned(d.B_bf16, 16)));
     if (d.r > 0 && d.t_f32 && !aligned(d.t_f32, 32)) return QERL_ERR_ALIGN;
   }
   if (M == 0) return QERL_OK;
@@ -269,6 +313,8 @@ extern "C" int nvfp4_lora_linear_packed_group(const void* x, int64_t M, int64_t 
   if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total) return QERL_ERR_WORKSPACE;
   if (stream_ok && g_use_stream)
     return stream_group((const uint16_t*)x, M, K, ldx, members, n_members, (uint8_t*)workspace, L, (hipStream_t)stream);
+  if (M > 16 && M <= g_mid_max_tokens && mid_ok)
+    return mid_group((const uint16_t*)x, M, K, ldx, members, n_members, (uint8_t*)workspace, L, (hipStream_t)stream);
   for (int i = 0; i < n_members; ++i) {   // general case: member by member
     const qerl_linear_desc& d = members[i];
     const int rc = nvfp4_lora_linear_packed(x, M, K, ldx, d.packed, d.tensor_scale, d.N, d.A_bf16, d.B_bf16, d.r,
@@ -309,27 +355,8 @@ extern "C" int nvfp4_lora_linear_packed(const void* x, int64_t M, int64_t K, int
 
   const bool lora_gemm_ok = r == 0 || (r % 8 == 0 && aligned(A, 16) && aligned(B, 16));
   if (M > 16 && M <= g_mid_max_tokens && lora_gemm_ok) {
-    const bool few = M <= 128;   // K-splits and their workspace areas exist for these only
-    // A few dozen tokens: the LoRA down-projection writes lora_scale * x A^T as three bf16 terms into the
-    // workspace, then the weight-streaming kernel computes the layer with those 3r columns appended to K.
-    MidArgs g{};
-    g.x = c.x; g.ldx = ldx; g.M = M; g.K = K; g.N = N; g.k_tiles = (int)ceil_div(K, kPackTileK);
-    g.ts = (const uint16_t*)(ws + L.t_off); g.ext_stages = (int)ceil_div(3 * r, 128); g.ts_ld = (int64_t)g.ext_stages * 128;
-    g.r = (int)r; g.tensor_scale = tensor_scale;
-    if (r > 0) {
-      GemmArgs d{};
-      d.x = c.x; d.ldx = ldx; d.M = M; d.K = K; d.k_tiles = g.k_tiles; d.ts = g.ts; d.ts_ld = g.ts_ld;
-      d.lora_scale = lora_scale; d.tensor_scale = tensor_scale;
-      d.N = r; d.wbf16 = c.A; d.n_tiles = (int)ceil_div(r, 32);
-      d.tpart = few ? partial + mid_partial_bytes(M, N) / sizeof(uint32_t) : nullptr; d.counters = (uint32_t*)ws + L.n_main_ctr;
-      const int rc = launch_lora_down_gemm(d, c.st);
-      if (rc != QERL_OK) return rc;
-    }
-    g.packed = (const uint8_t*)packed; g.n_tiles = (int)ceil_div(N, 32);
-    g.B = c.B; g.y = c.y; g.ldy = ldy; g.partial = (float*)partial;
-    const int prc = plan_mid(g, few ? mid_partial_bytes(M, N) : 0);
-    if (prc != QERL_OK) return prc;
-    return launch_mid(g, c.st);
+    qerl_linear_desc d{packed, tensor_scale, N, A, B, r, lora_scale, y, ldy, nullptr};
+    return mid_group(c.x, M, K, ldx, &d, 1, ws, L, c.st);
   }
   if (M > 16 && lora_gemm_ok) {
     // Prefill: one split-K GEMM writes lora_scale * x A^T as three bf16 terms into the workspace,

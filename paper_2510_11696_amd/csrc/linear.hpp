@@ -4,6 +4,7 @@
 
 namespace qerl {
 
+constexpr int kMaxGroup = 4;   // linears that can share one launch (they read the same x)
 constexpr int kFmtNvfp4 = 0;   // rows are NVFP4 (codes + scales)
 constexpr int kFmtBf16 = 1;    // rows are dense bf16 (the LoRA A matrix); output is fp32 t
 
@@ -43,7 +44,6 @@ int launch_prepack(const uint8_t* codes, const uint8_t* scales, int64_t N, int64
                    hipStream_t st);
 
 // ---- streaming decode kernel for one linear or a group sharing x (linear_stream.hip) ----
-constexpr int kMaxGroup = 4;
 struct StreamMember {
   const uint8_t* packed; const float* tensor_scale; const uint16_t* A; const uint16_t* B; uint16_t* y;
   int64_t ldy; int64_t N; int n_tiles; int tile_begin;   // row-tiles [tile_begin, tile_begin + n_tiles) of the group
@@ -78,6 +78,10 @@ struct GemmArgs {
   uint16_t* y; int64_t ldy;
   int n_tiles; int n_blocks; int nblk_per_xcd;
   uint32_t* tpart; uint32_t* counters;                                      // LoRA down-projection over several K-parts: partial sums, arrival counts (zero between calls); or null
+  // LoRA down-projection of a group of adapters that read the same x (g_n > 0): grid.y runs over the 32-row
+  // tiles of all adapters; member i owns tiles [g_tile0[i], g_tile0[i+1]) and has its own A, ts and scales
+  int g_n; int g_tile0[kMaxGroup + 1]; const uint16_t* g_A[kMaxGroup]; const uint16_t* g_ts[kMaxGroup]; int64_t g_ts_ld[kMaxGroup];
+  int g_r[kMaxGroup]; float g_lora_scale[kMaxGroup]; const float* g_tensor_scale[kMaxGroup];
 };
 int launch_gemm(const GemmArgs& a, hipStream_t st);
 int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st);
@@ -85,14 +89,19 @@ int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st);
 // ---- 17..128 tokens: weight-streaming MFMA kernel on tile-packed weights (linear_mid.hip) ----
 constexpr size_t kMidPartialCap = (size_t)32 << 20;   // most workspace bytes the K-splits' partial outputs may take
 constexpr size_t kMidDownBytes = (size_t)64 * 2 * 16 * 64 * sizeof(float);   // K-parts' sums of the LoRA down-projection: at most 64 workgroups, two 32 x 32 tiles each
-struct MidArgs {
-  const uint16_t* x; int64_t ldx; int64_t M; int64_t K; int64_t N;
-  const uint8_t* packed; int k_tiles; const float* tensor_scale;
+struct MidMember {
+  const uint8_t* packed; const float* tensor_scale; int64_t N; int n_tiles;
   const uint16_t* ts; int64_t ts_ld; int ext_stages;                        // [M, ts_ld] bf16: hi | mid | lo of lora_scale / S32 * t; stages of 128 columns
   const uint16_t* B; int r;
   uint16_t* y; int64_t ldy;
-  float* partial;                                                           // [S][M][N] fp32 when S > 1
-  int n_tiles; int n_blocks; int m_chunks; int S; int kt_per_split; int MT; int W;
+  int block_begin;                                                          // first column block (W row-tiles each) of this member
+  int64_t partial_off;                                                      // floats: this member's [S][M][N] partial outputs start here
+};
+struct MidArgs {
+  const uint16_t* x; int64_t ldx; int64_t M; int64_t K; int k_tiles;
+  int n_members; MidMember mem[kMaxGroup];                                  // unused entries: block_begin = INT_MAX
+  float* partial;                                                           // K-splits' partial outputs when S > 1
+  int n_blocks; int m_chunks; int S; int kt_per_split; int MT; int W;
 };
 extern int g_mid_max_tokens;
 int plan_mid(MidArgs& a, size_t partial_cap_bytes);

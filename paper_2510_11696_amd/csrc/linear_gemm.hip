@@ -252,7 +252,27 @@ __global__ __launch_bounds__(512) void lora_down32_kernel(const GemmArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps everything derived from it in SGPRs
   const int n32 = lane & 31, kg = lane >> 5;
   const int64_t m0 = (int64_t)blockIdx.x * 32;
-  const int nt0 = blockIdx.y * NT;
+  // one adapter, or (NT == 1) the adapter that owns tile blockIdx.y of the group
+  int nt0 = blockIdx.y * NT;
+  const uint16_t* Aw = a.wbf16;
+  uint16_t* ts = const_cast<uint16_t*>(a.ts);
+  int64_t ts_ld = a.ts_ld, rN = a.N;
+  float lora_scale = a.lora_scale;
+  const float* tensor_scale = a.tensor_scale;
+  bool first_tile = blockIdx.y == 0;
+  if (a.g_n > 0) {
+    int mi = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxGroup; ++i) mi = (i < a.g_n && (int)blockIdx.y >= a.g_tile0[i]) ? i : mi;
+#pragma unroll
+    for (int i = 0; i < kMaxGroup; ++i)
+      if (mi == i) {
+        Aw = a.g_A[i]; ts = const_cast<uint16_t*>(a.g_ts[i]); ts_ld = a.g_ts_ld[i]; rN = a.g_r[i];
+        lora_scale = a.g_lora_scale[i]; tensor_scale = a.g_tensor_scale[i];
+        nt0 = (int)blockIdx.y - a.g_tile0[i];
+      }
+    first_tile = nt0 == 0;
+  }
   int64_t mrow = m0 + n32;
   mrow = mrow < a.M ? mrow : a.M - 1;
   const uint16_t* xrow = a.x + mrow * a.ldx + 8 * kg;
@@ -273,9 +293,9 @@ __global__ __launch_bounds__(512) void lora_down32_kernel(const GemmArgs a) {
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
         int64_t row = (int64_t)(nt0 + nt) * 32 + n32;
-        row = row < a.N ? row : a.N - 1;
+        row = row < rN ? row : rN - 1;
         c.w[nt][j] = u32x4{0u, 0u, 0u, 0u};
-        if (k < k_hi) c.w[nt][j] = *reinterpret_cast<const u32x4*>(a.wbf16 + row * a.K + k);
+        if (k < k_hi) c.w[nt][j] = *reinterpret_cast<const u32x4*>(Aw + row * a.K + k);
       }
     }
   };
@@ -361,8 +381,7 @@ __global__ __launch_bounds__(512) void lora_down32_kernel(const GemmArgs a) {
     }
     if (lane == 0) __hip_atomic_store(a.counters + slot, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
   }
-  uint16_t* ts = const_cast<uint16_t*>(a.ts);
-  const float t_mult = a.lora_scale / *a.tensor_scale;   // undone by the final * S32 of the main launch
+  const float t_mult = lora_scale / *tensor_scale;   // undone by the final * S32 of the main launch
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     const int64_t n = (int64_t)(nt0 + nt) * 32 + n32;
@@ -370,24 +389,24 @@ __global__ __launch_bounds__(512) void lora_down32_kernel(const GemmArgs a) {
     for (int i = 0; i < 16; ++i) {
       const float sum = acc[nt][i];
       const int64_t m = m0 + 8 * (i >> 2) + 4 * kg + (i & 3);
-      if (m < a.M && n < a.N) {
+      if (m < a.M && n < rN) {
         const float v = sum * t_mult;
         const uint32_t h = f32_to_bf16_bits(v);
         const float r1 = v - bf16_bits_to_f32(h);
         const uint32_t md = f32_to_bf16_bits(r1);
         const uint32_t l = f32_to_bf16_bits(r1 - bf16_bits_to_f32(md));
-        uint16_t* row = ts + m * a.ts_ld;
+        uint16_t* row = ts + m * ts_ld;
         row[n] = (uint16_t)h;
-        row[a.N + n] = (uint16_t)md;
-        row[2 * a.N + n] = (uint16_t)l;
+        row[rN + n] = (uint16_t)md;
+        row[2 * rN + n] = (uint16_t)l;
       }
     }
   }
-  if (blockIdx.y == 0) {   // zero the padding columns [3N, ts_ld)
-    const int pad = (int)(a.ts_ld - 3 * a.N);
+  if (first_tile) {   // zero the padding columns [3 r, ts_ld)
+    const int pad = (int)(ts_ld - 3 * rN);
     for (int idx = lane; idx < 32 * pad; idx += 64) {
       const int64_t m = m0 + idx / pad;
-      if (m < a.M) ts[m * a.ts_ld + 3 * a.N + idx % pad] = 0;
+      if (m < a.M) ts[m * ts_ld + 3 * rN + idx % pad] = 0;
     }
   }
 }
@@ -442,6 +461,26 @@ int launch_gemm(const GemmArgs& a, hipStream_t st) {
 
 // ts = three-term bf16 split of (lora_scale / S32) * x A^T, [M, ts_ld]; a.N = r rows of A.
 int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st) {
+  if (a.g_n > 0) {   // several adapters reading the same x: one 32-row tile per workgroup
+    if (!a.x || a.g_n > kMaxGroup || a.M < 1 || a.K < 16) return QERL_ERR_SHAPE;
+    int tiles = 0;
+    for (int i = 0; i < a.g_n; ++i) {
+      if (!a.g_A[i] || !a.g_ts[i] || !a.g_tensor_scale[i]) return QERL_ERR_NULL;
+      if (a.g_r[i] < 1 || a.g_ts_ld[i] < 3 * a.g_r[i] || a.g_tile0[i] != tiles) return QERL_ERR_SHAPE;
+      tiles += (int)ceil_div(a.g_r[i], 32);
+    }
+    if (a.g_tile0[a.g_n] != tiles) return QERL_ERR_SHAPE;
+    int64_t P = 1;
+    const int64_t base_wgs = ceil_div(a.M, 32) * tiles;
+    if (a.tpart && a.counters && base_wgs < 32) {
+      P = 64 / base_wgs;
+      const int64_t p_max = ceil_div(a.K, 512);
+      P = P < p_max ? P : p_max;
+      P = P > kDownMaxParts ? kDownMaxParts : (P < 1 ? 1 : P);
+    }
+    lora_down32_kernel<1><<<dim3((unsigned)ceil_div(a.M, 32), (unsigned)tiles, (unsigned)P), 512, 0, st>>>(a);
+    return launch_status();
+  }
   if (!a.x || !a.wbf16 || !a.tensor_scale || !a.ts) return QERL_ERR_NULL;
   if (a.M < 1 || a.N < 1 || a.K < 16 || a.ts_ld < 3 * a.N) return QERL_ERR_SHAPE;
   const int tiles = (int)ceil_div(a.N, 32);

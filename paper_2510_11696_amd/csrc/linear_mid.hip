@@ -56,8 +56,16 @@ __global__ __launch_bounds__(W * 64) void mid_kernel(const MidArgs a) {
   if (nb >= a.n_blocks) return;                    // padding of the last group of eight (uniform)
   const int chunk = inner / a.S, split = inner % a.S;
   const int64_t m0 = (int64_t)chunk * BM;
-  const int nt = nb * W + wave;
-  const int nt_ld = nt < a.n_tiles ? nt : a.n_tiles - 1;
+  // the linear of the group this column block belongs to (one member: always the first)
+  int mi = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxGroup; ++i) mi = nb >= a.mem[i].block_begin ? i : mi;
+  MidMember mem = a.mem[0];
+#pragma unroll
+  for (int i = 1; i < kMaxGroup; ++i)
+    if (mi == i) mem = a.mem[i];
+  const int nt = (nb - mem.block_begin) * W + wave;   // row-tile within the member
+  const int nt_ld = nt < mem.n_tiles ? nt : mem.n_tiles - 1;
   const int kt0 = split * a.kt_per_split;
   const int kt1 = kt0 + a.kt_per_split < a.k_tiles ? kt0 + a.kt_per_split : a.k_tiles;
   const int n = kt1 - kt0;                         // >= 1 (host)
@@ -89,7 +97,7 @@ __global__ __launch_bounds__(W * 64) void mid_kernel(const MidArgs a) {
       xs[buf * kChunks + row * 16 + (c ^ (row & 15))] = r[i];
     }
   };
-  const uint8_t* wbase = a.packed + (int64_t)nt_ld * a.k_tiles * kPackTileBytes;
+  const uint8_t* wbase = mem.packed + (int64_t)nt_ld * a.k_tiles * kPackTileBytes;
   auto gload_w = [&](MidTile& t, int kt) {
     const uint8_t* base = wbase + (int64_t)kt * kPackTileBytes;
     t.c0 = *reinterpret_cast<const u32x4*>(base + lane * 16);
@@ -152,25 +160,25 @@ main_done:
   // ---- LoRA up-projection: 3r extra columns [hi | mid | lo] . [B ; B ; B]^T.  ts already carries the
   // factor lora_scale / S32, so one multiplication by S32 at the end scales both branches.
   if (split == 0) {
-    for (int e = 0; e < a.ext_stages; ++e) {
-      gload_x(xr[0], a.ts, a.ts_ld, a.ts_ld, e);
+    for (int e = 0; e < mem.ext_stages; ++e) {
+      gload_x(xr[0], mem.ts, mem.ts_ld, mem.ts_ld, e);
       swrite_x(0, xr[0]);
       __syncthreads();
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         int64_t row = (int64_t)nt * 32 + n32;
-        row = row < a.N ? row : a.N - 1;
+        row = row < mem.N ? row : mem.N - 1;
         const int c = e * 128 + 16 * j + 8 * kg;
         u32x4 b = {0u, 0u, 0u, 0u};
-        if (c < 3 * a.r) b = *reinterpret_cast<const u32x4*>(a.B + row * a.r + (c % a.r));
+        if (c < 3 * mem.r) b = *reinterpret_cast<const u32x4*>(mem.B + row * mem.r + (c % mem.r));
         mma_step(xs, j, __builtin_bit_cast(bf16x8, b));
       }
       __syncthreads();
     }
   }
-  const float S32 = *a.tensor_scale;
+  const float S32 = *mem.tensor_scale;
   const int64_t nn = (int64_t)nt * 32 + n32;
-  if (nt >= a.n_tiles || nn >= a.N) return;
+  if (nt >= mem.n_tiles || nn >= mem.N) return;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -178,8 +186,8 @@ main_done:
       const int64_t m = m0 + mt * 32 + 8 * (i >> 2) + 4 * kg + (i & 3);
       if (m < a.M) {
         const float v = acc[mt][i] * S32;
-        if (a.S == 1) a.y[m * a.ldy + nn] = (uint16_t)f32_to_bf16_bits(v);
-        else a.partial[((int64_t)split * a.M + m) * a.N + nn] = v;
+        if (a.S == 1) mem.y[m * mem.ldy + nn] = (uint16_t)f32_to_bf16_bits(v);
+        else a.partial[mem.partial_off + ((int64_t)split * a.M + m) * mem.N + nn] = v;
       }
     }
 }
@@ -213,9 +221,11 @@ static int launch_mid_t(const MidArgs& a, hipStream_t st) {
 }
 
 int plan_mid(MidArgs& a, size_t partial_cap_bytes) {
-  if (a.M < 1 || a.M > g_mid_max_tokens || a.n_tiles < 1 || a.k_tiles < 1) return QERL_ERR_SHAPE;
+  if (a.M < 1 || a.M > g_mid_max_tokens || a.n_members < 1 || a.n_members > kMaxGroup || a.k_tiles < 1) return QERL_ERR_SHAPE;
   const int MT = a.M <= 32 ? 1 : a.M <= 64 ? 2 : 4;
   a.MT = MT; a.m_chunks = (int)ceil_div(a.M, 32 * MT);
+  int64_t n_sum = 0;
+  for (int i = 0; i < a.n_members; ++i) n_sum += a.mem[i].N;
   // Waves per workgroup and K-splits: the pair with the shortest estimated time.  A wave spends about
   // 650 + 350 MT cycles on a stage (dequantisation plus MT x 8 MFMAs); workgroups spread evenly over the 256
   // CUs, their waves over the CU's four SIMDs.  A split costs a second launch and the partial sums' traffic.
@@ -226,31 +236,54 @@ int plan_mid(MidArgs& a, size_t partial_cap_bytes) {
   for (int wi = 0; wi < 2; ++wi) {
     const int W = w_opts[wi];
     if (g_force_w > 0 && W != g_force_w) continue;
+    int64_t blocks = 0;
+    for (int i = 0; i < a.n_members; ++i) blocks += ceil_div(a.mem[i].n_tiles, W);
     for (int S = 1; S <= 8; ++S) {
       if (g_force_s > 0 && S != g_force_s) continue;
-      if (S > 1 && ((size_t)S * a.M * a.N * sizeof(float) > partial_cap_bytes || a.k_tiles / S < 4)) continue;
+      if (S > 1 && ((size_t)S * a.M * n_sum * sizeof(float) > partial_cap_bytes || a.k_tiles / S < 4)) continue;
       const int64_t per = ceil_div(a.k_tiles, S), S_eff = ceil_div(a.k_tiles, per);
       if (S_eff != S) continue;
-      const int64_t wgs = ceil_div(a.n_tiles, W) * a.m_chunks * S;
+      const int64_t wgs = blocks * a.m_chunks * S;
       const int64_t on_cu = ceil_div(wgs, 256), per_simd = ceil_div(on_cu * W, 4);
       double us = (double)(per_simd * per) * cyc / 2400.0;
-      if (S > 1) us += 4.0 + 2.0 * (double)S * a.M * a.N * sizeof(float) / 4.0e6;
+      if (S > 1) us += 4.0 + 2.0 * (double)S * a.M * n_sum * sizeof(float) / 4.0e6;
       if (a.W == 0 || us < best) { best = us; a.W = W; a.S = S; a.kt_per_split = (int)per; }
     }
   }
   if (a.W == 0) return QERL_ERR_SHAPE;
-  a.n_blocks = (int)ceil_div(a.n_tiles, a.W);
+  int blocks = 0;
+  int64_t poff = 0;
+  for (int i = 0; i < kMaxGroup; ++i) {
+    if (i < a.n_members) {
+      a.mem[i].block_begin = blocks; a.mem[i].partial_off = poff;
+      blocks += (int)ceil_div(a.mem[i].n_tiles, a.W);
+      poff += (int64_t)a.S * a.M * a.mem[i].N;
+    } else {
+      a.mem[i] = a.mem[0];
+      a.mem[i].block_begin = 0x7fffffff;
+    }
+  }
+  a.n_blocks = blocks;
   return QERL_OK;
 }
 
 int launch_mid(const MidArgs& a, hipStream_t st) {
   // every pointer the kernel dereferences must be set by the caller
-  if (!a.x || !a.packed || !a.tensor_scale || !a.y || (a.r > 0 && (!a.ts || !a.B)) || (a.S > 1 && !a.partial)) return QERL_ERR_NULL;
-  if (a.M < 1 || a.M > g_mid_max_tokens || a.N < 1 || a.K < 16 || a.n_tiles < 1 || a.k_tiles < 1 || a.S < 1 || a.kt_per_split < 1 ||
+  if (!a.x || a.n_members < 1 || a.n_members > kMaxGroup || (a.S > 1 && !a.partial)) return QERL_ERR_NULL;
+  if (a.M < 1 || a.M > g_mid_max_tokens || a.K < 16 || a.k_tiles < 1 || a.S < 1 || a.S > 8 || a.kt_per_split < 1 ||
       (int64_t)a.kt_per_split * a.S < a.k_tiles || (int64_t)a.kt_per_split * (a.S - 1) >= a.k_tiles ||
-      (int64_t)a.m_chunks * a.MT * 32 < a.M || (int64_t)a.n_blocks * a.W < a.n_tiles ||
-      (a.r > 0 && (a.ts_ld < 3 * a.r || a.ts_ld != (int64_t)a.ext_stages * 128)) || (a.r == 0 && a.ext_stages != 0))
+      (int64_t)a.m_chunks * a.MT * 32 < a.M)
     return QERL_ERR_SHAPE;
+  int blocks = 0;
+  for (int i = 0; i < a.n_members; ++i) {
+    const MidMember& m = a.mem[i];
+    if (!m.packed || !m.tensor_scale || !m.y || (m.r > 0 && (!m.ts || !m.B))) return QERL_ERR_NULL;
+    if (m.N < 1 || m.n_tiles < 1 || m.block_begin != blocks ||
+        (m.r > 0 && (m.ts_ld < 3 * m.r || m.ts_ld != (int64_t)m.ext_stages * 128)) || (m.r == 0 && m.ext_stages != 0))
+      return QERL_ERR_SHAPE;
+    blocks += (int)ceil_div(m.n_tiles, a.W);
+  }
+  if (blocks != a.n_blocks) return QERL_ERR_SHAPE;
   int rc = QERL_ERR_SHAPE;
   if (a.MT == 1 && a.W == 2) rc = launch_mid_t<1, 2>(a, st);
   else if (a.MT == 1 && a.W == 4) rc = launch_mid_t<1, 4>(a, st);
@@ -259,9 +292,14 @@ int launch_mid(const MidArgs& a, hipStream_t st) {
   else if (a.MT == 4 && a.W == 4) rc = launch_mid_t<4, 4>(a, st);
   else if (a.MT == 4 && a.W == 8) rc = launch_mid_t<4, 8>(a, st);
   if (rc != QERL_OK || a.S == 1) return rc;
-  if (a.S > 8) return QERL_ERR_SHAPE;
-  mid_reduce_kernel<<<dim3((unsigned)ceil_div(a.N, 256), (unsigned)a.M), dim3(256), 0, st>>>(a.partial, a.S, a.M, a.N, a.y, a.ldy);
-  return launch_status();
+  for (int i = 0; i < a.n_members; ++i) {
+    const MidMember& m = a.mem[i];
+    mid_reduce_kernel<<<dim3((unsigned)ceil_div(m.N, 256), (unsigned)a.M), dim3(256), 0, st>>>(a.partial + m.partial_off, a.S, a.M, m.N,
+                                                                                               m.y, m.ldy);
+    rc = launch_status();
+    if (rc != QERL_OK) return rc;
+  }
+  return QERL_OK;
 }
 
 }  // namespace qerl

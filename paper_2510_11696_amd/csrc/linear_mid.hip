@@ -30,7 +30,6 @@
 namespace qerl {
 
 constexpr int kRing = 8;      // weight stages per wave: one in use, seven requested
-constexpr int kXAhead = 4;    // x slabs in registers
 
 struct MidTile { u32x4 c0, c1; u32x2 sc; };   // one wave's share of a packed tile: 2 x 4 steps x 8 codes, 8 scale bytes
 
@@ -38,6 +37,7 @@ template <int MT, int W>
 __global__ __launch_bounds__(W * 64) void mid_kernel(const MidArgs a) {
   constexpr int BM = MT * 32;
   constexpr int kThreads = W * 64;
+  constexpr int kXAhead = MT == 4 ? 2 : 4;         // x slabs in registers (they are shared reads, usually L2 hits; 128 tokens leave room for two)
   constexpr int kChunks = BM * 16;                 // 16-byte chunks of one x slab (BM x 128)
   constexpr int XL = kChunks / kThreads;           // chunks per thread
   static_assert(kChunks % kThreads == 0 && kRing % kXAhead == 0 && kRing % 2 == 0, "ring sizes");
@@ -60,10 +60,7 @@ __global__ __launch_bounds__(W * 64) void mid_kernel(const MidArgs a) {
   int mi = 0;
 #pragma unroll
   for (int i = 1; i < kMaxGroup; ++i) mi = nb >= a.mem[i].block_begin ? i : mi;
-  MidMember mem = a.mem[0];
-#pragma unroll
-  for (int i = 1; i < kMaxGroup; ++i)
-    if (mi == i) mem = a.mem[i];
+  const MidMember& mem = a.mem[__builtin_amdgcn_readfirstlane(mi)];   // uniform index: scalar loads from the kernel arguments
   const int nt = (nb - mem.block_begin) * W + wave;   // row-tile within the member
   const int nt_ld = nt < mem.n_tiles ? nt : mem.n_tiles - 1;
   const int kt0 = split * a.kt_per_split;
@@ -112,13 +109,41 @@ __global__ __launch_bounds__(W * 64) void mid_kernel(const MidArgs a) {
       acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, wf, acc[mt], 0, 0, 0);
     }
   };
-  auto compute = [&](int buf, const MidTile& t) {
+  // One stage, software-pipelined by hand (a SIMD holds one or two of these waves, so what a wave does not
+  // overlap itself stays exposed): on entry `wf` holds the dequantised weights of the stage's first step;
+  // the conversions of step j + 1 (of the next stage's first step, from `tn`, at the end) are written
+  // between the MFMAs of step j, and every x fragment is re-requested from LDS right after the MFMA that
+  // used it.
+  auto dequant_step = [&](const MidTile& t, int j) {
+    const uint32_t codes = j < 4 ? t.c0[j & 3] : t.c1[j & 3];
+    return dequant8_bf16(codes, e4m3_byte_f32(j < 4 ? t.sc[0] : t.sc[1], j & 3));
+  };
+  bf16x8 wf;
+  auto compute = [&](int buf, const MidTile& t, const MidTile& tn) {
     const u32x4* xst = xs + buf * kChunks;
+    if constexpr (MT > 2) {   // four token blocks: the MFMAs of a step already cover its conversions; keep the registers
+#pragma unroll
+      for (int j = 0; j < 8; ++j) mma_step(xst, j, dequant_step(t, j));
+      return;
+    }
+    bf16x8 af[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int row = mt * 32 + n32;
+      af[mt] = __builtin_bit_cast(bf16x8, xst[row * 16 + (kg ^ (row & 15))]);
+    }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const uint32_t codes = j < 4 ? t.c0[j & 3] : t.c1[j & 3];
-      const float s = e4m3_byte_f32(j < 4 ? t.sc[0] : t.sc[1], j & 3);
-      mma_step(xst, j, dequant8_bf16(codes, s));
+      const bf16x8 wfn = j < 7 ? dequant_step(t, j + 1) : dequant_step(tn, 0);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mt], wf, acc[mt], 0, 0, 0);
+        if (j < 7) {
+          const int row = mt * 32 + n32;
+          af[mt] = __builtin_bit_cast(bf16x8, xst[row * 16 + ((2 * (j + 1) + kg) ^ (row & 15))]);
+        }
+      }
+      wf = wfn;
     }
   };
 
@@ -135,13 +160,14 @@ __global__ __launch_bounds__(W * 64) void mid_kernel(const MidArgs a) {
 #pragma unroll
   for (int d = 0; d < kRing - 1; ++d) gload_w(wr[d], clamp_kt(kt0 + d));
   swrite_x(0, xr[0]);
+  wf = dequant_step(wr[0], 0);
   __syncthreads();
   // ---- main loop, unrolled over the ring so that every register array index is a constant: whole rounds of
   // the ring without a branch inside, then the remaining stages as straight-line code with forward exits only
   auto stage = [&](int i, int u) {
     gload_x(xr[u % kXAhead], a.x, a.ldx, a.K, clamp_kt(kt0 + i + kXAhead));
     gload_w(wr[(u + kRing - 1) % kRing], clamp_kt(kt0 + i + kRing - 1));
-    compute(u & 1, wr[u]);
+    compute(u & 1, wr[u], wr[(u + 1) % kRing]);
     swrite_x((u + 1) & 1, xr[(u + 1) % kXAhead]);
     __syncthreads();
   };
@@ -192,19 +218,22 @@ main_done:
     }
 }
 
-// y = sum over the K-splits, in split order, of the fp32 partial outputs [S][M][N].  Grid: (N / 256, M).
-__global__ __launch_bounds__(256) void mid_reduce_kernel(const float* partial, int S, int64_t M, int64_t N, uint16_t* y,
-                                                         int64_t ldy) {
+// y = sum over the K-splits, in split order, of the fp32 partial outputs [S][M][N] of every member.
+// Grid: (max N / 256, M, members).
+struct MidReduceArgs { const float* partial; int S; int64_t M; int64_t N[kMaxGroup]; int64_t off[kMaxGroup]; uint16_t* y[kMaxGroup]; int64_t ldy[kMaxGroup]; };
+__global__ __launch_bounds__(256) void mid_reduce_kernel(const MidReduceArgs a) {
+  const int mi = blockIdx.z;
+  const int64_t N = a.N[mi];
   const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x, m = blockIdx.y;
   if (n >= N) return;
-  const float* p = partial + m * N + n;
+  const float* p = a.partial + a.off[mi] + m * N + n;
   float v[8];
 #pragma unroll
-  for (int s = 0; s < 8; ++s) v[s] = s < S ? p[(int64_t)s * M * N] : 0.f;
+  for (int s = 0; s < 8; ++s) v[s] = s < a.S ? p[(int64_t)s * a.M * N] : 0.f;
   float sum = 0.f;
 #pragma unroll
   for (int s = 0; s < 8; ++s) sum += v[s];
-  y[m * ldy + n] = (uint16_t)f32_to_bf16_bits(sum);
+  a.y[mi][m * a.ldy[mi] + n] = (uint16_t)f32_to_bf16_bits(sum);
 }
 
 // ---- host ------------------------------------------------------------------------------------------
@@ -292,14 +321,16 @@ int launch_mid(const MidArgs& a, hipStream_t st) {
   else if (a.MT == 4 && a.W == 4) rc = launch_mid_t<4, 4>(a, st);
   else if (a.MT == 4 && a.W == 8) rc = launch_mid_t<4, 8>(a, st);
   if (rc != QERL_OK || a.S == 1) return rc;
+  MidReduceArgs ra{};
+  ra.partial = a.partial; ra.S = a.S; ra.M = a.M;
+  int64_t n_max = 0;
   for (int i = 0; i < a.n_members; ++i) {
     const MidMember& m = a.mem[i];
-    mid_reduce_kernel<<<dim3((unsigned)ceil_div(m.N, 256), (unsigned)a.M), dim3(256), 0, st>>>(a.partial + m.partial_off, a.S, a.M, m.N,
-                                                                                               m.y, m.ldy);
-    rc = launch_status();
-    if (rc != QERL_OK) return rc;
+    ra.N[i] = m.N; ra.off[i] = m.partial_off; ra.y[i] = m.y; ra.ldy[i] = m.ldy;
+    n_max = n_max > m.N ? n_max : m.N;
   }
-  return QERL_OK;
+  mid_reduce_kernel<<<dim3((unsigned)ceil_div(n_max, 256), (unsigned)a.M, (unsigned)a.n_members), dim3(256), 0, st>>>(ra);
+  return launch_status();
 }
 
 }  // namespace qerl

@@ -57,6 +57,7 @@ static WorkspaceLayout workspace_layout(int64_t M, int64_t N, int64_t K, int64_t
     const size_t mid = mid_partial_bytes(M, N) + kMidDownBytes;
     need = need > mid ? need : mid;
   }
+  if (M > 128 && need < kDownExchangeBytes) need = kDownExchangeBytes;   // K-parts of the prefill path's LoRA down-projection
   L.total = L.partial_off + align256(need);
   return L;
 }
@@ -368,6 +369,7 @@ extern "C" int nvfp4_lora_linear_packed(const void* x, int64_t M, int64_t K, int
     if (r > 0) {
       GemmArgs d = g;
       d.N = r; d.wbf16 = c.A; d.n_tiles = (int)ceil_div(r, 32);
+      d.tpart = partial; d.counters = (uint32_t*)ws + L.n_main_ctr;
       const int rc = launch_lora_down_gemm(d, c.st);
       if (rc != QERL_OK) return rc;
     }

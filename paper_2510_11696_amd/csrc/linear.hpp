@@ -84,6 +84,8 @@ struct GemmArgs {
   int g_r[kMaxGroup]; float g_lora_scale[kMaxGroup]; const float* g_tensor_scale[kMaxGroup];
 };
 int launch_gemm(const GemmArgs& a, hipStream_t st);
+constexpr int kDownMaxSlots = 256;                                           // workgroups of a K-split LoRA down-projection
+constexpr size_t kDownExchangeBytes = (size_t)kDownMaxSlots * 2 * 16 * 64 * sizeof(float);   // their partial sums: two 32 x 32 tiles each
 int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st);
 
 // ---- 17..128 tokens: weight-streaming MFMA kernel on tile-packed weights (linear_mid.hip) ----

@@ -484,12 +484,12 @@ int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st) {
   if (!a.x || !a.wbf16 || !a.tensor_scale || !a.ts) return QERL_ERR_NULL;
   if (a.M < 1 || a.N < 1 || a.K < 16 || a.ts_ld < 3 * a.N) return QERL_ERR_SHAPE;
   const int tiles = (int)ceil_div(a.N, 32);
-  // With few token blocks K is split over workgroups (up to eight parts, at least 512 columns each) when
-  // the caller provides the exchange area.
+  // While token blocks x rank tiles do not fill the chip, K is split over workgroups (up to eight parts, at
+  // least 512 columns each, at most kDownMaxSlots workgroups) when the caller provides the exchange area.
   int64_t P = 1;
   const int64_t base_wgs = ceil_div(a.M, 32) * ceil_div(tiles, tiles >= 2 ? 2 : 1);
-  if (a.tpart && a.counters && base_wgs < 32) {
-    P = 64 / base_wgs;
+  if (a.tpart && a.counters && base_wgs <= kDownMaxSlots / 2) {
+    P = (base_wgs < 32 ? 64 : kDownMaxSlots) / base_wgs;   // a few dozen workgroups for a few tokens, one per CU otherwise
     const int64_t p_max = ceil_div(a.K, 512);
     P = P < p_max ? P : p_max;
     P = P > kDownMaxParts ? kDownMaxParts : (P < 1 ? 1 : P);

@@ -99,6 +99,18 @@ def test_a_few_dozen_tokens_on_packed_weights(M, N, K, r):
 
 
 @pytest.mark.parametrize("packed", PATHS)
+@pytest.mark.parametrize("M,N,K,r", [
+    (129, 512, 3584, 32),    # one token past the 17..128-token kernel: two blocks of token rows in the GEMM
+    (200, 1000, 2112, 16),   # ragged N and K
+    (256, 96, 18944, 32),    # long K: the LoRA down-projection splits K over workgroups
+    (300, 300, 1024, 0),     # no adapter
+    (640, 130, 5120, 64),    # rank 64, ragged last column tile
+])
+def test_prefill_token_counts(M, N, K, r, packed):
+    _run(M, N, K, r, seed=M + N + K + r, packed=packed)
+
+
+@pytest.mark.parametrize("packed", PATHS)
 def test_adversarial_weights_through_the_linear(packed):
     for name, W in cases.quantizer_cases(48, 512, seed=31).items():
         if name in ("scaled_up", "scaled_down"):
@@ -353,3 +365,23 @@ def test_full_size_7b_mlp_block_as_the_benchmark_launches_it():
                                    B.float().numpy()[rows], 2.0)
     check_linear(out[:, torch.from_numpy(rows).cuda()], ref, ("full-size down",))
 
+
+
+@pytest.mark.timeout(400)
+def test_full_size_14b_gate_at_prefill_as_the_benchmark_launches_it():
+    """14B gate_proj (13824 x 5120), 2048 tokens, r = 64 -- the prefill configuration of the benchmark --
+    checked on sampled output rows against the oracle."""
+    M, K, N, r = 2048, 5120, 13824, 64
+    print("full-size prefill case", M, N, K, r, flush=True)
+    g = lambda a: torch.from_numpy(a).cuda()
+    x = qs.activations(M, K, 8001)
+    W = cases.gaussian(N, K, 8002)
+    codes, scales, ts = oracle.nvfp4_quantize(W)
+    del W
+    A, B = qs.lora_pair(N, K, r, 8003)
+    pw = qerl.nvfp4_prepack(g(codes), g(scales), torch.tensor([ts], device="cuda"))
+    y = qerl.nvfp4_lora_linear_packed(x.cuda(), pw, A.cuda(), B.cuda(), 1.0)
+    torch.cuda.synchronize()
+    rows = _sampled_rows(N, 8004, n=96)
+    ref = oracle.nvfp4_lora_linear(x.float().numpy(), codes[rows], scales[rows], ts, A.float().numpy(), B.float().numpy()[rows], 1.0)
+    check_linear(y[:, torch.from_numpy(rows).cuda()], ref, ("full-size prefill gate",))

@@ -417,7 +417,7 @@ struct GemmConfig { int MT, NT, W, wg_per_cu; float quality; };
 // wg_per_cu: workgroups of this shape resident on one CU (register use); quality: relative speed
 // measured at equal useful work on 14B-shaped layers.
 static const GemmConfig kConfigs[] = {
-    {4, 2, 4, 1, 0.60f}, {4, 2, 5, 1, 0.90f}, {4, 2, 8, 1, 0.95f}, {4, 1, 4, 2, 0.75f}, {4, 1, 8, 2, 1.00f},
+    {4, 2, 4, 1, 0.75f}, {4, 2, 5, 1, 0.90f}, {4, 2, 8, 1, 1.00f}, {4, 1, 4, 2, 0.95f}, {4, 1, 8, 2, 0.92f},
 };
 static int g_force_cfg = -1;
 

@@ -19,7 +19,13 @@ What each function follows
 * Noisy RMSNorm  (Z + w) (.) x / sqrt(mean(x^2) + delta): Section 3.3,
   "Noise Merging", Eq. (10); Appendix "Proof of Noise Sharing".
 * Exponential sigma schedule: Section 3.3, Eq. (8); stage 0 is noise-free
-  (Algorithm 1, "Set noise level").
+  (Algorithm 1, "Set noise level").  Linear, cosine and logarithmic decay are
+  named in the scheduler ablation without formulas; the readings are stated
+  at aqn_sigma_schedule.
+* Noise vector Z ~ N(0, sigma^2 I), resampled for each forward pass: Section
+  3.3, "Adaptive Quantization Noise".  The paper fixes the distribution, not
+  the generator; aqn_noise_philox states the counter-based construction both
+  sides of this build implement.
 
 The paper states only the *de*quantisation.  The quantisation rule used here
 is the round-to-nearest scale chain this build was asked to follow:
@@ -38,6 +44,8 @@ tests that run without a GPU (tests/test_oracle_*.py); none is "parity
 unpinned".
 """
 from __future__ import annotations
+
+import math
 
 import numpy as np
 
@@ -217,3 +225,91 @@ def aqn_sigma(stage, num_stages, sigma_start, sigma_end):
         return float(sigma_start)
     return float(sigma_start) * (float(sigma_end) / float(sigma_start)) ** (
         (stage - 1) / (num_stages - 1))
+
+
+# --- scheduler ablation (Section 4 "Noise Scheduler", Appendix on schedulers) --------------
+SCHEDULE_KINDS = ("exponential", "linear", "cosine", "logarithmic")
+
+
+def aqn_sigma_schedule(kind, stage, num_stages, sigma_start, sigma_end):
+    """sigma at stage k = 1..K for the four decay curves the paper compares; k = 0 -> 0.
+
+    Only the exponential curve has a formula in the paper (Eq. 8).  Readings for the
+    other three, each running from sigma_start at k = 1 to sigma_end at k = K with
+    u = (k - 1) / (K - 1):
+      linear       s0 + (s1 - s0) u
+      cosine       s1 + (s0 - s1) (1 + cos(pi u)) / 2          (half-cosine anneal)
+      logarithmic  s0 + (s1 - s0) ln(1 + (k - 1)) / ln(K)      (fast early decay)
+    """
+    if kind not in SCHEDULE_KINDS:
+        raise ValueError("unknown schedule")
+    if kind == "exponential":
+        return aqn_sigma(stage, num_stages, sigma_start, sigma_end)
+    if stage < 0 or stage > num_stages or num_stages < 1:
+        raise ValueError("stage must be in 0..num_stages")
+    if stage == 0:
+        return 0.0
+    if num_stages == 1:
+        return float(sigma_start)
+    s0, s1 = float(sigma_start), float(sigma_end)
+    u = (stage - 1) / (num_stages - 1)
+    if kind == "linear":
+        return s0 + (s1 - s0) * u
+    if kind == "cosine":
+        return s1 + (s0 - s1) * (1.0 + math.cos(math.pi * u)) / 2.0
+    return s0 + (s1 - s0) * math.log(1.0 + (stage - 1)) / math.log(num_stages)
+
+
+# --- noise vector: counter-based generator + Box-Muller ---------------------------------
+_PHILOX_M0, _PHILOX_M1 = 0xD2511F53, 0xCD9E8D57          # multipliers
+_PHILOX_W0, _PHILOX_W1 = 0x9E3779B9, 0xBB67AE85          # key increments (golden ratio, sqrt 3 - 1)
+
+
+def philox4x32_10(counter, key):
+    """Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as
+    easy as 1, 2, 3", SC'11).  counter: uint32 [n, 4]; key: two uint32.  Returns uint32 [n, 4].
+
+    One round maps (c0, c1, c2, c3) to
+        (hi(M1 c2) ^ c1 ^ k0,  lo(M1 c2),  hi(M0 c0) ^ c3 ^ k1,  lo(M0 c0))
+    and the key is bumped by (W0, W1) before every round but the first."""
+    c = np.asarray(counter, dtype=np.uint64).reshape(-1, 4).copy()
+    k0, k1 = int(key[0]) & 0xFFFFFFFF, int(key[1]) & 0xFFFFFFFF
+    mask = np.uint64(0xFFFFFFFF)
+    for rnd in range(10):
+        if rnd:
+            k0 = (k0 + _PHILOX_W0) & 0xFFFFFFFF
+            k1 = (k1 + _PHILOX_W1) & 0xFFFFFFFF
+        p0 = np.uint64(_PHILOX_M0) * c[:, 0]
+        p1 = np.uint64(_PHILOX_M1) * c[:, 2]
+        c = np.stack([(p1 >> np.uint64(32)) ^ c[:, 1] ^ np.uint64(k0), p1 & mask,
+                      (p0 >> np.uint64(32)) ^ c[:, 3] ^ np.uint64(k1), p0 & mask], axis=1)
+    return c.astype(np.uint32)
+
+
+def aqn_noise_philox(n, sigma, seed, subsequence):
+    """Z[i] ~ N(0, sigma^2), i < n, float64 (the device rounds the same values to fp32).
+
+    Construction (this build's; the paper fixes only the distribution): elements come in
+    groups of four.  Group b uses counter (b mod 2^32, b >> 32, subsequence mod 2^32,
+    subsequence >> 32) and key (seed mod 2^32, seed >> 32); the four outputs r0..r3 give two
+    Box-Muller pairs from 24-bit uniforms (exact in fp32):
+        u1 = ((r0 >> 8) + 1) 2^-24 in (0, 1],  u2 = (r1 >> 8) 2^-24 in [0, 1)
+        z0 = sqrt(-2 ln u1) cos(2 pi u2),      z1 = sqrt(-2 ln u1) sin(2 pi u2)
+    and likewise (r2, r3) -> (z2, z3);  Z[4 b + j] = sigma z_j.  A new forward pass takes a
+    new subsequence; a new run a new seed."""
+    n = int(n)
+    nb = (n + 3) // 4
+    b = np.arange(nb, dtype=np.uint64)
+    ctr = np.stack([b & np.uint64(0xFFFFFFFF), b >> np.uint64(32),
+                    np.full(nb, int(subsequence) & 0xFFFFFFFF, dtype=np.uint64),
+                    np.full(nb, (int(subsequence) >> 32) & 0xFFFFFFFF, dtype=np.uint64)], axis=1)
+    r = philox4x32_10(ctr, (int(seed) & 0xFFFFFFFF, (int(seed) >> 32) & 0xFFFFFFFF)).astype(np.float64)
+    z = np.empty((nb, 4), dtype=np.float64)
+    for pair in range(2):
+        u1 = (np.floor(r[:, 2 * pair] / 256.0) + 1.0) * 2.0 ** -24
+        u2 = np.floor(r[:, 2 * pair + 1] / 256.0) * 2.0 ** -24
+        radius = np.sqrt(-2.0 * np.log(u1))
+        z[:, 2 * pair] = radius * np.cos(2.0 * np.pi * u2)
+        z[:, 2 * pair + 1] = radius * np.sin(2.0 * np.pi * u2)
+    return float(sigma) * z.reshape(-1)[:n]
+

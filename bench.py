@@ -54,9 +54,7 @@ class Layer:
             self.lin[shp.name] = (packed, A, B)
         self.gain_in = (1 + 0.05 * torch.randn(hidden, generator=gen, device="cuda")).to(torch.bfloat16)
         self.gain_post = (1 + 0.05 * torch.randn(hidden, generator=gen, device="cuda")).to(torch.bfloat16)
-        sigma = qerl.aqn_sigma(1, 10, 1e-2, 5e-4)
-        self.z_in = torch.randn(hidden, generator=gen, device="cuda") * sigma
-        self.z_post = torch.randn(hidden, generator=gen, device="cuda") * sigma
+        self.z_in = self.z_post = None     # views into the stack's noise buffer, refilled on the device every step
 
 
 class Stack:
@@ -76,6 +74,14 @@ class Stack:
         self.out = {s.name: torch.empty((M, s.N), dtype=torch.bfloat16, device="cuda") for s in cfg["linears"]}
         self.t = {s.name: torch.empty((8, M, cfg["r"]), dtype=torch.float32, device="cuda") for s in cfg["linears"]}
         self.lora_scale = cfg["alpha"] / cfg["r"]
+        # the noise vectors of all RMSNorms in one buffer: one generator launch per forward pass (Section 3.3:
+        # the vector is resampled for each forward pass)
+        self.sigma = qerl.aqn_sigma(1, 10, 1e-2, 5e-4)
+        self.noise = torch.empty((2 * self.n_layers * hidden,), dtype=torch.float32, device="cuda")
+        for i, L in enumerate(self.layers):
+            L.z_in = self.noise[(2 * i) * hidden:(2 * i + 1) * hidden]
+            L.z_post = self.noise[(2 * i + 1) * hidden:(2 * i + 2) * hidden]
+        self.passes = 0
         by = {s.name: s for s in cfg["linears"]}
         need = max([qerl.nvfp4_lora_linear_workspace_bytes(M, s.N, s.K, cfg["r"]) for s in cfg["linears"]]
                    + [qerl.nvfp4_lora_linear_workspace_bytes(M, sum(by[n].N for n in g), by[g[0]].K, cfg["r"] * len(g))
@@ -104,6 +110,9 @@ class Stack:
                                                    outs=[self.out[n] for n in names], ts=ts)
 
     def step(self):
+        # (a captured step replays with the subsequence it was recorded with: same cost, same values)
+        qerl.aqn_noise_fill(self.noise.numel(), self.sigma, qs.seed_for(0, 0), self.passes, out=self.noise)
+        self.passes += 1
         for L in self.layers:
             self.norm_group(L, ("q", "k", "v"), L.gain_in, L.z_in)
             self.linear(L, "o", self.attn)
@@ -294,7 +303,7 @@ def main():
         "config": {"workload": f"config {args.config}: {cfg['model']}-shaped decoder linears, "
                                f"{stack.n_layers} layers, {'decode' if decode else 'prefill'} M={M}, "
                                f"LoRA r={cfg['r']} alpha={cfg['alpha']:g}, "
-                               "AQN RMSNorm before q/k/v and gate/up; "
+                               "AQN RMSNorm before q/k/v and gate/up, noise vectors regenerated on the device every step; "
                                + ("eager launches" if args.eager else "one HIP graph replay per step"),
                    "packed_weight_bytes_per_step": step_bytes,
                    "tflops": round(tflops, 2),

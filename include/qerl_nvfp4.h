@@ -224,6 +224,38 @@ QERL_API int aqn_rmsnorm_lora_down(const void* x_bf16, int64_t M, int64_t H, int
  * (Algorithm 1: stage 0 carries quantisation noise only).  NaN on bad stage. */
 QERL_API double aqn_sigma(int stage_k, int num_stages, double sigma_start, double sigma_end);
 
+/* Host.  The four sigma decay curves of the scheduler ablation (Section 4, "Noise
+ * Scheduler"), k = 1..K, k = 0 -> 0; u = (k-1)/(K-1).  Only the exponential one has
+ * a formula in the paper (Eq. 8, = aqn_sigma); the others are this library's reading:
+ *   linear       s0 + (s1 - s0) u
+ *   cosine       s1 + (s0 - s1) (1 + cos(pi u)) / 2
+ *   logarithmic  s0 + (s1 - s0) ln(1 + (k-1)) / ln(K)
+ * NaN on a bad kind or stage. */
+#define QERL_SCHEDULE_EXPONENTIAL 0
+#define QERL_SCHEDULE_LINEAR 1
+#define QERL_SCHEDULE_COSINE 2
+#define QERL_SCHEDULE_LOGARITHMIC 3
+QERL_API double aqn_sigma_schedule(int kind, int stage_k, int num_stages, double sigma_start, double sigma_end);
+
+/* ---------------------------------------------------------------------------
+ * aqn_noise_fill -- the noise vector of Section 3.3, "Adaptive Quantization
+ * Noise": noise[i] ~ N(0, sigma^2) independently, i < n, generated on the device
+ * (the paper resamples it for each forward pass; one call can fill the vectors of
+ * all RMSNorms of a model at once).  The paper fixes the distribution only; the
+ * construction is counter-based so that a call is a pure function of
+ * (seed, subsequence, n, sigma): Philox4x32 with 10 rounds (Salmon et al., SC'11),
+ * group b = i / 4 with counter (b lo, b hi, subsequence lo, subsequence hi) and
+ * key (seed lo, seed hi); its outputs r0..r3 give two Box-Muller pairs from
+ * 24-bit uniforms u1 = ((r0 >> 8) + 1) 2^-24, u2 = (r1 >> 8) 2^-24:
+ * z0 = sqrt(-2 ln u1) cos(2 pi u2), z1 = ... sin(...), likewise (r2, r3);
+ * noise[4 b + j] = sigma z_j, all in fp32.  Use a new subsequence per forward
+ * pass and a new seed per run.
+ *   noise: device, fp32 [n] out (4-byte aligned; 16-byte alignment stores faster)
+ * Errors: n < 0, sigma negative or not finite (QERL_ERR_SHAPE); NULL noise with n > 0.
+ */
+QERL_API int aqn_noise_fill(float* noise_f32, int64_t n, float sigma, uint64_t seed, uint64_t subsequence,
+                            void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -44,6 +44,8 @@ _SIGNATURES = {
     "aqn_rmsnorm_lora_down": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_p, ctypes.c_float,
                                              _c_p, _c_i64, _c_p, _c_p, _c_p, ctypes.c_int, _c_p]),
     "aqn_sigma": (ctypes.c_double, [ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_double]),
+    "aqn_sigma_schedule": (ctypes.c_double, [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_double]),
+    "aqn_noise_fill": (ctypes.c_int, [_c_p, _c_i64, ctypes.c_float, ctypes.c_uint64, ctypes.c_uint64, _c_p]),
 }
 
 EXPORTED_SYMBOLS = tuple(_SIGNATURES)
@@ -154,6 +156,24 @@ def aqn_rmsnorm_lora_down(x, gain, noise, eps, As, out: Optional[torch.Tensor] =
 
 def aqn_sigma(stage: int, num_stages: int, sigma_start: float, sigma_end: float) -> float:
     return float(load_library().aqn_sigma(stage, num_stages, sigma_start, sigma_end))
+
+
+SCHEDULE_KINDS = {"exponential": 0, "linear": 1, "cosine": 2, "logarithmic": 3}
+
+
+def aqn_sigma_schedule(kind: str, stage: int, num_stages: int, sigma_start: float, sigma_end: float) -> float:
+    return float(load_library().aqn_sigma_schedule(SCHEDULE_KINDS[kind], stage, num_stages, sigma_start, sigma_end))
+
+
+def aqn_noise_fill(n: int, sigma: float, seed: int, subsequence: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """fp32 [n] on the GPU: N(0, sigma^2) noise, a pure function of (seed, subsequence, n, sigma)."""
+    if out is None:
+        out = torch.empty((n,), dtype=torch.float32, device="cuda")
+    if out.numel() < n:
+        raise ValueError("out is too small")
+    _check("aqn_noise_fill", load_library().aqn_noise_fill(
+        _dev(out, torch.float32, "out"), n, float(sigma), seed & (2 ** 64 - 1), subsequence & (2 ** 64 - 1), _stream()))
+    return out
 
 
 def nvfp4_quantize_workspace_bytes(N: int, K: int) -> int:

@@ -103,3 +103,16 @@ def test_workspace_size_is_monotone_enough(lib):
     assert f(8, 3584, 18944, 32) >= f(8, 3584, 3584, 32)
     assert f(128, 3584, 3584, 32) >= f(8, 3584, 3584, 32)
     assert f(8, 3584, 18944, 32) < 64 << 20
+
+
+def test_sigma_schedules_match_the_oracle():
+    from oracle import nvfp4_oracle as oracle
+    for kind in oracle.SCHEDULE_KINDS:
+        for K in (1, 2, 10):
+            for k in range(K + 1):
+                got = qerl.aqn_sigma_schedule(kind, k, K, 1e-2, 5e-4)
+                want = oracle.aqn_sigma_schedule(kind, k, K, 1e-2, 5e-4)
+                assert abs(got - want) <= 1e-17, (kind, K, k, got, want)
+        bad = qerl.aqn_sigma_schedule(kind, 11, 10, 1e-2, 5e-4)
+        assert bad != bad   # NaN
+

@@ -154,7 +154,9 @@ QERL_API int nvfp4_lora_linear_packed(const void* x_bf16, int64_t M, int64_t K, 
  *            the pointers inside are device pointers).
  *   workspace: as for nvfp4_lora_linear, sized with
  *            nvfp4_lora_linear_workspace_bytes(M, sum of N, K, sum of r).
- * Errors: as nvfp4_lora_linear_packed, plus n_members outside 1..4.
+ * Errors: as nvfp4_lora_linear_packed, plus n_members outside 1..4; a bias with an
+ * adapter the fast kernels do not take (rank not a multiple of 8, or above 64 at
+ * M <= 16, or A/B not 16-byte aligned): QERL_ERR_SHAPE.
  */
 #define QERL_T_PARTS 8
 typedef struct {
@@ -172,6 +174,8 @@ typedef struct {
                                   [QERL_T_PARTS][M][r], 32-byte aligned (the kernel adds them in slice order);
                                   or NULL: the call computes x A^T itself.  Used at M <= 16 only; larger M
                                   recompute it. */
+  const void* bias_bf16;       /* [N] bf16 added to every output row before the one rounding to bf16 (the
+                                  q/k/v projections of the Qwen2.5 blocks carry one), or NULL */
 } qerl_linear_desc;
 QERL_API int nvfp4_lora_linear_packed_group(const void* x_bf16, int64_t M, int64_t K, int64_t ldx,
                                             const qerl_linear_desc* members, int n_members,

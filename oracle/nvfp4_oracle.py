@@ -179,8 +179,12 @@ def nvfp4_dequantize(codes, scales, tensor_scale):
 
 
 def nvfp4_lora_linear(x, codes, scales, tensor_scale, A=None, B=None,
-                      lora_scale=0.0, acc_dtype=np.float64):
-    """y[M,N] = x . W_hat^T + lora_scale * (x . A^T) . B^T     (Eq. 2 + Eq. 6)
+                      lora_scale=0.0, acc_dtype=np.float64, bias=None):
+    """y[M,N] = x . W_hat^T + lora_scale * (x . A^T) . B^T (+ bias[N])     (Eq. 2 + Eq. 6)
+
+    bias: the additive vector the q/k/v projections of the Qwen2.5 blocks carry (the paper's
+    equations show none; a linear layer's bias is added to every output row, before any
+    rounding).
 
     x[M,K], A[r,K], B[N,r] hold bf16 values in float32.  W_hat is the fp32
     dequantisation; products and sums run in `acc_dtype` (float64 by default;
@@ -196,6 +200,8 @@ def nvfp4_lora_linear(x, codes, scales, tensor_scale, A=None, B=None,
         B = np.asarray(B, dtype=np.float32).astype(acc_dtype)
         t = x @ A.T
         y = y + acc_dtype(lora_scale) * (t @ B.T)
+    if bias is not None:
+        y = y + np.asarray(bias, dtype=np.float32).astype(acc_dtype)[None, :]
     return y
 
 

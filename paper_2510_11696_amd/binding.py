@@ -300,14 +300,16 @@ T_PARTS = 8   # QERL_T_PARTS in the header
 class _LinearDesc(ctypes.Structure):
     """Mirror of qerl_linear_desc in the header."""
     _fields_ = [("packed", _c_p), ("tensor_scale", _c_p), ("N", _c_i64), ("A", _c_p), ("B", _c_p),
-                ("r", _c_i64), ("lora_scale", ctypes.c_float), ("y", _c_p), ("ldy", _c_i64), ("t", _c_p)]
+                ("r", _c_i64), ("lora_scale", ctypes.c_float), ("y", _c_p), ("ldy", _c_i64), ("t", _c_p),
+                ("bias", _c_p)]
 
 
 def nvfp4_lora_linear_packed_group(x, weights, As=None, Bs=None, lora_scales=None,
-                                   workspace: Optional[Workspace] = None, outs=None, ts=None):
+                                   workspace: Optional[Workspace] = None, outs=None, ts=None, biases=None):
     """Several packed linears that read the same x (q/k/v, gate/up) in one launch.
     weights: list of PackedWeight; As/Bs: lists of LoRA matrices (or None); ts: optional list of
-    precomputed x A^T (fp32 [M, r], from aqn_rmsnorm_lora_down); returns the list of outputs."""
+    precomputed x A^T (fp32 [M, r], from aqn_rmsnorm_lora_down); biases: optional list of bf16 [N]
+    vectors (or None); returns the list of outputs."""
     lib = load_library()
     M, K, ldx = _rows(x, "x")
     n = len(weights)
@@ -337,9 +339,14 @@ def nvfp4_lora_linear_packed_group(x, weights, As=None, Bs=None, lora_scales=Non
             if tuple(ts[i].shape) != (T_PARTS, M, r) or not ts[i].is_contiguous():
                 raise ValueError("t must be contiguous [T_PARTS, M, r] as aqn_rmsnorm_lora_down writes it")
             t_ptr = _dev(ts[i], torch.float32, "t")
+        bias_ptr = None
+        if biases is not None and biases[i] is not None:
+            if tuple(biases[i].shape) != (w.N,) or not biases[i].is_contiguous():
+                raise ValueError("bias must be contiguous [N]")
+            bias_ptr = _dev(biases[i], torch.bfloat16, "bias")
         descs[i] = _LinearDesc(_dev(w.packed, torch.uint8, "packed"),
                                _dev(w.tensor_scale, torch.float32, "tensor_scale"), w.N, a_ptr, b_ptr, r,
-                               float(lora_scales[i]), _dev(outs[i], torch.bfloat16, "out"), ldy, t_ptr)
+                               float(lora_scales[i]), _dev(outs[i], torch.bfloat16, "out"), ldy, t_ptr, bias_ptr)
         n_sum += w.N
         r_sum += r
     if workspace is None:

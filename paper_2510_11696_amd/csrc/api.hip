@@ -213,9 +213,11 @@ static int stream_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, co
     m.r = (int)d[i].r; m.lora_scale = d[i].lora_scale;
     m.y_vec = aligned(d[i].y_bf16, 16) && d[i].ldy % 8 == 0;
     m.t_ext = m.r > 0 ? d[i].t_f32 : nullptr;
+    m.bias = (const uint16_t*)d[i].bias_bf16;
     m.t_off = 0x7fffffff;                 // not part of the producers' stack ...
     if (m.r > 0 && !m.t_ext) { m.t_off = rt; rt += m.r; }   // ... unless the launch has to compute its t
     any |= m.r > 0;
+    a.any_bias |= m.bias != nullptr;
     tiles += m.n_tiles;
   }
   for (int i = n; i < kMaxGroup; ++i) {   // unused entries: never selected, but valid to read
@@ -261,6 +263,7 @@ static int mid_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const
     m.packed = (const uint8_t*)d[i].packed; m.tensor_scale = d[i].tensor_scale; m.N = d[i].N;
     m.n_tiles = (int)ceil_div(d[i].N, kPackTileRows);
     m.r = (int)d[i].r; m.B = (const uint16_t*)d[i].B_bf16; m.y = (uint16_t*)d[i].y_bf16; m.ldy = d[i].ldy;
+    m.bias = (const uint16_t*)d[i].bias_bf16;
     m.ext_stages = (int)ceil_div(3 * d[i].r, 128); m.ts_ld = (int64_t)m.ext_stages * 128; m.ts = ts;
     ts += M * m.ts_ld;
     n_sum += d[i].N;
@@ -287,6 +290,11 @@ static int mid_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const
 }  // namespace qerl
 
 extern "C" QERL_API void qerl_debug_use_stream(int on) { qerl::g_use_stream = on != 0; }
+
+static int packed_single(const void* x, int64_t M, int64_t K, int64_t ldx, const void* packed,
+                         const float* tensor_scale, int64_t N, const void* A, const void* B,
+                         int64_t r, float lora_scale, const void* bias, void* y, int64_t ldy, void* workspace,
+                         size_t workspace_bytes, void* stream);
 
 extern "C" int nvfp4_lora_linear_packed_group(const void* x, int64_t M, int64_t K, int64_t ldx,
                                               const qerl_linear_desc* members, int n_members, void* workspace,
@@ -318,8 +326,8 @@ extern "C" int nvfp4_lora_linear_packed_group(const void* x, int64_t M, int64_t 
     return mid_group((const uint16_t*)x, M, K, ldx, members, n_members, (uint8_t*)workspace, L, (hipStream_t)stream);
   for (int i = 0; i < n_members; ++i) {   // general case: member by member
     const qerl_linear_desc& d = members[i];
-    const int rc = nvfp4_lora_linear_packed(x, M, K, ldx, d.packed, d.tensor_scale, d.N, d.A_bf16, d.B_bf16, d.r,
-                                            d.lora_scale, d.y_bf16, d.ldy, workspace, workspace_bytes, stream);
+    const int rc = packed_single(x, M, K, ldx, d.packed, d.tensor_scale, d.N, d.A_bf16, d.B_bf16, d.r,
+                                 d.lora_scale, d.bias_bf16, d.y_bf16, d.ldy, workspace, workspace_bytes, stream);
     if (rc != QERL_OK) return rc;
   }
   return QERL_OK;
@@ -343,6 +351,14 @@ extern "C" int nvfp4_lora_linear_packed(const void* x, int64_t M, int64_t K, int
                                         const float* tensor_scale, int64_t N, const void* A, const void* B,
                                         int64_t r, float lora_scale, void* y, int64_t ldy, void* workspace,
                                         size_t workspace_bytes, void* stream) {
+  return packed_single(x, M, K, ldx, packed, tensor_scale, N, A, B, r, lora_scale, nullptr, y, ldy, workspace,
+                       workspace_bytes, stream);
+}
+
+static int packed_single(const void* x, int64_t M, int64_t K, int64_t ldx, const void* packed,
+                         const float* tensor_scale, int64_t N, const void* A, const void* B,
+                         int64_t r, float lora_scale, const void* bias, void* y, int64_t ldy, void* workspace,
+                         size_t workspace_bytes, void* stream) {
   LinearCall c{(const uint16_t*)x, M, K, ldx, tensor_scale, N, (const uint16_t*)A, (const uint16_t*)B, r,
                lora_scale, (uint16_t*)y, ldy, workspace, workspace_bytes, (hipStream_t)stream};
   const int vr = validate(c, packed, packed);
@@ -356,7 +372,7 @@ extern "C" int nvfp4_lora_linear_packed(const void* x, int64_t M, int64_t K, int
 
   const bool lora_gemm_ok = r == 0 || (r % 8 == 0 && aligned(A, 16) && aligned(B, 16));
   if (M > 16 && M <= g_mid_max_tokens && lora_gemm_ok) {
-    qerl_linear_desc d{packed, tensor_scale, N, A, B, r, lora_scale, y, ldy, nullptr};
+    qerl_linear_desc d{packed, tensor_scale, N, A, B, r, lora_scale, y, ldy, nullptr, bias};
     return mid_group(c.x, M, K, ldx, &d, 1, ws, L, c.st);
   }
   if (M > 16 && lora_gemm_ok) {
@@ -374,14 +390,15 @@ extern "C" int nvfp4_lora_linear_packed(const void* x, int64_t M, int64_t K, int
       if (rc != QERL_OK) return rc;
     }
     g.N = N; g.packed = (const uint8_t*)packed; g.n_tiles = (int)ceil_div(N, 32);
-    g.B = c.B; g.y = c.y; g.ldy = ldy;
+    g.B = c.B; g.y = c.y; g.ldy = ldy; g.bias = (const uint16_t*)bias;
     return launch_gemm(g, c.st);
   }
 
   if (g_use_stream && M <= 16 && (r == 0 || (r <= 64 && r % 8 == 0 && aligned(A, 16) && aligned(B, 16)))) {
-    qerl_linear_desc d{packed, tensor_scale, N, A, B, r, lora_scale, y, ldy, nullptr};
+    qerl_linear_desc d{packed, tensor_scale, N, A, B, r, lora_scale, y, ldy, nullptr, bias};
     return stream_group(c.x, M, K, ldx, &d, 1, ws, L, c.st);
   }
+  if (bias) return QERL_ERR_SHAPE;   // the remaining kernels (adapters of unusual rank or alignment) add no bias
 
   // Decode: passes of up to 16 tokens.  For the usual adapters (r <= 64, 16-byte aligned) the LoRA
   // down-projection runs on the first workgroups of the same launch; otherwise it gets a launch of its own.

@@ -50,6 +50,7 @@ struct StreamMember {
   int r; int t_off;                                      // rank; column offset of this member's t in the stacked t (INT_MAX if t_ext)
   int y_vec;                                             // y rows allow 16-byte stores (aligned base, ldy % 8 == 0)
   const float* t_ext;                                    // x A^T computed before the launch, fp32 [QERL_T_PARTS][M][r] partial sums, or null: producers compute it
+  const uint16_t* bias;                                  // [N] bf16 added to every token row, or null
   float lora_scale;
 };
 struct StreamArgs {
@@ -57,7 +58,7 @@ struct StreamArgs {
   int n_members; StreamMember mem[kMaxGroup];
   // flat copy of what the streaming loop needs of the member table (unused entries: INT_MAX / member 0's pointer)
   int tb1, tb2, tb3; const uint8_t* mp0; const uint8_t* mp1; const uint8_t* mp2; const uint8_t* mp3;
-  int total_tiles; int r_total; int any_lora;            // row-tiles; stacked rank the producers compute; any member with r > 0
+  int total_tiles; int r_total; int any_lora; int any_bias;            // row-tiles; stacked rank the producers compute; any member with r > 0
   int Sk; int kr_len; int per_range; int n_producers;    // K-ranges, K-tiles in each, consumer workgroups per range; producers
   int units_base; int units_rem;                         // consumer ci owns units_base (+1 if ci < units_rem) row-tiles
   int prod_steps; int prod_cb; int prod_red_off;          // producers: 16-input steps of K each, steps per LDS column block, offset of their reduction area
@@ -75,6 +76,7 @@ struct GemmArgs {
   const uint16_t* wbf16;                                                    // kFmtBf16: [N, K] dense rows (LoRA A)
   const uint16_t* ts; int64_t ts_ld; int ext_stages;                        // [M, ts_ld] bf16: hi | mid | lo of lora_scale * t
   const uint16_t* B; int r; float lora_scale;
+  const uint16_t* bias;                                                     // [N] bf16 or null
   uint16_t* y; int64_t ldy;
   int n_tiles; int n_blocks; int nblk_per_xcd;
   uint32_t* tpart; uint32_t* counters;                                      // LoRA down-projection over several K-parts: partial sums, arrival counts (zero between calls); or null
@@ -95,6 +97,7 @@ struct MidMember {
   const uint8_t* packed; const float* tensor_scale; int64_t N; int n_tiles;
   const uint16_t* ts; int64_t ts_ld; int ext_stages;                        // [M, ts_ld] bf16: hi | mid | lo of lora_scale / S32 * t; stages of 128 columns
   const uint16_t* B; int r;
+  const uint16_t* bias;                                                     // [N] bf16 or null
   uint16_t* y; int64_t ldy;
   int block_begin;                                                          // first column block (W row-tiles each) of this member
   int64_t partial_off;                                                      // floats: this member's [S][M][N] partial outputs start here

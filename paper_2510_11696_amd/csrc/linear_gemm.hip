@@ -230,10 +230,11 @@ main_done:
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
         const int64_t n = (int64_t)(nt0 + nt) * 32 + n32;
+        const float bias = (a.bias && n < a.N) ? bf16_bits_to_f32(a.bias[n]) : 0.f;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int64_t m = m0 + mt * 32 + 8 * (i >> 2) + 4 * kg + (i & 3);
-          if (m < a.M && n < a.N) a.y[m * a.ldy + n] = (uint16_t)f32_to_bf16_bits(acc[mt][nt][i] * S32);
+          if (m < a.M && n < a.N) a.y[m * a.ldy + n] = (uint16_t)f32_to_bf16_bits(acc[mt][nt][i] * S32 + bias);
         }
       }
   }

@@ -205,13 +205,14 @@ main_done:
   const float S32 = *mem.tensor_scale;
   const int64_t nn = (int64_t)nt * 32 + n32;
   if (nt >= mem.n_tiles || nn >= mem.N) return;
+  const float bias = (mem.bias && split == 0) ? bf16_bits_to_f32(mem.bias[nn]) : 0.f;   // split 0 carries it, like the LoRA columns
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int64_t m = m0 + mt * 32 + 8 * (i >> 2) + 4 * kg + (i & 3);
       if (m < a.M) {
-        const float v = acc[mt][i] * S32;
+        const float v = acc[mt][i] * S32 + bias;
         if (a.S == 1) mem.y[m * mem.ldy + nn] = (uint16_t)f32_to_bf16_bits(v);
         else a.partial[mem.partial_off + ((int64_t)split * a.M + m) * mem.N + nn] = v;
       }

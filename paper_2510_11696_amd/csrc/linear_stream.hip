@@ -259,6 +259,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
   // ---- what the epilogue wave reads from memory: requested ahead, because a load of that wave queues behind
   // the whole weight ring of its CU, a latency it must never wait out between one barrier and the next.
   const bool lora_range = range == 0 && a.any_lora != 0;   // only the first K-range adds the LoRA branch
+  const bool bias_range = range == 0 && a.any_bias != 0;   // ... and the bias
   // B rows (32 rows x r of the unit's member): one unit ahead, parked with the unit's sums
   u32x4 bnext[kLoraSteps];
   auto request_b = [&](int u) {
@@ -557,6 +558,13 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
       QTRACE(6);
     }
+    // the bias of this lane's output row, requested before the LoRA arithmetic that hides its latency; the
+    // first K-range carries it
+    uint16_t bias_bits = 0;
+    if (bias_range) {
+      const int64_t nb_row = (int64_t)(nt - mem.tile_begin) * 32 + n32;
+      if (mem.bias && nb_row < mem.N) bias_bits = mem.bias[nb_row];
+    }
     float out[MR];
 #pragma unroll
     for (int q = 0; q < MR; ++q) out[q] = pend_base[(slot * MR + q) * 64 + lane];
@@ -576,6 +584,11 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
       }
 #pragma unroll
       for (int q = 0; q < MR; ++q) out[q] += ((lh[q] + lm[q]) + ll[q]) * mem.lora_scale;
+    }
+    if (bias_range) {
+      const float bias = bf16_bits_to_f32(bias_bits);   // +0 for a member without one
+#pragma unroll
+      for (int q = 0; q < MR; ++q) out[q] += bias;
     }
     ++u_done;
     // out = this range's share of tile nt.  With several K-ranges it goes to the workspace as it is

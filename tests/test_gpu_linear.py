@@ -385,3 +385,40 @@ def test_full_size_14b_gate_at_prefill_as_the_benchmark_launches_it():
     rows = _sampled_rows(N, 8004, n=96)
     ref = oracle.nvfp4_lora_linear(x.float().numpy(), codes[rows], scales[rows], ts, A.float().numpy(), B.float().numpy()[rows], 1.0)
     check_linear(y[:, torch.from_numpy(rows).cuda()], ref, ("full-size prefill gate",))
+
+
+@pytest.mark.parametrize("M", [1, 8, 16, 40, 128, 200])
+@pytest.mark.parametrize("K,Ns,rs", [
+    (3584, (3584, 512, 512), (32, 32, 32)),      # q, k, v of the 7B block: the three projections that carry a bias
+    (18944, (96, 40), (32, 0)),                  # K split over workgroup ranges; a member without adapter; ragged tile
+])
+def test_bias_in_grouped_and_single_launches(M, K, Ns, rs):
+    print("bias case", M, K, Ns, rs, flush=True)
+    x = qs.activations(M, K, 9100 + M)
+    g = lambda a: torch.from_numpy(a).cuda()
+    ws_, As, Bs, biases, refs = [], [], [], [], []
+    for i, (N, r) in enumerate(zip(Ns, rs)):
+        W = cases.gaussian(N, K, 9200 + 10 * i + M)
+        codes, scales, ts = oracle.nvfp4_quantize(W)
+        A = B = None
+        if r:
+            A, B = qs.lora_pair(N, K, r, 9300 + i)
+        bias = (torch.randn(N, generator=torch.Generator().manual_seed(9400 + i)) * 0.5).to(torch.bfloat16)
+        ws_.append(qerl.nvfp4_prepack(g(codes), g(scales), torch.tensor([ts], device="cuda")))
+        As.append(A.cuda() if r else None)
+        Bs.append(B.cuda() if r else None)
+        biases.append(bias.cuda())
+        refs.append(oracle.nvfp4_lora_linear(x.float().numpy(), codes, scales, ts, A.float().numpy() if r else None,
+                                             B.float().numpy() if r else None, 2.0, bias=bias.float().numpy()))
+    outs = qerl.nvfp4_lora_linear_packed_group(x.cuda(), ws_, As, Bs, [2.0] * len(Ns), biases=biases)
+    torch.cuda.synchronize()
+    for i, (y, ref) in enumerate(zip(outs, refs)):
+        check_linear(y, ref, ("group with bias", i, M, K))
+        single = qerl.nvfp4_lora_linear_packed_group(x.cuda(), ws_[i:i + 1], As[i:i + 1], Bs[i:i + 1], [2.0],
+                                                     biases=biases[i:i + 1])[0]
+        check_linear(single, ref, ("single with bias", i, M, K))
+    # a member without bias next to members with one
+    mixed = qerl.nvfp4_lora_linear_packed_group(x.cuda(), ws_, As, Bs, [2.0] * len(Ns), biases=[biases[0]] + [None] * (len(Ns) - 1))
+    check_linear(mixed[0], refs[0], ("mixed", 0))
+    assert not torch.equal(mixed[1], outs[1])
+

@@ -109,3 +109,19 @@ def test_rmsnorm_noise_identities():
     assert not z.any()
     # zero noise vector == no noise
     assert np.array_equal(o.aqn_rmsnorm(x, g, np.zeros(H, dtype=np.float32)), y_clean)
+
+
+def test_bias_is_added_to_every_row_before_any_rounding():
+    """A zero weight tensor leaves y = bias in every row; in general y(bias) - y(no bias) = bias to the
+    last fp64 bit of the smaller term, LoRA or not."""
+    W, x, A, B = _tiny(6, 32, 3, 2, 77)
+    bias = np.array([0.5, -1.25, 3.0, 0.0, -0.0078125, 100.0], dtype=np.float32)
+    codes0, scales0, ts0 = o.nvfp4_quantize(np.zeros_like(W))
+    y0 = o.nvfp4_lora_linear(x, codes0, scales0, ts0, bias=bias)
+    assert (y0 == bias[None, :].astype(np.float64)).all()
+    codes, scales, ts = o.nvfp4_quantize(W)
+    plain = o.nvfp4_lora_linear(x, codes, scales, ts, A, B, 2.0)
+    with_bias = o.nvfp4_lora_linear(x, codes, scales, ts, A, B, 2.0, bias=bias)
+    assert np.allclose(with_bias - plain, bias[None, :], rtol=0, atol=1e-12)
+    assert with_bias.shape == plain.shape
+

@@ -63,6 +63,7 @@ struct StreamArgs {
   int units_base; int units_rem;                         // consumer ci owns units_base (+1 if ci < units_rem) row-tiles
   int prod_steps; int prod_cb; int prod_red_off;          // producers: 16-input steps of K each, steps per LDS column block, offset of their reduction area
   int xs_stride; int red_off; int pend_off; int tsum_off;   // LDS layout (bytes): x row stride, reduction buffers, parked units, t of a member
+  int red_bufs; int max_pending; int pend_steps;          // reduction buffers, parking slots, 16-rank steps of B parked per slot
   float* t; uint32_t* lora_ctl; uint32_t* tpart;         // stacked t [M, r_total]; hand-over words; producer partials
   uint32_t* partial; uint32_t* counters;                 // K-range exchange
 };

@@ -190,13 +190,15 @@ __device__ __forceinline__ void stream_producer(const StreamArgs& a, unsigned ch
 
 struct StreamTile { u32x4 c0, c1; u32x2 sc; };
 
-constexpr int kRedBufs = 4;                // partial-tile buffers between the main waves and the epilogue wave
+constexpr int kRedBufs = 4;                // partial-tile buffers between the main waves and the epilogue wave (at most; 2 when LDS is short)
 constexpr int kLoraSteps = 4;               // 16-wide j steps of the up-projection (r <= 64)
-constexpr int kMaxPending = 4;              // units an epilogue wave can park while t is not ready
+constexpr int kMaxPending = 4;              // units an epilogue wave can park while t is not ready (at most; 2 when LDS is short)
 
-template <int MR, int D>
+// TIGHT: two reduction buffers and parking slots instead of four, B fragments parked for the adapters' actual
+// rank only (the LDS budget of 16 tokens with K = 3584 in one range)
+template <int MR, int D, bool TIGHT>
 __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamArgs a) {
-  // x slice [(M+1) rows][xs_stride bytes], red[kRedBufs][7][64][MR] floats, parked units, t of a member.  The alignment matters:
+  // x slice [M (+ 1 zero) rows][xs_stride bytes], red[red_bufs][7][64][MR] floats, parked units, t of a member.  The alignment matters:
   // 16-byte LDS accesses from a misaligned base run several times slower.
   extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
   __shared__ StreamMember s_mem[kMaxGroup];
@@ -241,7 +243,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
 #pragma unroll
       for (int tok = 0; tok < MT; ++tok)
         if (tok < a.M) *reinterpret_cast<u32x4*>(smem + tok * a.xs_stride + ch * 16) = xv[tok];
-      *reinterpret_cast<u32x4*>(smem + a.M * a.xs_stride + ch * 16) = u32x4{0u, 0u, 0u, 0u};   // the zero row
+      if (!TIGHT) *reinterpret_cast<u32x4*>(smem + a.M * a.xs_stride + ch * 16) = u32x4{0u, 0u, 0u, 0u};   // the zero row
     }
   };
   u32x4 xv[MT];
@@ -258,6 +260,8 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
 
   // ---- what the epilogue wave reads from memory: requested ahead, because a load of that wave queues behind
   // the whole weight ring of its CU, a latency it must never wait out between one barrier and the next.
+  constexpr int red_bufs = TIGHT ? 2 : kRedBufs, max_pending = TIGHT ? 2 : kMaxPending;
+  const int pend_steps = TIGHT ? a.pend_steps : kLoraSteps;
   const bool lora_range = range == 0 && a.any_lora != 0;   // only the first K-range adds the LoRA branch
   const bool bias_range = range == 0 && a.any_bias != 0;   // ... and the bias
   // B rows (32 rows x r of the unit's member): one unit ahead, parked with the unit's sums
@@ -345,7 +349,11 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
     QSTART(6);
     QTRACE(1);
 
-    const int xrow = n32 < a.M ? n32 : a.M;          // tokens >= M read the zero row
+    // MFMA rows beyond the tokens read a zero row (all-zero operand rows also keep the matrix unit's power
+    // down: measurably faster than feeding it copies of a real row).  Where LDS is short there is none and
+    // they read the last token's row: an output row depends on its own input row only, and rows >= M are
+    // never stored, so any data will do there.
+    const int xrow = n32 < a.M ? n32 : (TIGHT ? a.M - 1 : a.M);
     const unsigned char* xbase = smem + xrow * a.xs_stride + kg * 16;
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     float acc[MR];
@@ -391,18 +399,18 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
             // Unit finished: hand the partial tile to the epilogue wave through one of kRedBufs buffers and
             // go on.  No barrier: the waves of a workgroup drift apart freely, and only a buffer that the
             // epilogue wave has not taken over yet (it is kRedBufs units behind) makes this wave wait.
-            if (cu >= kRedBufs) {
-              while (__hip_atomic_load(&s_cons, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < cu - kRedBufs + 1)
+            if (cu >= red_bufs) {
+              while (__hip_atomic_load(&s_cons, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < cu - red_bufs + 1)
                 __builtin_amdgcn_s_sleep(1);
             }
-            float* slot = red + (((cu % kRedBufs) * kMainWaves + wave) * 64 + lane) * MR;
+            float* slot = red + (((cu % red_bufs) * kMainWaves + wave) * 64 + lane) * MR;
 #pragma unroll
             for (int q = 0; q < MR; q += 4) {
               *reinterpret_cast<f32x4*>(slot + q) = f32x4{acc[q], acc[q + 1], acc[q + 2], acc[q + 3]};
               acc[q] = 0.f; acc[q + 1] = 0.f; acc[q + 2] = 0.f; acc[q + 3] = 0.f;
             }
             QTRACE(2 + (cu < 4 ? cu : 4));
-            if (lane == 0) __hip_atomic_fetch_add(&s_prod[cu % kRedBufs], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (lane == 0) __hip_atomic_fetch_add(&s_prod[cu % red_bufs], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
             ++cu;
           }
           ck = kt0;
@@ -447,8 +455,8 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
   u32x4 th[kLoraSteps], tm[kLoraSteps], tl[kLoraSteps];
   int t_member = -1;                      // member whose split t is in th/tm/tl
   bool poisoned = false, t_ready = a.n_producers == 0;
-  float* pend_base = reinterpret_cast<float*>(smem + a.pend_off);          // [kMaxPending][MR][64]
-  u32x4* pend_b = reinterpret_cast<u32x4*>(smem + a.pend_off + kMaxPending * MR * 64 * 4);   // [kMaxPending][kLoraSteps][64]
+  float* pend_base = reinterpret_cast<float*>(smem + a.pend_off);          // [max_pending][MR][64]
+  u32x4* pend_b = reinterpret_cast<u32x4*>(smem + a.pend_off + max_pending * MR * 64 * 4);   // [max_pending][pend_steps][64]
   int u_recv = 0, u_done = 0;             // units received / finalized so far
   int b_wanted = -1;                      // unit whose B rows are to be requested next
   // t of member mi: its partial sums (QERL_T_PARTS slices of K computed before the launch, or the producers'
@@ -495,17 +503,19 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
 
   while (u_done < n_units) {
     if (b_wanted >= 0) { request_b(b_wanted); b_wanted = -1; }
-    if (u_recv < n_units && u_recv - u_done < kMaxPending) {
+    if (u_recv < n_units && u_recv - u_done < max_pending) {
       // ---- receive unit u_recv
-      const int u = u_recv, slot = u % kMaxPending;
+      const int u = u_recv, slot = u % max_pending;
       const int nt = u0 + u;
       const int mi = member_index(nt);
       QTRACE(2 + (u < 4 ? u : 4));
-      while (__hip_atomic_load(&s_prod[u % kRedBufs], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < n_live)
-        __builtin_amdgcn_s_sleep(1);      // the live waves' partial tiles of unit u are in red[u % kRedBufs]
+      const int rb = u % red_bufs;
+      while (__hip_atomic_load(&s_prod[rb], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < n_live)
+        __builtin_amdgcn_s_sleep(1);      // the live waves' partial tiles of unit u are in red[u % red_bufs]
       if (lora_range) {
 #pragma unroll
-        for (int s = 0; s < kLoraSteps; ++s) pend_b[(slot * kLoraSteps + s) * 64 + lane] = bnext[s];
+        for (int s = 0; s < kLoraSteps; ++s)
+          if (s < pend_steps) pend_b[(slot * pend_steps + s) * 64 + lane] = bnext[s];
         b_wanted = u + 1;                 // requested at the end of this round: nothing finalize waits for may queue behind it
       }
       float S32 = S32m[0];
@@ -518,7 +528,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
 #pragma unroll
           for (int q4 = 0; q4 < MR / 4; ++q4) {
             part[w][q4] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (w < n_live) part[w][q4] = *reinterpret_cast<const f32x4*>(red + (((u % kRedBufs) * kMainWaves + w) * 64 + lane) * MR + 4 * q4);
+            if (w < n_live) part[w][q4] = *reinterpret_cast<const f32x4*>(red + ((rb * kMainWaves + w) * 64 + lane) * MR + 4 * q4);
           }
 #pragma unroll
         for (int q = 0; q < MR; ++q) {
@@ -531,19 +541,19 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
       // the buffer may be written again (its reads above have returned: the sums were formed from them);
       // its counter goes back to zero before the main waves are told
       if (lane == 0) {
-        __hip_atomic_store(&s_prod[u % kRedBufs], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        __hip_atomic_store(&s_prod[rb], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         __hip_atomic_store(&s_cons, u + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
       }
       ++u_recv;
     }
     // ---- finalize the oldest received unit, if it can be
-    const int u = u_done, slot = u % kMaxPending;
+    const int u = u_done, slot = u % max_pending;
     const int nt = u0 + u;
     const int mi = member_index(nt);
     const StreamMember mem = s_mem[mi];
     const bool needs_lora = lora_range && mem.r > 0;
     if (needs_lora && !t_ready && !mem.t_ext) {
-      const bool can_receive_more = u_recv < n_units && u_recv - u_done < kMaxPending;
+      const bool can_receive_more = u_recv < n_units && u_recv - u_done < max_pending;
       uint32_t spins = 0;
       for (;;) {
         if (__hip_atomic_load(a.lora_ctl + kCtlArrive, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)a.n_producers) {
@@ -576,7 +586,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
 #pragma unroll
       for (int s = 0; s < kLoraSteps; ++s) {
         if (16 * s < mem.r) {
-          const bf16x8 bf = __builtin_bit_cast(bf16x8, pend_b[(slot * kLoraSteps + s) * 64 + lane]);
+          const bf16x8 bf = __builtin_bit_cast(bf16x8, pend_b[(slot * pend_steps + s) * 64 + lane]);
           lh = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, th[s]), bf, lh, 0, 0, 0);
           lm = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tm[s]), bf, lm, 0, 0, 0);
           ll = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tl[s]), bf, ll, 0, 0, 0);
@@ -695,18 +705,23 @@ __global__ __launch_bounds__(256) void stream_reduce_kernel(const ReduceArgs a) 
 static int g_force_ranges = 0;
 static int g_force_depth = 0;
 
-// LDS layout for M tokens (+ zero row) of a K-range of kr_len K-tiles: x slice, reduction buffers, and --
-// with LoRA -- the parking area of the epilogue wave.  Producers use the start of the same allocation.
-struct StreamLds { int kr_len, xs_stride, red_off, pend_off, tsum_off; size_t total; };
-static StreamLds stream_lds(int M, int kr_len, int MR, bool lora) {
+// LDS layout for M tokens of a K-range of kr_len K-tiles: x slice, reduction buffers, the parking area of
+// the epilogue wave (sums always; B fragments for `steps` 16-rank steps with LoRA), t of a member.  `roomy`:
+// four reduction buffers and four parking slots; otherwise two of each (the main waves and the epilogue wave
+// are then coupled more tightly), which is what lets 16 tokens of K = 3584 fit without splitting K.
+struct StreamLds { int kr_len, xs_stride, red_off, pend_off, tsum_off, red_bufs, max_pending, pend_steps; size_t total; };
+static StreamLds stream_lds(int M, int kr_len, int MR, int steps, bool roomy) {
   StreamLds l{};
   l.kr_len = kr_len;
-  l.xs_stride = kr_len * 256 + 16;   // rows 16 bytes apart in bank space: token rows and the zero row read conflict-free
-  const size_t xs = (size_t)(M + 1) * (size_t)l.xs_stride;
+  l.red_bufs = roomy ? kRedBufs : 2; l.max_pending = roomy ? kMaxPending : 2;
+  l.pend_steps = roomy ? (steps > 0 ? kLoraSteps : 0) : steps;
+  steps = l.pend_steps;
+  l.xs_stride = kr_len * 256 + 16;   // rows 16 bytes apart in bank space: the token rows read conflict-free
+  const size_t xs = (size_t)(M + (roomy ? 1 : 0)) * (size_t)l.xs_stride;   // + the zero row
   l.red_off = (int)((xs + 255) & ~(size_t)255);
-  const size_t red_consumer = (size_t)kRedBufs * kMainWaves * MR * 64 * sizeof(float);
+  const size_t red_consumer = (size_t)l.red_bufs * kMainWaves * MR * 64 * sizeof(float);
   l.pend_off = l.red_off + (int)red_consumer;
-  const size_t pend = (size_t)kMaxPending * (MR * 64 * sizeof(float) + (lora ? kLoraSteps * 64 * 16 : 0));   // sums always, B fragments with LoRA
+  const size_t pend = (size_t)l.max_pending * (MR * 64 * sizeof(float) + (size_t)steps * 64 * 16);
   l.tsum_off = l.pend_off + (int)pend;
   const size_t tsum = (size_t)16 * 64 * sizeof(float) + 16 * 32 * 2;               // t of one member (up to 16 tokens x 64 ranks); output tile staging
   l.total = l.tsum_off + tsum;
@@ -718,8 +733,14 @@ constexpr size_t kStreamLdsMax = 160 * 1024 - 512;   // the static flag word tak
 int plan_stream(StreamArgs& a, size_t* lds_bytes, int* MR_out) {
   const int MR = a.M <= 8 ? 4 : 8;
   *MR_out = MR;
-  const bool lora = a.any_lora != 0;
-  const size_t lds_cap = 150 * 1024;
+  int r_max = 0;
+  for (int i = 0; i < a.n_members; ++i) r_max = a.mem[i].r > r_max ? a.mem[i].r : r_max;
+  const int steps = (int)ceil_div(r_max, 16);             // B fragments parked per unit: 16 ranks each
+  const size_t lds_cap = kStreamLdsMax - 2048;
+  auto layout = [&](int kr_len) {                          // the roomy layout if it fits
+    const StreamLds l = stream_lds(a.M, kr_len, MR, steps, true);
+    return l.total <= lds_cap ? l : stream_lds(a.M, kr_len, MR, steps, false);
+  };
   // Number of K-ranges: at least what makes the x slice fit, and beyond that whatever gives the shortest
   // critical path -- tiles a main wave multiplies one after the other (about half a microsecond each), plus
   // the second launch that adds the ranges' partial tiles once K is split at all.  A unit cannot take less
@@ -732,7 +753,7 @@ int plan_stream(StreamArgs& a, size_t* lds_bytes, int* MR_out) {
   double best_cost = 0;
   for (int Sk = 1; Sk <= sk_limit; ++Sk) {
     const int kr_len = (int)ceil_div(a.k_tiles, Sk);
-    if (stream_lds(a.M, kr_len, MR, lora).total > lds_cap) continue;
+    if (layout(kr_len).total > lds_cap) continue;
     if (g_force_ranges > 0 && Sk != g_force_ranges) continue;
     int64_t per_range = cus / Sk;
     if (per_range < 1) break;
@@ -745,8 +766,9 @@ int plan_stream(StreamArgs& a, size_t* lds_bytes, int* MR_out) {
   }
   if (best == 0) return QERL_ERR_SHAPE;
   const int Sk = best;
-  const StreamLds l = stream_lds(a.M, (int)ceil_div(a.k_tiles, Sk), MR, lora);
+  const StreamLds l = layout((int)ceil_div(a.k_tiles, Sk));
   size_t total = l.total;
+  a.red_bufs = l.red_bufs; a.max_pending = l.max_pending; a.pend_steps = l.pend_steps;
   if (a.n_producers > 0) {
     // producers: column blocks of their K share as large as LDS allows (one block = one round of loads)
     const int64_t steps = a.K / 16;
@@ -772,16 +794,16 @@ int plan_stream(StreamArgs& a, size_t* lds_bytes, int* MR_out) {
   return QERL_OK;
 }
 
-template <int MR, int D>
+template <int MR, int D, bool TIGHT>
 static int launch_stream_t(const StreamArgs& a, size_t lds, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_kernel<MR, D>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_kernel<MR, D, TIGHT>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStreamLdsMax) != hipSuccess)
       return launch_status();
     attr_set = true;
   }
-  stream_kernel<MR, D><<<dim3(a.n_producers + a.per_range * a.Sk), dim3(kStreamWaves * 64), lds, st>>>(a);
+  stream_kernel<MR, D, TIGHT><<<dim3(a.n_producers + a.per_range * a.Sk), dim3(kStreamWaves * 64), lds, st>>>(a);
   if (a.Sk > 1) {
     const int rc = launch_status();
     if (rc != QERL_OK) return rc;
@@ -816,12 +838,23 @@ int launch_stream(const StreamArgs& a, size_t lds, int MR, hipStream_t st) {
     return QERL_ERR_SHAPE;
   if (a.M < 1 || a.M > 16 || a.K < 16 || a.k_tiles < 1 || a.Sk < 1 || a.per_range < 1 || a.kr_len < 1 || (int64_t)a.kr_len * a.Sk < a.k_tiles ||
       a.units_base * a.per_range + a.units_rem != a.total_tiles ||
-      a.total_tiles < 1 || lds > kStreamLdsMax || a.red_off <= 0 || a.pend_off < a.red_off)
+      a.total_tiles < 1 || lds > kStreamLdsMax || a.red_off <= 0 || a.pend_off < a.red_off ||
+      a.red_bufs < 2 || a.red_bufs > kRedBufs || a.max_pending < 2 || a.max_pending > kMaxPending || a.pend_steps < 0 ||
+      a.pend_steps > kLoraSteps || (size_t)a.red_off < (size_t)(a.M + (a.red_bufs == 2 ? 0 : 1)) * (size_t)a.xs_stride ||
+      (size_t)(a.pend_off - a.red_off) < (size_t)a.red_bufs * kMainWaves * MR * 64 * sizeof(float) ||
+      (size_t)(a.tsum_off - a.pend_off) < (size_t)a.max_pending * (MR * 64 * sizeof(float) + (size_t)a.pend_steps * 64 * 16) ||
+      (size_t)a.tsum_off + 16 * 64 * sizeof(float) + 16 * 32 * 2 > lds)
     return QERL_ERR_SHAPE;
-  if (MR == 4 && g_force_depth == 3) return launch_stream_t<4, 3>(a, lds, st);
-  if (MR == 4 && g_force_depth == 6) return launch_stream_t<4, 6>(a, lds, st);
-  if (MR == 4) return launch_stream_t<4, 4>(a, lds, st);
-  return launch_stream_t<8, 4>(a, lds, st);
+  const bool tight = a.red_bufs == 2;
+  if (tight != (a.max_pending == 2) || (!tight && (a.red_bufs != kRedBufs || a.max_pending != kMaxPending ||
+                                                   (a.pend_steps != kLoraSteps && a.pend_steps != 0))))
+    return QERL_ERR_SHAPE;
+  if (MR == 4 && tight) return launch_stream_t<4, 4, true>(a, lds, st);
+  if (MR == 4 && g_force_depth == 3) return launch_stream_t<4, 3, false>(a, lds, st);
+  if (MR == 4 && g_force_depth == 6) return launch_stream_t<4, 6, false>(a, lds, st);
+  if (MR == 4) return launch_stream_t<4, 4, false>(a, lds, st);
+  if (tight) return launch_stream_t<8, 4, true>(a, lds, st);
+  return launch_stream_t<8, 4, false>(a, lds, st);
 }
 
 }  // namespace qerl

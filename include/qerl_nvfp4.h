@@ -215,7 +215,7 @@ QERL_API int aqn_rmsnorm(const void* x_bf16, int64_t M, int64_t H, int64_t ldx,
  * is the fp32 product of the ROUNDED y that this call writes (what the linear
  * kernels would compute themselves from y) in a fixed summation order.
  * Errors: as aqn_rmsnorm, plus M > 16, H % 16 != 0, H > 8192, n_adapters outside
- * 1..4, ranks not multiples of 8 in 8..64 or summing to more than 128
+ * 1..4, ranks not multiples of 8 in 8..64
  * (QERL_ERR_SHAPE); unaligned rows or pointers (QERL_ERR_ALIGN).
  */
 QERL_API int aqn_rmsnorm_lora_down(const void* x_bf16, int64_t M, int64_t H, int64_t ldx,

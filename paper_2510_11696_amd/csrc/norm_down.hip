@@ -26,7 +26,7 @@ namespace qerl {
 constexpr int kNdThreads = 512, kNdWaves = 8;
 constexpr int kNdMaxAdapters = 4;
 constexpr int kNdParts = QERL_T_PARTS;
-constexpr int kNdMaxTiles = 4;             // 32-rank tiles of the stacked adapters: sum of ranks <= 128
+constexpr int kNdMaxTiles = 8;             // 32-rank tiles of the stacked adapters (one workgroup column each): four adapters of rank 64
 constexpr int kNdStepsPerWave = 4;         // 16-input steps of the slice per wave held in registers at a time
 
 #ifdef QERL_ND_TRACE

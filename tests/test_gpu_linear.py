@@ -277,6 +277,7 @@ def test_grouped_launch_equals_oracle(M, K, Ns, rs):
     (2048, (96, 64), (64, 16), None),               # two rank tiles in one adapter; a partial rank tile; stage 0
     (4096, (64,), (8,), 1e-2),
     (5120, (1024, 96), (64, 64), 5e-3),             # rows longer than 4096: the wide variants; 14B / 32B hidden size
+    (5120, (160, 64, 64), (64, 64, 64), 1e-2),      # q, k, v adapters of the 32B configuration: six rank tiles
 ])
 def test_norm_with_lora_down_feeds_grouped_linear(M, H, Ns, rs, sigma):
     """aqn_rmsnorm_lora_down: y within one bf16 unit of the oracle (as aqn_rmsnorm), t = y A^T within fp32 summation error of

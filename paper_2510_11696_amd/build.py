@@ -25,7 +25,7 @@ COMMON = [
     "-Wno-unused-command-line-argument",
 ]
 PER_FILE = {"quantize.hip": ["-ffp-contract=off"]}
-# extra hipcc flags for tuning builds, e.g. QERL_EXTRA_HIPCC_FLAGS=-DQERL_STREAM_TRACE
+# extra hipcc flags for tuning builds, e.g. QERL_EXTRA_HIPCC_FLAGS="-DQERL_TUNING_HOOKS -DQERL_STREAM_TRACE=1"
 COMMON += os.environ.get("QERL_EXTRA_HIPCC_FLAGS", "").split()
 
 

@@ -289,7 +289,9 @@ static int mid_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const
 }
 }  // namespace qerl
 
+#ifdef QERL_TUNING_HOOKS   // built only for tuning sessions: they change process-wide state
 extern "C" QERL_API void qerl_debug_use_stream(int on) { qerl::g_use_stream = on != 0; }
+#endif  // QERL_TUNING_HOOKS
 
 static int packed_single(const void* x, int64_t M, int64_t K, int64_t ldx, const void* packed,
                          const float* tensor_scale, int64_t N, const void* A, const void* B,

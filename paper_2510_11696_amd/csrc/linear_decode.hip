@@ -524,7 +524,9 @@ int launch_prepack(const uint8_t* codes, const uint8_t* scales, int64_t N, int64
 
 // Tuning hook for experiments (not part of the public header): force K-tiles per
 // wave (1, 2) and row-tiles per workgroup (1, 2, 4); 0 = automatic.
+#ifdef QERL_TUNING_HOOKS   // built only for tuning sessions: they change process-wide state
 extern "C" QERL_API void qerl_debug_force_decode(int kw, int t) {
   qerl::g_force_kw = kw;
   qerl::g_force_t = t;
 }
+#endif  // QERL_TUNING_HOOKS

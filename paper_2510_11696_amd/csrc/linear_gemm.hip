@@ -504,4 +504,6 @@ int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st) {
 }  // namespace qerl
 
 // Tuning hook for experiments (not part of the public header): force a GEMM tile configuration, -1 = automatic.
+#ifdef QERL_TUNING_HOOKS   // built only for tuning sessions: they change process-wide state
 extern "C" QERL_API void qerl_debug_force_gemm(int cfg) { qerl::g_force_cfg = cfg; }
+#endif  // QERL_TUNING_HOOKS

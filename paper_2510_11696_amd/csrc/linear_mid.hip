@@ -337,5 +337,7 @@ int launch_mid(const MidArgs& a, hipStream_t st) {
 }  // namespace qerl
 
 // Tuning hook for experiments (not part of the public header): waves per workgroup and K-splits, 0 = automatic.
+#ifdef QERL_TUNING_HOOKS   // built only for tuning sessions: they change process-wide state
 extern "C" QERL_API void qerl_debug_force_mid(int waves, int splits) { qerl::g_force_w = waves; qerl::g_force_s = splits; }
 extern "C" QERL_API void qerl_debug_mid_max_tokens(int m) { qerl::g_mid_max_tokens = m; }
+#endif  // QERL_TUNING_HOOKS

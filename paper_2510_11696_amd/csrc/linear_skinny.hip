@@ -356,7 +356,9 @@ int launch_skinny(const SkinnyPlan& p, const SkinnyArgs& a, int fmt, hipStream_t
 
 // Tuning hook for experiments (not part of the public header): force the
 // K-tiles per wave (1 or 2) and rows-per-workgroup factor (1, 2, 4); 0 = automatic.
+#ifdef QERL_TUNING_HOOKS   // built only for tuning sessions: they change process-wide state
 extern "C" QERL_API void qerl_debug_force_skinny(int kt, int t) {
   qerl::g_force_kt = kt;
   qerl::g_force_t = t;
 }
+#endif  // QERL_TUNING_HOOKS

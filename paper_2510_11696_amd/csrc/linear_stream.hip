@@ -860,8 +860,10 @@ int launch_stream(const StreamArgs& a, size_t lds, int MR, hipStream_t st) {
 }  // namespace qerl
 
 // Tuning hooks for experiments (not part of the public header): number of K-ranges and ring depth; 0 = automatic.
+#ifdef QERL_TUNING_HOOKS   // built only for tuning sessions: they change process-wide state
 extern "C" QERL_API void qerl_debug_force_stream(int ranges) { qerl::g_force_ranges = ranges; }
 extern "C" QERL_API void qerl_debug_force_stream_depth(int d) { qerl::g_force_depth = d; }
+#endif  // QERL_TUNING_HOOKS
 #ifdef QERL_STREAM_TRACE
 extern "C" QERL_API int qerl_debug_read_trace(void* dst, size_t bytes) {
   return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(qerl::g_trace), bytes, 0, hipMemcpyDeviceToHost);

@@ -116,3 +116,68 @@ def test_sigma_schedules_match_the_oracle():
         bad = qerl.aqn_sigma_schedule(kind, 11, 10, 1e-2, 5e-4)
         assert bad != bad   # NaN
 
+
+def test_host_side_validation_of_the_fused_entry_points(lib):
+    """Group linear, fused norm + LoRA-down, packed linear and noise fill: every call fails validation on the
+    host (or is a no-op) before anything could be launched, so none of the fake pointers is ever dereferenced."""
+    from paper_2510_11696_amd.binding import _LinearDesc
+    fake = 0x10000
+    grp = lib.nvfp4_lora_linear_packed_group
+    d = (_LinearDesc * 5)()
+    for i in range(5):
+        d[i] = _LinearDesc(fake, fake, 32, None, None, 0, 0.0, fake, 32, None, None)
+    dp = ctypes.cast(d, ctypes.c_void_p)
+    big = 1 << 26
+    assert grp(fake, 2, 64, 64, None, 1, fake, big, None) == -1            # no descriptors
+    assert grp(fake, 2, 64, 64, dp, 0, fake, big, None) == -2               # 0 members
+    assert grp(fake, 2, 64, 64, dp, 5, fake, big, None) == -2               # more than 4
+    assert grp(fake, 0, 64, 64, dp, 2, fake, big, None) == 0                # no tokens: no-op
+    assert grp(fake + 2, 2, 64, 64, dp, 2, fake, big, None) == -3           # x not 16-byte aligned
+    assert grp(fake, 2, 64, 68, dp, 2, fake, big, None) == -3               # ldx % 8
+    assert grp(fake, 2, 64, 64, dp, 2, None, big, None) == -4
+    assert grp(fake, 2, 64, 64, dp, 2, fake, 64, None) == -4
+    d[1].ldy = 16                                                            # ldy < N
+    assert grp(fake, 2, 64, 64, dp, 2, fake, big, None) == -2
+    d[1].ldy = 32
+    d[1].r = 8                                                               # rank without A / B
+    assert grp(fake, 2, 64, 64, dp, 2, fake, big, None) == -1
+    d[1].A = fake; d[1].B = fake; d[1].t = fake + 4                          # precomputed t not 32-byte aligned
+    assert grp(fake, 2, 64, 64, dp, 2, fake, big, None) == -3
+
+    pk = lib.nvfp4_lora_linear_packed
+    assert pk(fake, 0, 64, 64, fake, fake, 16, None, None, 0, 0.0, fake, 16, fake, big, None) == 0
+    assert pk(fake, 2, 64, 64, fake + 8, fake, 16, None, None, 0, 0.0, fake, 16, fake, big, None) == -3
+    assert pk(fake, 2, 0, 0, fake, fake, 16, None, None, 0, 0.0, fake, 16, fake, big, None) == -2
+    assert lib.nvfp4_prepack(fake, fake, 4, 24, fake, None) == -2
+    assert lib.nvfp4_prepack(fake, fake, 4, 32, fake + 4, None) == -3
+    assert lib.nvfp4_prepack(None, fake, 4, 32, fake, None) == -1
+    assert lib.nvfp4_prepack(fake, fake, 0, 32, fake, None) == 0
+    assert lib.nvfp4_prepack_bytes(33, 130) == 2 * 2 * 2304 and lib.nvfp4_prepack_bytes(0, 64) == 0
+
+    nd = lib.aqn_rmsnorm_lora_down
+    A = (ctypes.c_void_p * 5)(*([fake] * 5)); T = (ctypes.c_void_p * 5)(*([fake] * 5))
+    R = (ctypes.c_int64 * 5)(32, 32, 32, 32, 32)
+    ap, tp, rp = (ctypes.cast(v, ctypes.c_void_p) for v in (A, T, R))
+    assert nd(fake, 17, 64, 64, fake, None, 1e-6, fake, 64, ap, rp, tp, 1, None) == -2     # more than 16 tokens
+    assert nd(fake, 2, 72, 72, fake, None, 1e-6, fake, 72, ap, rp, tp, 1, None) == -2      # H % 16
+    assert nd(fake, 2, 16384, 16384, fake, None, 1e-6, fake, 16384, ap, rp, tp, 1, None) == -2
+    assert nd(fake, 2, 64, 64, fake, None, 1e-6, fake, 64, ap, rp, tp, 0, None) == -2
+    assert nd(fake, 2, 64, 64, fake, None, 1e-6, fake, 64, ap, rp, tp, 5, None) == -2
+    assert nd(fake, 2, 64, 64, None, None, 1e-6, fake, 64, ap, rp, tp, 1, None) == -1
+    assert nd(fake, 2, 64, 64, fake, None, 1e-6, fake, 64, None, rp, tp, 1, None) == -1
+    assert nd(fake + 2, 2, 64, 64, fake, None, 1e-6, fake, 64, ap, rp, tp, 1, None) == -3
+    R[0] = 12                                                                              # rank not a multiple of 8
+    assert nd(fake, 2, 64, 64, fake, None, 1e-6, fake, 64, ap, rp, tp, 1, None) == -2
+    R[0] = 72
+    assert nd(fake, 2, 64, 64, fake, None, 1e-6, fake, 64, ap, rp, tp, 1, None) == -2
+    R[0] = 32
+    assert nd(fake, 0, 64, 64, fake, None, 1e-6, fake, 64, ap, rp, tp, 1, None) == 0
+
+    nf = lib.aqn_noise_fill
+    assert nf(None, 0, 1e-2, 1, 1, None) == 0
+    assert nf(None, 8, 1e-2, 1, 1, None) == -1
+    assert nf(fake, -1, 1e-2, 1, 1, None) == -2
+    assert nf(fake, 8, -1e-2, 1, 1, None) == -2
+    assert nf(fake, 8, float("inf"), 1, 1, None) == -2
+    assert nf(fake + 2, 8, 1e-2, 1, 1, None) == -3
+

@@ -260,6 +260,50 @@ QERL_API double aqn_sigma_schedule(int kind, int stage_k, int num_stages, double
 QERL_API int aqn_noise_fill(float* noise_f32, int64_t n, float sigma, uint64_t seed, uint64_t subsequence,
                             void* stream);
 
+/* ---------------------------------------------------------------------------
+ * MXFP4 variant (Preliminary, "Model Quantization": FP4 E2M1 elements with one
+ * shared FP8 E8M0 scale -- a power of two -- per block of 32; the paper evaluates
+ * it next to NVFP4).  Blocks run along K.  The paper states no conversion rule;
+ * these functions follow the OCP Microscaling (MX) v1.0 one: per block
+ * X = floor(log2(max |v|)) - emax_elem (2 for E2M1, 8 for E4M3) clamped to
+ * [-127, 127], scale byte = X + 127, element = round-to-nearest-even of v / 2^X,
+ * saturating at the largest element (6, 448); an all-zero block gets byte 0.
+ *
+ * mxfp4_quantize:  W [N, ldw] bf16 -> codes [N, K/2] (low nibble = even k, bit 3
+ *                  of a nibble = sign), scales [N, K/32] E8M0.  K % 32 == 0.
+ * mxfp4_dequantize: -> W_hat [N, K] fp32 = 2^(scale - 127) * E2M1(code), exact.
+ * mxfp8_quantize:  x [M, ldx] bf16 -> codes [M, K] E4M3 bytes (bit 7 = sign),
+ *                  scales [M, K/32] E8M0: the activation format of the native path.
+ * mxfp4_prepack:   codes/scales -> tiles of 32 rows x 128 inputs (2176 bytes) in the
+ *                  operand order of the scaled matrix instruction; packed must be
+ *                  16-byte aligned, mxfp4_prepack_bytes(N, K) bytes.
+ * mxfp4_linear_native: y [M, N] bf16 = MXFP8(x) . MXFP4(W)^T for decode-sized
+ *   batches (M <= 32), both operands going through CDNA4's block-scaled matrix
+ *   instruction as stored (no conversion arithmetic).  NOT the paper's setting:
+ *   there activations stay bf16 (weight-only).  x is quantised to MXFP8 inside the
+ *   call (into the workspace); the result is the exact product of the two
+ *   quantised operands summed in fp32, rounded once to bf16; it differs from the
+ *   weight-only result by the activation rounding (up to 2^-4 relative per
+ *   element).  No LoRA branch and no bias in this variant.
+ *   workspace: >= mxfp4_linear_native_workspace_bytes(M, N, K), 256-byte aligned;
+ *   needs no initialisation.
+ * Errors: as the NVFP4 functions (NULL, shape incl. K % 32 and M > 32, alignment,
+ * workspace).
+ */
+QERL_API int mxfp4_quantize(const void* W_bf16, int64_t N, int64_t K, int64_t ldw,
+                            uint8_t* codes, uint8_t* scales_e8m0, void* stream);
+QERL_API int mxfp4_dequantize(const uint8_t* codes, const uint8_t* scales_e8m0, int64_t N, int64_t K,
+                              float* W_f32, void* stream);
+QERL_API int mxfp8_quantize(const void* x_bf16, int64_t M, int64_t K, int64_t ldx,
+                            uint8_t* codes_e4m3, uint8_t* scales_e8m0, void* stream);
+QERL_API size_t mxfp4_prepack_bytes(int64_t N, int64_t K);   /* host */
+QERL_API int mxfp4_prepack(const uint8_t* codes, const uint8_t* scales_e8m0, int64_t N, int64_t K,
+                           void* packed, void* stream);
+QERL_API size_t mxfp4_linear_native_workspace_bytes(int64_t M, int64_t N, int64_t K);   /* host */
+QERL_API int mxfp4_linear_native(const void* x_bf16, int64_t M, int64_t K, int64_t ldx,
+                                 const void* packed, int64_t N, void* y_bf16, int64_t ldy,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -46,6 +46,13 @@ _SIGNATURES = {
     "aqn_sigma": (ctypes.c_double, [ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_double]),
     "aqn_sigma_schedule": (ctypes.c_double, [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_double]),
     "aqn_noise_fill": (ctypes.c_int, [_c_p, _c_i64, ctypes.c_float, ctypes.c_uint64, ctypes.c_uint64, _c_p]),
+    "mxfp4_quantize": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_p, _c_p]),
+    "mxfp4_dequantize": (ctypes.c_int, [_c_p, _c_p, _c_i64, _c_i64, _c_p, _c_p]),
+    "mxfp8_quantize": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_p, _c_p]),
+    "mxfp4_prepack_bytes": (_c_sz, [_c_i64, _c_i64]),
+    "mxfp4_prepack": (ctypes.c_int, [_c_p, _c_p, _c_i64, _c_i64, _c_p, _c_p]),
+    "mxfp4_linear_native_workspace_bytes": (_c_sz, [_c_i64, _c_i64, _c_i64]),
+    "mxfp4_linear_native": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_i64, _c_p, _c_i64, _c_p, _c_sz, _c_p]),
 }
 
 EXPORTED_SYMBOLS = tuple(_SIGNATURES)
@@ -376,3 +383,74 @@ def aqn_rmsnorm(x, gain, noise: Optional[torch.Tensor] = None, eps: float = 1e-6
         _dev(x, torch.bfloat16, "x"), M, H, ldx, _dev(gain, torch.bfloat16, "gain"), n_ptr,
         float(eps), _dev(out, torch.bfloat16, "out"), ldy, _stream()))
     return out
+
+
+# ---- MXFP4 variant ---------------------------------------------------------------------------------
+def mxfp4_quantize(W: torch.Tensor):
+    """W [N, K] bf16 (rows may be strided) -> (codes [N, K/2] u8, scales [N, K/32] u8 E8M0)."""
+    N, K, ldw = _rows(W, "W")
+    codes = torch.empty((N, K // 2), dtype=torch.uint8, device=W.device)
+    scales = torch.empty((N, K // 32), dtype=torch.uint8, device=W.device)
+    _check("mxfp4_quantize", load_library().mxfp4_quantize(
+        _dev(W, torch.bfloat16, "W"), N, K, ldw, _dev(codes, torch.uint8, "codes"), _dev(scales, torch.uint8, "scales"), _stream()))
+    return codes, scales
+
+
+def mxfp4_dequantize(codes: torch.Tensor, scales: torch.Tensor) -> torch.Tensor:
+    N, K = codes.shape[0], codes.shape[1] * 2
+    W = torch.empty((N, K), dtype=torch.float32, device=codes.device)
+    _check("mxfp4_dequantize", load_library().mxfp4_dequantize(
+        _dev(codes, torch.uint8, "codes"), _dev(scales, torch.uint8, "scales"), N, K, _dev(W, torch.float32, "W"), _stream()))
+    return W
+
+
+def mxfp8_quantize(x: torch.Tensor):
+    """x [M, K] bf16 -> (codes [M, K] u8 E4M3, scales [M, K/32] u8 E8M0)."""
+    M, K, ldx = _rows(x, "x")
+    codes = torch.empty((M, K), dtype=torch.uint8, device=x.device)
+    scales = torch.empty((M, K // 32), dtype=torch.uint8, device=x.device)
+    _check("mxfp8_quantize", load_library().mxfp8_quantize(
+        _dev(x, torch.bfloat16, "x"), M, K, ldx, _dev(codes, torch.uint8, "codes"), _dev(scales, torch.uint8, "scales"), _stream()))
+    return codes, scales
+
+
+class MxPackedWeight:
+    """MXFP4 weights in the tile order of the scaled matrix instruction."""
+
+    def __init__(self, packed: torch.Tensor, N: int, K: int):
+        self.packed, self.N, self.K = packed, N, K
+
+
+def mxfp4_prepack(codes: torch.Tensor, scales: torch.Tensor) -> MxPackedWeight:
+    lib = load_library()
+    N, K = codes.shape[0], codes.shape[1] * 2
+    if not codes.is_contiguous() or not scales.is_contiguous() or tuple(scales.shape) != (N, K // 32):
+        raise ValueError("codes [N, K/2] and scales [N, K/32] must be contiguous")
+    packed = torch.empty((lib.mxfp4_prepack_bytes(N, K),), dtype=torch.uint8, device=codes.device)
+    _check("mxfp4_prepack", lib.mxfp4_prepack(_dev(codes, torch.uint8, "codes"), _dev(scales, torch.uint8, "scales"), N, K,
+                                              _dev(packed, torch.uint8, "packed"), _stream()))
+    return MxPackedWeight(packed, N, K)
+
+
+def mxfp4_linear_native(x: torch.Tensor, w: MxPackedWeight, workspace: Optional[torch.Tensor] = None,
+                        out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """y = MXFP8(x) . MXFP4(W)^T on the block-scaled matrix instruction, M <= 32 tokens."""
+    lib = load_library()
+    M, K, ldx = _rows(x, "x")
+    if K != w.K:
+        raise ValueError("x must have K columns")
+    if out is None:
+        out = torch.empty((M, w.N), dtype=torch.bfloat16, device=x.device)
+    _, n_out, ldy = _rows(out, "out")
+    if out.shape[0] != M or n_out != w.N:
+        raise ValueError("out must be [M, N]")
+    need = lib.mxfp4_linear_native_workspace_bytes(M, w.N, K)
+    if workspace is None:
+        workspace = torch.empty((need + 256,), dtype=torch.uint8, device=x.device)
+    base = workspace.data_ptr()
+    ptr = (base + 255) & ~255
+    _check("mxfp4_linear_native", lib.mxfp4_linear_native(
+        _dev(x, torch.bfloat16, "x"), M, K, ldx, _dev(w.packed, torch.uint8, "packed"), w.N,
+        _dev(out, torch.bfloat16, "out"), ldy, ptr, workspace.numel() - (ptr - base), _stream()))
+    return out
+

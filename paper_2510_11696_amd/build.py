@@ -24,7 +24,7 @@ COMMON = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
 ]
-PER_FILE = {"quantize.hip": ["-ffp-contract=off"]}
+PER_FILE = {"quantize.hip": ["-ffp-contract=off"], "mx.hip": ["-ffp-contract=off"]}
 # extra hipcc flags for tuning builds, e.g. QERL_EXTRA_HIPCC_FLAGS="-DQERL_TUNING_HOOKS -DQERL_STREAM_TRACE=1"
 COMMON += os.environ.get("QERL_EXTRA_HIPCC_FLAGS", "").split()
 

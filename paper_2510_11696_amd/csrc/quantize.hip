@@ -45,21 +45,6 @@ __global__ __launch_bounds__(kAmaxThreads) void amax_partial_kernel(
   }
 }
 
-// fp32 v >= 0 -> E4M3 byte, nearest-even, subnormals kept, saturating at 448.
-__device__ __forceinline__ uint32_t e4m3_encode_rne_sat(float v) {
-  if (v >= 448.0f) return 0x7Eu;
-  if (v < 0x1p-6f) return (uint32_t)__builtin_rintf(v * 512.0f);   // units of 2^-9; 8 carries into 0x08
-  uint32_t b = __float_as_uint(v);
-  b += 0x7FFFFu + ((b >> 20) & 1u);                                // round the 20 dropped bits to even
-  return (b >> 20) - (120u << 3);                                  // re-bias 127 -> 7
-}
-
-// fp32 q >= 0 -> E2M1 magnitude index.  The boundaries are the midpoints of
-// {0,.5,1,1.5,2,3,4,6}; a midpoint goes to the neighbour with mantissa bit 0.
-__device__ __forceinline__ uint32_t e2m1_encode_rne_sat(float q) {
-  return (uint32_t)(q > 0.25f) + (uint32_t)(q >= 0.75f) + (uint32_t)(q > 1.25f) +
-         (uint32_t)(q >= 1.75f) + (uint32_t)(q > 2.5f) + (uint32_t)(q >= 3.5f) + (uint32_t)(q > 5.0f);
-}
 
 // Pass 2: one thread per 16-weight block.
 __global__ __launch_bounds__(256) void encode_kernel(

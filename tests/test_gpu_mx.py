@@ -1,0 +1,144 @@
+"""MXFP4 variant on the GPU: quantisers and dequantiser bit-exact, packed layout, and the linear on the
+block-scaled matrix instruction against the oracle's product of the two quantised operands."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2510_11696_amd as qerl
+import qerl_synth as qs
+from oracle import mx_oracle as mx
+from tests import cases
+from tests.gpu_util import check_linear
+
+pytestmark = pytest.mark.gpu
+
+
+def _bf16(a):
+    return torch.from_numpy(np.asarray(a, dtype=np.float32)).to(torch.bfloat16)
+
+
+@pytest.mark.parametrize("N,K", [(48, 512), (5, 32), (100, 18944), (512, 3584)])
+def test_mxfp4_quantize_bit_exact(N, K):
+    print("mx quantize case", N, K, flush=True)
+    tensors = {"gaussian": cases.gaussian(N, K, seed=N + K)}
+    if N * K <= 48 * 512:
+        tensors.update(cases.quantizer_cases(N, K, seed=7))
+    for name, W in tensors.items():
+        W = _bf16(W)
+        codes, scales = qerl.mxfp4_quantize(W.cuda())
+        ref_c, ref_s = mx.mxfp4_quantize(W.float().numpy())
+        assert np.array_equal(scales.cpu().numpy(), ref_s), name
+        assert np.array_equal(codes.cpu().numpy(), ref_c), name
+        What = qerl.mxfp4_dequantize(codes, scales).cpu().numpy().astype(np.float64)
+        assert np.array_equal(What, mx.mxfp4_dequantize(ref_c, ref_s).astype(np.float32).astype(np.float64)), name
+
+
+def test_mx_quantize_special_blocks_and_strided_rows():
+    rows = np.zeros((6, 64), dtype=np.float32)
+    rows[0, :4] = [6.0, 2.5, 3.5, -5.0]                 # ties
+    rows[1, 32:36] = [3.9, -0.0, 1e-30, 7.0]            # saturation inside the block; signed zero; underflow
+    rows[2, :2] = [2.0 ** 100, -2.0 ** 96]              # large exponents
+    rows[3, :2] = [2.0 ** -120, 2.0 ** -126]            # scale byte near its lower clamp
+    rows[4, :] = 448.0
+    rows[5, 0] = 500.0                                   # MXFP8: clamps to 448
+    W = _bf16(rows)
+    wide = torch.zeros((6, 96), dtype=torch.bfloat16)
+    wide[:, :64] = W
+    for src in (W.cuda(), wide.cuda()[:, :64]):          # contiguous and strided rows
+        c, s = qerl.mxfp4_quantize(src)
+        rc, rs = mx.mxfp4_quantize(W.float().numpy())
+        assert np.array_equal(c.cpu().numpy(), rc) and np.array_equal(s.cpu().numpy(), rs)
+        c8, s8 = qerl.mxfp8_quantize(src)
+        rc8, rs8 = mx.mxfp8_quantize(W.float().numpy())
+        assert np.array_equal(c8.cpu().numpy(), rc8) and np.array_equal(s8.cpu().numpy(), rs8)
+    assert qerl.mxfp4_quantize(torch.empty((0, 64), dtype=torch.bfloat16, device="cuda"))[0].numel() == 0
+
+
+@pytest.mark.parametrize("M,K", [(1, 32), (8, 3584), (32, 5120), (7, 18944)])
+def test_mxfp8_activation_quantize_bit_exact(M, K):
+    x = qs.activations(M, K, 600 + M)
+    c, s = qerl.mxfp8_quantize(x.cuda())
+    rc, rs = mx.mxfp8_quantize(x.float().numpy())
+    assert np.array_equal(s.cpu().numpy(), rs)
+    assert np.array_equal(c.cpu().numpy(), rc)
+
+
+def _pack_reference(codes, scales):
+    """Tiles of 32 rows x 128 inputs, 2176 bytes: step s (64 inputs) holds, for lane l = (n = l % 32, g = l // 32),
+    the 16 code bytes of inputs 64 s + 32 g .. + 31 of row n at s * 1024 + l * 16 and their scale byte at 2048 + s * 64 + l."""
+    N, K = codes.shape[0], codes.shape[1] * 2
+    nt, kt = -(-N // 32), -(-K // 128)
+    cp = np.zeros((nt * 32, kt * 64), dtype=np.uint8); cp[:N, :K // 2] = codes
+    sp = np.zeros((nt * 32, kt * 4), dtype=np.uint8); sp[:N, :K // 32] = scales
+    out = np.zeros((nt, kt, 2176), dtype=np.uint8)
+    for a in range(nt):
+        for b in range(kt):
+            for s in range(2):
+                for lane in range(64):
+                    n, g = a * 32 + lane % 32, lane // 32
+                    k0 = b * 128 + 64 * s + 32 * g
+                    out[a, b, s * 1024 + lane * 16: s * 1024 + lane * 16 + 16] = cp[n, k0 // 2: k0 // 2 + 16]
+                    out[a, b, 2048 + s * 64 + lane] = sp[n, k0 // 32]
+    return out.reshape(-1)
+
+
+@pytest.mark.parametrize("N,K", [(32, 128), (40, 320), (100, 64), (64, 1024)])
+def test_mxfp4_prepack_is_the_documented_permutation(N, K):
+    rng = np.random.default_rng(N + K)
+    codes = rng.integers(0, 256, size=(N, K // 2)).astype(np.uint8)
+    scales = rng.integers(0, 255, size=(N, K // 32)).astype(np.uint8)
+    pw = qerl.mxfp4_prepack(torch.from_numpy(codes).cuda(), torch.from_numpy(scales).cuda())
+    assert np.array_equal(pw.packed.cpu().numpy(), _pack_reference(codes, scales))
+
+
+def _problem(M, N, K, seed):
+    W = _bf16(cases.gaussian(N, K, seed))
+    x = qs.activations(M, K, seed + 1)
+    codes, scales = mx.mxfp4_quantize(W.float().numpy())
+    pw = qerl.mxfp4_prepack(torch.from_numpy(codes).cuda(), torch.from_numpy(scales).cuda())
+    return x, codes, scales, pw
+
+
+def test_native_linear_reads_dequantised_columns_for_one_hot_rows():
+    """x = rows of the identity (exact in MXFP8): y[m, :] is column k_m of the dequantised weights, for k_m
+    in both halves of a 64-input step, across steps, tiles and the padded tail."""
+    N, K = 96, 320
+    _, codes, scales, pw = _problem(1, N, K, 11)
+    ks = [0, 1, 31, 32, 33, 63, 64, 127, 128, 200, 319]
+    x = torch.zeros((len(ks), K), dtype=torch.bfloat16)
+    for m, k in enumerate(ks):
+        x[m, k] = 1.0
+    y = qerl.mxfp4_linear_native(x.cuda(), pw).float().cpu().numpy()
+    What = mx.mxfp4_dequantize(codes, scales)
+    want = torch.from_numpy(What[:, ks].T.astype(np.float32)).to(torch.bfloat16).float().numpy()
+    assert np.array_equal(y, want)
+
+
+@pytest.mark.parametrize("M,N,K", [
+    (1, 64, 128), (3, 40, 320), (8, 512, 3584), (8, 3584, 3584), (8, 96, 18944),   # the last: K split over ranges of workgroups
+    (16, 1000, 2112), (32, 130, 5120), (9, 33, 27648),
+])
+def test_native_linear_is_the_product_of_the_quantised_operands(M, N, K):
+    """Products of FP8 and FP4 values are exact and the sums are fp32: the result is held to the same gate as the
+    NVFP4 linear (2^-8 |y| + 1e-3 row maximum), against the oracle's float64 product of the two quantised operands."""
+    print("mx linear case", M, N, K, flush=True)
+    x, codes, scales, pw = _problem(M, N, K, 100 + M + N)
+    y = qerl.mxfp4_linear_native(x.cuda(), pw)
+    torch.cuda.synchronize()
+    check_linear(y, mx.mx_linear_native(x.float().numpy(), codes, scales), ("mx native", M, N, K))
+    again = qerl.mxfp4_linear_native(x.cuda(), pw)
+    assert torch.equal(y, again)
+
+
+def test_how_far_the_native_path_is_from_the_weight_only_result():
+    """Not a parity claim: the measured cost of rounding activations to MXFP8 on Gaussian inputs, relative to
+    each output row's root mean square (the weight-only result is what the paper's kernels compute)."""
+    M, N, K = 8, 3584, 3584
+    x, codes, scales, pw = _problem(M, N, K, 4242)
+    y = qerl.mxfp4_linear_native(x.cuda(), pw).float().cpu().numpy().astype(np.float64)
+    ref = mx.mx_linear_weight_only(x.float().numpy(), codes, scales)
+    rel_rms = np.sqrt(((y - ref) ** 2).mean(axis=1)) / np.sqrt((ref ** 2).mean(axis=1))
+    rel_max = np.abs(y - ref).max(axis=1) / np.abs(ref).max(axis=1)
+    print("native vs weight-only: rms error / row rms =", rel_rms.max(), " max error / row max =", rel_max.max(), flush=True)
+    assert rel_rms.max() < 0.05 and rel_max.max() < 0.05
+    assert rel_max.max() > 2e-3      # and it is not the weight-only result: the activation rounding is visible

@@ -274,17 +274,18 @@ QERL_API int aqn_noise_fill(float* noise_f32, int64_t n, float sigma, uint64_t s
  * mxfp4_dequantize: -> W_hat [N, K] fp32 = 2^(scale - 127) * E2M1(code), exact.
  * mxfp8_quantize:  x [M, ldx] bf16 -> codes [M, K] E4M3 bytes (bit 7 = sign),
  *                  scales [M, K/32] E8M0: the activation format of the native path.
- * mxfp4_prepack:   codes/scales -> tiles of 32 rows x 128 inputs (2176 bytes) in the
+ * mxfp4_prepack:   codes/scales -> tiles of 32 rows x 256 inputs (4352 bytes) in the
  *                  operand order of the scaled matrix instruction; packed must be
  *                  16-byte aligned, mxfp4_prepack_bytes(N, K) bytes.
  * mxfp4_linear_native: y [M, N] bf16 = MXFP8(x) . MXFP4(W)^T for decode-sized
  *   batches (M <= 32), both operands going through CDNA4's block-scaled matrix
  *   instruction as stored (no conversion arithmetic).  NOT the paper's setting:
  *   there activations stay bf16 (weight-only).  x is quantised to MXFP8 inside the
- *   call (into the workspace); the result is the exact product of the two
+ *   kernel (the function mxfp8_quantize computes); the result is the exact product of the two
  *   quantised operands summed in fp32, rounded once to bf16; it differs from the
  *   weight-only result by the activation rounding (up to 2^-4 relative per
  *   element).  No LoRA branch and no bias in this variant.
+ *   x 16-byte aligned with ldx % 8 == 0.
  *   workspace: >= mxfp4_linear_native_workspace_bytes(M, N, K), 256-byte aligned;
  *   needs no initialisation.
  * Errors: as the NVFP4 functions (NULL, shape incl. K % 32 and M > 32, alignment,

@@ -21,15 +21,17 @@
 //
 // Kernels:
 //   mxfp4_quantize_kernel / mxfp8_quantize_kernel   one thread per block of 32 (bit-exact vs the rule)
-//   mxfp4_prepack_kernel   canonical (codes [N, K/2], scales [N, K/32]) -> tiles of 32 rows x 128 inputs,
-//                          2176 bytes: two steps of 64 inputs, each 1 KiB of codes (lane l = (n = l % 32,
-//                          g = l / 32) owns the 16 bytes of inputs 64 s + 32 g .. + 31 of row n) and 64
-//                          scale bytes (one per lane: the scale of those 32 inputs), i.e. MFMA operand order
+//   mxfp4_prepack_kernel   canonical (codes [N, K/2], scales [N, K/32]) -> tiles of 32 rows x 256 inputs,
+//                          4352 bytes: four steps of 64 inputs, each 1 KiB of codes (lane l = (n = l % 32,
+//                          g = l / 32) owns the 16 bytes of inputs 64 j + 32 g .. + 31 of row n), then 256
+//                          scale bytes: one dword per lane whose byte j is the scale of its 32 inputs of
+//                          step j -- the matrix instruction picks the byte by an immediate, so a lane's
+//                          four scales arrive with one load and need no arithmetic
 //   mx_native_kernel       decode-sized batches (M <= 32): a workgroup's eight waves split the 64-input
-//                          steps of its K-range and keep their x fragments in registers; each wave
+//                          steps of its K-range, quantise their x fragments to MXFP8 and keep them in registers; each wave
 //                          streams its steps of one row-tile after the other (the next tile's loads in
-//                          flight while the current one is multiplied), the eight partial tiles are added
-//                          through LDS in wave order.  Bound by streaming the packed weights:
+//                          flight while the current one is multiplied), the seven partial tiles are added
+//                          through LDS in wave order by the eighth wave, which also stores.  Bound by streaming the packed weights:
 //                          0.53125 B per weight.
 #include "common.hpp"
 
@@ -37,9 +39,10 @@ namespace qerl {
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 
-constexpr int kMxTileBytes = 2176;      // 32 rows x 128 inputs: 2 x 1024 B codes + 2 x 64 B scales
-constexpr int kMxWaves = 8;
-constexpr int kMxMaxSteps = 8;          // 64-input steps per wave and K-range held in registers
+constexpr int kMxTileBytes = 4352;      // 32 rows x 256 inputs: 4 x 1024 B codes + 256 B scales
+constexpr int kMxWaves = 8;             // seven that stream and multiply, one that adds their partial tiles and stores
+constexpr int kMxMain = kMxWaves - 1;
+constexpr int kMxMaxGroups = 2;         // tiles (groups of four 64-input steps) per wave and K-range held in registers
 
 // ---- quantisers -----------------------------------------------------------------------------------
 // One thread per block of 32 bf16 values.  EMAX: 2 (E2M1 elements, two per byte out) or 8 (E4M3, one per byte).
@@ -121,11 +124,11 @@ __global__ __launch_bounds__(256) void mxfp4_dequantize_kernel(const uint8_t* __
 __global__ __launch_bounds__(256) void mxfp4_prepack_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales,
                                                             int64_t N, int64_t K, int64_t n_tiles, int64_t k_tiles, uint8_t* __restrict__ out) {
   // one thread per (tile, step, lane): 16 code bytes and one scale byte
-  const int64_t total = n_tiles * k_tiles * 2 * 64;
+  const int64_t total = n_tiles * k_tiles * 4 * 64;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
-    const int lane = (int)(i & 63), s = (int)((i >> 6) & 1);
-    const int64_t tile = i >> 7, kt = tile % k_tiles, nt = tile / k_tiles;
-    const int64_t n = nt * 32 + (lane & 31), k0 = kt * 128 + 64 * s + 32 * (lane >> 5);
+    const int lane = (int)(i & 63), j = (int)((i >> 6) & 3);
+    const int64_t tile = i >> 8, kt = tile % k_tiles, nt = tile / k_tiles;
+    const int64_t n = nt * 32 + (lane & 31), k0 = kt * 256 + 64 * j + 32 * (lane >> 5);
     u32x4 c = {0u, 0u, 0u, 0u};
     uint8_t sc = 0;
     if (n < N && k0 < K) {               // K % 32 == 0: a block is inside or outside as a whole
@@ -133,103 +136,174 @@ __global__ __launch_bounds__(256) void mxfp4_prepack_kernel(const uint8_t* __res
       sc = scales[n * (K / 32) + k0 / 32];
     }
     uint8_t* t = out + tile * kMxTileBytes;
-    *reinterpret_cast<u32x4*>(t + s * 1024 + lane * 16) = c;
-    t[2048 + s * 64 + lane] = sc;
+    *reinterpret_cast<u32x4*>(t + j * 1024 + lane * 16) = c;
+    t[4096 + lane * 4 + j] = sc;
   }
 }
 
 // ---- the linear ---------------------------------------------------------------------------------------
 struct MxArgs {
-  const uint8_t* xq; const uint8_t* xs; int M; int64_t K;      // MXFP8 activations: codes [M, K], scales [M, K/32]
+  const uint16_t* x; int64_t ldx; int M; int64_t K;            // bf16 activations: quantised to MXFP8 by the waves that use them
   const uint8_t* packed; int k_tiles; int n_tiles; int64_t N;
   uint16_t* y; int64_t ldy;
   float* partial;                                               // [Sk][n_tiles][MR][64] when Sk > 1
-  int Sk; int steps_per_range; int per_range; int units_base; int units_rem;
+  int Sk; int groups_per_range; int per_range; int units_base; int units_rem;
 };
 
-// NS: 64-input steps per wave; MR: accumulator registers with live tokens (4: M <= 8, 16: M <= 32)
-template <int NS, int MR>
+// NG: tiles (four 64-input steps each) per wave; MR: accumulator registers with live tokens (4: M <= 8, 16: M <= 32)
+template <int NG, int MR>
 __global__ __launch_bounds__(kMxWaves * 64) void mx_native_kernel(const MxArgs a) {
-  __shared__ float red[2][kMxWaves][MR][64];
+  __shared__ float red[2][kMxMain][MR][64];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n32 = lane & 31, kg = lane >> 5;
   const int range = (int)blockIdx.x / a.per_range, ci = (int)blockIdx.x - range * a.per_range;
   const int n_units = a.units_base + (ci < a.units_rem ? 1 : 0);
   const int u0 = ci * a.units_base + (ci < a.units_rem ? ci : a.units_rem);
-  const int n_steps = 2 * a.k_tiles;                                   // 64-input steps of the padded K
-  const int step0 = range * a.steps_per_range;                         // this range: steps [step0, step0 + 8 NS)
+  constexpr int NS = 4 * NG;
+  const int n_groups = a.k_tiles;                                      // tiles along the padded K
+  const int group0 = range * a.groups_per_range;                       // this range: tiles [group0, group0 + 7 NG)
 
-  // ---- this wave's steps: step0 + wave + 8 i; x fragments and scales stay in registers
+  if (n_units == 0) return;                                            // uniform per workgroup
+  const int n_rounds = 2 * ((n_units + 1) / 2);                        // barriers every wave of the workgroup passes
+  if (wave == kMxMain) {
+    // ---- the eighth wave adds the seven partial tiles of a unit in wave order and stores the result; the
+    // streaming waves never store, so their loads are the only memory operations they ever wait for
+    for (int u = 0; u < n_rounds; ++u) {
+      __syncthreads();
+      if (u >= n_units) continue;
+      const int nt = u0 + u;
+      const int64_t n = (int64_t)nt * 32 + n32;
+#pragma unroll
+      for (int q = 0; q < MR; ++q) {
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < kMxMain; ++w) sum += red[u & 1][w][q][lane];
+        const int tok = 8 * (q >> 2) + 4 * kg + (q & 3);
+        if (a.Sk > 1) a.partial[(((int64_t)range * a.n_tiles + nt) * MR + q) * 64 + lane] = sum;
+        else if (tok < a.M && n < a.N) a.y[(int64_t)tok * a.ldy + n] = (uint16_t)f32_to_bf16_bits(sum);
+      }
+    }
+    return;
+  }
+  // ---- this wave's tiles along K: group0 + wave + 7 i, four steps each.  Their x fragments are quantised to MXFP8 here, once, and stay in
+  // registers with their scales: lane (token, g) reads inputs 16 g .. + 15 (of block 0 of the step) and
+  // 32 + 16 g .. + 15 (of block 1); the two lanes of a token exchange their chunk maxima to get both block
+  // maxima, and each quantises its own 32 values -- the same function mxfp8_quantize computes.
   v8i xa[NS];
   int xsc[NS];
 #pragma unroll
   for (int i = 0; i < NS; ++i) {
-    const int s = step0 + wave + kMxWaves * i;
-    const int64_t kb = (int64_t)s * 64, ka = kb + 16 * kg, kc = kb + 32 + 16 * kg, ks = kb + 32 * kg;
-    u32x4 lo = {0u, 0u, 0u, 0u}, hi = {0u, 0u, 0u, 0u};   // a step past the end of K, or a row past the tokens: zeros
-    xsc[i] = 0;
-    if (s < n_steps && n32 < a.M) {
-      if (ka < a.K) lo = *reinterpret_cast<const u32x4*>(a.xq + (int64_t)n32 * a.K + ka);
-      if (kc < a.K) hi = *reinterpret_cast<const u32x4*>(a.xq + (int64_t)n32 * a.K + kc);
-      if (ks < a.K) xsc[i] = a.xs[(int64_t)n32 * (a.K / 32) + ks / 32];
+    const int grp = group0 + wave + kMxMain * (i >> 2);
+    const int64_t kb = (int64_t)grp * 256 + 64 * (i & 3), ka = kb + 16 * kg, kc = kb + 32 + 16 * kg;
+    u32x4 v[4] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};   // a step past the end of K, or a row past the tokens: zeros
+    if (grp < n_groups && n32 < a.M) {
+      const uint16_t* row = a.x + (int64_t)n32 * a.ldx;
+      if (ka < a.K) { v[0] = *reinterpret_cast<const u32x4*>(row + ka); v[1] = *reinterpret_cast<const u32x4*>(row + ka + 8); }
+      if (kc < a.K) { v[2] = *reinterpret_cast<const u32x4*>(row + kc); v[3] = *reinterpret_cast<const u32x4*>(row + kc + 8); }
     }
-    xa[i] = v8i{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+    uint32_t m01[2] = {0u, 0u};          // chunk maxima as bf16 bit patterns
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int d = 0; d < 8; ++d) {
+        const uint32_t w = v[2 * h + (d >> 2)][d & 3];
+        const uint32_t lo = w & 0x7fffu, hi = (w >> 16) & 0x7fffu;
+        m01[h] = lo > m01[h] ? lo : m01[h];
+        m01[h] = hi > m01[h] ? hi : m01[h];
+      }
+    const uint32_t mine = m01[0] | (m01[1] << 16);
+    const uint32_t other = (uint32_t)__shfl_xor((int)mine, 32, 64);
+    const uint32_t b0 = (mine & 0xffffu) > (other & 0xffffu) ? (mine & 0xffffu) : (other & 0xffffu);
+    const uint32_t b1 = (mine >> 16) > (other >> 16) ? (mine >> 16) : (other >> 16);
+    int sb[2];
+    float inv[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int field = (int)((h ? b1 : b0) >> 7);
+      sb[h] = field - 8 > 0 ? field - 8 : 0;                                  // scale byte = exponent field - emax(E4M3), clamped
+      inv[h] = __uint_as_float((uint32_t)(254 - sb[h]) << 23);
+    }
+    uint32_t q[8];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        // four values per register: scaled by the exact power of two, clamped to the largest element, then the
+        // hardware's round-to-nearest-even conversion to E4M3 (two values per instruction)
+        int acc = 0;
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+          const uint32_t pair = v[2 * h + ((2 * d + jj) >> 2)][(2 * d + jj) & 3];
+          const float x0 = __builtin_amdgcn_fmed3f(bf16_bits_to_f32(pair & 0xffffu) * inv[h], -448.0f, 448.0f);
+          const float x1 = __builtin_amdgcn_fmed3f(__uint_as_float(pair & 0xffff0000u) * inv[h], -448.0f, 448.0f);
+          acc = jj == 0 ? __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, acc, false) : __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, acc, true);
+        }
+        q[4 * h + d] = (uint32_t)acc;
+      }
+    xa[i] = v8i{(int)q[0], (int)q[1], (int)q[2], (int)q[3], (int)q[4], (int)q[5], (int)q[6], (int)q[7]};
+    xsc[i] = kg ? sb[1] : sb[0];         // lanes 0..31 carry the scale of block 0, lanes 32..63 that of block 1
   }
-  // ---- weights: this wave's steps of one row-tile = NS loads of 16 bytes + NS scale bytes per lane
-  struct WTile { u32x4 c[NS]; uint32_t sc[NS]; };
+  // ---- weights: this wave's NG tiles of one row-tile = 4 NG loads of 16 bytes + NG scale dwords per lane
+  struct WTile { u32x4 c[NG][4]; uint32_t sc[NG]; };
   auto issue = [&](WTile& t, int u) {
     const int nt = u0 + (u < n_units ? u : n_units - 1);               // past the end: the last tile again (keeps the loads unconditional)
     const uint8_t* base = a.packed + (int64_t)nt * a.k_tiles * kMxTileBytes;
 #pragma unroll
-    for (int i = 0; i < NS; ++i) {
-      int s = step0 + wave + kMxWaves * i;
-      s = s < n_steps ? s : n_steps - 1;                               // a dead step multiplies a zero x fragment
-      const uint8_t* tile = base + (int64_t)(s >> 1) * kMxTileBytes;
-      t.c[i] = *reinterpret_cast<const u32x4*>(tile + (s & 1) * 1024 + lane * 16);
-      t.sc[i] = tile[2048 + (s & 1) * 64 + lane];
+    for (int i = 0; i < NG; ++i) {
+      int grp = group0 + wave + kMxMain * i;
+      grp = grp < n_groups ? grp : n_groups - 1;                       // a dead tile multiplies zero x fragments
+      const uint8_t* tile = base + (int64_t)grp * kMxTileBytes;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) t.c[i][j] = *reinterpret_cast<const u32x4*>(tile + j * 1024 + lane * 16);
+      t.sc[i] = *reinterpret_cast<const uint32_t*>(tile + 4096 + lane * 4);
     }
   };
   auto multiply = [&](const WTile& t, float (&out)[MR]) {
     f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int i = 0; i < NS; ++i) {
-      const v8i b = v8i{(int)t.c[i][0], (int)t.c[i][1], (int)t.c[i][2], (int)t.c[i][3], 0, 0, 0, 0};
-      // A = activations (FP8 E4M3, cbsz 0), B = weights (FP4 E2M1, blgp 4); byte 0 of each lane's scale register
-      acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(xa[i], b, acc, 0, 4, 0, xsc[i], 0, (int)t.sc[i]);
+    for (int i = 0; i < NG; ++i) {
+      auto step = [&](auto jc) {
+        constexpr int j = decltype(jc)::value;
+        const v8i b = v8i{(int)t.c[i][j][0], (int)t.c[i][j][1], (int)t.c[i][j][2], (int)t.c[i][j][3], 0, 0, 0, 0};
+        // A = activations (FP8 E4M3, cbsz 0), scale in byte 0 of its register; B = weights (FP4 E2M1, blgp 4),
+        // scale = byte j of the lane's scale dword
+        acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(xa[4 * i + j], b, acc, 0, 4, 0, xsc[4 * i + j], j, (int)t.sc[i]);
+      };
+      step(std::integral_constant<int, 0>{});
+      step(std::integral_constant<int, 1>{});
+      step(std::integral_constant<int, 2>{});
+      step(std::integral_constant<int, 3>{});
     }
 #pragma unroll
     for (int q = 0; q < MR; ++q) out[q] = acc[q];
   };
-  if (n_units == 0) return;                                            // uniform per workgroup
+  // Two tiles in flight per wave, in two fixed sets of registers.  The loop body has no branch around a load or
+  // a barrier (past the end the last tile is loaded and multiplied again; the eighth wave skips its store): that
+  // keeps the compiler's wait counts exact, so multiplying one tile never waits for the other tile's loads.
   WTile t0, t1;
-  issue(t0, 0);
+  __builtin_amdgcn_sched_barrier(0);     // t0's loads strictly before t1's here too: the loop head's wait count is the
+  issue(t0, 0);                          // minimum over the ways into it
+  __builtin_amdgcn_sched_barrier(0);
   issue(t1, 1);
+  __builtin_amdgcn_sched_barrier(0);
   for (int u = 0; u < n_units; u += 2) {
+    float part[MR];
+    multiply(t0, part);
+    __builtin_amdgcn_sched_barrier(0);   // the refill is issued right here, in program order: the wait counts rely on it
+    issue(t0, u + 2);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      if (u + h >= n_units) break;
-      float part[MR];
-      if (h == 0) { multiply(t0, part); issue(t0, u + 2); }
-      else { multiply(t1, part); issue(t1, u + 3); }
-      // the eight waves' partial tiles, added in wave order by the first MR * 64 threads
-      float (*rb)[MR][64] = red[h];
+    for (int q = 0; q < MR; ++q) red[0][wave][q][lane] = part[q];
+    __syncthreads();
+    multiply(t1, part);
+    __builtin_amdgcn_sched_barrier(0);
+    issue(t1, u + 3);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int q = 0; q < MR; ++q) rb[wave][q][lane] = part[q];
-      __syncthreads();
-      const int nt = u0 + u + h;
-      for (int e = tid; e < MR * 64; e += kMxWaves * 64) {
-        const int q = e >> 6, l = e & 63;
-        float sum = 0.f;
-#pragma unroll
-        for (int w = 0; w < kMxWaves; ++w) sum += rb[w][q][l];
-        const int tok = 8 * (q >> 2) + 4 * (l >> 5) + (q & 3);
-        const int64_t n = (int64_t)nt * 32 + (l & 31);
-        if (a.Sk > 1) a.partial[(((int64_t)range * a.n_tiles + nt) * MR + q) * 64 + l] = sum;
-        else if (tok < a.M && n < a.N) a.y[(int64_t)tok * a.ldy + n] = (uint16_t)f32_to_bf16_bits(sum);
-      }
-      // red[h] is written again two units later, after the barrier of unit u + h + 1: every read above is done by then
-    }
+    for (int q = 0; q < MR; ++q) red[1][wave][q][lane] = part[q];
+    __syncthreads();
+    // red[h] is written again two units later, after the barrier of the unit in between: the eighth wave has read it by then
   }
 }
 
@@ -251,38 +325,30 @@ static int64_t grid_for(int64_t items) {
   return b < 1 ? 1 : (b > 8192 ? 8192 : b);
 }
 
-// workspace of mxfp4_linear_native: activation codes, activation scales, K-range partial tiles
-struct MxWorkspace { size_t xq_off, xs_off, partial_off, total; int Sk, NS; };
+// workspace of mxfp4_linear_native: K-range partial tiles
+struct MxWorkspace { size_t partial_off, total; int Sk, NG; };
 static MxWorkspace mx_workspace(int64_t M, int64_t N, int64_t K) {
   MxWorkspace w{};
-  const int64_t n_steps = 2 * ceil_div(K > 0 ? K : 1, 128);
-  w.Sk = (int)ceil_div(n_steps, kMxWaves * kMxMaxSteps);
-  w.NS = (int)ceil_div(n_steps, (int64_t)kMxWaves * w.Sk);
-  if (w.NS < 4) w.NS = 4;                                              // instantiated: 4..8
+  (void)M;
+  const int64_t n_groups = ceil_div(K > 0 ? K : 1, 256);
+  w.Sk = (int)ceil_div(n_groups, kMxMain * kMxMaxGroups);
+  w.NG = (int)ceil_div(n_groups, (int64_t)kMxMain * w.Sk);             // 1 or 2
   auto al = [](size_t v) { return (v + 255) & ~(size_t)255; };
-  const size_t rows = (size_t)(M > 0 ? M : 1), kk = (size_t)(K > 0 ? K : 32);
-  w.xq_off = 0;
-  w.xs_off = al(rows * kk);
-  w.partial_off = w.xs_off + al(rows * (kk / 32));
+  w.partial_off = 0;
   w.total = w.partial_off + al((size_t)w.Sk * (size_t)ceil_div(N > 0 ? N : 1, 32) * 16 * 64 * sizeof(float));
   return w;
 }
 
-template <int NS, int MR>
+template <int NG, int MR>
 static int launch_mx_t(const MxArgs& a, int grid, hipStream_t st) {
-  mx_native_kernel<NS, MR><<<dim3((unsigned)grid), dim3(kMxWaves * 64), 0, st>>>(a);
+  mx_native_kernel<NG, MR><<<dim3((unsigned)grid), dim3(kMxWaves * 64), 0, st>>>(a);
   return launch_status();
 }
 template <int MR>
-static int launch_mx(const MxArgs& a, int NS, int grid, hipStream_t st) {
-  switch (NS) {
-    case 4: return launch_mx_t<4, MR>(a, grid, st);
-    case 5: return launch_mx_t<5, MR>(a, grid, st);
-    case 6: return launch_mx_t<6, MR>(a, grid, st);
-    case 7: return launch_mx_t<7, MR>(a, grid, st);
-    case 8: return launch_mx_t<8, MR>(a, grid, st);
-    default: return QERL_ERR_SHAPE;
-  }
+static int launch_mx(const MxArgs& a, int NG, int grid, hipStream_t st) {
+  if (NG == 1) return launch_mx_t<1, MR>(a, grid, st);
+  if (NG == 2) return launch_mx_t<2, MR>(a, grid, st);
+  return QERL_ERR_SHAPE;
 }
 
 }  // namespace qerl
@@ -319,7 +385,7 @@ extern "C" int mxfp4_dequantize(const uint8_t* codes, const uint8_t* scales, int
 
 extern "C" size_t mxfp4_prepack_bytes(int64_t N, int64_t K) {
   if (N <= 0 || K <= 0) return 0;
-  return (size_t)ceil_div(N, 32) * (size_t)ceil_div(K, 128) * kMxTileBytes;
+  return (size_t)ceil_div(N, 32) * (size_t)ceil_div(K, 256) * kMxTileBytes;
 }
 
 extern "C" int mxfp4_prepack(const uint8_t* codes, const uint8_t* scales, int64_t N, int64_t K, void* packed, void* stream) {
@@ -327,8 +393,8 @@ extern "C" int mxfp4_prepack(const uint8_t* codes, const uint8_t* scales, int64_
   if (N == 0 || K == 0) return QERL_OK;
   if (!codes || !scales || !packed) return QERL_ERR_NULL;
   if (!aligned(packed, 16) || !aligned(codes, 16) || (K / 2) % 16 != 0) return QERL_ERR_ALIGN;
-  const int64_t nt = ceil_div(N, 32), kt = ceil_div(K, 128);
-  mxfp4_prepack_kernel<<<dim3((unsigned)grid_for(nt * kt * 128)), dim3(256), 0, (hipStream_t)stream>>>(codes, scales, N, K, nt, kt,
+  const int64_t nt = ceil_div(N, 32), kt = ceil_div(K, 256);
+  mxfp4_prepack_kernel<<<dim3((unsigned)grid_for(nt * kt * 256)), dim3(256), 0, (hipStream_t)stream>>>(codes, scales, N, K, nt, kt,
                                                                                                     (uint8_t*)packed);
   return launch_status();
 }
@@ -341,26 +407,23 @@ extern "C" int mxfp4_linear_native(const void* x, int64_t M, int64_t K, int64_t 
   if (M == 0 || N == 0) return QERL_OK;
   if (K == 0) return QERL_ERR_SHAPE;
   if (!x || !packed || !y) return QERL_ERR_NULL;
-  if (!aligned(x, 4) || ldx % 2 != 0 || !aligned(packed, 16) || !aligned(y, 2)) return QERL_ERR_ALIGN;
+  if (!aligned(x, 16) || ldx % 8 != 0 || !aligned(packed, 16) || !aligned(y, 2)) return QERL_ERR_ALIGN;
   const MxWorkspace w = mx_workspace(M, N, K);
   if (!workspace || !aligned(workspace, 256) || workspace_bytes < w.total) return QERL_ERR_WORKSPACE;
   uint8_t* ws = (uint8_t*)workspace;
   hipStream_t st = (hipStream_t)stream;
-  mx_quantize_kernel<8><<<dim3((unsigned)grid_for(M * (K / 32))), dim3(256), 0, st>>>((const uint16_t*)x, M, K, ldx, ws + w.xq_off,
-                                                                                    ws + w.xs_off);
-  int rc = launch_status();
-  if (rc != QERL_OK) return rc;
+  int rc = QERL_OK;
   MxArgs a{};
-  a.xq = ws + w.xq_off; a.xs = ws + w.xs_off; a.M = (int)M; a.K = K;
-  a.packed = (const uint8_t*)packed; a.k_tiles = (int)ceil_div(K, 128); a.n_tiles = (int)ceil_div(N, 32); a.N = N;
+  a.x = (const uint16_t*)x; a.ldx = ldx; a.M = (int)M; a.K = K;
+  a.packed = (const uint8_t*)packed; a.k_tiles = (int)ceil_div(K, 256); a.n_tiles = (int)ceil_div(N, 32); a.N = N;
   a.y = (uint16_t*)y; a.ldy = ldy; a.partial = (float*)(ws + w.partial_off);
-  a.Sk = w.Sk; a.steps_per_range = kMxWaves * w.NS;
+  a.Sk = w.Sk; a.groups_per_range = kMxMain * w.NG;
   int per_range = 256 / w.Sk;
   if (per_range < 1) per_range = 1;
   if (per_range > a.n_tiles) per_range = a.n_tiles;
   a.per_range = per_range; a.units_base = a.n_tiles / per_range; a.units_rem = a.n_tiles % per_range;
   const int grid = per_range * w.Sk;
-  rc = M <= 8 ? launch_mx<4>(a, w.NS, grid, st) : launch_mx<16>(a, w.NS, grid, st);
+  rc = M <= 8 ? launch_mx<4>(a, w.NG, grid, st) : launch_mx<16>(a, w.NG, grid, st);
   if (rc != QERL_OK || w.Sk == 1) return rc;
   if (M <= 8) mx_reduce_kernel<4><<<dim3((unsigned)a.n_tiles), dim3(256), 0, st>>>(a.partial, w.Sk, a.n_tiles, (int)M, N, a.y, ldy);
   else mx_reduce_kernel<16><<<dim3((unsigned)a.n_tiles), dim3(256), 0, st>>>(a.partial, w.Sk, a.n_tiles, (int)M, N, a.y, ldy);

@@ -64,21 +64,21 @@ def test_mxfp8_activation_quantize_bit_exact(M, K):
 
 
 def _pack_reference(codes, scales):
-    """Tiles of 32 rows x 128 inputs, 2176 bytes: step s (64 inputs) holds, for lane l = (n = l % 32, g = l // 32),
-    the 16 code bytes of inputs 64 s + 32 g .. + 31 of row n at s * 1024 + l * 16 and their scale byte at 2048 + s * 64 + l."""
+    """Tiles of 32 rows x 256 inputs, 4352 bytes: step j (64 inputs) holds, for lane l = (n = l % 32, g = l // 32),
+    the 16 code bytes of inputs 64 j + 32 g .. + 31 of row n at j * 1024 + l * 16 and their scale byte at 4096 + 4 l + j."""
     N, K = codes.shape[0], codes.shape[1] * 2
-    nt, kt = -(-N // 32), -(-K // 128)
-    cp = np.zeros((nt * 32, kt * 64), dtype=np.uint8); cp[:N, :K // 2] = codes
-    sp = np.zeros((nt * 32, kt * 4), dtype=np.uint8); sp[:N, :K // 32] = scales
-    out = np.zeros((nt, kt, 2176), dtype=np.uint8)
+    nt, kt = -(-N // 32), -(-K // 256)
+    cp = np.zeros((nt * 32, kt * 128), dtype=np.uint8); cp[:N, :K // 2] = codes
+    sp = np.zeros((nt * 32, kt * 8), dtype=np.uint8); sp[:N, :K // 32] = scales
+    out = np.zeros((nt, kt, 4352), dtype=np.uint8)
     for a in range(nt):
         for b in range(kt):
-            for s in range(2):
+            for j in range(4):
                 for lane in range(64):
                     n, g = a * 32 + lane % 32, lane // 32
-                    k0 = b * 128 + 64 * s + 32 * g
-                    out[a, b, s * 1024 + lane * 16: s * 1024 + lane * 16 + 16] = cp[n, k0 // 2: k0 // 2 + 16]
-                    out[a, b, 2048 + s * 64 + lane] = sp[n, k0 // 32]
+                    k0 = b * 256 + 64 * j + 32 * g
+                    out[a, b, j * 1024 + lane * 16: j * 1024 + lane * 16 + 16] = cp[n, k0 // 2: k0 // 2 + 16]
+                    out[a, b, 4096 + 4 * lane + j] = sp[n, k0 // 32]
     return out.reshape(-1)
 
 
@@ -142,3 +142,20 @@ def test_how_far_the_native_path_is_from_the_weight_only_result():
     print("native vs weight-only: rms error / row rms =", rel_rms.max(), " max error / row max =", rel_max.max(), flush=True)
     assert rel_rms.max() < 0.05 and rel_max.max() < 0.05
     assert rel_max.max() > 2e-3      # and it is not the weight-only result: the activation rounding is visible
+
+
+def test_native_linear_quantises_awkward_activations_like_the_oracle():
+    """Activations with ties, values beyond the largest element after scaling, block-subnormal and zero entries,
+    signed zeros and an all-zero block go through the kernel's own MXFP8 conversion: same result as the oracle's."""
+    N, K = 64, 256
+    _, codes, scales, pw = _problem(1, N, K, 77)
+    x = np.zeros((6, K), dtype=np.float32)
+    x[0, :8] = [448.0, 208.0, 240.0, 17.0, 19.0, 1.0 / 512, 3.0 / 1024, -0.0]     # ties at 3 mantissa bits; block subnormals
+    x[1, 32:40] = [500.0, -499.0, 464.0, 460.0, 1e-3, -1e-3, 2.0 ** -7, 2.0 ** -9]   # clamps to 448; tiny next to large
+    x[2, 64:96] = np.linspace(-3.0, 3.0, 32)
+    x[3, :] = 2.0 ** -60
+    x[4, 128:132] = [2.0 ** 40, -2.0 ** 36, 2.0 ** 33, 2.0 ** 30]
+    xt = _bf16(x)
+    y = qerl.mxfp4_linear_native(xt.cuda(), pw)
+    check_linear(y, mx.mx_linear_native(xt.float().numpy(), codes, scales), ("awkward activations",))
+

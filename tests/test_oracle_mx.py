@@ -117,3 +117,37 @@ def test_linears_are_the_products_of_their_dequantised_operands():
     # the native path differs from the weight-only one by the activation rounding only: a few percent of a row's scale
     d = np.abs(mx.mx_linear_native(x, c, s) - mx.mx_linear_weight_only(x, c, s))
     assert d.max() <= 2.0 ** -4 * (np.abs(x) @ np.abs(What).T).max()
+
+
+def _rel_rms(a, ref):
+    return float(np.sqrt(np.mean((a - ref) ** 2)) / np.sqrt(np.mean(ref ** 2)))
+
+
+def test_error_study_of_the_formats_on_gaussian_weights():
+    """What each storage format costs on N(0, 0.02^2) weights (the synthetic stand-in for a trained matrix), as
+    relative rms error of the dequantised weights: NVFP4 (E4M3 per 16 + tensor scale) < MXFP4 (a bare power of
+    two per 32) < an NVFP4 tensor requantised to MXFP4 -- the only way to feed it to the block-scaled matrix
+    instruction, whose scales are E8M0 per 32: an E4M3 scale is not a power of two, and the product of an E2M1
+    code with an E4M3 mantissa needs five significand bits, one more than an FP8 E4M3 element holds, so no
+    element format of the instruction carries NVFP4 exactly.  The ranges are the measured values +- 10 %."""
+    rng = np.random.default_rng(11)
+    W = (rng.standard_normal((128, 1024)) * 0.02).astype(np.float32)
+    c, s, ts = o.nvfp4_quantize(W)
+    Wn = o.nvfp4_dequantize(c, s, ts).astype(np.float64)
+    Wm = mx.mxfp4_dequantize(*mx.mxfp4_quantize(W))
+    Wr = mx.mxfp4_dequantize(*mx.mxfp4_quantize(Wn.astype(np.float32)))
+    e_nv, e_mx, e_re = _rel_rms(Wn, W), _rel_rms(Wm, W), _rel_rms(Wr, W)
+    assert 0.085 < e_nv < 0.105 and 0.102 < e_mx < 0.126 and 0.134 < e_re < 0.164
+    assert e_nv < e_mx < e_re
+    # exhaustive: some (code, scale mantissa) products are not E4M3 values
+    grid8 = {float(o.e4m3_decode(np.uint8(b))) for b in range(0x7F)}
+    products = {m * (8 + f) / 8 for m in (0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0) for f in range(8)}
+    assert any(p not in grid8 for p in products)
+    assert 1.5 * 1.125 not in grid8
+    # activations in MXFP8 add a relative rms error of about 3 % of their own, nearly independent of the weights' error
+    x = rng.standard_normal((8, 1024)).astype(np.float32)
+    xq = mx.mxfp8_dequantize(*mx.mxfp8_quantize(x))
+    assert 0.02 < _rel_rms(xq, x) < 0.04
+    y = x.astype(np.float64) @ W.astype(np.float64).T
+    wo, nat = _rel_rms(x.astype(np.float64) @ Wm.T, y), _rel_rms(xq @ Wm.T, y)
+    assert wo < nat < wo * 1.1

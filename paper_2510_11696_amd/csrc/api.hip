@@ -287,6 +287,38 @@ static int mid_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const
   if (prc != QERL_OK) return prc;
   return launch_mid(g, st);
 }
+// More tokens than mid_kernel takes: one launch of the LoRA down-projection for all adapters of the group, then
+// one GEMM launch whose column blocks run over all members (k and v alone would fill half the chip).
+static int gemm_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const qerl_linear_desc* d, int n,
+                      uint8_t* ws, const WorkspaceLayout& L, hipStream_t st) {
+  GemmArgs g{};
+  g.x = x; g.ldx = ldx; g.M = M; g.K = K; g.k_tiles = ceil_div(K, kPackTileK); g.m_n = n;
+  GemmArgs dn{};
+  dn.x = x; dn.ldx = ldx; dn.M = M; dn.K = K; dn.k_tiles = g.k_tiles;
+  uint16_t* ts = (uint16_t*)(ws + L.t_off);
+  int tiles = 0;
+  for (int i = 0; i < n; ++i) {
+    GemmMember& m = g.m[i];
+    m.packed = (const uint8_t*)d[i].packed; m.tensor_scale = d[i].tensor_scale; m.N = d[i].N;
+    m.n_tiles = (int)ceil_div(d[i].N, kPackTileRows);
+    m.r = (int)d[i].r; m.B = (const uint16_t*)d[i].B_bf16; m.y = (uint16_t*)d[i].y_bf16; m.ldy = d[i].ldy;
+    m.bias = (const uint16_t*)d[i].bias_bf16;
+    m.ext_stages = (int)ceil_div(3 * d[i].r, 64); m.ts_ld = (int64_t)m.ext_stages * 64; m.ts = ts;
+    ts += M * m.ts_ld;
+    if (d[i].r > 0) {
+      const int gi = dn.g_n++;
+      dn.g_tile0[gi] = tiles; dn.g_A[gi] = (const uint16_t*)d[i].A_bf16; dn.g_ts[gi] = m.ts; dn.g_ts_ld[gi] = m.ts_ld;
+      dn.g_r[gi] = (int)d[i].r; dn.g_lora_scale[gi] = d[i].lora_scale; dn.g_tensor_scale[gi] = d[i].tensor_scale;
+      tiles += (int)ceil_div(d[i].r, 32);
+    }
+  }
+  if (dn.g_n > 0) {
+    dn.g_tile0[dn.g_n] = tiles;
+    const int rc = launch_lora_down_gemm(dn, st);   // no K-parts: 32-token blocks x rank tiles fill the chip
+    if (rc != QERL_OK) return rc;
+  }
+  return launch_gemm(g, st);
+}
 }  // namespace qerl
 
 #ifdef QERL_TUNING_HOOKS   // built only for tuning sessions: they change process-wide state
@@ -326,6 +358,8 @@ extern "C" int nvfp4_lora_linear_packed_group(const void* x, int64_t M, int64_t 
     return stream_group((const uint16_t*)x, M, K, ldx, members, n_members, (uint8_t*)workspace, L, (hipStream_t)stream);
   if (M > 16 && M <= g_mid_max_tokens && mid_ok)
     return mid_group((const uint16_t*)x, M, K, ldx, members, n_members, (uint8_t*)workspace, L, (hipStream_t)stream);
+  if (M > g_mid_max_tokens && mid_ok && n_members > 1)
+    return gemm_group((const uint16_t*)x, M, K, ldx, members, n_members, (uint8_t*)workspace, L, (hipStream_t)stream);
   for (int i = 0; i < n_members; ++i) {   // general case: member by member
     const qerl_linear_desc& d = members[i];
     const int rc = packed_single(x, M, K, ldx, d.packed, d.tensor_scale, d.N, d.A_bf16, d.B_bf16, d.r,

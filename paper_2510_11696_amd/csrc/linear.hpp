@@ -71,6 +71,17 @@ int plan_stream(StreamArgs& a, size_t* lds_bytes, int* MR);
 int launch_stream(const StreamArgs& a, size_t lds_bytes, int MR, hipStream_t st);
 
 // ---- prefill path: MFMA GEMM on tile-packed weights (linear_gemm.hip) ----
+// One linear of a prefill launch: gemm32_kernel's column blocks run over the members of a group that reads the
+// same x (q + k + v, gate + up); a single linear is a group of one, filled in from the GemmArgs fields of the
+// same names by launch_gemm.
+struct GemmMember {
+  const uint8_t* packed; const float* tensor_scale; int64_t N; int n_tiles;
+  const uint16_t* ts; int64_t ts_ld; int ext_stages;                        // [M, ts_ld] bf16: hi | mid | lo of lora_scale / S32 * t; stages of 64 columns
+  const uint16_t* B; int r;
+  const uint16_t* bias;                                                     // [N] bf16 or null
+  uint16_t* y; int64_t ldy;
+  int block_begin;                                                          // first column block of this member (set by the launcher)
+};
 struct GemmArgs {
   const uint16_t* x; int64_t ldx; int64_t M; int64_t K; int64_t N;
   const uint8_t* packed; int64_t k_tiles; const float* tensor_scale;        // kFmtNvfp4 weights
@@ -80,6 +91,7 @@ struct GemmArgs {
   const uint16_t* bias;                                                     // [N] bf16 or null
   uint16_t* y; int64_t ldy;
   int n_tiles; int n_blocks; int nblk_per_xcd;
+  int m_n; GemmMember m[kMaxGroup];                                         // the main launch's members (m_n == 0: one, from the fields above)
   uint32_t* tpart; uint32_t* counters;                                      // LoRA down-projection over several K-parts: partial sums, arrival counts (zero between calls); or null
   // LoRA down-projection of a group of adapters that read the same x (g_n > 0): grid.y runs over the 32-row
   // tiles of all adapters; member i owns tiles [g_tile0[i], g_tile0[i+1]) and has its own A, ts and scales

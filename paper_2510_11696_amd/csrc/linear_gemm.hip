@@ -71,7 +71,13 @@ __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
   const int nb = xcd * a.nblk_per_xcd + nb_local;
   if (nb >= a.n_blocks) return;          // padding of the last XCD's share (uniform per workgroup)
   const int64_t m0 = (int64_t)mb * BM;
-  const int nt0 = (nb * W + wave) * NT;
+  // the member of the group this column block belongs to: a uniform index into the kernel arguments, so
+  // its fields arrive by scalar loads
+  int mi = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxGroup; ++i) mi = (i < a.m_n && nb >= a.m[i].block_begin) ? i : mi;
+  const GemmMember& mem = a.m[__builtin_amdgcn_readfirstlane(mi)];
+  const int nt0 = ((nb - mem.block_begin) * W + wave) * NT;
   const int64_t n_stages = ceil_div_dev(a.K, 64);
   const int64_t s_begin = 0, s_end = n_stages;
 
@@ -109,8 +115,8 @@ __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
       int tile = nt0 + nt;
-      tile = tile < a.n_tiles ? tile : a.n_tiles - 1;
-      const uint8_t* base = a.packed + ((int64_t)tile * a.k_tiles + (s >> 1)) * kPackTileBytes;
+      tile = tile < mem.n_tiles ? tile : mem.n_tiles - 1;
+      const uint8_t* base = mem.packed + ((int64_t)tile * a.k_tiles + (s >> 1)) * kPackTileBytes;
       const int plane = (int)(s & 1);
       wr.c[nt] = *reinterpret_cast<const u32x4*>(base + plane * 1024 + lane * 16);
       wr.sc[nt] = *reinterpret_cast<const uint32_t*>(base + 2048 + n32 * 8 + plane * 4);
@@ -203,9 +209,9 @@ main_done:
   {
     // ---- LoRA up-projection: 3r extra columns  [hi | mid | lo] . [B ; B ; B]^T.  ts already carries
     // the factor lora_scale / S32, so one multiplication by S32 at the end scales both branches.
-    for (int e = 0; e < a.ext_stages; ++e) {
+    for (int e = 0; e < mem.ext_stages; ++e) {
       u32x4 xe[XL];
-      gload_x(xe, a.ts, a.ts_ld, a.ts_ld, e);
+      gload_x(xe, mem.ts, mem.ts_ld, mem.ts_ld, e);
       swrite_x(0, xe);
       __syncthreads();
 #pragma unroll
@@ -214,27 +220,27 @@ main_done:
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
           int64_t row = (int64_t)(nt0 + nt) * 32 + n32;
-          row = row < a.N ? row : a.N - 1;
+          row = row < mem.N ? row : mem.N - 1;
           const int c = e * 64 + 16 * j + 8 * kg;
           u32x4 b = {0u, 0u, 0u, 0u};
-          if (c < 3 * a.r) b = *reinterpret_cast<const u32x4*>(a.B + row * a.r + (c % a.r));
+          if (c < 3 * mem.r) b = *reinterpret_cast<const u32x4*>(mem.B + row * mem.r + (c % mem.r));
           wf[nt] = __builtin_bit_cast(bf16x8, b);
         }
         mma_step(xs, j, wf);
       }
       __syncthreads();
     }
-    const float S32 = *a.tensor_scale;
+    const float S32 = *mem.tensor_scale;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
         const int64_t n = (int64_t)(nt0 + nt) * 32 + n32;
-        const float bias = (a.bias && n < a.N) ? bf16_bits_to_f32(a.bias[n]) : 0.f;
+        const float bias = (mem.bias && n < mem.N) ? bf16_bits_to_f32(mem.bias[n]) : 0.f;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int64_t m = m0 + mt * 32 + 8 * (i >> 2) + 4 * kg + (i & 3);
-          if (m < a.M && n < a.N) a.y[m * a.ldy + n] = (uint16_t)f32_to_bf16_bits(acc[mt][nt][i] * S32 + bias);
+          if (m < a.M && n < mem.N) mem.y[m * mem.ldy + n] = (uint16_t)f32_to_bf16_bits(acc[mt][nt][i] * S32 + bias);
         }
       }
   }
@@ -414,11 +420,14 @@ __global__ __launch_bounds__(512) void lora_down32_kernel(const GemmArgs a) {
 
 // ---- host ------------------------------------------------------------------------------------------
 
-struct GemmConfig { int MT, NT, W, wg_per_cu; float quality; };
+struct GemmConfig { int MT, NT, W, wg_per_cu; float quality, quality_rounds; };
 // wg_per_cu: workgroups of this shape resident on one CU (register use); quality: relative speed
-// measured at equal useful work on 14B-shaped layers.
+// measured at equal useful work on 14B-shaped layers, for a launch that fits the chip at once and
+// (quality_rounds) for one that takes several rounds -- the one-tile-per-wave shapes re-read x four times as
+// often, which a full chip notices (gate + up in one launch: 0.85 PFLOP/s against 1.0).
 static const GemmConfig kConfigs[] = {
-    {4, 2, 4, 1, 0.75f}, {4, 2, 5, 1, 0.90f}, {4, 2, 8, 1, 1.00f}, {4, 1, 4, 2, 0.95f}, {4, 1, 8, 2, 0.92f},
+    {4, 2, 4, 1, 0.75f, 0.75f}, {4, 2, 5, 1, 0.90f, 0.90f}, {4, 2, 8, 1, 1.00f, 1.00f},
+    {4, 1, 4, 2, 0.95f, 0.74f}, {4, 1, 8, 2, 0.92f, 0.72f},
 };
 static int g_force_cfg = -1;
 
@@ -426,28 +435,44 @@ template <int MT, int NT, int W>
 static int launch_cfg(const GemmArgs& a, hipStream_t st) {
   constexpr size_t lds = 2 * (size_t)MT * 32 * 8 * sizeof(u32x4);
   GemmArgs b = a;
-  b.n_blocks = (int)ceil_div(a.n_tiles, W * NT);
+  b.n_blocks = 0;
+  for (int i = 0; i < b.m_n; ++i) {
+    b.m[i].block_begin = b.n_blocks;
+    b.n_blocks += (int)ceil_div(b.m[i].n_tiles, W * NT);
+  }
   b.nblk_per_xcd = (int)ceil_div(b.n_blocks, 8);
   const int64_t m_blocks = ceil_div(a.M, MT * 32);
   gemm32_kernel<MT, NT, W><<<dim3((unsigned)(8 * b.nblk_per_xcd * m_blocks)), W * 64, lds, st>>>(b);
   return launch_status();
 }
 
-int launch_gemm(const GemmArgs& a, hipStream_t st) {
+int launch_gemm(const GemmArgs& a0, hipStream_t st) {
+  GemmArgs a = a0;
+  if (a.m_n == 0) {   // a single linear, described by the top-level fields
+    a.m_n = 1;
+    a.m[0] = GemmMember{a.packed, a.tensor_scale, a.N, a.n_tiles, a.ts, a.ts_ld, a.ext_stages, a.B, a.r, a.bias, a.y, a.ldy, 0};
+  }
   // every pointer the kernel dereferences must be set by the caller
-  if (!a.x || !a.packed || !a.tensor_scale || !a.y || (a.r > 0 && (!a.ts || !a.B))) return QERL_ERR_NULL;
-  if (a.M < 1 || a.N < 1 || a.K < 16 || a.n_tiles < 1 || a.k_tiles < 1 || (a.r > 0 && a.ts_ld < 3 * a.r))
-    return QERL_ERR_SHAPE;
+  if (!a.x || a.m_n < 1 || a.m_n > kMaxGroup || a.M < 1 || a.K < 16 || a.k_tiles < 1) return QERL_ERR_SHAPE;
+  for (int i = 0; i < a.m_n; ++i) {
+    const GemmMember& m = a.m[i];
+    if (!m.packed || !m.tensor_scale || !m.y || (m.r > 0 && (!m.ts || !m.B))) return QERL_ERR_NULL;
+    if (m.N < 1 || m.n_tiles < 1 || m.ldy < m.N || m.r < 0 || (m.r > 0 && m.ts_ld < 3 * m.r) ||
+        m.ext_stages * 64 < 3 * m.r || (int64_t)m.ext_stages * 64 > (m.r > 0 ? m.ts_ld : 0))
+      return QERL_ERR_SHAPE;
+  }
   int best = 0;
   float best_score = -1.f;
   for (int c = 0; c < (int)(sizeof(kConfigs) / sizeof(kConfigs[0])); ++c) {
     const GemmConfig& g = kConfigs[c];
     const int64_t bm = g.MT * 32, bn = (int64_t)g.W * g.NT * 32;
-    const int64_t wgs = ceil_div(a.M, bm) * ceil_div(a.N, bn);
+    int64_t col_blocks = 0, n_sum = 0;
+    for (int i = 0; i < a.m_n; ++i) { col_blocks += ceil_div(a.m[i].N, bn); n_sum += a.m[i].N; }
+    const int64_t wgs = ceil_div(a.M, bm) * col_blocks;
     const int64_t slots = 256 * g.wg_per_cu;
     const int64_t rounds = ceil_div(wgs, slots);
-    const float useful = (float)((double)a.M * (double)a.N / ((double)rounds * (double)slots * (double)bm * (double)bn));
-    const float score = useful * g.quality;
+    const float useful = (float)((double)a.M * (double)n_sum / ((double)rounds * (double)slots * (double)bm * (double)bn));
+    const float score = useful * (rounds > 1 ? g.quality_rounds : g.quality);
     if (score > best_score) { best_score = score; best = c; }
   }
   if (g_force_cfg >= 0) best = g_force_cfg;

@@ -444,6 +444,10 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
   xstore(ch0 + tid, xv);
   __syncthreads();
   QTRACE(1);
+  // This wave shares its SIMD with a streaming wave whose conversion arithmetic would otherwise take every
+  // other issue slot: its work per unit is small, and whatever it has not finished when the streaming waves
+  // are done is the tail of the launch.
+  __builtin_amdgcn_s_setprio(3);
 
   // tensor scales of all members up front: no memory round trip between a unit's barrier and its stores
   float S32m[kMaxGroup];
@@ -789,6 +793,10 @@ int plan_stream(StreamArgs& a, size_t* lds_bytes, int* MR_out) {
   int64_t per_range = cus / Sk;
   if (per_range > a.total_tiles) per_range = a.total_tiles;
   if (per_range < 1) per_range = 1;
+  // As many workgroups as give every one the same number of units (+- 1 only where the tiles do not divide):
+  // the launch ends with its slowest workgroup, and the memory system is shared, so 237 workgroups of five
+  // units finish before 160 of five beside 96 of four do.
+  per_range = ceil_div(a.total_tiles, ceil_div(a.total_tiles, per_range));
   a.per_range = (int)per_range; a.kr_len = l.kr_len;
   a.units_base = a.total_tiles / a.per_range; a.units_rem = a.total_tiles % a.per_range;
   return QERL_OK;

@@ -234,7 +234,7 @@ def test_rmsnorm_feeds_linear_end_to_end():
     check_linear(y, ref, "norm->linear")
 
 
-@pytest.mark.parametrize("M", [1, 8, 16, 17, 40, 128])
+@pytest.mark.parametrize("M", [1, 8, 16, 17, 40, 128, 160, 300])   # the last two: the prefill kernel's grouped launch
 @pytest.mark.parametrize("K,Ns,rs", [
     (3584, (3584, 512, 512), (32, 32, 32)),      # q, k, v of the 7B block
     (3584, (1184, 1184), (32, 32)),              # a slice of gate, up

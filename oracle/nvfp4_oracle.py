@@ -22,6 +22,9 @@ What each function follows
   (Algorithm 1, "Set noise level").  Linear, cosine and logarithmic decay are
   named in the scheduler ablation without formulas; the readings are stated
   at aqn_sigma_schedule.
+* Gated input of the down projection, SiLU(gate) (.) up: the feed-forward
+  block of the architectures the paper adapts (Preliminary, "Low-rank
+  Adaptation" names W_gate, W_up, W_down); reading stated at silu_mul.
 * Noise vector Z ~ N(0, sigma^2 I), resampled for each forward pass: Section
   3.3, "Adaptive Quantization Noise".  The paper fixes the distribution, not
   the generator; aqn_noise_philox states the counter-based construction both
@@ -203,6 +206,32 @@ def nvfp4_lora_linear(x, codes, scales, tensor_scale, A=None, B=None,
     if bias is not None:
         y = y + np.asarray(bias, dtype=np.float32).astype(acc_dtype)[None, :]
     return y
+
+
+def round_to_bf16(v):
+    """fp64 -> nearest bf16 value (ties to even), returned as float64.  bf16 keeps the top 16 bits of an
+    IEEE fp32; the inputs met here are far inside the fp32 range, so rounding the fp32 bit pattern is exact
+    double rounding-free only if v is first representable in fp32 -- callers pass fp32-exact values or accept
+    the (documented) one-ulp ambiguity at bf16 ties."""
+    f = np.asarray(v, dtype=np.float64).astype(np.float32)
+    b = f.view(np.uint32).astype(np.uint64)
+    b = (b + 0x7FFF + ((b >> 16) & 1)) & 0xFFFF0000
+    return b.astype(np.uint32).view(np.float32).astype(np.float64).reshape(np.shape(v))
+
+
+def silu_mul(gate, up):
+    """Input of the feed-forward block's down projection: act = SiLU(gate) (.) up, SiLU(g) = g / (1 + e^-g).
+
+    The paper adapts W_gate, W_up and W_down of each block (Preliminary, "Low-rank Adaptation") of the
+    Qwen2.5 / LLaMA architectures it cites, whose feed-forward block is down(SiLU(gate(x)) (.) up(x)); it
+    does not restate the gating.  Reading: the roundings of a bf16 model evaluated operator by operator --
+    gate and up arrive as bf16 values, SiLU(gate) is rounded to bf16, the product is rounded to bf16 -- with
+    the function itself evaluated exactly (float64 here).  Returns bf16 values in float64.
+    """
+    g = np.asarray(gate, dtype=np.float32).astype(np.float64)
+    u = np.asarray(up, dtype=np.float32).astype(np.float64)
+    s = round_to_bf16(g / (1.0 + np.exp(-g)))
+    return round_to_bf16(s * u)
 
 
 def aqn_rmsnorm(x, gain, noise=None, eps=1e-6):

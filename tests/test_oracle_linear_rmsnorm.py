@@ -125,3 +125,48 @@ def test_bias_is_added_to_every_row_before_any_rounding():
     assert np.allclose(with_bias - plain, bias[None, :], rtol=0, atol=1e-12)
     assert with_bias.shape == plain.shape
 
+
+
+# ---- SiLU(gate) (.) up, the input of the down projection -------------------------------------------------
+def test_round_to_bf16_is_nearest_even_on_the_top_16_bits():
+    r = o.round_to_bf16
+    assert r(1.0) == 1.0 and r(-0.15625) == -0.15625                # representable values stay
+    assert r(1.0 + 2.0 ** -8) == 1.0                                 # tie between 1 and 1 + 2^-7: even mantissa wins
+    assert r(1.0 + 3 * 2.0 ** -8) == 1.0 + 2.0 ** -6                 # tie between 1 + 2^-7 and 1 + 2^-6: even wins
+    assert r(1.0 + 2.0 ** -8 + 2.0 ** -20) == 1.0 + 2.0 ** -7        # just above the tie
+    v = np.array([0.1, -2.7, 1e-5, 123.456, 6.02e8])
+    assert np.array_equal(r(r(v)), r(v))                             # idempotent
+    assert np.all(np.abs(r(v) - v) <= np.abs(v) * 2.0 ** -8)         # half a unit in the last of 8 significant bits
+
+
+def test_silu_mul_closed_forms_and_brute_force():
+    import math
+    z = np.zeros(4, dtype=np.float32)
+    u = np.array([1.0, -2.0, 0.5, 3.0], dtype=np.float32)
+    assert np.array_equal(o.silu_mul(z, u), np.zeros(4))                          # SiLU(0) = 0
+    big = np.array([40.0, 64.0, 100.0], dtype=np.float32)
+    one = np.ones(3, dtype=np.float32)
+    assert np.array_equal(o.silu_mul(big, one), big.astype(np.float64))           # SiLU(g) -> g
+    assert np.all(np.abs(o.silu_mul(-big, one)) < 1e-15)                               # SiLU(-g) -> -0
+    # SiLU(g) - SiLU(-g) = g (sigma(g) + sigma(-g) = 1), up to the two bf16 roundings
+    g = np.array([0.25, 0.5, 1.0, 2.0, 3.0, 5.0], dtype=np.float32)
+    d = o.silu_mul(g, np.ones_like(g)) - o.silu_mul(-g, np.ones_like(g))
+    assert np.all(np.abs(d - g) <= 2.0 ** -8 * g)
+    # the minimum of SiLU is about -0.27846 at g = -1.27846
+    assert abs(o.silu_mul(np.float32(-1.2784645), np.float32(1.0)) + 0.27846) < 2.0 ** -9
+    # element by element against math.exp and an independent bf16 rounding through struct
+    import struct
+
+    def bf16(v):
+        bits = struct.unpack("<I", struct.pack("<f", v))[0]
+        bits = (bits + 0x7FFF + ((bits >> 16) & 1)) & 0xFFFF0000
+        return struct.unpack("<f", struct.pack("<I", bits))[0]
+    rng = np.random.default_rng(3)
+    gs = [bf16(float(v)) for v in rng.standard_normal(200) * 3]
+    us = [bf16(float(v)) for v in rng.standard_normal(200) * 2]
+    got = o.silu_mul(np.array(gs, dtype=np.float32), np.array(us, dtype=np.float32))
+    for gi, ui, yi in zip(gs, us, got):
+        want = bf16(bf16(gi / (1.0 + math.exp(-gi))) * ui)
+        assert yi == want, (gi, ui, yi, want)
+    # the gate's sign decides the sign of SiLU; the product follows the usual sign rule
+    assert o.silu_mul(np.float32(-1.0), np.float32(-1.0)) > 0 > o.silu_mul(np.float32(-1.0), np.float32(1.0))

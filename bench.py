@@ -58,9 +58,10 @@ class Layer:
 
 
 class Stack:
-    def __init__(self, config_no: int, M: int, layers: int | None = None):
+    def __init__(self, config_no: int, M: int, layers: int | None = None, swiglu: bool = False):
         cfg = qs.CONFIGS[config_no]
         self.cfg, self.M = cfg, M
+        self.swiglu = swiglu
         self.n_layers = layers or cfg["layers"]
         gen = torch.Generator(device="cuda")
         gen.manual_seed(qs.seed_for(config_no, 0))
@@ -86,6 +87,8 @@ class Stack:
         need = max([qerl.nvfp4_lora_linear_workspace_bytes(M, s.N, s.K, cfg["r"]) for s in cfg["linears"]]
                    + [qerl.nvfp4_lora_linear_workspace_bytes(M, sum(by[n].N for n in g), by[g[0]].K, cfg["r"] * len(g))
                       for g in (("q", "k", "v"), ("gate", "up"))])
+        if swiglu:
+            need = max(need, qerl.load_library().nvfp4_lora_linear_swiglu_workspace_bytes(M, by["down"].N, by["down"].K, cfg["r"]))
         self.ws = qerl.Workspace(need)
         self.packed_bytes_per_layer = sum(s.packed_bytes for s in cfg["linears"])
         self.flops_per_layer = sum(2 * M * s.N * s.K for s in cfg["linears"])
@@ -117,7 +120,12 @@ class Stack:
             self.norm_group(L, ("q", "k", "v"), L.gain_in, L.z_in)
             self.linear(L, "o", self.attn)
             self.norm_group(L, ("gate", "up"), L.gain_post, L.z_post)
-            self.linear(L, "down", self.act)
+            if self.swiglu:   # down reads SiLU(gate) (.) up straight from the two outputs above
+                packed, A, B = L.lin["down"]
+                qerl.nvfp4_lora_linear_packed_swiglu(self.out["gate"], self.out["up"], packed, A, B, self.lora_scale,
+                                                     workspace=self.ws, out=self.out["down"])
+            else:
+                self.linear(L, "down", self.act)
 
 
 def capture(fn):
@@ -255,6 +263,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="BASELINE config number (1-based)")
     ap.add_argument("--M", type=int, default=None)
     ap.add_argument("--layers", type=int, default=None)
+    ap.add_argument("--swiglu", action="store_true",
+                    help="the down projection reads SiLU(gate) (.) up from the gate/up outputs (fused into its launch at M <= 16) instead of a resident input")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--eager", action="store_true", help="launch from Python each step instead of replaying a HIP graph")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -281,7 +291,7 @@ def main():
     M = args.M or cfg["M"][0]
     if args.layers is None and M > 128:
         args.layers = 4                     # compute bound: a few distinct layers are enough
-    stack = Stack(args.config, M, args.layers)
+    stack = Stack(args.config, M, args.layers, swiglu=args.swiglu)
     stack.eager = args.eager
     step = stack.step if args.eager else capture(stack.step)
     for _ in range(args.warmup):
@@ -304,6 +314,7 @@ def main():
                                f"{stack.n_layers} layers, {'decode' if decode else 'prefill'} M={M}, "
                                f"LoRA r={cfg['r']} alpha={cfg['alpha']:g}, "
                                "AQN RMSNorm before q/k/v and gate/up, noise vectors regenerated on the device every step; "
+                               + ("down reads SiLU(gate)*up of the gate/up outputs; " if args.swiglu else "")
                                + ("eager launches" if args.eager else "one HIP graph replay per step"),
                    "packed_weight_bytes_per_step": step_bytes,
                    "tflops": round(tflops, 2),

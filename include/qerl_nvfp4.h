@@ -181,6 +181,30 @@ QERL_API int nvfp4_lora_linear_packed_group(const void* x_bf16, int64_t M, int64
                                             const qerl_linear_desc* members, int n_members,
                                             void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---------------------------------------------------------------------------
+ * nvfp4_lora_linear_packed_swiglu -- the feed-forward block's down projection
+ * on its gated input (the paper adapts W_gate, W_up, W_down of the cited
+ * Qwen2.5 / LLaMA blocks: Preliminary, "Low-rank Adaptation"):
+ *   act = bf16( bf16(SiLU(gate)) (.) up ),  SiLU(g) = g / (1 + e^-g)
+ *   y   = act . W_hat^T + lora_scale * (act . A^T) . B^T          (Eq. 6, Eq. 2)
+ * i.e. nvfp4_lora_linear_packed applied to the tensor a bf16 model evaluated
+ * operator by operator would hand it.  At M <= 16 the product is formed while
+ * the kernel stages its input (no intermediate tensor, no extra launch); for
+ * more tokens one elementwise pass writes act into the workspace first.
+ *   gate [M, ldg], up [M, ldu] bf16 (the outputs of the gate / up projections),
+ *   16-byte aligned, ldg % 8 == ldu % 8 == 0; everything else as
+ *   nvfp4_lora_linear_packed.
+ *   workspace: >= nvfp4_lora_linear_swiglu_workspace_bytes(M, N, K, r), prepared
+ *   like a linear workspace (qerl_workspace_init once).
+ * Errors: as nvfp4_lora_linear_packed.
+ */
+QERL_API size_t nvfp4_lora_linear_swiglu_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t r); /* host */
+QERL_API int nvfp4_lora_linear_packed_swiglu(const void* gate_bf16, const void* up_bf16, int64_t M, int64_t K,
+                                             int64_t ldg, int64_t ldu, const void* packed,
+                                             const float* tensor_scale, int64_t N, const void* A_bf16,
+                                             const void* B_bf16, int64_t r, float lora_scale, void* y_bf16,
+                                             int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Zero the control words of a linear workspace.  Call once after allocating
  * it (and again if a kernel using it was ever aborted). */
 QERL_API int qerl_workspace_init(void* workspace, size_t workspace_bytes, void* stream);

@@ -36,6 +36,10 @@ _SIGNATURES = {
     "nvfp4_lora_linear_packed": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_p, _c_i64,
                                                 _c_p, _c_p, _c_i64, ctypes.c_float, _c_p, _c_i64,
                                                 _c_p, _c_sz, _c_p]),
+    "nvfp4_lora_linear_swiglu_workspace_bytes": (_c_sz, [_c_i64, _c_i64, _c_i64, _c_i64]),
+    "nvfp4_lora_linear_packed_swiglu": (ctypes.c_int, [_c_p, _c_p, _c_i64, _c_i64, _c_i64, _c_i64, _c_p, _c_p, _c_i64,
+                                                       _c_p, _c_p, _c_i64, ctypes.c_float, _c_p, _c_i64,
+                                                       _c_p, _c_sz, _c_p]),
     "nvfp4_lora_linear_packed_group": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, ctypes.c_int,
                                                       _c_p, _c_sz, _c_p]),
     "qerl_workspace_init": (ctypes.c_int, [_c_p, _c_sz, _c_p]),
@@ -298,6 +302,37 @@ def nvfp4_lora_linear_packed(x, w: PackedWeight, A: Optional[torch.Tensor] = Non
         _dev(x, torch.bfloat16, "x"), M, K, ldx, _dev(w.packed, torch.uint8, "packed"),
         _dev(w.tensor_scale, torch.float32, "tensor_scale"), N, a_ptr, b_ptr, r, float(lora_scale),
         _dev(out, torch.bfloat16, "out"), ldy, workspace.ptr, workspace.nbytes, _stream()))
+    return out
+
+
+def nvfp4_lora_linear_packed_swiglu(gate, up, w: PackedWeight, A: Optional[torch.Tensor] = None,
+                                    B: Optional[torch.Tensor] = None, lora_scale: float = 0.0,
+                                    workspace: Optional[Workspace] = None, out: Optional[torch.Tensor] = None):
+    """The down projection applied to bf16(bf16(SiLU(gate)) * up)."""
+    lib = load_library()
+    M, K, ldg = _rows(gate, "gate")
+    M2, K2, ldu = _rows(up, "up")
+    N = w.N
+    if K != w.K or (M2, K2) != (M, K):
+        raise ValueError("gate and up must both be [M, K]")
+    r = 0
+    a_ptr = b_ptr = None
+    if A is not None and B is not None and A.shape[0] > 0:
+        r = A.shape[0]
+        if tuple(A.shape) != (r, K) or tuple(B.shape) != (N, r) or not A.is_contiguous() or not B.is_contiguous():
+            raise ValueError("A must be contiguous [r, K] and B contiguous [N, r]")
+        a_ptr, b_ptr = _dev(A, torch.bfloat16, "A"), _dev(B, torch.bfloat16, "B")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=gate.device)
+    _, n_out, ldy = _rows(out, "out")
+    if out.shape[0] != M or n_out != N:
+        raise ValueError("out must be [M, N]")
+    if workspace is None:
+        workspace = Workspace(lib.nvfp4_lora_linear_swiglu_workspace_bytes(M, N, K, r), gate.device)
+    _check("nvfp4_lora_linear_packed_swiglu", lib.nvfp4_lora_linear_packed_swiglu(
+        _dev(gate, torch.bfloat16, "gate"), _dev(up, torch.bfloat16, "up"), M, K, ldg, ldu,
+        _dev(w.packed, torch.uint8, "packed"), _dev(w.tensor_scale, torch.float32, "tensor_scale"), N, a_ptr, b_ptr, r,
+        float(lora_scale), _dev(out, torch.bfloat16, "out"), ldy, workspace.ptr, workspace.nbytes, _stream()))
     return out
 
 

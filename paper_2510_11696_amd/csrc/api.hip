@@ -62,6 +62,18 @@ static WorkspaceLayout workspace_layout(int64_t M, int64_t N, int64_t K, int64_t
   return L;
 }
 
+// act[m, k] = bf16(bf16(SiLU(gate[m, k])) * up[m, k]), eight values per thread
+__global__ __launch_bounds__(256) void silu_mul_kernel(const uint16_t* __restrict__ gate, int64_t ldg, const uint16_t* __restrict__ up,
+                                                       int64_t ldu, int64_t M, int64_t K, uint16_t* __restrict__ act) {
+  const int64_t chunks = K / 8, total = M * chunks;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t m = i / chunks, c = i - m * chunks;
+    const u32x4 g = *reinterpret_cast<const u32x4*>(gate + m * ldg + c * 8);
+    const u32x4 u = *reinterpret_cast<const u32x4*>(up + m * ldu + c * 8);
+    *reinterpret_cast<u32x4*>(act + m * K + c * 8) = silu_mul8(g, u);
+  }
+}
+
 __global__ void zero_words_kernel(uint32_t* p, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
     p[i] = 0u;
@@ -200,9 +212,10 @@ static bool g_use_stream = true;
 
 // One streaming launch for a group of packed linears sharing x (M <= 16; every r in {0} or 8..64 step 8).
 static int stream_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const qerl_linear_desc* d, int n,
-                        uint8_t* ws, const WorkspaceLayout& L, hipStream_t st) {
+                        uint8_t* ws, const WorkspaceLayout& L, hipStream_t st, const uint16_t* x2 = nullptr, int64_t ldx2 = 0) {
   StreamArgs a{};
   a.x = x; a.ldx = ldx; a.M = (int)M; a.K = K; a.k_tiles = (int)ceil_div(K, kPackTileK);
+  a.x2 = x2; a.ldx2 = ldx2;
   a.n_members = n;
   int tiles = 0, rt = 0, any = 0;
   for (int i = 0; i < n; ++i) {
@@ -389,6 +402,41 @@ extern "C" int nvfp4_lora_linear_packed(const void* x, int64_t M, int64_t K, int
                                         size_t workspace_bytes, void* stream) {
   return packed_single(x, M, K, ldx, packed, tensor_scale, N, A, B, r, lora_scale, nullptr, y, ldy, workspace,
                        workspace_bytes, stream);
+}
+
+extern "C" size_t nvfp4_lora_linear_swiglu_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t r) {
+  return workspace_layout(M, N, K, r).total + align256((size_t)(M > 0 ? M : 0) * (size_t)(K > 0 ? K : 0) * sizeof(uint16_t));
+}
+
+extern "C" int nvfp4_lora_linear_packed_swiglu(const void* gate, const void* up, int64_t M, int64_t K, int64_t ldg, int64_t ldu,
+                                               const void* packed, const float* tensor_scale, int64_t N, const void* A,
+                                               const void* B, int64_t r, float lora_scale, void* y, int64_t ldy,
+                                               void* workspace, size_t workspace_bytes, void* stream) {
+  LinearCall c{(const uint16_t*)gate, M, K, ldg, tensor_scale, N, (const uint16_t*)A, (const uint16_t*)B, r,
+               lora_scale, (uint16_t*)y, ldy, workspace, ~(size_t)0, (hipStream_t)stream};
+  const int vr = validate(c, packed, packed);
+  if (vr != QERL_OK) return vr > 0 ? QERL_OK : vr;
+  if (K == 0 || ldu < K) return QERL_ERR_SHAPE;
+  if (!up) return QERL_ERR_NULL;
+  if (!aligned(packed, 16) || !aligned(gate, 16) || ldg % 8 != 0 || !aligned(up, 16) || ldu % 8 != 0) return QERL_ERR_ALIGN;
+  const WorkspaceLayout L = workspace_layout(M, N, K, r);
+  const size_t act_bytes = align256((size_t)M * (size_t)K * sizeof(uint16_t));
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total + act_bytes) return QERL_ERR_WORKSPACE;
+  uint8_t* ws = (uint8_t*)workspace;
+  if (g_use_stream && M <= 16 && (r == 0 || (r <= 64 && r % 8 == 0 && aligned(A, 16) && aligned(B, 16)))) {
+    // decode: the product is formed while the kernel stages its input; no intermediate tensor
+    qerl_linear_desc d{packed, tensor_scale, N, A, B, r, lora_scale, y, ldy, nullptr, nullptr};
+    return stream_group(c.x, M, K, ldg, &d, 1, ws, L, c.st, (const uint16_t*)up, ldu);
+  }
+  // more tokens: one elementwise pass into the workspace, then the linear on it
+  uint16_t* act = (uint16_t*)(ws + L.total);
+  const int64_t total = M * (K / 8);
+  int64_t blocks = ceil_div(total, 256);
+  blocks = blocks > 4096 ? 4096 : blocks;
+  silu_mul_kernel<<<dim3((unsigned)blocks), dim3(256), 0, c.st>>>(c.x, ldg, (const uint16_t*)up, ldu, M, K, act);
+  const int rc = launch_status();
+  if (rc != QERL_OK) return rc;
+  return packed_single(act, M, K, K, packed, tensor_scale, N, A, B, r, lora_scale, nullptr, y, ldy, workspace, L.total, stream);
 }
 
 static int packed_single(const void* x, int64_t M, int64_t K, int64_t ldx, const void* packed,

@@ -43,6 +43,25 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, v);
 }
 
+// Eight gated activations: bf16(bf16(SiLU(g)) * u), SiLU(g) = g / (1 + e^-g) -- the roundings of a bf16 model
+// evaluated operator by operator.  The function itself is evaluated in fp32 with the hardware's exp2 and
+// reciprocal (about 1 ulp each: every consumer workgroup of the decode kernel recomputes its slice, so the
+// dozens of instructions of the exactly rounded library routines would cost microseconds per launch); the
+// result before the rounding to bf16 is within a few fp32 ulp of the exact one.  g -> -inf gives -0, g -> +inf gives g.
+__device__ __forceinline__ float silu_f32(float g) {
+  const float e = __builtin_amdgcn_exp2f(g * -1.44269504088896341f);   // e^-g; +inf for g << 0
+  return g * __builtin_amdgcn_rcpf(1.0f + e);
+}
+__device__ __forceinline__ uint32_t silu_mul2(uint32_t g, uint32_t u) {
+  const float g0 = bf16_bits_to_f32(g & 0xffffu), g1 = __uint_as_float(g & 0xffff0000u);
+  const float u0 = bf16_bits_to_f32(u & 0xffffu), u1 = __uint_as_float(u & 0xffff0000u);
+  const uint32_t s = pack_bf16x2(silu_f32(g0), silu_f32(g1));
+  return pack_bf16x2(bf16_bits_to_f32(s & 0xffffu) * u0, __uint_as_float(s & 0xffff0000u) * u1);
+}
+__device__ __forceinline__ u32x4 silu_mul8(u32x4 g, u32x4 u) {
+  return u32x4{silu_mul2(g[0], u[0]), silu_mul2(g[1], u[1]), silu_mul2(g[2], u[2]), silu_mul2(g[3], u[3])};
+}
+
 // E4M3 byte (sign clear, not NaN) -> fp32, exact.  (b << 20) places the 4+3
 // bits at an fp32's low exponent / top mantissa bits; multiplying by 2^120
 // re-biases 127 -> 7 and, with fp32 denormals enabled, also covers the

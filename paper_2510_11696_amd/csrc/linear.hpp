@@ -55,6 +55,7 @@ struct StreamMember {
 };
 struct StreamArgs {
   const uint16_t* x; int64_t ldx; int M; int64_t K; int k_tiles;
+  const uint16_t* x2; int64_t ldx2;                       // not null: the input is SiLU(x) (.) x2, formed while x is staged
   int n_members; StreamMember mem[kMaxGroup];
   // flat copy of what the streaming loop needs of the member table (unused entries: INT_MAX / member 0's pointer)
   int tb1, tb2, tb3; const uint8_t* mp0; const uint8_t* mp1; const uint8_t* mp2; const uint8_t* mp3;

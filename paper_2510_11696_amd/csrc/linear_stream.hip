@@ -91,7 +91,7 @@ __device__ unsigned long long g_trace[512 * 8 * 8];
 constexpr int kProdMaxSteps = 96;          // steps per column block: 3 chunks of 16 bytes per lane and row
 constexpr int kProdRowsPerWave = 10;       // (64 rows of A + 16 tokens) / 8 waves
 
-template <int MR>
+template <int MR, bool GATED>
 __device__ __forceinline__ void stream_producer(const StreamArgs& a, unsigned char* smem) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps everything derived from it in SGPRs
@@ -148,6 +148,15 @@ __device__ __forceinline__ void stream_producer(const StreamArgs& a, unsigned ch
       }
       for (int c = tid; c < row_chunks; c += kStreamWaves * 64)   // MFMA rows beyond the tokens / the stacked ranks read zeros
         *reinterpret_cast<u32x4*>(smem + n_rows * stride + c * 16) = u32x4{0u, 0u, 0u, 0u};
+      if constexpr (GATED) {             // gated input: the token rows in LDS become SiLU(x) (.) x2
+        __syncthreads();
+        for (int idx = tid; idx < a.M * row_chunks; idx += kStreamWaves * 64) {
+          const int row = idx / row_chunks, c = idx - row * row_chunks;
+          u32x4* p = reinterpret_cast<u32x4*>(smem + (rows_a + row) * stride + c * 16);
+          const u32x4 u = *reinterpret_cast<const u32x4*>(a.x2 + (int64_t)row * a.ldx2 + (int64_t)cb0 * 16 + c * 8);
+          *p = silu_mul8(*p, u);
+        }
+      }
       __syncthreads();
       if (cb0 == p_s0) QTRACE(1);
       const unsigned char* xrow = smem + (rows_a + (n32 < a.M ? n32 : a.M)) * stride + kg * 16;
@@ -196,7 +205,7 @@ constexpr int kMaxPending = 4;              // units an epilogue wave can park w
 
 // TIGHT: two reduction buffers and parking slots instead of four, B fragments parked for the adapters' actual
 // rank only (the LDS budget of 16 tokens with K = 3584 in one range)
-template <int MR, int D, bool TIGHT>
+template <int MR, int D, bool TIGHT, bool GATED>
 __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamArgs a) {
   // x slice [M (+ 1 zero) rows][xs_stride bytes], red[red_bufs][7][64][MR] floats, parked units, t of a member.  The alignment matters:
   // 16-byte LDS accesses from a misaligned base run several times slower.
@@ -207,7 +216,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
   // grid: the producers, then the consumers range by range: exactly the workgroups that have work, so that
   // all of them are resident from the start (one per CU)
   if ((int)blockIdx.x < a.n_producers) {
-    stream_producer<MR>(a, smem);
+    stream_producer<MR, GATED>(a, smem);
     return;
   }
   const int tid = threadIdx.x, lane = tid & 63;
@@ -236,6 +245,16 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
     for (int tok = 0; tok < MT; ++tok) {
       xv[tok] = u32x4{0u, 0u, 0u, 0u};
       if (tok < a.M && ch < chunks_per_row && k < a.K) xv[tok] = *reinterpret_cast<const u32x4*>(a.x + (int64_t)tok * a.ldx + k);
+    }
+    if constexpr (GATED) {               // gated input: the second operand, then the product in place
+      u32x4 uv[MT];
+#pragma unroll
+      for (int tok = 0; tok < MT; ++tok) {
+        uv[tok] = u32x4{0u, 0u, 0u, 0u};
+        if (tok < a.M && ch < chunks_per_row && k < a.K) uv[tok] = *reinterpret_cast<const u32x4*>(a.x2 + (int64_t)tok * a.ldx2 + k);
+      }
+#pragma unroll
+      for (int tok = 0; tok < MT; ++tok) xv[tok] = silu_mul8(xv[tok], uv[tok]);
     }
   };
   auto xstore = [&](int ch, const u32x4 (&xv)[MT]) {
@@ -802,16 +821,16 @@ int plan_stream(StreamArgs& a, size_t* lds_bytes, int* MR_out) {
   return QERL_OK;
 }
 
-template <int MR, int D, bool TIGHT>
+template <int MR, int D, bool TIGHT, bool GATED = false>
 static int launch_stream_t(const StreamArgs& a, size_t lds, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_kernel<MR, D, TIGHT>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_kernel<MR, D, TIGHT, GATED>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStreamLdsMax) != hipSuccess)
       return launch_status();
     attr_set = true;
   }
-  stream_kernel<MR, D, TIGHT><<<dim3(a.n_producers + a.per_range * a.Sk), dim3(kStreamWaves * 64), lds, st>>>(a);
+  stream_kernel<MR, D, TIGHT, GATED><<<dim3(a.n_producers + a.per_range * a.Sk), dim3(kStreamWaves * 64), lds, st>>>(a);
   if (a.Sk > 1) {
     const int rc = launch_status();
     if (rc != QERL_OK) return rc;
@@ -826,6 +845,7 @@ static int launch_stream_t(const StreamArgs& a, size_t lds, hipStream_t st) {
 int launch_stream(const StreamArgs& a, size_t lds, int MR, hipStream_t st) {
   // every pointer the kernel dereferences must be set by the caller
   if (!a.x || !a.counters || !a.partial || a.n_members < 1 || a.n_members > kMaxGroup) return QERL_ERR_NULL;
+  if (a.x2 && (a.ldx2 < a.K || a.ldx2 % 8 != 0 || ((uintptr_t)a.x2 & 15) != 0)) return QERL_ERR_ALIGN;
   for (int i = 0; i < a.n_members; ++i) {
     const StreamMember& m = a.mem[i];
     if (!m.packed || !m.tensor_scale || !m.y || m.N < 1 || m.n_tiles < 1) return QERL_ERR_NULL;
@@ -857,6 +877,10 @@ int launch_stream(const StreamArgs& a, size_t lds, int MR, hipStream_t st) {
   if (tight != (a.max_pending == 2) || (!tight && (a.red_bufs != kRedBufs || a.max_pending != kMaxPending ||
                                                    (a.pend_steps != kLoraSteps && a.pend_steps != 0))))
     return QERL_ERR_SHAPE;
+  if (a.x2) {   // the variants that form SiLU(x) (.) x2 while staging (kept apart: the code costs the plain ones 2 %)
+    if (MR == 4) return tight ? launch_stream_t<4, 4, true, true>(a, lds, st) : launch_stream_t<4, 4, false, true>(a, lds, st);
+    return tight ? launch_stream_t<8, 4, true, true>(a, lds, st) : launch_stream_t<8, 4, false, true>(a, lds, st);
+  }
   if (MR == 4 && tight) return launch_stream_t<4, 4, true>(a, lds, st);
   if (MR == 4 && g_force_depth == 3) return launch_stream_t<4, 3, false>(a, lds, st);
   if (MR == 4 && g_force_depth == 6) return launch_stream_t<4, 6, false>(a, lds, st);

@@ -154,6 +154,16 @@ def test_host_side_validation_of_the_fused_entry_points(lib):
     assert lib.nvfp4_prepack(fake, fake, 0, 32, fake, None) == 0
     assert lib.nvfp4_prepack_bytes(33, 130) == 2 * 2 * 2304 and lib.nvfp4_prepack_bytes(0, 64) == 0
 
+    sw = lib.nvfp4_lora_linear_packed_swiglu
+    assert sw(fake, fake, 0, 64, 64, 64, fake, fake, 16, None, None, 0, 0.0, fake, 16, fake, big, None) == 0
+    assert sw(fake, None, 2, 64, 64, 64, fake, fake, 16, None, None, 0, 0.0, fake, 16, fake, big, None) == -1   # no up
+    assert sw(fake, fake, 2, 64, 64, 32, fake, fake, 16, None, None, 0, 0.0, fake, 16, fake, big, None) == -2   # ldu < K
+    assert sw(fake, fake + 2, 2, 64, 64, 64, fake, fake, 16, None, None, 0, 0.0, fake, 16, fake, big, None) == -3
+    assert sw(fake, fake, 2, 64, 64, 68, fake, fake, 16, None, None, 0, 0.0, fake, 16, fake, big, None) == -3   # ldu % 8
+    need = lib.nvfp4_lora_linear_swiglu_workspace_bytes(40, 16, 64, 0)
+    assert need >= qerl.nvfp4_lora_linear_workspace_bytes(40, 16, 64, 0) + 40 * 64 * 2
+    assert sw(fake, fake, 40, 64, 64, 64, fake, fake, 16, None, None, 0, 0.0, fake, 16, fake, need - 256, None) == -4
+
     nd = lib.aqn_rmsnorm_lora_down
     A = (ctypes.c_void_p * 5)(*([fake] * 5)); T = (ctypes.c_void_p * 5)(*([fake] * 5))
     R = (ctypes.c_int64 * 5)(32, 32, 32, 32, 32)

@@ -423,3 +423,47 @@ def test_bias_in_grouped_and_single_launches(M, K, Ns, rs):
     check_linear(mixed[0], refs[0], ("mixed", 0))
     assert not torch.equal(mixed[1], outs[1])
 
+
+
+@pytest.mark.parametrize("M", [1, 8, 16, 17, 40, 200])
+@pytest.mark.parametrize("K,N,r,fused_buffer", [
+    (18944, 160, 32, True),      # the 7B down projection's K (several K-ranges), ragged row tile; gate | up side by side
+    (2048, 96, 16, False),
+    (3584, 64, 0, False),        # no adapter
+])
+def test_down_projection_on_the_gated_input(M, K, N, r, fused_buffer):
+    """y = down(bf16(bf16(SiLU(gate)) * up)): within tolerance of the oracle, and nearly bit for bit what the
+    plain packed linear gives when it is handed the oracle's gated tensor (the device evaluates SiLU in fp32
+    with the hardware's exp2 and reciprocal, the oracle in fp64: a rounding to bf16 may fall the other way for a few
+    elements in ten thousand)."""
+    print("swiglu case", M, K, N, r, flush=True)
+    gu = qs.activations(M, 2 * K, 7100 + M) * 2.0
+    gate, up = gu[:, :K], gu[:, K:]
+    W = cases.gaussian(N, K, 7200 + M)
+    codes, scales, ts = oracle.nvfp4_quantize(W)
+    A = B = None
+    if r:
+        A, B = qs.lora_pair(N, K, r, 7300)
+    g = lambda a: torch.from_numpy(a).cuda()
+    pw = qerl.nvfp4_prepack(g(codes), g(scales), torch.tensor([ts], device="cuda"))
+    act = oracle.silu_mul(gate.float().numpy(), up.float().numpy())
+    ref = oracle.nvfp4_lora_linear(act.astype(np.float32), codes, scales, ts, A.float().numpy() if r else None,
+                                   B.float().numpy() if r else None, 2.0)
+    if fused_buffer:
+        dev = gu.cuda()
+        gd, ud = dev[:, :K], dev[:, K:]
+    else:
+        gd, ud = gate.contiguous().cuda(), up.contiguous().cuda()
+    Ad, Bd = (A.cuda(), B.cuda()) if r else (None, None)
+    y = qerl.nvfp4_lora_linear_packed_swiglu(gd, ud, pw, Ad, Bd, 2.0)
+    torch.cuda.synchronize()
+    check_linear(y, ref, ("swiglu", M, K, N, r))
+    act_dev = torch.from_numpy(act.astype(np.float32)).to(torch.bfloat16).cuda()
+    assert np.array_equal(act_dev.float().cpu().numpy(), act.astype(np.float32))       # the oracle's tensor is bf16-exact
+    plain = qerl.nvfp4_lora_linear_packed(act_dev, pw, Ad, Bd, 2.0)
+    d = (y.float() - plain.float()).abs().cpu().numpy()
+    scale = np.abs(ref).max(axis=1, keepdims=True)
+    assert (d <= 2.0 ** -6 * scale).all(), d.max()
+    assert (d == 0).mean() >= 0.9, (d == 0).mean()
+    again = qerl.nvfp4_lora_linear_packed_swiglu(gd, ud, pw, Ad, Bd, 2.0)
+    assert torch.equal(y, again)

@@ -22,6 +22,9 @@ What each function follows
   (Algorithm 1, "Set noise level").  Linear, cosine and logarithmic decay are
   named in the scheduler ablation without formulas; the readings are stated
   at aqn_sigma_schedule.
+* Backward pass of the layer (the paper optimises A and B only and
+  backpropagates through the frozen quantised weights: Preliminary,
+  "Low-rank Adaptation"): nvfp4_lora_linear_backward.
 * Gated input of the down projection, SiLU(gate) (.) up: the feed-forward
   block of the architectures the paper adapts (Preliminary, "Low-rank
   Adaptation" names W_gate, W_up, W_down); reading stated at silu_mul.
@@ -206,6 +209,33 @@ def nvfp4_lora_linear(x, codes, scales, tensor_scale, A=None, B=None,
     if bias is not None:
         y = y + np.asarray(bias, dtype=np.float32).astype(acc_dtype)[None, :]
     return y
+
+
+def nvfp4_lora_linear_backward(x, dy, codes, scales, tensor_scale, A=None, B=None, lora_scale=0.0):
+    """Gradients of  y = x W_hat^T + s (x A^T) B^T  (Eq. 2 + Eq. 6, s = lora_scale) for an upstream dL/dy = dy:
+
+        dx = dy W_hat + s (dy B) A          [M, K]     (W_hat is frozen: it gets no gradient)
+        dA = s (dy B)^T x                   [r, K]
+        dB = s dy^T (x A^T)                 [N, r]
+
+    The paper trains only the LoRA matrices and backpropagates through the quantised weights
+    (Preliminary, "Low-rank Adaptation": W frozen, A and B optimised; Section 3.1: gradient
+    backpropagation through the LoRA layers); it prints no formulas for the gradients, these are the plain
+    matrix-calculus ones.  float64 throughout, nothing rounded.  Returns (dx, dA, dB); dA and dB are None
+    without an adapter.
+    """
+    x = np.asarray(x, dtype=np.float32).astype(np.float64)
+    dy = np.asarray(dy, dtype=np.float32).astype(np.float64)
+    W_hat = nvfp4_dequantize(codes, scales, tensor_scale).astype(np.float64)
+    dx = dy @ W_hat
+    if A is None or B is None or np.asarray(A).shape[0] == 0:
+        return dx, None, None
+    A = np.asarray(A, dtype=np.float32).astype(np.float64)
+    B = np.asarray(B, dtype=np.float32).astype(np.float64)
+    s = np.float64(lora_scale)
+    u = dy @ B                      # [M, r]
+    t = x @ A.T                     # [M, r]
+    return dx + s * (u @ A), s * (u.T @ x), s * (dy.T @ t)
 
 
 def round_to_bf16(v):

@@ -170,3 +170,69 @@ def test_silu_mul_closed_forms_and_brute_force():
         assert yi == want, (gi, ui, yi, want)
     # the gate's sign decides the sign of SiLU; the product follows the usual sign rule
     assert o.silu_mul(np.float32(-1.0), np.float32(-1.0)) > 0 > o.silu_mul(np.float32(-1.0), np.float32(1.0))
+
+
+# ---- backward pass ----------------------------------------------------------------------------------------
+def _bwd_case(seed, M=3, N=20, K=32, r=8):
+    rng = np.random.default_rng(seed)
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    codes, scales, ts = o.nvfp4_quantize(W)
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    dy = rng.standard_normal((M, N)).astype(np.float32)
+    A = (rng.standard_normal((r, K)) / r).astype(np.float32)
+    B = (rng.standard_normal((N, r)) * 0.1).astype(np.float32)
+    return x, dy, codes, scales, ts, A, B
+
+
+def test_backward_is_the_adjoint_of_the_forward_map():
+    """<dy, J v> = <J^T dy, v> for the three arguments the layer is (bi)linear in; the forward map is the pinned
+    nvfp4_lora_linear.  y is linear in x, and linear in A (B fixed) and in B (A fixed): the directional
+    derivatives are exact differences of forward values, no step size involved."""
+    x, dy, codes, scales, ts, A, B = _bwd_case(1)
+    s = 1.75
+    f = lambda x_, A_, B_: o.nvfp4_lora_linear(x_, codes, scales, ts, A_, B_, s)
+    dx, dA, dB = o.nvfp4_lora_linear_backward(x, dy, codes, scales, ts, A, B, s)
+    rng = np.random.default_rng(2)
+    vx = rng.standard_normal(x.shape).astype(np.float32)
+    vA = rng.standard_normal(A.shape).astype(np.float32)
+    vB = rng.standard_normal(B.shape).astype(np.float32)
+    zero_x = np.zeros_like(x)
+    assert np.isclose(np.sum(dy * (f(vx, A, B) - f(zero_x, A, B))), np.sum(dx * vx), rtol=1e-12)
+    zA, zB = np.zeros_like(A), np.zeros_like(B)
+    assert np.isclose(np.sum(dy * (f(x, vA, B) - f(x, zA, B))), np.sum(dA * vA), rtol=1e-11)
+    assert np.isclose(np.sum(dy * (f(x, A, vB) - f(x, A, zB))), np.sum(dB * vB), rtol=1e-11)
+
+
+def test_backward_entries_by_brute_force_and_special_cases():
+    x, dy, codes, scales, ts, A, B = _bwd_case(3, M=2, N=5, K=16, r=3)
+    s = 0.5
+    W = o.nvfp4_dequantize(codes, scales, ts).astype(np.float64)
+    dx, dA, dB = o.nvfp4_lora_linear_backward(x, dy, codes, scales, ts, A, B, s)
+    M, K = x.shape
+    N, r = B.shape
+    for m in range(M):
+        for k in range(K):
+            want = sum(float(dy[m, n]) * (W[n, k] + s * sum(float(B[n, j]) * float(A[j, k]) for j in range(r))) for n in range(N))
+            assert abs(dx[m, k] - want) <= 1e-12 * max(1.0, abs(want))
+    for j in range(r):
+        for k in range(K):
+            want = s * sum(float(dy[m, n]) * float(B[n, j]) * float(x[m, k]) for m in range(M) for n in range(N))
+            assert abs(dA[j, k] - want) <= 1e-12 * max(1.0, abs(want))
+    for n in range(N):
+        for j in range(r):
+            want = s * sum(float(dy[m, n]) * sum(float(x[m, k]) * float(A[j, k]) for k in range(K)) for m in range(M))
+            assert abs(dB[n, j] - want) <= 1e-12 * max(1.0, abs(want))
+    # without an adapter: dx = dy W_hat, no LoRA gradients; with B = 0: dx has no LoRA term and dA = 0, dB != 0
+    dx0, a0, b0 = o.nvfp4_lora_linear_backward(x, dy, codes, scales, ts)
+    assert a0 is None and b0 is None and np.allclose(dx0, dy.astype(np.float64) @ W, rtol=1e-14)
+    dx1, dA1, dB1 = o.nvfp4_lora_linear_backward(x, dy, codes, scales, ts, A, np.zeros_like(B), s)
+    assert np.array_equal(dx1, dx0) and not dA1.any() and dB1.any()
+    # finite differences of a quadratic loss L = |y|^2 / 2 (dL/dy = y): central differences are exact up to rounding
+    y = o.nvfp4_lora_linear(x, codes, scales, ts, A, B, s)
+    gx, gA, gB = o.nvfp4_lora_linear_backward(x, y.astype(np.float32), codes, scales, ts, A, B, s)
+    L = lambda A_: 0.5 * np.sum(o.nvfp4_lora_linear(x, codes, scales, ts, A_, B, s) ** 2)
+    h = np.float32(2.0 ** -6)
+    E = np.zeros_like(A); E[1, 5] = h
+    fd = (L(A + E) - L(A - E)) / (2 * float(h))
+    yg = o.nvfp4_lora_linear_backward(x, y.astype(np.float32), codes, scales, ts, A, B, s)[1][1, 5]
+    assert abs(fd - yg) <= 1e-4 * max(1.0, abs(fd))      # y was rounded to fp32 for the call: not bit-exact

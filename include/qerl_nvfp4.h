@@ -205,6 +205,38 @@ QERL_API int nvfp4_lora_linear_packed_swiglu(const void* gate_bf16, const void* 
                                              const void* B_bf16, int64_t r, float lora_scale, void* y_bf16,
                                              int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---------------------------------------------------------------------------
+ * nvfp4_lora_linear_backward -- gradients of y = x W_hat^T + s (x A^T) B^T for an
+ * upstream dY (the paper trains A and B only and backpropagates through the
+ * frozen quantised weights: Preliminary, "Low-rank Adaptation"; Eq. 2, Eq. 6):
+ *   dX [M, lddx] bf16 = dY W_hat + s (dY B) A        (one rounding to bf16)
+ *   dA [r, K]    fp32 = s (dY B)^T x
+ *   dB [N, r]    fp32 = s dY^T (x A^T)               (s = lora_scale)
+ * fp32 accumulation; x A^T and dY B are carried as three bf16 terms (exact to
+ * 2^-24 relative) as in the forward pass.
+ *   nvfp4_prepack_t: the canonical codes / scales re-ordered once into the
+ *     transposed tile order dX needs (tiles of 32 inputs x 128 rows, 2304
+ *     bytes; nvfp4_prepack_t_bytes(N, K) bytes, 16-byte aligned).  Same size
+ *     per weight as the forward order; the weights are frozen, so both orders
+ *     are made once.
+ *   x [M, ldx], dY [M, lddy] bf16, 16-byte aligned, ld % 8 == 0; N % 8 == 0;
+ *   A [r, K], B [N, r] bf16 contiguous, 16-byte aligned; r % 8 == 0, r <= 64.
+ *   r == 0: only dX is written (x, A, B, dA, dB may be NULL).
+ *   workspace: >= nvfp4_lora_linear_backward_workspace_bytes(M, N, K, r),
+ *   256-byte aligned; needs no initialisation.
+ * Errors: as the forward functions.
+ */
+QERL_API size_t nvfp4_prepack_t_bytes(int64_t N, int64_t K);   /* host */
+QERL_API int nvfp4_prepack_t(const uint8_t* codes, const uint8_t* scales, int64_t N, int64_t K,
+                             void* packed_t, void* stream);
+QERL_API size_t nvfp4_lora_linear_backward_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t r); /* host */
+QERL_API int nvfp4_lora_linear_backward(const void* x_bf16, const void* dy_bf16, int64_t M, int64_t K, int64_t N,
+                                        int64_t ldx, int64_t lddy, const void* packed_t,
+                                        const float* tensor_scale, const void* A_bf16, const void* B_bf16,
+                                        int64_t r, float lora_scale, void* dx_bf16, int64_t lddx,
+                                        float* dA_f32, float* dB_f32, void* workspace, size_t workspace_bytes,
+                                        void* stream);
+
 /* Zero the control words of a linear workspace.  Call once after allocating
  * it (and again if a kernel using it was ever aborted). */
 QERL_API int qerl_workspace_init(void* workspace, size_t workspace_bytes, void* stream);

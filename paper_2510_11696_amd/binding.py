@@ -40,6 +40,11 @@ _SIGNATURES = {
     "nvfp4_lora_linear_packed_swiglu": (ctypes.c_int, [_c_p, _c_p, _c_i64, _c_i64, _c_i64, _c_i64, _c_p, _c_p, _c_i64,
                                                        _c_p, _c_p, _c_i64, ctypes.c_float, _c_p, _c_i64,
                                                        _c_p, _c_sz, _c_p]),
+    "nvfp4_prepack_t_bytes": (_c_sz, [_c_i64, _c_i64]),
+    "nvfp4_prepack_t": (ctypes.c_int, [_c_p, _c_p, _c_i64, _c_i64, _c_p, _c_p]),
+    "nvfp4_lora_linear_backward_workspace_bytes": (_c_sz, [_c_i64, _c_i64, _c_i64, _c_i64]),
+    "nvfp4_lora_linear_backward": (ctypes.c_int, [_c_p, _c_p, _c_i64, _c_i64, _c_i64, _c_i64, _c_i64, _c_p, _c_p, _c_p, _c_p,
+                                                  _c_i64, ctypes.c_float, _c_p, _c_i64, _c_p, _c_p, _c_p, _c_sz, _c_p]),
     "nvfp4_lora_linear_packed_group": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, ctypes.c_int,
                                                       _c_p, _c_sz, _c_p]),
     "qerl_workspace_init": (ctypes.c_int, [_c_p, _c_sz, _c_p]),
@@ -334,6 +339,62 @@ def nvfp4_lora_linear_packed_swiglu(gate, up, w: PackedWeight, A: Optional[torch
         _dev(w.packed, torch.uint8, "packed"), _dev(w.tensor_scale, torch.float32, "tensor_scale"), N, a_ptr, b_ptr, r,
         float(lora_scale), _dev(out, torch.bfloat16, "out"), ldy, workspace.ptr, workspace.nbytes, _stream()))
     return out
+
+
+class PackedWeightT:
+    """The transposed tile order of one NVFP4 weight (nvfp4_prepack_t), for the backward pass."""
+
+    def __init__(self, packed, tensor_scale, N, K):
+        self.packed, self.tensor_scale, self.N, self.K = packed, tensor_scale, N, K
+
+
+def nvfp4_prepack_t(codes: torch.Tensor, scales: torch.Tensor, tensor_scale: torch.Tensor) -> PackedWeightT:
+    lib = load_library()
+    N, K = codes.shape[0], codes.shape[1] * 2
+    if tuple(scales.shape) != (N, K // 16) or not codes.is_contiguous() or not scales.is_contiguous():
+        raise ValueError("codes must be contiguous [N, K/2] and scales contiguous [N, K/16]")
+    packed = torch.empty((lib.nvfp4_prepack_t_bytes(N, K),), dtype=torch.uint8, device=codes.device)
+    _check("nvfp4_prepack_t", lib.nvfp4_prepack_t(_dev(codes, torch.uint8, "codes"), _dev(scales, torch.uint8, "scales"),
+                                                  N, K, _dev(packed, torch.uint8, "packed"), _stream()))
+    return PackedWeightT(packed, tensor_scale, N, K)
+
+
+def nvfp4_lora_linear_backward(x, dy, w: PackedWeightT, A: Optional[torch.Tensor] = None,
+                               B: Optional[torch.Tensor] = None, lora_scale: float = 0.0,
+                               workspace: Optional[torch.Tensor] = None):
+    """(dx bf16 [M, K], dA fp32 [r, K] or None, dB fp32 [N, r] or None)."""
+    lib = load_library()
+    M, N, lddy = _rows(dy, "dy")
+    K = w.K
+    if N != w.N:
+        raise ValueError("dy has the wrong number of columns")
+    r = 0
+    x_ptr = a_ptr = b_ptr = da_ptr = db_ptr = None
+    ldx = K
+    dA = dB = None
+    if A is not None and B is not None and A.shape[0] > 0:
+        r = A.shape[0]
+        if tuple(A.shape) != (r, K) or tuple(B.shape) != (N, r) or not A.is_contiguous() or not B.is_contiguous():
+            raise ValueError("A must be contiguous [r, K] and B contiguous [N, r]")
+        Mx, Kx, ldx = _rows(x, "x")
+        if (Mx, Kx) != (M, K):
+            raise ValueError("x must be [M, K]")
+        x_ptr = _dev(x, torch.bfloat16, "x")
+        a_ptr, b_ptr = _dev(A, torch.bfloat16, "A"), _dev(B, torch.bfloat16, "B")
+        dA = torch.empty((r, K), dtype=torch.float32, device=dy.device)
+        dB = torch.empty((N, r), dtype=torch.float32, device=dy.device)
+        da_ptr, db_ptr = _dev(dA, torch.float32, "dA"), _dev(dB, torch.float32, "dB")
+    dx = torch.empty((M, K), dtype=torch.bfloat16, device=dy.device)
+    need = lib.nvfp4_lora_linear_backward_workspace_bytes(M, N, K, r)
+    if workspace is None:
+        workspace = torch.empty((need + 256,), dtype=torch.uint8, device=dy.device)
+    base = workspace.data_ptr()
+    ws_ptr = (base + 255) & ~255
+    _check("nvfp4_lora_linear_backward", lib.nvfp4_lora_linear_backward(
+        x_ptr, _dev(dy, torch.bfloat16, "dy"), M, K, N, ldx, lddy, _dev(w.packed, torch.uint8, "packed_t"),
+        _dev(w.tensor_scale, torch.float32, "tensor_scale"), a_ptr, b_ptr, r, float(lora_scale),
+        _dev(dx, torch.bfloat16, "dx"), K, da_ptr, db_ptr, ws_ptr, workspace.numel() - (ws_ptr - base), _stream()))
+    return dx, dA, dB
 
 
 T_PARTS = 8   # QERL_T_PARTS in the header

@@ -91,6 +91,21 @@ __device__ __forceinline__ bf16x8 dequant8_bf16(uint32_t codes, float s) {
   return __builtin_bit_cast(bf16x8, o);
 }
 
+// 8 weights of one lane that lie along the rows of W (one dword of codes of the transposed tile order), each
+// times its own block scale (the 8 scale bytes in sc) -> bf16 x8; every product is exact
+__device__ __forceinline__ bf16x8 dequant8_t_bf16(uint32_t codes, u32x2 sc) {
+  const f32x2 p0 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 0);
+  const f32x2 p1 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 1);
+  const f32x2 p2 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 2);
+  const f32x2 p3 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(codes, 1.0f, 3);
+  u32x4 o;
+  o[0] = pack_bf16x2(p0.x * __builtin_amdgcn_cvt_f32_fp8(sc[0], 0), p0.y * __builtin_amdgcn_cvt_f32_fp8(sc[0], 1));
+  o[1] = pack_bf16x2(p1.x * __builtin_amdgcn_cvt_f32_fp8(sc[0], 2), p1.y * __builtin_amdgcn_cvt_f32_fp8(sc[0], 3));
+  o[2] = pack_bf16x2(p2.x * __builtin_amdgcn_cvt_f32_fp8(sc[1], 0), p2.y * __builtin_amdgcn_cvt_f32_fp8(sc[1], 1));
+  o[3] = pack_bf16x2(p3.x * __builtin_amdgcn_cvt_f32_fp8(sc[1], 2), p3.y * __builtin_amdgcn_cvt_f32_fp8(sc[1], 3));
+  return __builtin_bit_cast(bf16x8, o);
+}
+
 __device__ __forceinline__ float e4m3_byte_f32(uint32_t v, int b) {
   switch (b) {
     case 0: return __builtin_amdgcn_cvt_f32_fp8(v, 0);

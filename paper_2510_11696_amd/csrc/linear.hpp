@@ -93,6 +93,7 @@ struct GemmArgs {
   uint16_t* y; int64_t ldy;
   int n_tiles; int n_blocks; int nblk_per_xcd;
   int m_n; GemmMember m[kMaxGroup];                                         // the main launch's members (m_n == 0: one, from the fields above)
+  int transposed;                                                           // packed is in nvfp4_prepack_t's order: K counts rows of W, N its columns
   uint32_t* tpart; uint32_t* counters;                                      // LoRA down-projection over several K-parts: partial sums, arrival counts (zero between calls); or null
   // LoRA down-projection of a group of adapters that read the same x (g_n > 0): grid.y runs over the 32-row
   // tiles of all adapters; member i owns tiles [g_tile0[i], g_tile0[i+1]) and has its own A, ts and scales

@@ -1,0 +1,235 @@
+// Backward pass of the NVFP4 + LoRA linear: only the adapters are trained, the gradient flows through the
+// frozen quantised weights (Preliminary, "Low-rank Adaptation"; Eq. 2, Eq. 6).  For an upstream dY [M, N]:
+//
+//   dX = dY W_hat + s (dY B) A          [M, K]  bf16
+//   dA = s (dY B)^T x                   [r, K]  fp32
+//   dB = s dY^T (x A^T)                 [N, r]  fp32          (s = lora_scale)
+//
+// dX contracts over N, i.e. over the ROWS of the packed weight tiles, so the same bytes are needed in a second,
+// transposed tile order (nvfp4_prepack_t; the weights are frozen, the order is made once):
+//   tile (kt, nt) = 32 inputs k = 32 kt .. + 31  x  128 rows n = 128 nt .. + 127, 2304 bytes like the forward tile:
+//   two 1 KiB planes of codes (plane p = rows 64 p .. 64 p + 63; lane l = (c = l % 32, g = l / 32) owns 16 bytes:
+//   dword j holds the codes of rows 64 p + 16 j + 8 g .. + 7 at input 32 kt + c, nibble i = row + i), then 256 scale
+//   bytes [plane][input block 0..1][64 rows].  Tiles of one kt are consecutive along nt.
+// gemm32_kernel<.., TR = true> multiplies dY with it (the eight weights of a lane and step carry eight different
+// E4M3 scales; products stay exact in bf16), the LoRA term enters as 3r more contraction columns exactly as in
+// the forward pass with the roles of A and B exchanged (both transposed once per call: they change with every
+// optimiser step).  dA and dB are skinny products over the token dimension: one thread per column of x (of dY),
+// all ranks in registers, tokens split over a few workgroups whose partial sums are added in order.
+#include "linear.hpp"
+
+namespace qerl {
+
+// ---- transposed tile order -----------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void prepack_t_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales,
+                                                        int64_t N, int64_t K, int64_t k_tiles32, int64_t n_tiles128,
+                                                        uint8_t* __restrict__ out) {
+  // one thread per (tile, plane, lane) for the codes; the first 256 threads-worth of each tile also place a scale byte
+  const int64_t total = k_tiles32 * n_tiles128 * 128;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int lane = (int)(i & 63), plane = (int)((i >> 6) & 1);
+    const int64_t tile = i >> 7, nt = tile % n_tiles128, kt = tile / n_tiles128;
+    const int c = lane & 31, g = lane >> 5;
+    const int64_t k = kt * 32 + c;
+    uint8_t* t = out + tile * kPackTileBytes;
+    u32x4 v = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      uint32_t w = 0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int64_t n = nt * 128 + plane * 64 + 16 * j + 8 * g + e;
+        uint32_t nib = 0;
+        if (n < N && k < K) nib = (codes[n * (K / 2) + k / 2] >> (4 * (int)(k & 1))) & 0xFu;
+        w |= nib << (4 * e);
+      }
+      v[j] = w;
+    }
+    *reinterpret_cast<u32x4*>(t + plane * 1024 + lane * 16) = v;
+    // scale bytes: [plane][input block kb][64 rows]; this thread places two of the tile's 256
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int idx = plane * 128 + h * 64 + lane;          // = plane * 128 + kb * 64 + row, kb = h, row = lane
+      const int64_t n = nt * 128 + plane * 64 + lane, kb = kt * 2 + h;
+      uint8_t sc = 0;
+      if (n < N && kb * 16 < K) sc = scales[n * (K / 16) + kb];
+      t[2048 + idx] = sc;
+    }
+  }
+}
+
+// out[c, r] = in[r, c] for a small bf16 matrix (the adapters)
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __restrict__ in, int64_t R, int64_t C, uint16_t* __restrict__ out) {
+  const int64_t total = R * C;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t c = i / R, r = i - c * R;        // consecutive threads write consecutive elements of out
+    out[i] = in[r * C + c];
+  }
+}
+
+// ---- dA, dB: partial[chunk][c][j] = sum over the chunk's tokens of P[m, j] * Q[m, c] ------------------------
+// P [M, r] arrives as the three bf16 terms the LoRA down-projection kernel writes ([M, ts_ld]: hi | mid | lo,
+// their sum exact to 2^-24); Q is x or dY (bf16, row-major).  One thread per column c, all r sums in registers.
+constexpr int kGradRanks = 64;       // most ranks
+constexpr int kGradTokens = 32;      // tokens of P staged in LDS at a time
+constexpr int kGradChunksMax = 8;    // token chunks (workgroups along M) whose partial sums are added in order
+__global__ __launch_bounds__(256) void lora_grad_partial_kernel(const uint16_t* __restrict__ ts, int64_t ts_ld, int r,
+                                                                const uint16_t* __restrict__ Q, int64_t ldq, int64_t M, int64_t C,
+                                                                int64_t tokens_per_chunk, float* __restrict__ partial) {
+  __shared__ float P[kGradTokens][kGradRanks];
+  const int tid = threadIdx.x;
+  const int64_t c = (int64_t)blockIdx.x * 256 + tid;
+  const int64_t m_lo = (int64_t)blockIdx.y * tokens_per_chunk;
+  const int64_t m_hi = m_lo + tokens_per_chunk < M ? m_lo + tokens_per_chunk : M;
+  float acc[kGradRanks];
+#pragma unroll
+  for (int j = 0; j < kGradRanks; ++j) acc[j] = 0.f;
+  for (int64_t m0 = m_lo; m0 < m_hi; m0 += kGradTokens) {
+    __syncthreads();                      // the previous tile has been read
+    for (int e = tid; e < kGradTokens * kGradRanks; e += 256) {
+      const int mm = e / kGradRanks, j = e - mm * kGradRanks;
+      float v = 0.f;
+      if (m0 + mm < m_hi && j < r) {
+        const uint16_t* row = ts + (m0 + mm) * ts_ld;
+        v = (bf16_bits_to_f32(row[j]) + bf16_bits_to_f32(row[r + j])) + bf16_bits_to_f32(row[2 * r + j]);
+      }
+      P[mm][j] = v;
+    }
+    __syncthreads();
+    if (c < C) {
+      for (int mm = 0; mm < kGradTokens; ++mm) {
+        if (m0 + mm >= m_hi) break;       // uniform
+        const float q = bf16_bits_to_f32(Q[(m0 + mm) * ldq + c]);
+#pragma unroll
+        for (int j = 0; j < kGradRanks; ++j) acc[j] += P[mm][j] * q;
+      }
+    }
+  }
+  if (c < C) {
+    float* dst = partial + ((int64_t)blockIdx.y * C + c) * kGradRanks;
+#pragma unroll
+    for (int j4 = 0; j4 < kGradRanks / 4; ++j4)
+      *reinterpret_cast<f32x4*>(dst + 4 * j4) = f32x4{acc[4 * j4], acc[4 * j4 + 1], acc[4 * j4 + 2], acc[4 * j4 + 3]};
+  }
+}
+
+// out = mult * sum over chunks (in chunk order); stored as [C, r] or transposed as [r, C]
+__global__ __launch_bounds__(256) void lora_grad_reduce_kernel(const float* __restrict__ partial, int n_chunks, int64_t C, int r,
+                                                               const float* __restrict__ mult, int transposed, float* __restrict__ out) {
+  const int64_t total = C * r;
+  const float s = *mult;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    // consecutive threads write consecutive elements of out
+    int64_t c; int j;
+    if (transposed) { j = (int)(i / C); c = i - (int64_t)j * C; } else { c = i / r; j = (int)(i - c * r); }
+    float sum = 0.f;
+    for (int z = 0; z < n_chunks; ++z) sum += partial[((int64_t)z * C + c) * kGradRanks + j];
+    out[i] = sum * s;
+  }
+}
+
+static size_t al256(size_t v) { return (v + 255) & ~(size_t)255; }
+struct BackwardLayout { size_t at_off, bt_off, tsu_off, tst_off, part_off, total; int64_t ts_ld; int ext_stages; int n_chunks; int64_t tokens_per_chunk; };
+static BackwardLayout backward_layout(int64_t M, int64_t N, int64_t K, int64_t r) {
+  BackwardLayout L{};
+  const size_t m = (size_t)(M > 0 ? M : 1), n = (size_t)(N > 0 ? N : 1), k = (size_t)(K > 0 ? K : 1), rr = (size_t)(r > 0 ? r : 0);
+  L.ext_stages = (int)ceil_div(3 * (int64_t)rr, 64);
+  L.ts_ld = (int64_t)L.ext_stages * 64;
+  int64_t chunks = ceil_div((int64_t)m, 64);
+  chunks = chunks > kGradChunksMax ? kGradChunksMax : chunks;
+  L.n_chunks = (int)chunks;
+  L.tokens_per_chunk = ceil_div((int64_t)m, chunks);
+  L.at_off = 0;
+  L.bt_off = L.at_off + al256(k * rr * 2);
+  L.tsu_off = L.bt_off + al256(n * rr * 2);
+  L.tst_off = L.tsu_off + al256(m * (size_t)L.ts_ld * 2);
+  L.part_off = L.tst_off + al256(m * (size_t)L.ts_ld * 2);
+  L.total = L.part_off + (rr ? al256((size_t)chunks * (n > k ? n : k) * kGradRanks * sizeof(float)) : 0);
+  if (L.total == 0) L.total = 256;
+  return L;
+}
+static int grid_for(int64_t items) {
+  int64_t b = ceil_div(items, 256);
+  return (int)(b < 1 ? 1 : (b > 8192 ? 8192 : b));
+}
+
+}  // namespace qerl
+
+using namespace qerl;
+
+extern "C" size_t nvfp4_prepack_t_bytes(int64_t N, int64_t K) {
+  if (N <= 0 || K <= 0) return 0;
+  return (size_t)ceil_div(K, 32) * (size_t)ceil_div(N, 128) * kPackTileBytes;
+}
+
+extern "C" int nvfp4_prepack_t(const uint8_t* codes, const uint8_t* scales, int64_t N, int64_t K, void* packed_t, void* stream) {
+  if (N < 0 || K < 0 || K % kBlock != 0) return QERL_ERR_SHAPE;
+  if (N == 0 || K == 0) return QERL_OK;
+  if (!codes || !scales || !packed_t) return QERL_ERR_NULL;
+  if (!aligned(packed_t, 16)) return QERL_ERR_ALIGN;
+  const int64_t kt = ceil_div(K, 32), nt = ceil_div(N, 128);
+  prepack_t_kernel<<<dim3((unsigned)grid_for(kt * nt * 128)), dim3(256), 0, (hipStream_t)stream>>>(codes, scales, N, K, kt, nt, (uint8_t*)packed_t);
+  return launch_status();
+}
+
+extern "C" size_t nvfp4_lora_linear_backward_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t r) {
+  return backward_layout(M, N, K, r).total;
+}
+
+extern "C" int nvfp4_lora_linear_backward(const void* x, const void* dy, int64_t M, int64_t K, int64_t N, int64_t ldx, int64_t lddy,
+                                          const void* packed_t, const float* tensor_scale, const void* A, const void* B,
+                                          int64_t r, float lora_scale, void* dx, int64_t lddx, float* dA, float* dB,
+                                          void* workspace, size_t workspace_bytes, void* stream) {
+  if (M < 0 || N < 0 || K < 0 || r < 0 || K % kBlock != 0 || N % 8 != 0 || ldx < K || lddy < N || lddx < K) return QERL_ERR_SHAPE;
+  if (r > kGradRanks || r % 8 != 0) return QERL_ERR_SHAPE;
+  if (M == 0 || N == 0 || K == 0) return M == 0 ? QERL_OK : QERL_ERR_SHAPE;
+  if (!dy || !dx || !packed_t || !tensor_scale) return QERL_ERR_NULL;
+  if (r > 0 && (!x || !A || !B || !dA || !dB)) return QERL_ERR_NULL;
+  if (!aligned(dy, 16) || lddy % 8 != 0 || !aligned(packed_t, 16) || !aligned(dx, 2)) return QERL_ERR_ALIGN;
+  if (r > 0 && (!aligned(x, 16) || ldx % 8 != 0 || !aligned(A, 16) || !aligned(B, 16) || !aligned(dA, 4) || !aligned(dB, 4)))
+    return QERL_ERR_ALIGN;
+  const BackwardLayout L = backward_layout(M, N, K, r);
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total) return QERL_ERR_WORKSPACE;
+  uint8_t* ws = (uint8_t*)workspace;
+  hipStream_t st = (hipStream_t)stream;
+  uint16_t* AT = (uint16_t*)(ws + L.at_off);
+  uint16_t* BT = (uint16_t*)(ws + L.bt_off);
+  uint16_t* tsU = (uint16_t*)(ws + L.tsu_off);
+  uint16_t* tsT = (uint16_t*)(ws + L.tst_off);
+  float* part = (float*)(ws + L.part_off);
+  int rc = QERL_OK;
+  if (r > 0) {
+    transpose_bf16_kernel<<<dim3((unsigned)grid_for(r * K)), dim3(256), 0, st>>>((const uint16_t*)A, r, K, AT);
+    transpose_bf16_kernel<<<dim3((unsigned)grid_for(N * r)), dim3(256), 0, st>>>((const uint16_t*)B, N, r, BT);
+    if ((rc = launch_status()) != QERL_OK) return rc;
+    // U = dY B and t = x A^T, each as three bf16 terms of (lora_scale / S32) times the product
+    GemmArgs d{};
+    d.x = (const uint16_t*)dy; d.ldx = lddy; d.M = M; d.K = N; d.k_tiles = ceil_div(N, kPackTileK);
+    d.N = r; d.wbf16 = BT; d.n_tiles = (int)ceil_div(r, 32); d.ts = tsU; d.ts_ld = L.ts_ld; d.ext_stages = L.ext_stages;
+    d.r = (int)r; d.lora_scale = lora_scale; d.tensor_scale = tensor_scale;
+    if ((rc = launch_lora_down_gemm(d, st)) != QERL_OK) return rc;
+    d.x = (const uint16_t*)x; d.ldx = ldx; d.K = K; d.k_tiles = ceil_div(K, kPackTileK); d.wbf16 = (const uint16_t*)A; d.ts = tsT;
+    if ((rc = launch_lora_down_gemm(d, st)) != QERL_OK) return rc;
+  }
+  {
+    GemmArgs g{};
+    g.x = (const uint16_t*)dy; g.ldx = lddy; g.M = M; g.K = N; g.k_tiles = ceil_div(N, kPackTileK);
+    g.N = K; g.packed = (const uint8_t*)packed_t; g.n_tiles = (int)ceil_div(K, 32); g.tensor_scale = tensor_scale;
+    g.ts = r > 0 ? tsU : nullptr; g.ts_ld = r > 0 ? L.ts_ld : 0; g.ext_stages = r > 0 ? L.ext_stages : 0;
+    g.B = r > 0 ? AT : nullptr; g.r = (int)r; g.lora_scale = lora_scale;
+    g.y = (uint16_t*)dx; g.ldy = lddx; g.transposed = 1;
+    if ((rc = launch_gemm(g, st)) != QERL_OK) return rc;
+  }
+  if (r > 0) {
+    // the three-term values carry lora_scale / S32; the gradients want lora_scale: one multiplication by S32
+    const dim3 blk(256);
+    lora_grad_partial_kernel<<<dim3((unsigned)ceil_div(K, 256), (unsigned)L.n_chunks), blk, 0, st>>>(
+        tsU, L.ts_ld, (int)r, (const uint16_t*)x, ldx, M, K, L.tokens_per_chunk, part);
+    lora_grad_reduce_kernel<<<dim3((unsigned)grid_for(K * r)), blk, 0, st>>>(part, L.n_chunks, K, (int)r, tensor_scale, 1, dA);
+    lora_grad_partial_kernel<<<dim3((unsigned)ceil_div(N, 256), (unsigned)L.n_chunks), blk, 0, st>>>(
+        tsT, L.ts_ld, (int)r, (const uint16_t*)dy, lddy, M, N, L.tokens_per_chunk, part);
+    lora_grad_reduce_kernel<<<dim3((unsigned)grid_for(N * r)), blk, 0, st>>>(part, L.n_chunks, N, (int)r, tensor_scale, 0, dB);
+    rc = launch_status();
+  }
+  return rc;
+}

@@ -49,7 +49,11 @@ struct WeightRegs {      // one stage = 64 inputs (4 MFMA steps) of NT column ti
   uint32_t sc[NT];       // 4 scale bytes
 };
 
-template <int MT, int NT, int W>
+// TR: the packed operand is in the transposed tile order (nvfp4_prepack_t): the contraction runs over the rows
+// of W, so the eight weights of a lane and MFMA step carry eight different block scales; the scale bytes of a
+// stage (128 per column tile) ride along with the x slab through LDS.  Used by the backward pass
+// (dX = dY W_hat); everything around the dequantisation step is shared with the forward kernel.
+template <int MT, int NT, int W, bool TR = false>
 __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
   constexpr int BM = MT * 32;
   constexpr int kThreads = W * 64;
@@ -58,6 +62,8 @@ __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
   // x slab [2][BM][8 chunks]; chunk c of row r sits at r*8 + (c ^ ((r >> 1) & 7)): rows r, r+1 use
   // different bank halves, so 16 consecutive rows at one column touch 16 distinct 16-byte bank groups.
   extern __shared__ u32x4 xs[];
+  constexpr int kScBytes = W * NT * 128;                   // TR: scale bytes of one stage, all column tiles of the workgroup
+  uint8_t* ssc = reinterpret_cast<uint8_t*>(xs + 2 * kChunks);   // TR: [2][kScBytes] behind the x slabs
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps everything derived from it in SGPRs
@@ -119,8 +125,23 @@ __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
       const uint8_t* base = mem.packed + ((int64_t)tile * a.k_tiles + (s >> 1)) * kPackTileBytes;
       const int plane = (int)(s & 1);
       wr.c[nt] = *reinterpret_cast<const u32x4*>(base + plane * 1024 + lane * 16);
-      wr.sc[nt] = *reinterpret_cast<const uint32_t*>(base + 2048 + n32 * 8 + plane * 4);
+      wr.sc[nt] = 0u;
+      if constexpr (!TR) wr.sc[nt] = *reinterpret_cast<const uint32_t*>(base + 2048 + n32 * 8 + plane * 4);
     }
+  };
+  // TR: thread t < 8 W NT fetches 16 of the 128 scale bytes of column tile t / 8 for stage s
+  const int sc_tl = tid >> 3, sc_part = tid & 7;
+  auto gload_sc = [&](u32x4& r, int64_t s) {
+    r = u32x4{0u, 0u, 0u, 0u};
+    if (tid < W * NT * 8) {
+      int tile = (nb - mem.block_begin) * W * NT + sc_tl;
+      tile = tile < mem.n_tiles ? tile : mem.n_tiles - 1;
+      const uint8_t* base = mem.packed + ((int64_t)tile * a.k_tiles + (s >> 1)) * kPackTileBytes;
+      r = *reinterpret_cast<const u32x4*>(base + 2048 + (int)(s & 1) * 128 + sc_part * 16);
+    }
+  };
+  auto swrite_sc = [&](int buf, const u32x4& r) {
+    if (tid < W * NT * 8) *reinterpret_cast<u32x4*>(ssc + buf * kScBytes + sc_tl * 128 + sc_part * 16) = r;
   };
   auto mma_step = [&](const u32x4* xst, int j, const bf16x8 (&wf)[NT]) {
 #pragma unroll
@@ -167,6 +188,21 @@ __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
     }
   };
 
+  // TR: no pipelining across steps -- each step's weights are dequantised right before its MFMAs, with the
+  // eight scale bytes of the lane's (input block, 8 rows) read from LDS
+  auto compute_tr = [&](int buf, const WeightRegs<NT>& wr) {
+    const u32x4* xst = xs + buf * kChunks;
+    const uint8_t* sst = ssc + buf * kScBytes + wave * NT * 128 + (n32 >> 4) * 64 + 8 * kg;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      bf16x8 wt[NT];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+        wt[nt] = dequant8_t_bf16(wr.c[nt][j], *reinterpret_cast<const u32x2*>(sst + nt * 128 + 16 * j));
+      mma_step(xst, j, wt);
+    }
+  };
+
   // ---- main loop over 64-input stages.  Weights are requested kGemmRing - 1 stages ahead into a ring of
   // registers, x slabs kGemmXAhead stages ahead (shared between workgroups, so usually an L2 hit; they pass through LDS: written a stage before use, one barrier
   // per stage): a stage lasts a few hundred nanoseconds, a memory round trip several times that.  The loop is
@@ -176,21 +212,31 @@ __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
     constexpr int R = kGemmRing, PX = kGemmXAhead;
     WeightRegs<NT> wring[R];
     u32x4 xring[PX][XL];
+    u32x4 scring[PX];
     const int64_t s_last = s_end - 1;
     auto clamp_s = [&](int64_t s) { return s < s_last ? s : s_last; };
 #pragma unroll
-    for (int p = 0; p < PX; ++p) gload_x(xring[p], a.x, a.ldx, a.K, clamp_s(s_begin + p));
+    for (int p = 0; p < PX; ++p) {
+      gload_x(xring[p], a.x, a.ldx, a.K, clamp_s(s_begin + p));
+      if constexpr (TR) gload_sc(scring[p], clamp_s(s_begin + p));
+    }
 #pragma unroll
     for (int d = 0; d < R - 1; ++d) gload_w(wring[d], clamp_s(s_begin + d));
     swrite_x(0, xring[0]);
+    if constexpr (TR) swrite_sc(0, scring[0]);
+    if constexpr (!TR) {
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) wf[nt] = dequant8_bf16(wring[0].c[nt][0], e4m3_byte_f32(wring[0].sc[nt], 0));
+      for (int nt = 0; nt < NT; ++nt) wf[nt] = dequant8_bf16(wring[0].c[nt][0], e4m3_byte_f32(wring[0].sc[nt], 0));
+    }
     __syncthreads();
     auto stage = [&](int64_t s, int u) {
       gload_x(xring[u % PX], a.x, a.ldx, a.K, clamp_s(s + PX));
+      if constexpr (TR) gload_sc(scring[u % PX], clamp_s(s + PX));
       gload_w(wring[(u + R - 1) % R], clamp_s(s + R - 1));
-      compute(u & 1, wring[u], wring[(u + 1) % R]);
+      if constexpr (TR) compute_tr(u & 1, wring[u]);
+      else compute(u & 1, wring[u], wring[(u + 1) % R]);
       swrite_x((u + 1) & 1, xring[(u + 1) % PX]);
+      if constexpr (TR) swrite_sc((u + 1) & 1, scring[(u + 1) % PX]);
       __syncthreads();
     };
     int64_t s = s_begin;
@@ -431,9 +477,9 @@ static const GemmConfig kConfigs[] = {
 };
 static int g_force_cfg = -1;
 
-template <int MT, int NT, int W>
+template <int MT, int NT, int W, bool TR = false>
 static int launch_cfg(const GemmArgs& a, hipStream_t st) {
-  constexpr size_t lds = 2 * (size_t)MT * 32 * 8 * sizeof(u32x4);
+  constexpr size_t lds = 2 * (size_t)MT * 32 * 8 * sizeof(u32x4) + (TR ? 2 * (size_t)W * NT * 128 : 0);
   GemmArgs b = a;
   b.n_blocks = 0;
   for (int i = 0; i < b.m_n; ++i) {
@@ -442,7 +488,7 @@ static int launch_cfg(const GemmArgs& a, hipStream_t st) {
   }
   b.nblk_per_xcd = (int)ceil_div(b.n_blocks, 8);
   const int64_t m_blocks = ceil_div(a.M, MT * 32);
-  gemm32_kernel<MT, NT, W><<<dim3((unsigned)(8 * b.nblk_per_xcd * m_blocks)), W * 64, lds, st>>>(b);
+  gemm32_kernel<MT, NT, W, TR><<<dim3((unsigned)(8 * b.nblk_per_xcd * m_blocks)), W * 64, lds, st>>>(b);
   return launch_status();
 }
 
@@ -475,6 +521,7 @@ int launch_gemm(const GemmArgs& a0, hipStream_t st) {
     const float score = useful * (rounds > 1 ? g.quality_rounds : g.quality);
     if (score > best_score) { best_score = score; best = c; }
   }
+  if (a.transposed) return launch_cfg<4, 2, 8, true>(a, st);   // the backward pass: one tile shape
   if (g_force_cfg >= 0) best = g_force_cfg;
   const GemmArgs& b = a;
 #define QERL_GEMM_CASE(idx, mt, nt, w) \

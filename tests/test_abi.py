@@ -164,6 +164,30 @@ def test_host_side_validation_of_the_fused_entry_points(lib):
     assert need >= qerl.nvfp4_lora_linear_workspace_bytes(40, 16, 64, 0) + 40 * 64 * 2
     assert sw(fake, fake, 40, 64, 64, 64, fake, fake, 16, None, None, 0, 0.0, fake, 16, fake, need - 256, None) == -4
 
+    bw = lib.nvfp4_lora_linear_backward
+    okb = dict(x=fake, dy=fake, M=4, K=64, N=32, ldx=64, lddy=32, pt=fake, ts=fake, A=fake, B=fake, r=8, s=1.0,
+               dx=fake, lddx=64, dA=fake, dB=fake, ws=fake, wsb=big)
+
+    def callb(**kw):
+        a = dict(okb, **kw)
+        return bw(a["x"], a["dy"], a["M"], a["K"], a["N"], a["ldx"], a["lddy"], a["pt"], a["ts"], a["A"], a["B"], a["r"],
+                  a["s"], a["dx"], a["lddx"], a["dA"], a["dB"], a["ws"], a["wsb"], None)
+    assert callb(M=0) == 0
+    assert callb(K=40, ldx=40, lddx=40) == -2            # K % 16
+    assert callb(N=30, lddy=32) == -2                    # N % 8
+    assert callb(r=72) == -2 and callb(r=12) == -2       # rank above 64 / not a multiple of 8
+    assert callb(lddx=32) == -2 and callb(lddy=16) == -2
+    assert callb(dy=None) == -1 and callb(dx=None) == -1 and callb(pt=None) == -1
+    assert callb(dA=None) == -1 and callb(x=None) == -1
+    assert callb(r=0, x=None, A=None, B=None, dA=None, dB=None, ws=None) == -4   # r = 0 needs no x / A / B, but a workspace
+    assert callb(dy=fake + 2) == -3 and callb(lddy=36) == -3 and callb(A=fake + 8) == -3
+    assert callb(wsb=64) == -4 and callb(ws=fake + 16) == -4
+    assert lib.nvfp4_prepack_t_bytes(33, 130) == 5 * 1 * 2304 and lib.nvfp4_prepack_t_bytes(0, 64) == 0
+    assert lib.nvfp4_prepack_t(fake, fake, 4, 24, fake, None) == -2
+    assert lib.nvfp4_prepack_t(fake, fake, 4, 32, fake + 4, None) == -3
+    assert lib.nvfp4_prepack_t(None, fake, 4, 32, fake, None) == -1
+    assert lib.nvfp4_lora_linear_backward_workspace_bytes(2048, 13824, 5120, 64) < 64 << 20
+
     nd = lib.aqn_rmsnorm_lora_down
     A = (ctypes.c_void_p * 5)(*([fake] * 5)); T = (ctypes.c_void_p * 5)(*([fake] * 5))
     R = (ctypes.c_int64 * 5)(32, 32, 32, 32, 32)

@@ -69,47 +69,77 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __r
 
 // ---- dA, dB: partial[chunk][c][j] = sum over the chunk's tokens of P[m, j] * Q[m, c] ------------------------
 // P [M, r] arrives as the three bf16 terms the LoRA down-projection kernel writes ([M, ts_ld]: hi | mid | lo,
-// their sum exact to 2^-24); Q is x or dY (bf16, row-major).  One thread per column c, all r sums in registers.
+// their sum exact to 2^-24) and is summed into fp32 first; Q is x or dY (bf16, row-major).
 constexpr int kGradRanks = 64;       // most ranks
-constexpr int kGradTokens = 32;      // tokens of P staged in LDS at a time
 constexpr int kGradChunksMax = 8;    // token chunks (workgroups along M) whose partial sums are added in order
-__global__ __launch_bounds__(256) void lora_grad_partial_kernel(const uint16_t* __restrict__ ts, int64_t ts_ld, int r,
-                                                                const uint16_t* __restrict__ Q, int64_t ldq, int64_t M, int64_t C,
-                                                                int64_t tokens_per_chunk, float* __restrict__ partial) {
-  __shared__ float P[kGradTokens][kGradRanks];
-  const int tid = threadIdx.x;
-  const int64_t c = (int64_t)blockIdx.x * 256 + tid;
-  const int64_t m_lo = (int64_t)blockIdx.y * tokens_per_chunk;
-  const int64_t m_hi = m_lo + tokens_per_chunk < M ? m_lo + tokens_per_chunk : M;
-  float acc[kGradRanks];
-#pragma unroll
-  for (int j = 0; j < kGradRanks; ++j) acc[j] = 0.f;
-  for (int64_t m0 = m_lo; m0 < m_hi; m0 += kGradTokens) {
-    __syncthreads();                      // the previous tile has been read
-    for (int e = tid; e < kGradTokens * kGradRanks; e += 256) {
-      const int mm = e / kGradRanks, j = e - mm * kGradRanks;
-      float v = 0.f;
-      if (m0 + mm < m_hi && j < r) {
-        const uint16_t* row = ts + (m0 + mm) * ts_ld;
-        v = (bf16_bits_to_f32(row[j]) + bf16_bits_to_f32(row[r + j])) + bf16_bits_to_f32(row[2 * r + j]);
-      }
-      P[mm][j] = v;
+// P[m][j] = hi + mid + lo of the three-term value (0 for j >= r), fp32 [M][kGradRanks]
+__global__ __launch_bounds__(256) void lora_grad_p_kernel(const uint16_t* __restrict__ ts, int64_t ts_ld, int r, int64_t M,
+                                                          float* __restrict__ P) {
+  const int64_t total = M * kGradRanks;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t m = i / kGradRanks;
+    const int j = (int)(i - m * kGradRanks);
+    float v = 0.f;
+    if (j < r) {
+      const uint16_t* row = ts + m * ts_ld;
+      v = (bf16_bits_to_f32(row[j]) + bf16_bits_to_f32(row[r + j])) + bf16_bits_to_f32(row[2 * r + j]);
     }
-    __syncthreads();
-    if (c < C) {
-      for (int mm = 0; mm < kGradTokens; ++mm) {
-        if (m0 + mm >= m_hi) break;       // uniform
-        const float q = bf16_bits_to_f32(Q[(m0 + mm) * ldq + c]);
+    P[i] = v;
+  }
+}
+
+// A workgroup owns 64 columns of Q, half of the ranks (blockIdx.z) and one token chunk (blockIdx.y); its four
+// waves take a quarter of the chunk's tokens each -- lane = column, the sums in registers -- and are added through
+// LDS in wave order.  P[m][:] is the same for every lane: its address is uniform, so the values arrive by scalar
+// loads and each product is one multiply-add with a scalar operand; with several workgroups per CU the latency
+// of those loads (one row per token) is covered by other waves.
+constexpr int kGradHalf = kGradRanks / 2;
+__global__ __launch_bounds__(256) void lora_grad_partial_kernel(const float* __restrict__ P, const uint16_t* __restrict__ Q, int64_t ldq,
+                                                                int64_t M, int64_t C, int64_t tokens_per_chunk, float* __restrict__ partial) {
+  __shared__ float red[4][kGradHalf][64];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t c = (int64_t)blockIdx.x * 64 + lane;
+  const int64_t cc = c < C ? c : C - 1;   // spare lanes of the last workgroup repeat a column and store nothing
+  const int j0 = (int)blockIdx.z * kGradHalf;
+  const int64_t c_lo = (int64_t)blockIdx.y * tokens_per_chunk;
+  const int64_t c_hi = c_lo + tokens_per_chunk < M ? c_lo + tokens_per_chunk : M;
+  const int64_t per_wave = (c_hi - c_lo + 3) / 4;
+  const int64_t m_lo = c_lo + wave * per_wave;
+  const int64_t m_hi = m_lo + per_wave < c_hi ? m_lo + per_wave : c_hi;
+  float acc[kGradHalf];
 #pragma unroll
-        for (int j = 0; j < kGradRanks; ++j) acc[j] += P[mm][j] * q;
+  for (int j = 0; j < kGradHalf; ++j) acc[j] = 0.f;
+  for (int64_t m = m_lo; m < m_hi; m += 8) {
+    float q[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const int64_t mm = m + t < m_hi ? m + t : m_hi - 1;
+      q[t] = bf16_bits_to_f32(Q[mm * ldq + cc]);
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      if (m + t < m_hi) {                 // uniform
+        const float* p = P + (m + t) * kGradRanks + j0;
+#pragma unroll
+        for (int j = 0; j < kGradHalf; ++j) acc[j] += p[j] * q[t];
       }
     }
   }
-  if (c < C) {
-    float* dst = partial + ((int64_t)blockIdx.y * C + c) * kGradRanks;
 #pragma unroll
-    for (int j4 = 0; j4 < kGradRanks / 4; ++j4)
-      *reinterpret_cast<f32x4*>(dst + 4 * j4) = f32x4{acc[4 * j4], acc[4 * j4 + 1], acc[4 * j4 + 2], acc[4 * j4 + 3]};
+  for (int j = 0; j < kGradHalf; ++j) red[wave][j][lane] = acc[j];
+  __syncthreads();
+  // wave w adds ranks 8 w .. 8 w + 7 of the four partial sums, in wave order
+  if (c < C) {
+    float* dst = partial + ((int64_t)blockIdx.y * C + c) * kGradRanks + j0 + 8 * wave;
+    float o[8];
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj) {
+      const int j = 8 * wave + jj;
+      o[jj] = ((red[0][j][lane] + red[1][j][lane]) + red[2][j][lane]) + red[3][j][lane];
+    }
+    *reinterpret_cast<f32x4*>(dst) = f32x4{o[0], o[1], o[2], o[3]};
+    *reinterpret_cast<f32x4*>(dst + 4) = f32x4{o[4], o[5], o[6], o[7]};
   }
 }
 
@@ -129,7 +159,7 @@ __global__ __launch_bounds__(256) void lora_grad_reduce_kernel(const float* __re
 }
 
 static size_t al256(size_t v) { return (v + 255) & ~(size_t)255; }
-struct BackwardLayout { size_t at_off, bt_off, tsu_off, tst_off, part_off, total; int64_t ts_ld; int ext_stages; int n_chunks; int64_t tokens_per_chunk; };
+struct BackwardLayout { size_t at_off, bt_off, tsu_off, tst_off, p_off, part_off, total; int64_t ts_ld; int ext_stages; int n_chunks; int64_t tokens_per_chunk; };
 static BackwardLayout backward_layout(int64_t M, int64_t N, int64_t K, int64_t r) {
   BackwardLayout L{};
   const size_t m = (size_t)(M > 0 ? M : 1), n = (size_t)(N > 0 ? N : 1), k = (size_t)(K > 0 ? K : 1), rr = (size_t)(r > 0 ? r : 0);
@@ -143,7 +173,8 @@ static BackwardLayout backward_layout(int64_t M, int64_t N, int64_t K, int64_t r
   L.bt_off = L.at_off + al256(k * rr * 2);
   L.tsu_off = L.bt_off + al256(n * rr * 2);
   L.tst_off = L.tsu_off + al256(m * (size_t)L.ts_ld * 2);
-  L.part_off = L.tst_off + al256(m * (size_t)L.ts_ld * 2);
+  L.p_off = L.tst_off + al256(m * (size_t)L.ts_ld * 2);
+  L.part_off = L.p_off + (rr ? al256(m * kGradRanks * sizeof(float)) : 0);
   L.total = L.part_off + (rr ? al256((size_t)chunks * (n > k ? n : k) * kGradRanks * sizeof(float)) : 0);
   if (L.total == 0) L.total = 256;
   return L;
@@ -223,11 +254,14 @@ extern "C" int nvfp4_lora_linear_backward(const void* x, const void* dy, int64_t
   if (r > 0) {
     // the three-term values carry lora_scale / S32; the gradients want lora_scale: one multiplication by S32
     const dim3 blk(256);
-    lora_grad_partial_kernel<<<dim3((unsigned)ceil_div(K, 256), (unsigned)L.n_chunks), blk, 0, st>>>(
-        tsU, L.ts_ld, (int)r, (const uint16_t*)x, ldx, M, K, L.tokens_per_chunk, part);
+    float* P = (float*)(ws + L.p_off);
+    lora_grad_p_kernel<<<dim3((unsigned)grid_for(M * kGradRanks)), blk, 0, st>>>(tsU, L.ts_ld, (int)r, M, P);
+    lora_grad_partial_kernel<<<dim3((unsigned)ceil_div(K, 64), (unsigned)L.n_chunks, r > kGradHalf ? 2u : 1u), blk, 0, st>>>(
+        P, (const uint16_t*)x, ldx, M, K, L.tokens_per_chunk, part);
     lora_grad_reduce_kernel<<<dim3((unsigned)grid_for(K * r)), blk, 0, st>>>(part, L.n_chunks, K, (int)r, tensor_scale, 1, dA);
-    lora_grad_partial_kernel<<<dim3((unsigned)ceil_div(N, 256), (unsigned)L.n_chunks), blk, 0, st>>>(
-        tsT, L.ts_ld, (int)r, (const uint16_t*)dy, lddy, M, N, L.tokens_per_chunk, part);
+    lora_grad_p_kernel<<<dim3((unsigned)grid_for(M * kGradRanks)), blk, 0, st>>>(tsT, L.ts_ld, (int)r, M, P);
+    lora_grad_partial_kernel<<<dim3((unsigned)ceil_div(N, 64), (unsigned)L.n_chunks, r > kGradHalf ? 2u : 1u), blk, 0, st>>>(
+        P, (const uint16_t*)dy, lddy, M, N, L.tokens_per_chunk, part);
     lora_grad_reduce_kernel<<<dim3((unsigned)grid_for(N * r)), blk, 0, st>>>(part, L.n_chunks, N, (int)r, tensor_scale, 0, dB);
     rc = launch_status();
   }

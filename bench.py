@@ -255,6 +255,61 @@ def cpu_baseline(config_no: int, M: int, budget_s: float = 20.0):
                       + ", ".join(names) + f"; {t_total:.1f} s"}
 
 
+def backward_bench(args):
+    """--backward: the backward pass (dX through the frozen weights, dA, dB) of every linear of a few layers at
+    the configuration's prefill size; one JSON line in the same format, TFLOP/s on the dX flops."""
+    cfg = qs.CONFIGS[args.config]
+    M = args.M or cfg["M"][0]
+    n_layers = args.layers or 2
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(qs.seed_for(args.config, 1))
+    r = cfg["r"]
+    lib = qerl.load_library()
+    lin, need = [], 0
+    for _ in range(n_layers):
+        for shp in cfg["linears"]:
+            W = (torch.randn((shp.N, shp.K), generator=gen, device="cuda", dtype=torch.float32) * 0.02).to(torch.bfloat16)
+            codes, scales, ts = qerl.nvfp4_quantize(W)
+            pt = qerl.nvfp4_prepack_t(codes, scales, ts)
+            del W, codes, scales
+            A = (torch.randn((r, shp.K), generator=gen, device="cuda") / r).to(torch.bfloat16)
+            B = (torch.randn((shp.N, r), generator=gen, device="cuda") * 0.01).to(torch.bfloat16)
+            lin.append((shp, pt, A, B))
+            need = max(need, lib.nvfp4_lora_linear_backward_workspace_bytes(M, shp.N, shp.K, r))
+    xs = {k: torch.randn((M, k), generator=gen, device="cuda").to(torch.bfloat16) for k in {s.K for s, *_ in lin}}
+    dys = {n: torch.randn((M, n), generator=gen, device="cuda").to(torch.bfloat16) for n in {s.N for s, *_ in lin}}
+    ws = torch.empty((need + 256,), dtype=torch.uint8, device="cuda")
+    scale = cfg["alpha"] / r
+
+    def step():
+        for shp, pt, A, B in lin:
+            qerl.nvfp4_lora_linear_backward(xs[shp.K], dys[shp.N], pt, A, B, scale, workspace=ws)
+    for _ in range(args.warmup):
+        step()
+    ms = timed(step, args.steps)
+    flops = sum(2 * M * s.N * s.K for s, *_ in lin)
+    tflops = flops / (ms * 1e-3) / 1e12
+    # the dominant kernel: dX of the widest linear (gate: 13824 rows contracted), timed alone with its LoRA launches
+    shp, pt, A, B = max(lin, key=lambda e: e[0].N * e[0].K)
+    one = lambda: qerl.nvfp4_lora_linear_backward(None, dys[shp.N], pt, None, None, 0.0, workspace=ws)
+    one()
+    us = timed(one, max(3, args.steps)) * 1e3
+    fl = 2 * M * shp.N * shp.K
+    print(json.dumps({
+        "metric": "NVFP4+LoRA linear backward: TFLOP/s (dX flops 2*M*N*K; dA, dB and LoRA flops not counted)",
+        "value": round(tflops, 1), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 x fp4(e2m1)*fp8(e4m3) -> fp32 accumulate", "data": "synthetic",
+        "config": {"workload": f"config {args.config}: backward of {cfg['model']}-shaped decoder linears, {n_layers} layers, "
+                               f"M={M}, LoRA r={r} alpha={cfg['alpha']:g}; dX bf16, dA and dB fp32; eager launches"},
+        "roofline": {"bound": "mfma", "achieved": round(fl / (us * 1e-6) / 1e12, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(fl / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                     "kernel": "gemm32_kernel<4, 2, 8, true>", "algorithmic_flops_per_launch": fl,
+                     "shape": {"name": shp.name, "N": shp.N, "K": shp.K, "M": M}, "us_per_launch": round(us, 2),
+                     "note": "dX alone (no adapter): one launch"},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -263,6 +318,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="BASELINE config number (1-based)")
     ap.add_argument("--M", type=int, default=None)
     ap.add_argument("--layers", type=int, default=None)
+    ap.add_argument("--backward", action="store_true",
+                    help="time the backward pass (dX, dA, dB) of the configuration's linears at its prefill size instead of the forward step")
     ap.add_argument("--swiglu", action="store_true",
                     help="the down projection reads SiLU(gate) (.) up from the gate/up outputs (fused into its launch at M <= 16) instead of a resident input")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -286,6 +343,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes_read": 256 << 20, "bytes_written": 256 << 20, "launches": 5}))
+        return
+    if args.backward:
+        backward_bench(args)
         return
     cfg = qs.CONFIGS[args.config]
     M = args.M or cfg["M"][0]

@@ -209,6 +209,7 @@ extern "C" int nvfp4_lora_linear(const void* x, int64_t M, int64_t K, int64_t ld
 
 namespace qerl {
 static bool g_use_stream = true;
+static int64_t g_mid_producer_bytes = 24 << 20;   // 17..128 tokens: LoRA down-projections run inside the main launch when it streams at least this many packed bytes (long enough to hide them)
 
 // One streaming launch for a group of packed linears sharing x (M <= 16; every r in {0} or 8..64 step 8).
 static int stream_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const qerl_linear_desc* d, int n,
@@ -288,16 +289,37 @@ static int mid_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const
     }
   }
   uint32_t* partial = (uint32_t*)(ws + L.partial_off);
+  g.partial = (float*)partial;
+  const int prc = plan_mid(g, few ? mid_partial_bytes(M, n_sum) : 0);
+  if (prc != QERL_OK) return prc;
   if (dn.g_n > 0) {
     dn.g_tile0[dn.g_n] = tiles;
     dn.tpart = few ? partial + mid_partial_bytes(M, n_sum) / sizeof(uint32_t) : nullptr;
     dn.counters = (uint32_t*)ws + L.n_main_ctr;
-    const int rc = launch_lora_down_gemm(dn, st);
-    if (rc != QERL_OK) return rc;
+    int64_t packed_bytes = 0;
+    for (int i = 0; i < n; ++i) packed_bytes += (int64_t)g.mem[i].n_tiles * g.k_tiles * kPackTileBytes;
+    // measured on 7B shapes: above 64 tokens it always pays (7.5 against 8.2 ms per step at 128); below, only where the
+    // main launch runs long enough to hide producers of two or four waves (gate + up, down: 1-2 % of the step)
+    if (few && (M > 64 || packed_bytes >= g_mid_producer_bytes)) {
+      // the down-projections run as the first workgroups of the main launch: token blocks x rank tiles x K-parts
+      // (parts as the stand-alone launch would choose them: a few dozen workgroups, at least 512 columns each)
+      const int64_t base_wgs = ceil_div(M, 32) * tiles;
+      int64_t P = base_wgs < 32 ? 64 / base_wgs : 1;
+      const int64_t p_max = ceil_div(K, 512);
+      P = P < p_max ? P : p_max;
+      P = P > 8 ? 8 : (P < 1 ? 1 : P);
+      g.p_tbs = (int)ceil_div(M, 32); g.p_tiles = tiles; g.p_parts = (int)P;
+      g.n_prod = (int)(ceil_div(base_wgs * P, 8) * 8);
+      g.ready = (uint32_t*)ws + L.n_main_ctr + L.n_down_ctr;      // the hand-over words (zero between calls)
+      g.done = g.ready + 2;
+      g.n_consumers = g.n_blocks * g.m_chunks * g.S;
+      dn.ready = g.ready;
+      g.dn = dn;
+    } else {
+      const int rc = launch_lora_down_gemm(dn, st);
+      if (rc != QERL_OK) return rc;
+    }
   }
-  g.partial = (float*)partial;
-  const int prc = plan_mid(g, few ? mid_partial_bytes(M, n_sum) : 0);
-  if (prc != QERL_OK) return prc;
   return launch_mid(g, st);
 }
 // More tokens than mid_kernel takes: one launch of the LoRA down-projection for all adapters of the group, then
@@ -336,6 +358,7 @@ static int gemm_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, cons
 
 #ifdef QERL_TUNING_HOOKS   // built only for tuning sessions: they change process-wide state
 extern "C" QERL_API void qerl_debug_use_stream(int on) { qerl::g_use_stream = on != 0; }
+extern "C" QERL_API void qerl_debug_mid_producer_bytes(long long b) { qerl::g_mid_producer_bytes = b; }
 #endif  // QERL_TUNING_HOOKS
 
 static int packed_single(const void* x, int64_t M, int64_t K, int64_t ldx, const void* packed,

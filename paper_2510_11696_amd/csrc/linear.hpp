@@ -94,6 +94,7 @@ struct GemmArgs {
   int n_tiles; int n_blocks; int nblk_per_xcd;
   int m_n; GemmMember m[kMaxGroup];                                         // the main launch's members (m_n == 0: one, from the fields above)
   int transposed;                                                           // packed is in nvfp4_prepack_t's order: K counts rows of W, N its columns
+  uint32_t* ready;                                                          // LoRA down-projection inside another kernel's launch: workgroups that have written ts count themselves here (else null)
   uint32_t* tpart; uint32_t* counters;                                      // LoRA down-projection over several K-parts: partial sums, arrival counts (zero between calls); or null
   // LoRA down-projection of a group of adapters that read the same x (g_n > 0): grid.y runs over the 32-row
   // tiles of all adapters; member i owns tiles [g_tile0[i], g_tile0[i+1]) and has its own A, ts and scales
@@ -122,6 +123,11 @@ struct MidArgs {
   int n_members; MidMember mem[kMaxGroup];                                  // unused entries: block_begin = INT_MAX
   float* partial;                                                           // K-splits' partial outputs when S > 1
   int n_blocks; int m_chunks; int S; int kt_per_split; int MT; int W;
+  // LoRA down-projections inside the launch (n_prod > 0): the first n_prod workgroups (a multiple of 8) compute ts
+  // as lora_down_block does -- token block x rank tile x K-part = p_tbs x p_tiles x p_parts of them, the rest idle --
+  // and the workgroups that carry the LoRA columns wait until `ready` has counted p_tbs * p_tiles of them; every
+  // consumer workgroup counts itself in `done` when it leaves, the last one zeroes both words for the next call.
+  GemmArgs dn; int n_prod; int p_tbs; int p_tiles; int p_parts; uint32_t* ready; uint32_t* done; int n_consumers;
 };
 extern int g_mid_max_tokens;
 int plan_mid(MidArgs& a, size_t partial_cap_bytes);

@@ -26,6 +26,7 @@
 //
 // Operand layouts and the packed tile format are described in linear_decode.hip.
 #include "linear.hpp"
+#include "lora_down.hpp"
 
 namespace qerl {
 
@@ -296,172 +297,10 @@ main_done:
 // A skinny GEMM (r <= 64 output columns per block) that is bound by reading x once.  One workgroup owns
 // 32 tokens; its eight waves split K in interleaved 64-column chunks, read both operands straight from
 // global memory in MFMA operand layout (double buffered in registers), and are summed through LDS.
-constexpr int kDownMaxParts = 8;   // K-parts of the LoRA down-projection when there are few token blocks
-
 template <int NT>
 __global__ __launch_bounds__(512) void lora_down32_kernel(const GemmArgs a) {
-  constexpr int kWaves = 8;
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps everything derived from it in SGPRs
-  const int n32 = lane & 31, kg = lane >> 5;
-  const int64_t m0 = (int64_t)blockIdx.x * 32;
-  // one adapter, or (NT == 1) the adapter that owns tile blockIdx.y of the group
-  int nt0 = blockIdx.y * NT;
-  const uint16_t* Aw = a.wbf16;
-  uint16_t* ts = const_cast<uint16_t*>(a.ts);
-  int64_t ts_ld = a.ts_ld, rN = a.N;
-  float lora_scale = a.lora_scale;
-  const float* tensor_scale = a.tensor_scale;
-  bool first_tile = blockIdx.y == 0;
-  if (a.g_n > 0) {
-    int mi = 0;
-#pragma unroll
-    for (int i = 1; i < kMaxGroup; ++i) mi = (i < a.g_n && (int)blockIdx.y >= a.g_tile0[i]) ? i : mi;
-#pragma unroll
-    for (int i = 0; i < kMaxGroup; ++i)
-      if (mi == i) {
-        Aw = a.g_A[i]; ts = const_cast<uint16_t*>(a.g_ts[i]); ts_ld = a.g_ts_ld[i]; rN = a.g_r[i];
-        lora_scale = a.g_lora_scale[i]; tensor_scale = a.g_tensor_scale[i];
-        nt0 = (int)blockIdx.y - a.g_tile0[i];
-      }
-    first_tile = nt0 == 0;
-  }
-  int64_t mrow = m0 + n32;
-  mrow = mrow < a.M ? mrow : a.M - 1;
-  const uint16_t* xrow = a.x + mrow * a.ldx + 8 * kg;
-
-  // K-part of this workgroup (gridDim.z parts, whole 64-column chunks each)
-  const int P = (int)gridDim.z;
-  const int64_t part_cols = ceil_div_dev(ceil_div_dev(a.K, 64), P) * 64;
-  const int64_t k_lo = (int64_t)blockIdx.z * part_cols;
-  const int64_t k_hi = k_lo + part_cols < a.K ? k_lo + part_cols : a.K;
-
-  struct Chunk { u32x4 x[4]; u32x4 w[NT][4]; };   // 64 columns = 4 MFMA steps
-  auto load = [&](Chunk& c, int64_t kb) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int64_t k = kb + 16 * j + 8 * kg;
-      c.x[j] = u32x4{0u, 0u, 0u, 0u};
-      if (k < k_hi) c.x[j] = *reinterpret_cast<const u32x4*>(xrow + kb + 16 * j);
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        int64_t row = (int64_t)(nt0 + nt) * 32 + n32;
-        row = row < rN ? row : rN - 1;
-        c.w[nt][j] = u32x4{0u, 0u, 0u, 0u};
-        if (k < k_hi) c.w[nt][j] = *reinterpret_cast<const u32x4*>(Aw + row * a.K + k);
-      }
-    }
-  };
-  f32x16 acc[NT];
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) acc[nt][i] = 0.f;
-  auto mma = [&](const Chunk& c) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, c.x[j]),
-                                                          __builtin_bit_cast(bf16x8, c.w[nt][j]), acc[nt], 0, 0, 0);
-  };
-  Chunk c0, c1;
-  const int64_t step = (int64_t)kWaves * 64;
-  int64_t kb = k_lo + (int64_t)wave * 64;
-  if (kb < k_hi) load(c0, kb);
-  while (kb < k_hi) {
-    const bool has1 = kb + step < k_hi;
-    if (has1) load(c1, kb + step);
-    mma(c0);
-    if (!has1) break;
-    const bool has2 = kb + 2 * step < k_hi;
-    if (has2) load(c0, kb + 2 * step);
-    mma(c1);
-    kb += 2 * step;
-    if (!has2) break;
-  }
-
-  __shared__ float red[kWaves - 1][NT * 16][64];
-  if (wave > 0) {
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) red[wave - 1][nt * 16 + i][lane] = acc[nt][i];
-  }
-  __syncthreads();
-  if (wave != 0) return;
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-#pragma unroll
-      for (int w = 0; w < kWaves - 1; ++w) acc[nt][i] += red[w][nt * 16 + i][lane];
-    }
-  if (P > 1) {
-    // Several K-parts: every part leaves its sums in the workspace (written through to memory before its
-    // arrival is counted); the workgroup that arrives last adds all parts in part order and goes on.
-    const int slot = blockIdx.x * gridDim.y + blockIdx.y;
-    const int64_t part_stride = (int64_t)gridDim.x * gridDim.y * (NT * 16 * 64);
-    uint32_t* mine = a.tpart + (int64_t)blockIdx.z * part_stride + (int64_t)slot * (NT * 16 * 64) + lane;
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i)
-        __hip_atomic_store(mine + (nt * 16 + i) * 64, __float_as_uint(acc[nt][i]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-    uint32_t old = 0;
-    if (lane == 0) old = __hip_atomic_fetch_add(a.counters + slot, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    old = __builtin_amdgcn_readfirstlane(old);
-    if (old != (uint32_t)(P - 1)) return;
-    const uint32_t* all = a.tpart + (int64_t)slot * (NT * 16 * 64) + lane;
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      uint32_t v[kDownMaxParts][16];        // one tile's values of all parts requested together
-#pragma unroll
-      for (int z = 0; z < kDownMaxParts; ++z)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          v[z][i] = 0u;
-          if (z < P) v[z][i] = __hip_atomic_load(all + (int64_t)z * part_stride + (nt * 16 + i) * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        float sum = 0.f;
-#pragma unroll
-        for (int z = 0; z < kDownMaxParts; ++z) sum += __uint_as_float(v[z][i]);
-        acc[nt][i] = sum;
-      }
-    }
-    if (lane == 0) __hip_atomic_store(a.counters + slot, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
-  }
-  const float t_mult = lora_scale / *tensor_scale;   // undone by the final * S32 of the main launch
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    const int64_t n = (int64_t)(nt0 + nt) * 32 + n32;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float sum = acc[nt][i];
-      const int64_t m = m0 + 8 * (i >> 2) + 4 * kg + (i & 3);
-      if (m < a.M && n < rN) {
-        const float v = sum * t_mult;
-        const uint32_t h = f32_to_bf16_bits(v);
-        const float r1 = v - bf16_bits_to_f32(h);
-        const uint32_t md = f32_to_bf16_bits(r1);
-        const uint32_t l = f32_to_bf16_bits(r1 - bf16_bits_to_f32(md));
-        uint16_t* row = ts + m * ts_ld;
-        row[n] = (uint16_t)h;
-        row[rN + n] = (uint16_t)md;
-        row[2 * rN + n] = (uint16_t)l;
-      }
-    }
-  }
-  if (first_tile) {   // zero the padding columns [3 r, ts_ld)
-    const int pad = (int)(ts_ld - 3 * rN);
-    for (int idx = lane; idx < 32 * pad; idx += 64) {
-      const int64_t m = m0 + idx / pad;
-      if (m < a.M) ts[m * ts_ld + 3 * rN + idx % pad] = 0;
-    }
-  }
+  __shared__ float red[7 * NT * 16 * 64];
+  lora_down_block<NT, 8>(a, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z, (int)gridDim.z, (int)gridDim.x, (int)gridDim.y, red);
 }
 
 // ---- host ------------------------------------------------------------------------------------------

@@ -26,10 +26,12 @@
 //
 // Operand layouts and the packed tile format are described in linear_decode.hip.
 #include "linear.hpp"
+#include "lora_down.hpp"
 
 namespace qerl {
 
 constexpr int kRing = 8;      // weight stages per wave: one in use, seven requested
+constexpr uint32_t kMidSpinLimit = 1u << 16;   // polls (of ~0.5 us) a consumer spends on the producers of its launch before it gives up
 
 struct MidTile { u32x4 c0, c1; u32x2 sc; };   // one wave's share of a packed tile: 2 x 4 steps x 8 codes, 8 scale bytes
 
@@ -49,8 +51,18 @@ __global__ __launch_bounds__(W * 64) void mid_kernel(const MidArgs a) {
   const int n32 = lane & 31, kg = lane >> 5;
   // Workgroup ids go round-robin to the 8 XCDs: the splits and token blocks of one row-tile group get ids
   // that are equal mod 8, i.e. they share an L2.
+  if ((int)blockIdx.x < a.n_prod) {
+    // ---- a LoRA producer: one (token block, rank tile, K-part) of the down-projections; dispatched before
+    // every consumer, waits for nothing but its own loads
+    const int id = (int)blockIdx.x;
+    if (id >= a.p_tbs * a.p_tiles * a.p_parts) return;
+    const int bx = id % a.p_tbs, by = (id / a.p_tbs) % a.p_tiles, bz = id / (a.p_tbs * a.p_tiles);
+    lora_down_block<1, W>(a.dn, bx, by, bz, a.p_parts, a.p_tbs, a.p_tiles, reinterpret_cast<float*>(xs));
+    return;
+  }
+  const int bid = (int)blockIdx.x - a.n_prod;
   const int inner_n = a.m_chunks * a.S;
-  const int xcd = blockIdx.x & 7, rest = blockIdx.x >> 3;
+  const int xcd = bid & 7, rest = bid >> 3;
   const int inner = rest % inner_n;
   const int nb = (rest / inner_n) * 8 + xcd;
   if (nb >= a.n_blocks) return;                    // padding of the last group of eight (uniform)
@@ -185,6 +197,16 @@ main_done:
 
   // ---- LoRA up-projection: 3r extra columns [hi | mid | lo] . [B ; B ; B]^T.  ts already carries the
   // factor lora_scale / S32, so one multiplication by S32 at the end scales both branches.
+  bool poisoned = false;
+  if (split == 0 && mem.ext_stages > 0 && a.n_prod > 0) {
+    // ts comes from the producers of this launch: wait (bounded) until all of them have published it
+    uint32_t spins = 0;
+    while (__hip_atomic_load(a.ready, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (uint32_t)(a.p_tbs * a.p_tiles)) {
+      if (++spins > kMidSpinLimit) { poisoned = true; break; }   // never reached unless a producer died: make it visible
+      __builtin_amdgcn_s_sleep(32);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  }
   if (split == 0) {
     for (int e = 0; e < mem.ext_stages; ++e) {
       gload_x(xr[0], mem.ts, mem.ts_ld, mem.ts_ld, e);
@@ -202,7 +224,15 @@ main_done:
       __syncthreads();
     }
   }
-  const float S32 = *mem.tensor_scale;
+  if (a.n_prod > 0 && tid == 0) {
+    // the last consumer to leave re-arms the hand-over words (every waiting workgroup has passed its wait by then)
+    const uint32_t old = __hip_atomic_fetch_add(a.done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (old == (uint32_t)(a.n_consumers - 1)) {
+      __hip_atomic_store(a.ready, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(a.done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+  const float S32 = poisoned ? __uint_as_float(0x7fc00000u) : *mem.tensor_scale;
   const int64_t nn = (int64_t)nt * 32 + n32;
   if (nt >= mem.n_tiles || nn >= mem.N) return;
   const float bias = (mem.bias && split == 0) ? bf16_bits_to_f32(mem.bias[nn]) : 0.f;   // split 0 carries it, like the LoRA columns
@@ -246,7 +276,7 @@ template <int MT, int W>
 static int launch_mid_t(const MidArgs& a, hipStream_t st) {
   constexpr size_t lds = 2 * (size_t)MT * 32 * 16 * sizeof(u32x4);
   const int64_t groups = ceil_div(a.n_blocks, 8);
-  mid_kernel<MT, W><<<dim3((unsigned)(groups * 8 * a.m_chunks * a.S)), dim3(W * 64), lds, st>>>(a);
+  mid_kernel<MT, W><<<dim3((unsigned)(a.n_prod + groups * 8 * a.m_chunks * a.S)), dim3(W * 64), lds, st>>>(a);
   return launch_status();
 }
 
@@ -314,6 +344,21 @@ int launch_mid(const MidArgs& a, hipStream_t st) {
     blocks += (int)ceil_div(m.n_tiles, a.W);
   }
   if (blocks != a.n_blocks) return QERL_ERR_SHAPE;
+  if (a.n_prod != 0) {   // the producers' description, checked as the stand-alone launch checks it
+    const GemmArgs& d = a.dn;
+    if (a.n_prod < 0 || a.n_prod % 8 != 0 || a.p_tbs < 1 || a.p_tiles < 1 || a.p_parts < 1 || a.p_parts > kDownMaxParts ||
+        (int64_t)a.p_tbs * a.p_tiles * a.p_parts > a.n_prod || (int64_t)a.p_tbs * 32 < a.M ||
+        a.n_consumers != a.n_blocks * a.m_chunks * a.S || d.g_n < 1 || d.g_n > kMaxGroup || d.M != a.M || d.K != a.K)
+      return QERL_ERR_SHAPE;
+    if (!a.ready || !a.done || d.ready != a.ready || d.x != a.x || (a.p_parts > 1 && (!d.tpart || !d.counters))) return QERL_ERR_NULL;
+    int tiles = 0;
+    for (int i = 0; i < d.g_n; ++i) {
+      if (!d.g_A[i] || !d.g_ts[i] || !d.g_tensor_scale[i]) return QERL_ERR_NULL;
+      if (d.g_r[i] < 1 || d.g_ts_ld[i] < 3 * d.g_r[i] || d.g_tile0[i] != tiles) return QERL_ERR_SHAPE;
+      tiles += (int)ceil_div(d.g_r[i], 32);
+    }
+    if (d.g_tile0[d.g_n] != tiles || tiles != a.p_tiles) return QERL_ERR_SHAPE;
+  }
   int rc = QERL_ERR_SHAPE;
   if (a.MT == 1 && a.W == 2) rc = launch_mid_t<1, 2>(a, st);
   else if (a.MT == 1 && a.W == 4) rc = launch_mid_t<1, 4>(a, st);

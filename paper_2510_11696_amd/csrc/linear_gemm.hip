@@ -311,8 +311,9 @@ struct GemmConfig { int MT, NT, W, wg_per_cu; float quality, quality_rounds; };
 // (quality_rounds) for one that takes several rounds -- the one-tile-per-wave shapes re-read x four times as
 // often, which a full chip notices (gate + up in one launch: 0.85 PFLOP/s against 1.0).
 static const GemmConfig kConfigs[] = {
-    {4, 2, 4, 1, 0.75f, 0.75f}, {4, 2, 5, 1, 0.90f, 0.90f}, {4, 2, 8, 1, 1.00f, 1.00f},
+    {4, 2, 4, 1, 0.72f, 0.72f}, {4, 2, 5, 1, 0.75f, 0.75f}, {4, 2, 8, 1, 1.00f, 1.00f},
     {4, 1, 4, 2, 0.95f, 0.74f}, {4, 1, 8, 2, 0.92f, 0.72f},
+    {4, 1, 10, 1, 0.90f, 0.86f},   // 320 output rows per workgroup, ten waves: N = 5120 in one full round
 };
 static int g_force_cfg = -1;
 
@@ -350,6 +351,7 @@ int launch_gemm(const GemmArgs& a0, hipStream_t st) {
   float best_score = -1.f;
   for (int c = 0; c < (int)(sizeof(kConfigs) / sizeof(kConfigs[0])); ++c) {
     const GemmConfig& g = kConfigs[c];
+    if (a.transposed && c != 2 && c != 5) continue;   // the backward pass is instantiated for two shapes
     const int64_t bm = g.MT * 32, bn = (int64_t)g.W * g.NT * 32;
     int64_t col_blocks = 0, n_sum = 0;
     for (int i = 0; i < a.m_n; ++i) { col_blocks += ceil_div(a.m[i].N, bn); n_sum += a.m[i].N; }
@@ -360,13 +362,13 @@ int launch_gemm(const GemmArgs& a0, hipStream_t st) {
     const float score = useful * (rounds > 1 ? g.quality_rounds : g.quality);
     if (score > best_score) { best_score = score; best = c; }
   }
-  if (a.transposed) return launch_cfg<4, 2, 8, true>(a, st);   // the backward pass: one tile shape
+  if (a.transposed) return best == 5 ? launch_cfg<4, 1, 10, true>(a, st) : launch_cfg<4, 2, 8, true>(a, st);
   if (g_force_cfg >= 0) best = g_force_cfg;
   const GemmArgs& b = a;
 #define QERL_GEMM_CASE(idx, mt, nt, w) \
   if (best == idx) return launch_cfg<mt, nt, w>(b, st);
   QERL_GEMM_CASE(0, 4, 2, 4) QERL_GEMM_CASE(1, 4, 2, 5) QERL_GEMM_CASE(2, 4, 2, 8)
-  QERL_GEMM_CASE(3, 4, 1, 4) QERL_GEMM_CASE(4, 4, 1, 8)
+  QERL_GEMM_CASE(3, 4, 1, 4) QERL_GEMM_CASE(4, 4, 1, 8) QERL_GEMM_CASE(5, 4, 1, 10)
 #undef QERL_GEMM_CASE
   return QERL_ERR_SHAPE;
 }

@@ -58,6 +58,11 @@ __global__ __launch_bounds__(256) void prepack_t_kernel(const uint8_t* __restric
   }
 }
 
+__global__ void backward_zero_kernel(uint32_t* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
 // out[c, r] = in[r, c] for a small bf16 matrix (the adapters)
 __global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __restrict__ in, int64_t R, int64_t C, uint16_t* __restrict__ out) {
   const int64_t total = R * C;
@@ -159,7 +164,7 @@ __global__ __launch_bounds__(256) void lora_grad_reduce_kernel(const float* __re
 }
 
 static size_t al256(size_t v) { return (v + 255) & ~(size_t)255; }
-struct BackwardLayout { size_t at_off, bt_off, tsu_off, tst_off, p_off, part_off, total; int64_t ts_ld; int ext_stages; int n_chunks; int64_t tokens_per_chunk; };
+struct BackwardLayout { size_t ctr_off, at_off, bt_off, tsu_off, tst_off, p_off, part_off, total; int64_t ts_ld; int ext_stages; int n_chunks; int64_t tokens_per_chunk; };
 static BackwardLayout backward_layout(int64_t M, int64_t N, int64_t K, int64_t r) {
   BackwardLayout L{};
   const size_t m = (size_t)(M > 0 ? M : 1), n = (size_t)(N > 0 ? N : 1), k = (size_t)(K > 0 ? K : 1), rr = (size_t)(r > 0 ? r : 0);
@@ -169,13 +174,16 @@ static BackwardLayout backward_layout(int64_t M, int64_t N, int64_t K, int64_t r
   chunks = chunks > kGradChunksMax ? kGradChunksMax : chunks;
   L.n_chunks = (int)chunks;
   L.tokens_per_chunk = ceil_div((int64_t)m, chunks);
-  L.at_off = 0;
+  L.ctr_off = 0;                                   // arrival counters of the K-split down-projections (zeroed by every call)
+  L.at_off = al256(kDownMaxSlots * sizeof(uint32_t));
   L.bt_off = L.at_off + al256(k * rr * 2);
   L.tsu_off = L.bt_off + al256(n * rr * 2);
   L.tst_off = L.tsu_off + al256(m * (size_t)L.ts_ld * 2);
   L.p_off = L.tst_off + al256(m * (size_t)L.ts_ld * 2);
   L.part_off = L.p_off + (rr ? al256(m * kGradRanks * sizeof(float)) : 0);
-  L.total = L.part_off + (rr ? al256((size_t)chunks * (n > k ? n : k) * kGradRanks * sizeof(float)) : 0);
+  size_t part = rr ? al256((size_t)chunks * (n > k ? n : k) * kGradRanks * sizeof(float)) : 0;
+  if (rr && part < kDownExchangeBytes) part = kDownExchangeBytes;   // the same area first holds the down-projections' K-part sums
+  L.total = L.part_off + part;
   if (L.total == 0) L.total = 256;
   return L;
 }
@@ -230,6 +238,7 @@ extern "C" int nvfp4_lora_linear_backward(const void* x, const void* dy, int64_t
   float* part = (float*)(ws + L.part_off);
   int rc = QERL_OK;
   if (r > 0) {
+    backward_zero_kernel<<<dim3(1), dim3(kDownMaxSlots), 0, st>>>((uint32_t*)(ws + L.ctr_off), kDownMaxSlots);
     transpose_bf16_kernel<<<dim3((unsigned)grid_for(r * K)), dim3(256), 0, st>>>((const uint16_t*)A, r, K, AT);
     transpose_bf16_kernel<<<dim3((unsigned)grid_for(N * r)), dim3(256), 0, st>>>((const uint16_t*)B, N, r, BT);
     if ((rc = launch_status()) != QERL_OK) return rc;
@@ -238,6 +247,7 @@ extern "C" int nvfp4_lora_linear_backward(const void* x, const void* dy, int64_t
     d.x = (const uint16_t*)dy; d.ldx = lddy; d.M = M; d.K = N; d.k_tiles = ceil_div(N, kPackTileK);
     d.N = r; d.wbf16 = BT; d.n_tiles = (int)ceil_div(r, 32); d.ts = tsU; d.ts_ld = L.ts_ld; d.ext_stages = L.ext_stages;
     d.r = (int)r; d.lora_scale = lora_scale; d.tensor_scale = tensor_scale;
+    d.tpart = (uint32_t*)part; d.counters = (uint32_t*)(ws + L.ctr_off);   // K split over workgroups while token blocks alone do not fill the chip
     if ((rc = launch_lora_down_gemm(d, st)) != QERL_OK) return rc;
     d.x = (const uint16_t*)x; d.ldx = ldx; d.K = K; d.k_tiles = ceil_div(K, kPackTileK); d.wbf16 = (const uint16_t*)A; d.ts = tsT;
     if ((rc = launch_lora_down_gemm(d, st)) != QERL_OK) return rc;

@@ -304,7 +304,7 @@ def backward_bench(args):
                                f"M={M}, LoRA r={r} alpha={cfg['alpha']:g}; dX bf16, dA and dB fp32; eager launches"},
         "roofline": {"bound": "mfma", "achieved": round(fl / (us * 1e-6) / 1e12, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(fl / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
-                     "kernel": "gemm32_kernel<4, 2, 8, true>", "algorithmic_flops_per_launch": fl,
+                     "kernel": "gemm32_kernel<.., true> (transposed operand)", "algorithmic_flops_per_launch": fl,
                      "shape": {"name": shp.name, "N": shp.N, "K": shp.K, "M": M}, "us_per_launch": round(us, 2),
                      "note": "dX alone (no adapter): one launch"},
     }))

@@ -14,8 +14,8 @@
 // gemm32_kernel<.., TR = true> multiplies dY with it (the eight weights of a lane and step carry eight different
 // E4M3 scales; products stay exact in bf16), the LoRA term enters as 3r more contraction columns exactly as in
 // the forward pass with the roles of A and B exchanged (both transposed once per call: they change with every
-// optimiser step).  dA and dB are skinny products over the token dimension: one thread per column of x (of dY),
-// all ranks in registers, tokens split over a few workgroups whose partial sums are added in order.
+// optimiser step).  dA and dB are skinny products over the token dimension (MFMA, operands transposed through LDS),
+// tokens split over a few workgroups whose partial sums are added in order.
 #include "linear.hpp"
 
 namespace qerl {
@@ -74,77 +74,86 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __r
 
 // ---- dA, dB: partial[chunk][c][j] = sum over the chunk's tokens of P[m, j] * Q[m, c] ------------------------
 // P [M, r] arrives as the three bf16 terms the LoRA down-projection kernel writes ([M, ts_ld]: hi | mid | lo,
-// their sum exact to 2^-24) and is summed into fp32 first; Q is x or dY (bf16, row-major).
+// their sum exact to 2^-24); Q is x or dY (bf16, row-major).  Both operands are contracted over their ROWS, so a
+// lane's eight consecutive contraction values lie in eight different rows: tiles of 32 tokens go through LDS
+// row by row (coalesced) and are read back column-wise, two bf16 values per dword.  A workgroup owns 128 columns
+// of Q (32 per wave), all ranks and one token chunk; three MFMAs per rank tile and 16 tokens (one per term).
 constexpr int kGradRanks = 64;       // most ranks
 constexpr int kGradChunksMax = 8;    // token chunks (workgroups along M) whose partial sums are added in order
-// P[m][j] = hi + mid + lo of the three-term value (0 for j >= r), fp32 [M][kGradRanks]
-__global__ __launch_bounds__(256) void lora_grad_p_kernel(const uint16_t* __restrict__ ts, int64_t ts_ld, int r, int64_t M,
-                                                          float* __restrict__ P) {
-  const int64_t total = M * kGradRanks;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
-    const int64_t m = i / kGradRanks;
-    const int j = (int)(i - m * kGradRanks);
-    float v = 0.f;
-    if (j < r) {
-      const uint16_t* row = ts + m * ts_ld;
-      v = (bf16_bits_to_f32(row[j]) + bf16_bits_to_f32(row[r + j])) + bf16_bits_to_f32(row[2 * r + j]);
-    }
-    P[i] = v;
-  }
-}
-
-// A workgroup owns 64 columns of Q, half of the ranks (blockIdx.z) and one token chunk (blockIdx.y); its four
-// waves take a quarter of the chunk's tokens each -- lane = column, the sums in registers -- and are added through
-// LDS in wave order.  P[m][:] is the same for every lane: its address is uniform, so the values arrive by scalar
-// loads and each product is one multiply-add with a scalar operand; with several workgroups per CU the latency
-// of those loads (one row per token) is covered by other waves.
-constexpr int kGradHalf = kGradRanks / 2;
-__global__ __launch_bounds__(256) void lora_grad_partial_kernel(const float* __restrict__ P, const uint16_t* __restrict__ Q, int64_t ldq,
-                                                                int64_t M, int64_t C, int64_t tokens_per_chunk, float* __restrict__ partial) {
-  __shared__ float red[4][kGradHalf][64];
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int64_t c = (int64_t)blockIdx.x * 64 + lane;
-  const int64_t cc = c < C ? c : C - 1;   // spare lanes of the last workgroup repeat a column and store nothing
-  const int j0 = (int)blockIdx.z * kGradHalf;
-  const int64_t c_lo = (int64_t)blockIdx.y * tokens_per_chunk;
-  const int64_t c_hi = c_lo + tokens_per_chunk < M ? c_lo + tokens_per_chunk : M;
-  const int64_t per_wave = (c_hi - c_lo + 3) / 4;
-  const int64_t m_lo = c_lo + wave * per_wave;
-  const int64_t m_hi = m_lo + per_wave < c_hi ? m_lo + per_wave : c_hi;
-  float acc[kGradHalf];
+constexpr int kGradTokens = 32;      // tokens per LDS tile
+constexpr int kGradQStride = 128 + 8, kGradPStride = 3 * kGradRanks + 8;   // u16 per LDS row: 16 bytes of padding shift the banks from row to row
+__global__ __launch_bounds__(256) void lora_grad_partial_kernel(const uint16_t* __restrict__ ts, int64_t ts_ld, int r,
+                                                                const uint16_t* __restrict__ Q, int64_t ldq, int64_t M, int64_t C,
+                                                                int64_t tokens_per_chunk, float* __restrict__ partial) {
+  __shared__ __attribute__((aligned(16))) uint16_t sQ[kGradTokens * kGradQStride];
+  __shared__ __attribute__((aligned(16))) uint16_t sP[kGradTokens * kGradPStride];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n32 = lane & 31, kg = lane >> 5;
+  const int64_t c0 = (int64_t)blockIdx.x * 128;
+  const int64_t m_lo = (int64_t)blockIdx.y * tokens_per_chunk;
+  const int64_t m_hi = m_lo + tokens_per_chunk < M ? m_lo + tokens_per_chunk : M;
+  const int p_chunks = 3 * r / 8;      // 16-byte chunks of a row of the three terms
+  f32x16 acc[2];
 #pragma unroll
-  for (int j = 0; j < kGradHalf; ++j) acc[j] = 0.f;
-  for (int64_t m = m_lo; m < m_hi; m += 8) {
-    float q[8];
+  for (int jt = 0; jt < 2; ++jt)
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      const int64_t mm = m + t < m_hi ? m + t : m_hi - 1;
-      q[t] = bf16_bits_to_f32(Q[mm * ldq + cc]);
+    for (int i = 0; i < 16; ++i) acc[jt][i] = 0.f;
+  for (int64_t m0 = m_lo; m0 < m_hi; m0 += kGradTokens) {
+    __syncthreads();                   // the previous tile has been read
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {      // Q tile: 32 rows x 16 chunks
+      const int idx = tid + 256 * i, row = idx >> 4, ch = idx & 15;
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (m0 + row < m_hi && c0 + ch * 8 < C) v = *reinterpret_cast<const u32x4*>(Q + (m0 + row) * ldq + c0 + ch * 8);
+      *reinterpret_cast<u32x4*>(sQ + row * kGradQStride + ch * 8) = v;
     }
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      if (m + t < m_hi) {                 // uniform
-        const float* p = P + (m + t) * kGradRanks + j0;
+    for (int i = 0; i < 3; ++i) {      // P tile: 32 rows x up to 24 chunks
+      const int idx = tid + 256 * i, row = idx / 24, ch = idx - row * 24;
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (m0 + row < m_hi && ch < p_chunks) v = *reinterpret_cast<const u32x4*>(ts + (m0 + row) * ts_ld + ch * 8);
+      *reinterpret_cast<u32x4*>(sP + row * kGradPStride + ch * 8) = v;
+    }
+    __syncthreads();
 #pragma unroll
-        for (int j = 0; j < kGradHalf; ++j) acc[j] += p[j] * q[t];
+    for (int ks = 0; ks < kGradTokens / 16; ++ks) {
+      const int rb = ks * 16 + 8 * kg;   // this lane's eight tokens of the step
+      u32x4 af;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t lo = sQ[(rb + 2 * e) * kGradQStride + wave * 32 + n32], hi = sQ[(rb + 2 * e + 1) * kGradQStride + wave * 32 + n32];
+        af[e] = lo | (hi << 16);
+      }
+#pragma unroll
+      for (int jt = 0; jt < 2; ++jt) {
+        const int j = jt * 32 + n32;
+        if (jt * 32 < r) {             // uniform
+#pragma unroll
+          for (int t = 0; t < 3; ++t) {
+            u32x4 bf = {0u, 0u, 0u, 0u};
+            if (j < r) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const uint32_t lo = sP[(rb + 2 * e) * kGradPStride + t * r + j], hi = sP[(rb + 2 * e + 1) * kGradPStride + t * r + j];
+                bf[e] = lo | (hi << 16);
+              }
+            }
+            acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af), __builtin_bit_cast(bf16x8, bf), acc[jt], 0, 0, 0);
+          }
+        }
       }
     }
   }
+  // acc[jt][q] = sum for column c0 + 32 wave + 8 (q / 4) + 4 kg + q % 4 and rank 32 jt + n32
 #pragma unroll
-  for (int j = 0; j < kGradHalf; ++j) red[wave][j][lane] = acc[j];
-  __syncthreads();
-  // wave w adds ranks 8 w .. 8 w + 7 of the four partial sums, in wave order
-  if (c < C) {
-    float* dst = partial + ((int64_t)blockIdx.y * C + c) * kGradRanks + j0 + 8 * wave;
-    float o[8];
+  for (int jt = 0; jt < 2; ++jt) {
+    const int j = jt * 32 + n32;
 #pragma unroll
-    for (int jj = 0; jj < 8; ++jj) {
-      const int j = 8 * wave + jj;
-      o[jj] = ((red[0][j][lane] + red[1][j][lane]) + red[2][j][lane]) + red[3][j][lane];
+    for (int q = 0; q < 16; ++q) {
+      const int64_t c = c0 + wave * 32 + 8 * (q >> 2) + 4 * kg + (q & 3);
+      if (c < C && j < r) partial[((int64_t)blockIdx.y * C + c) * kGradRanks + j] = acc[jt][q];
     }
-    *reinterpret_cast<f32x4*>(dst) = f32x4{o[0], o[1], o[2], o[3]};
-    *reinterpret_cast<f32x4*>(dst + 4) = f32x4{o[4], o[5], o[6], o[7]};
   }
 }
 
@@ -180,7 +189,7 @@ static BackwardLayout backward_layout(int64_t M, int64_t N, int64_t K, int64_t r
   L.tsu_off = L.bt_off + al256(n * rr * 2);
   L.tst_off = L.tsu_off + al256(m * (size_t)L.ts_ld * 2);
   L.p_off = L.tst_off + al256(m * (size_t)L.ts_ld * 2);
-  L.part_off = L.p_off + (rr ? al256(m * kGradRanks * sizeof(float)) : 0);
+  L.part_off = L.p_off;
   size_t part = rr ? al256((size_t)chunks * (n > k ? n : k) * kGradRanks * sizeof(float)) : 0;
   if (rr && part < kDownExchangeBytes) part = kDownExchangeBytes;   // the same area first holds the down-projections' K-part sums
   L.total = L.part_off + part;
@@ -264,14 +273,11 @@ extern "C" int nvfp4_lora_linear_backward(const void* x, const void* dy, int64_t
   if (r > 0) {
     // the three-term values carry lora_scale / S32; the gradients want lora_scale: one multiplication by S32
     const dim3 blk(256);
-    float* P = (float*)(ws + L.p_off);
-    lora_grad_p_kernel<<<dim3((unsigned)grid_for(M * kGradRanks)), blk, 0, st>>>(tsU, L.ts_ld, (int)r, M, P);
-    lora_grad_partial_kernel<<<dim3((unsigned)ceil_div(K, 64), (unsigned)L.n_chunks, r > kGradHalf ? 2u : 1u), blk, 0, st>>>(
-        P, (const uint16_t*)x, ldx, M, K, L.tokens_per_chunk, part);
+    lora_grad_partial_kernel<<<dim3((unsigned)ceil_div(K, 128), (unsigned)L.n_chunks), blk, 0, st>>>(
+        tsU, L.ts_ld, (int)r, (const uint16_t*)x, ldx, M, K, L.tokens_per_chunk, part);
     lora_grad_reduce_kernel<<<dim3((unsigned)grid_for(K * r)), blk, 0, st>>>(part, L.n_chunks, K, (int)r, tensor_scale, 1, dA);
-    lora_grad_p_kernel<<<dim3((unsigned)grid_for(M * kGradRanks)), blk, 0, st>>>(tsT, L.ts_ld, (int)r, M, P);
-    lora_grad_partial_kernel<<<dim3((unsigned)ceil_div(N, 64), (unsigned)L.n_chunks, r > kGradHalf ? 2u : 1u), blk, 0, st>>>(
-        P, (const uint16_t*)dy, lddy, M, N, L.tokens_per_chunk, part);
+    lora_grad_partial_kernel<<<dim3((unsigned)ceil_div(N, 128), (unsigned)L.n_chunks), blk, 0, st>>>(
+        tsT, L.ts_ld, (int)r, (const uint16_t*)dy, lddy, M, N, L.tokens_per_chunk, part);
     lora_grad_reduce_kernel<<<dim3((unsigned)grid_for(N * r)), blk, 0, st>>>(part, L.n_chunks, N, (int)r, tensor_scale, 0, dB);
     rc = launch_status();
   }

@@ -339,7 +339,7 @@ int launch_gemm(const GemmArgs& a0, hipStream_t st) {
     a.m[0] = GemmMember{a.packed, a.tensor_scale, a.N, a.n_tiles, a.ts, a.ts_ld, a.ext_stages, a.B, a.r, a.bias, a.y, a.ldy, 0};
   }
   // every pointer the kernel dereferences must be set by the caller
-  if (!a.x || a.m_n < 1 || a.m_n > kMaxGroup || a.M < 1 || a.K < 16 || a.k_tiles < 1) return QERL_ERR_SHAPE;
+  if (!a.x || a.m_n < 1 || a.m_n > kMaxGroup || a.M < 1 || a.K < (a.transposed ? 8 : 16) || a.k_tiles < 1) return QERL_ERR_SHAPE;
   for (int i = 0; i < a.m_n; ++i) {
     const GemmMember& m = a.m[i];
     if (!m.packed || !m.tensor_scale || !m.y || (m.r > 0 && (!m.ts || !m.B))) return QERL_ERR_NULL;
@@ -376,7 +376,7 @@ int launch_gemm(const GemmArgs& a0, hipStream_t st) {
 // ts = three-term bf16 split of (lora_scale / S32) * x A^T, [M, ts_ld]; a.N = r rows of A.
 int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st) {
   if (a.g_n > 0) {   // several adapters reading the same x: one 32-row tile per workgroup
-    if (!a.x || a.g_n > kMaxGroup || a.M < 1 || a.K < 16) return QERL_ERR_SHAPE;
+    if (!a.x || a.g_n > kMaxGroup || a.M < 1 || a.K < 8) return QERL_ERR_SHAPE;
     int tiles = 0;
     for (int i = 0; i < a.g_n; ++i) {
       if (!a.g_A[i] || !a.g_ts[i] || !a.g_tensor_scale[i]) return QERL_ERR_NULL;
@@ -396,7 +396,7 @@ int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st) {
     return launch_status();
   }
   if (!a.x || !a.wbf16 || !a.tensor_scale || !a.ts) return QERL_ERR_NULL;
-  if (a.M < 1 || a.N < 1 || a.K < 16 || a.ts_ld < 3 * a.N) return QERL_ERR_SHAPE;
+  if (a.M < 1 || a.N < 1 || a.K < 8 || a.ts_ld < 3 * a.N) return QERL_ERR_SHAPE;
   const int tiles = (int)ceil_div(a.N, 32);
   // While token blocks x rank tiles do not fill the chip, K is split over workgroups (up to eight parts, at
   // least 512 columns each, at most kDownMaxSlots workgroups) when the caller provides the exchange area.

@@ -67,6 +67,7 @@ def _check_f32(got, ref, what):
     (200, 64, 3584, 64),         # the largest rank
     (300, 3584, 512, 32),        # the 7B k/v projection
     (64, 256, 256, 0),           # no adapter: dX only
+    (16, 8, 256, 0), (16, 8, 256, 8),   # a contraction of eight rows
 ])
 def test_backward_equals_oracle(M, N, K, r):
     print("backward case", M, N, K, r, flush=True)

@@ -315,7 +315,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="BASELINE config number (1-based)")
+    ap.add_argument("--config", type=int, default=2, help="workload configuration number (1-based; see qerl_synth.CONFIGS)")
     ap.add_argument("--M", type=int, default=None)
     ap.add_argument("--layers", type=int, default=None)
     ap.add_argument("--backward", action="store_true",

@@ -388,6 +388,25 @@ def test_full_size_14b_gate_at_prefill_as_the_benchmark_launches_it():
     check_linear(y[:, torch.from_numpy(rows).cuda()], ref, ("full-size prefill gate",))
 
 
+def test_grouped_prefill_with_many_token_blocks_and_rank_64():
+    """33 token blocks, four adapters of rank 64 (eight rank tiles): the grouped down-projection and GEMM launches."""
+    M, K, Ns, rs = 1056, 256, (64, 96, 32, 64), (64, 64, 64, 64)
+    x = qs.activations(M, K, 9900)
+    g = lambda a: torch.from_numpy(a).cuda()
+    ws_, As, Bs, refs = [], [], [], []
+    for i, (N, r) in enumerate(zip(Ns, rs)):
+        W = cases.gaussian(N, K, 9910 + i)
+        codes, scales, ts = oracle.nvfp4_quantize(W)
+        A, B = qs.lora_pair(N, K, r, 9920 + i)
+        ws_.append(qerl.nvfp4_prepack(g(codes), g(scales), torch.tensor([ts], device="cuda")))
+        As.append(A.cuda()); Bs.append(B.cuda())
+        refs.append(oracle.nvfp4_lora_linear(x.float().numpy(), codes, scales, ts, A.float().numpy(), B.float().numpy(), 2.0))
+    outs = qerl.nvfp4_lora_linear_packed_group(x.cuda(), ws_, As, Bs, [2.0] * len(Ns))
+    torch.cuda.synchronize()
+    for i, (y, ref) in enumerate(zip(outs, refs)):
+        check_linear(y, ref, ("many token blocks", i))
+
+
 @pytest.mark.parametrize("M", [1, 8, 16, 40, 128, 200])
 @pytest.mark.parametrize("K,Ns,rs", [
     (3584, (3584, 512, 512), (32, 32, 32)),      # q, k, v of the 7B block: the three projections that carry a bias

@@ -305,15 +305,15 @@ __global__ __launch_bounds__(512) void lora_down32_kernel(const GemmArgs a) {
 
 // ---- host ------------------------------------------------------------------------------------------
 
-struct GemmConfig { int MT, NT, W, wg_per_cu; float quality, quality_rounds; };
-// wg_per_cu: workgroups of this shape resident on one CU (register use); quality: relative speed
-// measured at equal useful work on 14B-shaped layers, for a launch that fits the chip at once and
-// (quality_rounds) for one that takes several rounds -- the one-tile-per-wave shapes re-read x four times as
-// often, which a full chip notices (gate + up in one launch: 0.85 PFLOP/s against 1.0).
+struct GemmConfig { int MT, NT, W, wg_per_cu; float quality, quality_shared, quality_rounds; };
+// wg_per_cu: workgroups of this shape that fit one CU (register use).  Relative speeds at equal useful work,
+// measured on 7B / 14B / 32B-shaped layers at 192..4096 tokens: quality when every workgroup has a CU of its own
+// (at most 256 of them), quality_shared when a single round puts two on a CU, quality_rounds when the launch takes
+// several rounds.  The one-tile-per-wave shapes hide the conversions behind more waves but re-read x more often.
 static const GemmConfig kConfigs[] = {
-    {4, 2, 4, 1, 0.72f, 0.72f}, {4, 2, 5, 1, 0.75f, 0.75f}, {4, 2, 8, 1, 1.00f, 1.00f},
-    {4, 1, 4, 2, 0.95f, 0.74f}, {4, 1, 8, 2, 0.92f, 0.72f},
-    {4, 1, 10, 1, 0.90f, 0.86f},   // 320 output rows per workgroup, ten waves: N = 5120 in one full round
+    {4, 2, 4, 1, 0.72f, 0.72f, 0.72f}, {4, 2, 5, 1, 0.75f, 0.75f, 0.75f}, {4, 2, 8, 1, 1.00f, 1.00f, 1.00f},
+    {4, 1, 4, 2, 0.95f, 0.84f, 0.85f}, {4, 1, 8, 2, 0.95f, 0.93f, 0.95f},
+    {4, 1, 10, 1, 0.90f, 0.90f, 0.86f},   // 320 output rows per workgroup, ten waves: N = 5120 in one full round
 };
 static int g_force_cfg = -1;
 
@@ -356,10 +356,11 @@ int launch_gemm(const GemmArgs& a0, hipStream_t st) {
     int64_t col_blocks = 0, n_sum = 0;
     for (int i = 0; i < a.m_n; ++i) { col_blocks += ceil_div(a.m[i].N, bn); n_sum += a.m[i].N; }
     const int64_t wgs = ceil_div(a.M, bm) * col_blocks;
-    const int64_t slots = 256 * g.wg_per_cu;
+    const bool alone = wgs <= 256;                              // every workgroup gets a CU of its own
+    const int64_t slots = alone ? 256 : 256 * g.wg_per_cu;
     const int64_t rounds = ceil_div(wgs, slots);
     const float useful = (float)((double)a.M * (double)n_sum / ((double)rounds * (double)slots * (double)bm * (double)bn));
-    const float score = useful * (rounds > 1 ? g.quality_rounds : g.quality);
+    const float score = useful * (rounds > 1 ? g.quality_rounds : alone ? g.quality : g.quality_shared);
     if (score > best_score) { best_score = score; best = c; }
   }
   if (a.transposed) return best == 5 ? launch_cfg<4, 1, 10, true>(a, st) : launch_cfg<4, 2, 8, true>(a, st);

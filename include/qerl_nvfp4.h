@@ -333,18 +333,20 @@ QERL_API int aqn_noise_fill(float* noise_f32, int64_t n, float sigma, uint64_t s
  * mxfp4_prepack:   codes/scales -> tiles of 32 rows x 256 inputs (4352 bytes) in the
  *                  operand order of the scaled matrix instruction; packed must be
  *                  16-byte aligned, mxfp4_prepack_bytes(N, K) bytes.
- * mxfp4_linear_native: y [M, N] bf16 = MXFP8(x) . MXFP4(W)^T for decode-sized
- *   batches (M <= 32), both operands going through CDNA4's block-scaled matrix
- *   instruction as stored (no conversion arithmetic).  NOT the paper's setting:
- *   there activations stay bf16 (weight-only).  x is quantised to MXFP8 inside the
- *   kernel (the function mxfp8_quantize computes); the result is the exact product of the two
- *   quantised operands summed in fp32, rounded once to bf16; it differs from the
- *   weight-only result by the activation rounding (up to 2^-4 relative per
- *   element).  No LoRA branch and no bias in this variant.
+ * mxfp4_linear_native: y [M, N] bf16 = MXFP8(x) . MXFP4(W)^T, both operands
+ *   going through CDNA4's block-scaled matrix instruction as stored (no
+ *   conversion arithmetic).  NOT the paper's setting: there activations stay
+ *   bf16 (weight-only).  x is quantised to MXFP8 (the function mxfp8_quantize
+ *   computes) inside the kernel for M <= 32 (a weight-streaming kernel) and by a
+ *   launch of its own into the workspace for more tokens (a GEMM, 128 x 256
+ *   tiles); the result is the exact product of the two quantised operands summed
+ *   in fp32, rounded once to bf16; it differs from the weight-only result by the
+ *   activation rounding (up to 2^-4 relative per element).  No LoRA branch and
+ *   no bias in this variant.
  *   x 16-byte aligned with ldx % 8 == 0.
  *   workspace: >= mxfp4_linear_native_workspace_bytes(M, N, K), 256-byte aligned;
  *   needs no initialisation.
- * Errors: as the NVFP4 functions (NULL, shape incl. K % 32 and M > 32, alignment,
+ * Errors: as the NVFP4 functions (NULL, shape incl. K % 32, alignment,
  * workspace).
  */
 QERL_API int mxfp4_quantize(const void* W_bf16, int64_t N, int64_t K, int64_t ldw,

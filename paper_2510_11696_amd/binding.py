@@ -530,7 +530,7 @@ def mxfp4_prepack(codes: torch.Tensor, scales: torch.Tensor) -> MxPackedWeight:
 
 def mxfp4_linear_native(x: torch.Tensor, w: MxPackedWeight, workspace: Optional[torch.Tensor] = None,
                         out: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """y = MXFP8(x) . MXFP4(W)^T on the block-scaled matrix instruction, M <= 32 tokens."""
+    """y = MXFP8(x) . MXFP4(W)^T on the block-scaled matrix instruction (any number of tokens)."""
     lib = load_library()
     M, K, ldx = _rows(x, "x")
     if K != w.K:

@@ -33,6 +33,8 @@
 //                          flight while the current one is multiplied), the seven partial tiles are added
 //                          through LDS in wave order by the eighth wave, which also stores.  Bound by streaming the packed weights:
 //                          0.53125 B per weight.
+//   mx_gemm_kernel         more tokens: x quantised by a launch of mx_quantize_kernel, then a GEMM with
+//                          128 x 256 tiles on the same instruction (described at the kernel).
 #include "common.hpp"
 
 namespace qerl {
@@ -351,6 +353,176 @@ static int launch_mx(const MxArgs& a, int NG, int grid, hipStream_t st) {
   return QERL_ERR_SHAPE;
 }
 
+// ---- more than 32 tokens: a GEMM on the block-scaled matrix instruction ---------------------------------------
+// y = MXFP8(x) . MXFP4(W)^T, x quantised beforehand (mx_quantize_kernel<8>) into codes [M, K] and scales [M, K / 32].
+// No conversion arithmetic at all: packed weights go global -> registers -> matrix instruction.  Workgroup tile
+// 128 tokens x 256 rows, eight waves as 2 x 4: a wave owns 64 tokens x 64 rows (2 x 2 accumulator tiles), so every
+// x fragment read from LDS and every weight fragment feeds two instructions.  A stage is one packed tile (256
+// inputs, four instruction steps, 16 instructions per wave between barriers): its weights are requested one stage
+// ahead into registers, its x slab (128 tokens x 256 bytes + 8 scale bytes per token) one stage ahead into
+// registers and then into the other of two LDS buffers (16-byte chunks XOR-swizzled by row; the scale bytes of a
+// row regrouped so that a lane finds the four bytes of its half in one dword and the instruction picks by an
+// immediate).  No branch inside a stage depends on the thread or the stage: requests past the end are redirected
+// to the last stage, so the compiler's wait counts stay exact.  Bound by the FP8 matrix rate.
+struct MxGemmArgs {
+  const uint8_t* xq; const uint8_t* xs; int64_t M, K;     // MXFP8 codes [M, K], scales [M, K / 32]
+  const uint8_t* packed; int k_tiles; int n_tiles; int64_t N;
+  uint16_t* y; int64_t ldy;
+  int n_blocks, nblk_per_xcd;
+};
+
+constexpr int kMxgBM = 128, kMxgThreads = 512, kMxgMT = 2, kMxgNT = 2;
+struct MxgW { u32x4 c[kMxgNT][4]; uint32_t sc[kMxgNT]; };          // one wave's weights of a stage
+struct MxgX { u32x4 c[4]; uint32_t s0, s1; };                       // one thread's share of an x slab: four chunks, two scale bytes
+
+__global__ __launch_bounds__(kMxgThreads) void mx_gemm_kernel(const MxGemmArgs a) {
+  constexpr int BM = kMxgBM, MT = kMxgMT, NT = kMxgNT;
+  constexpr int kChunks = BM * 16;                         // 16-byte chunks of one x slab (BM rows x 256 bytes)
+  __shared__ u32x4 xs[2 * kChunks];                        // chunk c of row r at r * 16 + (c ^ (r & 15))
+  __shared__ __attribute__((aligned(8))) uint8_t xsc[2 * BM * 8];   // row r: bytes [g * 4 + j] = scale of block 2 j + g
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 2, wn = wave & 3;                 // the wave's token half and row quarter
+  const int n32 = lane & 31, kg = lane >> 5;
+  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;   // each XCD walks a contiguous eighth of the column blocks
+  const int nb_local = local % a.nblk_per_xcd, mb = local / a.nblk_per_xcd;
+  const int nb = xcd * a.nblk_per_xcd + nb_local;
+  if (nb >= a.n_blocks) return;
+  const int64_t m0 = (int64_t)mb * BM;
+  const int nt0 = (nb * 4 + wn) * NT;
+  const int64_t n_blk = a.K / 32;
+
+  f32x16 acc[MT][NT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[mt][nt][i] = 0.f;
+
+  // thread -> (row, chunk) of the slab: chunks tid, tid + 512, ...; scale bytes: row tid / 4, blocks 2 (tid % 4), + 1
+  auto gload_x = [&](MxgX& r, int kt) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int idx = tid + i * kMxgThreads, row = idx >> 4, ch = idx & 15;
+      int64_t gr = m0 + row;
+      gr = gr < a.M ? gr : a.M - 1;
+      int64_t k = (int64_t)kt * 256 + ch * 16;
+      k = k < a.K ? k : a.K - 16;                          // past the end of K: any bytes, zeroed before they reach LDS
+      r.c[i] = *reinterpret_cast<const u32x4*>(a.xq + gr * a.K + k);
+    }
+    int64_t gr = m0 + (tid >> 2);
+    gr = gr < a.M ? gr : a.M - 1;
+    int64_t b0 = (int64_t)kt * 8 + 2 * (tid & 3), b1 = b0 + 1;
+    b0 = b0 < n_blk ? b0 : n_blk - 1;
+    b1 = b1 < n_blk ? b1 : n_blk - 1;
+    r.s0 = a.xs[gr * n_blk + b0];
+    r.s1 = a.xs[gr * n_blk + b1];
+  };
+  auto swrite_x = [&](int buf, const MxgX& r, int kt) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int idx = tid + i * kMxgThreads, row = idx >> 4, ch = idx & 15;
+      // beyond K (K % 256 != 0): zero codes -- a stray byte could be an FP8 NaN, and the weights there are zero
+      const u32x4 v = (int64_t)kt * 256 + ch * 16 < a.K ? r.c[i] : u32x4{0u, 0u, 0u, 0u};
+      xs[buf * kChunks + row * 16 + (ch ^ (row & 15))] = v;
+    }
+    const int row = tid >> 2, j = tid & 3;                  // blocks 2 j (half 0) and 2 j + 1 (half 1) of the row
+    const bool in0 = (int64_t)kt * 8 + 2 * j < n_blk, in1 = (int64_t)kt * 8 + 2 * j + 1 < n_blk;
+    xsc[(buf * BM + row) * 8 + j] = in0 ? (uint8_t)r.s0 : (uint8_t)0;
+    xsc[(buf * BM + row) * 8 + 4 + j] = in1 ? (uint8_t)r.s1 : (uint8_t)0;
+  };
+  auto gload_w = [&](MxgW& w, int kt) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      int tile = nt0 + nt;
+      tile = tile < a.n_tiles ? tile : a.n_tiles - 1;
+      const uint8_t* base = a.packed + ((int64_t)tile * a.k_tiles + kt) * kMxTileBytes;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) w.c[nt][j] = *reinterpret_cast<const u32x4*>(base + j * 1024 + lane * 16);
+      w.sc[nt] = *reinterpret_cast<const uint32_t*>(base + 4096 + lane * 4);
+    }
+  };
+  auto compute = [&](int buf, const MxgW& w) {
+    const u32x4* xst = xs + buf * kChunks;
+    int xscale[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int row = wm * 64 + mt * 32 + n32;
+      xscale[mt] = (int)*reinterpret_cast<const uint32_t*>(xsc + (buf * BM + row) * 8 + kg * 4);
+    }
+    auto step = [&](auto jc) {
+      constexpr int j = decltype(jc)::value;
+      v8i xa[MT];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const int row = wm * 64 + mt * 32 + n32, sw = row & 15;
+        const u32x4 c0 = xst[row * 16 + ((4 * j + kg) ^ sw)], c1 = xst[row * 16 + ((4 * j + 2 + kg) ^ sw)];
+        xa[mt] = v8i{(int)c0[0], (int)c0[1], (int)c0[2], (int)c0[3], (int)c1[0], (int)c1[1], (int)c1[2], (int)c1[3]};
+      }
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const v8i b = v8i{(int)w.c[nt][j][0], (int)w.c[nt][j][1], (int)w.c[nt][j][2], (int)w.c[nt][j][3], 0, 0, 0, 0};
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(xa[mt], b, acc[mt][nt], 0, 4, j, xscale[mt], j, (int)w.sc[nt]);
+      }
+    };
+    step(std::integral_constant<int, 0>{});
+    step(std::integral_constant<int, 1>{});
+    step(std::integral_constant<int, 2>{});
+    step(std::integral_constant<int, 3>{});
+  };
+
+  {
+    const int n = a.k_tiles, last = n - 1;
+    auto clamp_kt = [&](int kt) { return kt < last ? kt : last; };
+    MxgW w0, w1;
+    MxgX x0, x1;
+    gload_x(x0, 0);
+    gload_x(x1, clamp_kt(1));
+    gload_w(w0, 0);
+    swrite_x(0, x0, 0);
+    __syncthreads();
+    // Two stages per round so that buffer and register names are constants.  Stage kt: the slab of kt + 2 and the
+    // weights of kt + 1 are requested, kt is multiplied, the slab of kt + 1 (requested a stage ago) goes to LDS.
+    auto stage = [&](int kt, int buf, MxgW& wcur, MxgW& wnext, MxgX& xfar, const MxgX& xnear) {
+      gload_x(xfar, clamp_kt(kt + 2));
+      gload_w(wnext, clamp_kt(kt + 1));
+      __builtin_amdgcn_sched_barrier(0);   // the requests stay ahead of the stage's arithmetic
+      compute(buf, wcur);
+      __builtin_amdgcn_sched_barrier(0);
+      swrite_x(buf ^ 1, xnear, clamp_kt(kt + 1));
+      __syncthreads();
+    };
+    int kt = 0;
+    for (; kt + 2 <= n; kt += 2) {
+      stage(kt, 0, w0, w1, x0, x1);
+      stage(kt + 1, 1, w1, w0, x1, x0);
+    }
+    if (kt < n) stage(kt, 0, w0, w1, x0, x1);
+  }
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const int64_t nn = (int64_t)(nt0 + nt) * 32 + n32;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int64_t m = m0 + wm * 64 + mt * 32 + 8 * (i >> 2) + 4 * kg + (i & 3);
+        if (m < a.M && nn < a.N) a.y[m * a.ldy + nn] = (uint16_t)f32_to_bf16_bits(acc[mt][nt][i]);
+      }
+    }
+}
+
+static int launch_mx_gemm(MxGemmArgs a, hipStream_t st) {
+  a.n_blocks = (int)ceil_div(a.n_tiles, 4 * kMxgNT);
+  a.nblk_per_xcd = (int)ceil_div(a.n_blocks, 8);
+  const int64_t m_blocks = ceil_div(a.M, kMxgBM);
+  mx_gemm_kernel<<<dim3((unsigned)(8 * a.nblk_per_xcd * m_blocks)), dim3(kMxgThreads), 0, st>>>(a);
+  return launch_status();
+}
+
 }  // namespace qerl
 
 using namespace qerl;
@@ -399,15 +571,38 @@ extern "C" int mxfp4_prepack(const uint8_t* codes, const uint8_t* scales, int64_
   return launch_status();
 }
 
-extern "C" size_t mxfp4_linear_native_workspace_bytes(int64_t M, int64_t N, int64_t K) { return mx_workspace(M, N, K).total; }
+// beyond the decode kernel's 32 tokens: x as MXFP8 codes and scales
+static size_t mx_gemm_workspace(int64_t M, int64_t K) {
+  auto al = [](size_t v) { return (v + 255) & ~(size_t)255; };
+  return al((size_t)M * (size_t)K) + al((size_t)M * (size_t)(K / 32));
+}
+extern "C" size_t mxfp4_linear_native_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+  if (M > 32) return mx_gemm_workspace(M, K > 0 ? K : 32);
+  return mx_workspace(M, N, K).total;
+}
 
 extern "C" int mxfp4_linear_native(const void* x, int64_t M, int64_t K, int64_t ldx, const void* packed, int64_t N, void* y, int64_t ldy,
                                    void* workspace, size_t workspace_bytes, void* stream) {
-  if (M < 0 || M > 32 || N < 0 || K < 0 || K % 32 != 0 || ldx < K || ldy < N || N >= ((int64_t)1 << 24)) return QERL_ERR_SHAPE;
+  if (M < 0 || N < 0 || K < 0 || K % 32 != 0 || ldx < K || ldy < N || N >= ((int64_t)1 << 24)) return QERL_ERR_SHAPE;
   if (M == 0 || N == 0) return QERL_OK;
   if (K == 0) return QERL_ERR_SHAPE;
   if (!x || !packed || !y) return QERL_ERR_NULL;
   if (!aligned(x, 16) || ldx % 8 != 0 || !aligned(packed, 16) || !aligned(y, 2)) return QERL_ERR_ALIGN;
+  if (M > 32) {
+    // quantise x once, then the GEMM
+    const size_t need = mx_gemm_workspace(M, K);
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < need) return QERL_ERR_WORKSPACE;
+    uint8_t* xq = (uint8_t*)workspace;
+    uint8_t* xsc = xq + (((size_t)M * (size_t)K + 255) & ~(size_t)255);
+    hipStream_t st = (hipStream_t)stream;
+    mx_quantize_kernel<8><<<dim3((unsigned)grid_for(M * (K / 32))), dim3(256), 0, st>>>((const uint16_t*)x, M, K, ldx, xq, xsc);
+    int rc = launch_status();
+    if (rc != QERL_OK) return rc;
+    MxGemmArgs g{};
+    g.xq = xq; g.xs = xsc; g.M = M; g.K = K; g.packed = (const uint8_t*)packed;
+    g.k_tiles = (int)ceil_div(K, 256); g.n_tiles = (int)ceil_div(N, 32); g.N = N; g.y = (uint16_t*)y; g.ldy = ldy;
+    return launch_mx_gemm(g, st);
+  }
   const MxWorkspace w = mx_workspace(M, N, K);
   if (!workspace || !aligned(workspace, 256) || workspace_bytes < w.total) return QERL_ERR_WORKSPACE;
   uint8_t* ws = (uint8_t*)workspace;

@@ -117,6 +117,8 @@ def test_native_linear_reads_dequantised_columns_for_one_hot_rows():
 @pytest.mark.parametrize("M,N,K", [
     (1, 64, 128), (3, 40, 320), (8, 512, 3584), (8, 3584, 3584), (8, 96, 18944),   # the last: K split over ranges of workgroups
     (16, 1000, 2112), (32, 130, 5120), (9, 33, 27648),
+    # more than 32 tokens: the GEMM (x quantised by a launch of its own); ragged token blocks, row tiles and a half step of K
+    (33, 64, 128), (64, 130, 320), (130, 1000, 2112), (300, 96, 96), (200, 3584, 3584), (513, 40, 32), (1100, 5120, 1024),
 ])
 def test_native_linear_is_the_product_of_the_quantised_operands(M, N, K):
     """Products of FP8 and FP4 values are exact and the sums are fp32: the result is held to the same gate as the

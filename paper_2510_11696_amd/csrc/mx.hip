@@ -451,15 +451,17 @@ __global__ __launch_bounds__(kMxgThreads) void mx_gemm_kernel(const MxGemmArgs a
       const int row = wm * 64 + mt * 32 + n32;
       xscale[mt] = (int)*reinterpret_cast<const uint32_t*>(xsc + (buf * BM + row) * 8 + kg * 4);
     }
-    auto step = [&](auto jc) {
-      constexpr int j = decltype(jc)::value;
-      v8i xa[MT];
+    // x fragments of step j + 1 are requested from LDS before the instructions of step j are issued
+    auto frags = [&](v8i (&xa)[MT], int j) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         const int row = wm * 64 + mt * 32 + n32, sw = row & 15;
         const u32x4 c0 = xst[row * 16 + ((4 * j + kg) ^ sw)], c1 = xst[row * 16 + ((4 * j + 2 + kg) ^ sw)];
         xa[mt] = v8i{(int)c0[0], (int)c0[1], (int)c0[2], (int)c0[3], (int)c1[0], (int)c1[1], (int)c1[2], (int)c1[3]};
       }
+    };
+    auto step = [&](const v8i (&xa)[MT], auto jc) {
+      constexpr int j = decltype(jc)::value;
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
         const v8i b = v8i{(int)w.c[nt][j][0], (int)w.c[nt][j][1], (int)w.c[nt][j][2], (int)w.c[nt][j][3], 0, 0, 0, 0};
@@ -468,10 +470,15 @@ __global__ __launch_bounds__(kMxgThreads) void mx_gemm_kernel(const MxGemmArgs a
           acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(xa[mt], b, acc[mt][nt], 0, 4, j, xscale[mt], j, (int)w.sc[nt]);
       }
     };
-    step(std::integral_constant<int, 0>{});
-    step(std::integral_constant<int, 1>{});
-    step(std::integral_constant<int, 2>{});
-    step(std::integral_constant<int, 3>{});
+    v8i xa[MT], xb[MT];
+    frags(xa, 0);
+    frags(xb, 1);
+    step(xa, std::integral_constant<int, 0>{});
+    frags(xa, 2);
+    step(xb, std::integral_constant<int, 1>{});
+    frags(xb, 3);
+    step(xa, std::integral_constant<int, 2>{});
+    step(xb, std::integral_constant<int, 3>{});
   };
 
   {

@@ -316,6 +316,7 @@ static const GemmConfig kConfigs[] = {
     {4, 1, 10, 1, 0.90f, 0.90f, 0.86f},   // 320 output rows per workgroup, ten waves: N = 5120 in one full round
 };
 static int g_force_cfg = -1;
+static bool g_split = true;   // whole rounds and remainder as two launches when that is estimated faster
 
 template <int MT, int NT, int W, bool TR = false>
 static int launch_cfg(const GemmArgs& a, hipStream_t st) {
@@ -347,31 +348,95 @@ int launch_gemm(const GemmArgs& a0, hipStream_t st) {
         m.ext_stages * 64 < 3 * m.r || (int64_t)m.ext_stages * 64 > (m.r > 0 ? m.ts_ld : 0))
       return QERL_ERR_SHAPE;
   }
-  int best = 0;
-  float best_score = -1.f;
-  for (int c = 0; c < (int)(sizeof(kConfigs) / sizeof(kConfigs[0])); ++c) {
+  // Estimated time of every eligible shape, in units of one output element's K-loop on a fully used chip at
+  // quality 1: rounds x slots x tile area / quality.
+  const int n_cfg = (int)(sizeof(kConfigs) / sizeof(kConfigs[0]));
+  auto cfg_time = [&](int c, const GemmMember* m, int n) {
     const GemmConfig& g = kConfigs[c];
-    if (a.transposed && c != 2 && c != 5) continue;   // the backward pass is instantiated for two shapes
     const int64_t bm = g.MT * 32, bn = (int64_t)g.W * g.NT * 32;
-    int64_t col_blocks = 0, n_sum = 0;
-    for (int i = 0; i < a.m_n; ++i) { col_blocks += ceil_div(a.m[i].N, bn); n_sum += a.m[i].N; }
+    int64_t col_blocks = 0;
+    for (int i = 0; i < n; ++i) col_blocks += ceil_div(m[i].N, bn);
     const int64_t wgs = ceil_div(a.M, bm) * col_blocks;
     const bool alone = wgs <= 256;                              // every workgroup gets a CU of its own
     const int64_t slots = alone ? 256 : 256 * g.wg_per_cu;
     const int64_t rounds = ceil_div(wgs, slots);
-    const float useful = (float)((double)a.M * (double)n_sum / ((double)rounds * (double)slots * (double)bm * (double)bn));
-    const float score = useful * (rounds > 1 ? g.quality_rounds : alone ? g.quality : g.quality_shared);
-    if (score > best_score) { best_score = score; best = c; }
-  }
+    const float q = rounds > 1 ? g.quality_rounds : alone ? g.quality : g.quality_shared;
+    return (double)rounds * (double)slots * (double)bm * (double)bn / q;
+  };
+  auto best_cfg = [&](const GemmMember* m, int n, double& t_best) {
+    int best = -1;
+    for (int c = 0; c < n_cfg; ++c) {
+      if (a.transposed && c != 2 && c != 5) continue;   // the backward pass is instantiated for two shapes
+      const double t = cfg_time(c, m, n);
+      if (best < 0 || t < t_best) { t_best = t; best = c; }
+    }
+    return best;
+  };
+  double t_single = 0;
+  int best = best_cfg(a.m, a.m_n, t_single);
   if (a.transposed) return best == 5 ? launch_cfg<4, 1, 10, true>(a, st) : launch_cfg<4, 2, 8, true>(a, st);
   if (g_force_cfg >= 0) best = g_force_cfg;
-  const GemmArgs& b = a;
+  auto launch_one = [&](int c, const GemmArgs& b) -> int {
 #define QERL_GEMM_CASE(idx, mt, nt, w) \
-  if (best == idx) return launch_cfg<mt, nt, w>(b, st);
-  QERL_GEMM_CASE(0, 4, 2, 4) QERL_GEMM_CASE(1, 4, 2, 5) QERL_GEMM_CASE(2, 4, 2, 8)
-  QERL_GEMM_CASE(3, 4, 1, 4) QERL_GEMM_CASE(4, 4, 1, 8) QERL_GEMM_CASE(5, 4, 1, 10)
+    if (c == idx) return launch_cfg<mt, nt, w>(b, st);
+    QERL_GEMM_CASE(0, 4, 2, 4) QERL_GEMM_CASE(1, 4, 2, 5) QERL_GEMM_CASE(2, 4, 2, 8)
+    QERL_GEMM_CASE(3, 4, 1, 4) QERL_GEMM_CASE(4, 4, 1, 8) QERL_GEMM_CASE(5, 4, 1, 10)
 #undef QERL_GEMM_CASE
-  return QERL_ERR_SHAPE;
+    return QERL_ERR_SHAPE;
+  };
+  // A launch of several rounds whose last round is partly empty: the whole rounds go out in one shape,
+  // the remaining columns as a launch of their own in whatever shape suits them (smaller tiles fill the chip
+  // where a part round of large ones would leave CUs idle).  A member cut by the boundary appears in both
+  // launches; the second sees it from a row-tile offset on (the packed tiles of 32 rows are contiguous per row tile).
+  if (g_split && g_force_cfg < 0) {
+    // ~15 us in the units above: the gap between the launches, the second one's fill and drain
+    const double overhead = 8.4e9 / (double)a.K;
+    double t_split = 0.97 * t_single;   // what a pair of launches has to beat
+    int c_main = -1, c_rem = -1;
+    GemmArgs main_args, rem_args;
+    for (int c1 = 0; c1 < n_cfg; ++c1) {
+      const GemmConfig& g = kConfigs[c1];
+      const int64_t bm = g.MT * 32, bn = (int64_t)g.W * g.NT * 32, tiles_per_block = (int64_t)g.W * g.NT;
+      int64_t col_blocks = 0;
+      for (int i = 0; i < a.m_n; ++i) col_blocks += ceil_div(a.m[i].N, bn);
+      const int64_t m_blocks = ceil_div(a.M, bm), wgs = m_blocks * col_blocks, slots = 256 * (int64_t)g.wg_per_cu;
+      const int64_t whole = wgs / slots;
+      int64_t c_blocks = whole * slots / m_blocks;             // column blocks of the whole rounds
+      if (whole < 1 || wgs % slots == 0 || c_blocks < 1 || c_blocks >= col_blocks) continue;
+      GemmArgs ma = a, ra = a;
+      ma.m_n = ra.m_n = 0;
+      for (int i = 0; i < a.m_n; ++i) {
+        const GemmMember& m = a.m[i];
+        const int64_t cb = ceil_div(m.N, bn);
+        const int64_t take = c_blocks < cb ? c_blocks : cb;    // this member's column blocks in the first launch
+        c_blocks -= take;
+        if (take > 0) {
+          GemmMember& d = ma.m[ma.m_n++];
+          d = m;
+          if (take < cb) { d.N = take * bn; d.n_tiles = (int)(take * tiles_per_block); }
+        }
+        if (take < cb) {
+          GemmMember& d = ra.m[ra.m_n++];
+          d = m;
+          const int64_t t0 = take * tiles_per_block, row0 = t0 * 32;
+          d.packed = m.packed + t0 * a.k_tiles * kPackTileBytes;
+          d.N = m.N - row0; d.n_tiles = m.n_tiles - (int)t0;
+          if (m.B) d.B = m.B + row0 * m.r;
+          if (m.bias) d.bias = m.bias + row0;
+          d.y = m.y + row0;
+        }
+      }
+      double t_rem = 0;
+      const int cr = best_cfg(ra.m, ra.m_n, t_rem);
+      const double t = cfg_time(c1, ma.m, ma.m_n) + t_rem + overhead;
+      if (t < t_split) { t_split = t; c_main = c1; c_rem = cr; main_args = ma; rem_args = ra; }
+    }
+    if (c_main >= 0) {
+      const int rc = launch_one(c_main, main_args);
+      return rc != QERL_OK ? rc : launch_one(c_rem, rem_args);
+    }
+  }
+  return launch_one(best, a);
 }
 
 // ts = three-term bf16 split of (lora_scale / S32) * x A^T, [M, ts_ld]; a.N = r rows of A.
@@ -420,4 +485,5 @@ int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st) {
 // Tuning hook for experiments (not part of the public header): force a GEMM tile configuration, -1 = automatic.
 #ifdef QERL_TUNING_HOOKS   // built only for tuning sessions: they change process-wide state
 extern "C" QERL_API void qerl_debug_force_gemm(int cfg) { qerl::g_force_cfg = cfg; }
+extern "C" QERL_API void qerl_debug_gemm_split(int on) { qerl::g_split = on != 0; }
 #endif  // QERL_TUNING_HOOKS

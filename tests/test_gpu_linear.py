@@ -407,6 +407,39 @@ def test_grouped_prefill_with_many_token_blocks_and_rank_64():
         check_linear(y, ref, ("many token blocks", i))
 
 
+@pytest.mark.timeout(600)
+def test_full_size_14b_gate_and_up_at_prefill_as_the_benchmark_launches_them():
+    """14B gate_proj and up_proj (13824 x 5120 each) in one grouped call at 2048 tokens, r = 64, with bias: 864
+    workgroups of the largest tile shape, 3.4 rounds of the chip, which goes out as three whole rounds plus a launch
+    of the remaining columns in a smaller shape, cut inside up_proj.  Checked on sampled output rows against the
+    oracle, the rows on both sides of every multiple of 512 near the cut among them."""
+    M, K, N, r = 2048, 5120, 13824, 64
+    print("full-size grouped prefill case", M, N, K, r, flush=True)
+    g = lambda a: torch.from_numpy(a).cuda()
+    x = qs.activations(M, K, 8101)
+    members = []
+    for i in range(2):
+        W = cases.gaussian(N, K, 8110 + i)
+        codes, scales, ts = oracle.nvfp4_quantize(W)
+        del W
+        A, B = qs.lora_pair(N, K, r, 8120 + i)
+        bias = (torch.randn(N, generator=torch.Generator().manual_seed(8130 + i)) * 0.5).to(torch.bfloat16)
+        pw = qerl.nvfp4_prepack(g(codes), g(scales), torch.tensor([ts], device="cuda"))
+        members.append((codes, scales, ts, A, B, bias, pw))
+        print("  quantised member", i, flush=True)
+    outs = qerl.nvfp4_lora_linear_packed_group(x.cuda(), [m[6] for m in members], [m[3].cuda() for m in members],
+                                               [m[4].cuda() for m in members], [1.0, 1.0],
+                                               biases=[m[5].cuda() for m in members])
+    torch.cuda.synchronize()
+    x_np = x.float().numpy()
+    edges = np.concatenate([np.arange(c - 2, c + 2) for c in range(9216, N, 512)])
+    for i, (codes, scales, ts, A, B, bias, _) in enumerate(members):
+        rows = np.unique(np.concatenate([_sampled_rows(N, 8140 + i, n=64), edges]))
+        ref = oracle.nvfp4_lora_linear(x_np, codes[rows], scales[rows], ts, A.float().numpy(), B.float().numpy()[rows], 1.0,
+                                       bias=bias.float().numpy()[rows])
+        check_linear(outs[i][:, torch.from_numpy(rows).cuda()], ref, ("full-size grouped prefill", i))
+
+
 @pytest.mark.parametrize("M", [1, 8, 16, 40, 128, 200])
 @pytest.mark.parametrize("K,Ns,rs", [
     (3584, (3584, 512, 512), (32, 32, 32)),      # q, k, v of the 7B block: the three projections that carry a bias

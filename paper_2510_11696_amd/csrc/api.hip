@@ -349,7 +349,8 @@ static int gemm_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, cons
   }
   if (dn.g_n > 0) {
     dn.g_tile0[dn.g_n] = tiles;
-    const int rc = launch_lora_down_gemm(dn, st);   // no K-parts: 32-token blocks x rank tiles fill the chip
+    dn.tpart = (uint32_t*)(ws + L.partial_off); dn.counters = (uint32_t*)ws + L.n_main_ctr;   // K-parts while token blocks alone do not fill the chip
+    const int rc = launch_lora_down_gemm(dn, st);
     if (rc != QERL_OK) return rc;
   }
   return launch_gemm(g, st);

@@ -103,7 +103,7 @@ struct GemmArgs {
 };
 int launch_gemm(const GemmArgs& a, hipStream_t st);
 constexpr int kDownMaxSlots = 256;                                           // workgroups of a K-split LoRA down-projection
-constexpr size_t kDownExchangeBytes = (size_t)kDownMaxSlots * 2 * 16 * 64 * sizeof(float);   // their partial sums: two 32 x 32 tiles each
+constexpr size_t kDownExchangeBytes = (size_t)16 << 20;   // the K-parts' partial sums (32-token kernel: kDownMaxSlots workgroups of two 32 x 32 tiles; 64-token kernel: up to eight tiles per wave quartet)
 int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st);
 
 // ---- 17..128 tokens: weight-streaming MFMA kernel on tile-packed weights (linear_mid.hip) ----

@@ -303,6 +303,209 @@ __global__ __launch_bounds__(512) void lora_down32_kernel(const GemmArgs a) {
   lora_down_block<NT, 8>(a, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z, (int)gridDim.z, (int)gridDim.x, (int)gridDim.y, red);
 }
 
+// ---- the same product for a few hundred tokens and more ----------------------------------------------
+// lora_down32_kernel fetches both operands in MFMA operand layout (one row per lane, 32 bytes of a row per
+// instruction), which the memory pipeline serves at a fraction of its rate.  Here a workgroup of four waves owns
+// 64 tokens, all rank tiles of all adapters of the launch and K-part blockIdx.y: x and A slabs of 64 columns are
+// fetched row-contiguously (eight lanes per 128-byte row segment), three or four slabs ahead through a register ring, and
+// handed to the MFMA operand layout through LDS (double buffered, one barrier per slab, the row-XOR swizzle of the
+// GEMM above).  Wave w owns token half w & 1 and the rank tiles (w >> 1), (w >> 1) + 2, ...: no sums across waves.
+// K-parts meet in the workspace as in lora_down_block: the workgroup that arrives last adds them in part order.
+// The adapters come in the group form of GemmArgs (g_*); ts as lora_down_block writes it.
+template <int TPW>   // rank tiles per wave
+__global__ __launch_bounds__(256) void lora_down64_kernel(const GemmArgs a, const int n_tiles, const int P) {
+  constexpr int T = 2 * TPW;                      // rank tiles held in LDS (the last one a repeat when n_tiles is odd)
+  constexpr int kXChunks = 64 * 8, kAChunks = T * 32 * 8;
+  extern __shared__ u32x4 lds64[];                // [2][x slab | A slab]
+  __shared__ uint32_t s_old;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n32 = lane & 31, kg = lane >> 5;
+  const int mt = wave & 1, t_first = wave >> 1;
+  const int tb = blockIdx.x, bz = blockIdx.y;
+  const int64_t m0 = (int64_t)tb * 64;
+  const int64_t part_cols = ceil_div_dev(ceil_div_dev(a.K, 64), P) * 64;
+  const int64_t k_lo = (int64_t)bz * part_cols;
+  const int64_t k_hi = k_lo + part_cols < a.K ? k_lo + part_cols : a.K;
+  const int n_slabs = k_hi > k_lo ? (int)ceil_div_dev(k_hi - k_lo, 64) : 0;
+
+  // the adapter that owns rank tile t (uniform), and the tile's index inside it
+  auto member_of = [&](int t) {
+    int mi = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxGroup; ++i) mi = (i < a.g_n && t >= a.g_tile0[i]) ? i : mi;
+    return mi;
+  };
+  // ---- loaders: thread tid fetches chunk tid & 7 of row tid >> 3 (+ 32 per further request)
+  const int lrow = tid >> 3, lchunk = tid & 7;
+  const uint16_t* xsrc[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    int64_t m = m0 + lrow + 32 * i;
+    m = m < a.M ? m : a.M - 1;
+    xsrc[i] = a.x + m * a.ldx;
+  }
+  const uint16_t* asrc[T];
+#pragma unroll
+  for (int i = 0; i < T; ++i) {
+    const int t = i < n_tiles ? i : n_tiles - 1;
+    int mi = member_of(t);
+    const uint16_t* A = a.g_A[0];
+    int rN = a.g_r[0], t0 = a.g_tile0[0];
+#pragma unroll
+    for (int j = 1; j < kMaxGroup; ++j)
+      if (mi == j) { A = a.g_A[j]; rN = a.g_r[j]; t0 = a.g_tile0[j]; }
+    int row = (t - t0) * 32 + lrow;
+    row = row < rN ? row : rN - 1;
+    asrc[i] = A + (int64_t)row * a.K;
+  }
+  struct Slab { u32x4 x[2]; u32x4 w[T]; };
+  // slabs past the part's end contribute nothing: their x is zeroed (the address is redirected into the row)
+  auto load = [&](Slab& sl, int s) {
+    int64_t k = k_lo + (int64_t)s * 64 + lchunk * 8;
+    const bool in = k < k_hi;
+    k = k < a.K - 8 ? k : a.K - 8;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      u32x4 v = *reinterpret_cast<const u32x4*>(xsrc[i] + k);
+      sl.x[i] = in ? v : u32x4{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int i = 0; i < T; ++i) sl.w[i] = *reinterpret_cast<const u32x4*>(asrc[i] + k);
+  };
+  auto to_lds = [&](int buf, const Slab& sl) {
+    u32x4* base = lds64 + buf * (kXChunks + kAChunks);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int row = lrow + 32 * i;
+      base[row * 8 + (lchunk ^ ((row >> 1) & 7))] = sl.x[i];
+    }
+#pragma unroll
+    for (int i = 0; i < T; ++i) {
+      const int row = lrow + 32 * i;
+      base[kXChunks + row * 8 + (lchunk ^ ((row >> 1) & 7))] = sl.w[i];
+    }
+  };
+  f32x16 acc[TPW];
+#pragma unroll
+  for (int i = 0; i < TPW; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+  auto compute = [&](int buf) {
+    const u32x4* base = lds64 + buf * (kXChunks + kAChunks);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int xrow = mt * 32 + n32;
+      const bf16x8 xf = __builtin_bit_cast(bf16x8, base[xrow * 8 + ((2 * j + kg) ^ ((xrow >> 1) & 7))]);
+#pragma unroll
+      for (int i = 0; i < TPW; ++i) {
+        const int arow = (t_first + 2 * i) * 32 + n32;
+        const bf16x8 af = __builtin_bit_cast(bf16x8, base[kXChunks + arow * 8 + ((2 * j + kg) ^ ((arow >> 1) & 7))]);
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, af, acc[i], 0, 0, 0);
+      }
+    }
+  };
+
+  // ---- main loop: whole rounds of the ring, the last one padded with empty slabs
+  {
+    constexpr int D = TPW == 4 ? 3 : 4;   // slabs in flight per thread (registers)
+    Slab ring[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) load(ring[d], d);
+    for (int s0 = 0; s0 < n_slabs; s0 += D) {
+#pragma unroll
+      for (int u = 0; u < D; ++u) {
+        to_lds(u & 1, ring[u]);
+        load(ring[u], s0 + u + D);
+        __syncthreads();
+        compute(u & 1);
+      }
+    }
+  }
+
+  // ---- K-parts: every part leaves its sums in the workspace (written through to memory before the workgroup's
+  // arrival is counted); the workgroup that arrives last adds all parts in part order and goes on.
+  if (P > 1) {
+    constexpr int kWgFloats = 4 * TPW * 16 * 64;
+    const int64_t part_stride = (int64_t)gridDim.x * kWgFloats;
+    uint32_t* mine = a.tpart + (int64_t)bz * part_stride + (int64_t)tb * kWgFloats + wave * (TPW * 16 * 64) + lane;
+#pragma unroll
+    for (int i = 0; i < TPW; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        __hip_atomic_store(mine + (i * 16 + e) * 64, __float_as_uint(acc[i][e]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    __syncthreads();
+    if (tid == 0) s_old = __hip_atomic_fetch_add(a.counters + tb, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (s_old != (uint32_t)(P - 1)) return;
+    const uint32_t* all = a.tpart + (int64_t)tb * kWgFloats + wave * (TPW * 16 * 64) + lane;
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+      uint32_t v[kDownMaxParts][16];
+#pragma unroll
+      for (int z = 0; z < kDownMaxParts; ++z)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          v[z][e] = 0u;
+          if (z < P) v[z][e] = __hip_atomic_load(all + (int64_t)z * part_stride + (i * 16 + e) * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        float sum = 0.f;
+#pragma unroll
+        for (int z = 0; z < kDownMaxParts; ++z) sum += __uint_as_float(v[z][e]);
+        acc[i][e] = sum;
+      }
+      __builtin_amdgcn_sched_barrier(0);   // one tile's 128 values at a time in registers
+    }
+    if (tid == 0) __hip_atomic_store(a.counters + tb, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+  }
+
+  // ---- ts = three bf16 terms of (lora_scale / S32) * sum, per adapter
+#pragma unroll
+  for (int i = 0; i < TPW; ++i) {
+    const int t = t_first + 2 * i;
+    if (t >= n_tiles) continue;
+    const int mi = member_of(t);
+    uint16_t* ts = const_cast<uint16_t*>(a.g_ts[0]);
+    int64_t ts_ld = a.g_ts_ld[0];
+    int rN = a.g_r[0], t0 = a.g_tile0[0];
+    float lora_scale = a.g_lora_scale[0];
+    const float* tensor_scale = a.g_tensor_scale[0];
+#pragma unroll
+    for (int j = 1; j < kMaxGroup; ++j)
+      if (mi == j) {
+        ts = const_cast<uint16_t*>(a.g_ts[j]); ts_ld = a.g_ts_ld[j]; rN = a.g_r[j]; t0 = a.g_tile0[j];
+        lora_scale = a.g_lora_scale[j]; tensor_scale = a.g_tensor_scale[j];
+      }
+    const float t_mult = lora_scale / *tensor_scale;   // undone by the final * S32 of the main launch
+    const int n = (t - t0) * 32 + n32;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int64_t m = m0 + mt * 32 + 8 * (e >> 2) + 4 * kg + (e & 3);
+      if (m < a.M && n < rN) {
+        const float v = acc[i][e] * t_mult;
+        const uint32_t h = f32_to_bf16_bits(v);
+        const float r1 = v - bf16_bits_to_f32(h);
+        const uint32_t md = f32_to_bf16_bits(r1);
+        const uint32_t l = f32_to_bf16_bits(r1 - bf16_bits_to_f32(md));
+        uint16_t* row = ts + m * ts_ld;
+        row[n] = (uint16_t)h;
+        row[rN + n] = (uint16_t)md;
+        row[2 * rN + n] = (uint16_t)l;
+      }
+    }
+    if (t == t0) {   // the adapter's first tile: zero the padding columns [3 r, ts_ld) of this wave's 32 tokens
+      const int pad = (int)(ts_ld - 3 * rN);
+      for (int idx = lane; idx < 32 * pad; idx += 64) {
+        const int64_t m = m0 + mt * 32 + idx / pad;
+        if (m < a.M) ts[m * ts_ld + 3 * rN + idx % pad] = 0;
+      }
+    }
+  }
+}
+
 // ---- host ------------------------------------------------------------------------------------------
 
 struct GemmConfig { int MT, NT, W, wg_per_cu; float quality, quality_shared, quality_rounds; };
@@ -440,6 +643,54 @@ int launch_gemm(const GemmArgs& a0, hipStream_t st) {
 }
 
 // ts = three-term bf16 split of (lora_scale / S32) * x A^T, [M, ts_ld]; a.N = r rows of A.
+// Token counts from which the 64-token kernel takes over
+static int g_down64_min_tokens = 256;
+static int g_down64_parts = 0;   // tuning: force the number of K-parts (0 = automatic)
+
+template <int TPW>
+static int launch_down64_t(const GemmArgs& a, int n_tiles, int P, dim3 grid, hipStream_t st) {
+  constexpr size_t lds = 2 * ((size_t)64 * 8 + (size_t)2 * TPW * 32 * 8) * sizeof(u32x4);   // up to 80 KB
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&lora_down64_kernel<TPW>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return launch_status();
+    attr_set = true;
+  }
+  lora_down64_kernel<TPW><<<grid, 256, lds, st>>>(a, n_tiles, P);
+  return launch_status();
+}
+
+static int launch_lora_down64(const GemmArgs& a0, hipStream_t st) {
+  GemmArgs a = a0;
+  if (a.g_n == 0) {   // a single adapter, put into the group form
+    a.g_n = 1;
+    a.g_tile0[0] = 0; a.g_tile0[1] = (int)ceil_div(a.N, 32);
+    a.g_A[0] = a.wbf16; a.g_ts[0] = a.ts; a.g_ts_ld[0] = a.ts_ld; a.g_r[0] = (int)a.N;
+    a.g_lora_scale[0] = a.lora_scale; a.g_tensor_scale[0] = a.tensor_scale;
+  }
+  const int n_tiles = a.g_tile0[a.g_n];
+  const int tpw = (n_tiles + 1) / 2;
+  const int64_t tbs = ceil_div(a.M, 64);
+  // K-parts until the chip is full (twice over for a single adapter, whose parts exchange little): at most eight,
+  // at least 512 columns each, one arrival counter per token block, and the parts' sums must fit the exchange area
+  int64_t P = 1;
+  if (a.tpart && a.counters && tbs <= kDownMaxSlots) {
+    P = (tpw == 1 ? 512 : 256) / tbs;
+    const int64_t p_max = ceil_div(a.K, 512);
+    P = P < p_max ? P : p_max;
+    P = P > kDownMaxParts ? kDownMaxParts : (P < 1 ? 1 : P);
+    if (g_down64_parts > 0) P = g_down64_parts;
+    while (P > 1 && (size_t)(tbs * P) * 4 * tpw * 16 * 64 * sizeof(float) > kDownExchangeBytes) --P;
+  }
+  const dim3 grid((unsigned)tbs, (unsigned)P);
+  if (tpw == 1) return launch_down64_t<1>(a, n_tiles, (int)P, grid, st);
+  if (tpw == 2) return launch_down64_t<2>(a, n_tiles, (int)P, grid, st);
+  if (tpw == 3) return launch_down64_t<3>(a, n_tiles, (int)P, grid, st);
+  if (tpw == 4) return launch_down64_t<4>(a, n_tiles, (int)P, grid, st);
+  return QERL_ERR_SHAPE;
+}
+
 int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st) {
   if (a.g_n > 0) {   // several adapters reading the same x: one 32-row tile per workgroup
     if (!a.x || a.g_n > kMaxGroup || a.M < 1 || a.K < 8) return QERL_ERR_SHAPE;
@@ -450,6 +701,7 @@ int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st) {
       tiles += (int)ceil_div(a.g_r[i], 32);
     }
     if (a.g_tile0[a.g_n] != tiles) return QERL_ERR_SHAPE;
+    if (a.M >= g_down64_min_tokens && tiles <= 8 && a.K % 8 == 0) return launch_lora_down64(a, st);
     int64_t P = 1;
     const int64_t base_wgs = ceil_div(a.M, 32) * tiles;
     if (a.tpart && a.counters && base_wgs < 32) {
@@ -464,6 +716,7 @@ int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st) {
   if (!a.x || !a.wbf16 || !a.tensor_scale || !a.ts) return QERL_ERR_NULL;
   if (a.M < 1 || a.N < 1 || a.K < 8 || a.ts_ld < 3 * a.N) return QERL_ERR_SHAPE;
   const int tiles = (int)ceil_div(a.N, 32);
+  if (a.M >= g_down64_min_tokens && tiles <= 8 && a.K % 8 == 0) return launch_lora_down64(a, st);
   // While token blocks x rank tiles do not fill the chip, K is split over workgroups (up to eight parts, at
   // least 512 columns each, at most kDownMaxSlots workgroups) when the caller provides the exchange area.
   int64_t P = 1;
@@ -486,4 +739,6 @@ int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st) {
 #ifdef QERL_TUNING_HOOKS   // built only for tuning sessions: they change process-wide state
 extern "C" QERL_API void qerl_debug_force_gemm(int cfg) { qerl::g_force_cfg = cfg; }
 extern "C" QERL_API void qerl_debug_gemm_split(int on) { qerl::g_split = on != 0; }
+extern "C" QERL_API void qerl_debug_down64_min_tokens(int m) { qerl::g_down64_min_tokens = m; }
+extern "C" QERL_API void qerl_debug_down64_parts(int p) { qerl::g_down64_parts = p; }
 #endif  // QERL_TUNING_HOOKS

@@ -407,6 +407,39 @@ def test_grouped_prefill_with_many_token_blocks_and_rank_64():
         check_linear(y, ref, ("many token blocks", i))
 
 
+@pytest.mark.parametrize("M,K,Ns,rs", [
+    (257, 992, (64, 40, 96), (64, 32, 8)),            # 4 rank tiles, one of them partial; K not a multiple of 64; ragged token block
+    (300, 2048, (32, 32, 64, 32), (64, 64, 64, 64)),  # 8 rank tiles: four per wave
+    (320, 64, (96,), (8,)),                           # one partial rank tile; a single slab, no K-parts
+    (513, 4096, (64, 64, 32), (64, 32, 64)),          # 5 rank tiles (the sixth slot repeats the last); 8 K-parts
+    (1030, 1536, (40,), (64,)),                       # one adapter, two tiles; 17 token blocks
+])
+def test_lora_down_projection_of_256_tokens_and_more(M, K, Ns, rs):
+    """The 64-token down-projection kernel behind the prefill GEMM: odd and full rank-tile counts, partial tiles,
+    K-parts with a ragged last slab, ragged token blocks.  Small N keeps the main product cheap; the adapters' share
+    of the output is made large (lora_scale 8) so that a wrong t shows."""
+    print("down-projection case", M, K, Ns, rs, flush=True)
+    x = qs.activations(M, K, 9700 + M)
+    g = lambda a: torch.from_numpy(a).cuda()
+    ws_, As, Bs, refs = [], [], [], []
+    for i, (N, r) in enumerate(zip(Ns, rs)):
+        W = cases.gaussian(N, K, 9710 + 10 * i + M)
+        codes, scales, ts = oracle.nvfp4_quantize(W)
+        A, B = qs.lora_pair(N, K, r, 9720 + i)
+        ws_.append(qerl.nvfp4_prepack(g(codes), g(scales), torch.tensor([ts], device="cuda")))
+        As.append(A.cuda()); Bs.append(B.cuda())
+        refs.append(oracle.nvfp4_lora_linear(x.float().numpy(), codes, scales, ts, A.float().numpy(), B.float().numpy(), 8.0))
+    outs = qerl.nvfp4_lora_linear_packed_group(x.cuda(), ws_, As, Bs, [8.0] * len(Ns))
+    torch.cuda.synchronize()
+    for i, (y, ref) in enumerate(zip(outs, refs)):
+        check_linear(y, ref, ("down-projection", i, M, K))
+    again = qerl.nvfp4_lora_linear_packed_group(x.cuda(), ws_, As, Bs, [8.0] * len(Ns))
+    assert all(torch.equal(p, q) for p, q in zip(outs, again))
+    if len(Ns) == 1:
+        single = qerl.nvfp4_lora_linear_packed(x.cuda(), ws_[0], As[0], Bs[0], 8.0)
+        check_linear(single, refs[0], ("down-projection, single call", M, K))
+
+
 @pytest.mark.timeout(600)
 def test_full_size_14b_gate_and_up_at_prefill_as_the_benchmark_launches_them():
     """14B gate_proj and up_proj (13824 x 5120 each) in one grouped call at 2048 tokens, r = 64, with bias: 864

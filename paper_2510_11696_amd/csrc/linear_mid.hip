@@ -289,7 +289,7 @@ int plan_mid(MidArgs& a, size_t partial_cap_bytes) {
   // Waves per workgroup and K-splits: the pair with the shortest estimated time.  A wave spends about
   // 650 + 350 MT cycles on a stage (dequantisation plus MT x 8 MFMAs); workgroups spread evenly over the 256
   // CUs, their waves over the CU's four SIMDs.  A split costs a second launch and the partial sums' traffic.
-  const int w_opts[2] = {MT == 4 ? 4 : 2, MT == 4 ? 8 : 4};
+  const int w_opts[2] = {4, MT == 4 ? 8 : 2};   // the first wins ties: four waves measured equal or better than two at equal estimates
   const double cyc = 650.0 + 350.0 * MT;
   double best = 0;
   a.W = 0;

@@ -289,7 +289,12 @@ int plan_mid(MidArgs& a, size_t partial_cap_bytes) {
   // Waves per workgroup and K-splits: the pair with the shortest estimated time.  A wave spends about
   // 650 + 350 MT cycles on a stage (dequantisation plus MT x 8 MFMAs); workgroups spread evenly over the 256
   // CUs, their waves over the CU's four SIMDs.  A split costs a second launch and the partial sums' traffic.
-  const int w_opts[2] = {4, MT == 4 ? 8 : 2};   // the first wins ties: four waves measured equal or better than two at equal estimates
+  // the first wins ties: four waves measured equal or better than two at equal estimates, except for a group of
+  // few row tiles (q + k + v at 7B: 144) at up to 32 tokens, which then has too few workgroups
+  int64_t tiles_sum = 0;
+  for (int i = 0; i < a.n_members; ++i) tiles_sum += a.mem[i].n_tiles;
+  const bool small_group = MT == 1 && a.n_members > 1 && tiles_sum < 256;
+  const int w_opts[2] = {MT == 4 || !small_group ? 4 : 2, MT == 4 ? 8 : (small_group ? 4 : 2)};
   const double cyc = 650.0 + 350.0 * MT;
   double best = 0;
   a.W = 0;

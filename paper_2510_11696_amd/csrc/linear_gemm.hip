@@ -415,10 +415,11 @@ __global__ __launch_bounds__(256) void lora_down64_kernel(const GemmArgs a, cons
     for (int s0 = 0; s0 < n_slabs; s0 += D) {
 #pragma unroll
       for (int u = 0; u < D; ++u) {
-        to_lds(u & 1, ring[u]);
+        const int buf = (s0 + u) & 1;   // consecutive slabs alternate (D may be odd)
+        to_lds(buf, ring[u]);
         load(ring[u], s0 + u + D);
         __syncthreads();
-        compute(u & 1);
+        compute(buf);
       }
     }
   }

@@ -99,23 +99,38 @@ __global__ __launch_bounds__(256) void lora_grad_partial_kernel(const uint16_t* 
   for (int jt = 0; jt < 2; ++jt)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[jt][i] = 0.f;
-  for (int64_t m0 = m_lo; m0 < m_hi; m0 += kGradTokens) {
-    __syncthreads();                   // the previous tile has been read
+  // the tile after the current one is requested before the current one is multiplied (registers), so that a
+  // workgroup pays the memory latency once, not once per tile
+  u32x4 qreg[2], preg[3];
+  auto request = [&](int64_t m0) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {      // Q tile: 32 rows x 16 chunks
       const int idx = tid + 256 * i, row = idx >> 4, ch = idx & 15;
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (m0 + row < m_hi && c0 + ch * 8 < C) v = *reinterpret_cast<const u32x4*>(Q + (m0 + row) * ldq + c0 + ch * 8);
-      *reinterpret_cast<u32x4*>(sQ + row * kGradQStride + ch * 8) = v;
+      qreg[i] = u32x4{0u, 0u, 0u, 0u};
+      if (m0 + row < m_hi && c0 + ch * 8 < C) qreg[i] = *reinterpret_cast<const u32x4*>(Q + (m0 + row) * ldq + c0 + ch * 8);
     }
 #pragma unroll
     for (int i = 0; i < 3; ++i) {      // P tile: 32 rows x up to 24 chunks
       const int idx = tid + 256 * i, row = idx / 24, ch = idx - row * 24;
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (m0 + row < m_hi && ch < p_chunks) v = *reinterpret_cast<const u32x4*>(ts + (m0 + row) * ts_ld + ch * 8);
-      *reinterpret_cast<u32x4*>(sP + row * kGradPStride + ch * 8) = v;
+      preg[i] = u32x4{0u, 0u, 0u, 0u};
+      if (m0 + row < m_hi && ch < p_chunks) preg[i] = *reinterpret_cast<const u32x4*>(ts + (m0 + row) * ts_ld + ch * 8);
+    }
+  };
+  request(m_lo);
+  for (int64_t m0 = m_lo; m0 < m_hi; m0 += kGradTokens) {
+    __syncthreads();                   // the previous tile has been read
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int idx = tid + 256 * i, row = idx >> 4, ch = idx & 15;
+      *reinterpret_cast<u32x4*>(sQ + row * kGradQStride + ch * 8) = qreg[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+      const int idx = tid + 256 * i, row = idx / 24, ch = idx - row * 24;
+      *reinterpret_cast<u32x4*>(sP + row * kGradPStride + ch * 8) = preg[i];
     }
     __syncthreads();
+    request(m0 + kGradTokens);         // past the chunk's end every guard fails: zeros, no access
 #pragma unroll
     for (int ks = 0; ks < kGradTokens / 16; ++ks) {
       const int rb = ks * 16 + 8 * kg;   // this lane's eight tokens of the step

@@ -82,6 +82,9 @@ constexpr int kGradRanks = 64;       // most ranks
 constexpr int kGradChunksMax = 8;    // token chunks (workgroups along M) whose partial sums are added in order
 constexpr int kGradTokens = 32;      // tokens per LDS tile
 constexpr int kGradQStride = 128 + 8, kGradPStride = 3 * kGradRanks + 8;   // u16 per LDS row: 16 bytes of padding shift the banks from row to row
+// RANK_MAJOR: the result is wanted as [r, C] (dA): the MFMA operands change places, so that a lane owns a column
+// and the partial sums leave as partial[chunk][j][c], rows of C contiguous like the final result.
+template <bool RANK_MAJOR>
 __global__ __launch_bounds__(256) void lora_grad_partial_kernel(const uint16_t* __restrict__ ts, int64_t ts_ld, int r,
                                                                 const uint16_t* __restrict__ Q, int64_t ldq, int64_t M, int64_t C,
                                                                 int64_t tokens_per_chunk, float* __restrict__ partial) {
@@ -154,35 +157,51 @@ __global__ __launch_bounds__(256) void lora_grad_partial_kernel(const uint16_t* 
                 bf[e] = lo | (hi << 16);
               }
             }
-            acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af), __builtin_bit_cast(bf16x8, bf), acc[jt], 0, 0, 0);
+            if constexpr (RANK_MAJOR)
+              acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bf), __builtin_bit_cast(bf16x8, af), acc[jt], 0, 0, 0);
+            else
+              acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af), __builtin_bit_cast(bf16x8, bf), acc[jt], 0, 0, 0);
           }
         }
       }
     }
   }
-  // acc[jt][q] = sum for column c0 + 32 wave + 8 (q / 4) + 4 kg + q % 4 and rank 32 jt + n32
+  if constexpr (RANK_MAJOR) {
+    // acc[jt][q] = sum for rank 32 jt + 8 (q / 4) + 4 kg + q % 4 and column c0 + 32 wave + n32
+    const int64_t c = c0 + wave * 32 + n32;
 #pragma unroll
-  for (int jt = 0; jt < 2; ++jt) {
-    const int j = jt * 32 + n32;
+    for (int jt = 0; jt < 2; ++jt)
 #pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const int64_t c = c0 + wave * 32 + 8 * (q >> 2) + 4 * kg + (q & 3);
-      if (c < C && j < r) partial[((int64_t)blockIdx.y * C + c) * kGradRanks + j] = acc[jt][q];
+      for (int q = 0; q < 16; ++q) {
+        const int j = jt * 32 + 8 * (q >> 2) + 4 * kg + (q & 3);
+        if (c < C && j < r) partial[((int64_t)blockIdx.y * kGradRanks + j) * C + c] = acc[jt][q];
+      }
+  } else {
+    // acc[jt][q] = sum for column c0 + 32 wave + 8 (q / 4) + 4 kg + q % 4 and rank 32 jt + n32
+#pragma unroll
+    for (int jt = 0; jt < 2; ++jt) {
+      const int j = jt * 32 + n32;
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int64_t c = c0 + wave * 32 + 8 * (q >> 2) + 4 * kg + (q & 3);
+        if (c < C && j < r) partial[((int64_t)blockIdx.y * C + c) * kGradRanks + j] = acc[jt][q];
+      }
     }
   }
 }
 
-// out = mult * sum over chunks (in chunk order); stored as [C, r] or transposed as [r, C]
+// out = mult * sum over chunks (in chunk order): [C, r] from partial[chunk][c][j], or (rank_major) [r, C] from
+// partial[chunk][j][c]; consecutive threads read and write consecutive elements either way
 __global__ __launch_bounds__(256) void lora_grad_reduce_kernel(const float* __restrict__ partial, int n_chunks, int64_t C, int r,
-                                                               const float* __restrict__ mult, int transposed, float* __restrict__ out) {
+                                                               const float* __restrict__ mult, int rank_major, float* __restrict__ out) {
   const int64_t total = C * r;
   const float s = *mult;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
-    // consecutive threads write consecutive elements of out
-    int64_t c; int j;
-    if (transposed) { j = (int)(i / C); c = i - (int64_t)j * C; } else { c = i / r; j = (int)(i - c * r); }
+    int64_t first, stride;
+    if (rank_major) { first = i; stride = (int64_t)kGradRanks * C; }                       // i = j C + c
+    else { const int64_t c = i / r; first = c * kGradRanks + (i - c * r); stride = C * kGradRanks; }
     float sum = 0.f;
-    for (int z = 0; z < n_chunks; ++z) sum += partial[((int64_t)z * C + c) * kGradRanks + j];
+    for (int z = 0; z < n_chunks; ++z) sum += partial[first + z * stride];
     out[i] = sum * s;
   }
 }
@@ -288,10 +307,10 @@ extern "C" int nvfp4_lora_linear_backward(const void* x, const void* dy, int64_t
   if (r > 0) {
     // the three-term values carry lora_scale / S32; the gradients want lora_scale: one multiplication by S32
     const dim3 blk(256);
-    lora_grad_partial_kernel<<<dim3((unsigned)ceil_div(K, 128), (unsigned)L.n_chunks), blk, 0, st>>>(
+    lora_grad_partial_kernel<true><<<dim3((unsigned)ceil_div(K, 128), (unsigned)L.n_chunks), blk, 0, st>>>(
         tsU, L.ts_ld, (int)r, (const uint16_t*)x, ldx, M, K, L.tokens_per_chunk, part);
     lora_grad_reduce_kernel<<<dim3((unsigned)grid_for(K * r)), blk, 0, st>>>(part, L.n_chunks, K, (int)r, tensor_scale, 1, dA);
-    lora_grad_partial_kernel<<<dim3((unsigned)ceil_div(N, 128), (unsigned)L.n_chunks), blk, 0, st>>>(
+    lora_grad_partial_kernel<false><<<dim3((unsigned)ceil_div(N, 128), (unsigned)L.n_chunks), blk, 0, st>>>(
         tsT, L.ts_ld, (int)r, (const uint16_t*)dy, lddy, M, N, L.tokens_per_chunk, part);
     lora_grad_reduce_kernel<<<dim3((unsigned)grid_for(N * r)), blk, 0, st>>>(part, L.n_chunks, N, (int)r, tensor_scale, 0, dB);
     rc = launch_status();

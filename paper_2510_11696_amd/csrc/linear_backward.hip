@@ -58,17 +58,26 @@ __global__ __launch_bounds__(256) void prepack_t_kernel(const uint8_t* __restric
   }
 }
 
-__global__ void backward_zero_kernel(uint32_t* p, int n) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0u;
-}
-
-// out[c, r] = in[r, c] for a small bf16 matrix (the adapters)
-__global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __restrict__ in, int64_t R, int64_t C, uint16_t* __restrict__ out) {
+// One launch before the products of a call: AT[c, j] = A[j, c] and BT[j, n] = B[n, j] (the adapters change with every
+// optimiser step, so both are transposed per call), and the arrival counters of the K-split down-projections set
+// to zero.  Blocks [0, blocks_a) transpose A, the next blocks_b transpose B, the last block clears the counters.
+__global__ __launch_bounds__(256) void backward_prepare_kernel(const uint16_t* __restrict__ A, int64_t r, int64_t K, uint16_t* __restrict__ AT,
+                                                               const uint16_t* __restrict__ B, int64_t N, uint16_t* __restrict__ BT,
+                                                               int blocks_a, int blocks_b, uint32_t* __restrict__ counters, int n_counters) {
+  int b = blockIdx.x;
+  if (b >= blocks_a + blocks_b) {
+    for (int i = threadIdx.x; i < n_counters; i += 256) counters[i] = 0u;
+    return;
+  }
+  const uint16_t* in = A;
+  uint16_t* out = AT;
+  int64_t R = r, C = K;           // in is [R, C], out [C, R]
+  int blocks = blocks_a;
+  if (b >= blocks_a) { b -= blocks_a; in = B; out = BT; R = N; C = r; blocks = blocks_b; }
   const int64_t total = R * C;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
-    const int64_t c = i / R, r = i - c * R;        // consecutive threads write consecutive elements of out
-    out[i] = in[r * C + c];
+  for (int64_t i = (int64_t)b * 256 + threadIdx.x; i < total; i += (int64_t)blocks * 256) {
+    const int64_t c = i / R, rr = i - c * R;       // consecutive threads write consecutive elements of out
+    out[i] = in[rr * C + c];
   }
 }
 
@@ -281,9 +290,9 @@ extern "C" int nvfp4_lora_linear_backward(const void* x, const void* dy, int64_t
   float* part = (float*)(ws + L.part_off);
   int rc = QERL_OK;
   if (r > 0) {
-    backward_zero_kernel<<<dim3(1), dim3(kDownMaxSlots), 0, st>>>((uint32_t*)(ws + L.ctr_off), kDownMaxSlots);
-    transpose_bf16_kernel<<<dim3((unsigned)grid_for(r * K)), dim3(256), 0, st>>>((const uint16_t*)A, r, K, AT);
-    transpose_bf16_kernel<<<dim3((unsigned)grid_for(N * r)), dim3(256), 0, st>>>((const uint16_t*)B, N, r, BT);
+    const int blocks_a = grid_for(r * K), blocks_b = grid_for(N * r);
+    backward_prepare_kernel<<<dim3((unsigned)(blocks_a + blocks_b + 1)), dim3(256), 0, st>>>(
+        (const uint16_t*)A, r, K, AT, (const uint16_t*)B, N, BT, blocks_a, blocks_b, (uint32_t*)(ws + L.ctr_off), kDownMaxSlots);
     if ((rc = launch_status()) != QERL_OK) return rc;
     // U = dY B and t = x A^T, each as three bf16 terms of (lora_scale / S32) times the product
     GemmArgs d{};

@@ -84,9 +84,14 @@ class Stack:
             L.z_post = self.noise[(2 * i + 1) * hidden:(2 * i + 2) * hidden]
         self.passes = 0
         by = {s.name: s for s in cfg["linears"]}
+        # a decoder block (q, k, v, o, gate, up, down), or any other list of linears run one after the other
+        self.block = all(n in by for n in ("q", "k", "v", "o", "gate", "up", "down"))
+        groups = (("q", "k", "v"), ("gate", "up")) if self.block else ()
         need = max([qerl.nvfp4_lora_linear_workspace_bytes(M, s.N, s.K, cfg["r"]) for s in cfg["linears"]]
                    + [qerl.nvfp4_lora_linear_workspace_bytes(M, sum(by[n].N for n in g), by[g[0]].K, cfg["r"] * len(g))
-                      for g in (("q", "k", "v"), ("gate", "up"))])
+                      for g in groups])
+        if swiglu and not self.block:
+            raise SystemExit("--swiglu needs a configuration with gate, up and down projections")
         if swiglu:
             need = max(need, qerl.load_library().nvfp4_lora_linear_swiglu_workspace_bytes(M, by["down"].N, by["down"].K, cfg["r"]))
         self.ws = qerl.Workspace(need)
@@ -116,6 +121,14 @@ class Stack:
         # (a captured step replays with the subsequence it was recorded with: same cost, same values)
         qerl.aqn_noise_fill(self.noise.numel(), self.sigma, qs.seed_for(0, 0), self.passes, out=self.noise)
         self.passes += 1
+        if not self.block:
+            for L in self.layers:
+                for shp in self.cfg["linears"]:
+                    if shp.K == self.cfg["hidden"]:
+                        self.norm_group(L, (shp.name,), L.gain_in, L.z_in)
+                    else:
+                        self.linear(L, shp.name, self.act)
+            return
         for L in self.layers:
             self.norm_group(L, ("q", "k", "v"), L.gain_in, L.z_in)
             self.linear(L, "o", self.attn)
@@ -172,7 +185,7 @@ def dominant_kernel_roofline(stack: Stack, reps: int):
     the step.  M > 16: the gate_proj call (the small lora_down32_kernel launch belongs to it)."""
     by = {s.name: s for s in stack.cfg["linears"]}
     if stack.M <= 16:
-        names = ("gate", "up")
+        names = ("gate", "up") if stack.block else (stack.cfg["linears"][0].name,)
         for L in stack.layers[:1]:          # any valid t will do for timing: it only feeds the up-projection
             stack.norm_group(L, names, L.gain_post, L.z_post)
         ts = [stack.t[n] for n in names]
@@ -183,7 +196,7 @@ def dominant_kernel_roofline(stack: Stack, reps: int):
                 qerl.nvfp4_lora_linear_packed_group(stack.xn, list(ws), list(As), list(Bs),
                                                     [stack.lora_scale] * len(names), workspace=stack.ws,
                                                     outs=[stack.out[n] for n in names], ts=ts)
-        shape = {"name": "gate+up", "N": sum(by[n].N for n in names), "K": by["gate"].K, "M": stack.M}
+        shape = {"name": "+".join(names), "N": sum(by[n].N for n in names), "K": by[names[0]].K, "M": stack.M}
         bytes_per_launch = sum(by[n].packed_bytes for n in names)
     else:
         shp = max(stack.cfg["linears"], key=lambda s: (s.packed_bytes, s.name == "gate"))
@@ -199,7 +212,7 @@ def dominant_kernel_roofline(stack: Stack, reps: int):
     common = {"shape": shape, "us_per_launch": round(ms * 1e3, 2),
               "note": "one call per launch slot, back to back over the layers' distinct weights, launch gaps included"}
     if stack.M <= 128:
-        kernel = "stream_kernel" if stack.M <= 16 else "gemm32_kernel"
+        kernel = "stream_kernel" if stack.M <= 16 else "mid_kernel"
         achieved = bytes_per_launch / (ms * 1e-3) / 1e9
         return {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4),

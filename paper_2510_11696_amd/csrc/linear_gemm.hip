@@ -359,17 +359,15 @@ __global__ __launch_bounds__(256) void lora_down64_kernel(const GemmArgs a, cons
     row = row < rN ? row : rN - 1;
     asrc[i] = A + (int64_t)row * a.K;
   }
-  struct Slab { u32x4 x[2]; u32x4 w[T]; };
-  // slabs past the part's end contribute nothing: their x is zeroed (the address is redirected into the row)
+  struct Slab { u32x4 x[2]; u32x4 w[T]; bool in; };
+  // slabs past the part's end contribute nothing: their x is zeroed on its way to LDS (the address is redirected
+  // into the row; nothing here touches the loaded value, which would wait for it)
   auto load = [&](Slab& sl, int s) {
     int64_t k = k_lo + (int64_t)s * 64 + lchunk * 8;
-    const bool in = k < k_hi;
+    sl.in = k < k_hi;
     k = k < a.K - 8 ? k : a.K - 8;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      u32x4 v = *reinterpret_cast<const u32x4*>(xsrc[i] + k);
-      sl.x[i] = in ? v : u32x4{0u, 0u, 0u, 0u};
-    }
+    for (int i = 0; i < 2; ++i) sl.x[i] = *reinterpret_cast<const u32x4*>(xsrc[i] + k);
 #pragma unroll
     for (int i = 0; i < T; ++i) sl.w[i] = *reinterpret_cast<const u32x4*>(asrc[i] + k);
   };
@@ -378,7 +376,7 @@ __global__ __launch_bounds__(256) void lora_down64_kernel(const GemmArgs a, cons
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int row = lrow + 32 * i;
-      base[row * 8 + (lchunk ^ ((row >> 1) & 7))] = sl.x[i];
+      base[row * 8 + (lchunk ^ ((row >> 1) & 7))] = sl.in ? sl.x[i] : u32x4{0u, 0u, 0u, 0u};
     }
 #pragma unroll
     for (int i = 0; i < T; ++i) {
@@ -417,7 +415,9 @@ __global__ __launch_bounds__(256) void lora_down64_kernel(const GemmArgs a, cons
       for (int u = 0; u < D; ++u) {
         const int buf = (s0 + u) & 1;   // consecutive slabs alternate (D may be odd)
         to_lds(buf, ring[u]);
+        __builtin_amdgcn_sched_barrier(0);   // the requests stay here, D slabs ahead of their use
         load(ring[u], s0 + u + D);
+        __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
         compute(buf);
       }

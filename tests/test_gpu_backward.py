@@ -66,6 +66,7 @@ def _check_f32(got, ref, what):
     (130, 1000, 2112, 32),       # two token blocks, ragged everywhere
     (200, 64, 3584, 64),         # the largest rank
     (300, 3584, 512, 32),        # the 7B k/v projection
+    (520, 520, 1024, 64),        # 64-token down-projection kernel: nine token blocks (the last of 8 tokens), two rank tiles, a contraction (520) that ends inside a slab
     (64, 256, 256, 0),           # no adapter: dX only
     (16, 8, 256, 0), (16, 8, 256, 8),   # a contraction of eight rows
 ])

@@ -323,6 +323,62 @@ def backward_bench(args):
     }))
 
 
+def mx_bench(args):
+    """--mx: the MXFP4 variant's linear (x quantised to MXFP8, block-scaled matrix instruction) over the linears
+    of a few layers of the configuration, no adapters; one JSON line in the same format."""
+    cfg = qs.CONFIGS[args.config]
+    M = args.M or cfg["M"][0]
+    n_layers = args.layers or 2
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(qs.seed_for(args.config, 2))
+    lib = qerl.load_library()
+    lin, need = [], 0
+    for _ in range(n_layers):
+        for shp in cfg["linears"]:
+            W = (torch.randn((shp.N, shp.K), generator=gen, device="cuda", dtype=torch.float32) * 0.02).to(torch.bfloat16)
+            codes, scales = qerl.mxfp4_quantize(W)
+            lin.append((shp, qerl.mxfp4_prepack(codes, scales)))
+            del W, codes, scales
+            need = max(need, lib.mxfp4_linear_native_workspace_bytes(M, shp.N, shp.K))
+    xs = {k: torch.randn((M, k), generator=gen, device="cuda").to(torch.bfloat16) for k in {s.K for s, _ in lin}}
+    ys = {n: torch.empty((M, n), dtype=torch.bfloat16, device="cuda") for n in {s.N for s, _ in lin}}
+    ws = torch.empty((need + 256,), dtype=torch.uint8, device="cuda")
+
+    def sweep():
+        for shp, pw in lin:
+            qerl.mxfp4_linear_native(xs[shp.K], pw, workspace=ws, out=ys[shp.N])
+    step = sweep if args.eager else capture(sweep)
+    for _ in range(args.warmup):
+        step()
+    ms = timed(step, args.steps)
+    packed = sum(s.N * s.K * 17 // 32 for s, _ in lin)          # 4 bits per weight + one scale byte per 32
+    flops = sum(2 * M * s.N * s.K for s, _ in lin)
+    shp, pw = max(lin, key=lambda e: e[0].N * e[0].K)
+    one = lambda: qerl.mxfp4_linear_native(xs[shp.K], pw, workspace=ws, out=ys[shp.N])
+    one()
+    us = timed(one, max(3, args.steps)) * 1e3
+    if M <= 32:      # weight streaming: HBM bound
+        value, unit, metric = packed / (ms * 1e-3) / 1e9, "GB/s", "MXFP4 linear (MXFP8 activations): packed-weight GB/s"
+        ach = shp.N * shp.K * 17 // 32 / (us * 1e-6) / 1e9
+        roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
+                "traffic": None, "kernel": "mx_native_kernel", "algorithmic_bytes_per_launch": shp.N * shp.K * 17 // 32}
+    else:            # GEMM on the scaled FP8 x FP4 instruction; measured against the FP8 peak the instruction is listed under
+        value, unit, metric = flops / (ms * 1e-3) / 1e12, "TFLOP/s", "MXFP4 linear (MXFP8 activations): TFLOP/s (2*M*N*K)"
+        ach = 2 * M * shp.N * shp.K / (us * 1e-6) / 1e12
+        roof = {"bound": "mfma", "achieved": round(ach, 1), "peak": 5000.0, "unit": "TFLOP/s", "frac": round(ach / 5000.0, 4),
+                "traffic": None, "kernel": "mx_gemm_kernel (after mxfp8 quantisation of x)", "algorithmic_flops_per_launch": 2 * M * shp.N * shp.K}
+    roof.update({"shape": {"name": shp.name, "N": shp.N, "K": shp.K, "M": M}, "us_per_launch": round(us, 2),
+                 "note": "one call (activation quantisation + multiply), eager"})
+    print(json.dumps({
+        "metric": metric, "value": round(value, 1), "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp8(e4m3)*e8m0 x fp4(e2m1)*e8m0 -> fp32 accumulate", "data": "synthetic",
+        "config": {"workload": f"config {args.config}: MXFP4 variant of {cfg['model']}-shaped decoder linears, {n_layers} layers, "
+                               f"M={M}, no adapters; " + ("eager launches" if args.eager else "one HIP graph replay per step")},
+        "roofline": roof,
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -333,6 +389,8 @@ def main():
     ap.add_argument("--layers", type=int, default=None)
     ap.add_argument("--backward", action="store_true",
                     help="time the backward pass (dX, dA, dB) of the configuration's linears at its prefill size instead of the forward step")
+    ap.add_argument("--mx", action="store_true",
+                    help="time the MXFP4 variant's linear (MXFP8 activations, block-scaled matrix instruction) over the configuration's linears")
     ap.add_argument("--swiglu", action="store_true",
                     help="the down projection reads SiLU(gate) (.) up from the gate/up outputs (fused into its launch at M <= 16) instead of a resident input")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -359,6 +417,9 @@ def main():
         return
     if args.backward:
         backward_bench(args)
+        return
+    if args.mx:
+        mx_bench(args)
         return
     cfg = qs.CONFIGS[args.config]
     M = args.M or cfg["M"][0]

@@ -75,8 +75,8 @@ class Stack:
         self.out = {s.name: torch.empty((M, s.N), dtype=torch.bfloat16, device="cuda") for s in cfg["linears"]}
         self.t = {s.name: torch.empty((8, M, cfg["r"]), dtype=torch.float32, device="cuda") for s in cfg["linears"]}
         self.lora_scale = cfg["alpha"] / cfg["r"]
-        # the noise vectors of all RMSNorms in one buffer: one generator launch per forward pass (Section 3.3:
-        # the vector is resampled for each forward pass)
+        # the noise vectors of all RMSNorms in one buffer: one generator launch per forward pass, which draws
+        # every vector anew (Section 3.3, "Adaptive Quantization Noise")
         self.sigma = qerl.aqn_sigma(1, 10, 1e-2, 5e-4)
         self.noise = torch.empty((2 * self.n_layers * hidden,), dtype=torch.float32, device="cuda")
         for i, L in enumerate(self.layers):

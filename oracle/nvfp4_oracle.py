@@ -28,7 +28,7 @@ What each function follows
 * Gated input of the down projection, SiLU(gate) (.) up: the feed-forward
   block of the architectures the paper adapts (Preliminary, "Low-rank
   Adaptation" names W_gate, W_up, W_down); reading stated at silu_mul.
-* Noise vector Z ~ N(0, sigma^2 I), resampled for each forward pass: Section
+* Noise vector Z ~ N(0, sigma^2 I), drawn anew per forward pass: Section
   3.3, "Adaptive Quantization Noise".  The paper fixes the distribution, not
   the generator; aqn_noise_philox states the counter-based construction both
   sides of this build implement.
@@ -184,6 +184,14 @@ def nvfp4_dequantize(codes, scales, tensor_scale):
     return (np.float32(tensor_scale) * inner).astype(np.float32)
 
 
+def lora_down_projection(x, A, acc_dtype=np.float64):
+    """t[M,r] = x . A^T: the inner factor of the low-rank branch B A x (Eq. 2), in
+    `acc_dtype`, not rounded.  x[M,K], A[r,K] hold bf16 values in float32."""
+    x = np.asarray(x, dtype=np.float32).astype(acc_dtype)
+    A = np.asarray(A, dtype=np.float32).astype(acc_dtype)
+    return x @ A.T
+
+
 def nvfp4_lora_linear(x, codes, scales, tensor_scale, A=None, B=None,
                       lora_scale=0.0, acc_dtype=np.float64, bias=None):
     """y[M,N] = x . W_hat^T + lora_scale * (x . A^T) . B^T (+ bias[N])     (Eq. 2 + Eq. 6)
@@ -202,9 +210,8 @@ def nvfp4_lora_linear(x, codes, scales, tensor_scale, A=None, B=None,
     W_hat = nvfp4_dequantize(codes, scales, tensor_scale).astype(acc_dtype)
     y = x @ W_hat.T
     if A is not None and B is not None and np.asarray(A).shape[0] > 0:
-        A = np.asarray(A, dtype=np.float32).astype(acc_dtype)
         B = np.asarray(B, dtype=np.float32).astype(acc_dtype)
-        t = x @ A.T
+        t = lora_down_projection(x, A, acc_dtype)
         y = y + acc_dtype(lora_scale) * (t @ B.T)
     if bias is not None:
         y = y + np.asarray(bias, dtype=np.float32).astype(acc_dtype)[None, :]

@@ -1,5 +1,5 @@
 // Adaptive Quantization Noise on the device: the noise vector of Section 3.3
-//   Z ~ N(0, sigma^2 I), "resampled for each forward pass",
+//   Z ~ N(0, sigma^2 I), drawn anew per forward pass (Section 3.3, "Adaptive Quantization Noise"),
 // and the sigma decay curves of the scheduler ablation (Eq. 8 for the exponential one).
 //
 // aqn_noise_fill writes Z for any number of RMSNorm gains in one launch (a model keeps the vectors

@@ -30,17 +30,6 @@
 
 namespace qerl {
 
-__device__ __forceinline__ void split3_bf16(const float (&v)[8], u32x4& hi, u32x4& mid, u32x4& lo) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint32_t h = pack_bf16x2(v[2 * i], v[2 * i + 1]);
-    const float r0 = v[2 * i] - bf16_bits_to_f32(h & 0xffffu), r1 = v[2 * i + 1] - __uint_as_float(h & 0xffff0000u);
-    const uint32_t m = pack_bf16x2(r0, r1);
-    const float q0 = r0 - bf16_bits_to_f32(m & 0xffffu), q1 = r1 - __uint_as_float(m & 0xffff0000u);
-    hi[i] = h; mid[i] = m; lo[i] = pack_bf16x2(q0, q1);
-  }
-}
-
 constexpr int kGemmRing = 4;    // stages of weights in registers per wave (even)
 constexpr int kGemmXAhead = 2;  // x slabs in registers (divides kGemmRing)
 

@@ -46,25 +46,6 @@ __device__ __forceinline__ bf16x8 stream_e2m1x8(uint32_t codes) {
              __builtin_bit_cast(uint32_t, p2), __builtin_bit_cast(uint32_t, p3)};
   return __builtin_bit_cast(bf16x8, o);
 }
-__device__ __forceinline__ float stream_e4m3(uint32_t v, int b) {
-  switch (b) {
-    case 0: return __builtin_amdgcn_cvt_f32_fp8(v, 0);
-    case 1: return __builtin_amdgcn_cvt_f32_fp8(v, 1);
-    case 2: return __builtin_amdgcn_cvt_f32_fp8(v, 2);
-    default: return __builtin_amdgcn_cvt_f32_fp8(v, 3);
-  }
-}
-__device__ __forceinline__ void stream_split3(const float (&v)[8], u32x4& hi, u32x4& mid, u32x4& lo) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint32_t h = pack_bf16x2(v[2 * i], v[2 * i + 1]);
-    const float r0 = v[2 * i] - bf16_bits_to_f32(h & 0xffffu), r1 = v[2 * i + 1] - __uint_as_float(h & 0xffff0000u);
-    const uint32_t m = pack_bf16x2(r0, r1);
-    const float q0 = r0 - bf16_bits_to_f32(m & 0xffffu), q1 = r1 - __uint_as_float(m & 0xffff0000u);
-    hi[i] = h; mid[i] = m; lo[i] = pack_bf16x2(q0, q1);
-  }
-}
-
 // Optional timeline stamps for tuning (build with -DQERL_STREAM_TRACE): eight 100 MHz time stamps per wave
 // of the first 512 workgroups, read back with qerl_debug_read_trace().
 #ifdef QERL_STREAM_TRACE
@@ -401,7 +382,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
             const bf16x8 w = stream_e2m1x8(j + 1 < 4 ? t.c0[(j + 1) & 3] : t.c1[(j + 1) & 3]);
             tmp[(j + 1) & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, w, zero, 0, 0, 0);
           }
-          const float s = stream_e4m3(t.sc[j >> 2], j & 3);
+          const float s = e4m3_byte_f32(t.sc[j >> 2], j & 3);
 #pragma unroll
           for (int q = 0; q < MR; ++q) acc[q] = __builtin_fmaf(s, tmp[j & 1][q], acc[q]);
         }
@@ -487,7 +468,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
   // all parts of a group in flight together -- added in part order, and left in LDS as [token][rank]; from
   // there each lane takes its MFMA operand rows and splits the fp32 values into three bf16 terms (exact to
   // 2^-24 relative).  The partials were written through to memory before this wave looks (kernel boundary, or
-  // the producers' count), and no cache can hold an older copy: ordinary loads suffice.
+  // the producers' count followed by an agent-scope acquire fence): ordinary loads suffice.
   float* tsum = reinterpret_cast<float*>(smem + a.tsum_off);               // [M][r] of the current member
   uint16_t* ytile = reinterpret_cast<uint16_t*>(smem + a.tsum_off + 16 * 64 * 4);   // [16 tokens][32 rows] bf16, output staging
   auto load_t = [&](int mi) {
@@ -518,7 +499,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
         tv[4] = t1[0]; tv[5] = t1[1]; tv[6] = t1[2]; tv[7] = t1[3];
         if (poisoned) tv[0] = __uint_as_float(0x7fc00000u);   // the hand-over timed out: make it visible
       }
-      stream_split3(tv, th[s], tm[s], tl[s]);
+      split3_bf16(tv, th[s], tm[s], tl[s]);
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // ... and read before the next member overwrites them
     t_member = mi;
@@ -588,7 +569,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
         __builtin_amdgcn_s_sleep(32);
       }
       if (!t_ready) continue;
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // the producers' partials were written by other workgroups: once per launch
       QTRACE(6);
     }
     // the bias of this lane's output row, requested before the LoRA arithmetic that hides its latency; the

@@ -304,7 +304,7 @@ def test_norm_with_lora_down_feeds_grouped_linear(M, H, Ns, rs, sigma):
     assert bf16_ulp_distance(y_plain, ref_y).max() <= 1
     y64 = y.float().cpu().numpy().astype(np.float64)
     for (codes, scales, ts, A, B), t_gpu in zip(W_q, ts_gpu):
-        t_ref = y64 @ A.float().numpy().astype(np.float64).T
+        t_ref = oracle.lora_down_projection(y.float().cpu().numpy(), A.float().numpy())   # Eq. 2's inner factor on the y the kernel wrote
         bound = 4 * H * 2.0 ** -24 * (np.abs(y64) @ np.abs(A.float().numpy().astype(np.float64)).T) + 1e-30
         assert tuple(t_gpu.shape) == (8, M, A.shape[0])
         assert (np.abs(t_gpu.cpu().numpy().astype(np.float64).sum(0) - t_ref) <= bound).all()

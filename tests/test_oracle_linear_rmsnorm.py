@@ -40,6 +40,27 @@ def test_linear_brute_force_python_loops(N, K, M, r):
             assert abs(y[m, n] - want) <= 1e-12 * (1 + abs(want))
 
 
+def test_lora_down_projection_by_loops_one_hot_and_exact_integers():
+    """t = x A^T, the inner factor of Eq. 2's low-rank branch: Python loops; a one-hot token reads out a
+    column of A exactly; small-integer operands give exactly representable sums whatever the order."""
+    W, x, A, B = _tiny(4, 48, 3, 3, seed=33)
+    t = o.lora_down_projection(x, A)
+    assert t.shape == (3, 3) and t.dtype == np.float64
+    for m in range(3):
+        for j in range(3):
+            want = sum(float(x[m, k]) * float(A[j, k]) for k in range(48))
+            assert abs(t[m, j] - want) <= 1e-13 * (1 + abs(want))
+    x1 = np.zeros((1, 48), dtype=np.float32)
+    x1[0, 17] = 1.0
+    assert np.array_equal(o.lora_down_projection(x1, A)[0], A[:, 17].astype(np.float64))
+    rng = np.random.default_rng(5)
+    xi = rng.integers(-8, 9, size=(2, 32)).astype(np.float32)
+    Ai = rng.integers(-8, 9, size=(5, 32)).astype(np.float32)
+    assert np.array_equal(o.lora_down_projection(xi, Ai), (xi.astype(np.int64) @ Ai.astype(np.int64).T).astype(np.float64))
+    # not transposed, not the outer factor: a [r, K] operand with r != M gives [M, r]
+    assert o.lora_down_projection(xi, Ai).shape == (2, 5)
+
+
 def test_one_hot_input_reads_out_a_weight_column():
     W, x, A, B = _tiny(6, 32, 1, 0, seed=5)
     codes, scales, S32 = o.nvfp4_quantize(W)

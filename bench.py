@@ -1,19 +1,20 @@
 """Benchmark of the NVFP4 + LoRA linear hot path on one MI355X.
 
-A step is one decode pass of batch M through the linear stack of every decoder
-layer of the model (default: Qwen2.5-7B shapes, 28 layers, M = 8, LoRA r = 32):
-per layer  aqn_rmsnorm -> {q, k, v} -> o -> aqn_rmsnorm -> {gate, up} -> down
-(linears in braces share their input and go out as one grouped call; at decode
-sizes the norm's launch also computes their LoRA down-projections),
-all on NVFP4 weights that are resident in HBM and distinct per layer, so one
-step streams 28 x 131 MB = 3.67 GB of packed weights and nothing is served
-from a cache that would not be there in a rollout.  Attention and SiLU*mul are
-not part of this library; o and down read fixed synthetic activations.
+Default workload: BASELINE configuration 5 -- the Qwen2.5-32B-shaped linear stack, all 64 layers' NVFP4
+weights resident in HBM and distinct (17.55 GB packed, so nothing is served from a cache that a rollout would not
+have), LoRA r = 64 on all seven projections, an AQN RMSNorm before q/k/v and before gate/up.  A step is one pass
+of M tokens through every layer's linears:
+    per layer  aqn_rmsnorm -> {q, k, v} -> o -> aqn_rmsnorm -> {gate, up} -> down
+(linears in braces share their input and go out as one grouped call; at decode sizes the norm's launch also
+computes their LoRA down-projections).  Attention is not part of this library; o reads a fixed synthetic
+activation, and so does down unless --swiglu makes it read SiLU(gate) * up.
 
-Prints ONE JSON line: whole-step weight-GB/s as `value`, the roofline of the
-dominant kernel (at decode sizes the grouped gate_proj + up_proj launch)
-measured live with events on the launch stream, and the CPU oracle timed on a
-bounded sample.
+Prints ONE JSON line.  `value` is the whole-step packed-weight GB/s of the headline leg (decode, M = 16);
+`legs` carries the other token counts of the configuration (M = 1, 128: GB/s; M = 4096: TFLOP/s), each with the
+roofline of its dominant kernel measured live with events on the launch stream; `achievable` holds what a
+nothing-but-loads kernel and a nothing-but-MFMA kernel reach on this machine (--no-peaks skips them); `cpu_baseline`
+is the oracle timed on a bounded sample on the host cores.  --config 2/3/4 and --M select the other
+configurations (one leg).
 """
 from __future__ import annotations
 
@@ -54,18 +55,47 @@ class Layer:
             self.lin[shp.name] = (packed, A, B)
         self.gain_in = (1 + 0.05 * torch.randn(hidden, generator=gen, device="cuda")).to(torch.bfloat16)
         self.gain_post = (1 + 0.05 * torch.randn(hidden, generator=gen, device="cuda")).to(torch.bfloat16)
-        self.z_in = self.z_post = None     # views into the stack's noise buffer, refilled on the device every step
+        self.z_in = self.z_post = None     # views into the model's noise buffer, refilled on the device every step
+
+
+class Weights:
+    """Every layer's frozen tensors of a configuration, generated and quantised on the device, plus the noise
+    buffer of all its RMSNorms.  Shared by the legs (token counts) of a run."""
+
+    def __init__(self, config_no: int, layers: int | None = None):
+        cfg = qs.CONFIGS[config_no]
+        self.config_no, self.cfg = config_no, cfg
+        self.n_layers = layers or cfg["layers"]
+        self.gen = torch.Generator(device="cuda")
+        self.gen.manual_seed(qs.seed_for(config_no, 0))
+        t0 = time.perf_counter()
+        self.layers = []
+        for i in range(self.n_layers):
+            self.layers.append(Layer(cfg, i, self.gen, config_no))
+            if i % 16 == 15:
+                torch.cuda.synchronize()
+                print(f"bench.py: {i + 1} of {self.n_layers} layers quantised and packed "
+                      f"({time.perf_counter() - t0:.0f} s)", file=sys.stderr, flush=True)
+        hidden = cfg["hidden"]
+        # the noise vectors of all RMSNorms in one buffer: one generator launch per forward pass, which draws
+        # every vector anew (Section 3.3, "Adaptive Quantization Noise")
+        self.sigma = qerl.aqn_sigma(1, 10, 1e-2, 5e-4)
+        self.noise = torch.empty((2 * self.n_layers * hidden,), dtype=torch.float32, device="cuda")
+        for i, L in enumerate(self.layers):
+            L.z_in = self.noise[(2 * i) * hidden:(2 * i + 1) * hidden]
+            L.z_post = self.noise[(2 * i + 1) * hidden:(2 * i + 2) * hidden]
+        self.packed_bytes_per_layer = sum(s.packed_bytes for s in cfg["linears"])
 
 
 class Stack:
-    def __init__(self, config_no: int, M: int, layers: int | None = None, swiglu: bool = False):
-        cfg = qs.CONFIGS[config_no]
-        self.cfg, self.M = cfg, M
-        self.swiglu = swiglu
-        self.n_layers = layers or cfg["layers"]
-        gen = torch.Generator(device="cuda")
-        gen.manual_seed(qs.seed_for(config_no, 0))
-        self.layers = [Layer(cfg, i, gen, config_no) for i in range(self.n_layers)]
+    """Activations, outputs and workspace for M tokens on a model's weights, and the step over its layers."""
+
+    def __init__(self, weights: Weights, M: int, swiglu: bool = False, eager: bool = False):
+        cfg = weights.cfg
+        self.w, self.cfg, self.M = weights, cfg, M
+        self.swiglu, self.eager = swiglu, eager
+        self.n_layers, self.layers = weights.n_layers, weights.layers
+        gen = weights.gen
         hidden = cfg["hidden"]
         inter = max(s.K for s in cfg["linears"])
         self.h = torch.randn((M, hidden), generator=gen, device="cuda").to(torch.bfloat16)
@@ -75,13 +105,6 @@ class Stack:
         self.out = {s.name: torch.empty((M, s.N), dtype=torch.bfloat16, device="cuda") for s in cfg["linears"]}
         self.t = {s.name: torch.empty((8, M, cfg["r"]), dtype=torch.float32, device="cuda") for s in cfg["linears"]}
         self.lora_scale = cfg["alpha"] / cfg["r"]
-        # the noise vectors of all RMSNorms in one buffer: one generator launch per forward pass, which draws
-        # every vector anew (Section 3.3, "Adaptive Quantization Noise")
-        self.sigma = qerl.aqn_sigma(1, 10, 1e-2, 5e-4)
-        self.noise = torch.empty((2 * self.n_layers * hidden,), dtype=torch.float32, device="cuda")
-        for i, L in enumerate(self.layers):
-            L.z_in = self.noise[(2 * i) * hidden:(2 * i + 1) * hidden]
-            L.z_post = self.noise[(2 * i + 1) * hidden:(2 * i + 2) * hidden]
         self.passes = 0
         by = {s.name: s for s in cfg["linears"]}
         # a decoder block (q, k, v, o, gate, up, down), or any other list of linears run one after the other
@@ -95,7 +118,7 @@ class Stack:
         if swiglu:
             need = max(need, qerl.load_library().nvfp4_lora_linear_swiglu_workspace_bytes(M, by["down"].N, by["down"].K, cfg["r"]))
         self.ws = qerl.Workspace(need)
-        self.packed_bytes_per_layer = sum(s.packed_bytes for s in cfg["linears"])
+        self.packed_bytes_per_layer = weights.packed_bytes_per_layer
         self.flops_per_layer = sum(2 * M * s.N * s.K for s in cfg["linears"])
 
     def linear(self, layer, name, x):
@@ -119,7 +142,7 @@ class Stack:
 
     def step(self):
         # (a captured step replays with the subsequence it was recorded with: same cost, same values)
-        qerl.aqn_noise_fill(self.noise.numel(), self.sigma, qs.seed_for(0, 0), self.passes, out=self.noise)
+        qerl.aqn_noise_fill(self.w.noise.numel(), self.w.sigma, qs.seed_for(0, 0), self.passes, out=self.w.noise)
         self.passes += 1
         if not self.block:
             for L in self.layers:
@@ -166,8 +189,10 @@ def timed(fn, iters):
     return start.elapsed_time(stop) / iters
 
 
-def measured_traffic(kernel: str, shape_name: str, M: int):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summaries (profiles/traffic.json), or None."""
+def measured_traffic(kernel: str, config_no: int, shape_name: str, M: int):
+    """HBM bytes per launch (fetched + written) from the committed rocprofv3 --pmc summaries
+    (profiles/traffic.json: key -> {"bytes", "kernel_source", "source_sha256_16", "measured_at_commit"}), or None.
+    A warning goes to stderr when the kernel's source file is not the one the table was measured with."""
     path = os.path.join(ROOT, "profiles", "traffic.json")
     if not os.path.exists(path):
         return None
@@ -175,7 +200,16 @@ def measured_traffic(kernel: str, shape_name: str, M: int):
         table = json.load(open(path))
     except Exception:
         return None
-    return table.get(f"{kernel}:{shape_name}:M{M}")
+    e = table.get(f"{kernel}:config{config_no}:{shape_name}:M{M}")
+    if not isinstance(e, dict):
+        return None
+    src = os.path.join(ROOT, "paper_2510_11696_amd", "csrc", e.get("kernel_source", ""))
+    if os.path.isfile(src):
+        import hashlib
+        if hashlib.sha256(open(src, "rb").read()).hexdigest()[:16] != e.get("source_sha256_16"):
+            print(f"bench.py: {e.get('kernel_source')} has changed since profiles/traffic.json was measured "
+                  f"(commit {e.get('measured_at_commit')}): roofline.traffic may be stale", file=sys.stderr)
+    return e.get("bytes")
 
 
 def dominant_kernel_roofline(stack: Stack, reps: int):
@@ -216,13 +250,13 @@ def dominant_kernel_roofline(stack: Stack, reps: int):
         achieved = bytes_per_launch / (ms * 1e-3) / 1e9
         return {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": measured_traffic(kernel, shape["name"], stack.M), "kernel": kernel,
+                "traffic": measured_traffic(kernel, stack.w.config_no, shape["name"], stack.M), "kernel": kernel,
                 "algorithmic_bytes_per_launch": bytes_per_launch, **common}
     flops = 2 * stack.M * shape["N"] * shape["K"]
     achieved = flops / (ms * 1e-3) / 1e12
     return {"bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
-            "traffic": measured_traffic("gemm32_kernel", shape["name"], stack.M), "kernel": "gemm32_kernel",
+            "traffic": measured_traffic("gemm32_kernel", stack.w.config_no, shape["name"], stack.M), "kernel": "gemm32_kernel",
             "algorithmic_flops_per_launch": flops, **common}
 
 
@@ -379,13 +413,79 @@ def mx_bench(args):
     }))
 
 
+def measure_peaks():
+    """What a kernel that does nothing else reaches on this machine: a streaming read of 4 GiB (far beyond the
+    256 MiB memory-side cache) and a loop of nothing but v_mfma_f32_32x32x16_bf16.  Best of a few launch shapes."""
+    lib = qerl.load_library()
+    st = torch.cuda.current_stream().cuda_stream
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+    nbytes = 4 << 30
+    buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    buf.view(torch.int32).random_(0, 1 << 30)
+    best_read, shape_read = 0.0, None
+    for wgs, kib in ((256, 8), (256, 16), (512, 8), (512, 16), (1024, 8), (1024, 4)):
+        fn = lambda: lib.qerl_peak_stream_read(buf.data_ptr(), nbytes, wgs, kib, sink.data_ptr(), st)
+        assert fn() == 0
+        ms = timed(fn, 3)
+        gbs = nbytes / (ms * 1e-3) / 1e9
+        if gbs > best_read:
+            best_read, shape_read = gbs, f"{wgs} workgroups x 8 waves, {kib} KiB in flight per wave"
+    del buf
+    ops = torch.randn(1024, device="cuda").to(torch.bfloat16)          # 2 KiB of real bf16 bit patterns
+    best_mfma, shape_mfma = 0.0, None
+    for wgs in (256, 512):
+        iters = 20000
+        fn = lambda: lib.qerl_peak_mfma_bf16(ops.data_ptr(), wgs, iters, sink.data_ptr(), st)
+        assert fn() == 0
+        ms = timed(fn, 3)
+        tf = wgs * 4 * iters * 8 * 32768 / (ms * 1e-3) / 1e12
+        if tf > best_mfma:
+            best_mfma, shape_mfma = tf, f"{wgs} workgroups x 4 waves, 8 accumulators each, Gaussian bf16 operands"
+    return {"hbm_read_GBps": round(best_read, 1), "hbm_read_shape": shape_read,
+            "mfma_bf16_TFLOPs": round(best_mfma, 1), "mfma_shape": shape_mfma,
+            "note": "measured in this run by qerl_peak_stream_read (4 GiB) / qerl_peak_mfma_bf16"}
+
+
+def run_leg(weights: Weights, M: int, args, steps: int, warmup: int, peaks):
+    """One token count on the model's resident weights: whole-step time and the dominant kernel's roofline."""
+    cfg = weights.cfg
+    stack = Stack(weights, M, swiglu=args.swiglu, eager=args.eager)
+    step = stack.step if args.eager else capture(stack.step)
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    ms = timed(step, steps)
+    step_bytes = stack.packed_bytes_per_layer * stack.n_layers
+    tflops = stack.flops_per_layer * stack.n_layers / (ms * 1e-3) / 1e12
+    gbps = step_bytes / (ms * 1e-3) / 1e9
+    decode = M <= 128
+    value = gbps if decode else tflops
+    roof = dominant_kernel_roofline(stack, max(3, steps // 2))
+    peak = HBM_PEAK_GBS if decode else MFMA_BF16_PEAK_TFLOPS
+    leg = {"M": M, "value": round(value, 1), "unit": "GB/s" if decode else "TFLOP/s", "steps": steps, "warmup": warmup,
+           "ms_per_step": round(ms, 4), "weight_GBps": round(gbps, 1), "tflops": round(tflops, 2),
+           "frac_of_peak_whole_step": round(value / peak, 4), "roofline": roof}
+    if decode:
+        # at the published peaks the step cannot take less than the longer of its HBM time and its MFMA time
+        t_hbm, t_mfma = step_bytes / (HBM_PEAK_GBS * 1e9), stack.flops_per_layer * stack.n_layers / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+        leg["binding_roof"] = "hbm" if t_hbm >= t_mfma else "mfma"
+        leg["frac_of_binding_roof"] = round(max(t_hbm, t_mfma) / (ms * 1e-3), 4)
+    if peaks:
+        ach = peaks["hbm_read_GBps"] if decode else peaks["mfma_bf16_TFLOPs"]
+        leg["frac_of_achievable_whole_step"] = round(value / ach, 4)
+        roof["frac_of_achievable"] = round(roof["achieved"] / ach, 4)
+    del stack
+    torch.cuda.empty_cache()
+    return leg
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="workload configuration number (1-based; see qerl_synth.CONFIGS)")
-    ap.add_argument("--M", type=int, default=None)
+    ap.add_argument("--config", type=int, default=5, help="workload configuration number (1-based; see qerl_synth.CONFIGS)")
+    ap.add_argument("--M", type=int, default=None, help="one token count instead of the configuration's legs")
     ap.add_argument("--layers", type=int, default=None)
     ap.add_argument("--backward", action="store_true",
                     help="time the backward pass (dX, dA, dB) of the configuration's linears at its prefill size instead of the forward step")
@@ -394,6 +494,7 @@ def main():
     ap.add_argument("--swiglu", action="store_true",
                     help="the down projection reads SiLU(gate) (.) up from the gate/up outputs (fused into its launch at M <= 16) instead of a resident input")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the achievable-ceiling microbenchmarks")
     ap.add_argument("--eager", action="store_true", help="launch from Python each step instead of replaying a HIP graph")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB device copy five times (reference for the rocprofv3 "
@@ -422,40 +523,55 @@ def main():
         mx_bench(args)
         return
     cfg = qs.CONFIGS[args.config]
-    M = args.M or cfg["M"][0]
-    if args.layers is None and M > 128:
+    # the headline leg first, then the configuration's other token counts
+    if args.M is not None:
+        Ms = [args.M]
+    elif args.config == 5:
+        Ms = [16, 1, 128, 4096]
+    else:
+        Ms = list(cfg["M"])
+    if args.layers is None and args.config != 5 and min(Ms) > 128:
         args.layers = 4                     # compute bound: a few distinct layers are enough
-    stack = Stack(args.config, M, args.layers, swiglu=args.swiglu)
-    stack.eager = args.eager
-    step = stack.step if args.eager else capture(stack.step)
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    ms = timed(step, args.steps)
-    step_bytes = stack.packed_bytes_per_layer * stack.n_layers
-    tflops = stack.flops_per_layer * stack.n_layers / (ms * 1e-3) / 1e12
+    peaks = None if args.no_peaks else measure_peaks()
+    weights = Weights(args.config, args.layers)
+    legs = []
+    for i, M in enumerate(Ms):
+        # the headline leg is timed over exactly --steps steps after --warmup; a prefill step of the whole stack is
+        # a quarter of a second, so further prefill legs take a quarter of the steps
+        steps = args.steps if (i == 0 or M <= 128) else max(3, args.steps // 4)
+        warmup = args.warmup if (i == 0 or M <= 128) else min(args.warmup, 1)
+        legs.append(run_leg(weights, M, args, steps, warmup, peaks))
+        print(f"bench.py: leg M={M}: {legs[-1]['ms_per_step']} ms per step, {legs[-1]['value']} {legs[-1]['unit']}",
+              file=sys.stderr, flush=True)
+    head = legs[0]
+    M = head["M"]
     decode = M <= 128
-    value = step_bytes / (ms * 1e-3) / 1e9 if decode else tflops
-    roof = dominant_kernel_roofline(stack, max(3, args.steps // 2))
+    step_bytes = weights.packed_bytes_per_layer * weights.n_layers
     line = {
         "metric": "NVFP4+LoRA linear: packed-weight GB/s at decode" if decode
                   else "NVFP4+LoRA linear: TFLOP/s at prefill (2*M*N*K, LoRA flops not counted)",
-        "value": round(value, 1), "unit": "GB/s" if decode else "TFLOP/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": head["value"], "unit": head["unit"],
+        "n_gpus": 1, "steps": head["steps"], "warmup": head["warmup"],
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 x fp4(e2m1)*fp8(e4m3) -> fp32 accumulate", "data": "synthetic",
         "config": {"workload": f"config {args.config}: {cfg['model']}-shaped decoder linears, "
-                               f"{stack.n_layers} layers, {'decode' if decode else 'prefill'} M={M}, "
+                               f"{weights.n_layers} layers resident ({step_bytes / 1e9:.2f} GB packed), "
+                               f"{'decode' if decode else 'prefill'} M={M}, "
                                f"LoRA r={cfg['r']} alpha={cfg['alpha']:g}, "
                                "AQN RMSNorm before q/k/v and gate/up, noise vectors regenerated on the device every step; "
                                + ("down reads SiLU(gate)*up of the gate/up outputs; " if args.swiglu else "")
                                + ("eager launches" if args.eager else "one HIP graph replay per step"),
                    "packed_weight_bytes_per_step": step_bytes,
-                   "tflops": round(tflops, 2),
-                   "weight_GBps": round(step_bytes / (ms * 1e-3) / 1e9, 1),
-                   "frac_of_peak_whole_step": round(value / (HBM_PEAK_GBS if decode else MFMA_BF16_PEAK_TFLOPS), 4)},
-        "roofline": roof,
+                   "tflops": head["tflops"], "weight_GBps": head["weight_GBps"],
+                   "frac_of_peak_whole_step": head["frac_of_peak_whole_step"]},
+        "roofline": head["roofline"],
     }
+    if "frac_of_achievable_whole_step" in head:
+        line["config"]["frac_of_achievable_whole_step"] = head["frac_of_achievable_whole_step"]
+    if len(legs) > 1:
+        line["legs"] = legs[1:]
+    if peaks:
+        line["achievable"] = peaks
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(args.config, M)
     print(json.dumps(line))

@@ -363,6 +363,26 @@ QERL_API int mxfp4_linear_native(const void* x_bf16, int64_t M, int64_t K, int64
                                  const void* packed, int64_t N, void* y_bf16, int64_t ldy,
                                  void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---------------------------------------------------------------------------
+ * Measurement aids: what a kernel on this GPU can reach of the two rooflines the
+ * linear is measured against (reported by the benchmark beside the published
+ * peaks; no part of the method).
+ * qerl_peak_stream_read: `workgroups` persistent workgroups of eight waves read
+ *   `bytes` (a multiple of 16 KiB, >= 1 MiB, 16-byte aligned device memory) once
+ *   with 16-byte loads, each wave keeping kib_in_flight_per_wave (4, 8 or 16) KiB
+ *   requested; bytes / duration is the achievable HBM read rate when the buffer
+ *   is far larger than the caches.  sink4: 4 bytes of device memory (practically
+ *   never written).
+ * qerl_peak_mfma_bf16: `workgroups` workgroups of four waves each issue
+ *   8 * iters v_mfma_f32_32x32x16_bf16 on eight independent accumulators;
+ *   flops = workgroups * 4 * iters * 8 * 32768.  operands_2kib: 2 KiB of bf16
+ *   values (two operand fragments of 16 bytes per lane).
+ * Errors: NULL / misaligned pointers, sizes outside the ranges above.
+ */
+QERL_API int qerl_peak_stream_read(const void* src, size_t bytes, int workgroups, int kib_in_flight_per_wave,
+                                   void* sink4, void* stream);
+QERL_API int qerl_peak_mfma_bf16(const void* operands_2kib, int workgroups, int iters, void* sink4, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -62,6 +62,8 @@ _SIGNATURES = {
     "mxfp4_prepack": (ctypes.c_int, [_c_p, _c_p, _c_i64, _c_i64, _c_p, _c_p]),
     "mxfp4_linear_native_workspace_bytes": (_c_sz, [_c_i64, _c_i64, _c_i64]),
     "mxfp4_linear_native": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_i64, _c_p, _c_i64, _c_p, _c_sz, _c_p]),
+    "qerl_peak_stream_read": (ctypes.c_int, [_c_p, _c_sz, ctypes.c_int, ctypes.c_int, _c_p, _c_p]),
+    "qerl_peak_mfma_bf16": (ctypes.c_int, [_c_p, ctypes.c_int, ctypes.c_int, _c_p, _c_p]),
 }
 
 EXPORTED_SYMBOLS = tuple(_SIGNATURES)

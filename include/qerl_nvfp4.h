@@ -144,6 +144,31 @@ QERL_API int nvfp4_lora_linear_packed(const void* x_bf16, int64_t M, int64_t K, 
                                       void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * nvfp4_lora_linear_packed_noalloc -- nvfp4_lora_linear_packed for callers that
+ * cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * without the workspace pair, same results bit for bit.  The scratch is an array
+ * of nvfp4_lora_linear_packed_noalloc_max_bytes() (36 MiB) inside the library,
+ * one copy per GPU, held until the process ends; the call allocates nothing and
+ * frees nothing, and enqueues one small fill kernel (which clears the control
+ * words at the front of the array) ahead of the linear's own launches.
+ *   Limit: nvfp4_lora_linear_workspace_bytes(M, N, K, r) must not exceed
+ *   nvfp4_lora_linear_packed_noalloc_max_bytes(), else QERL_ERR_WORKSPACE and
+ *   nothing is enqueued (every single linear of Qwen2.5-7B/14B/32B shape up to
+ *   4096 tokens and rank 64 fits).
+ *   All calls on one GPU share that GPU's array: calls that overlap in time on
+ *   one GPU (different streams, different threads) race; order them on one
+ *   stream.  The array belongs to the device that is current at the call.
+ * Errors: as nvfp4_lora_linear_packed; QERL_ERR_LAUNCH also if the array's
+ * device address cannot be obtained.
+ */
+QERL_API size_t nvfp4_lora_linear_packed_noalloc_max_bytes(void);   /* host */
+QERL_API int nvfp4_lora_linear_packed_noalloc(const void* x_bf16, int64_t M, int64_t K, int64_t ldx,
+                                              const void* packed, const float* tensor_scale, int64_t N,
+                                              const void* A_bf16, const void* B_bf16, int64_t r, float lora_scale,
+                                              void* y_bf16, int64_t ldy, void* stream);
+
+/* ---------------------------------------------------------------------------
  * nvfp4_lora_linear_packed_group -- up to 4 linears that read the same x (the
  * q/k/v or the gate/up projections of a block, which share one noisy RMSNorm
  * output: Section 3.3) in ONE launch.  Each member is the same function of its

@@ -36,6 +36,9 @@ _SIGNATURES = {
     "nvfp4_lora_linear_packed": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_p, _c_i64,
                                                 _c_p, _c_p, _c_i64, ctypes.c_float, _c_p, _c_i64,
                                                 _c_p, _c_sz, _c_p]),
+    "nvfp4_lora_linear_packed_noalloc_max_bytes": (_c_sz, []),
+    "nvfp4_lora_linear_packed_noalloc": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_p, _c_i64,
+                                                        _c_p, _c_p, _c_i64, ctypes.c_float, _c_p, _c_i64, _c_p]),
     "nvfp4_lora_linear_swiglu_workspace_bytes": (_c_sz, [_c_i64, _c_i64, _c_i64, _c_i64]),
     "nvfp4_lora_linear_packed_swiglu": (ctypes.c_int, [_c_p, _c_p, _c_i64, _c_i64, _c_i64, _c_i64, _c_p, _c_p, _c_i64,
                                                        _c_p, _c_p, _c_i64, ctypes.c_float, _c_p, _c_i64,
@@ -309,6 +312,31 @@ def nvfp4_lora_linear_packed(x, w: PackedWeight, A: Optional[torch.Tensor] = Non
         _dev(x, torch.bfloat16, "x"), M, K, ldx, _dev(w.packed, torch.uint8, "packed"),
         _dev(w.tensor_scale, torch.float32, "tensor_scale"), N, a_ptr, b_ptr, r, float(lora_scale),
         _dev(out, torch.bfloat16, "out"), ldy, workspace.ptr, workspace.nbytes, _stream()))
+    return out
+
+
+def nvfp4_lora_linear_packed_noalloc(x, w: PackedWeight, A: Optional[torch.Tensor], B: Optional[torch.Tensor],
+                                     lora_scale: float, out: torch.Tensor):
+    """nvfp4_lora_linear_packed on the library's own per-GPU scratch array: no workspace, nothing allocated
+    (the caller brings `out`).  Calls on one GPU share that array and must not overlap."""
+    lib = load_library()
+    M, K, ldx = _rows(x, "x")
+    if K != w.K:
+        raise ValueError("x has the wrong number of columns")
+    r = 0
+    a_ptr = b_ptr = None
+    if A is not None and B is not None and A.shape[0] > 0:
+        r = A.shape[0]
+        if tuple(A.shape) != (r, K) or tuple(B.shape) != (w.N, r) or not A.is_contiguous() or not B.is_contiguous():
+            raise ValueError("A must be contiguous [r, K] and B contiguous [N, r]")
+        a_ptr, b_ptr = _dev(A, torch.bfloat16, "A"), _dev(B, torch.bfloat16, "B")
+    _, n_out, ldy = _rows(out, "out")
+    if out.shape[0] != M or n_out != w.N:
+        raise ValueError("out must be [M, N]")
+    _check("nvfp4_lora_linear_packed_noalloc", lib.nvfp4_lora_linear_packed_noalloc(
+        _dev(x, torch.bfloat16, "x"), M, K, ldx, _dev(w.packed, torch.uint8, "packed"),
+        _dev(w.tensor_scale, torch.float32, "tensor_scale"), w.N, a_ptr, b_ptr, r, float(lora_scale),
+        _dev(out, torch.bfloat16, "out"), ldy, _stream()))
     return out
 
 

@@ -538,3 +538,53 @@ static int packed_single(const void* x, int64_t M, int64_t K, int64_t ldx, const
   }
   return QERL_OK;
 }
+
+// ---- nvfp4_lora_linear_packed_noalloc: the packed linear for callers that cannot allocate ----------------------
+// The scratch that nvfp4_lora_linear_packed takes as its workspace argument lives here in a file-scope device
+// array instead.  Each GPU holds its own copy of the array at its own address: the address is looked up once per
+// device (with that device current) and only that pointer is ever handed to kernels.
+namespace qerl {
+constexpr size_t kNoallocScratchBytes = (size_t)36 << 20;   // covers every single linear of the five benchmark configurations (largest: 32.7 MiB)
+static __device__ __align__(256) unsigned char scratch[kNoallocScratchBytes];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` per device, nullptr until first used there
+
+static int noalloc_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return launch_status();
+  if (dev < 0 || dev >= kMaxDevices) return QERL_ERR_SHAPE;
+  void* p = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+  if (!p) {
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) { set_last_hip_error((int)e); (void)hipGetLastError(); return QERL_ERR_LAUNCH; }
+    __atomic_store_n(&g_scratch_ptr[dev], p, __ATOMIC_RELEASE);   // racing first calls look up the same address
+  }
+  *out = p;
+  return QERL_OK;
+}
+}  // namespace qerl
+
+extern "C" size_t nvfp4_lora_linear_packed_noalloc_max_bytes(void) { return kNoallocScratchBytes; }
+
+extern "C" int nvfp4_lora_linear_packed_noalloc(const void* x, int64_t M, int64_t K, int64_t ldx, const void* packed,
+                                                const float* tensor_scale, int64_t N, const void* A, const void* B,
+                                                int64_t r, float lora_scale, void* y, int64_t ldy, void* stream) {
+  // every host-side check of the ordinary entry point first, against the fixed scratch size: nothing is launched
+  // and no device is touched for a call that would be rejected
+  LinearCall c{(const uint16_t*)x, M, K, ldx, tensor_scale, N, (const uint16_t*)A, (const uint16_t*)B, r,
+               lora_scale, (uint16_t*)y, ldy, (void*)(uintptr_t)256, kNoallocScratchBytes, (hipStream_t)stream};
+  const int vr = validate(c, packed, packed);
+  if (vr != QERL_OK) return vr > 0 ? QERL_OK : vr;
+  if (K == 0) return QERL_ERR_SHAPE;
+  if (!aligned(packed, 16) || !aligned(x, 16) || ldx % 8 != 0) return QERL_ERR_ALIGN;
+  void* ws = nullptr;
+  const int rc = noalloc_scratch(&ws);
+  if (rc != QERL_OK) return rc;
+  // The array keeps whatever the last call on this GPU left in it.  What must start at zero are the control
+  // words at its front; they are cleared by a fill kernel (not a memset node, so the call can be captured).
+  zero_words_kernel<<<dim3(16), dim3(256), 0, (hipStream_t)stream>>>((uint32_t*)ws, kCtrlBytes / sizeof(uint32_t));
+  const int zr = launch_status();
+  if (zr != QERL_OK) return zr;
+  return packed_single(x, M, K, ldx, packed, tensor_scale, N, A, B, r, lora_scale, nullptr, y, ldy, ws,
+                       kNoallocScratchBytes, stream);
+}

@@ -46,6 +46,8 @@ extern "C" {
 #define QERL_ERR_ALIGN      -3  /* pointer or leading dimension not aligned as documented */
 #define QERL_ERR_WORKSPACE  -4  /* workspace NULL or smaller than *_workspace_bytes()  */
 #define QERL_ERR_LAUNCH     -5  /* HIP runtime error; see qerl_last_hip_error()        */
+#define QERL_ERR_TIMEOUT    -6  /* reported by qerl_workspace_status(): a kernel's bounded
+                                   wait on another workgroup gave up                   */
 
 /* Host.  Static string for a status code. */
 QERL_API const char* qerl_status_string(int status);
@@ -205,6 +207,61 @@ typedef struct {
 QERL_API int nvfp4_lora_linear_packed_group(const void* x_bf16, int64_t M, int64_t K, int64_t ldx,
                                             const qerl_linear_desc* members, int n_members,
                                             void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Fused decode launches.  Up to 16 tokens each of these is ONE persistent launch
+ * (one workgroup per compute unit) in which the weight stream never stops: the
+ * RMSNorm with the noisy gain (Eq. 10; Section 3.3 "Noise Merging": q, k, v share
+ * one such norm, gate and up another) is applied while the input is staged, the
+ * adapters' down-projections x A^T (Eq. 2) run on a few workgroups of the same
+ * launch, and -- in the feed-forward call -- SiLU(gate) (.) up is formed in the
+ * epilogue of the gate / up tiles, a device-wide hand-over follows, and down_proj
+ * streams on behind it.  For more tokens the same operators run as separate
+ * launches (same results contract).
+ *
+ * aqn_rmsnorm_nvfp4_lora_linear_group:
+ *   xn = aqn_rmsnorm(x, gain, noise, eps) rounded to bf16 (gain == NULL: xn = x),
+ *   members[i].y = nvfp4_lora_linear_packed(xn, member i)           i < n_members <= 4
+ * aqn_rmsnorm_nvfp4_lora_mlp:
+ *   xn as above; g = gate(xn), u = up(xn), both rounded to bf16;
+ *   act = bf16( bf16(SiLU(g)) (.) u )   (as nvfp4_lora_linear_packed_swiglu);
+ *   down->y = nvfp4_lora_linear_packed(act, down).    gate->y, up->y are not written.
+ *   gate->N == up->N == down's K, a multiple of 8.
+ * Arguments as in aqn_rmsnorm and nvfp4_lora_linear_packed_group (descriptors are
+ * HOST structs read during the call; t_f32 is ignored); x 16-byte aligned, ldx % 8
+ * == 0, gain / noise 16-byte aligned; at M <= 16 every adapter needs r % 8 == 0,
+ * r <= 64 and 16-byte aligned A and B (QERL_ERR_SHAPE otherwise).
+ *   workspace: >= the matching *_workspace_bytes(), 256-byte aligned, prepared once
+ *   with qerl_workspace_init(); a linear workspace of that size serves as well (the
+ *   control words share one layout).  Calls sharing it must be ordered on one stream.
+ * Co-residency: the workgroups of these launches (and of the other decode
+ * kernels' in-launch hand-overs) wait for each other, which requires that all of
+ * them are resident at once: one process per GPU, no other kernel holding
+ * compute units for the duration of the call.  Every such wait is bounded; if one
+ * gives up, the sticky error word of the workspace is set, the outputs of that
+ * call are unreliable, and qerl_workspace_status() reports QERL_ERR_TIMEOUT until
+ * the workspace is prepared again with qerl_workspace_init().
+ */
+QERL_API size_t aqn_rmsnorm_nvfp4_lora_linear_group_workspace_bytes(int64_t M, int64_t K, const int64_t* Ns,
+                                                                    const int64_t* rs, int n_members);   /* host */
+QERL_API int aqn_rmsnorm_nvfp4_lora_linear_group(const void* x_bf16, int64_t M, int64_t K, int64_t ldx,
+                                                 const void* gain_bf16, const float* noise_f32, float eps,
+                                                 const qerl_linear_desc* members, int n_members,
+                                                 void* workspace, size_t workspace_bytes, void* stream);
+QERL_API size_t aqn_rmsnorm_nvfp4_lora_mlp_workspace_bytes(int64_t M, int64_t H, int64_t I, int64_t N_down,
+                                                           int64_t r_gate, int64_t r_up, int64_t r_down);   /* host */
+QERL_API int aqn_rmsnorm_nvfp4_lora_mlp(const void* x_bf16, int64_t M, int64_t H, int64_t ldx,
+                                        const void* gain_bf16, const float* noise_f32, float eps,
+                                        const qerl_linear_desc* gate, const qerl_linear_desc* up,
+                                        const qerl_linear_desc* down,
+                                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* qerl_workspace_status: reads the sticky error word of a workspace (synchronises
+ * with `stream`): QERL_OK, or QERL_ERR_TIMEOUT if a bounded wait of any kernel that
+ * used the workspace gave up since the last qerl_workspace_init().
+ * qerl_status_from_error_word (host): the decoding of that word. */
+QERL_API int qerl_workspace_status(const void* workspace, void* stream);
+QERL_API int qerl_status_from_error_word(uint32_t word);
 
 /* ---------------------------------------------------------------------------
  * nvfp4_lora_linear_packed_swiglu -- the feed-forward block's down projection

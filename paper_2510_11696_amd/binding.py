@@ -65,6 +65,14 @@ _SIGNATURES = {
     "mxfp4_prepack": (ctypes.c_int, [_c_p, _c_p, _c_i64, _c_i64, _c_p, _c_p]),
     "mxfp4_linear_native_workspace_bytes": (_c_sz, [_c_i64, _c_i64, _c_i64]),
     "mxfp4_linear_native": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_i64, _c_p, _c_i64, _c_p, _c_sz, _c_p]),
+    "aqn_rmsnorm_nvfp4_lora_linear_group_workspace_bytes": (_c_sz, [_c_i64, _c_i64, _c_p, _c_p, ctypes.c_int]),
+    "aqn_rmsnorm_nvfp4_lora_linear_group": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_p, ctypes.c_float,
+                                                           _c_p, ctypes.c_int, _c_p, _c_sz, _c_p]),
+    "aqn_rmsnorm_nvfp4_lora_mlp_workspace_bytes": (_c_sz, [_c_i64] * 7),
+    "aqn_rmsnorm_nvfp4_lora_mlp": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_p, ctypes.c_float,
+                                                  _c_p, _c_p, _c_p, _c_p, _c_sz, _c_p]),
+    "qerl_workspace_status": (ctypes.c_int, [_c_p, _c_p]),
+    "qerl_status_from_error_word": (ctypes.c_int, [ctypes.c_uint32]),
     "qerl_peak_stream_read": (ctypes.c_int, [_c_p, _c_sz, ctypes.c_int, ctypes.c_int, _c_p, _c_p]),
     "qerl_peak_mfma_bf16": (ctypes.c_int, [_c_p, ctypes.c_int, ctypes.c_int, _c_p, _c_p]),
 }
@@ -488,6 +496,109 @@ def nvfp4_lora_linear_packed_group(x, weights, As=None, Bs=None, lora_scales=Non
         _dev(x, torch.bfloat16, "x"), M, K, ldx, ctypes.cast(descs, _c_p), n,
         workspace.ptr, workspace.nbytes, _stream()))
     return outs
+
+
+def _make_desc(w: PackedWeight, A, B, lora_scale, out, bias, K):
+    """One qerl_linear_desc from torch tensors (out may be None: y = NULL); returns (desc, r)."""
+    if w.K != K:
+        raise ValueError("every member must have K columns")
+    r = 0
+    a_ptr = b_ptr = None
+    if A is not None and B is not None and A.shape[0] > 0:
+        r = A.shape[0]
+        if tuple(A.shape) != (r, K) or tuple(B.shape) != (w.N, r) or not A.is_contiguous() or not B.is_contiguous():
+            raise ValueError("A must be contiguous [r, K] and B contiguous [N, r]")
+        a_ptr, b_ptr = _dev(A, torch.bfloat16, "A"), _dev(B, torch.bfloat16, "B")
+    y_ptr, ldy = None, 0
+    if out is not None:
+        _, n_out, ldy = _rows(out, "out")
+        if n_out != w.N:
+            raise ValueError("out must be [M, N]")
+        y_ptr = _dev(out, torch.bfloat16, "out")
+    bias_ptr = None
+    if bias is not None:
+        if tuple(bias.shape) != (w.N,) or not bias.is_contiguous():
+            raise ValueError("bias must be contiguous [N]")
+        bias_ptr = _dev(bias, torch.bfloat16, "bias")
+    return _LinearDesc(_dev(w.packed, torch.uint8, "packed"), _dev(w.tensor_scale, torch.float32, "tensor_scale"),
+                       w.N, a_ptr, b_ptr, r, float(lora_scale), y_ptr, ldy, None, bias_ptr), r
+
+
+def _norm_args(x, gain, noise):
+    M, H, ldx = _rows(x, "x")
+    g_ptr = n_ptr = None
+    if gain is not None:
+        if gain.numel() != H or not gain.is_contiguous():
+            raise ValueError("gain must be contiguous [H]")
+        g_ptr = _dev(gain, torch.bfloat16, "gain")
+        if noise is not None:
+            if noise.numel() != H or not noise.is_contiguous():
+                raise ValueError("noise must be contiguous [H]")
+            n_ptr = _dev(noise, torch.float32, "noise")
+    return M, H, ldx, g_ptr, n_ptr
+
+
+def aqn_rmsnorm_nvfp4_lora_linear_group(x, gain, noise, eps, weights, As=None, Bs=None, lora_scales=None,
+                                        workspace: Optional[Workspace] = None, outs=None, biases=None):
+    """AQN RMSNorm of x (gain None: x as it is), then the packed linears `weights` on it; one launch up to
+    16 tokens.  Returns the list of outputs."""
+    lib = load_library()
+    M, K, ldx, g_ptr, n_ptr = _norm_args(x, gain, noise)
+    n = len(weights)
+    As = As if As is not None else [None] * n
+    Bs = Bs if Bs is not None else [None] * n
+    lora_scales = lora_scales if lora_scales is not None else [0.0] * n
+    biases = biases if biases is not None else [None] * n
+    if outs is None:
+        outs = [torch.empty((M, w.N), dtype=torch.bfloat16, device=x.device) for w in weights]
+    descs = (_LinearDesc * n)()
+    rs = []
+    for i, w in enumerate(weights):
+        if outs[i].shape[0] != M:
+            raise ValueError("out must be [M, N]")
+        descs[i], r = _make_desc(w, As[i], Bs[i], lora_scales[i], outs[i], biases[i], K)
+        rs.append(r)
+    if workspace is None:
+        workspace = Workspace(aqn_rmsnorm_nvfp4_lora_linear_group_workspace_bytes(M, K, [w.N for w in weights], rs), x.device)
+    _check("aqn_rmsnorm_nvfp4_lora_linear_group", lib.aqn_rmsnorm_nvfp4_lora_linear_group(
+        _dev(x, torch.bfloat16, "x"), M, K, ldx, g_ptr, n_ptr, float(eps), ctypes.cast(descs, _c_p), n,
+        workspace.ptr, workspace.nbytes, _stream()))
+    return outs
+
+
+def aqn_rmsnorm_nvfp4_lora_linear_group_workspace_bytes(M: int, K: int, Ns, rs) -> int:
+    n = len(Ns)
+    return int(load_library().aqn_rmsnorm_nvfp4_lora_linear_group_workspace_bytes(
+        M, K, ctypes.cast((ctypes.c_int64 * n)(*Ns), _c_p), ctypes.cast((ctypes.c_int64 * n)(*rs), _c_p), n))
+
+
+def aqn_rmsnorm_nvfp4_lora_mlp(x, gain, noise, eps, gate: PackedWeight, up: PackedWeight, down: PackedWeight,
+                               As=(None, None, None), Bs=(None, None, None), lora_scales=(0.0, 0.0, 0.0),
+                               workspace: Optional[Workspace] = None, out: Optional[torch.Tensor] = None):
+    """Feed-forward block: AQN RMSNorm -> gate, up -> SiLU(gate) * up -> down; one launch up to 16 tokens.
+    As / Bs / lora_scales are (gate, up, down) triples.  Returns down's output [M, down.N]."""
+    lib = load_library()
+    M, H, ldx, g_ptr, n_ptr = _norm_args(x, gain, noise)
+    if gate.N != up.N or down.K != gate.N:
+        raise ValueError("gate and up must have the same N, which is down's K")
+    if out is None:
+        out = torch.empty((M, down.N), dtype=torch.bfloat16, device=x.device)
+    if out.shape[0] != M:
+        raise ValueError("out must be [M, N]")
+    dg, rg = _make_desc(gate, As[0], Bs[0], lora_scales[0], None, None, H)
+    du, ru = _make_desc(up, As[1], Bs[1], lora_scales[1], None, None, H)
+    dd, rd = _make_desc(down, As[2], Bs[2], lora_scales[2], out, None, gate.N)
+    if workspace is None:
+        workspace = Workspace(lib.aqn_rmsnorm_nvfp4_lora_mlp_workspace_bytes(M, H, gate.N, down.N, rg, ru, rd), x.device)
+    _check("aqn_rmsnorm_nvfp4_lora_mlp", lib.aqn_rmsnorm_nvfp4_lora_mlp(
+        _dev(x, torch.bfloat16, "x"), M, H, ldx, g_ptr, n_ptr, float(eps), ctypes.byref(dg), ctypes.byref(du),
+        ctypes.byref(dd), workspace.ptr, workspace.nbytes, _stream()))
+    return out
+
+
+def workspace_status(workspace: Workspace) -> int:
+    """0, or the negative status a kernel's abandoned wait left in the workspace (synchronises)."""
+    return int(load_library().qerl_workspace_status(workspace.ptr, _stream()))
 
 
 def aqn_rmsnorm(x, gain, noise: Optional[torch.Tensor] = None, eps: float = 1e-6,

@@ -19,11 +19,9 @@ constexpr size_t kMaxCounterTiles = 16384;   // rows / 16 the control region can
 
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-// The control region has a FIXED size and position so that calls of different shapes can share one
+// The control region has a FIXED size and position (linear.hpp) so that calls of different shapes can share one
 // workspace: no call's data region may overlap another call's control words (they must stay zero).
-constexpr size_t kCtrlMainWords = 16384;   // arrival counters of the main kernels: N / 16 <= 16384
-constexpr size_t kCtrlDownWords = 256;     // arrival counters of the LoRA down-projection kernel: r / 16 <= 256
-constexpr size_t kCtrlBytes = (kCtrlMainWords + kCtrlDownWords + 64) * sizeof(uint32_t);   // + hand-over words, 256-multiple
+constexpr size_t kCtrlBytes = kCtrlRegionBytes;
 
 // 17..128 tokens: room for the K-splits' partial outputs (up to 8 splits, capped); the K-parts' sums of the
 // LoRA down-projection follow it.
@@ -91,6 +89,7 @@ extern "C" const char* qerl_status_string(int status) {
     case QERL_ERR_ALIGN: return "pointer or leading dimension not aligned as required";
     case QERL_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case QERL_ERR_LAUNCH: return "HIP runtime error at launch (see qerl_last_hip_error)";
+    case QERL_ERR_TIMEOUT: return "a kernel's bounded wait on another workgroup gave up: results unreliable, re-initialise the workspace";
     default: return "unknown status";
   }
 }

@@ -62,6 +62,29 @@ __device__ __forceinline__ u32x4 silu_mul8(u32x4 g, u32x4 u) {
   return u32x4{silu_mul2(g[0], u[0]), silu_mul2(g[1], u[1]), silu_mul2(g[2], u[2]), silu_mul2(g[3], u[3])};
 }
 
+// Eight normalised activations of one token row (Eq. 10): bf16((gain[k] + noise[k]) * (x[k] * rstd)) for
+// k = k0 .. k0 + 7 (k0 a multiple of 8; gain 16-byte aligned, noise 16-byte aligned or null); gain + noise is
+// formed in fp32 and not re-rounded, one rounding at the end -- the arithmetic of aqn_rmsnorm.
+__device__ __forceinline__ u32x4 norm_scale8(u32x4 v, float rstd, const uint16_t* __restrict__ gain,
+                                             const float* __restrict__ noise, int64_t k0) {
+  const u32x4 g = *reinterpret_cast<const u32x4*>(gain + k0);
+  f32x4 z0 = {0.f, 0.f, 0.f, 0.f}, z1 = {0.f, 0.f, 0.f, 0.f};
+  if (noise) {
+    z0 = *reinterpret_cast<const f32x4*>(noise + k0);
+    z1 = *reinterpret_cast<const f32x4*>(noise + k0 + 4);
+  }
+  const float z[8] = {z0[0], z0[1], z0[2], z0[3], z1[0], z1[1], z1[2], z1[3]};
+  u32x4 o;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float ga = bf16_bits_to_f32(g[j] & 0xffffu) + z[2 * j];
+    const float gb = bf16_bits_to_f32(g[j] >> 16) + z[2 * j + 1];
+    const float a = bf16_bits_to_f32(v[j] & 0xffffu), b = bf16_bits_to_f32(v[j] >> 16);
+    o[j] = pack_bf16x2(ga * (a * rstd), gb * (b * rstd));
+  }
+  return o;
+}
+
 // E4M3 byte (sign clear, not NaN) -> fp32, exact.  (b << 20) places the 4+3
 // bits at an fp32's low exponent / top mantissa bits; multiplying by 2^120
 // re-biases 127 -> 7 and, with fp32 denormals enabled, also covers the

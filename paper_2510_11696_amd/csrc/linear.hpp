@@ -5,6 +5,10 @@
 namespace qerl {
 
 constexpr int kMaxGroup = 4;   // linears that can share one launch (they read the same x)
+// Control region at the front of every linear workspace (fixed size and position, zero between calls):
+constexpr size_t kCtrlMainWords = 16384;   // arrival counters of the main kernels: N / 16 <= 16384
+constexpr size_t kCtrlDownWords = 256;     // arrival counters of the LoRA down-projection kernel: r / 16 <= 256
+constexpr size_t kCtrlRegionBytes = (kCtrlMainWords + kCtrlDownWords + 64) * sizeof(uint32_t);   // + 64 hand-over words, 256-multiple
 constexpr int kFmtNvfp4 = 0;   // rows are NVFP4 (codes + scales)
 constexpr int kFmtBf16 = 1;    // rows are dense bf16 (the LoRA A matrix); output is fp32 t
 
@@ -70,6 +74,39 @@ struct StreamArgs {
 };
 int plan_stream(StreamArgs& a, size_t* lds_bytes, int* MR);
 int launch_stream(const StreamArgs& a, size_t lds_bytes, int MR, hipStream_t st);
+
+// ---- persistent multi-stage decode kernel (linear_block.hip) ----
+constexpr int kBlkWaves = 12;            // waves per workgroup, one workgroup per CU
+constexpr int kBlkMaxStages = 3;         // dependent stages in one launch
+constexpr size_t kBlkTpartWords = 16 * 16 * 256;   // per stage: producers x tokens x stacked rank
+// control words of the block kernel, relative to the hand-over words of the workspace's control region
+constexpr int kBlkArrive = 8;            // + stage: producers of that stage that have stored their partial t
+constexpr int kBlkBarrier = 12;          // workgroups past the stage boundaries so far
+constexpr int kBlkExit = 13;             // workgroups that have left
+constexpr int kCtlErr = 16;              // sticky: a bounded wait gave up (bit 0 stage boundary, bit 1 LoRA hand-over, bit 2 another kernel's hand-over)
+struct BlkMember {
+  const uint8_t* packed; const float* tensor_scale; const uint16_t* A; const uint16_t* B; const uint16_t* bias;
+  uint16_t* y; int64_t ldy; int64_t N; int n_tiles; int tile_begin;   // row tiles [tile_begin, tile_begin + n_tiles) of the stage (unused entries: INT_MAX)
+  int r; int t_off; float lora_scale; int y_vec;                       // rank; column of this member's t in the stage's stacked t; y rows allow 16-byte stores
+};
+struct BlkStage {
+  const uint16_t* x; int64_t ldx; int64_t K; int k_tiles;              // input [M, K]: memory written before the launch, or by the previous stage
+  const uint16_t* gain; const float* noise; float eps;                 // gain != null: the input is the AQN RMSNorm of x (Eq. 10)
+  int n_members; BlkMember mem[kMaxGroup];
+  int total_tiles; int total_v;                                        // row tiles of all members; units a wave takes whole (pairs: one per gate / up tile pair)
+  int pairs; uint16_t* act; int64_t ld_act; int act_vec;               // members 0, 1 are gate_proj, up_proj: act[M, N] = SiLU(gate) (.) up is stored instead of their outputs
+  int Sk; int kr_len; int per_range;                                   // K-ranges, K-tiles in each (multiple of the ring depth), consumer workgroups per range
+  int n_producers; int r_total; int prod_steps; int prod_cb; int prod_red_off;   // LoRA down-projection of the stage (lora_producer.hpp)
+  int ctr_off; int64_t partial_off;                                    // this stage's arrival words / partial tiles (floats) in the workspace areas
+};
+struct BlkArgs {
+  int M; int n_stages; int n_wgs; int n_prod_max;                      // workgroups [0, n_prod_max) are the producers of every stage
+  BlkStage st[kBlkMaxStages];
+  int t_lds_off; int y_lds_off;                                        // LDS: split t of the members; one output tile per wave
+  uint32_t* ctl; uint32_t* counters; float* partial; uint32_t* tpart;
+};
+int plan_block(BlkArgs& a, size_t* lds_bytes, int* MR, size_t* partial_floats, size_t* counter_words);
+int launch_block(const BlkArgs& a, size_t lds_bytes, int MR, hipStream_t st);
 
 // ---- prefill path: MFMA GEMM on tile-packed weights (linear_gemm.hip) ----
 // One linear of a prefill launch: gemm32_kernel's column blocks run over the members of a group that reads the

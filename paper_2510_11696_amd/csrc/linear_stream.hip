@@ -28,13 +28,13 @@
 //     linear_decode.hip (ready word, bounded wait, NaN on time-out).
 // Results are bit-identical from call to call: every sum has a fixed order.
 #include "linear.hpp"
+#include "lora_producer.hpp"
 
 namespace qerl {
 
 constexpr int kStreamWaves = 8;             // 7 main + 1 epilogue
 constexpr int kMainWaves = kStreamWaves - 1;
 constexpr int kCtlArrive = 0, kCtlDone = 2;   // producers that have stored their partial t; consumers that have read it
-constexpr int kTpartTokens = 16;              // token rows per producer in the partial-t area
 constexpr uint32_t kStreamSpinLimit = 1u << 14;
 
 __device__ __forceinline__ bf16x8 stream_e2m1x8(uint32_t codes) {
@@ -63,119 +63,19 @@ __device__ unsigned long long g_trace[512 * 8 * 8];
 #define QSTART(p) do { } while (0)
 #endif
 
-// ---- producers: t[tok][j] = sum_k x[tok,k] * Astack[j,k] for the stacked A of all members ----------
-// Producer p of P owns a run of 16-input steps of K.  Its share of x and of up to 64 stacked rows of A is
-// first copied to LDS with row-contiguous loads (a wave instruction reads 1 KiB of ONE row: few pages and
-// full cache lines per request, which matters because these requests queue behind the weight streams of all
-// other workgroups), everything requested before anything is stored; then the waves take MFMA operands from
-// LDS, steps interleaved over the eight waves.
-constexpr int kProdMaxSteps = 96;          // steps per column block: 3 chunks of 16 bytes per lane and row
-constexpr int kProdRowsPerWave = 10;       // (64 rows of A + 16 tokens) / 8 waves
-
+// ---- producers: t = x Astack^T for the stacked A of all members (lora_producer.hpp) ------------------
 template <int MR, bool GATED>
 __device__ __forceinline__ void stream_producer(const StreamArgs& a, unsigned char* smem) {
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps everything derived from it in SGPRs
-  const int n32 = lane & 31, kg = lane >> 5;
-  const int n_at = (a.r_total + 31) >> 5, n_pairs = (n_at + 1) >> 1;
-  constexpr int kElems = 2 * MR * 64;
-  const int steps = (int)(a.K / 16);
-  const int p_s0 = (int)blockIdx.x * a.prod_steps;
-  const int p_s1 = p_s0 + a.prod_steps < steps ? p_s0 + a.prod_steps : steps;
-  float* red = reinterpret_cast<float*>(smem + a.prod_red_off);
-  QTRACE(0);
-  for (int pair = 0; pair < n_pairs; ++pair) {
-    f32x16 pacc[2];
+  LoraProducerArgs p;
+  p.x = a.x; p.ldx = a.ldx; p.x2 = a.x2; p.ldx2 = a.ldx2;
+  p.M = a.M; p.K = a.K; p.r_total = a.r_total; p.n_members = a.n_members;
 #pragma unroll
-    for (int at = 0; at < 2; ++at)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) pacc[at][i] = 0.f;
-    const int rows_a = a.r_total - 64 * pair < 64 ? a.r_total - 64 * pair : 64;   // stacked rows of this pass
-    const int n_rows = rows_a + a.M;                                              // LDS rows: A rows, then tokens, then a zero row
-    for (int cb0 = p_s0; cb0 < p_s1; cb0 += a.prod_cb) {
-      const int nsb = cb0 + a.prod_cb < p_s1 ? a.prod_cb : p_s1 - cb0;            // steps of this column block
-      const int row_chunks = 2 * nsb, stride = row_chunks * 16 + 16;              // bytes between LDS rows
-      // wave w copies rows w, w + 8, ...; lane l the chunks l, l + 64, l + 128
-      u32x4 v[kProdRowsPerWave][3];
-#pragma unroll
-      for (int ri = 0; ri < kProdRowsPerWave; ++ri) {
-        const int row = wave + 8 * ri;
-        const uint16_t* src = nullptr;
-        if (row < rows_a) {
-          const int srow = 64 * pair + row;               // row of the stacked A: lives in member mi at srow - t_off
-          int mi = 0;
-#pragma unroll
-          for (int i = 1; i < kMaxGroup; ++i)
-            if (i < a.n_members && srow >= a.mem[i].t_off) mi = i;
-          src = a.mem[mi].A + (int64_t)(srow - a.mem[mi].t_off) * a.K;
-        } else if (row < n_rows) {
-          src = a.x + (int64_t)(row - rows_a) * a.ldx;
-        }
-#pragma unroll
-        for (int ci = 0; ci < 3; ++ci) {
-          const int c = lane + 64 * ci;
-          v[ri][ci] = u32x4{0u, 0u, 0u, 0u};
-          if (src && c < row_chunks) v[ri][ci] = *reinterpret_cast<const u32x4*>(src + (int64_t)cb0 * 16 + c * 8);
-        }
-      }
-#pragma unroll
-      for (int ri = 0; ri < kProdRowsPerWave; ++ri) {
-        const int row = wave + 8 * ri;
-#pragma unroll
-        for (int ci = 0; ci < 3; ++ci) {
-          const int c = lane + 64 * ci;
-          if (row < n_rows && c < row_chunks) *reinterpret_cast<u32x4*>(smem + row * stride + c * 16) = v[ri][ci];
-        }
-      }
-      for (int c = tid; c < row_chunks; c += kStreamWaves * 64)   // MFMA rows beyond the tokens / the stacked ranks read zeros
-        *reinterpret_cast<u32x4*>(smem + n_rows * stride + c * 16) = u32x4{0u, 0u, 0u, 0u};
-      if constexpr (GATED) {             // gated input: the token rows in LDS become SiLU(x) (.) x2
-        __syncthreads();
-        for (int idx = tid; idx < a.M * row_chunks; idx += kStreamWaves * 64) {
-          const int row = idx / row_chunks, c = idx - row * row_chunks;
-          u32x4* p = reinterpret_cast<u32x4*>(smem + (rows_a + row) * stride + c * 16);
-          const u32x4 u = *reinterpret_cast<const u32x4*>(a.x2 + (int64_t)row * a.ldx2 + (int64_t)cb0 * 16 + c * 8);
-          *p = silu_mul8(*p, u);
-        }
-      }
-      __syncthreads();
-      if (cb0 == p_s0) QTRACE(1);
-      const unsigned char* xrow = smem + (rows_a + (n32 < a.M ? n32 : a.M)) * stride + kg * 16;
-      const unsigned char* arow0 = smem + (n32 < rows_a ? n32 : n_rows) * stride + kg * 16;
-      const unsigned char* arow1 = smem + (32 + n32 < rows_a ? 32 + n32 : n_rows) * stride + kg * 16;
-      for (int sidx = wave; sidx < nsb; sidx += kStreamWaves) {
-        const bf16x8 xf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(xrow + sidx * 32));
-        const bf16x8 a0 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(arow0 + sidx * 32));
-        const bf16x8 a1 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(arow1 + sidx * 32));
-        pacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, a0, pacc[0], 0, 0, 0);
-        pacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, a1, pacc[1], 0, 0, 0);
-      }
-      __syncthreads();   // all fragments read before the next block (or the sums below) overwrite them
-    }
-#pragma unroll
-    for (int at = 0; at < 2; ++at)
-#pragma unroll
-      for (int q = 0; q < MR; ++q) red[(wave * 2 + at) * MR * 64 + q * 64 + lane] = pacc[at][q];
-    __syncthreads();
-    // this workgroup's partial of t, in [token][stacked rank] order (what the consumers' MFMA operand wants)
-    for (int e = tid; e < kElems; e += kStreamWaves * 64) {
-      float sum = red[e];
-      for (int w = 1; w < kStreamWaves; ++w) sum += red[w * kElems + e];
-      const int at = e / (MR * 64), q = (e / 64) % MR, l = e & 63;
-      const int tok = 8 * (q >> 2) + 4 * (l >> 5) + (q & 3), j = (2 * pair + at) * 32 + (l & 31);
-      if (tok < a.M && j < a.r_total)
-        __hip_atomic_store(a.tpart + ((int64_t)blockIdx.x * kTpartTokens + tok) * a.r_total + j, __float_as_uint(sum),
-                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    __syncthreads();   // red is reused by the next pair
-  }
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's partial stores have completed
-  QTRACE(2);
-  __syncthreads();
-  // Consumers wait for all P arrivals and add the P partials themselves, in producer order: one
-  // memory round trip less than electing a producer to publish the sum.
-  if (tid == 0) __hip_atomic_fetch_add(a.lora_ctl + kCtlArrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  QTRACE(3);
+  for (int i = 0; i < kMaxGroup; ++i) { p.A[i] = a.mem[i].A; p.t_off[i] = a.mem[i].t_off; }
+  p.index = (int)blockIdx.x;
+  p.prod_steps = a.prod_steps; p.prod_cb = a.prod_cb; p.prod_red_off = a.prod_red_off;
+  p.tpart = a.tpart; p.arrive = a.lora_ctl + kCtlArrive;
+  p.gain = nullptr; p.noise = nullptr; p.rstd = nullptr;
+  lora_producer<MR, GATED ? 1 : 0, kStreamWaves>(p, smem);
 }
 
 struct StreamTile { u32x4 c0, c1; u32x2 sc; };

@@ -14,7 +14,9 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
-LIB_PATH = os.path.join(HERE, "libqerl_nvfp4.so")
+LIB_PATH = os.environ.get("QERL_BUILD_LIB_PATH") or os.path.join(HERE, "libqerl_nvfp4.so")   # (tuning builds may go elsewhere)
+if os.environ.get("QERL_BUILD_OBJ_DIR"):
+    OBJ_DIR = os.environ["QERL_BUILD_OBJ_DIR"]
 
 # -packed-fp32-ops is switched off for all device code (v_pk_*_f32 are not to
 # be generated); quantize.hip additionally forbids fp contraction so that each

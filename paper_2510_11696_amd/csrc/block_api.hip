@@ -2,6 +2,7 @@
 //   aqn_rmsnorm_nvfp4_lora_linear_group  RMSNorm with noisy gain (Eq. 10) -> up to four NVFP4 + LoRA linears (Eq. 6, Eq. 2)
 //   aqn_rmsnorm_nvfp4_lora_mlp           RMSNorm -> gate_proj, up_proj -> SiLU(gate) (.) up -> down_proj
 // one launch each up to 16 tokens; beyond that they run the same operators as separate launches.
+#include <stdlib.h>
 #include "linear.hpp"
 
 namespace qerl {
@@ -11,11 +12,12 @@ static size_t blk_align256(size_t v) { return (v + 255) & ~(size_t)255; }
 // Workspace of a block launch: the control region every linear workspace starts with (arrival words of the tiles,
 // hand-over words), the producers' partial t of up to three stages, the K-ranges' partial tiles, and room for
 // intermediate activations.
-struct BlkWorkspace { size_t tpart_off, partial_off, act_off, total; };
+struct BlkWorkspace { size_t tpart_off, tfinal_off, partial_off, act_off, total; };
 static BlkWorkspace blk_workspace(size_t partial_floats, size_t act_bytes) {
   BlkWorkspace w;
   w.tpart_off = kCtrlRegionBytes;
-  w.partial_off = w.tpart_off + blk_align256((size_t)kBlkMaxStages * kBlkTpartWords * sizeof(uint32_t));
+  w.tfinal_off = w.tpart_off + blk_align256((size_t)kBlkMaxStages * kBlkTpartWords * sizeof(uint32_t));
+  w.partial_off = w.tfinal_off + blk_align256((size_t)kBlkMaxStages * kBlkTfinalWords * sizeof(float));
   w.act_off = w.partial_off + blk_align256(partial_floats * sizeof(float));
   w.total = w.act_off + blk_align256(act_bytes);
   return w;
@@ -47,6 +49,11 @@ static int blk_fill_stage(BlkStage& S, const void* x, int64_t K, int64_t ldx, co
     b.A = (const uint16_t*)m.A_bf16; b.B = (const uint16_t*)m.B_bf16; b.bias = (const uint16_t*)m.bias_bf16;
     b.y = (uint16_t*)m.y_bf16; b.ldy = m.ldy; b.N = m.N; b.n_tiles = (int)ceil_div(m.N, kPackTileRows); b.tile_begin = tiles;
     b.r = (int)m.r; b.lora_scale = m.lora_scale;
+    b.stride_k = kPackTileBytes; b.stride_n = (int64_t)S.k_tiles * kPackTileBytes;
+#ifdef QERL_TUNING_HOOKS   // timing experiment only (the weights are NOT in that order: results are wrong)
+    if (getenv("QERL_BLK_KMAJOR_TIMING")) { b.stride_n = kPackTileBytes; b.stride_k = (int64_t)b.n_tiles * kPackTileBytes; }
+    if (getenv("QERL_BLK_SAMETILE_TIMING")) { b.stride_n = 0; b.stride_k = 0; }   // every unit reads one tile: no memory traffic to speak of
+#endif
     b.y_vec = (m.y_bf16 && aligned(m.y_bf16, 16) && m.ldy % 8 == 0) ? 1 : 0;
     tiles += b.n_tiles;
   }
@@ -73,6 +80,7 @@ static int blk_plan_and_launch(BlkArgs& a, uint8_t* ws, size_t ws_bytes, size_t 
   a.counters = (uint32_t*)ws;
   a.ctl = (uint32_t*)ws + kCtrlMainWords + kCtrlDownWords;
   a.tpart = (uint32_t*)(ws + w.tpart_off);
+  a.tfinal = (float*)(ws + w.tfinal_off);
   a.partial = (float*)(ws + w.partial_off);
   return launch_block(a, lds, MR, st);
 }
@@ -168,6 +176,7 @@ static int mlp_impl(const void* x, int64_t M, int64_t H, int64_t ldx, const void
     a.counters = (uint32_t*)ws;
     a.ctl = (uint32_t*)ws + kCtrlMainWords + kCtrlDownWords;
     a.tpart = (uint32_t*)(ws + w.tpart_off);
+    a.tfinal = (float*)(ws + w.tfinal_off);
     a.partial = (float*)(ws + w.partial_off);
     return launch_block(a, lds, MR, (hipStream_t)stream);
   }

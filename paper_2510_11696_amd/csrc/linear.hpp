@@ -76,18 +76,25 @@ int plan_stream(StreamArgs& a, size_t* lds_bytes, int* MR);
 int launch_stream(const StreamArgs& a, size_t lds_bytes, int MR, hipStream_t st);
 
 // ---- persistent multi-stage decode kernel (linear_block.hip) ----
-constexpr int kBlkWaves = 12;            // waves per workgroup, one workgroup per CU
+#ifndef QERL_BLK_WAVES
+#define QERL_BLK_WAVES 8
+#endif
+constexpr int kBlkWaves = QERL_BLK_WAVES;   // waves per workgroup, one workgroup per CU
 constexpr int kBlkMaxStages = 3;         // dependent stages in one launch
-constexpr size_t kBlkTpartWords = 16 * 16 * 256;   // per stage: producers x tokens x stacked rank
+constexpr int kBlkMaxProducers = 32;     // producer workgroups of a stage
+constexpr size_t kBlkTpartWords = (size_t)kBlkMaxProducers * 16 * 256;   // per stage: producers along K x tokens x stacked rank
+constexpr size_t kBlkTfinalWords = 16 * 256;   // per stage: the finished t, tokens x stacked rank
 // control words of the block kernel, relative to the hand-over words of the workspace's control region
 constexpr int kBlkArrive = 8;            // + stage: producers of that stage that have stored their partial t
 constexpr int kBlkBarrier = 12;          // workgroups past the stage boundaries so far
 constexpr int kBlkExit = 13;             // workgroups that have left
+constexpr int kBlkReady = 20;            // + stage: the stage's t is complete in memory
 constexpr int kCtlErr = 16;              // sticky: a bounded wait gave up (bit 0 stage boundary, bit 1 LoRA hand-over, bit 2 another kernel's hand-over)
 struct BlkMember {
   const uint8_t* packed; const float* tensor_scale; const uint16_t* A; const uint16_t* B; const uint16_t* bias;
   uint16_t* y; int64_t ldy; int64_t N; int n_tiles; int tile_begin;   // row tiles [tile_begin, tile_begin + n_tiles) of the stage (unused entries: INT_MAX)
   int r; int t_off; float lora_scale; int y_vec;                       // rank; column of this member's t in the stage's stacked t; y rows allow 16-byte stores
+  int64_t stride_k; int64_t stride_n;                                  // bytes from a packed tile to the next K-tile of its row tile / to the same K-tile of the next row tile
 };
 struct BlkStage {
   const uint16_t* x; int64_t ldx; int64_t K; int k_tiles;              // input [M, K]: memory written before the launch, or by the previous stage
@@ -95,15 +102,16 @@ struct BlkStage {
   int n_members; BlkMember mem[kMaxGroup];
   int total_tiles; int total_v;                                        // row tiles of all members; units a wave takes whole (pairs: one per gate / up tile pair)
   int pairs; uint16_t* act; int64_t ld_act; int act_vec;               // members 0, 1 are gate_proj, up_proj: act[M, N] = SiLU(gate) (.) up is stored instead of their outputs
-  int Sk; int kr_len; int per_range;                                   // K-ranges, K-tiles in each (multiple of the ring depth), consumer workgroups per range
-  int n_producers; int r_total; int prod_steps; int prod_cb; int prod_red_off;   // LoRA down-projection of the stage (lora_producer.hpp)
+  int Sk; int phases; int kr_len; int per_range;                       // K is cut into Sk ranges (of workgroups) x phases (in time) x kr_len K-tiles (a multiple of the ring depth); consumer workgroups per range
+  int n_producers; int prod_k; int r_total; int prod_steps; int prod_cb; int prod_red_off;   // LoRA down-projection of the stage (lora_producer.hpp): producer workgroups = pairs of rank tiles x prod_k runs of K
   int ctr_off; int64_t partial_off;                                    // this stage's arrival words / partial tiles (floats) in the workspace areas
 };
 struct BlkArgs {
   int M; int n_stages; int n_wgs; int n_prod_max;                      // workgroups [0, n_prod_max) are the producers of every stage
   BlkStage st[kBlkMaxStages];
-  int t_lds_off; int y_lds_off;                                        // LDS: split t of the members; one output tile per wave
-  uint32_t* ctl; uint32_t* counters; float* partial; uint32_t* tpart;
+  int g_lds_off; int t_lds_off; int y_lds_off; int p_lds_off; int e_lds_off;   // LDS behind the x slice: gain + noise of the slice; split t of the members; one output tile per wave; parked accumulators; the pairs' hand-over
+  int park_units;                                                      // parked accumulator tiles per wave (stages with several phases)
+  uint32_t* ctl; uint32_t* counters; float* partial; uint32_t* tpart; float* tfinal;
 };
 int plan_block(BlkArgs& a, size_t* lds_bytes, int* MR, size_t* partial_floats, size_t* counter_words);
 int launch_block(const BlkArgs& a, size_t lds_bytes, int MR, hipStream_t st);

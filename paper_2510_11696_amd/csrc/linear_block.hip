@@ -42,8 +42,21 @@
 namespace qerl {
 
 constexpr int kBlkThreads = kBlkWaves * 64;
-constexpr int kBlkD = 4;                        // ring depth in tiles; every K-range length is a multiple of it
+#ifndef QERL_BLK_DEPTH
+#define QERL_BLK_DEPTH 4
+#endif
+constexpr int kBlkD = QERL_BLK_DEPTH;           // ring depth in tiles; every K-range length is a multiple of it
 constexpr uint32_t kBlkSpinLimit = 1u << 17;    // polls of a bounded wait (x s_sleep: tens of milliseconds)
+
+// Optional timeline stamps for tuning (build with -DQERL_BLK_TRACE): 16 time stamps (100 MHz) per wave, read back with
+// qerl_debug_read_block_trace().  Stamp 0 is the kernel entry; stage s uses 1 + 5 s ...: boundary passed, input
+// staged, first unit multiplied, first unit finished, last unit finished; 15 is the exit.
+#ifdef QERL_BLK_TRACE
+__device__ unsigned long long g_blk_trace[256 * kBlkWaves * 16];
+#define BSTAMP(p) do { if (lane == 0 && blockIdx.x < 256) g_blk_trace[((int)blockIdx.x * kBlkWaves + wave) * 16 + (p)] = wall_clock64(); } while (0)
+#else
+#define BSTAMP(p) do { } while (0)
+#endif
 
 struct BlkTile { u32x4 c0, c1; u32x2 sc; };
 
@@ -63,24 +76,55 @@ __device__ __forceinline__ void blk_issue(BlkTile& t, const uint8_t* base, int l
   t.sc = *reinterpret_cast<const u32x2*>(base + 2048 + n32 * 8);
 }
 
-// One packed tile (32 rows x 128 inputs = 8 scale blocks) times the x fragments at xk.
+// The eight x fragments (one per 16-input scale block) of a K-tile, from the LDS slice.  They are requested a whole
+// tile ahead (right after the previous tile's arithmetic, with the weight refill), so that no matrix instruction
+// ever waits for an LDS round trip.
+struct BlkXFrag { u32x4 f[8]; };
+__device__ __forceinline__ void blk_xload(BlkXFrag& x, const unsigned char* xk) {
+#ifdef QERL_BLK_NOXLOAD   // timing experiment
+  return;
+#endif
+#pragma unroll
+  for (int j = 0; j < 8; ++j) x.f[j] = *reinterpret_cast<const u32x4*>(xk + j * 32);
+}
+
+// One packed tile (32 rows x 128 inputs = 8 scale blocks) times its x fragments.  The issue order is pinned block by
+// block: the matrix instruction of block j + 1 goes out BEFORE the scale-and-add of block j (whose product was
+// issued a whole block earlier and is complete by then: no wait states), and the conversions of block j + 2 fill
+// the time the matrix unit needs.  Left to itself the scheduler puts each scale-and-add right behind its own
+// matrix instruction and pads the gap with idle cycles.
 template <int MR>
-__device__ __forceinline__ void blk_consume(const BlkTile& t, const unsigned char* xk, float (&acc)[MR]) {
+__device__ __forceinline__ void blk_consume(const BlkTile& t, const BlkXFrag& x, float (&acc)[MR]) {
+#ifdef QERL_BLK_NOCOMPUTE   // timing experiment: the loads stay alive, the arithmetic is gone
+  acc[0] += __uint_as_float((t.c0[0] ^ t.c0[3] ^ t.c1[0] ^ t.c1[3] ^ t.sc[0] ^ t.sc[1] ^ x.f[0][0] ^ x.f[7][3]) & 0x3fffffu);
+  return;
+#endif
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   f32x16 tmp[2];
-  tmp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(xk)),
-                                                   blk_e2m1x8(t.c0[0]), zero, 0, 0, 0);
+  bf16x8 w = blk_e2m1x8(t.c0[0]);
+  tmp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, x.f[0]), w, zero, 0, 0, 0);
+  w = blk_e2m1x8(t.c0[1]);
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    if (j + 1 < 8) {   // the product of the next scale block is on its way while this one is scaled and added
-      const bf16x8 xa = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(xk + (j + 1) * 32));
-      const bf16x8 w = blk_e2m1x8(j + 1 < 4 ? t.c0[(j + 1) & 3] : t.c1[(j + 1) & 3]);
-      tmp[(j + 1) & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, w, zero, 0, 0, 0);
-    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (j + 1 < 8) tmp[(j + 1) & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, x.f[j + 1]), w, zero, 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
     const float s = e4m3_byte_f32(t.sc[j >> 2], j & 3);
 #pragma unroll
     for (int q = 0; q < MR; ++q) acc[q] = __builtin_fmaf(s, tmp[j & 1][q], acc[q]);
+    if (j + 2 < 8) w = blk_e2m1x8(j + 2 < 4 ? t.c0[(j + 2) & 3] : t.c1[(j + 2) & 3]);
+    // all 16 registers of the product stay reserved until here: handing the unused ones to other values would
+    // make those writes wait for the matrix instruction that is still writing the block (a dozen idle cycles each)
+    asm volatile("" :: "v"(tmp[j & 1]));
   }
+}
+
+// Workgroup barrier for data that went through LDS only: waits for this wave's LDS operations, not for its
+// outstanding global loads (__syncthreads() would wait for the whole weight ring to come in).
+__device__ __forceinline__ void blk_lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
 }
 
 // Bounded wait until *word >= target (agent scope).  Returns false when it gave up.
@@ -97,7 +141,6 @@ __global__ __launch_bounds__(kBlkThreads) void block_kernel(const BlkArgs a) {
   // dynamic LDS: x slice [M + 1 rows][xs_stride], then the split t of up to four members, then one output tile
   // per wave.  256-byte alignment matters: 16-byte LDS accesses from a misaligned base run several times slower.
   extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
-  __shared__ float s_ss[kBlkWaves][16];
   __shared__ float s_rstd[16];
   __shared__ uint32_t s_tstate[kMaxGroup];   // per member: 0 t not loaded, 1 being loaded, 2 in LDS, 3 in LDS but the producers never arrived
   constexpr int MT = MR == 4 ? 8 : 16;
@@ -108,21 +151,27 @@ __global__ __launch_bounds__(kBlkThreads) void block_kernel(const BlkArgs a) {
   const int wg = (int)blockIdx.x;
   const bool prod_wg = wg < a.n_prod_max;
   const int cons = wg - a.n_prod_max;         // consumer workgroup index
+  BSTAMP(0);
   uint32_t* const err_word = a.ctl + kCtlErr;
   unsigned char* const tarea = smem + a.t_lds_off;
   uint16_t* const ytile = reinterpret_cast<uint16_t*>(smem + a.y_lds_off) + wave * (16 * 32);
 
   // ---- stage boundary: everybody's outputs of the previous stage are complete and visible ----------------------
+  // (What a later stage reads -- the gated activation -- is stored with agent-scope atomic stores, which go
+  // through to memory, so no cache write-back is needed here: each wave waits for its own stores, one thread
+  // counts the workgroup in and waits for the others, one wave invalidates the CU's caches.)
   auto stage_boundary = [&](int s) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's stores of the stage have completed
     __syncthreads();
-    if (tid == 0) {
-      __hip_atomic_fetch_add(a.ctl + kBlkBarrier, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (!blk_wait_ge(a.ctl + kBlkBarrier, (uint32_t)(a.n_wgs * s), 1))
-        __hip_atomic_fetch_or(err_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (wave == 0) {
+      if (lane == 0) {
+        __hip_atomic_fetch_add(a.ctl + kBlkBarrier, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (!blk_wait_ge(a.ctl + kBlkBarrier, (uint32_t)(a.n_wgs * s), 1))
+          __hip_atomic_fetch_or(err_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     }
     __syncthreads();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
   };
   // ---- exit: the last workgroup to leave re-arms the control words, unless a wait gave up somewhere -------------
   auto leave = [&]() {
@@ -131,8 +180,10 @@ __global__ __launch_bounds__(kBlkThreads) void block_kernel(const BlkArgs a) {
       const uint32_t old = __hip_atomic_fetch_add(a.ctl + kBlkExit, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (old == (uint32_t)(a.n_wgs - 1) &&
           __hip_atomic_load(err_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
-        for (int s = 0; s < kBlkMaxStages; ++s)
+        for (int s = 0; s < kBlkMaxStages; ++s) {
           __hip_atomic_store(a.ctl + kBlkArrive + s, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_store(a.ctl + kBlkReady + s, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         __hip_atomic_store(a.ctl + kBlkBarrier, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(a.ctl + kBlkExit, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
@@ -155,29 +206,28 @@ __global__ __launch_bounds__(kBlkThreads) void block_kernel(const BlkArgs a) {
     for (int s = 0; s < a.n_stages; ++s) {
       const BlkStage& S = a.st[s];
       if (s > 0) stage_boundary(s);
+      BSTAMP(1 + 5 * s);
       if (wg >= S.n_producers) continue;
       const bool norm = S.gain != nullptr;
-      if (norm) {                      // row statistics over all of K
+      if (norm) {                      // row statistics over all of K: wave w owns token rows w and w + 8
         const int chunks_row = (int)(S.K / 8);
-        float ss[MT];
 #pragma unroll
-        for (int t = 0; t < MT; ++t) ss[t] = 0.f;
-        for (int ch = tid; ch < chunks_row; ch += kBlkThreads) {
+        for (int r = 0; r < MT / 8; ++r) {
+          const int t = wave + 8 * r;
+          float ss = 0.f;
+          for (int c0 = 0; c0 < chunks_row; c0 += 64 * 10) {
+            u32x4 xq[10];
 #pragma unroll
-          for (int t = 0; t < MT; ++t)
-            if (t < a.M) ss[t] += sumsq(*reinterpret_cast<const u32x4*>(S.x + (int64_t)t * S.ldx + (int64_t)ch * 8));
-        }
+            for (int i = 0; i < 10; ++i) {
+              const int c = c0 + lane + 64 * i;
+              xq[i] = u32x4{0u, 0u, 0u, 0u};
+              if (t < a.M && c < chunks_row) xq[i] = *reinterpret_cast<const u32x4*>(S.x + (int64_t)t * S.ldx + (int64_t)c * 8);
+            }
 #pragma unroll
-        for (int t = 0; t < MT; ++t) {
-          const float w = wave_sum(ss[t]);
-          if (lane == 0) s_ss[wave][t] = w;
-        }
-        __syncthreads();
-        if (tid < a.M) {
-          float total = 0.f;
-#pragma unroll
-          for (int w = 0; w < kBlkWaves; ++w) total += s_ss[w][tid];
-          s_rstd[tid] = 1.0f / sqrtf(total / (float)S.K + S.eps);
+            for (int i = 0; i < 10; ++i) ss += sumsq(xq[i]);
+          }
+          const float rstd = 1.0f / sqrtf(wave_sum(ss) / (float)S.K + S.eps);
+          if (lane == 0 && t < a.M) s_rstd[t] = rstd;
         }
         __syncthreads();
       }
@@ -186,407 +236,559 @@ __global__ __launch_bounds__(kBlkThreads) void block_kernel(const BlkArgs a) {
       p.M = a.M; p.K = S.K; p.r_total = S.r_total; p.n_members = S.n_members;
 #pragma unroll
       for (int i = 0; i < kMaxGroup; ++i) { p.A[i] = S.mem[i].A; p.t_off[i] = S.mem[i].t_off; }
-      p.index = wg;
+      p.index = wg % S.prod_k; p.only_pair = wg / S.prod_k; p.n_arrivals = S.n_producers; p.n_k = S.prod_k;
+      p.tfinal = a.tfinal + (int64_t)s * kBlkTfinalWords; p.ready = a.ctl + kBlkReady + s;
       p.prod_steps = S.prod_steps; p.prod_cb = S.prod_cb; p.prod_red_off = S.prod_red_off;
       p.tpart = a.tpart + (int64_t)s * kBlkTpartWords; p.arrive = a.ctl + kBlkArrive + s;
       p.gain = S.gain; p.noise = S.noise; p.rstd = s_rstd;
+      BSTAMP(2 + 5 * s);
       if (norm) lora_producer<MR, 2, kBlkWaves>(p, smem);
       else lora_producer<MR, 0, kBlkWaves>(p, smem);
+      BSTAMP(5 + 5 * s);
     }
+    BSTAMP(15);
     leave();
     return;
   }
 
   // ---- which units are mine ----------------------------------------------------------------------------------
-  struct Geo { int range, slot, slots_r, n_my, kr0, nvalid; };
+  // A stage's K-tiles are cut into Sk ranges (of workgroups) x `phases` (in time) x kr_len tiles.  A wave owns row
+  // tiles outright: tile v = slot + j * slots_r of its range, j = 0 .. n_my - 1, and walks each of them once per
+  // phase (the accumulators wait in LDS between phases, the workgroup re-stages its x slice at each phase).
+  // Pairs (gate_proj / up_proj): waves 0..3 of a workgroup take gate tiles, waves 4..7 the up tiles of the same
+  // rows; wave w + 4 hands its finished tile to wave w, which forms SiLU(gate) (.) up and stores it.
+  struct Geo { int range, slot, slots_r, n_my; };
   auto geo = [&](int s) {
     const BlkStage& S = a.st[s];
     Geo g;
     g.range = cons / S.per_range;
     const int ci = cons - g.range * S.per_range;
-    g.slot = ci * kBlkWaves + wave;
-    g.slots_r = S.per_range * kBlkWaves;
+    if (S.pairs) { g.slot = ci * (kBlkWaves / 2) + (wave & 3); g.slots_r = S.per_range * (kBlkWaves / 2); }
+    else { g.slot = ci * kBlkWaves + wave; g.slots_r = S.per_range * kBlkWaves; }
     g.n_my = (g.range < S.Sk && g.slot < S.total_v) ? (S.total_v - g.slot + g.slots_r - 1) / g.slots_r : 0;
-    g.kr0 = g.range * S.kr_len;
-    const int left = S.k_tiles - g.kr0;
-    g.nvalid = left < S.kr_len ? left : S.kr_len;
     return g;
   };
-  struct Pass { int s, j, h; Geo g; };
+  auto seg_k0 = [&](const BlkStage& S, int range, int ph) { return (range * S.phases + ph) * S.kr_len; };
+  struct Pass { int s, ph, j; Geo g; };
   // row tile (within the stage's stacked members) of a pass
   auto pass_tile = [&](const Pass& p) {
     const BlkStage& S = a.st[p.s];
     const int v = p.g.slot + p.j * p.g.slots_r;
-    return (S.pairs && p.h) ? S.mem[1].tile_begin + v : v;
+    return (S.pairs && wave >= kBlkWaves / 2) ? S.mem[1].tile_begin + v : v;
   };
   auto member_of = [&](const BlkStage& S, int nt) {
     return (nt >= S.mem[1].tile_begin ? 1 : 0) + (nt >= S.mem[2].tile_begin ? 1 : 0) + (nt >= S.mem[3].tile_begin ? 1 : 0);
   };
-  auto pass_base = [&](const Pass& p) {
+  // address of the first tile of a pass, its K-tiles that exist, and the distance between successive K-tiles (the
+  // members' tile order is given by two strides: row-tile-major as nvfp4_prepack writes it, or K-tile-major)
+  auto pass_base = [&](const Pass& p, int64_t& kstride, int& nvalid) {
     const BlkStage& S = a.st[p.s];
     const int nt = pass_tile(p);
     int tb = 0;
     const uint8_t* mp = S.mem[0].packed;
-    if (nt >= S.mem[1].tile_begin) { tb = S.mem[1].tile_begin; mp = S.mem[1].packed; }
-    if (nt >= S.mem[2].tile_begin) { tb = S.mem[2].tile_begin; mp = S.mem[2].packed; }
-    if (nt >= S.mem[3].tile_begin) { tb = S.mem[3].tile_begin; mp = S.mem[3].packed; }
-    return mp + ((int64_t)(nt - tb) * S.k_tiles + p.g.kr0) * kPackTileBytes;
+    int64_t sk = S.mem[0].stride_k, sn = S.mem[0].stride_n;
+    if (nt >= S.mem[1].tile_begin) { tb = S.mem[1].tile_begin; mp = S.mem[1].packed; sk = S.mem[1].stride_k; sn = S.mem[1].stride_n; }
+    if (nt >= S.mem[2].tile_begin) { tb = S.mem[2].tile_begin; mp = S.mem[2].packed; sk = S.mem[2].stride_k; sn = S.mem[2].stride_n; }
+    if (nt >= S.mem[3].tile_begin) { tb = S.mem[3].tile_begin; mp = S.mem[3].packed; sk = S.mem[3].stride_k; sn = S.mem[3].stride_n; }
+    kstride = sk;
+    const int k0 = seg_k0(S, p.g.range, p.ph);
+    const int left = S.k_tiles - k0;
+    nvalid = left < S.kr_len ? left : S.kr_len;
+    return mp + (int64_t)(nt - tb) * sn + (int64_t)k0 * sk;
   };
   auto next_pass = [&](Pass& p) {     // false: there is none
-    if (a.st[p.s].pairs && p.h == 0) { p.h = 1; return true; }
-    p.h = 0;
     ++p.j;
-    while (p.j >= p.g.n_my) {
+    if (p.j < p.g.n_my) return true;
+    p.j = 0;
+    ++p.ph;
+    if (p.g.n_my > 0 && p.ph < a.st[p.s].phases) return true;
+    p.ph = 0;
+    for (;;) {
       ++p.s;
       if (p.s >= a.n_stages) return false;
       p.g = geo(p.s);
-      p.j = 0;
+      if (p.g.n_my > 0) return true;
     }
-    return true;
   };
 
   Pass cur;
-  cur.s = 0; cur.j = -1; cur.h = 0; cur.g = geo(0);
-  if (a.st[0].pairs) cur.h = 1;        // so that next_pass() steps to (j = 0, h = 0)
+  cur.s = -1; cur.ph = 0; cur.j = 0; cur.g = Geo{0, 0, 1, 0};
   bool have_cur = next_pass(cur);
   const uint8_t* const park = a.st[0].mem[0].packed;   // where loads go that nobody needs: always valid memory
-
-  // ---- the ring: first D tiles of my first unit, requested before anything else ---------------------------------
   BlkTile ring[D];
-  {
-    const uint8_t* b0 = have_cur ? pass_base(cur) : park;
-    const int nv = have_cur ? cur.g.nvalid : 1;
+  auto issue_first_ring = [&]() {      // first D tiles of my first unit
+    int64_t ks0 = 0;
+    int nv = 1;
+    const uint8_t* b0 = have_cur ? pass_base(cur, ks0, nv) : park;
+    if (!have_cur) { ks0 = 0; nv = 1; }
 #pragma unroll
-    for (int d = 0; d < D; ++d) blk_issue(ring[d], b0 + (int64_t)(d < nv ? d : nv - 1) * kPackTileBytes, lane, n32);
-  }
+    for (int d = 0; d < D; ++d) blk_issue(ring[d], b0 + (int64_t)(d < nv ? d : nv - 1) * ks0, lane, n32);
+  };
 
-  float held[MR];                      // gate_proj's finished tile while up_proj's is being computed (pairs, one K-range)
+  // ---- stage input: the K-tiles of (stage, range, phase) into LDS, normalised on the way if the stage normalises -----
+  // Wave w owns token rows w and w + 8: it requests its rows' chunks (all of the row in the first phase of a
+  // normalising stage, for the row statistics; the slice otherwise) in one round of loads, sums the squares, knows
+  // rstd without asking anybody, and writes the slice to LDS; gain + noise of the slice go to LDS once (thread =
+  // chunk) and the rows are normalised in place.  For the very first input the weight ring is requested right
+  // behind the input's loads and before anything waits for them: a load issued behind the ring would wait for
+  // ~70 KB per CU to come in first, and a ring issued after the staging would start microseconds late.
+  constexpr int XB = MR == 4 ? 10 : 8;                      // chunks per lane and row in flight (registers: XB x rows x 4)
+  constexpr int XR = MT / 8;                                // rows per wave
+  auto stage_input = [&](int s, int ph, bool with_ring) {
+    const BlkStage& S = a.st[s];
+    const Geo g0 = geo(s);                                  // the range is the same for all waves of the workgroup
+    const int xs_stride = S.kr_len * 256 + 16;
+    const int chunks_row = (int)(S.K / 8);                  // 16-byte chunks of a row
+    const int sl_chunks = S.kr_len * 16;                    // chunks of the slice (K-tiles padded)
+    const int sl0 = seg_k0(S, g0.range, ph) * 16;
+    const int sl_end = sl0 + sl_chunks < chunks_row ? sl0 + sl_chunks : chunks_row;
+    const bool stage_slice = g0.range < S.Sk;
+    const bool norm = S.gain != nullptr;
+    const bool stats = norm && ph == 0;
+    // gain + noise of the slice: thread = chunk, at most two chunks per thread
+    u32x4 gv[2];
+    f32x4 zv[2][2];
+    if (norm && stage_slice) {
 #pragma unroll
-  for (int q = 0; q < MR; ++q) held[q] = 0.f;
+      for (int c = 0; c < 2; ++c) {
+        const int lc = tid + c * kBlkThreads, ch = sl0 + lc;
+        gv[c] = u32x4{0u, 0u, 0u, 0u};
+        zv[c][0] = f32x4{0.f, 0.f, 0.f, 0.f}; zv[c][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (lc < sl_chunks && ch < chunks_row) {
+          gv[c] = *reinterpret_cast<const u32x4*>(S.gain + (int64_t)ch * 8);
+          if (S.noise) {
+            zv[c][0] = *reinterpret_cast<const f32x4*>(S.noise + (int64_t)ch * 8);
+            zv[c][1] = *reinterpret_cast<const f32x4*>(S.noise + (int64_t)ch * 8 + 4);
+          }
+        }
+      }
+    }
+    // my rows
+    float ss[XR];
+#pragma unroll
+    for (int r = 0; r < XR; ++r) ss[r] = 0.f;
+    const int cb = stats ? 0 : sl0, ce = stats ? chunks_row : sl_end;
+    bool ring_pending = with_ring;
+    if (stage_slice) {
+      for (int c0 = cb; c0 < ce; c0 += 64 * XB) {
+        u32x4 xq[XR][XB];
+#pragma unroll
+        for (int r = 0; r < XR; ++r) {
+          const int t = wave + 8 * r;
+#pragma unroll
+          for (int i = 0; i < XB; ++i) {
+            const int c = c0 + lane + 64 * i;
+            xq[r][i] = u32x4{0u, 0u, 0u, 0u};
+            if (t < a.M && c < ce) xq[r][i] = *reinterpret_cast<const u32x4*>(S.x + (int64_t)t * S.ldx + (int64_t)c * 8);
+          }
+        }
+        if (ring_pending) { issue_first_ring(); ring_pending = false; }
+#pragma unroll
+        for (int r = 0; r < XR; ++r) {
+          const int t = wave + 8 * r;
+#pragma unroll
+          for (int i = 0; i < XB; ++i) {
+            const int c = c0 + lane + 64 * i;
+            if (stats) ss[r] += sumsq(xq[r][i]);
+            if (t < a.M && c >= sl0 && c < sl_end) *reinterpret_cast<u32x4*>(smem + t * xs_stride + (c - sl0) * 16) = xq[r][i];
+          }
+        }
+      }
+    }
+    if (ring_pending) issue_first_ring();
+    if (stage_slice) {
+      // the zero row, and zeros where the slice is padded beyond K
+      for (int lc = tid; lc < sl_chunks; lc += kBlkThreads) {
+        *reinterpret_cast<u32x4*>(smem + a.M * xs_stride + lc * 16) = u32x4{0u, 0u, 0u, 0u};
+        if (sl0 + lc >= chunks_row)
+          for (int t = 0; t < a.M; ++t) *reinterpret_cast<u32x4*>(smem + t * xs_stride + lc * 16) = u32x4{0u, 0u, 0u, 0u};
+      }
+    }
+    if (norm) {
+      if (stats) {
+#pragma unroll
+        for (int r = 0; r < XR; ++r) {
+          const int t = wave + 8 * r;
+          const float rstd = 1.0f / sqrtf(wave_sum(ss[r]) / (float)S.K + S.eps);
+          if (lane == 0 && t < a.M) s_rstd[t] = rstd;        // (kept for the later phases)
+        }
+      }
+      blk_lds_barrier();             // the raw rows and every row's rstd are in LDS
+      if (stage_slice) {
+        // normalised in place, thread = chunk (all threads busy whatever the number of tokens); gain + noise are in registers
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          const int lc = tid + c * kBlkThreads;
+          if (lc < sl_chunks && sl0 + lc < chunks_row) {
+            float g[8];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              g[2 * j] = bf16_bits_to_f32(gv[c][j] & 0xffffu) + zv[c][j >> 1][(2 * j) & 3];
+              g[2 * j + 1] = bf16_bits_to_f32(gv[c][j] >> 16) + zv[c][j >> 1][(2 * j + 1) & 3];
+            }
+            u32x4 o[MT];
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+              if (t < a.M) o[t] = *reinterpret_cast<const u32x4*>(smem + t * xs_stride + lc * 16);
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+              if (t < a.M) {
+                const float rs = s_rstd[t];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                  const float lo = bf16_bits_to_f32(o[t][j] & 0xffffu), hi = bf16_bits_to_f32(o[t][j] >> 16);
+                  o[t][j] = pack_bf16x2(g[2 * j] * (lo * rs), g[2 * j + 1] * (hi * rs));
+                }
+                *reinterpret_cast<u32x4*>(smem + t * xs_stride + lc * 16) = o[t];
+              }
+            }
+          }
+        }
+      }
+    }
+    blk_lds_barrier();
+  };
+
+  float* const parkbuf = reinterpret_cast<float*>(smem + a.p_lds_off) + wave * a.park_units * 64 * MR;
+  uint32_t* const xflag = reinterpret_cast<uint32_t*>(smem + a.e_lds_off);                    // [4] units handed over, [4] units taken
+  float* const xbuf = reinterpret_cast<float*>(smem + a.e_lds_off + 64) + (wave & 3) * 64 * MR;  // the pair's up_proj tile
+  if (tid < 8) xflag[tid] = 0u;
+  if (tid < kMaxGroup) s_tstate[tid] = 0u;
 
   for (int s = 0; s < a.n_stages; ++s) {
     const BlkStage& S = a.st[s];
-    if (s > 0) stage_boundary(s);
-    if (tid < kMaxGroup) s_tstate[tid] = 0u;
-
-    // ---- stage input: this workgroup's K-range slice into LDS (all of K for a producer's row statistics) --------
     const Geo g0 = geo(s);             // range and K-tiles are the same for all waves of the workgroup
     const int xs_stride = S.kr_len * 256 + 16;
-    const int chunks_row = (int)(S.K / 8);                 // 16-byte chunks of a row
-    const int sl_chunks = S.kr_len * 16;                   // chunks of the slice (K-tiles padded)
-    const int sl0 = g0.kr0 * 16;
-    const bool stage_slice = g0.range < S.Sk;
-    const bool norm = S.gain != nullptr;
-    float ss[MT];
-#pragma unroll
-    for (int t = 0; t < MT; ++t) ss[t] = 0.f;
-    if (stage_slice) {
-      for (int lc = tid; lc < sl_chunks; lc += kBlkThreads) {
-        const int ch = sl0 + lc;
-#pragma unroll
-        for (int t0 = 0; t0 < MT; t0 += 8) {
-          u32x4 v[8];
-#pragma unroll
-          for (int t = 0; t < 8; ++t) {
-            v[t] = u32x4{0u, 0u, 0u, 0u};
-            if (t0 + t < a.M && ch < chunks_row) v[t] = *reinterpret_cast<const u32x4*>(S.x + (int64_t)(t0 + t) * S.ldx + (int64_t)ch * 8);
-          }
-#pragma unroll
-          for (int t = 0; t < 8; ++t) {
-            if (t0 + t < a.M) *reinterpret_cast<u32x4*>(smem + (t0 + t) * xs_stride + lc * 16) = v[t];
-            if (norm) ss[t0 + t] += sumsq(v[t]);
-          }
-        }
-        *reinterpret_cast<u32x4*>(smem + a.M * xs_stride + lc * 16) = u32x4{0u, 0u, 0u, 0u};   // the zero row
-      }
-    }
-    if (norm && stage_slice) {
-      // the rest of the rows, for the statistics only
-      for (int ch = tid; ch < chunks_row; ch += kBlkThreads) {
-        if (ch >= sl0 && ch < sl0 + sl_chunks) continue;
-#pragma unroll
-        for (int t = 0; t < MT; ++t)
-          if (t < a.M) ss[t] += sumsq(*reinterpret_cast<const u32x4*>(S.x + (int64_t)t * S.ldx + (int64_t)ch * 8));
-      }
-#pragma unroll
-      for (int t = 0; t < MT; ++t) {
-        const float w = wave_sum(ss[t]);
-        if (lane == 0) s_ss[wave][t] = w;
-      }
-    }
-    __syncthreads();
-    if (norm && tid < a.M) {
-      float total = 0.f;
-#pragma unroll
-      for (int w = 0; w < kBlkWaves; ++w) total += s_ss[w][tid];
-      s_rstd[tid] = 1.0f / sqrtf(total / (float)S.K + S.eps);
-    }
-    __syncthreads();
-    if (norm && stage_slice) {
-      for (int lc = tid; lc < sl_chunks; lc += kBlkThreads) {
-        const int ch = sl0 + lc;
-        if (ch < chunks_row) {
-          for (int t = 0; t < a.M; ++t) {
-            u32x4* p = reinterpret_cast<u32x4*>(smem + t * xs_stride + lc * 16);
-            *p = norm_scale8(*p, s_rstd[t], S.gain, S.noise, (int64_t)ch * 8);
-          }
-        }
-      }
-    }
-    __syncthreads();
-
-    // ---- my units of this stage ----------------------------------------------------------------------------------
     const int xrow = n32 < a.M ? n32 : a.M;
     const unsigned char* const xbase = smem + xrow * xs_stride + kg * 16;
-    const bool first_range = g0.range == 0;
-    while (have_cur && cur.s == s) {
-      const int nt = pass_tile(cur);
-      const int mi = member_of(S, nt);
-      const BlkMember& mem = S.mem[mi];
-      const uint8_t* const base = pass_base(cur);
-      const int nvalid = cur.g.nvalid;
-      float acc[MR];
+    const bool pair_up = S.pairs && wave >= kBlkWaves / 2;   // this wave computes up_proj tiles and hands them over
+    for (int ph = 0; ph < S.phases; ++ph) {
+      if (ph == 0) {
+        if (s > 0) {
+          stage_boundary(s);
+          if (tid < kMaxGroup) s_tstate[tid] = 0u;
+          if (tid < 8) xflag[tid] = 0u;
+        }
+      } else {
+        blk_lds_barrier();             // every wave is done with the previous phase's x slice
+      }
+      stage_input(s, ph, s == 0 && ph == 0);
+      BSTAMP(2 + 5 * s);
+      bool first_pass = true;
+      BlkXFrag xf;
+      const bool last_phase = ph + 1 == S.phases;
+      while (have_cur && cur.s == s && cur.ph == ph) {
+        const int nt = pass_tile(cur);
+        const int mi = member_of(S, nt);
+        const BlkMember& mem = S.mem[mi];
+        int64_t kstride = 0;
+        int nvalid = 1;
+        const uint8_t* const base = pass_base(cur, kstride, nvalid);
+        float* const myslot = parkbuf + (cur.j * 64 + lane) * MR;
+        float acc[MR];
+        if (ph == 0) {
 #pragma unroll
-      for (int q = 0; q < MR; ++q) acc[q] = 0.f;
-      int i0 = 0;
-      for (; i0 + D < S.kr_len; i0 += D) {
+          for (int q = 0; q < MR; ++q) acc[q] = 0.f;
+        } else {
+#pragma unroll
+          for (int q4 = 0; q4 < MR / 4; ++q4) {
+            const f32x4 v = *reinterpret_cast<const f32x4*>(myslot + 4 * q4);
+            acc[4 * q4] = v[0]; acc[4 * q4 + 1] = v[1]; acc[4 * q4 + 2] = v[2]; acc[4 * q4 + 3] = v[3];
+          }
+        }
+        if (first_pass) blk_xload(xf, xbase);   // (later units: requested at the end of the unit before)
+        int i0 = 0;
+        for (; i0 + D < S.kr_len; i0 += D) {
+#pragma unroll
+          for (int d = 0; d < D; ++d) {
+            if (i0 + d < nvalid) blk_consume<MR>(ring[d], xf, acc);
+            // the refill stays below the last use of the slot (see linear_stream.hip): same registers, no copies
+#pragma unroll
+            for (int q = 0; q < MR; ++q) asm volatile("" : "+v"(acc[q]));
+            __builtin_amdgcn_sched_barrier(0);
+            const int nx = i0 + D + d;
+            blk_issue(ring[d], base + (int64_t)(nx < nvalid ? nx : nvalid - 1) * kstride, lane, n32);
+            blk_xload(xf, xbase + (i0 + d + 1) * 256);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+        // last ring round of the unit: what the epilogue reads from memory is requested now, then the refills go
+        // to the next unit (of this or a later phase or stage)
+        Pass nxt = cur;
+        const bool have_next = next_pass(nxt);
+        int64_t nkstride = 0;
+        int nnv = 1;
+        const uint8_t* const nbase = have_next ? pass_base(nxt, nkstride, nnv) : park;
+        if (!have_next) { nkstride = 0; nnv = 1; }
+        const bool lora = last_phase && mem.r > 0;   // (with K split over ranges, the wave that adds the shares applies it)
+        const int64_t row0 = (int64_t)(nt - mem.tile_begin) * 32;
+        u32x4 bfrag[4];
+        {
+          int64_t brow = row0 + n32;
+          brow = brow < mem.N ? brow : mem.N - 1;
+#pragma unroll
+          for (int st = 0; st < 4; ++st) {
+            const int j0 = 16 * st + 8 * kg;
+            const bool live = lora && j0 < mem.r;   // (every unit issues the same number of loads: the wait counts stay exact)
+            const uint16_t* src = live ? mem.B + brow * mem.r + j0 : reinterpret_cast<const uint16_t*>(park) + lane * 8;
+            bfrag[st] = *reinterpret_cast<const u32x4*>(src);
+            if (!live) bfrag[st] = u32x4{0u, 0u, 0u, 0u};
+          }
+        }
+        uint16_t bias_bits = 0;
+        {
+          const bool live = last_phase && mem.bias && row0 + n32 < mem.N;
+          const uint16_t* src = live ? mem.bias + row0 + n32 : reinterpret_cast<const uint16_t*>(park);
+          bias_bits = *src;
+          if (!live) bias_bits = 0;
+        }
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-          if (i0 + d < nvalid) blk_consume<MR>(ring[d], xbase + (i0 + d) * 256, acc);
-          // the refill stays below the last use of the slot (see linear_stream.hip): same registers, no copies
+          if (i0 + d < nvalid) blk_consume<MR>(ring[d], xf, acc);
 #pragma unroll
           for (int q = 0; q < MR; ++q) asm volatile("" : "+v"(acc[q]));
           __builtin_amdgcn_sched_barrier(0);
-          const int nx = i0 + D + d;
-          blk_issue(ring[d], base + (int64_t)(nx < nvalid ? nx : nvalid - 1) * kPackTileBytes, lane, n32);
+          blk_issue(ring[d], nbase + (int64_t)(d < nnv ? d : nnv - 1) * nkstride, lane, n32);
+          blk_xload(xf, xbase + (d + 1 < D ? i0 + d + 1 : 0) * 256);   // the unit's next tile, or the first tile of the next unit of this phase
+          __builtin_amdgcn_sched_barrier(0);
         }
-      }
-      // last ring round of the unit: what the epilogue reads from memory is requested now, then the refills go
-      // to the next unit (of this or the next stage)
-      Pass nxt = cur;
-      const bool have_next = next_pass(nxt);
-      const uint8_t* const nbase = have_next ? pass_base(nxt) : park;
-      const int nnv = have_next ? nxt.g.nvalid : 1;
-      const bool lora = first_range && mem.r > 0;
-      const int64_t row0 = (int64_t)(nt - mem.tile_begin) * 32;
-      u32x4 bfrag[4];
-      {
-        int64_t brow = row0 + n32;
-        brow = brow < mem.N ? brow : mem.N - 1;
-#pragma unroll
-        for (int st = 0; st < 4; ++st) {
-          const int j0 = 16 * st + 8 * kg;
-          const bool live = lora && j0 < mem.r;   // (every unit issues the same number of loads: the wait counts stay exact)
-          const uint16_t* src = live ? mem.B + brow * mem.r + j0 : reinterpret_cast<const uint16_t*>(park) + lane * 8;
-          bfrag[st] = *reinterpret_cast<const u32x4*>(src);
-          if (!live) bfrag[st] = u32x4{0u, 0u, 0u, 0u};
-        }
-      }
-      uint16_t bias_bits = 0;
-      {
-        const uint16_t* src = (first_range && mem.bias && row0 + n32 < mem.N) ? mem.bias + row0 + n32
-                                                                            : reinterpret_cast<const uint16_t*>(park);
-        bias_bits = *src;
-        if (!(first_range && mem.bias && row0 + n32 < mem.N)) bias_bits = 0;
-      }
-#pragma unroll
-      for (int d = 0; d < D; ++d) {
-        if (i0 + d < nvalid) blk_consume<MR>(ring[d], xbase + (i0 + d) * 256, acc);
-#pragma unroll
-        for (int q = 0; q < MR; ++q) asm volatile("" : "+v"(acc[q]));
-        __builtin_amdgcn_sched_barrier(0);
-        blk_issue(ring[d], nbase + (int64_t)(d < nnv ? d : nnv - 1) * kPackTileBytes, lane, n32);
-      }
+        if (first_pass) BSTAMP(3 + 5 * s);
 
-      // ---- epilogue of the unit ------------------------------------------------------------------------------------
-      const float S32 = *mem.tensor_scale;
-      float out[MR];
+        if (!last_phase) {
+          // more K to come for this tile: the accumulators wait in LDS
 #pragma unroll
-      for (int q = 0; q < MR; ++q) out[q] = acc[q] * S32;
-      if (lora) {
-        // t of this member in LDS as three bf16 terms; the first wave of the workgroup that needs it puts it there
-        uint32_t ts = __hip_atomic_load(&s_tstate[mi], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP);
-        if (ts < 2u) {
-          int won = 0;
-          if (lane == 0) {
-            uint32_t expect = 0u;
-            won = __hip_atomic_compare_exchange_strong(&s_tstate[mi], &expect, 1u, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
-                                                       __HIP_MEMORY_SCOPE_WORKGROUP) ? 1 : 0;
-          }
-          won = __builtin_amdgcn_readfirstlane(won);
-          if (won) {
-            const bool arrived = blk_wait_ge(a.ctl + kBlkArrive + s, (uint32_t)S.n_producers, 32);
-            if (!arrived && lane == 0) __hip_atomic_fetch_or(err_word, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-            const int r4 = mem.r >> 2, n4 = a.M * r4;
-            const float* src = reinterpret_cast<const float*>(a.tpart + (int64_t)s * kBlkTpartWords) + mem.t_off;
-            uint16_t* th = reinterpret_cast<uint16_t*>(tarea) + (mi * 3) * MT * 64;
-            for (int e0 = 0; e0 < n4; e0 += 64) {
-              const int e = e0 + lane, tok = e / r4, j4 = e - tok * r4;
-              f32x4 sum = {0.f, 0.f, 0.f, 0.f};
-              for (int p0 = 0; p0 < S.n_producers; p0 += 8) {
-                f32x4 tq[8];
+          for (int q4 = 0; q4 < MR / 4; ++q4)
+            *reinterpret_cast<f32x4*>(myslot + 4 * q4) = f32x4{acc[4 * q4], acc[4 * q4 + 1], acc[4 * q4 + 2], acc[4 * q4 + 3]};
+        } else {
+          // ---- epilogue of the unit ----------------------------------------------------------------------------------
+          const float S32 = *mem.tensor_scale;
+          float out[MR];
 #pragma unroll
-                for (int b = 0; b < 8; ++b) {
-                  tq[b] = f32x4{0.f, 0.f, 0.f, 0.f};
-                  if (e < n4 && p0 + b < S.n_producers)
-                    tq[b] = *reinterpret_cast<const f32x4*>(src + ((int64_t)(p0 + b) * kTpartTokens + tok) * S.r_total + 4 * j4);
+          for (int q = 0; q < MR; ++q) out[q] = acc[q] * S32;
+          auto add_lora_bias = [&]() {
+            if (lora) {
+              // t of this member in LDS as three bf16 terms; the first wave of the workgroup that needs it puts it there
+              uint32_t ts = __hip_atomic_load(&s_tstate[mi], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP);
+              if (ts < 2u) {
+                int won = 0;
+                if (lane == 0) {
+                  uint32_t expect = 0u;
+                  won = __hip_atomic_compare_exchange_strong(&s_tstate[mi], &expect, 1u, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                             __HIP_MEMORY_SCOPE_WORKGROUP) ? 1 : 0;
                 }
+                won = __builtin_amdgcn_readfirstlane(won);
+                if (won) {
+                  const bool arrived = blk_wait_ge(a.ctl + kBlkReady + s, 1u, 2);
+                  if (!arrived && lane == 0) __hip_atomic_fetch_or(err_word, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+                  // the finished t of this member, M x r floats: one round of loads, split into three bf16 terms
+                  const int r4 = mem.r >> 2, n4 = a.M * r4;
+                  const float* src = a.tfinal + (int64_t)s * kBlkTfinalWords + mem.t_off;
+                  uint16_t* th = reinterpret_cast<uint16_t*>(tarea) + (mi * 3) * MT * 64;
+                  f32x4 tq[4];
 #pragma unroll
-                for (int b = 0; b < 8; ++b) sum += tq[b];
-              }
-              if (e < n4) {
-                if (!arrived) sum[0] = __uint_as_float(0x7fc00000u);   // the producers never came: make it visible
-                uint32_t hi[2], mid[2], lo[2];
+                  for (int i = 0; i < 4; ++i) {
+                    const int e = lane + 64 * i, tok = e / r4, j4 = e - tok * r4;
+                    tq[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    if (e < n4) tq[i] = *reinterpret_cast<const f32x4*>(src + (int64_t)tok * S.r_total + 4 * j4);
+                  }
 #pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                  const float v0 = sum[2 * i], v1 = sum[2 * i + 1];
-                  const uint32_t h = pack_bf16x2(v0, v1);
-                  const float r0 = v0 - bf16_bits_to_f32(h & 0xffffu), r1 = v1 - __uint_as_float(h & 0xffff0000u);
-                  const uint32_t m = pack_bf16x2(r0, r1);
-                  const float q0 = r0 - bf16_bits_to_f32(m & 0xffffu), q1 = r1 - __uint_as_float(m & 0xffff0000u);
-                  hi[i] = h; mid[i] = m; lo[i] = pack_bf16x2(q0, q1);
+                  for (int i = 0; i < 4; ++i) {
+                    const int e = lane + 64 * i, tok = e / r4, j4 = e - tok * r4;
+                    if (e < n4) {
+                      f32x4 sum = tq[i];
+                      if (!arrived) sum[0] = __uint_as_float(0x7fc00000u);   // the producers never came: make it visible
+                      uint32_t hi[2], mid[2], lo[2];
+#pragma unroll
+                      for (int k = 0; k < 2; ++k) {
+                        const float v0 = sum[2 * k], v1 = sum[2 * k + 1];
+                        const uint32_t h = pack_bf16x2(v0, v1);
+                        const float r0 = v0 - bf16_bits_to_f32(h & 0xffffu), r1 = v1 - __uint_as_float(h & 0xffff0000u);
+                        const uint32_t m = pack_bf16x2(r0, r1);
+                        const float q0 = r0 - bf16_bits_to_f32(m & 0xffffu), q1 = r1 - __uint_as_float(m & 0xffff0000u);
+                        hi[k] = h; mid[k] = m; lo[k] = pack_bf16x2(q0, q1);
+                      }
+                      uint16_t* dst = th + tok * 64 + 4 * j4;
+                      *reinterpret_cast<u32x2*>(dst) = u32x2{hi[0], hi[1]};
+                      *reinterpret_cast<u32x2*>(dst + MT * 64) = u32x2{mid[0], mid[1]};
+                      *reinterpret_cast<u32x2*>(dst + 2 * MT * 64) = u32x2{lo[0], lo[1]};
+                    }
+                  }
+                  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                  if (lane == 0) __hip_atomic_store(&s_tstate[mi], arrived ? 2u : 3u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                } else {
+                  uint32_t spins = 0;
+                  while (__hip_atomic_load(&s_tstate[mi], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < 2u) {
+                    if (++spins > 4 * kBlkSpinLimit) break;   // the loading wave itself gives up long before this
+                    __builtin_amdgcn_s_sleep(8);
+                  }
                 }
-                uint16_t* dst = th + tok * 64 + 4 * j4;
-                *reinterpret_cast<u32x2*>(dst) = u32x2{hi[0], hi[1]};
-                *reinterpret_cast<u32x2*>(dst + MT * 64) = u32x2{mid[0], mid[1]};
-                *reinterpret_cast<u32x2*>(dst + 2 * MT * 64) = u32x2{lo[0], lo[1]};
               }
+              f32x16 l;
+#pragma unroll
+              for (int i = 0; i < 16; ++i) l[i] = 0.f;
+              const unsigned char* trow = tarea + ((mi * 3) * MT + (n32 < MT ? n32 : 0)) * 128 + kg * 16;
+#pragma unroll
+              for (int st = 0; st < 4; ++st) {
+                if (16 * st < mem.r) {
+                  const bf16x8 bf = __builtin_bit_cast(bf16x8, bfrag[st]);
+#pragma unroll
+                  for (int term = 0; term < 3; ++term) {
+                    u32x4 tv = *reinterpret_cast<const u32x4*>(trow + term * MT * 128 + st * 32);
+                    if (n32 >= a.M || 16 * st + 8 * kg >= mem.r) tv = u32x4{0u, 0u, 0u, 0u};   // rows beyond the tokens, ranks beyond r: never written
+                    l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tv), bf, l, 0, 0, 0);
+                  }
+                }
+              }
+#pragma unroll
+              for (int q = 0; q < MR; ++q) out[q] += l[q] * mem.lora_scale;
             }
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            if (lane == 0) __hip_atomic_store(&s_tstate[mi], arrived ? 2u : 3u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
-          } else {
-            uint32_t spins = 0;
-            while (__hip_atomic_load(&s_tstate[mi], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < 2u) {
-              if (++spins > 4 * kBlkSpinLimit) break;   // the loading wave itself gives up long before this
-              __builtin_amdgcn_s_sleep(8);
+            {
+              const float bias = bf16_bits_to_f32(bias_bits);   // +0 without one
+#pragma unroll
+              for (int q = 0; q < MR; ++q) out[q] += bias;
             }
-          }
-        }
-        f32x16 l;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) l[i] = 0.f;
-        const unsigned char* trow = tarea + ((mi * 3) * MT + (n32 < MT ? n32 : 0)) * 128 + kg * 16;
-#pragma unroll
-        for (int st = 0; st < 4; ++st) {
-          if (16 * st < mem.r) {
-            const bf16x8 bf = __builtin_bit_cast(bf16x8, bfrag[st]);
-#pragma unroll
-            for (int term = 0; term < 3; ++term) {
-              u32x4 tv = *reinterpret_cast<const u32x4*>(trow + term * MT * 128 + st * 32);
-              if (n32 >= a.M || 16 * st + 8 * kg >= mem.r) tv = u32x4{0u, 0u, 0u, 0u};   // rows beyond the tokens, ranks beyond r: never written
-              l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tv), bf, l, 0, 0, 0);
-            }
-          }
-        }
-#pragma unroll
-        for (int q = 0; q < MR; ++q) out[q] += l[q] * mem.lora_scale;
-      }
-      {
-        const float bias = bf16_bits_to_f32(bias_bits);   // +0 without one
-#pragma unroll
-        for (int q = 0; q < MR; ++q) out[q] += bias;
-      }
+          };
+          if (S.Sk == 1) add_lora_bias();
 
-      bool finish = true;              // this wave stores the tile (or the pair's activation)
-      if (S.Sk > 1) {
-        // K is split over ranges of workgroups: leave this range's share in the workspace and count; the wave that
-        // arrives last adds the shares in range order.  (A gate / up pair counts once, after up.)
-        uint64_t* mine = reinterpret_cast<uint64_t*>(a.partial + S.partial_off + (((int64_t)cur.g.range * S.total_tiles + nt) * 64 + lane) * MR);
+          bool finish = true;            // this wave stores the tile
+          if (S.Sk > 1) {
+            // K is split over ranges of workgroups: leave this range's share in the workspace and count; the wave that
+            // arrives last adds the shares in range order (all requested in one round of loads).
+            uint64_t* mine = reinterpret_cast<uint64_t*>(a.partial + S.partial_off + (((int64_t)cur.g.range * S.total_tiles + nt) * 64 + lane) * MR);
 #pragma unroll
-        for (int q2 = 0; q2 < MR / 2; ++q2) {
-          const uint64_t v = (uint64_t)__float_as_uint(out[2 * q2]) | ((uint64_t)__float_as_uint(out[2 * q2 + 1]) << 32);
-          __hip_atomic_store(mine + q2, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        finish = false;
-        if (!(S.pairs && cur.h == 0)) {
-          __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the shares are in memory before the count
-          const int v = cur.g.slot + cur.j * cur.g.slots_r;
-          uint32_t* ctr = a.counters + S.ctr_off + v;
-          uint32_t old = 0;
-          if (lane == 0) old = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          old = __builtin_amdgcn_readfirstlane(old);
-          if (old == (uint32_t)(S.Sk - 1)) {
-            finish = true;
-            if (lane == 0) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
-            auto range_sum = [&](int tile, float (&dst)[MR]) {
-              const uint64_t* p = reinterpret_cast<const uint64_t*>(a.partial + S.partial_off + ((int64_t)tile * 64 + lane) * MR);
+            for (int q2 = 0; q2 < MR / 2; ++q2) {
+              const uint64_t v = (uint64_t)__float_as_uint(out[2 * q2]) | ((uint64_t)__float_as_uint(out[2 * q2 + 1]) << 32);
+              __hip_atomic_store(mine + q2, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the shares are in memory before the count
+            uint32_t* ctr = a.counters + S.ctr_off + nt;
+            uint32_t old = 0;
+            if (lane == 0) old = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            old = __builtin_amdgcn_readfirstlane(old);
+            finish = old == (uint32_t)(S.Sk - 1);
+            if (finish) {
+              if (lane == 0) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+              const uint64_t* p = reinterpret_cast<const uint64_t*>(a.partial + S.partial_off + ((int64_t)nt * 64 + lane) * MR);
               const int64_t stride = (int64_t)S.total_tiles * 64 * MR / 2;
 #pragma unroll
-              for (int q = 0; q < MR; ++q) dst[q] = 0.f;
-              for (int z0 = 0; z0 < S.Sk; z0 += 4) {
-                uint64_t w[4][MR / 2];
+              for (int q = 0; q < MR; ++q) out[q] = 0.f;
+              constexpr int ZB = MR == 4 ? 16 : 8;     // ranges in flight per round
+              for (int z0 = 0; z0 < S.Sk; z0 += ZB) {
+                uint64_t w[ZB][MR / 2];
 #pragma unroll
-                for (int b = 0; b < 4; ++b)
+                for (int b = 0; b < ZB; ++b)
 #pragma unroll
                   for (int q2 = 0; q2 < MR / 2; ++q2) {
                     w[b][q2] = 0ull;   // +0.0f twice
                     if (z0 + b < S.Sk) w[b][q2] = __hip_atomic_load(p + (int64_t)(z0 + b) * stride + q2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                   }
 #pragma unroll
-                for (int b = 0; b < 4; ++b)
+                for (int b = 0; b < ZB; ++b)
 #pragma unroll
                   for (int q2 = 0; q2 < MR / 2; ++q2) {
-                    dst[2 * q2] += __uint_as_float((uint32_t)w[b][q2]);
-                    dst[2 * q2 + 1] += __uint_as_float((uint32_t)(w[b][q2] >> 32));
+                    out[2 * q2] += __uint_as_float((uint32_t)w[b][q2]);
+                    out[2 * q2 + 1] += __uint_as_float((uint32_t)(w[b][q2] >> 32));
                   }
               }
-            };
-            range_sum(nt, out);
-            if (S.pairs) range_sum(v, held);   // gate_proj's tile of the pair
+              add_lora_bias();
+            }
           }
-        }
-      } else if (S.pairs && cur.h == 0) {
-#pragma unroll
-        for (int q = 0; q < MR; ++q) held[q] = out[q];
-        finish = false;
-      }
 
-      if (finish) {
-        uint32_t bits[MR];
-        uint16_t* ybase; int64_t ldy, n0, nlim; bool vec;
-        if (S.pairs) {
-          // act = bf16(bf16(SiLU(gate)) * up) on the bf16-rounded projections: what a bf16 model evaluated operator
-          // by operator gives
+          if (finish && pair_up) {
+            // hand the finished up_proj tile to the wave that holds gate_proj's tile of the same rows
+            const int fi = wave & 3;
+            uint32_t spins = 0;
+            while (__hip_atomic_load(&xflag[4 + fi], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < (uint32_t)cur.j) {
+              if (++spins > 4 * kBlkSpinLimit) break;   // (the buffer is free once the unit before has been taken)
+              __builtin_amdgcn_s_sleep(2);
+            }
 #pragma unroll
-          for (int q = 0; q < MR; q += 2) {
-            const uint32_t gpk = pack_bf16x2(held[q], held[q + 1]), upk = pack_bf16x2(out[q], out[q + 1]);
-            const uint32_t r = silu_mul2(gpk, upk);
-            bits[q] = r & 0xffffu; bits[q + 1] = r >> 16;
+            for (int q4 = 0; q4 < MR / 4; ++q4)
+              *reinterpret_cast<f32x4*>(xbuf + lane * MR + 4 * q4) = f32x4{out[4 * q4], out[4 * q4 + 1], out[4 * q4 + 2], out[4 * q4 + 3]};
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            if (lane == 0) __hip_atomic_store(&xflag[fi], (uint32_t)(cur.j + 1), __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+            finish = false;
           }
-          ybase = S.act; ldy = S.ld_act; n0 = (int64_t)(nt - S.mem[1].tile_begin) * 32; nlim = S.mem[0].N; vec = S.act_vec != 0;
-        } else {
+
+          if (finish) {
+            uint32_t bits[MR];
+            uint16_t* ybase; int64_t ldy, n0, nlim; bool vec;
+            if (S.pairs) {
+              // act = bf16(bf16(SiLU(gate)) * up) on the bf16-rounded projections: what a bf16 model evaluated
+              // operator by operator gives.  up_proj's tile comes from the partner wave.
+              const int fi = wave & 3;
+              uint32_t spins = 0;
+              bool got = true;
+              while (__hip_atomic_load(&xflag[fi], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < (uint32_t)(cur.j + 1)) {
+                if (++spins > 4 * kBlkSpinLimit) { got = false; break; }
+                __builtin_amdgcn_s_sleep(2);
+              }
+              float up[MR];
 #pragma unroll
-          for (int q = 0; q < MR; ++q) bits[q] = f32_to_bf16_bits(out[q]);
-          ybase = mem.y; ldy = mem.ldy; n0 = row0; nlim = mem.N; vec = mem.y_vec != 0;
+              for (int q4 = 0; q4 < MR / 4; ++q4) {
+                const f32x4 v = *reinterpret_cast<const f32x4*>(xbuf + lane * MR + 4 * q4);
+                up[4 * q4] = v[0]; up[4 * q4 + 1] = v[1]; up[4 * q4 + 2] = v[2]; up[4 * q4 + 3] = v[3];
+              }
+              asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+              if (lane == 0) {
+                __hip_atomic_store(&xflag[4 + fi], (uint32_t)(cur.j + 1), __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                if (!got) __hip_atomic_fetch_or(err_word, 4u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              }
+#pragma unroll
+              for (int q = 0; q < MR; q += 2) {
+                const uint32_t gpk = pack_bf16x2(out[q], out[q + 1]), upk = pack_bf16x2(up[q], up[q + 1]);
+                const uint32_t r = silu_mul2(gpk, upk);
+                bits[q] = r & 0xffffu; bits[q + 1] = r >> 16;
+              }
+              ybase = S.act; ldy = S.ld_act; n0 = row0; nlim = S.mem[0].N; vec = S.act_vec != 0;
+            } else {
+#pragma unroll
+              for (int q = 0; q < MR; ++q) bits[q] = f32_to_bf16_bits(out[q]);
+              ybase = mem.y; ldy = mem.ldy; n0 = row0; nlim = mem.N; vec = mem.y_vec != 0;
+            }
+            if (vec && n0 + 32 <= nlim) {
+              // whole tile, 16-byte aligned rows: transposed through LDS, one 16-byte store per lane
+#pragma unroll
+              for (int q = 0; q < MR; ++q) {
+                const int tok = 8 * (q >> 2) + 4 * kg + (q & 3);
+                ytile[tok * 32 + n32] = (uint16_t)bits[q];
+              }
+              asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+              const int tok = lane >> 2, part = lane & 3;
+              if (tok < a.M) {
+                const u32x4 v = *reinterpret_cast<const u32x4*>(ytile + tok * 32 + part * 8);
+                uint16_t* dst = ybase + (int64_t)tok * ldy + n0 + part * 8;
+                if (S.pairs) {   // read by the next stage of this launch, on other compute units: through to memory
+                  __hip_atomic_store(reinterpret_cast<uint64_t*>(dst), (uint64_t)v[0] | ((uint64_t)v[1] << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                  __hip_atomic_store(reinterpret_cast<uint64_t*>(dst) + 1, (uint64_t)v[2] | ((uint64_t)v[3] << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                  *reinterpret_cast<u32x4*>(dst) = v;
+                }
+              }
+              asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // read before the next unit overwrites the tile
+            } else {
+#pragma unroll
+              for (int q = 0; q < MR; ++q) {
+                const int tok = 8 * (q >> 2) + 4 * kg + (q & 3);
+                if (tok < a.M && n0 + n32 < nlim) {
+                  if (S.pairs) __hip_atomic_store(ybase + (int64_t)tok * ldy + n0 + n32, (uint16_t)bits[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                  else ybase[(int64_t)tok * ldy + n0 + n32] = (uint16_t)bits[q];
+                }
+              }
+            }
+          }
         }
-        if (vec && n0 + 32 <= nlim) {
-          // whole tile, 16-byte aligned rows: transposed through LDS, one 16-byte store per lane
-#pragma unroll
-          for (int q = 0; q < MR; ++q) {
-            const int tok = 8 * (q >> 2) + 4 * kg + (q & 3);
-            ytile[tok * 32 + n32] = (uint16_t)bits[q];
-          }
-          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-          const int tok = lane >> 2, part = lane & 3;
-          if (tok < a.M) {
-            const u32x4 v = *reinterpret_cast<const u32x4*>(ytile + tok * 32 + part * 8);
-            *reinterpret_cast<u32x4*>(ybase + (int64_t)tok * ldy + n0 + part * 8) = v;
-          }
-          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // read before the next unit overwrites the tile
-        } else {
-#pragma unroll
-          for (int q = 0; q < MR; ++q) {
-            const int tok = 8 * (q >> 2) + 4 * kg + (q & 3);
-            if (tok < a.M && n0 + n32 < nlim) ybase[(int64_t)tok * ldy + n0 + n32] = (uint16_t)bits[q];
-          }
-        }
+        if (first_pass) BSTAMP(4 + 5 * s);
+        first_pass = false;
+        cur = nxt;
+        have_cur = have_next;
       }
-      cur = nxt;
-      have_cur = have_next;
     }
+    BSTAMP(5 + 5 * s);
   }
 
+  BSTAMP(15);
   leave();
 }
 
@@ -595,42 +797,69 @@ __global__ __launch_bounds__(kBlkThreads) void block_kernel(const BlkArgs a) {
 constexpr size_t kBlkLdsMax = 160 * 1024 - 2048;   // the static words (row statistics, t states) take the first aligned slots of the CU's 160 KiB
 
 static int g_blk_cus = 0;     // compute units of the device (one persistent workgroup each)
-static int g_blk_force_kr = 0;
+static int g_blk_force_kr = 0, g_blk_force_phases = 0;
 
-// Chooses the K-ranges of a stage for n_cons consumer workgroups and fills the stage's plan fields.  Model: a wave
-// multiplies one tile in about t_tile us when nothing holds it up, the chip streams about 6.5 MB per us; a unit is
-// as long as its K-range, a wave's units run one after the other, and splitting K costs a trip through memory.
-static int plan_block_stage(BlkStage& S, int M, int MR, int n_cons, size_t x_budget) {
+constexpr int kBlkParkMax = 2;   // accumulator tiles a wave may park between K-phases
+
+struct BlkLds { size_t x, g, t, y, park, exch; };
+static BlkLds blk_lds(int M, int MR, int kr, bool norm, int park_units, bool pairs) {
+  const int MT = MR == 4 ? 8 : 16;
+  BlkLds l;
+  l.x = ((size_t)(M + 1) * (size_t)(kr * 256 + 16) + 255) & ~(size_t)255;
+  l.g = 0; (void)norm;
+  l.t = (size_t)kMaxGroup * 3 * MT * 64 * 2;
+  l.y = (size_t)kBlkWaves * 16 * 32 * 2;
+  l.park = (size_t)kBlkWaves * (size_t)park_units * 64 * MR * sizeof(float);
+  l.exch = pairs ? 256 + (size_t)4 * 64 * MR * sizeof(float) : 0;
+  return l;
+}
+static size_t blk_lds_total(const BlkLds& l) { return l.x + l.g + l.t + l.y + l.park + l.exch; }
+
+// Chooses how a stage's K is cut -- Sk ranges of workgroups x phases in time x kr_len tiles -- for n_cons consumer
+// workgroups, and fills the stage's plan fields.  Model: a wave multiplies one tile in about t_tile us when nothing
+// holds it up (two waves share a SIMD), the chip streams about 6 MB per us; a wave's units and phases run one after
+// the other; splitting K over workgroups costs a trip through memory and the partial tiles' traffic, an extra phase
+// costs a workgroup barrier and a re-staging of x.  A gate / up pair is finished inside one workgroup, so its K is
+// never split over workgroups.
+static int plan_block_stage(BlkStage& S, int M, int MR, int n_cons, int* park_units) {
   const int D = kBlkD;
-  int cap = (int)(((int64_t)(x_budget / (size_t)(M + 1)) - 16) / 256);
-  cap -= cap % D;
-  if (cap < D) return QERL_ERR_SHAPE;
+  const bool norm = S.gain != nullptr, pairs = S.pairs != 0;
   const int kt_pad = (int)(ceil_div(S.k_tiles, D) * D);
-  const double t_tile = MR == 4 ? 0.55 : 0.65, chip_rate = 6.5e6, wave_rate = kPackTileBytes / t_tile;   // bytes per us
+  const int cpt_cap = 2 * kBlkThreads / 16;   // slice chunks whose gain + noise a workgroup stages in one round
+  const double t_tile = MR == 4 ? 0.46 : 0.65, chip_rate = 6.0e6, wave_rate = kPackTileBytes / t_tile;   // bytes per us
   const double bytes = (double)S.total_tiles * S.k_tiles * kPackTileBytes;
-  int best = 0;
+  int best_kr = 0, best_ph = 0, best_park = 0;
   double best_cost = 0;
-  for (int kr = D; kr <= (cap < kt_pad ? cap : kt_pad); kr += D) {
+  for (int kr = D; kr <= kt_pad && kr <= cpt_cap; kr += D) {
     if (g_blk_force_kr > 0 && kr != g_blk_force_kr) continue;
-    const int Sk = (int)ceil_div(S.k_tiles, kr);
-    if (Sk > n_cons) continue;
-    const int per_range = n_cons / Sk;
-    const int64_t slots_r = (int64_t)per_range * kBlkWaves;
-    const int64_t rounds = ceil_div(S.total_v, slots_r);
-    const int passes = (int)rounds * (S.pairs ? 2 : 1);
-    const int64_t active = (S.total_v < slots_r ? S.total_v : slots_r) * Sk;
-    const double rate = active * wave_rate < chip_rate ? active * wave_rate : chip_rate;
-    const double extra = Sk > 1 ? 1.5 * Sk * S.total_tiles * 64.0 * MR * 4 : 0.0;   // partial tiles out and back
-    double cost = (bytes + extra) / rate;
-    const double chain = passes * kr * t_tile;
-    cost = cost > chain ? cost : chain;
-    cost += 0.5 * passes + (Sk > 1 ? 3.0 : 0.0);
-    if (best == 0 || cost < best_cost - 1e-9) { best = kr; best_cost = cost; }
+    const int n_seg = (int)ceil_div(S.k_tiles, kr);
+    for (int ph = 1; ph <= 4; ++ph) {
+      if (n_seg % ph != 0) continue;
+      if (g_blk_force_phases > 0 && ph != g_blk_force_phases) continue;
+      const int Sk = n_seg / ph;
+      if (Sk > n_cons || (pairs && Sk != 1)) continue;
+      const int per_range = n_cons / Sk;
+      const int64_t slots_r = (int64_t)per_range * (pairs ? kBlkWaves / 2 : kBlkWaves);
+      const int64_t rounds = ceil_div(S.total_v, slots_r);
+      if (ph > 1 && rounds > kBlkParkMax) continue;
+      const int park = ph > 1 ? (int)rounds : 1;
+      if (blk_lds_total(blk_lds(M, MR, kr, norm, ph > 1 ? park : 0, pairs)) > kBlkLdsMax) continue;
+      const int64_t active = (S.total_v < slots_r ? S.total_v : slots_r) * Sk * (pairs ? 2 : 1);
+      const double rate = active * wave_rate < chip_rate ? active * wave_rate : chip_rate;
+      const double extra = Sk > 1 ? 1.5 * Sk * S.total_tiles * 64.0 * MR * 4 : 0.0;   // partial tiles out and back
+      double cost = (bytes + extra) / rate;
+      const double chain = (double)rounds * ph * kr * t_tile;
+      cost = cost > chain ? cost : chain;
+      cost += 2.0 * (rounds - 1) + (Sk > 1 ? 6.0 + 0.25 * Sk : 0.0) + 4.0 * (ph - 1);
+      if (best_kr == 0 || cost < best_cost - 1e-9) { best_kr = kr; best_ph = ph; best_park = park; best_cost = cost; }
+    }
   }
-  if (best == 0) return QERL_ERR_SHAPE;
-  S.kr_len = best;
-  S.Sk = (int)ceil_div(S.k_tiles, best);
+  if (best_kr == 0) return QERL_ERR_SHAPE;
+  S.kr_len = best_kr;
+  S.phases = best_ph;
+  S.Sk = (int)ceil_div(S.k_tiles, best_kr) / best_ph;
   S.per_range = n_cons / S.Sk;
+  *park_units = best_ph > 1 ? best_park : 0;
   return QERL_OK;
 }
 
@@ -644,41 +873,49 @@ int plan_block(BlkArgs& a, size_t* lds_bytes, int* MR_out, size_t* partial_float
     }
     g_blk_cus = n;
   }
-  const int MR = a.M <= 8 ? 4 : 8, MT = MR == 4 ? 8 : 16;
+  const int MR = a.M <= 8 ? 4 : 8;
   *MR_out = MR;
   a.n_wgs = g_blk_cus;
-  int n_lora = 0, pmax = 0;
+  int pmax = 0;
   for (int s = 0; s < a.n_stages; ++s) {
     BlkStage& S = a.st[s];
     int rt = 0;
-    for (int i = 0; i < S.n_members; ++i) if (S.mem[i].r > 0) { S.mem[i].t_off = rt; rt += S.mem[i].r; ++n_lora; } else S.mem[i].t_off = 0x7fffffff;
+    for (int i = 0; i < S.n_members; ++i) if (S.mem[i].r > 0) { S.mem[i].t_off = rt; rt += S.mem[i].r; } else S.mem[i].t_off = 0x7fffffff;
     for (int i = S.n_members; i < kMaxGroup; ++i) S.mem[i].t_off = 0x7fffffff;
     S.r_total = rt;
-    S.n_producers = 0;
+    S.n_producers = 0; S.prod_k = 1;
     if (rt > 0) {
-      int64_t np = ceil_div(2 * (int64_t)S.k_tiles, kBlkWaves);   // one half K-tile per producer wave and tile pair
-      S.n_producers = (int)(np < 1 ? 1 : (np > 16 ? 16 : np));
+      // one producer workgroup per pair of rank tiles (64 stacked rows) and run of K: every producer makes one round of
+      // loads; runs of about five K-tiles, as many as the producer budget allows
+      const int n_pairs = (int)ceil_div(rt, 64);
+      int64_t pk = ceil_div(S.k_tiles, 5);
+      const int64_t pk_max = kBlkMaxProducers / n_pairs;
+      pk = pk < 1 ? 1 : (pk > pk_max ? pk_max : pk);
+      S.prod_k = (int)pk;
+      S.n_producers = (int)pk * n_pairs;
     }
     pmax = S.n_producers > pmax ? S.n_producers : pmax;
   }
   a.n_prod_max = pmax;
   const int n_cons = a.n_wgs - pmax;
   if (n_cons < 1) return QERL_ERR_SHAPE;
-  // LDS: x slice first, then the split t of the four member slots, then the waves' output tiles
-  const size_t t_bytes = (size_t)kMaxGroup * 3 * MT * 64 * 2, y_bytes = (size_t)kBlkWaves * 16 * 32 * 2;
-  const size_t x_budget = (kBlkLdsMax - t_bytes - y_bytes - 512) & ~(size_t)255;
-  size_t xs_max = 0, part = 0, ctrs = 0, prod_need = 0;
+  size_t part = 0, ctrs = 0, prod_need = 0;
+  BlkLds mx{};
+  int park_max = 0;
   for (int s = 0; s < a.n_stages; ++s) {
     BlkStage& S = a.st[s];
-    const int rc = plan_block_stage(S, a.M, MR, n_cons, x_budget);
+    int park = 0;
+    const int rc = plan_block_stage(S, a.M, MR, n_cons, &park);
     if (rc != QERL_OK) return rc;
-    const size_t xs = (size_t)(a.M + 1) * (size_t)(S.kr_len * 256 + 16);
-    xs_max = xs > xs_max ? xs : xs_max;
+    park_max = park > park_max ? park : park_max;
+    const BlkLds l = blk_lds(a.M, MR, S.kr_len, S.gain != nullptr, park, S.pairs != 0);
+    mx.x = l.x > mx.x ? l.x : mx.x; mx.g = l.g > mx.g ? l.g : mx.g; mx.t = l.t; mx.y = l.y;
+    mx.park = l.park > mx.park ? l.park : mx.park; mx.exch = l.exch > mx.exch ? l.exch : mx.exch;
     S.ctr_off = (int)ctrs; S.partial_off = (int64_t)part;
-    if (S.Sk > 1) { ctrs += (size_t)S.total_v; part += (size_t)S.Sk * S.total_tiles * 64 * MR; }
+    if (S.Sk > 1) { ctrs += (size_t)S.total_tiles; part += (size_t)S.Sk * S.total_tiles * 64 * MR; }
     if (S.n_producers > 0) {
       const int64_t steps = S.K / 16;
-      S.prod_steps = (int)ceil_div(steps, S.n_producers);
+      S.prod_steps = (int)ceil_div(steps, S.prod_k);
       const size_t rows = (size_t)(S.r_total < 64 ? S.r_total : 64) + a.M + 1;
       const size_t red = lora_producer_red_bytes(kBlkWaves, MR);
       int64_t cb = ((int64_t)((kBlkLdsMax - red - 256) / rows) - 16) / 32;
@@ -694,12 +931,16 @@ int plan_block(BlkArgs& a, size_t* lds_bytes, int* MR_out, size_t* partial_float
 #ifdef QERL_TUNING_HOOKS
   if (getenv("QERL_BLK_TRACE"))
     for (int s = 0; s < a.n_stages; ++s)
-      fprintf(stderr, "block plan: M %d stage %d K-tiles %d tiles %d units %d  kr_len %d Sk %d per_range %d producers %d\n", a.M, s,
-              a.st[s].k_tiles, a.st[s].total_tiles, a.st[s].total_v, a.st[s].kr_len, a.st[s].Sk, a.st[s].per_range, a.st[s].n_producers);
+      fprintf(stderr, "block plan: M %d stage %d K-tiles %d tiles %d units %d  kr_len %d phases %d Sk %d per_range %d producers %d\n", a.M, s,
+              a.st[s].k_tiles, a.st[s].total_tiles, a.st[s].total_v, a.st[s].kr_len, a.st[s].phases, a.st[s].Sk, a.st[s].per_range, a.st[s].n_producers);
 #endif
-  a.t_lds_off = (int)((xs_max + 255) & ~(size_t)255);
-  a.y_lds_off = a.t_lds_off + (int)t_bytes;
-  size_t total = (size_t)a.y_lds_off + y_bytes;
+  a.park_units = park_max > 0 ? park_max : 1;
+  a.g_lds_off = (int)mx.x;
+  a.t_lds_off = a.g_lds_off + (int)mx.g;
+  a.y_lds_off = a.t_lds_off + (int)mx.t;
+  a.p_lds_off = a.y_lds_off + (int)mx.y;
+  a.e_lds_off = a.p_lds_off + (int)mx.park;
+  size_t total = (size_t)a.e_lds_off + (mx.exch > 0 ? mx.exch : 256);
   total = total > prod_need ? total : prod_need;
   if (total > kBlkLdsMax) return QERL_ERR_SHAPE;
   *lds_bytes = total;
@@ -725,23 +966,41 @@ int launch_block(const BlkArgs& a, size_t lds, int MR, hipStream_t st) {
   // every pointer the kernel dereferences and every bound its indexing assumes
   if (a.M < 1 || a.M > 16 || a.n_stages < 1 || a.n_stages > kBlkMaxStages || a.n_wgs < 2 || a.n_prod_max < 0 || a.n_prod_max >= a.n_wgs)
     return QERL_ERR_SHAPE;
-  if (!a.ctl || !a.counters || !a.partial || !a.tpart) return QERL_ERR_NULL;
-  if ((MR != 4 && MR != 8) || (a.M > 8 && MR != 8) || lds > kBlkLdsMax || a.t_lds_off < 0 || a.y_lds_off <= a.t_lds_off ||
-      (size_t)a.y_lds_off + kBlkWaves * 16 * 32 * 2 > lds)
+  if (!a.ctl || !a.counters || !a.partial || !a.tpart || !a.tfinal) return QERL_ERR_NULL;
+  const int MT = MR == 4 ? 8 : 16;
+  if ((MR != 4 && MR != 8) || (a.M > 8 && MR != 8) || lds > kBlkLdsMax || a.g_lds_off <= 0 || a.t_lds_off < a.g_lds_off ||
+      (size_t)a.y_lds_off < (size_t)a.t_lds_off + (size_t)kMaxGroup * 3 * MT * 64 * 2 || (size_t)a.p_lds_off < (size_t)a.y_lds_off + kBlkWaves * 16 * 32 * 2 ||
+      a.park_units < 1 || a.e_lds_off < a.p_lds_off || (size_t)a.e_lds_off + 256 > lds)
     return QERL_ERR_SHAPE;
+  bool any_phases = false, any_pairs = false;
   const int n_cons = a.n_wgs - a.n_prod_max;
   for (int s = 0; s < a.n_stages; ++s) {
     const BlkStage& S = a.st[s];
     if (!S.x || S.ldx < S.K || S.ldx % 8 != 0 || ((uintptr_t)S.x & 15) != 0 || S.K < 16 || S.K % 16 != 0) return QERL_ERR_ALIGN;
     if (S.k_tiles != (int)ceil_div(S.K, kPackTileK) || S.n_members < 1 || S.n_members > kMaxGroup) return QERL_ERR_SHAPE;
-    if (S.kr_len < kBlkD || S.kr_len % kBlkD != 0 || S.Sk < 1 || (int64_t)S.Sk * S.kr_len < S.k_tiles || (int64_t)(S.Sk - 1) * S.kr_len >= S.k_tiles ||
-        S.per_range < 1 || (int64_t)S.per_range * S.Sk > n_cons || (size_t)(a.M + 1) * (size_t)(S.kr_len * 256 + 16) > (size_t)a.t_lds_off)
+    const int64_t n_seg = (int64_t)S.Sk * S.phases;
+    if (S.kr_len < kBlkD || S.kr_len % kBlkD != 0 || S.Sk < 1 || S.phases < 1 || S.phases > 4 || n_seg * S.kr_len < S.k_tiles || (n_seg - 1) * S.kr_len >= S.k_tiles ||
+        S.per_range < 1 || (int64_t)S.per_range * S.Sk > n_cons || S.kr_len * 16 > 2 * kBlkThreads || (size_t)(a.M + 1) * (size_t)(S.kr_len * 256 + 16) > (size_t)a.g_lds_off ||
+        false)
       return QERL_ERR_SHAPE;
+    {
+      const int64_t slots_r = (int64_t)S.per_range * (S.pairs ? kBlkWaves / 2 : kBlkWaves);
+      if (S.phases > 1 && ceil_div(S.total_v, slots_r) > a.park_units) return QERL_ERR_SHAPE;
+      if (S.pairs && S.Sk != 1) return QERL_ERR_SHAPE;
+    }
+    any_phases |= S.phases > 1; any_pairs |= S.pairs != 0;
     if (S.gain && (((uintptr_t)S.gain & 15) != 0 || ((uintptr_t)S.noise & 15) != 0 || S.K % 8 != 0)) return QERL_ERR_ALIGN;
     int tiles = 0;
     for (int i = 0; i < S.n_members; ++i) {
       const BlkMember& m = S.mem[i];
       if (!m.packed || !m.tensor_scale || m.N < 1 || m.n_tiles != (int)ceil_div(m.N, kPackTileRows) || m.tile_begin != tiles) return QERL_ERR_SHAPE;
+      const bool row_major = m.stride_k == kPackTileBytes && m.stride_n == (int64_t)S.k_tiles * kPackTileBytes;
+      const bool k_major = m.stride_n == kPackTileBytes && m.stride_k == (int64_t)m.n_tiles * kPackTileBytes;
+#ifndef QERL_TUNING_HOOKS
+      if (!row_major && !k_major) return QERL_ERR_SHAPE;
+#else
+      (void)row_major; (void)k_major;
+#endif
       if (!(S.pairs) && !m.y) return QERL_ERR_NULL;
       if (m.r < 0 || m.r > 64 || m.r % 8 != 0 || (m.r > 0 && (!m.A || !m.B || ((uintptr_t)m.A & 15) != 0 || ((uintptr_t)m.B & 15) != 0))) return QERL_ERR_SHAPE;
       tiles += m.n_tiles;
@@ -755,9 +1014,11 @@ int launch_block(const BlkArgs& a, size_t lds, int MR, hipStream_t st) {
       return QERL_ERR_SHAPE;
     }
     if (S.r_total > 0) {
-      if (S.n_producers < 1 || S.n_producers > a.n_prod_max || S.n_producers > 16 || S.r_total > 256 || S.r_total % 8 != 0) return QERL_ERR_SHAPE;
+      if (S.n_producers < 1 || S.n_producers > a.n_prod_max || S.n_producers > kBlkMaxProducers || S.r_total > 256 || S.r_total % 8 != 0 ||
+          S.prod_k < 1 || S.n_producers != S.prod_k * (int)ceil_div(S.r_total, 64))
+        return QERL_ERR_SHAPE;
       const size_t rows = (size_t)(S.r_total < 64 ? S.r_total : 64) + a.M + 1;
-      if (S.prod_steps < 1 || S.prod_cb < 1 || S.prod_cb > kProdMaxSteps || (int64_t)S.prod_steps * S.n_producers < S.K / 16 ||
+      if (S.prod_steps < 1 || S.prod_cb < 1 || S.prod_cb > kProdMaxSteps || (int64_t)S.prod_steps * S.prod_k < S.K / 16 ||
           rows * (size_t)(S.prod_cb * 32 + 16) > (size_t)S.prod_red_off ||
           (size_t)S.prod_red_off + lora_producer_red_bytes(kBlkWaves, MR) > lds)
         return QERL_ERR_SHAPE;
@@ -765,11 +1026,18 @@ int launch_block(const BlkArgs& a, size_t lds, int MR, hipStream_t st) {
       return QERL_ERR_SHAPE;
     }
   }
+  if (any_phases && (size_t)a.p_lds_off + (size_t)kBlkWaves * a.park_units * 64 * MR * sizeof(float) > (size_t)a.e_lds_off) return QERL_ERR_SHAPE;
+  if (any_pairs && (size_t)a.e_lds_off + 256 + (size_t)4 * 64 * MR * sizeof(float) > lds) return QERL_ERR_SHAPE;
   return MR == 4 ? launch_block_t<4>(a, lds, st) : launch_block_t<8>(a, lds, st);
 }
 
 }  // namespace qerl
 
 #ifdef QERL_TUNING_HOOKS   // built only for tuning sessions: they change process-wide state
-extern "C" QERL_API void qerl_debug_force_block_kr(int kr) { qerl::g_blk_force_kr = kr; }
+extern "C" QERL_API void qerl_debug_force_block_kr(int kr, int phases) { qerl::g_blk_force_kr = kr; qerl::g_blk_force_phases = phases; }
+#endif
+#ifdef QERL_BLK_TRACE
+extern "C" QERL_API int qerl_debug_read_block_trace(void* dst, size_t bytes) {
+  return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(qerl::g_blk_trace), bytes, 0, hipMemcpyDeviceToHost);
+}
 #endif

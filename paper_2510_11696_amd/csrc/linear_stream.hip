@@ -71,7 +71,7 @@ __device__ __forceinline__ void stream_producer(const StreamArgs& a, unsigned ch
   p.M = a.M; p.K = a.K; p.r_total = a.r_total; p.n_members = a.n_members;
 #pragma unroll
   for (int i = 0; i < kMaxGroup; ++i) { p.A[i] = a.mem[i].A; p.t_off[i] = a.mem[i].t_off; }
-  p.index = (int)blockIdx.x;
+  p.index = (int)blockIdx.x; p.only_pair = -1; p.n_arrivals = 0; p.n_k = 0; p.tfinal = nullptr; p.ready = nullptr;
   p.prod_steps = a.prod_steps; p.prod_cb = a.prod_cb; p.prod_red_off = a.prod_red_off;
   p.tpart = a.tpart; p.arrive = a.lora_ctl + kCtlArrive;
   p.gain = nullptr; p.noise = nullptr; p.rstd = nullptr;

@@ -25,7 +25,11 @@ struct LoraProducerArgs {
   const uint16_t* x; int64_t ldx; const uint16_t* x2; int64_t ldx2;
   int M; int64_t K; int r_total; int n_members;
   const uint16_t* A[kProdMaxGroup]; int t_off[kProdMaxGroup];   // stacked rows [t_off[i], ...) are member i's (INT_MAX: not stacked)
-  int index;                                   // this producer's number
+  int index;                                   // this producer's number along K
+  int only_pair;                               // >= 0: this producer computes stacked rows [64 * only_pair, 64 * only_pair + 64) only (others have the other rows); -1: all rows
+  int n_arrivals;                              // arrivals that complete t (publishing producers only): the last one adds the partials
+  int n_k;                                     // producers along K (partials per element)
+  float* tfinal; uint32_t* ready;              // not null: the last producer to arrive adds the partials in producer order, stores t[tok][r_total] here and sets *ready
   int prod_steps, prod_cb, prod_red_off;       // 16-input steps of K per producer, steps per LDS column block, byte offset of the reduction area
   uint32_t* tpart;                             // [producer][kTpartTokens][r_total] fp32 bit patterns
   uint32_t* arrive;                            // counter the consumers watch
@@ -47,7 +51,7 @@ __device__ __forceinline__ void lora_producer(const LoraProducerArgs& a, unsigne
   const int p_s0 = a.index * a.prod_steps;
   const int p_s1 = p_s0 + a.prod_steps < steps ? p_s0 + a.prod_steps : steps;
   float* red = reinterpret_cast<float*>(smem + a.prod_red_off);
-  for (int pair = 0; pair < n_pairs; ++pair) {
+  for (int pair = a.only_pair >= 0 ? a.only_pair : 0; pair < (a.only_pair >= 0 ? a.only_pair + 1 : n_pairs); ++pair) {
     f32x16 pacc[2];
 #pragma unroll
     for (int at = 0; at < 2; ++at)
@@ -146,9 +150,42 @@ __device__ __forceinline__ void lora_producer(const LoraProducerArgs& a, unsigne
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's partial stores have completed
   __syncthreads();
-  // Consumers wait for all P arrivals and add the P partials themselves, in producer order: one
-  // memory round trip less than electing a producer to publish the sum.
-  if (tid == 0) __hip_atomic_fetch_add(a.arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (!a.tfinal) {
+    // Consumers wait for all P arrivals and add the P partials themselves, in producer order: one
+    // memory round trip less than electing a producer to publish the sum.
+    if (tid == 0) __hip_atomic_fetch_add(a.arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return;
+  }
+  // Publishing variant: the producer that arrives last adds the partials of all producers in producer order and
+  // stores the finished t, so that every consumer workgroup fetches M x r_total floats in one round of loads
+  // instead of adding P partials itself (P dependent rounds of loads on the critical path of its first tile).
+  uint32_t* flag = reinterpret_cast<uint32_t*>(red);
+  if (tid == 0) *flag = __hip_atomic_fetch_add(a.arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  if (*flag != (uint32_t)(a.n_arrivals - 1)) return;
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  const int n4 = a.M * (a.r_total >> 2);                 // groups of four ranks
+  for (int e = tid; e < n4; e += WAVES * 64) {
+    const int tok = e / (a.r_total >> 2), j4 = e - tok * (a.r_total >> 2);
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    for (int p0 = 0; p0 < a.n_k; p0 += 32) {   // all partials of the element in flight together: one round of loads
+      f32x4 tq[32];
+#pragma unroll
+      for (int b = 0; b < 32; ++b) {
+        tq[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (p0 + b < a.n_k)
+          tq[b] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(a.tpart) + ((int64_t)(p0 + b) * kTpartTokens + tok) * a.r_total + 4 * j4);
+      }
+#pragma unroll
+      for (int b = 0; b < 32; ++b) sum += tq[b];
+    }
+    uint64_t* dst = reinterpret_cast<uint64_t*>(a.tfinal + (int64_t)tok * a.r_total + 4 * j4);
+    __hip_atomic_store(dst, (uint64_t)__float_as_uint(sum[0]) | ((uint64_t)__float_as_uint(sum[1]) << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(dst + 1, (uint64_t)__float_as_uint(sum[2]) | ((uint64_t)__float_as_uint(sum[3]) << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's share of t is in memory
+  __syncthreads();
+  if (tid == 0) __hip_atomic_store(a.ready, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 }  // namespace qerl

@@ -13,10 +13,14 @@ def to_gpu_bf16(a_f32: np.ndarray) -> torch.Tensor:
     return t.cuda()
 
 
-def check_linear(y_gpu: torch.Tensor, y_ref: np.ndarray, what=""):
+def check_linear(y_gpu: torch.Tensor, y_ref: np.ndarray, what="", slack=1e-3):
     """Official gate: per row max|err| <= 2e-2 * max|y_ref row|.
     Tight gate (bf16 output rounding + fp32 summation order):
-        |err| <= 2^-8 |y_ref| + 1e-3 * max|y_ref row|."""
+        |err| <= 2^-8 |y_ref| + slack * max|y_ref row|,  slack = 1e-3 for one linear on exact inputs.
+    For a composition of operators (norm -> linear -> SiLU-mul -> linear) the device rounds each intermediate
+    from an fp32 sum where the oracle rounds an fp64 one, so a few per cent of the intermediate activations are
+    one bf16 unit (<= 2^-8 relative) apart; over a sum of K terms that adds about sqrt(0.02) * 2^-8 / 4 ~ 1.4e-4 of
+    the row maximum in rms, 6e-4 at the 4.5 sigma of ~1e5 outputs: such tests pass slack = 2e-3."""
     y = y_gpu.float().cpu().numpy().astype(np.float64)
     assert y.shape == y_ref.shape, (y.shape, y_ref.shape)
     assert np.all(np.isfinite(y)), what
@@ -24,7 +28,7 @@ def check_linear(y_gpu: torch.Tensor, y_ref: np.ndarray, what=""):
     row_inf = np.abs(y_ref).max(axis=1, keepdims=True) if y_ref.size else np.zeros((y_ref.shape[0], 1))
     assert np.all(err.max(axis=1, keepdims=True) <= 2e-2 * row_inf + 1e-30), (
         what, float((err.max(axis=1, keepdims=True) / (row_inf + 1e-30)).max()))
-    tight = 2.0 ** -8 * np.abs(y_ref) + 1e-3 * row_inf + 1e-30
+    tight = 2.0 ** -8 * np.abs(y_ref) + slack * row_inf + 1e-30
     bad = err > tight
     assert not bad.any(), (what, int(bad.sum()), float((err / tight).max()))
 

@@ -116,13 +116,13 @@ def test_feed_forward_block_in_one_launch(M, H, I, rs, sigma):
     again = call()
     torch.cuda.synchronize()
     assert qerl.workspace_status(ws) == 0
-    check_linear(y, ref, ("mlp", M, H, I, rs))
+    check_linear(y, ref, ("mlp", M, H, I, rs), slack=2e-3)
     assert torch.equal(y, again), "second run on the same workspace differs"
     # the same operators as separate launches agree with it to rounding
     xn_d = qerl.aqn_rmsnorm(xin.cuda(), gain.cuda(), Z.cuda() if Z is not None else None, 1e-6)
     gu = qerl.nvfp4_lora_linear_packed_group(xn_d, [gate["pw"], up["pw"]], [gate["Ad"], up["Ad"]], [gate["Bd"], up["Bd"]], [2.0, 2.0])
     sep = qerl.nvfp4_lora_linear_packed_swiglu(gu[0], gu[1], down["pw"], down["Ad"], down["Bd"], 2.0)
-    check_linear(sep, ref, ("mlp as separate launches", M, H, I, rs))
+    check_linear(sep, ref, ("mlp as separate launches", M, H, I, rs), slack=2e-3)
 
 
 @pytest.mark.parametrize("M", [17, 40])
@@ -136,6 +136,6 @@ def test_fused_entry_points_beyond_16_tokens_run_the_separate_launches(M):
     outs = qerl.aqn_rmsnorm_nvfp4_lora_linear_group(xin.cuda(), gain.cuda(), Z.cuda(), 1e-6, [gate["pw"], up["pw"]],
                                                     [gate["Ad"], up["Ad"]], [gate["Bd"], up["Bd"]], [2.0, 2.0])
     torch.cuda.synchronize()
-    check_linear(y, _ref(down, act, 2.0), ("mlp, separate launches", M))
+    check_linear(y, _ref(down, act, 2.0), ("mlp, separate launches", M), slack=2e-3)
     check_linear(outs[0], _ref(gate, xn, 2.0), ("group, separate launches", M))
     check_linear(outs[1], _ref(up, xn, 2.0), ("group, separate launches", M))

@@ -5,9 +5,11 @@ weights resident in HBM and distinct (17.55 GB packed, so nothing is served from
 have), LoRA r = 64 on all seven projections, an AQN RMSNorm before q/k/v and before gate/up.  A step is one pass
 of M tokens through every layer's linears:
     per layer  aqn_rmsnorm -> {q, k, v} -> o -> aqn_rmsnorm -> {gate, up} -> down
-(linears in braces share their input and go out as one grouped call; at decode sizes the norm's launch also
-computes their LoRA down-projections).  Attention is not part of this library; o reads a fixed synthetic
-activation, and so does down unless --swiglu makes it read SiLU(gate) * up.
+(linears in braces share their input and go out as one grouped call).  Attention is not part of this library; o
+reads a fixed synthetic activation.  Up to 16 tokens down reads SiLU(gate) * up of the step's own gate / up
+outputs, and {norm, q, k, v} and {norm, gate, up, SiLU-mul, down} each go out either as one persistent launch
+or as separate launches (norm + LoRA down-projections, the group, down), whichever --launch-plan says; beyond
+16 tokens down reads a fixed synthetic activation unless --swiglu is given.
 
 Prints ONE JSON line.  `value` is the whole-step packed-weight GB/s of the headline leg (decode, M = 16);
 `legs` carries the other token counts of the configuration (M = 1, 128: GB/s; M = 4096: TFLOP/s), each with the
@@ -90,10 +92,11 @@ class Weights:
 class Stack:
     """Activations, outputs and workspace for M tokens on a model's weights, and the step over its layers."""
 
-    def __init__(self, weights: Weights, M: int, swiglu: bool = False, eager: bool = False):
+    def __init__(self, weights: Weights, M: int, swiglu: bool = False, eager: bool = False, plan: str = "auto"):
         cfg = weights.cfg
         self.w, self.cfg, self.M = weights, cfg, M
         self.swiglu, self.eager = swiglu, eager
+        self.plan_request = plan
         self.n_layers, self.layers = weights.n_layers, weights.layers
         gen = weights.gen
         hidden = cfg["hidden"]
@@ -120,6 +123,69 @@ class Stack:
         self.ws = qerl.Workspace(need)
         self.packed_bytes_per_layer = weights.packed_bytes_per_layer
         self.flops_per_layer = sum(2 * M * s.N * s.K for s in cfg["linears"])
+        # Decode (up to 16 tokens) of a decoder block: down reads SiLU(gate) * up of this step's gate / up outputs,
+        # and each of {norm, q, k, v} and {norm, gate, up, SiLU-mul, down} can go out as ONE persistent launch
+        # (block_kernel) or as the separate launches (norm + LoRA down-projections, the grouped stream_kernel,
+        # stream_kernel with the SiLU-mul prologue).  Both compute the same thing; which is faster depends on the
+        # shapes, so the stack times both over all layers when it is set up and keeps the faster ("auto").
+        self.decode_block = self.block and M <= 16
+        self.plan = {"qkv": "separate", "mlp": "separate"}
+        self.plan_us = {}
+        if self.decode_block:
+            self.swiglu = True
+            r = cfg["r"]
+            lib = qerl.load_library()
+            self.ws_qkv = qerl.Workspace(qerl.aqn_rmsnorm_nvfp4_lora_linear_group_workspace_bytes(
+                M, hidden, [by[n].N for n in ("q", "k", "v")], [r] * 3))
+            self.ws_mlp = qerl.Workspace(lib.aqn_rmsnorm_nvfp4_lora_mlp_workspace_bytes(
+                M, hidden, by["gate"].N, by["down"].N, r, r, r))
+            need = max(need, lib.nvfp4_lora_linear_swiglu_workspace_bytes(M, by["down"].N, by["down"].K, r))
+            self.ws = qerl.Workspace(need)
+            if plan in ("separate", "fused"):
+                self.plan = {"qkv": plan, "mlp": plan}
+            else:
+                self.choose_plan()
+
+    def qkv(self, L, variant):
+        names = ("q", "k", "v")
+        if variant == "fused":
+            ws, As, Bs = zip(*(L.lin[n] for n in names))
+            qerl.aqn_rmsnorm_nvfp4_lora_linear_group(self.h, L.gain_in, L.z_in, 1e-6, list(ws), list(As), list(Bs),
+                                                     [self.lora_scale] * 3, workspace=self.ws_qkv,
+                                                     outs=[self.out[n] for n in names])
+        else:
+            self.norm_group(L, names, L.gain_in, L.z_in)
+
+    def mlp(self, L, variant):
+        if variant == "fused":
+            (wg, Ag, Bg), (wu, Au, Bu), (wd, Ad, Bd) = L.lin["gate"], L.lin["up"], L.lin["down"]
+            qerl.aqn_rmsnorm_nvfp4_lora_mlp(self.h, L.gain_post, L.z_post, 1e-6, wg, wu, wd, (Ag, Au, Ad), (Bg, Bu, Bd),
+                                            (self.lora_scale,) * 3, workspace=self.ws_mlp, out=self.out["down"])
+            return
+        self.norm_group(L, ("gate", "up"), L.gain_post, L.z_post)
+        if self.swiglu:   # down reads SiLU(gate) (.) up straight from the two outputs above
+            packed, A, B = L.lin["down"]
+            qerl.nvfp4_lora_linear_packed_swiglu(self.out["gate"], self.out["up"], packed, A, B, self.lora_scale,
+                                                 workspace=self.ws, out=self.out["down"])
+        else:
+            self.linear(L, "down", self.act)
+
+    def choose_plan(self):
+        """Time each part of the block both ways over every layer's distinct weights (graph replay, as the step
+        runs) and keep the faster."""
+        for part, fn in (("qkv", self.qkv), ("mlp", self.mlp)):
+            best = None
+            for variant in ("separate", "fused"):
+                def sweep(fn=fn, variant=variant):
+                    for L in self.layers:
+                        fn(L, variant)
+                run = sweep if self.eager else capture(sweep)
+                run()
+                us = timed(run, 5) / len(self.layers) * 1e3
+                self.plan_us[f"{part}:{variant}"] = round(us, 2)
+                if best is None or us < best[0]:
+                    best = (us, variant)
+            self.plan[part] = best[1]
 
     def linear(self, layer, name, x):
         packed, A, B = layer.lin[name]
@@ -153,15 +219,9 @@ class Stack:
                         self.linear(L, shp.name, self.act)
             return
         for L in self.layers:
-            self.norm_group(L, ("q", "k", "v"), L.gain_in, L.z_in)
+            self.qkv(L, self.plan["qkv"])
             self.linear(L, "o", self.attn)
-            self.norm_group(L, ("gate", "up"), L.gain_post, L.z_post)
-            if self.swiglu:   # down reads SiLU(gate) (.) up straight from the two outputs above
-                packed, A, B = L.lin["down"]
-                qerl.nvfp4_lora_linear_packed_swiglu(self.out["gate"], self.out["up"], packed, A, B, self.lora_scale,
-                                                     workspace=self.ws, out=self.out["down"])
-            else:
-                self.linear(L, "down", self.act)
+            self.mlp(L, self.plan["mlp"])
 
 
 def capture(fn):
@@ -214,11 +274,21 @@ def measured_traffic(kernel: str, config_no: int, shape_name: str, M: int):
 
 def dominant_kernel_roofline(stack: Stack, reps: int):
     """Average duration of one launch of the kernel most of the step's bytes / flops go through, run back
-    to back over every layer's distinct weights.  Decode (M <= 16): the grouped gate_proj + up_proj launch
-    of stream_kernel, fed with the LoRA down-projections the norm's launch left in memory, exactly as in
-    the step.  M > 16: the gate_proj call (the small lora_down32_kernel launch belongs to it)."""
+    to back over every layer's distinct weights.  Decode (M <= 16): the feed-forward block's single launch of
+    block_kernel where the step uses it, else the grouped gate_proj + up_proj launch of stream_kernel, fed
+    with the LoRA down-projections the norm's launch left in memory, exactly as in the step.  M > 16: the
+    gate_proj call (the small lora_down32_kernel launch belongs to it)."""
     by = {s.name: s for s in stack.cfg["linears"]}
-    if stack.M <= 16:
+    kernel = None
+    if stack.decode_block and stack.plan["mlp"] == "fused":
+        # the feed-forward block's persistent launch: norm, gate + up, SiLU-mul and down in block_kernel
+        def sweep():
+            for L in stack.layers:
+                stack.mlp(L, "fused")
+        shape = {"name": "norm+gate+up+silu_mul+down", "N": by["gate"].N, "K": by["gate"].K, "M": stack.M}
+        bytes_per_launch = sum(by[n].packed_bytes for n in ("gate", "up", "down"))
+        kernel = "block_kernel"
+    elif stack.M <= 16:
         names = ("gate", "up") if stack.block else (stack.cfg["linears"][0].name,)
         for L in stack.layers[:1]:          # any valid t will do for timing: it only feeds the up-projection
             stack.norm_group(L, names, L.gain_post, L.z_post)
@@ -246,7 +316,7 @@ def dominant_kernel_roofline(stack: Stack, reps: int):
     common = {"shape": shape, "us_per_launch": round(ms * 1e3, 2),
               "note": "one call per launch slot, back to back over the layers' distinct weights, launch gaps included"}
     if stack.M <= 128:
-        kernel = "stream_kernel" if stack.M <= 16 else "mid_kernel"
+        kernel = kernel or ("stream_kernel" if stack.M <= 16 else "mid_kernel")
         achieved = bytes_per_launch / (ms * 1e-3) / 1e9
         return {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4),
@@ -449,7 +519,7 @@ def measure_peaks():
 def run_leg(weights: Weights, M: int, args, steps: int, warmup: int, peaks):
     """One token count on the model's resident weights: whole-step time and the dominant kernel's roofline."""
     cfg = weights.cfg
-    stack = Stack(weights, M, swiglu=args.swiglu, eager=args.eager)
+    stack = Stack(weights, M, swiglu=args.swiglu, eager=args.eager, plan=args.launch_plan)
     step = stack.step if args.eager else capture(stack.step)
     for _ in range(warmup):
         step()
@@ -465,6 +535,10 @@ def run_leg(weights: Weights, M: int, args, steps: int, warmup: int, peaks):
     leg = {"M": M, "value": round(value, 1), "unit": "GB/s" if decode else "TFLOP/s", "steps": steps, "warmup": warmup,
            "ms_per_step": round(ms, 4), "weight_GBps": round(gbps, 1), "tflops": round(tflops, 2),
            "frac_of_peak_whole_step": round(value / peak, 4), "roofline": roof}
+    if stack.decode_block:
+        leg["launch_plan"] = dict(stack.plan)
+        if stack.plan_us:
+            leg["launch_plan_us_per_layer"] = stack.plan_us
     if decode:
         # at the published peaks the step cannot take less than the longer of its HBM time and its MFMA time
         t_hbm, t_mfma = step_bytes / (HBM_PEAK_GBS * 1e9), stack.flops_per_layer * stack.n_layers / (MFMA_BF16_PEAK_TFLOPS * 1e12)
@@ -493,6 +567,9 @@ def main():
                     help="time the MXFP4 variant's linear (MXFP8 activations, block-scaled matrix instruction) over the configuration's linears")
     ap.add_argument("--swiglu", action="store_true",
                     help="the down projection reads SiLU(gate) (.) up from the gate/up outputs (fused into its launch at M <= 16) instead of a resident input")
+    ap.add_argument("--launch-plan", choices=("auto", "separate", "fused"), default="auto",
+                    help="decode (M <= 16): {norm,q,k,v} and {norm,gate,up,SiLU-mul,down} as one persistent launch each "
+                         "(fused), as the separate launches, or whichever is faster per part when timed at set-up (auto)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-peaks", action="store_true", help="skip the achievable-ceiling microbenchmarks")
     ap.add_argument("--eager", action="store_true", help="launch from Python each step instead of replaying a HIP graph")
@@ -559,7 +636,9 @@ def main():
                                f"{'decode' if decode else 'prefill'} M={M}, "
                                f"LoRA r={cfg['r']} alpha={cfg['alpha']:g}, "
                                "AQN RMSNorm before q/k/v and gate/up, noise vectors regenerated on the device every step; "
-                               + ("down reads SiLU(gate)*up of the gate/up outputs; " if args.swiglu else "")
+                               + ("down reads SiLU(gate)*up of the gate/up outputs; " if (args.swiglu or head.get("launch_plan")) else "")
+                               + (f"launches per layer: q+k+v {head['launch_plan']['qkv']}, o 1, feed-forward {head['launch_plan']['mlp']}; "
+                                  if head.get("launch_plan") else "")
                                + ("eager launches" if args.eager else "one HIP graph replay per step"),
                    "packed_weight_bytes_per_step": step_bytes,
                    "tflops": head["tflops"], "weight_GBps": head["weight_GBps"],

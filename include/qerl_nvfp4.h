@@ -103,6 +103,13 @@ QERL_API int nvfp4_dequantize(const uint8_t* codes, const uint8_t* scales, const
  *     one stream.  A call that returned an error leaves it valid.  The control
  *     words sit at fixed offsets, so one workspace sized for the largest call
  *     (every argument at its maximum) serves calls of any smaller shape.
+ *     Where the adapters' down-projections run as the first workgroups of the
+ *     launch (M <= 128), the other workgroups wait for them: a bounded wait under
+ *     the co-residency assumption stated with aqn_rmsnorm_nvfp4_lora_mlp below.  A
+ *     wait that gives up writes NaN into y, sets the sticky error word of the
+ *     workspace and leaves the hand-over words as they are (the call has already
+ *     returned QERL_OK by then): qerl_workspace_status() reports it, and the
+ *     workspace must be prepared again with qerl_workspace_init() before reuse.
  *   tensor_scale: device pointer to one fp32, finite and non-zero (the
  *     quantizer never writes 0: an all-zero tensor gets 1).
  *
@@ -158,6 +165,8 @@ QERL_API int nvfp4_lora_linear_packed(const void* x_bf16, int64_t M, int64_t K, 
  *   nvfp4_lora_linear_packed_noalloc_max_bytes(), else QERL_ERR_WORKSPACE and
  *   nothing is enqueued (every single linear of Qwen2.5-7B/14B/32B shape up to
  *   4096 tokens and rank 64 fits).
+ *   The sticky error word of a wait that gave up is among the control words the
+ *   next call clears: with this entry point only the NaN in y shows it.
  *   All calls on one GPU share that GPU's array: calls that overlap in time on
  *   one GPU (different streams, different threads) race; order them on one
  *   stream.  The array belongs to the device that is current at the call.
@@ -262,6 +271,12 @@ QERL_API int aqn_rmsnorm_nvfp4_lora_mlp(const void* x_bf16, int64_t M, int64_t H
  * qerl_status_from_error_word (host): the decoding of that word. */
 QERL_API int qerl_workspace_status(const void* workspace, void* stream);
 QERL_API int qerl_status_from_error_word(uint32_t word);
+/* qerl_selftest_wait_gives_up: for tests of the error path.  Enqueues one wave that
+ * performs the kernels' bounded wait, cut to `polls` (1..1024) polls, on a hand-over
+ * word of `workspace` that nobody raises; it gives up, sets the sticky error word
+ * as the kernels do and exits.  Afterwards qerl_workspace_status() reports
+ * QERL_ERR_TIMEOUT until qerl_workspace_init().  Nothing hangs, nothing faults. */
+QERL_API int qerl_selftest_wait_gives_up(void* workspace, size_t workspace_bytes, uint32_t polls, void* stream);
 
 /* ---------------------------------------------------------------------------
  * nvfp4_lora_linear_packed_swiglu -- the feed-forward block's down projection

@@ -73,6 +73,7 @@ _SIGNATURES = {
                                                   _c_p, _c_p, _c_p, _c_p, _c_sz, _c_p]),
     "qerl_workspace_status": (ctypes.c_int, [_c_p, _c_p]),
     "qerl_status_from_error_word": (ctypes.c_int, [ctypes.c_uint32]),
+    "qerl_selftest_wait_gives_up": (ctypes.c_int, [_c_p, ctypes.c_size_t, ctypes.c_uint32, _c_p]),
     "qerl_peak_stream_read": (ctypes.c_int, [_c_p, _c_sz, ctypes.c_int, ctypes.c_int, _c_p, _c_p]),
     "qerl_peak_mfma_bf16": (ctypes.c_int, [_c_p, ctypes.c_int, ctypes.c_int, _c_p, _c_p]),
 }

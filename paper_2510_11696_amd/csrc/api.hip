@@ -208,6 +208,7 @@ extern "C" int nvfp4_lora_linear(const void* x, int64_t M, int64_t K, int64_t ld
 
 namespace qerl {
 static bool g_use_stream = true;
+static int64_t g_mid_gemm_min_rows = 16384;   // 65..128 tokens: groups with at least this many output rows go to the prefill GEMM
 static int64_t g_mid_producer_bytes = 24 << 20;   // 17..128 tokens: LoRA down-projections run inside the main launch when it streams at least this many packed bytes (long enough to hide them)
 
 // One streaming launch for a group of packed linears sharing x (M <= 16; every r in {0} or 8..64 step 8).
@@ -359,6 +360,7 @@ static int gemm_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, cons
 #ifdef QERL_TUNING_HOOKS   // built only for tuning sessions: they change process-wide state
 extern "C" QERL_API void qerl_debug_use_stream(int on) { qerl::g_use_stream = on != 0; }
 extern "C" QERL_API void qerl_debug_mid_producer_bytes(long long b) { qerl::g_mid_producer_bytes = b; }
+extern "C" QERL_API void qerl_debug_mid_gemm_min_rows(long long n) { qerl::g_mid_gemm_min_rows = n; }
 #endif  // QERL_TUNING_HOOKS
 
 static int packed_single(const void* x, int64_t M, int64_t K, int64_t ldx, const void* packed,
@@ -392,9 +394,13 @@ extern "C" int nvfp4_lora_linear_packed_group(const void* x, int64_t M, int64_t 
   if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total) return QERL_ERR_WORKSPACE;
   if (stream_ok && g_use_stream)
     return stream_group((const uint16_t*)x, M, K, ldx, members, n_members, (uint8_t*)workspace, L, (hipStream_t)stream);
-  if (M > 16 && M <= g_mid_max_tokens && mid_ok)
+  // 65..128 tokens on a group with many output rows (gate + up): the prefill GEMM has enough column blocks to fill
+  // the chip with one block of tokens and multiplies faster than the weight-streaming kernel (115 against 181 us
+  // for the 32B pair at 128 tokens); the workspace of such a shape holds the GEMM's areas
+  const bool wide = M > 64 && n_sum >= g_mid_gemm_min_rows && mid_partial_bytes(M, n_sum) >= kDownExchangeBytes;
+  if (M > 16 && M <= g_mid_max_tokens && mid_ok && !(wide && n_members > 1))
     return mid_group((const uint16_t*)x, M, K, ldx, members, n_members, (uint8_t*)workspace, L, (hipStream_t)stream);
-  if (M > g_mid_max_tokens && mid_ok && n_members > 1)
+  if ((M > g_mid_max_tokens || wide) && mid_ok && n_members > 1)
     return gemm_group((const uint16_t*)x, M, K, ldx, members, n_members, (uint8_t*)workspace, L, (hipStream_t)stream);
   for (int i = 0; i < n_members; ++i) {   // general case: member by member
     const qerl_linear_desc& d = members[i];

@@ -240,3 +240,10 @@ extern "C" int qerl_workspace_status(const void* workspace, void* stream) {
 }
 
 extern "C" int qerl_status_from_error_word(uint32_t word) { return word == 0u ? QERL_OK : QERL_ERR_TIMEOUT; }
+
+extern "C" int qerl_selftest_wait_gives_up(void* workspace, size_t workspace_bytes, uint32_t polls, void* stream) {
+  if (!workspace) return QERL_ERR_NULL;
+  if (!aligned(workspace, 256) || workspace_bytes < kCtrlRegionBytes) return QERL_ERR_WORKSPACE;
+  if (polls < 1 || polls > 1024) return QERL_ERR_SHAPE;   // a self-test, not a way to keep a wave spinning
+  return launch_block_wait_selftest((uint32_t*)workspace + kCtrlMainWords + kCtrlDownWords, polls, (hipStream_t)stream);
+}

@@ -114,6 +114,7 @@ struct BlkArgs {
   uint32_t* ctl; uint32_t* counters; float* partial; uint32_t* tpart; float* tfinal;
 };
 int plan_block(BlkArgs& a, size_t* lds_bytes, int* MR, size_t* partial_floats, size_t* counter_words);
+int launch_block_wait_selftest(uint32_t* ctl, uint32_t polls, hipStream_t st);   // error-path self-test: a bounded wait that gives up
 int launch_block(const BlkArgs& a, size_t lds_bytes, int MR, hipStream_t st);
 
 // ---- prefill path: MFMA GEMM on tile-packed weights (linear_gemm.hip) ----

@@ -128,12 +128,25 @@ __device__ __forceinline__ void blk_lds_barrier() {
 }
 
 // Bounded wait until *word >= target (agent scope).  Returns false when it gave up.
-__device__ __forceinline__ bool blk_wait_ge(const uint32_t* word, uint32_t target, int sleep) {
-  for (uint32_t spins = 0; spins < kBlkSpinLimit; ++spins) {
+__device__ __forceinline__ bool blk_wait_ge(const uint32_t* word, uint32_t target, int sleep, uint32_t limit = kBlkSpinLimit) {
+  for (uint32_t spins = 0; spins < limit; ++spins) {
     if (__hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) return true;
     if (sleep > 8) __builtin_amdgcn_s_sleep(32); else __builtin_amdgcn_s_sleep(2);
   }
   return false;
+}
+
+// One wave that waits, with the kernels' bounded wait cut to `polls` polls, for a hand-over word that nobody
+// raises, gives up, records it in the sticky word as the kernels do, and exits: the error path, end to end, with
+// nothing hanging.
+__global__ void blk_wait_selftest_kernel(uint32_t* ctl, uint32_t polls) {
+  if (threadIdx.x != 0) return;
+  if (!blk_wait_ge(ctl + kBlkReady + kBlkMaxStages - 1, 0xffffffffu, 2, polls))
+    __hip_atomic_fetch_or(ctl + kCtlErr, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+int launch_block_wait_selftest(uint32_t* ctl, uint32_t polls, hipStream_t st) {
+  blk_wait_selftest_kernel<<<1, 64, 0, st>>>(ctl, polls);
+  return launch_status();
 }
 
 template <int MR>
@@ -255,26 +268,29 @@ __global__ __launch_bounds__(kBlkThreads) void block_kernel(const BlkArgs a) {
   // A stage's K-tiles are cut into Sk ranges (of workgroups) x `phases` (in time) x kr_len tiles.  A wave owns row
   // tiles outright: tile v = slot + j * slots_r of its range, j = 0 .. n_my - 1, and walks each of them once per
   // phase (the accumulators wait in LDS between phases, the workgroup re-stages its x slice at each phase).
-  // Pairs (gate_proj / up_proj): waves 0..3 of a workgroup take gate tiles, waves 4..7 the up tiles of the same
-  // rows; wave w + 4 hands its finished tile to wave w, which forms SiLU(gate) (.) up and stores it.
+  // Pairs (gate_proj / up_proj), pairs == 1: waves 0..3 of a workgroup take gate tiles, waves 4..7 the up tiles of the
+  // same rows; wave w + 4 hands its finished tile to wave w, which forms SiLU(gate) (.) up and stores it.  pairs == 2
+  // (K split over ranges of workgroups, one phase): a wave walks gate_proj's tile and then up_proj's tile of the same
+  // rows over its K-range, leaves both shares in the workspace, and the wave that arrives last for the rows adds the
+  // shares of both, applies LoRA and bias to each and stores SiLU(gate) (.) up.
   struct Geo { int range, slot, slots_r, n_my; };
   auto geo = [&](int s) {
     const BlkStage& S = a.st[s];
     Geo g;
     g.range = cons / S.per_range;
     const int ci = cons - g.range * S.per_range;
-    if (S.pairs) { g.slot = ci * (kBlkWaves / 2) + (wave & 3); g.slots_r = S.per_range * (kBlkWaves / 2); }
+    if (S.pairs == 1) { g.slot = ci * (kBlkWaves / 2) + (wave & 3); g.slots_r = S.per_range * (kBlkWaves / 2); }
     else { g.slot = ci * kBlkWaves + wave; g.slots_r = S.per_range * kBlkWaves; }
     g.n_my = (g.range < S.Sk && g.slot < S.total_v) ? (S.total_v - g.slot + g.slots_r - 1) / g.slots_r : 0;
     return g;
   };
   auto seg_k0 = [&](const BlkStage& S, int range, int ph) { return (range * S.phases + ph) * S.kr_len; };
-  struct Pass { int s, ph, j; Geo g; };
+  struct Pass { int s, ph, j, sub; Geo g; };   // sub: pairs computed one after the other by one wave (pairs == 2): 0 gate_proj's tile, 1 up_proj's
   // row tile (within the stage's stacked members) of a pass
   auto pass_tile = [&](const Pass& p) {
     const BlkStage& S = a.st[p.s];
     const int v = p.g.slot + p.j * p.g.slots_r;
-    return (S.pairs && wave >= kBlkWaves / 2) ? S.mem[1].tile_begin + v : v;
+    return ((S.pairs == 1 && wave >= kBlkWaves / 2) || (S.pairs == 2 && p.sub)) ? S.mem[1].tile_begin + v : v;
   };
   auto member_of = [&](const BlkStage& S, int nt) {
     return (nt >= S.mem[1].tile_begin ? 1 : 0) + (nt >= S.mem[2].tile_begin ? 1 : 0) + (nt >= S.mem[3].tile_begin ? 1 : 0);
@@ -297,6 +313,8 @@ __global__ __launch_bounds__(kBlkThreads) void block_kernel(const BlkArgs a) {
     return mp + (int64_t)(nt - tb) * sn + (int64_t)k0 * sk;
   };
   auto next_pass = [&](Pass& p) {     // false: there is none
+    if (p.s >= 0 && a.st[p.s].pairs == 2 && p.sub == 0) { p.sub = 1; return true; }
+    p.sub = 0;
     ++p.j;
     if (p.j < p.g.n_my) return true;
     p.j = 0;
@@ -312,7 +330,7 @@ __global__ __launch_bounds__(kBlkThreads) void block_kernel(const BlkArgs a) {
   };
 
   Pass cur;
-  cur.s = -1; cur.ph = 0; cur.j = 0; cur.g = Geo{0, 0, 1, 0};
+  cur.s = -1; cur.ph = 0; cur.j = 0; cur.sub = 0; cur.g = Geo{0, 0, 1, 0};
   bool have_cur = next_pass(cur);
   const uint8_t* const park = a.st[0].mem[0].packed;   // where loads go that nobody needs: always valid memory
   BlkTile ring[D];
@@ -461,7 +479,8 @@ __global__ __launch_bounds__(kBlkThreads) void block_kernel(const BlkArgs a) {
     const int xs_stride = S.kr_len * 256 + 16;
     const int xrow = n32 < a.M ? n32 : a.M;
     const unsigned char* const xbase = smem + xrow * xs_stride + kg * 16;
-    const bool pair_up = S.pairs && wave >= kBlkWaves / 2;   // this wave computes up_proj tiles and hands them over
+    const bool pair_up = S.pairs == 1 && wave >= kBlkWaves / 2;   // this wave computes up_proj tiles and hands them over
+    const bool seq_pairs = S.pairs == 2;
     for (int ph = 0; ph < S.phases; ++ph) {
       if (ph == 0) {
         if (s > 0) {
@@ -520,7 +539,7 @@ __global__ __launch_bounds__(kBlkThreads) void block_kernel(const BlkArgs a) {
         int nnv = 1;
         const uint8_t* const nbase = have_next ? pass_base(nxt, nkstride, nnv) : park;
         if (!have_next) { nkstride = 0; nnv = 1; }
-        const bool lora = last_phase && mem.r > 0;   // (with K split over ranges, the wave that adds the shares applies it)
+        const bool lora = last_phase && mem.r > 0 && !seq_pairs;   // (with K split over ranges, the wave that adds the shares applies it)
         const int64_t row0 = (int64_t)(nt - mem.tile_begin) * 32;
         u32x4 bfrag[4];
         {
@@ -537,7 +556,7 @@ __global__ __launch_bounds__(kBlkThreads) void block_kernel(const BlkArgs a) {
         }
         uint16_t bias_bits = 0;
         {
-          const bool live = last_phase && mem.bias && row0 + n32 < mem.N;
+          const bool live = last_phase && !seq_pairs && mem.bias && row0 + n32 < mem.N;
           const uint16_t* src = live ? mem.bias + row0 + n32 : reinterpret_cast<const uint16_t*>(park);
           bias_bits = *src;
           if (!live) bias_bits = 0;
@@ -565,15 +584,16 @@ __global__ __launch_bounds__(kBlkThreads) void block_kernel(const BlkArgs a) {
           float out[MR];
 #pragma unroll
           for (int q = 0; q < MR; ++q) out[q] = acc[q] * S32;
-          auto add_lora_bias = [&]() {
-            if (lora) {
+          auto add_lora_bias = [&](float (&o)[MR], const int mi_, const bool lora_, const u32x4 (&bf_)[4], const uint32_t bias_bits_) {
+            const BlkMember& mm = S.mem[mi_];
+            if (lora_) {
               // t of this member in LDS as three bf16 terms; the first wave of the workgroup that needs it puts it there
-              uint32_t ts = __hip_atomic_load(&s_tstate[mi], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP);
+              uint32_t ts = __hip_atomic_load(&s_tstate[mi_], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP);
               if (ts < 2u) {
                 int won = 0;
                 if (lane == 0) {
                   uint32_t expect = 0u;
-                  won = __hip_atomic_compare_exchange_strong(&s_tstate[mi], &expect, 1u, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                  won = __hip_atomic_compare_exchange_strong(&s_tstate[mi_], &expect, 1u, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
                                                              __HIP_MEMORY_SCOPE_WORKGROUP) ? 1 : 0;
                 }
                 won = __builtin_amdgcn_readfirstlane(won);
@@ -582,9 +602,9 @@ __global__ __launch_bounds__(kBlkThreads) void block_kernel(const BlkArgs a) {
                   if (!arrived && lane == 0) __hip_atomic_fetch_or(err_word, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
                   // the finished t of this member, M x r floats: one round of loads, split into three bf16 terms
-                  const int r4 = mem.r >> 2, n4 = a.M * r4;
-                  const float* src = a.tfinal + (int64_t)s * kBlkTfinalWords + mem.t_off;
-                  uint16_t* th = reinterpret_cast<uint16_t*>(tarea) + (mi * 3) * MT * 64;
+                  const int r4 = mm.r >> 2, n4 = a.M * r4;
+                  const float* src = a.tfinal + (int64_t)s * kBlkTfinalWords + mm.t_off;
+                  uint16_t* th = reinterpret_cast<uint16_t*>(tarea) + (mi_ * 3) * MT * 64;
                   f32x4 tq[4];
 #pragma unroll
                   for (int i = 0; i < 4; ++i) {
@@ -615,10 +635,10 @@ __global__ __launch_bounds__(kBlkThreads) void block_kernel(const BlkArgs a) {
                     }
                   }
                   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                  if (lane == 0) __hip_atomic_store(&s_tstate[mi], arrived ? 2u : 3u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                  if (lane == 0) __hip_atomic_store(&s_tstate[mi_], arrived ? 2u : 3u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
                 } else {
                   uint32_t spins = 0;
-                  while (__hip_atomic_load(&s_tstate[mi], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < 2u) {
+                  while (__hip_atomic_load(&s_tstate[mi_], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < 2u) {
                     if (++spins > 4 * kBlkSpinLimit) break;   // the loading wave itself gives up long before this
                     __builtin_amdgcn_s_sleep(8);
                   }
@@ -627,31 +647,117 @@ __global__ __launch_bounds__(kBlkThreads) void block_kernel(const BlkArgs a) {
               f32x16 l;
 #pragma unroll
               for (int i = 0; i < 16; ++i) l[i] = 0.f;
-              const unsigned char* trow = tarea + ((mi * 3) * MT + (n32 < MT ? n32 : 0)) * 128 + kg * 16;
+              const unsigned char* trow = tarea + ((mi_ * 3) * MT + (n32 < MT ? n32 : 0)) * 128 + kg * 16;
 #pragma unroll
               for (int st = 0; st < 4; ++st) {
-                if (16 * st < mem.r) {
-                  const bf16x8 bf = __builtin_bit_cast(bf16x8, bfrag[st]);
+                if (16 * st < mm.r) {
+                  const bf16x8 bf = __builtin_bit_cast(bf16x8, bf_[st]);
 #pragma unroll
                   for (int term = 0; term < 3; ++term) {
                     u32x4 tv = *reinterpret_cast<const u32x4*>(trow + term * MT * 128 + st * 32);
-                    if (n32 >= a.M || 16 * st + 8 * kg >= mem.r) tv = u32x4{0u, 0u, 0u, 0u};   // rows beyond the tokens, ranks beyond r: never written
+                    if (n32 >= a.M || 16 * st + 8 * kg >= mm.r) tv = u32x4{0u, 0u, 0u, 0u};   // rows beyond the tokens, ranks beyond r: never written
                     l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tv), bf, l, 0, 0, 0);
                   }
                 }
               }
 #pragma unroll
-              for (int q = 0; q < MR; ++q) out[q] += l[q] * mem.lora_scale;
+              for (int q = 0; q < MR; ++q) o[q] += l[q] * mm.lora_scale;
             }
             {
-              const float bias = bf16_bits_to_f32(bias_bits);   // +0 without one
+              const float bias = bf16_bits_to_f32(bias_bits_);   // +0 without one
 #pragma unroll
-              for (int q = 0; q < MR; ++q) out[q] += bias;
+              for (int q = 0; q < MR; ++q) o[q] += bias;
             }
           };
-          if (S.Sk == 1) add_lora_bias();
-
           bool finish = true;            // this wave stores the tile
+          float up[MR];                  // pairs: up_proj's finished tile
+          bool have_up = false;
+          if (seq_pairs && cur.sub == 0) {
+            // gate_proj's share of the rows waits in LDS while the wave walks up_proj's tile
+#pragma unroll
+            for (int q4 = 0; q4 < MR / 4; ++q4)
+              *reinterpret_cast<f32x4*>(parkbuf + lane * MR + 4 * q4) = f32x4{out[4 * q4], out[4 * q4 + 1], out[4 * q4 + 2], out[4 * q4 + 3]};
+            finish = false;
+          } else if (seq_pairs) {
+            // `out` is up_proj's share; both shares go to the workspace, the last wave to arrive for these rows finishes both
+            float og[MR];
+#pragma unroll
+            for (int q4 = 0; q4 < MR / 4; ++q4) {
+              const f32x4 v = *reinterpret_cast<const f32x4*>(parkbuf + lane * MR + 4 * q4);
+              og[4 * q4] = v[0]; og[4 * q4 + 1] = v[1]; og[4 * q4 + 2] = v[2]; og[4 * q4 + 3] = v[3];
+            }
+            const int vt = nt - S.mem[1].tile_begin;     // the pair's index = gate_proj's tile
+            const int64_t stride = (int64_t)S.total_tiles * 64 * MR / 2;
+            uint64_t* const pg = reinterpret_cast<uint64_t*>(a.partial + S.partial_off + ((int64_t)vt * 64 + lane) * MR);
+            uint64_t* const pu = reinterpret_cast<uint64_t*>(a.partial + S.partial_off + ((int64_t)nt * 64 + lane) * MR);
+            if (S.Sk > 1) {
+#pragma unroll
+              for (int q2 = 0; q2 < MR / 2; ++q2) {
+                __hip_atomic_store(pg + (int64_t)cur.g.range * stride + q2, (uint64_t)__float_as_uint(og[2 * q2]) | ((uint64_t)__float_as_uint(og[2 * q2 + 1]) << 32),
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(pu + (int64_t)cur.g.range * stride + q2, (uint64_t)__float_as_uint(out[2 * q2]) | ((uint64_t)__float_as_uint(out[2 * q2 + 1]) << 32),
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              }
+              __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the shares are in memory before the count
+              uint32_t* ctr = a.counters + S.ctr_off + vt;
+              uint32_t old = 0;
+              if (lane == 0) old = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              old = __builtin_amdgcn_readfirstlane(old);
+              finish = old == (uint32_t)(S.Sk - 1);
+              if (finish && lane == 0) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+            }
+            if (finish) {
+              // B rows and biases of both members, and the shares, in one round of loads
+              u32x4 bg[4], bu[4];
+              int64_t brow = row0 + n32;
+              brow = brow < mem.N ? brow : mem.N - 1;
+              const BlkMember& m0 = S.mem[0];
+#pragma unroll
+              for (int st = 0; st < 4; ++st) {
+                const int j0 = 16 * st + 8 * kg;
+                bg[st] = u32x4{0u, 0u, 0u, 0u}; bu[st] = u32x4{0u, 0u, 0u, 0u};
+                if (j0 < m0.r) bg[st] = *reinterpret_cast<const u32x4*>(m0.B + brow * m0.r + j0);
+                if (j0 < mem.r) bu[st] = *reinterpret_cast<const u32x4*>(mem.B + brow * mem.r + j0);
+              }
+              uint32_t bias_g = 0, bias_u = 0;
+              if (m0.bias && row0 + n32 < m0.N) bias_g = m0.bias[row0 + n32];
+              if (mem.bias && row0 + n32 < mem.N) bias_u = mem.bias[row0 + n32];
+              if (S.Sk > 1) {
+#pragma unroll
+                for (int q = 0; q < MR; ++q) { og[q] = 0.f; out[q] = 0.f; }
+                constexpr int ZB = 2;
+                for (int z0 = 0; z0 < S.Sk; z0 += ZB) {
+                  uint64_t wg_[ZB][MR / 2], wu_[ZB][MR / 2];
+#pragma unroll
+                  for (int b = 0; b < ZB; ++b)
+#pragma unroll
+                    for (int q2 = 0; q2 < MR / 2; ++q2) {
+                      wg_[b][q2] = 0ull; wu_[b][q2] = 0ull;
+                      if (z0 + b < S.Sk) {
+                        wg_[b][q2] = __hip_atomic_load(pg + (int64_t)(z0 + b) * stride + q2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        wu_[b][q2] = __hip_atomic_load(pu + (int64_t)(z0 + b) * stride + q2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                      }
+                    }
+#pragma unroll
+                  for (int b = 0; b < ZB; ++b)
+#pragma unroll
+                    for (int q2 = 0; q2 < MR / 2; ++q2) {
+                      og[2 * q2] += __uint_as_float((uint32_t)wg_[b][q2]);
+                      og[2 * q2 + 1] += __uint_as_float((uint32_t)(wg_[b][q2] >> 32));
+                      out[2 * q2] += __uint_as_float((uint32_t)wu_[b][q2]);
+                      out[2 * q2 + 1] += __uint_as_float((uint32_t)(wu_[b][q2] >> 32));
+                    }
+                }
+              }
+              add_lora_bias(og, 0, m0.r > 0, bg, bias_g);
+              add_lora_bias(out, 1, mem.r > 0, bu, bias_u);
+#pragma unroll
+              for (int q = 0; q < MR; ++q) { up[q] = out[q]; out[q] = og[q]; }
+              have_up = true;
+            }
+          } else {
+          if (S.Sk == 1) add_lora_bias(out, mi, lora, bfrag, bias_bits);
+
           if (S.Sk > 1) {
             // K is split over ranges of workgroups: leave this range's share in the workspace and count; the wave that
             // arrives last adds the shares in range order (all requested in one round of loads).
@@ -691,8 +797,9 @@ __global__ __launch_bounds__(kBlkThreads) void block_kernel(const BlkArgs a) {
                     out[2 * q2 + 1] += __uint_as_float((uint32_t)(w[b][q2] >> 32));
                   }
               }
-              add_lora_bias();
+              add_lora_bias(out, mi, lora, bfrag, bias_bits);
             }
+          }
           }
 
           if (finish && pair_up) {
@@ -717,23 +824,24 @@ __global__ __launch_bounds__(kBlkThreads) void block_kernel(const BlkArgs a) {
             if (S.pairs) {
               // act = bf16(bf16(SiLU(gate)) * up) on the bf16-rounded projections: what a bf16 model evaluated
               // operator by operator gives.  up_proj's tile comes from the partner wave.
-              const int fi = wave & 3;
-              uint32_t spins = 0;
-              bool got = true;
-              while (__hip_atomic_load(&xflag[fi], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < (uint32_t)(cur.j + 1)) {
-                if (++spins > 4 * kBlkSpinLimit) { got = false; break; }
-                __builtin_amdgcn_s_sleep(2);
-              }
-              float up[MR];
+              if (!have_up) {
+                const int fi = wave & 3;
+                uint32_t spins = 0;
+                bool got = true;
+                while (__hip_atomic_load(&xflag[fi], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < (uint32_t)(cur.j + 1)) {
+                  if (++spins > 4 * kBlkSpinLimit) { got = false; break; }
+                  __builtin_amdgcn_s_sleep(2);
+                }
 #pragma unroll
-              for (int q4 = 0; q4 < MR / 4; ++q4) {
-                const f32x4 v = *reinterpret_cast<const f32x4*>(xbuf + lane * MR + 4 * q4);
-                up[4 * q4] = v[0]; up[4 * q4 + 1] = v[1]; up[4 * q4 + 2] = v[2]; up[4 * q4 + 3] = v[3];
-              }
-              asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-              if (lane == 0) {
-                __hip_atomic_store(&xflag[4 + fi], (uint32_t)(cur.j + 1), __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
-                if (!got) __hip_atomic_fetch_or(err_word, 4u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (int q4 = 0; q4 < MR / 4; ++q4) {
+                  const f32x4 v = *reinterpret_cast<const f32x4*>(xbuf + lane * MR + 4 * q4);
+                  up[4 * q4] = v[0]; up[4 * q4 + 1] = v[1]; up[4 * q4 + 2] = v[2]; up[4 * q4 + 3] = v[3];
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                if (lane == 0) {
+                  __hip_atomic_store(&xflag[4 + fi], (uint32_t)(cur.j + 1), __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                  if (!got) __hip_atomic_fetch_or(err_word, 4u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
               }
 #pragma unroll
               for (int q = 0; q < MR; q += 2) {
@@ -819,8 +927,7 @@ static size_t blk_lds_total(const BlkLds& l) { return l.x + l.g + l.t + l.y + l.
 // workgroups, and fills the stage's plan fields.  Model: a wave multiplies one tile in about t_tile us when nothing
 // holds it up (two waves share a SIMD), the chip streams about 6 MB per us; a wave's units and phases run one after
 // the other; splitting K over workgroups costs a trip through memory and the partial tiles' traffic, an extra phase
-// costs a workgroup barrier and a re-staging of x.  A gate / up pair is finished inside one workgroup, so its K is
-// never split over workgroups.
+// costs a workgroup barrier and a re-staging of x.  
 static int plan_block_stage(BlkStage& S, int M, int MR, int n_cons, int* park_units) {
   const int D = kBlkD;
   const bool norm = S.gain != nullptr, pairs = S.pairs != 0;
@@ -828,7 +935,7 @@ static int plan_block_stage(BlkStage& S, int M, int MR, int n_cons, int* park_un
   const int cpt_cap = 2 * kBlkThreads / 16;   // slice chunks whose gain + noise a workgroup stages in one round
   const double t_tile = MR == 4 ? 0.46 : 0.65, chip_rate = 6.0e6, wave_rate = kPackTileBytes / t_tile;   // bytes per us
   const double bytes = (double)S.total_tiles * S.k_tiles * kPackTileBytes;
-  int best_kr = 0, best_ph = 0, best_park = 0;
+  int best_kr = 0, best_ph = 0, best_park = 0, best_mode = 0;
   double best_cost = 0;
   for (int kr = D; kr <= kt_pad && kr <= cpt_cap; kr += D) {
     if (g_blk_force_kr > 0 && kr != g_blk_force_kr) continue;
@@ -837,21 +944,28 @@ static int plan_block_stage(BlkStage& S, int M, int MR, int n_cons, int* park_un
       if (n_seg % ph != 0) continue;
       if (g_blk_force_phases > 0 && ph != g_blk_force_phases) continue;
       const int Sk = n_seg / ph;
-      if (Sk > n_cons || (pairs && Sk != 1)) continue;
+      if (Sk > n_cons) continue;
+      // a gate / up pair: finished inside one workgroup by two waves (K in one range), or by one wave that walks
+      // both tiles over its K-range, with the shares of the ranges meeting in the workspace (one phase)
+      const int mode = !pairs ? 0 : (Sk == 1 ? 1 : 2);
+      if (mode == 2 && ph != 1) continue;
       const int per_range = n_cons / Sk;
-      const int64_t slots_r = (int64_t)per_range * (pairs ? kBlkWaves / 2 : kBlkWaves);
+      const int64_t slots_r = (int64_t)per_range * (mode == 1 ? kBlkWaves / 2 : kBlkWaves);
       const int64_t rounds = ceil_div(S.total_v, slots_r);
       if (ph > 1 && rounds > kBlkParkMax) continue;
-      const int park = ph > 1 ? (int)rounds : 1;
-      if (blk_lds_total(blk_lds(M, MR, kr, norm, ph > 1 ? park : 0, pairs)) > kBlkLdsMax) continue;
-      const int64_t active = (S.total_v < slots_r ? S.total_v : slots_r) * Sk * (pairs ? 2 : 1);
+      const int park = ph > 1 ? (int)rounds : (mode == 2 ? 1 : 0);
+      if (blk_lds_total(blk_lds(M, MR, kr, norm, park, mode == 1)) > kBlkLdsMax) continue;
+      const int64_t active = (S.total_v < slots_r ? S.total_v : slots_r) * Sk * (mode == 1 ? 2 : 1);
       const double rate = active * wave_rate < chip_rate ? active * wave_rate : chip_rate;
       const double extra = Sk > 1 ? 1.5 * Sk * S.total_tiles * 64.0 * MR * 4 : 0.0;   // partial tiles out and back
       double cost = (bytes + extra) / rate;
-      const double chain = (double)rounds * ph * kr * t_tile;
+      const double chain = (double)rounds * ph * kr * t_tile * (mode == 2 ? 2 : 1);
       cost = cost > chain ? cost : chain;
-      cost += 2.0 * (rounds - 1) + (Sk > 1 ? 6.0 + 0.25 * Sk : 0.0) + 4.0 * (ph - 1);
-      if (best_kr == 0 || cost < best_cost - 1e-9) { best_kr = kr; best_ph = ph; best_park = park; best_cost = cost; }
+      // measured: a further round of units 2 us, the exchange of a K split 6 us and more (a pair's: two shares, two
+      // adapters' t, behind the slowest of the ranges: 22 us against 11 us for a second phase on the 32B pair at 16
+      // tokens), a further phase 10 us
+      cost += 2.0 * (rounds - 1) + (Sk > 1 ? (mode == 2 ? 20.0 : 6.0) + 0.25 * Sk : 0.0) + 10.0 * (ph - 1);
+      if (best_kr == 0 || cost < best_cost - 1e-9) { best_kr = kr; best_ph = ph; best_park = park; best_cost = cost; best_mode = mode; }
     }
   }
   if (best_kr == 0) return QERL_ERR_SHAPE;
@@ -859,7 +973,8 @@ static int plan_block_stage(BlkStage& S, int M, int MR, int n_cons, int* park_un
   S.phases = best_ph;
   S.Sk = (int)ceil_div(S.k_tiles, best_kr) / best_ph;
   S.per_range = n_cons / S.Sk;
-  *park_units = best_ph > 1 ? best_park : 0;
+  S.pairs = best_mode;
+  *park_units = best_park;
   return QERL_OK;
 }
 
@@ -908,7 +1023,7 @@ int plan_block(BlkArgs& a, size_t* lds_bytes, int* MR_out, size_t* partial_float
     const int rc = plan_block_stage(S, a.M, MR, n_cons, &park);
     if (rc != QERL_OK) return rc;
     park_max = park > park_max ? park : park_max;
-    const BlkLds l = blk_lds(a.M, MR, S.kr_len, S.gain != nullptr, park, S.pairs != 0);
+    const BlkLds l = blk_lds(a.M, MR, S.kr_len, S.gain != nullptr, park, S.pairs == 1);
     mx.x = l.x > mx.x ? l.x : mx.x; mx.g = l.g > mx.g ? l.g : mx.g; mx.t = l.t; mx.y = l.y;
     mx.park = l.park > mx.park ? l.park : mx.park; mx.exch = l.exch > mx.exch ? l.exch : mx.exch;
     S.ctr_off = (int)ctrs; S.partial_off = (int64_t)part;
@@ -931,8 +1046,8 @@ int plan_block(BlkArgs& a, size_t* lds_bytes, int* MR_out, size_t* partial_float
 #ifdef QERL_TUNING_HOOKS
   if (getenv("QERL_BLK_TRACE"))
     for (int s = 0; s < a.n_stages; ++s)
-      fprintf(stderr, "block plan: M %d stage %d K-tiles %d tiles %d units %d  kr_len %d phases %d Sk %d per_range %d producers %d\n", a.M, s,
-              a.st[s].k_tiles, a.st[s].total_tiles, a.st[s].total_v, a.st[s].kr_len, a.st[s].phases, a.st[s].Sk, a.st[s].per_range, a.st[s].n_producers);
+      fprintf(stderr, "block plan: M %d stage %d K-tiles %d tiles %d units %d  kr_len %d phases %d Sk %d per_range %d producers %d pairs %d\n", a.M, s,
+              a.st[s].k_tiles, a.st[s].total_tiles, a.st[s].total_v, a.st[s].kr_len, a.st[s].phases, a.st[s].Sk, a.st[s].per_range, a.st[s].n_producers, a.st[s].pairs);
 #endif
   a.park_units = park_max > 0 ? park_max : 1;
   a.g_lds_off = (int)mx.x;
@@ -984,11 +1099,11 @@ int launch_block(const BlkArgs& a, size_t lds, int MR, hipStream_t st) {
         false)
       return QERL_ERR_SHAPE;
     {
-      const int64_t slots_r = (int64_t)S.per_range * (S.pairs ? kBlkWaves / 2 : kBlkWaves);
+      const int64_t slots_r = (int64_t)S.per_range * (S.pairs == 1 ? kBlkWaves / 2 : kBlkWaves);
       if (S.phases > 1 && ceil_div(S.total_v, slots_r) > a.park_units) return QERL_ERR_SHAPE;
-      if (S.pairs && S.Sk != 1) return QERL_ERR_SHAPE;
+      if (S.pairs < 0 || S.pairs > 2 || (S.pairs == 1 && S.Sk != 1) || (S.pairs == 2 && S.phases != 1)) return QERL_ERR_SHAPE;
     }
-    any_phases |= S.phases > 1; any_pairs |= S.pairs != 0;
+    any_phases |= S.phases > 1; any_pairs |= S.pairs == 1;
     if (S.gain && (((uintptr_t)S.gain & 15) != 0 || ((uintptr_t)S.noise & 15) != 0 || S.K % 8 != 0)) return QERL_ERR_ALIGN;
     int tiles = 0;
     for (int i = 0; i < S.n_members; ++i) {

@@ -297,7 +297,11 @@ __global__ __launch_bounds__(kDecMaxWaves * 64) void decode32_kernel(const Decod
     if (first && a.n_producers > 0) {
       uint32_t spins = 0;
       while (__hip_atomic_load(a.lora_ctl + kCtlReady, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
-        if (++spins > kSpinLimit) { poisoned = true; break; }
+        if (++spins > kSpinLimit) {
+          poisoned = true;
+          if (lane == 0) __hip_atomic_fetch_or(a.lora_ctl + kCtlErr, 4u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          break;
+        }
         __builtin_amdgcn_s_sleep(32);
       }
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
@@ -326,7 +330,7 @@ __global__ __launch_bounds__(kDecMaxWaves * 64) void decode32_kernel(const Decod
     if (first && a.n_producers > 0 && lane == 0) {
       // every first-slice workgroup has now read t; the last of them re-arms the control words
       const uint32_t old = __hip_atomic_fetch_add(a.lora_ctl + kCtlDone, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (old == (uint32_t)(a.n_groups - 1)) {
+      if (old == (uint32_t)(a.n_groups - 1) && __hip_atomic_load(a.lora_ctl + kCtlErr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {   // (not after a wait that gave up)
         __hip_atomic_store(a.lora_ctl + kCtlReady, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(a.lora_ctl + kCtlDone, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }

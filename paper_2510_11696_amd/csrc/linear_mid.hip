@@ -202,7 +202,11 @@ main_done:
     // ts comes from the producers of this launch: wait (bounded) until all of them have published it
     uint32_t spins = 0;
     while (__hip_atomic_load(a.ready, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (uint32_t)(a.p_tbs * a.p_tiles)) {
-      if (++spins > kMidSpinLimit) { poisoned = true; break; }   // never reached unless a producer died: make it visible
+      if (++spins > kMidSpinLimit) {   // never reached unless a producer died or was kept off the chip: make it visible
+        poisoned = true;
+        if (tid == 0) __hip_atomic_fetch_or(a.ready + kCtlErr, 4u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        break;
+      }
       __builtin_amdgcn_s_sleep(32);
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
@@ -227,7 +231,7 @@ main_done:
   if (a.n_prod > 0 && tid == 0) {
     // the last consumer to leave re-arms the hand-over words (every waiting workgroup has passed its wait by then)
     const uint32_t old = __hip_atomic_fetch_add(a.done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (old == (uint32_t)(a.n_consumers - 1)) {
+    if (old == (uint32_t)(a.n_consumers - 1) && __hip_atomic_load(a.ready + kCtlErr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {   // (not after a wait that gave up)
       __hip_atomic_store(a.ready, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(a.done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }

@@ -465,7 +465,11 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
           break;
         }
         if (can_receive_more) break;      // one look per unit while there is streaming to attend to
-        if (++spins > kStreamSpinLimit) { poisoned = true; t_ready = true; break; }   // bounded: poison the output
+        if (++spins > kStreamSpinLimit) {   // bounded: poison the output and leave word in the workspace
+          poisoned = true; t_ready = true;
+          if (lane == 0) __hip_atomic_fetch_or(a.lora_ctl + kCtlErr, 4u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          break;
+        }
         __builtin_amdgcn_s_sleep(32);
       }
       if (!t_ready) continue;
@@ -547,12 +551,14 @@ __global__ __launch_bounds__(kStreamWaves * 64) void stream_kernel(const StreamA
     if (!t_ready) {   // a workgroup without LoRA units still has to count, after the hand-over is complete
       uint32_t spins = 0;
       while (__hip_atomic_load(a.lora_ctl + kCtlArrive, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != (uint32_t)a.n_producers) {
-        if (++spins > kStreamSpinLimit) break;
+        if (++spins > kStreamSpinLimit) { __hip_atomic_fetch_or(a.lora_ctl + kCtlErr, 4u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); break; }
         __builtin_amdgcn_s_sleep(32);
       }
     }
+    // (after a wait that gave up the words stay as they are: a late producer may still count, and the sticky word
+    // tells the host that the workspace has to be initialised again)
     const uint32_t old = __hip_atomic_fetch_add(a.lora_ctl + kCtlDone, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (old == (uint32_t)(a.per_range - 1)) {
+    if (old == (uint32_t)(a.per_range - 1) && __hip_atomic_load(a.lora_ctl + kCtlErr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
       __hip_atomic_store(a.lora_ctl + kCtlArrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(a.lora_ctl + kCtlDone, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }

@@ -29,9 +29,25 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_status_strings(lib):
-    for code in range(0, -6, -1):
+    for code in range(0, -7, -1):
         assert lib.qerl_status_string(code)
+        assert b"unknown" not in lib.qerl_status_string(code)
     assert b"unknown" in lib.qerl_status_string(-99)
+
+
+def test_error_word_decoding_and_status_call_validation(lib):
+    """The sticky word of the control region: zero is fine, any bit a kernel's abandoned wait sets (stage boundary,
+    LoRA hand-over, another kernel's hand-over) reads as QERL_ERR_TIMEOUT; the host rejects bad arguments first."""
+    assert lib.qerl_status_from_error_word(0) == 0
+    for word in (1, 2, 4, 7, 0x80000000):
+        assert lib.qerl_status_from_error_word(word) == -6
+    assert b"wait" in lib.qerl_status_string(-6) or b"time" in lib.qerl_status_string(-6).lower()
+    assert lib.qerl_workspace_status(None, None) == -1
+    assert lib.qerl_workspace_status(0x10010, None) == -3
+    assert lib.qerl_selftest_wait_gives_up(None, 1 << 20, 4, None) == -1
+    assert lib.qerl_selftest_wait_gives_up(0x10000, 64, 4, None) == -4          # smaller than the control region
+    assert lib.qerl_selftest_wait_gives_up(0x10000, 1 << 20, 0, None) == -2
+    assert lib.qerl_selftest_wait_gives_up(0x10000, 1 << 20, 1 << 20, None) == -2  # no long spins on request
 
 
 def test_sigma_schedule_host(lib):

@@ -139,3 +139,26 @@ def test_fused_entry_points_beyond_16_tokens_run_the_separate_launches(M):
     check_linear(y, _ref(down, act, 2.0), ("mlp, separate launches", M), slack=2e-3)
     check_linear(outs[0], _ref(gate, xn, 2.0), ("group, separate launches", M))
     check_linear(outs[1], _ref(up, xn, 2.0), ("group, separate launches", M))
+
+
+def test_a_wait_that_gives_up_is_reported_until_the_workspace_is_initialised_again():
+    """The error path end to end, forced from the host: one wave runs the kernels' bounded wait (cut to a few polls) on
+    a hand-over word that nobody raises, gives up, sets the sticky word and exits normally."""
+    lib = qerl.load_library()
+    M, H = 4, 512
+    ws = qerl.Workspace(qerl.aqn_rmsnorm_nvfp4_lora_linear_group_workspace_bytes(M, H, [64], [16]))
+    st = torch.cuda.current_stream().cuda_stream
+    assert qerl.workspace_status(ws) == 0
+    assert lib.qerl_selftest_wait_gives_up(ws.ptr, ws.nbytes, 8, st) == 0
+    assert qerl.workspace_status(ws) == -6
+    assert qerl.workspace_status(ws) == -6                      # sticky
+    assert lib.qerl_workspace_init(ws.ptr, ws.nbytes, st) == 0
+    assert qerl.workspace_status(ws) == 0
+    # and the workspace serves a call again
+    xin, gain, Z, xn = _norm_inputs(M, H, 990, 1e-2)
+    m = _member(64, H, 16, 6400)
+    y = qerl.aqn_rmsnorm_nvfp4_lora_linear_group(xin.cuda(), gain.cuda(), Z.cuda(), 1e-6, [m["pw"]], [m["Ad"]], [m["Bd"]], [2.0],
+                                                 workspace=ws)[0]
+    torch.cuda.synchronize()
+    assert qerl.workspace_status(ws) == 0
+    check_linear(y, _ref(m, xn, 2.0), ("after re-initialisation",))

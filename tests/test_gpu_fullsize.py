@@ -24,7 +24,7 @@ pytestmark = pytest.mark.gpu
 class FullMember:
     """One full-size linear: whole tensor quantised and packed on the GPU, sampled rows quantised by the oracle."""
 
-    def __init__(self, name, N, K, r, seed, n_rows=160):
+    def __init__(self, name, N, K, r, seed, n_rows=160, keep_all=False):
         print("  building", name, N, K, r, flush=True)
         self.name, self.N, self.K, self.r = name, N, K, r
         W = cases.gaussian(N, K, seed)
@@ -32,10 +32,16 @@ class FullMember:
         amax_row = flat // K
         rng = np.random.default_rng(seed + 1)
         self.rows = np.unique(np.concatenate([np.arange(32), np.arange(N - 32, N), rng.integers(0, N, size=n_rows)]))
-        sub = np.unique(np.concatenate([self.rows, [amax_row]]))
-        codes, scales, ts = oracle.nvfp4_quantize(W[sub])
-        keep = np.searchsorted(sub, self.rows)
-        self.codes, self.scales, self.ts = codes[keep], scales[keep], ts
+        if keep_all:
+            # the oracle quantises the whole tensor (half a minute for 27648 x 5120): needed where the oracle has to
+            # produce every output of the layer, because the next operator of a composition reads them all
+            self.codes_all, self.scales_all, ts = oracle.nvfp4_quantize(W)
+            self.codes, self.scales, self.ts = self.codes_all[self.rows], self.scales_all[self.rows], ts
+        else:
+            sub = np.unique(np.concatenate([self.rows, [amax_row]]))
+            codes, scales, ts = oracle.nvfp4_quantize(W[sub])
+            keep = np.searchsorted(sub, self.rows)
+            self.codes, self.scales, self.ts = codes[keep], scales[keep], ts
         Wg = torch.from_numpy(W).to(torch.bfloat16).cuda()
         del W
         gc, gs, gts = qerl.nvfp4_quantize(Wg)
@@ -60,21 +66,27 @@ class FullMember:
                                         self.B.float().numpy()[self.rows] if self.r else None, lora_scale,
                                         bias=None if bias is None else bias[self.rows])
 
-    def check(self, y, x_f32, lora_scale, what):
-        check_linear(y[:, self.rows_d], self.reference(x_f32, lora_scale), what)
+    def reference_all(self, x_f32, lora_scale):
+        """Every output row (keep_all members only)."""
+        return oracle.nvfp4_lora_linear(x_f32, self.codes_all, self.scales_all, self.ts,
+                                        self.A.float().numpy() if self.r else None,
+                                        self.B.float().numpy() if self.r else None, lora_scale)
+
+    def check(self, y, x_f32, lora_scale, what, slack=1e-3):
+        check_linear(y[:, self.rows_d], self.reference(x_f32, lora_scale), what, slack=slack)
 
 
 @pytest.fixture(scope="module")
 def mlp_7b():
     H, I, r = 3584, 18944, 32
-    return {"gate": FullMember("7b gate", I, H, r, 61001), "up": FullMember("7b up", I, H, r, 61011),
+    return {"gate": FullMember("7b gate", I, H, r, 61001, keep_all=True), "up": FullMember("7b up", I, H, r, 61011, keep_all=True),
             "down": FullMember("7b down", H, I, r, 61021)}
 
 
 @pytest.fixture(scope="module")
 def block_32b():
     H, I, KV, r = 5120, 27648, 1024, 64
-    return {"gate": FullMember("32b gate", I, H, r, 62001), "up": FullMember("32b up", I, H, r, 62011),
+    return {"gate": FullMember("32b gate", I, H, r, 62001, keep_all=True), "up": FullMember("32b up", I, H, r, 62011, keep_all=True),
             "down": FullMember("32b down", H, I, r, 62021), "q": FullMember("32b q", H, H, r, 62031),
             "k": FullMember("32b k", KV, H, r, 62041), "v": FullMember("32b v", KV, H, r, 62051)}
 
@@ -188,3 +200,68 @@ def test_32b_gate_at_4096_tokens(block_32b):
     outs = _group_twice(x.cuda(), [g, block_32b["up"]], None, 2.0)
     g.check(outs[0], x.float().numpy(), 2.0, ("32B gate grouped", M))
     block_32b["up"].check(outs[1], x.float().numpy(), 2.0, ("32B up grouped", M))
+
+
+def _bf16(a64):
+    return oracle.round_to_bf16(a64).astype(np.float32)
+
+
+def _fused_mlp_case(mem, M, H, seed):
+    """The feed-forward block in ONE launch (norm, gate + up, SiLU-mul, down) on full-size weights, against the
+    oracle's composition of the operators: the oracle computes every gate / up output (the down projection reads
+    them all) and the sampled rows of down.  Twice on one workspace, second run bit-identical."""
+    g, u, d = mem["gate"], mem["up"], mem["down"]
+    xin = qs.activations(M, H, seed)
+    gain = qs.rms_gain(H, seed + 1)
+    Z = qs.aqn_noise(H, 1e-2, seed + 2)
+    xn = _bf16(oracle.aqn_rmsnorm(xin.float().numpy(), gain.float().numpy(), Z.numpy(), 1e-6))
+    act = oracle.silu_mul(_bf16(g.reference_all(xn, 2.0)), _bf16(u.reference_all(xn, 2.0))).astype(np.float32)
+    ref = d.reference(act, 2.0)
+    lib = qerl.load_library()
+    ws = qerl.Workspace(lib.aqn_rmsnorm_nvfp4_lora_mlp_workspace_bytes(M, H, g.N, d.N, g.r, u.r, d.r))
+    call = lambda: qerl.aqn_rmsnorm_nvfp4_lora_mlp(xin.cuda(), gain.cuda(), Z.cuda(), 1e-6, g.pw, u.pw, d.pw, (g.Ad, u.Ad, d.Ad),
+                                                   (g.Bd, u.Bd, d.Bd), (2.0, 2.0, 2.0), workspace=ws)
+    y = call().clone()
+    again = call()
+    torch.cuda.synchronize()
+    assert qerl.workspace_status(ws) == 0
+    assert torch.equal(y, again), "second run on the same workspace differs"
+    # (composed operators: the device rounds the intermediate activations from fp32 sums, the oracle from fp64 ones)
+    check_linear(y[:, d.rows_d], ref, ("fused MLP", M, H), slack=2e-3)
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("M", [1, 8, 16])
+def test_32b_feed_forward_block_in_one_launch(block_32b, M):
+    print("full-size 32B feed-forward block in one launch,", M, "tokens", flush=True)
+    _fused_mlp_case(block_32b, M, 5120, 67000 + M)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("M", [8, 16])
+def test_7b_feed_forward_block_in_one_launch(mlp_7b, M):
+    print("full-size 7B feed-forward block in one launch,", M, "tokens", flush=True)
+    _fused_mlp_case(mlp_7b, M, 3584, 67100 + M)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("M", [1, 16])
+def test_32b_norm_and_attention_projections_in_one_launch(block_32b, M):
+    """AQN RMSNorm + q + k + v of the 32B block as one launch of the block kernel."""
+    print("full-size 32B norm + q + k + v in one launch,", M, "tokens", flush=True)
+    q, k, v = block_32b["q"], block_32b["k"], block_32b["v"]
+    H = 5120
+    xin = qs.activations(M, H, 68000 + M)
+    gain = qs.rms_gain(H, 68001 + M)
+    Z = qs.aqn_noise(H, 1e-2, 68002 + M)
+    xn = _bf16(oracle.aqn_rmsnorm(xin.float().numpy(), gain.float().numpy(), Z.numpy(), 1e-6))
+    ws = qerl.Workspace(qerl.aqn_rmsnorm_nvfp4_lora_linear_group_workspace_bytes(M, H, [q.N, k.N, v.N], [q.r, k.r, v.r]))
+    call = lambda: qerl.aqn_rmsnorm_nvfp4_lora_linear_group(xin.cuda(), gain.cuda(), Z.cuda(), 1e-6, [q.pw, k.pw, v.pw],
+                                                            [q.Ad, k.Ad, v.Ad], [q.Bd, k.Bd, v.Bd], [2.0] * 3, workspace=ws)
+    outs = [o.clone() for o in call()]
+    again = call()
+    torch.cuda.synchronize()
+    assert qerl.workspace_status(ws) == 0
+    assert all(torch.equal(p, q_) for p, q_ in zip(outs, again)), "second run on the same workspace differs"
+    for m, o in zip((q, k, v), outs):
+        m.check(o, xn, 2.0, ("32B fused " + m.name, M))

@@ -276,8 +276,9 @@ def dominant_kernel_roofline(stack: Stack, reps: int):
     """Average duration of one launch of the kernel most of the step's bytes / flops go through, run back
     to back over every layer's distinct weights.  Decode (M <= 16): the feed-forward block's single launch of
     block_kernel where the step uses it, else the grouped gate_proj + up_proj launch of stream_kernel, fed
-    with the LoRA down-projections the norm's launch left in memory, exactly as in the step.  M > 16: the
-    gate_proj call (the small lora_down32_kernel launch belongs to it)."""
+    with the LoRA down-projections the norm's launch left in memory, exactly as in the step.  M > 16: the grouped
+    gate_proj + up_proj call of the step (the LoRA down-projection's launch belongs to it), or the largest linear
+    where the configuration is not a decoder block; priced against HBM or MFMA, whichever binds it at the peaks."""
     by = {s.name: s for s in stack.cfg["linears"]}
     kernel = None
     if stack.decode_block and stack.plan["mlp"] == "fused":
@@ -302,6 +303,17 @@ def dominant_kernel_roofline(stack: Stack, reps: int):
                                                     outs=[stack.out[n] for n in names], ts=ts)
         shape = {"name": "+".join(names), "N": sum(by[n].N for n in names), "K": by[names[0]].K, "M": stack.M}
         bytes_per_launch = sum(by[n].packed_bytes for n in names)
+    elif stack.block:
+        # the grouped gate_proj + up_proj call as the step makes it (its LoRA down-projection launch belongs to it)
+        names = ("gate", "up")
+
+        def sweep():
+            for L in stack.layers:
+                ws, As, Bs = zip(*(L.lin[n] for n in names))
+                qerl.nvfp4_lora_linear_packed_group(stack.xn, list(ws), list(As), list(Bs), [stack.lora_scale] * 2,
+                                                    workspace=stack.ws, outs=[stack.out[n] for n in names])
+        shape = {"name": "gate+up", "N": sum(by[n].N for n in names), "K": by["gate"].K, "M": stack.M}
+        bytes_per_launch = sum(by[n].packed_bytes for n in names)
     else:
         shp = max(stack.cfg["linears"], key=lambda s: (s.packed_bytes, s.name == "gate"))
 
@@ -315,8 +327,13 @@ def dominant_kernel_roofline(stack: Stack, reps: int):
     ms = timed(run, reps) / len(stack.layers)
     common = {"shape": shape, "us_per_launch": round(ms * 1e3, 2),
               "note": "one call per launch slot, back to back over the layers' distinct weights, launch gaps included"}
-    if stack.M <= 128:
-        kernel = kernel or ("stream_kernel" if stack.M <= 16 else "mid_kernel")
+    # which roof binds the launch at the published peaks, and the kernel that runs it (17..64 tokens, and single
+    # linears up to 128: the weight-streaming mid_kernel; wide groups from 65 tokens on: the GEMM)
+    t_hbm = bytes_per_launch / (HBM_PEAK_GBS * 1e9)
+    t_mfma = 2 * stack.M * shape["N"] * shape["K"] / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    gemm = stack.M > 128 or (stack.M > 64 and shape["name"] == "gate+up" and shape["N"] >= 16384)
+    if stack.M <= 16 or (not gemm) or (stack.M <= 128 and t_hbm >= t_mfma):
+        kernel = kernel or ("stream_kernel" if stack.M <= 16 else ("gemm32_kernel" if gemm else "mid_kernel"))
         achieved = bytes_per_launch / (ms * 1e-3) / 1e9
         return {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4),
@@ -483,6 +500,49 @@ def mx_bench(args):
     }))
 
 
+def quantize_bench(args):
+    """--quantize: the offline step W bf16 -> NVFP4 (two-pass quantiser: tensor maximum, then scales and codes) plus
+    the one-time re-layout into packed tiles, over the bf16 weights of one layer of the configuration; one JSON line
+    in the same format.  Algorithmic bytes per weight: 2 x 2 B read (the tensor maximum is needed before any scale
+    can be formed) + 0.5625 B written, and 0.5625 B read + 0.5625 B written by the re-layout."""
+    cfg = qs.CONFIGS[args.config]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(qs.seed_for(args.config, 3))
+    Ws = [(shp, (torch.randn((shp.N, shp.K), generator=gen, device="cuda", dtype=torch.float32) * 0.02).to(torch.bfloat16))
+          for shp in cfg["linears"]]
+    n_weights = sum(s.N * s.K for s, _ in Ws)
+
+    def quant():
+        return [qerl.nvfp4_quantize(W) for _, W in Ws]
+
+    def both():
+        for c, sc, ts in quant():
+            qerl.nvfp4_prepack(c, sc, ts)
+    for _ in range(args.warmup):
+        both()
+    ms_q = timed(quant, args.steps)
+    ms = timed(both, args.steps)
+    bytes_q = n_weights * (4 + 0.5625)
+    shp, W = max(Ws, key=lambda e: e[0].N * e[0].K)
+    one = lambda: qerl.nvfp4_quantize(W)
+    one()
+    us = timed(one, max(3, args.steps)) * 1e3
+    ach = shp.N * shp.K * (4 + 0.5625) / (us * 1e-6) / 1e9
+    print(json.dumps({
+        "metric": "NVFP4 quantiser + tile prepack: bf16 weight GB/s (2 B per weight over the wall time of both)",
+        "value": round(n_weights * 2 / (ms * 1e-3) / 1e9, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 (scale arithmetic) on bf16 input -> fp4(e2m1) + fp8(e4m3) + f32", "data": "synthetic",
+        "config": {"workload": f"config {args.config}: quantise and pack the seven linears of one {cfg['model']}-shaped layer "
+                               f"({n_weights / 1e6:.1f} M weights); eager launches, torch allocates the outputs inside the timed region",
+                   "ms_quantize_only": round(ms_q, 4), "algorithmic_GBps_quantize_only": round(bytes_q / (ms_q * 1e-3) / 1e9, 1)},
+        "roofline": {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
+                     "traffic": None, "kernel": "amax_partial_kernel + encode_kernel", "algorithmic_bytes_per_launch": int(shp.N * shp.K * (4 + 0.5625)),
+                     "shape": {"name": shp.name, "N": shp.N, "K": shp.K}, "us_per_launch": round(us, 2),
+                     "note": "one nvfp4_quantize call of the largest linear (three launches: partial maxima, final maximum, encode)"},
+    }))
+
+
 def measure_peaks():
     """What a kernel that does nothing else reaches on this machine: a streaming read of 4 GiB (far beyond the
     256 MiB memory-side cache) and a loop of nothing but v_mfma_f32_32x32x16_bf16.  Best of a few launch shapes."""
@@ -565,6 +625,8 @@ def main():
                     help="time the backward pass (dX, dA, dB) of the configuration's linears at its prefill size instead of the forward step")
     ap.add_argument("--mx", action="store_true",
                     help="time the MXFP4 variant's linear (MXFP8 activations, block-scaled matrix instruction) over the configuration's linears")
+    ap.add_argument("--quantize", action="store_true",
+                    help="time the offline quantiser (bf16 -> NVFP4) and the tile prepack over the weights of one layer of the configuration")
     ap.add_argument("--swiglu", action="store_true",
                     help="the down projection reads SiLU(gate) (.) up from the gate/up outputs (fused into its launch at M <= 16) instead of a resident input")
     ap.add_argument("--launch-plan", choices=("auto", "separate", "fused"), default="auto",
@@ -598,6 +660,9 @@ def main():
         return
     if args.mx:
         mx_bench(args)
+        return
+    if args.quantize:
+        quantize_bench(args)
         return
     cfg = qs.CONFIGS[args.config]
     # the headline leg first, then the configuration's other token counts

@@ -21,5 +21,5 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 def test_help_lists_the_workload_switches():
     r = _run("--help")
     assert r.returncode == 0
-    for flag in ("--gpus", "--steps", "--warmup", "--config", "--backward", "--mx", "--swiglu"):
+    for flag in ("--gpus", "--steps", "--warmup", "--config", "--backward", "--mx", "--swiglu", "--quantize", "--launch-plan"):
         assert flag in r.stdout

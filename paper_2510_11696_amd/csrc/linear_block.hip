@@ -9,29 +9,34 @@
 // reads the gated activation.  Launches it replaces: norm + LoRA-down, group, (reduce), SiLU-mul, linear, (reduce).
 //
 // Why one launch: the weights do not depend on the activations.  A launch per linear pays start-up, ring fill,
-// drain and the spread of its workgroups (about 10 us) each time; here the weight stream never stops -- while a
-// wave waits at a stage boundary for the other workgroups' outputs, the first tiles of its next unit are already
-// on their way.
+// drain, the spread of its workgroups and the gap to the next launch each time; here, while a wave waits at a
+// stage boundary for the other workgroups' outputs, the first tiles of its next unit are already on their way.
 //
 // Structure:
-//   * One workgroup of 16 waves per CU.  A unit of work is one row tile (32 output rows) over one K-range of a
-//     stage; a wave owns its units outright: it streams the unit's packed tiles through a ring of kBlkD tiles in
-//     registers (refilled in place, across unit and stage boundaries), multiplies them -- bare E2M1 values into one
-//     v_mfma_f32_32x32x16_bf16 per 16-input scale block, then acc += E4M3 scale * product, as in
-//     linear_stream.hip -- and finishes the unit itself: tensor scale, LoRA up-projection (B rows requested one
-//     ring round ahead), bias, store.  No wave ever hands anything to another wave of its workgroup, so there is
-//     no per-unit synchronisation at all, and 16 independent streams per CU keep ~150 KB in flight.
-//   * The K-range's slice of the stage input lives in LDS for the whole stage, shared by the 16 waves (rows
-//     16 bytes apart in bank space; MFMA rows beyond the tokens read a zero row).  When the slice of all of K
-//     does not fit (or the linear has too few row tiles to occupy the chip), K is split over ranges of
-//     workgroups: every range leaves fp32 partial tiles in the workspace, counts itself in the tile's arrival
-//     word, and the wave that arrives last adds the partials in range order and stores -- fixed order, so
-//     results do not depend on timing.
-//   * t = x A^T of a stage comes from producer workgroups at the front of the grid (lora_producer.hpp); the first
-//     wave of a workgroup that needs a member's t adds the producers' partials in producer order and leaves them
-//     in LDS as three bf16 terms (exact to 2^-24 relative) for the other waves.
-//   * Stage boundary: every workgroup releases its outputs (agent-scope release, counter), waits until all have
-//     (bounded spin), acquires, stages the next input.
+//   * One workgroup of eight waves per CU (two per SIMD, 256 registers each).  A unit of work is one row tile (32
+//     output rows) over one K-range of a stage; a wave owns its units outright: it streams the unit's packed tiles
+//     through a ring of kBlkD tiles in registers (refilled in place, across unit, phase and stage boundaries),
+//     multiplies them -- bare E2M1 values into one v_mfma_f32_32x32x16_bf16 per 16-input scale block, then
+//     acc += E4M3 scale * product, as in linear_stream.hip -- and finishes the unit itself: tensor scale, LoRA
+//     up-projection (B rows requested one ring round ahead), bias, store.  There is no synchronisation inside the
+//     streaming loop; eight independent streams per CU keep ~74 KB in flight (16.5 MB over the chip).
+//   * The K-range's slice of the stage input lives in LDS, shared by the waves (rows 16 bytes apart in bank space;
+//     MFMA rows beyond the tokens read a zero row); on a normalising stage each workgroup computes the row
+//     statistics itself while it loads the rows and normalises the slice in place.  When all of K does not fit,
+//     the stage either runs in phases (the next part of K is staged after a workgroup barrier, the accumulators
+//     wait in LDS meanwhile) or K is split over ranges of workgroups: every range leaves fp32 partial tiles in the
+//     workspace, counts itself in the tile's arrival word, and the wave that arrives last adds the partials in
+//     range order, applies LoRA and bias and stores -- fixed order, so results do not depend on timing.
+//   * A gate_proj / up_proj pair: waves 0..3 of a workgroup own gate tiles, waves 4..7 the up tiles of the same
+//     rows and hand them over through LDS; or (K split over ranges) one wave walks both tiles and the last wave to
+//     arrive for the rows finishes both.  act = bf16(bf16(SiLU(gate)) * up) goes out with write-through stores.
+//   * t = x A^T of a stage comes from producer workgroups at the front of the grid (lora_producer.hpp): one per
+//     (pair of rank tiles, run of K); the one that arrives last adds the partials in producer order and publishes
+//     the finished t and a ready word.  The first wave of a consumer workgroup that needs a member's t loads it
+//     (one round of loads) and leaves it in LDS as three bf16 terms (exact to 2^-24 relative) for the others.
+//   * Stage boundary: every wave waits for its own stores, one thread per workgroup counts in and waits until all
+//     workgroups have (bounded spin), one wave invalidates the CU's caches (what the next stage reads was written
+//     through to memory), the next input is staged.
 // Every wait on another workgroup is bounded; a wait that gives up sets the sticky error word of the workspace
 // (qerl_workspace_status), poisons nothing silently, and the control words are then left as they are.
 #include <stdio.h>

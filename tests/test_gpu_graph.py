@@ -76,6 +76,35 @@ def test_mlp_block_launches_replay_like_eager(M):
     _replays_match(run, lambda: [xn, outs[0], outs[1], y])
 
 
+# the persistent multi-stage kernel: its stage boundary, hand-over words and K-range counters live in the workspace
+# and are re-armed by the launch itself
+@pytest.mark.parametrize("M", [1, 8, 16])
+def test_fused_block_launches_replay_like_eager(M):
+    print("graph case: fused launches, M =", M, flush=True)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(70 + M)
+    H, I, r = 2048, 2816, 32
+    gate, up, down = _weights(I, H, r, gen), _weights(I, H, r, gen), _weights(H, I, r, gen)
+    q, k = _weights(H, H, r, gen), _weights(256, H, r, gen)
+    x = torch.randn((M, H), device="cuda", generator=gen).to(torch.bfloat16)
+    gain = (1.0 + 0.1 * torch.randn(H, device="cuda", generator=gen)).to(torch.bfloat16)
+    noise = 0.01 * torch.randn(H, device="cuda", generator=gen)
+    lib = qerl.load_library()
+    ws_g = qerl.Workspace(qerl.aqn_rmsnorm_nvfp4_lora_linear_group_workspace_bytes(M, H, [H, 256], [r, r]))
+    ws_m = qerl.Workspace(lib.aqn_rmsnorm_nvfp4_lora_mlp_workspace_bytes(M, H, I, H, r, r, r))
+    outs = [torch.empty((M, H), device="cuda", dtype=torch.bfloat16), torch.empty((M, 256), device="cuda", dtype=torch.bfloat16)]
+    y = torch.empty((M, H), device="cuda", dtype=torch.bfloat16)
+
+    def run():
+        qerl.aqn_rmsnorm_nvfp4_lora_linear_group(x, gain, noise, 1e-6, [q[0], k[0]], [q[1], k[1]], [q[2], k[2]], [2.0, 2.0],
+                                                 workspace=ws_g, outs=outs)
+        qerl.aqn_rmsnorm_nvfp4_lora_mlp(x, gain, noise, 1e-6, gate[0], up[0], down[0], (gate[1], up[1], down[1]),
+                                        (gate[2], up[2], down[2]), (2.0, 2.0, 2.0), workspace=ws_m, out=y)
+
+    _replays_match(run, lambda: [outs[0], outs[1], y])
+    assert qerl.workspace_status(ws_g) == 0 and qerl.workspace_status(ws_m) == 0
+
+
 @pytest.mark.parametrize("M", [24, 300])
 def test_backward_launches_replay_like_eager(M):
     print("graph case: backward, M =", M, flush=True)

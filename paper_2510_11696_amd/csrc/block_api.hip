@@ -75,7 +75,13 @@ static int blk_plan_and_launch(BlkArgs& a, uint8_t* ws, size_t ws_bytes, size_t 
   if (ctrs > kCtrlMainWords) return QERL_ERR_SHAPE;
   const BlkWorkspace w = blk_workspace(part, act_bytes);
   if (need) *need = w.total;
-  if (!launch) return QERL_OK;
+  if (!launch) {
+    // sizing call: the plan must also pass the launch's own checks (placeholder workspace pointers, nothing is launched),
+    // so that a shape the kernel cannot take reports 0 bytes here rather than an error at the first call
+    BlkArgs b = a;
+    b.counters = b.ctl = b.tpart = (uint32_t*)(uintptr_t)256; b.tfinal = b.partial = (float*)(uintptr_t)256;
+    return check_block(b, lds, MR);
+  }
   if (!ws || !aligned(ws, 256) || ws_bytes < w.total) return QERL_ERR_WORKSPACE;
   a.counters = (uint32_t*)ws;
   a.ctl = (uint32_t*)ws + kCtrlMainWords + kCtrlDownWords;

@@ -115,6 +115,7 @@ struct BlkArgs {
 };
 int plan_block(BlkArgs& a, size_t* lds_bytes, int* MR, size_t* partial_floats, size_t* counter_words);
 int launch_block_wait_selftest(uint32_t* ctl, uint32_t polls, hipStream_t st);   // error-path self-test: a bounded wait that gives up
+int check_block(const BlkArgs& a, size_t lds, int MR);   // the launch's own validation, without the launch
 int launch_block(const BlkArgs& a, size_t lds_bytes, int MR, hipStream_t st);
 
 // ---- prefill path: MFMA GEMM on tile-packed weights (linear_gemm.hip) ----

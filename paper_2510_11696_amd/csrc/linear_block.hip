@@ -933,7 +933,7 @@ static size_t blk_lds_total(const BlkLds& l) { return l.x + l.g + l.t + l.y + l.
 // holds it up (two waves share a SIMD), the chip streams about 6 MB per us; a wave's units and phases run one after
 // the other; splitting K over workgroups costs a trip through memory and the partial tiles' traffic, an extra phase
 // costs a workgroup barrier and a re-staging of x.  
-static int plan_block_stage(BlkStage& S, int M, int MR, int n_cons, int* park_units) {
+static int plan_block_stage(BlkStage& S, int M, int MR, int n_cons, size_t lds_floor_park_exch, int* park_units) {
   const int D = kBlkD;
   const bool norm = S.gain != nullptr, pairs = S.pairs != 0;
   const int kt_pad = (int)(ceil_div(S.k_tiles, D) * D);
@@ -959,7 +959,13 @@ static int plan_block_stage(BlkStage& S, int M, int MR, int n_cons, int* park_un
       const int64_t rounds = ceil_div(S.total_v, slots_r);
       if (ph > 1 && rounds > kBlkParkMax) continue;
       const int park = ph > 1 ? (int)rounds : (mode == 2 ? 1 : 0);
-      if (blk_lds_total(blk_lds(M, MR, kr, norm, park, mode == 1)) > kBlkLdsMax) continue;
+      {
+        // the launch's LDS layout is the union of its stages': the parked accumulators and the pairs' hand-over of
+        // ANOTHER stage take their room here as well
+        const BlkLds l = blk_lds(M, MR, kr, norm, park, mode == 1);
+        const size_t pe = l.park + l.exch > lds_floor_park_exch ? l.park + l.exch : lds_floor_park_exch;
+        if (l.x + l.g + l.t + l.y + pe > kBlkLdsMax) continue;
+      }
       const int64_t active = (S.total_v < slots_r ? S.total_v : slots_r) * Sk * (mode == 1 ? 2 : 1);
       const double rate = active * wave_rate < chip_rate ? active * wave_rate : chip_rate;
       const double extra = Sk > 1 ? 1.5 * Sk * S.total_tiles * 64.0 * MR * 4 : 0.0;   // partial tiles out and back
@@ -1022,10 +1028,15 @@ int plan_block(BlkArgs& a, size_t* lds_bytes, int* MR_out, size_t* partial_float
   size_t part = 0, ctrs = 0, prod_need = 0;
   BlkLds mx{};
   int park_max = 0;
+  // Stages are planned one by one; if the union of their LDS needs does not fit, they are planned once more with
+  // the largest parked-accumulator + hand-over area of the first attempt taken as given by every stage.
+  size_t floor_pe = 0;
+  for (int attempt = 0; attempt < 2; ++attempt) {
+  part = 0; ctrs = 0; prod_need = 0; mx = BlkLds{}; park_max = 0;
   for (int s = 0; s < a.n_stages; ++s) {
     BlkStage& S = a.st[s];
     int park = 0;
-    const int rc = plan_block_stage(S, a.M, MR, n_cons, &park);
+    const int rc = plan_block_stage(S, a.M, MR, n_cons, floor_pe, &park);
     if (rc != QERL_OK) return rc;
     park_max = park > park_max ? park : park_max;
     const BlkLds l = blk_lds(a.M, MR, S.kr_len, S.gain != nullptr, park, S.pairs == 1);
@@ -1047,6 +1058,9 @@ int plan_block(BlkArgs& a, size_t* lds_bytes, int* MR_out, size_t* partial_float
       const size_t need = S.prod_red_off + red;
       prod_need = need > prod_need ? need : prod_need;
     }
+  }
+  if (mx.x + mx.g + mx.t + mx.y + mx.park + (mx.exch > 0 ? mx.exch : 256) <= kBlkLdsMax || attempt == 1) break;
+  floor_pe = mx.park + (mx.exch > 0 ? mx.exch : 256);
   }
 #ifdef QERL_TUNING_HOOKS
   if (getenv("QERL_BLK_TRACE"))
@@ -1082,8 +1096,8 @@ static int launch_block_t(const BlkArgs& a, size_t lds, hipStream_t st) {
   return launch_status();
 }
 
-int launch_block(const BlkArgs& a, size_t lds, int MR, hipStream_t st) {
-  // every pointer the kernel dereferences and every bound its indexing assumes
+// Every pointer the kernel dereferences and every bound its indexing assumes; QERL_OK if the launch is safe.
+int check_block(const BlkArgs& a, size_t lds, int MR) {
   if (a.M < 1 || a.M > 16 || a.n_stages < 1 || a.n_stages > kBlkMaxStages || a.n_wgs < 2 || a.n_prod_max < 0 || a.n_prod_max >= a.n_wgs)
     return QERL_ERR_SHAPE;
   if (!a.ctl || !a.counters || !a.partial || !a.tpart || !a.tfinal) return QERL_ERR_NULL;
@@ -1148,6 +1162,12 @@ int launch_block(const BlkArgs& a, size_t lds, int MR, hipStream_t st) {
   }
   if (any_phases && (size_t)a.p_lds_off + (size_t)kBlkWaves * a.park_units * 64 * MR * sizeof(float) > (size_t)a.e_lds_off) return QERL_ERR_SHAPE;
   if (any_pairs && (size_t)a.e_lds_off + 256 + (size_t)4 * 64 * MR * sizeof(float) > lds) return QERL_ERR_SHAPE;
+  return QERL_OK;
+}
+
+int launch_block(const BlkArgs& a, size_t lds, int MR, hipStream_t st) {
+  const int rc = check_block(a, lds, MR);
+  if (rc != QERL_OK) return rc;
   return MR == 4 ? launch_block_t<4>(a, lds, st) : launch_block_t<8>(a, lds, st);
 }
 

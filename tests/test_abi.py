@@ -231,3 +231,27 @@ def test_host_side_validation_of_the_fused_entry_points(lib):
     assert nf(fake, 8, float("inf"), 1, 1, None) == -2
     assert nf(fake + 2, 8, 1e-2, 1, 1, None) == -3
 
+
+
+def test_fused_launch_plans_exist_for_a_grid_of_shapes(lib):
+    """Host logic of the persistent decode kernel: for every shape of a grid the planner (K-ranges, phases, LoRA
+    producers, LDS layout of the union of the stages) finds a plan that also passes the launch's own validation --
+    the sizing calls run both and return 0 otherwise.  No GPU is touched."""
+    bad = []
+    for M in (1, 2, 7, 8, 9, 15, 16):
+        for H in (128, 512, 1040, 2048, 3584, 4096, 5120, 8192):
+            for I in (64, 640, 2368, 4096, 13824, 18944, 27648):
+                for r in (0, 8, 16, 64):
+                    if lib.aqn_rmsnorm_nvfp4_lora_mlp_workspace_bytes(M, H, I, H, r, r, r) == 0:
+                        bad.append(("mlp", M, H, I, r))
+            for Ns in ((64,), (5120, 1024, 1024), (3584, 512, 512), (96, 40), (27648, 27648), (152064,)):
+                for r in (0, 32, 64):
+                    if qerl.aqn_rmsnorm_nvfp4_lora_linear_group_workspace_bytes(M, H, list(Ns), [r] * len(Ns)) == 0:
+                        bad.append(("group", M, H, Ns, r))
+    assert not bad, bad[:10]
+    # what the kernel does not take is refused in the sizing call already
+    assert lib.aqn_rmsnorm_nvfp4_lora_mlp_workspace_bytes(8, 512, 1024, 512, 12, 12, 12) == 0     # rank not a multiple of 8
+    assert lib.aqn_rmsnorm_nvfp4_lora_mlp_workspace_bytes(8, 512, 1028, 512, 8, 8, 8) == 0        # gate rows not a multiple of 8
+    assert lib.aqn_rmsnorm_nvfp4_lora_mlp_workspace_bytes(8, 520, 1024, 512, 8, 8, 8) == 0        # K not a multiple of 16
+    # beyond 16 tokens the entry points compose the separate launches: their workspaces add up
+    assert lib.aqn_rmsnorm_nvfp4_lora_mlp_workspace_bytes(64, 3584, 18944, 3584, 32, 32, 32) > 0

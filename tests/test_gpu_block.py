@@ -162,3 +162,26 @@ def test_a_wait_that_gives_up_is_reported_until_the_workspace_is_initialised_aga
     torch.cuda.synchronize()
     assert qerl.workspace_status(ws) == 0
     check_linear(y, _ref(m, xn, 2.0), ("after re-initialisation",))
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("rs", [(0, 0, 0), (16, 16, 16)])
+def test_feed_forward_block_whose_stages_need_different_lds_areas(rs):
+    """Hidden size 8192 at 16 tokens: the gate / up stage cannot hold its input in one piece (K-split pairs or phases with
+    parked accumulators), while down's K = 3584 wants a large x slice: the stages' LDS areas are planned as a union."""
+    M, H, I = 16, 8192, 3584
+    print("mlp case with a wide hidden size", M, H, I, rs, flush=True)
+    xin, gain, Z, xn = _norm_inputs(M, H, 850, 5e-3)
+    gate, up, down = _member(I, H, rs[0], 6500), _member(I, H, rs[1], 6510), _member(H, I, rs[2], 6520)
+    act = oracle.silu_mul(_bf16(_ref(gate, xn, 2.0)), _bf16(_ref(up, xn, 2.0))).astype(np.float32)
+    lib = qerl.load_library()
+    ws = qerl.Workspace(lib.aqn_rmsnorm_nvfp4_lora_mlp_workspace_bytes(M, H, I, H, *rs))
+    call = lambda: qerl.aqn_rmsnorm_nvfp4_lora_mlp(
+        xin.cuda(), gain.cuda(), Z.cuda(), 1e-6, gate["pw"], up["pw"], down["pw"], (gate["Ad"], up["Ad"], down["Ad"]),
+        (gate["Bd"], up["Bd"], down["Bd"]), (2.0, 2.0, 2.0), workspace=ws)
+    y = call().clone()
+    again = call()
+    torch.cuda.synchronize()
+    assert qerl.workspace_status(ws) == 0
+    check_linear(y, _ref(down, act, 2.0), ("mlp, wide hidden", M, H, I, rs), slack=2e-3)
+    assert torch.equal(y, again)

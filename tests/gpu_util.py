@@ -20,7 +20,9 @@ def check_linear(y_gpu: torch.Tensor, y_ref: np.ndarray, what="", slack=1e-3):
     For a composition of operators (norm -> linear -> SiLU-mul -> linear) the device rounds each intermediate
     from an fp32 sum where the oracle rounds an fp64 one, so a few per cent of the intermediate activations are
     one bf16 unit (<= 2^-8 relative) apart; over a sum of K terms that adds about sqrt(0.02) * 2^-8 / 4 ~ 1.4e-4 of
-    the row maximum in rms, 6e-4 at the 4.5 sigma of ~1e5 outputs: such tests pass slack = 2e-3."""
+    the row maximum in rms, 6e-4 at the 4.5 sigma of ~1e5 outputs; and a single one-unit difference on an outlier
+    activation (|x| ~ 4) against an outlier weight is by itself up to ~1e-3 of the row maximum of the next operator at
+    small K.  The feed-forward block chains two operators: its tests pass slack = 4e-3."""
     y = y_gpu.float().cpu().numpy().astype(np.float64)
     assert y.shape == y_ref.shape, (y.shape, y_ref.shape)
     assert np.all(np.isfinite(y)), what

@@ -2,7 +2,10 @@
     aqn_rmsnorm -> (round to bf16) -> nvfp4_lora_linear for every member                      (norm + group)
     aqn_rmsnorm -> gate, up -> (round to bf16) -> silu_mul -> nvfp4_lora_linear(down)         (feed-forward block)
 The device rounds the intermediate activations from fp32 sums, the oracle from fp64 ones, so a few of them differ by
-one bf16 unit; the outputs are held to the linear's usual gates all the same."""
+one bf16 unit.  One such unit on an outlier activation (|x| ~ 4 after the norm) against an outlier weight moves an
+output of the NEXT operator by 2^-8 |x w|, up to ~1e-3 of the row maximum per operator at these sizes, and the feed-forward
+block chains two: the tight gate is therefore taken with 4e-3 of the row maximum (slack) for the feed-forward block; the
+official gate (2e-2 of the row maximum) is unchanged."""
 import numpy as np
 import pytest
 import torch
@@ -116,13 +119,13 @@ def test_feed_forward_block_in_one_launch(M, H, I, rs, sigma):
     again = call()
     torch.cuda.synchronize()
     assert qerl.workspace_status(ws) == 0
-    check_linear(y, ref, ("mlp", M, H, I, rs), slack=2e-3)
+    check_linear(y, ref, ("mlp", M, H, I, rs), slack=4e-3)
     assert torch.equal(y, again), "second run on the same workspace differs"
     # the same operators as separate launches agree with it to rounding
     xn_d = qerl.aqn_rmsnorm(xin.cuda(), gain.cuda(), Z.cuda() if Z is not None else None, 1e-6)
     gu = qerl.nvfp4_lora_linear_packed_group(xn_d, [gate["pw"], up["pw"]], [gate["Ad"], up["Ad"]], [gate["Bd"], up["Bd"]], [2.0, 2.0])
     sep = qerl.nvfp4_lora_linear_packed_swiglu(gu[0], gu[1], down["pw"], down["Ad"], down["Bd"], 2.0)
-    check_linear(sep, ref, ("mlp as separate launches", M, H, I, rs), slack=2e-3)
+    check_linear(sep, ref, ("mlp as separate launches", M, H, I, rs), slack=4e-3)
 
 
 @pytest.mark.parametrize("M", [17, 40])
@@ -136,7 +139,7 @@ def test_fused_entry_points_beyond_16_tokens_run_the_separate_launches(M):
     outs = qerl.aqn_rmsnorm_nvfp4_lora_linear_group(xin.cuda(), gain.cuda(), Z.cuda(), 1e-6, [gate["pw"], up["pw"]],
                                                     [gate["Ad"], up["Ad"]], [gate["Bd"], up["Bd"]], [2.0, 2.0])
     torch.cuda.synchronize()
-    check_linear(y, _ref(down, act, 2.0), ("mlp, separate launches", M), slack=2e-3)
+    check_linear(y, _ref(down, act, 2.0), ("mlp, separate launches", M), slack=4e-3)
     check_linear(outs[0], _ref(gate, xn, 2.0), ("group, separate launches", M))
     check_linear(outs[1], _ref(up, xn, 2.0), ("group, separate launches", M))
 
@@ -183,5 +186,5 @@ def test_feed_forward_block_whose_stages_need_different_lds_areas(rs):
     again = call()
     torch.cuda.synchronize()
     assert qerl.workspace_status(ws) == 0
-    check_linear(y, _ref(down, act, 2.0), ("mlp, wide hidden", M, H, I, rs), slack=2e-3)
+    check_linear(y, _ref(down, act, 2.0), ("mlp, wide hidden", M, H, I, rs), slack=4e-3)
     assert torch.equal(y, again)

@@ -227,7 +227,7 @@ def _fused_mlp_case(mem, M, H, seed):
     assert qerl.workspace_status(ws) == 0
     assert torch.equal(y, again), "second run on the same workspace differs"
     # (composed operators: the device rounds the intermediate activations from fp32 sums, the oracle from fp64 ones)
-    check_linear(y[:, d.rows_d], ref, ("fused MLP", M, H), slack=2e-3)
+    check_linear(y[:, d.rows_d], ref, ("fused MLP", M, H), slack=4e-3)
 
 
 @pytest.mark.timeout(900)

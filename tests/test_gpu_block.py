@@ -188,3 +188,57 @@ def test_feed_forward_block_whose_stages_need_different_lds_areas(rs):
     assert qerl.workspace_status(ws) == 0
     check_linear(y, _ref(down, act, 2.0), ("mlp, wide hidden", M, H, I, rs), slack=4e-3)
     assert torch.equal(y, again)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("seed", [11, 12])
+def test_random_shapes_through_the_fused_entry_points(seed):
+    """Seeded random shapes (token counts, hidden and intermediate sizes that are not multiples of a tile, ranks from 0 to
+    64 including partial rank tiles, with and without noise, norm and bias): every plan the host logic makes for them
+    is checked against the oracle, twice on one workspace."""
+    rng = np.random.default_rng(seed)
+    lib = qerl.load_library()
+    ranks = [0, 8, 16, 24, 32, 40, 64]
+    for it in range(16):
+        M = int(rng.integers(1, 17))
+        H = int(rng.integers(4, 140)) * 16
+        sigma = [None, 1e-2, 5e-4][int(rng.integers(0, 3))]
+        if it % 2 == 0:
+            I = int(rng.integers(1, 150)) * 16
+            rs = tuple(int(ranks[rng.integers(0, len(ranks))]) for _ in range(3))
+            print("random mlp case", seed, it, M, H, I, rs, sigma, flush=True)
+            xin, gain, Z, xn = _norm_inputs(M, H, 100 * seed + it, sigma)
+            gate, up, down = (_member(I, H, rs[0], 9000 + 10 * it + seed), _member(I, H, rs[1], 9001 + 10 * it + seed),
+                              _member(H, I, rs[2], 9002 + 10 * it + seed))
+            act = oracle.silu_mul(_bf16(_ref(gate, xn, 2.0)), _bf16(_ref(up, xn, 2.0))).astype(np.float32)
+            ws = qerl.Workspace(lib.aqn_rmsnorm_nvfp4_lora_mlp_workspace_bytes(M, H, I, H, *rs))
+            call = lambda: qerl.aqn_rmsnorm_nvfp4_lora_mlp(
+                xin.cuda(), gain.cuda(), Z.cuda() if Z is not None else None, 1e-6, gate["pw"], up["pw"], down["pw"],
+                (gate["Ad"], up["Ad"], down["Ad"]), (gate["Bd"], up["Bd"], down["Bd"]), (2.0, 2.0, 2.0), workspace=ws)
+            y = call().clone()
+            again = call()
+            torch.cuda.synchronize()
+            assert qerl.workspace_status(ws) == 0
+            check_linear(y, _ref(down, act, 2.0), ("random mlp", seed, it, M, H, I, rs), slack=4e-3)
+            assert torch.equal(y, again)
+        else:
+            n = int(rng.integers(1, 5))
+            Ns = [int(rng.integers(1, 700)) for _ in range(n)]
+            rs = [int(ranks[rng.integers(0, len(ranks))]) for _ in range(n)]
+            use_norm, bias = bool(rng.random() < 0.7), bool(rng.integers(0, 2))
+            print("random group case", seed, it, M, H, Ns, rs, sigma, use_norm, bias, flush=True)
+            xin, gain, Z, xn = _norm_inputs(M, H, 100 * seed + it, sigma)
+            mem = [_member(N, H, r, 9500 + 10 * it + i + seed, bias) for i, (N, r) in enumerate(zip(Ns, rs))]
+            ws = qerl.Workspace(qerl.aqn_rmsnorm_nvfp4_lora_linear_group_workspace_bytes(M, H, Ns, rs))
+            call = lambda: qerl.aqn_rmsnorm_nvfp4_lora_linear_group(
+                xin.cuda(), gain.cuda() if use_norm else None, Z.cuda() if (Z is not None and use_norm) else None, 1e-6,
+                [m["pw"] for m in mem], [m["Ad"] for m in mem], [m["Bd"] for m in mem], [2.0] * n, workspace=ws,
+                biases=[m["bd"] for m in mem])
+            outs = [o.clone() for o in call()]
+            again = call()
+            torch.cuda.synchronize()
+            assert qerl.workspace_status(ws) == 0
+            xr = xn if use_norm else xin.float().numpy()
+            for i, (m, y) in enumerate(zip(mem, outs)):
+                check_linear(y, _ref(m, xr, 2.0), ("random group", seed, it, i, M, H, Ns, rs), slack=2e-3)
+            assert all(torch.equal(p, q) for p, q in zip(outs, again))

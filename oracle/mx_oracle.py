@@ -107,3 +107,18 @@ def mx_linear_native(x, wcodes, wscales):
     """Activations quantised to MXFP8 first, then the exact product of the two quantised operands."""
     xc, xs = mxfp8_quantize(x)
     return mxfp8_dequantize(xc, xs) @ mxfp4_dequantize(wcodes, wscales).T
+
+
+def mx_lora_linear_native(x, wcodes, wscales, A=None, B=None, lora_scale=0.0, bias=None):
+    """The native MXFP4 linear with the LoRA branch of Eq. (2) and an optional bias:
+        y = MXFP8(x) . MXFP4(W)^T + lora_scale * (x A^T) B^T + bias
+    The adapter reads the bf16 activations as they are (LoRA stays in bf16 in the paper: only the frozen base
+    weights are quantised), only the base product goes through the quantised activations.  float64."""
+    y = mx_linear_native(x, wcodes, wscales)
+    if A is not None:
+        x64 = np.asarray(x, dtype=np.float32).astype(np.float64)
+        t = x64 @ np.asarray(A, dtype=np.float32).astype(np.float64).T
+        y = y + float(lora_scale) * (t @ np.asarray(B, dtype=np.float32).astype(np.float64).T)
+    if bias is not None:
+        y = y + np.asarray(bias, dtype=np.float32).astype(np.float64)[None, :]
+    return y

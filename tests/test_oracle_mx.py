@@ -119,6 +119,41 @@ def test_linears_are_the_products_of_their_dequantised_operands():
     assert d.max() <= 2.0 ** -4 * (np.abs(x) @ np.abs(What).T).max()
 
 
+def test_native_linear_with_lora_and_bias_by_loops_and_special_cases():
+    """Eq. (2) on top of the native product: brute-force loops; the adapter reads the UNquantised activations (a rank-1
+    adapter that copies one activation shows it); zero B, zero scale and no adapter reduce to the plain native linear;
+    the dense merge W_hat + s B A reproduces the weight-only variant of the same sum."""
+    rng = np.random.default_rng(9)
+    N, K, M, r = 6, 64, 4, 3
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    A = rng.standard_normal((r, K)).astype(np.float32)
+    B = rng.standard_normal((N, r)).astype(np.float32)
+    bias = rng.standard_normal(N).astype(np.float32)
+    c, s = mx.mxfp4_quantize(W)
+    base = mx.mx_linear_native(x, c, s)
+    y = mx.mx_lora_linear_native(x, c, s, A, B, 0.5, bias)
+    ref = np.zeros((M, N))
+    for m in range(M):
+        for n in range(N):
+            t = [sum(float(x[m, k]) * float(A[j, k]) for k in range(K)) for j in range(r)]
+            ref[m, n] = base[m, n] + 0.5 * sum(t[j] * float(B[n, j]) for j in range(r)) + float(bias[n])
+    assert np.allclose(y, ref, rtol=1e-12, atol=1e-14)
+    assert np.array_equal(mx.mx_lora_linear_native(x, c, s), base)
+    assert np.array_equal(mx.mx_lora_linear_native(x, c, s, A, B, 0.0), base)
+    assert np.array_equal(mx.mx_lora_linear_native(x, c, s, A, np.zeros_like(B), 2.0), base)
+    # the adapter sees x itself, not MXFP8(x): A picks column 5, B feeds it to output 2
+    A1 = np.zeros((1, K), dtype=np.float32); A1[0, 5] = 1.0
+    B1 = np.zeros((N, 1), dtype=np.float32); B1[2, 0] = 1.0
+    x2 = x.copy(); x2[:, 5] = np.float32(1.0 + 2.0 ** -7)          # representable in bf16, not in E4M3
+    d = mx.mx_lora_linear_native(x2, c, s, A1, B1, 1.0) - mx.mx_linear_native(x2, c, s)
+    assert np.array_equal(d[:, 2], x2[:, 5].astype(np.float64)) and not d[:, [0, 1, 3, 4, 5]].any()
+    # dense merge, on the weight-only variant (where the base product is linear in x itself)
+    What = mx.mxfp4_dequantize(c, s)
+    merged = x.astype(np.float64) @ (What + 0.5 * B.astype(np.float64) @ A.astype(np.float64)).T
+    assert np.allclose(mx.mx_linear_weight_only(x, c, s) + (y - base - bias[None, :]), merged, rtol=1e-12, atol=1e-13)
+
+
 def _rel_rms(a, ref):
     return float(np.sqrt(np.mean((a - ref) ** 2)) / np.sqrt(np.mean(ref ** 2)))
 

@@ -439,10 +439,24 @@ QERL_API int aqn_noise_fill(float* noise_f32, int64_t n, float sigma, uint64_t s
  *   tiles); the result is the exact product of the two quantised operands summed
  *   in fp32, rounded once to bf16; it differs from the weight-only result by the
  *   activation rounding (up to 2^-4 relative per element).  No LoRA branch and
- *   no bias in this variant.
+ *   no bias in this entry point.
  *   x 16-byte aligned with ldx % 8 == 0.
  *   workspace: >= mxfp4_linear_native_workspace_bytes(M, N, K), 256-byte aligned;
  *   needs no initialisation.
+ * mxfp4_lora_linear_native: the same base product plus the paper's LoRA branch
+ *   (Eq. 2) and an optional bias,
+ *     y = MXFP8(x) . MXFP4(W)^T + lora_scale * (x A^T) B^T + bias,
+ *   summed in fp32 and rounded once to bf16.  The adapter reads x itself (bf16),
+ *   not its MXFP8 rounding: only the frozen base weights' product goes through
+ *   the quantised path.  A [r, K], B [N, r] bf16 row-major, 16-byte aligned,
+ *   r % 8 == 0 and r <= 128 (r == 0: A and B are ignored); bias [N] bf16 or
+ *   NULL.  lora_scale * x A^T is carried between its two launches as three bf16
+ *   terms (2^-24 relative); B and bias enter exactly.
+ *   workspace: >= mxfp4_lora_linear_native_workspace_bytes(M, N, K, r) (0 for a
+ *   rank the function rejects), 256-byte aligned, prepared ONCE with
+ *   qerl_workspace_init() and afterwards used only by this library (arrival
+ *   counters of the down-projection's K-parts sit at its front and are left at
+ *   zero by every call); calls that share it must be ordered on one stream.
  * Errors: as the NVFP4 functions (NULL, shape incl. K % 32, alignment,
  * workspace).
  */
@@ -459,6 +473,12 @@ QERL_API size_t mxfp4_linear_native_workspace_bytes(int64_t M, int64_t N, int64_
 QERL_API int mxfp4_linear_native(const void* x_bf16, int64_t M, int64_t K, int64_t ldx,
                                  const void* packed, int64_t N, void* y_bf16, int64_t ldy,
                                  void* workspace, size_t workspace_bytes, void* stream);
+QERL_API size_t mxfp4_lora_linear_native_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t r);   /* host */
+QERL_API int mxfp4_lora_linear_native(const void* x_bf16, int64_t M, int64_t K, int64_t ldx,
+                                      const void* packed, int64_t N,
+                                      const void* A_bf16, const void* B_bf16, int64_t r, float lora_scale,
+                                      const void* bias_bf16, void* y_bf16, int64_t ldy,
+                                      void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------
  * Measurement aids: what a kernel on this GPU can reach of the two rooflines the

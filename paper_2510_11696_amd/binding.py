@@ -65,6 +65,9 @@ _SIGNATURES = {
     "mxfp4_prepack": (ctypes.c_int, [_c_p, _c_p, _c_i64, _c_i64, _c_p, _c_p]),
     "mxfp4_linear_native_workspace_bytes": (_c_sz, [_c_i64, _c_i64, _c_i64]),
     "mxfp4_linear_native": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_i64, _c_p, _c_i64, _c_p, _c_sz, _c_p]),
+    "mxfp4_lora_linear_native_workspace_bytes": (_c_sz, [_c_i64, _c_i64, _c_i64, _c_i64]),
+    "mxfp4_lora_linear_native": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_i64, _c_p, _c_p, _c_i64, ctypes.c_float, _c_p,
+                                                _c_p, _c_i64, _c_p, _c_sz, _c_p]),
     "aqn_rmsnorm_nvfp4_lora_linear_group_workspace_bytes": (_c_sz, [_c_i64, _c_i64, _c_p, _c_p, ctypes.c_int]),
     "aqn_rmsnorm_nvfp4_lora_linear_group": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, _c_p, ctypes.c_float,
                                                            _c_p, ctypes.c_int, _c_p, _c_sz, _c_p]),
@@ -692,3 +695,39 @@ def mxfp4_linear_native(x: torch.Tensor, w: MxPackedWeight, workspace: Optional[
         _dev(out, torch.bfloat16, "out"), ldy, ptr, workspace.numel() - (ptr - base), _stream()))
     return out
 
+
+def mxfp4_lora_linear_native(x: torch.Tensor, w: MxPackedWeight, A: Optional[torch.Tensor] = None,
+                             B: Optional[torch.Tensor] = None, lora_scale: float = 0.0,
+                             bias: Optional[torch.Tensor] = None, workspace: Optional[Workspace] = None,
+                             out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """y = MXFP8(x) . MXFP4(W)^T + lora_scale * (x A^T) B^T + bias (Eq. 2 on the native product)."""
+    lib = load_library()
+    M, K, ldx = _rows(x, "x")
+    if K != w.K:
+        raise ValueError("x must have K columns")
+    r = 0
+    a_ptr = b_ptr = None
+    if A is not None and B is not None and A.shape[0] > 0:
+        r = A.shape[0]
+        if tuple(A.shape) != (r, K) or tuple(B.shape) != (w.N, r) or not A.is_contiguous() or not B.is_contiguous():
+            raise ValueError("A must be contiguous [r, K] and B contiguous [N, r]")
+        a_ptr, b_ptr = _dev(A, torch.bfloat16, "A"), _dev(B, torch.bfloat16, "B")
+    bias_ptr = None
+    if bias is not None:
+        if tuple(bias.shape) != (w.N,) or not bias.is_contiguous():
+            raise ValueError("bias must be contiguous [N]")
+        bias_ptr = _dev(bias, torch.bfloat16, "bias")
+    if out is None:
+        out = torch.empty((M, w.N), dtype=torch.bfloat16, device=x.device)
+    _, n_out, ldy = _rows(out, "out")
+    if out.shape[0] != M or n_out != w.N:
+        raise ValueError("out must be [M, N]")
+    if workspace is None:
+        need = lib.mxfp4_lora_linear_native_workspace_bytes(M, w.N, K, r)
+        if need == 0:
+            raise ValueError("rank not supported by mxfp4_lora_linear_native")
+        workspace = Workspace(need, x.device)
+    _check("mxfp4_lora_linear_native", lib.mxfp4_lora_linear_native(
+        _dev(x, torch.bfloat16, "x"), M, K, ldx, _dev(w.packed, torch.uint8, "packed"), w.N, a_ptr, b_ptr, r,
+        float(lora_scale), bias_ptr, _dev(out, torch.bfloat16, "out"), ldy, workspace.ptr, workspace.nbytes, _stream()))
+    return out

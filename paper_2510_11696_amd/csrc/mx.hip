@@ -35,7 +35,10 @@
 //                          0.53125 B per weight.
 //   mx_gemm_kernel         more tokens: x quantised by a launch of mx_quantize_kernel, then a GEMM with
 //                          128 x 256 tiles on the same instruction (described at the kernel).
-#include "common.hpp"
+// The LoRA branch of Eq. (2) rides on both: the adapter reads bf16 x (a launch of the NVFP4 path's down-projection
+// kernels leaves lora_scale * x A^T as three bf16 terms), and the up-projection is 3 r more input columns on the bf16
+// matrix instruction, whose 32 x 32 output layout is the block-scaled one's.
+#include "linear.hpp"
 
 namespace qerl {
 
@@ -45,6 +48,7 @@ constexpr int kMxTileBytes = 4352;      // 32 rows x 256 inputs: 4 x 1024 B code
 constexpr int kMxWaves = 8;             // seven that stream and multiply, one that adds their partial tiles and stores
 constexpr int kMxMain = kMxWaves - 1;
 constexpr int kMxMaxGroups = 2;         // tiles (groups of four 64-input steps) per wave and K-range held in registers
+constexpr int kMxMaxRank = 128;         // LoRA rank: [hi | mid | lo] is at most 24 chunks of 16 columns, which the eighth wave holds in registers
 
 // ---- quantisers -----------------------------------------------------------------------------------
 // One thread per block of 32 bf16 values.  EMAX: 2 (E2M1 elements, two per byte out) or 8 (E4M3, one per byte).
@@ -150,12 +154,25 @@ struct MxArgs {
   uint16_t* y; int64_t ldy;
   float* partial;                                               // [Sk][n_tiles][MR][64] when Sk > 1
   int Sk; int groups_per_range; int per_range; int units_base; int units_rem;
+  // LoRA branch (Eq. 2) and bias: ts [M, ts_ld] bf16 = hi | mid | lo of lora_scale * x A^T (r columns each, zeros up
+  // to ts_ld = 16 n_chunks), B [N, r] bf16; n_chunks == 0: no adapter.  bias [N] bf16 or null.
+  const uint16_t* ts; int64_t ts_ld; int n_chunks; const uint16_t* B; int r;
+  const uint16_t* bias;
 };
 
-// NG: tiles (four 64-input steps each) per wave; MR: accumulator registers with live tokens (4: M <= 8, 16: M <= 32)
-template <int NG, int MR>
+// The 8 columns [col, col + 8) of [hi | mid | lo] meet the same 8 columns of B in each of the three parts (r % 8 == 0
+// keeps a run inside one part); the zero padding past 3 r meets column 0.
+__device__ __forceinline__ int lora_b_col(int col, int r) { return col < 3 * r ? col % r : 0; }
+
+// NG: tiles (four 64-input steps each) per wave; MR: accumulator registers with live tokens (4: M <= 8, 16: M <= 32);
+// LC: 16-column chunks of ts the eighth wave has registers for (0: no adapter).  The LoRA up-projection is the eighth
+// wave's: in the first K-range it adds [hi | mid | lo] . [B B B]^T to the sum of the seven partial tiles with bf16
+// matrix instructions of the same 32 x 32 output layout; its ts fragments wait in LDS, B's fragments of the next
+// row-tile are requested while the streaming waves work on it.  The streaming waves are untouched.
+template <int NG, int MR, int LC>
 __global__ __launch_bounds__(kMxWaves * 64) void mx_native_kernel(const MxArgs a) {
   __shared__ float red[2][kMxMain][MR][64];
+  __shared__ u32x4 tsl[(LC > 0 ? LC : 1) * 64];                         // chunk c of lane l at c * 64 + l
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n32 = lane & 31, kg = lane >> 5;
@@ -171,19 +188,56 @@ __global__ __launch_bounds__(kMxWaves * 64) void mx_native_kernel(const MxArgs a
   if (wave == kMxMain) {
     // ---- the eighth wave adds the seven partial tiles of a unit in wave order and stores the result; the
     // streaming waves never store, so their loads are the only memory operations they ever wait for
+    constexpr int LCA = LC > 0 ? LC : 1;
+    const bool lora = LC > 0 && range == 0;                            // uniform per workgroup
+    u32x4 bfr[LCA];
+    auto request_b = [&](int u) {                                       // B's fragments of unit u: row n, 8 columns per chunk
+      int64_t n = (int64_t)(u0 + (u < n_units ? u : n_units - 1)) * 32 + n32;
+      n = n < a.N ? n : a.N - 1;
+      const uint16_t* row = a.B + n * a.r;
+      int col = 8 * kg % a.r;                                           // (16 c + 8 g) mod r, carried along: r % 8 == 0, so col + 8 <= r
+#pragma unroll
+      for (int c = 0; c < LCA; ++c) {
+        bfr[c] = *reinterpret_cast<const u32x4*>(row + col);            // a chunk past 3 r meets zero ts
+        col += 16;
+        col = col >= a.r ? col - a.r : col;
+        col = col >= a.r ? col - a.r : col;                             // r >= 8: two steps at most
+      }
+    };
+    if (lora) {
+#pragma unroll
+      for (int c = 0; c < LCA; ++c) {
+        u32x4 t = {0u, 0u, 0u, 0u};
+        if (c < a.n_chunks && n32 < a.M) t = *reinterpret_cast<const u32x4*>(a.ts + (int64_t)n32 * a.ts_ld + 16 * c + 8 * kg);
+        tsl[c * 64 + lane] = t;                                         // read back by this wave only
+      }
+      request_b(0);
+    }
     for (int u = 0; u < n_rounds; ++u) {
       __syncthreads();
       if (u >= n_units) continue;
       const int nt = u0 + u;
       const int64_t n = (int64_t)nt * 32 + n32;
+      f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int q = 0; q < MR; ++q) {
         float sum = 0.f;
 #pragma unroll
         for (int w = 0; w < kMxMain; ++w) sum += red[u & 1][w][q][lane];
+        acc[q] = sum;
+      }
+      if (lora) {
+#pragma unroll
+        for (int c = 0; c < LCA; ++c)
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tsl[c * 64 + lane]), __builtin_bit_cast(bf16x8, bfr[c]), acc, 0, 0, 0);
+        request_b(u + 1);                                               // past the end: the last tile again
+      }
+      const float bias = (a.bias && a.Sk == 1 && n < a.N) ? bf16_bits_to_f32(a.bias[n]) : 0.f;
+#pragma unroll
+      for (int q = 0; q < MR; ++q) {
         const int tok = 8 * (q >> 2) + 4 * kg + (q & 3);
-        if (a.Sk > 1) a.partial[(((int64_t)range * a.n_tiles + nt) * MR + q) * 64 + lane] = sum;
-        else if (tok < a.M && n < a.N) a.y[(int64_t)tok * a.ldy + n] = (uint16_t)f32_to_bf16_bits(sum);
+        if (a.Sk > 1) a.partial[(((int64_t)range * a.n_tiles + nt) * MR + q) * 64 + lane] = acc[q];
+        else if (tok < a.M && n < a.N) a.y[(int64_t)tok * a.ldy + n] = (uint16_t)f32_to_bf16_bits(acc[q] + bias);
       }
     }
     return;
@@ -310,7 +364,8 @@ __global__ __launch_bounds__(kMxWaves * 64) void mx_native_kernel(const MxArgs a
 }
 
 template <int MR>
-__global__ __launch_bounds__(256) void mx_reduce_kernel(const float* partial, int Sk, int n_tiles, int M, int64_t N, uint16_t* y, int64_t ldy) {
+__global__ __launch_bounds__(256) void mx_reduce_kernel(const float* partial, int Sk, int n_tiles, int M, int64_t N, uint16_t* y, int64_t ldy,
+                                                        const uint16_t* bias) {
   const int nt = blockIdx.x;
   for (int e = threadIdx.x; e < MR * 64; e += 256) {
     const int q = e >> 6, l = e & 63;
@@ -318,7 +373,7 @@ __global__ __launch_bounds__(256) void mx_reduce_kernel(const float* partial, in
     for (int r = 0; r < Sk; ++r) sum += partial[(((int64_t)r * n_tiles + nt) * MR + q) * 64 + l];
     const int tok = 8 * (q >> 2) + 4 * (l >> 5) + (q & 3);
     const int64_t n = (int64_t)nt * 32 + (l & 31);
-    if (tok < M && n < N) y[(int64_t)tok * ldy + n] = (uint16_t)f32_to_bf16_bits(sum);
+    if (tok < M && n < N) y[(int64_t)tok * ldy + n] = (uint16_t)f32_to_bf16_bits(sum + (bias ? bf16_bits_to_f32(bias[n]) : 0.f));
   }
 }
 
@@ -341,15 +396,23 @@ static MxWorkspace mx_workspace(int64_t M, int64_t N, int64_t K) {
   return w;
 }
 
-template <int NG, int MR>
+template <int NG, int MR, int LC>
 static int launch_mx_t(const MxArgs& a, int grid, hipStream_t st) {
-  mx_native_kernel<NG, MR><<<dim3((unsigned)grid), dim3(kMxWaves * 64), 0, st>>>(a);
+  mx_native_kernel<NG, MR, LC><<<dim3((unsigned)grid), dim3(kMxWaves * 64), 0, st>>>(a);
   return launch_status();
+}
+template <int NG, int MR>
+static int launch_mx_lc(const MxArgs& a, int grid, hipStream_t st) {
+  if (a.n_chunks == 0) return launch_mx_t<NG, MR, 0>(a, grid, st);
+  if (a.n_chunks <= 6) return launch_mx_t<NG, MR, 6>(a, grid, st);     // r <= 32
+  if (a.n_chunks <= 12) return launch_mx_t<NG, MR, 12>(a, grid, st);   // r <= 64
+  if (a.n_chunks <= 24) return launch_mx_t<NG, MR, 24>(a, grid, st);   // r <= 128
+  return QERL_ERR_SHAPE;
 }
 template <int MR>
 static int launch_mx(const MxArgs& a, int NG, int grid, hipStream_t st) {
-  if (NG == 1) return launch_mx_t<1, MR>(a, grid, st);
-  if (NG == 2) return launch_mx_t<2, MR>(a, grid, st);
+  if (NG == 1) return launch_mx_lc<1, MR>(a, grid, st);
+  if (NG == 2) return launch_mx_lc<2, MR>(a, grid, st);
   return QERL_ERR_SHAPE;
 }
 
@@ -369,6 +432,8 @@ struct MxGemmArgs {
   const uint8_t* packed; int k_tiles; int n_tiles; int64_t N;
   uint16_t* y; int64_t ldy;
   int n_blocks, nblk_per_xcd;
+  const uint16_t* ts; int64_t ts_ld; int n_chunks; const uint16_t* B; int r;   // as in MxArgs
+  const uint16_t* bias;
 };
 
 constexpr int kMxgBM = 128, kMxgThreads = 512, kMxgMT = 2, kMxgNT = 2;
@@ -509,15 +574,48 @@ __global__ __launch_bounds__(kMxgThreads) void mx_gemm_kernel(const MxGemmArgs a
     }
     if (kt < n) stage(kt, 0, w0, w1, x0, x1);
   }
+  // ---- LoRA up-projection (Eq. 2): 3 r more input columns, [hi | mid | lo] . [B B B]^T, on the bf16 matrix
+  // instruction of the same output layout; operands straight from memory, four chunks of 16 columns requested at a time
+  for (int c0 = 0; c0 < a.n_chunks; c0 += 4) {
+    u32x4 tf[4][MT], bf[4][NT];
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) {
+      const bool live = c0 + cc < a.n_chunks;
+      const int col = 16 * (live ? c0 + cc : a.n_chunks - 1) + 8 * kg;
+      const int bc = lora_b_col(col, a.r);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        int64_t row = m0 + wm * 64 + mt * 32 + n32;
+        row = row < a.M ? row : a.M - 1;
+        tf[cc][mt] = *reinterpret_cast<const u32x4*>(a.ts + row * a.ts_ld + col);
+        if (!live) tf[cc][mt] = u32x4{0u, 0u, 0u, 0u};
+      }
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        int64_t n = (int64_t)(nt0 + nt) * 32 + n32;
+        n = n < a.N ? n : a.N - 1;
+        bf[cc][nt] = *reinterpret_cast<const u32x4*>(a.B + n * a.r + bc);
+      }
+    }
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tf[cc][mt]), __builtin_bit_cast(bf16x8, bf[cc][nt]),
+                                                                acc[mt][nt], 0, 0, 0);
+  }
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
       const int64_t nn = (int64_t)(nt0 + nt) * 32 + n32;
+      const float bias = (a.bias && nn < a.N) ? bf16_bits_to_f32(a.bias[nn]) : 0.f;
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int64_t m = m0 + wm * 64 + mt * 32 + 8 * (i >> 2) + 4 * kg + (i & 3);
-        if (m < a.M && nn < a.N) a.y[m * a.ldy + nn] = (uint16_t)f32_to_bf16_bits(acc[mt][nt][i]);
+        if (m < a.M && nn < a.N) a.y[m * a.ldy + nn] = (uint16_t)f32_to_bf16_bits(acc[mt][nt][i] + bias);
       }
     }
 }
@@ -588,37 +686,74 @@ extern "C" size_t mxfp4_linear_native_workspace_bytes(int64_t M, int64_t N, int6
   return mx_workspace(M, N, K).total;
 }
 
-extern "C" int mxfp4_linear_native(const void* x, int64_t M, int64_t K, int64_t ldx, const void* packed, int64_t N, void* y, int64_t ldy,
-                                   void* workspace, size_t workspace_bytes, void* stream) {
-  if (M < 0 || N < 0 || K < 0 || K % 32 != 0 || ldx < K || ldy < N || N >= ((int64_t)1 << 24)) return QERL_ERR_SHAPE;
-  if (M == 0 || N == 0) return QERL_OK;
-  if (K == 0) return QERL_ERR_SHAPE;
-  if (!x || !packed || !y) return QERL_ERR_NULL;
-  if (!aligned(x, 16) || ldx % 8 != 0 || !aligned(packed, 16) || !aligned(y, 2)) return QERL_ERR_ALIGN;
+// ---- the native linear, with or without the LoRA branch and bias -------------------------------------------------
+namespace qerl {
+
+// lora_down_block divides by the NVFP4 tensor scale it is handed; MXFP4 has none
+static __device__ float mx_unit_scale = 1.0f;
+constexpr int kMxMaxDevices = 64;
+static const float* g_unit_scale_ptr[kMxMaxDevices];   // device address of mx_unit_scale per device, looked up once there
+
+static int unit_scale_ptr(const float** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return launch_status();
+  if (dev < 0 || dev >= kMxMaxDevices) return QERL_ERR_SHAPE;
+  const float* p = __atomic_load_n(&g_unit_scale_ptr[dev], __ATOMIC_ACQUIRE);
+  if (!p) {
+    void* q = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&q, HIP_SYMBOL(mx_unit_scale));
+    if (e != hipSuccess || !q) { set_last_hip_error((int)e); (void)hipGetLastError(); return QERL_ERR_LAUNCH; }
+    p = (const float*)q;
+    __atomic_store_n(&g_unit_scale_ptr[dev], p, __ATOMIC_RELEASE);   // racing first calls look up the same address
+  }
+  *out = p;
+  return QERL_OK;
+}
+
+// workspace of the LoRA variant: arrival counters of the down-projection's K-parts (zero between calls), their
+// partial sums, ts, then the plain variant's workspace
+struct MxLoraWorkspace { size_t ctr_off, tpart_off, ts_off, base_off, total; int64_t ts_ld; int n_chunks; };
+static MxLoraWorkspace mx_lora_workspace(int64_t M, int64_t N, int64_t K, int64_t r) {
+  auto al = [](size_t v) { return (v + 255) & ~(size_t)255; };
+  MxLoraWorkspace w{};
+  w.n_chunks = (int)ceil_div(3 * r, 16);
+  w.ts_ld = (int64_t)w.n_chunks * 16;
+  w.ctr_off = 0;
+  w.tpart_off = al(kCtrlDownWords * sizeof(uint32_t));
+  w.ts_off = w.tpart_off + (r > 0 ? kDownExchangeBytes : 0);
+  w.base_off = w.ts_off + al((size_t)(M > 0 ? M : 1) * (size_t)w.ts_ld * sizeof(uint16_t));
+  w.total = w.base_off + mxfp4_linear_native_workspace_bytes(M, N, K);
+  return w;
+}
+
+struct MxLora { const uint16_t* ts; int64_t ts_ld; int n_chunks; const uint16_t* B; int r; const uint16_t* bias; };
+
+static int mx_linear(const void* x, int64_t M, int64_t K, int64_t ldx, const void* packed, int64_t N, void* y, int64_t ldy,
+                     const MxLora& lo, void* workspace, size_t workspace_bytes, hipStream_t st) {
   if (M > 32) {
     // quantise x once, then the GEMM
     const size_t need = mx_gemm_workspace(M, K);
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < need) return QERL_ERR_WORKSPACE;
     uint8_t* xq = (uint8_t*)workspace;
     uint8_t* xsc = xq + (((size_t)M * (size_t)K + 255) & ~(size_t)255);
-    hipStream_t st = (hipStream_t)stream;
     mx_quantize_kernel<8><<<dim3((unsigned)grid_for(M * (K / 32))), dim3(256), 0, st>>>((const uint16_t*)x, M, K, ldx, xq, xsc);
     int rc = launch_status();
     if (rc != QERL_OK) return rc;
     MxGemmArgs g{};
     g.xq = xq; g.xs = xsc; g.M = M; g.K = K; g.packed = (const uint8_t*)packed;
     g.k_tiles = (int)ceil_div(K, 256); g.n_tiles = (int)ceil_div(N, 32); g.N = N; g.y = (uint16_t*)y; g.ldy = ldy;
+    g.ts = lo.ts; g.ts_ld = lo.ts_ld; g.n_chunks = lo.n_chunks; g.B = lo.B; g.r = lo.r; g.bias = lo.bias;
     return launch_mx_gemm(g, st);
   }
   const MxWorkspace w = mx_workspace(M, N, K);
   if (!workspace || !aligned(workspace, 256) || workspace_bytes < w.total) return QERL_ERR_WORKSPACE;
   uint8_t* ws = (uint8_t*)workspace;
-  hipStream_t st = (hipStream_t)stream;
   int rc = QERL_OK;
   MxArgs a{};
   a.x = (const uint16_t*)x; a.ldx = ldx; a.M = (int)M; a.K = K;
   a.packed = (const uint8_t*)packed; a.k_tiles = (int)ceil_div(K, 256); a.n_tiles = (int)ceil_div(N, 32); a.N = N;
   a.y = (uint16_t*)y; a.ldy = ldy; a.partial = (float*)(ws + w.partial_off);
+  a.ts = lo.ts; a.ts_ld = lo.ts_ld; a.n_chunks = lo.n_chunks; a.B = lo.B; a.r = lo.r; a.bias = lo.bias;
   a.Sk = w.Sk; a.groups_per_range = kMxMain * w.NG;
   int per_range = 256 / w.Sk;
   if (per_range < 1) per_range = 1;
@@ -627,7 +762,61 @@ extern "C" int mxfp4_linear_native(const void* x, int64_t M, int64_t K, int64_t 
   const int grid = per_range * w.Sk;
   rc = M <= 8 ? launch_mx<4>(a, w.NG, grid, st) : launch_mx<16>(a, w.NG, grid, st);
   if (rc != QERL_OK || w.Sk == 1) return rc;
-  if (M <= 8) mx_reduce_kernel<4><<<dim3((unsigned)a.n_tiles), dim3(256), 0, st>>>(a.partial, w.Sk, a.n_tiles, (int)M, N, a.y, ldy);
-  else mx_reduce_kernel<16><<<dim3((unsigned)a.n_tiles), dim3(256), 0, st>>>(a.partial, w.Sk, a.n_tiles, (int)M, N, a.y, ldy);
+  if (M <= 8) mx_reduce_kernel<4><<<dim3((unsigned)a.n_tiles), dim3(256), 0, st>>>(a.partial, w.Sk, a.n_tiles, (int)M, N, a.y, ldy, a.bias);
+  else mx_reduce_kernel<16><<<dim3((unsigned)a.n_tiles), dim3(256), 0, st>>>(a.partial, w.Sk, a.n_tiles, (int)M, N, a.y, ldy, a.bias);
   return launch_status();
+}
+
+static int mx_validate(const void* x, int64_t M, int64_t K, int64_t ldx, const void* packed, int64_t N, const void* y, int64_t ldy) {
+  if (M < 0 || N < 0 || K < 0 || K % 32 != 0 || ldx < K || ldy < N || N >= ((int64_t)1 << 24)) return QERL_ERR_SHAPE;
+  if (M == 0 || N == 0) return 1;   // nothing to do
+  if (K == 0) return QERL_ERR_SHAPE;
+  if (!x || !packed || !y) return QERL_ERR_NULL;
+  if (!aligned(x, 16) || ldx % 8 != 0 || !aligned(packed, 16) || !aligned(y, 2)) return QERL_ERR_ALIGN;
+  return QERL_OK;
+}
+
+}  // namespace qerl
+
+extern "C" int mxfp4_linear_native(const void* x, int64_t M, int64_t K, int64_t ldx, const void* packed, int64_t N, void* y, int64_t ldy,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+  const int vr = mx_validate(x, M, K, ldx, packed, N, y, ldy);
+  if (vr != QERL_OK) return vr > 0 ? QERL_OK : vr;
+  return mx_linear(x, M, K, ldx, packed, N, y, ldy, MxLora{}, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+extern "C" size_t mxfp4_lora_linear_native_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t r) {
+  if (r < 0 || r > kMxMaxRank) return 0;
+  return mx_lora_workspace(M, N, K, r).total;
+}
+
+extern "C" int mxfp4_lora_linear_native(const void* x, int64_t M, int64_t K, int64_t ldx, const void* packed, int64_t N, const void* A,
+                                        const void* B, int64_t r, float lora_scale, const void* bias, void* y, int64_t ldy,
+                                        void* workspace, size_t workspace_bytes, void* stream) {
+  if (r < 0 || r > kMxMaxRank || r % 8 != 0) return QERL_ERR_SHAPE;
+  const int vr = mx_validate(x, M, K, ldx, packed, N, y, ldy);
+  if (vr != QERL_OK) return vr > 0 ? QERL_OK : vr;
+  if (r > 0 && (!A || !B)) return QERL_ERR_NULL;
+  if (r > 0 && (!aligned(A, 16) || !aligned(B, 16))) return QERL_ERR_ALIGN;
+  if (bias && !aligned(bias, 2)) return QERL_ERR_ALIGN;
+  const MxLoraWorkspace L = mx_lora_workspace(M, N, K, r);
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total) return QERL_ERR_WORKSPACE;
+  uint8_t* ws = (uint8_t*)workspace;
+  hipStream_t st = (hipStream_t)stream;
+  MxLora lo{};
+  lo.bias = (const uint16_t*)bias;
+  if (r > 0) {
+    const float* one = nullptr;
+    int rc = unit_scale_ptr(&one);
+    if (rc != QERL_OK) return rc;
+    GemmArgs d{};
+    d.x = (const uint16_t*)x; d.ldx = ldx; d.M = M; d.K = K; d.N = r; d.wbf16 = (const uint16_t*)A; d.n_tiles = (int)ceil_div(r, 32);
+    d.tensor_scale = one; d.lora_scale = lora_scale; d.r = (int)r;
+    d.ts = (const uint16_t*)(ws + L.ts_off); d.ts_ld = L.ts_ld;
+    d.tpart = (uint32_t*)(ws + L.tpart_off); d.counters = (uint32_t*)(ws + L.ctr_off);
+    rc = launch_lora_down_gemm(d, st);
+    if (rc != QERL_OK) return rc;
+    lo.ts = d.ts; lo.ts_ld = L.ts_ld; lo.n_chunks = L.n_chunks; lo.B = (const uint16_t*)B; lo.r = (int)r;
+  }
+  return mx_linear(x, M, K, ldx, packed, N, y, ldy, lo, ws + L.base_off, workspace_bytes - L.base_off, st);
 }

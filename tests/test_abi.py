@@ -106,6 +106,32 @@ def test_host_side_validation_needs_no_gpu(lib):
     assert lib.nvfp4_dequantize(fake, fake, fake, 2, 24, fake, None) == -2
 
 
+def test_host_side_validation_of_the_mx_linears(lib):
+    fake = 0x10000
+    f = ctypes.c_float(1.0)
+    ok_ws = 1 << 30
+    # plain variant
+    assert lib.mxfp4_linear_native(fake, 4, 48, 48, fake, 8, fake, 8, fake, ok_ws, None) == -2      # K % 32
+    assert lib.mxfp4_linear_native(fake, 4, 64, 64, None, 8, fake, 8, fake, ok_ws, None) == -1
+    assert lib.mxfp4_linear_native(fake, 4, 64, 68, fake, 8, fake, 8, fake, ok_ws, None) == -3      # ldx % 8
+    assert lib.mxfp4_linear_native(fake, 4, 64, 64, fake, 8, fake, 8, fake, 16, None) == -4
+    assert lib.mxfp4_linear_native(fake, 0, 64, 64, fake, 8, fake, 8, None, 0, None) == 0
+    # with the LoRA branch and bias
+    call = lambda r, A=fake, B=fake, bias=None, ws=fake, wsb=ok_ws, K=64: lib.mxfp4_lora_linear_native(
+        fake, 4, K, K, fake, 8, A, B, r, f, bias, fake, 8, ws, wsb, None)
+    assert call(12) == -2 and call(136) == -2 and call(-8) == -2        # rank: a multiple of 8, at most 128
+    assert call(8, K=48) == -2
+    assert call(8, A=None) == -1 and call(8, B=None) == -1
+    assert call(8, A=fake + 8) == -3 and call(8, B=fake + 2) == -3 and call(0, bias=fake + 1) == -3
+    assert call(8, ws=None) == -4 and call(8, wsb=1024) == -4 and call(8, ws=fake + 64) == -4
+    assert call(0, A=None, B=None, wsb=lib.mxfp4_lora_linear_native_workspace_bytes(4, 8, 64, 0) - 1) == -4
+    for M in (1, 32, 33, 4096):
+        for r in (0, 32, 128):
+            assert lib.mxfp4_lora_linear_native_workspace_bytes(M, 5120, 5120, r) >= lib.mxfp4_linear_native_workspace_bytes(M, 5120, 5120)
+    assert lib.mxfp4_lora_linear_native_workspace_bytes(8, 64, 128, 136) == 0
+    assert lib.mxfp4_lora_linear_native_workspace_bytes(8, 64, 128, 32) < (32 << 20)
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     with pytest.raises(TypeError):

@@ -132,6 +132,65 @@ def test_native_linear_is_the_product_of_the_quantised_operands(M, N, K):
     assert torch.equal(y, again)
 
 
+@pytest.mark.parametrize("M,N,K,r,with_bias", [
+    (1, 64, 128, 8, True), (3, 40, 320, 16, False), (8, 512, 3584, 32, True), (8, 96, 18944, 64, True),   # K split over ranges
+    (16, 1000, 2112, 32, False), (32, 130, 5120, 128, True), (9, 33, 27648, 24, True), (5, 3584, 3584, 0, True),
+    (33, 64, 128, 8, True), (64, 130, 320, 32, False), (130, 1000, 2112, 64, True), (300, 96, 96, 40, True),
+    (200, 3584, 3584, 32, True), (1100, 5120, 1024, 128, True), (513, 40, 32, 0, True),
+])
+def test_native_linear_with_lora_and_bias(M, N, K, r, with_bias):
+    """Eq. (2) on the native product: the adapter reads bf16 x; the sum is held to the linear's gate against the
+    oracle's float64 composition.  Twice through one workspace (the K-parts' counters are left at zero), bit-equal;
+    without adapter and bias the entry point gives the plain native linear's bits."""
+    print("mx lora linear case", M, N, K, r, with_bias, flush=True)
+    x, codes, scales, pw = _problem(M, N, K, 300 + M + N + r)
+    rng = np.random.default_rng(1000 + M + r)
+    A = _bf16(rng.standard_normal((r, K)).astype(np.float32) / np.sqrt(K)) if r else None
+    B = _bf16(rng.standard_normal((N, r)).astype(np.float32) * 0.05) if r else None
+    bias = _bf16(rng.standard_normal(N).astype(np.float32) * 0.1) if with_bias else None
+    ws = qerl.Workspace(qerl.load_library().mxfp4_lora_linear_native_workspace_bytes(M, N, K, r))
+    cu = lambda t: None if t is None else t.cuda()
+    y = qerl.mxfp4_lora_linear_native(x.cuda(), pw, cu(A), cu(B), 1.5, cu(bias), workspace=ws)
+    torch.cuda.synchronize()
+    nf = lambda t: None if t is None else t.float().numpy()
+    check_linear(y, mx.mx_lora_linear_native(x.float().numpy(), codes, scales, nf(A), nf(B), 1.5, nf(bias)), ("mx lora", M, N, K, r))
+    again = qerl.mxfp4_lora_linear_native(x.cuda(), pw, cu(A), cu(B), 1.5, cu(bias), workspace=ws)
+    assert torch.equal(y, again)
+    plain = qerl.mxfp4_lora_linear_native(x.cuda(), pw, workspace=ws)
+    assert torch.equal(plain, qerl.mxfp4_linear_native(x.cuda(), pw))
+
+
+def test_native_lora_branch_reads_the_unquantised_activations():
+    """A rank-8 adapter whose first row copies one activation into one output: the difference to the plain linear is
+    that activation itself (1.0625: MXFP8 with the scale of a Gaussian block would make it 1 or 1.125), for few tokens and for the GEMM."""
+    N, K = 64, 256
+    for M in (4, 40):
+        x, codes, scales, pw = _problem(M, N, K, 55 + M)
+        x = x.clone()
+        x[:, 5] = 1.0625
+        A = torch.zeros((8, K), dtype=torch.bfloat16); A[0, 5] = 1.0
+        B = torch.zeros((N, 8), dtype=torch.bfloat16); B[2, 0] = 1.0
+        base = qerl.mxfp4_linear_native(x.cuda(), pw).float().cpu().numpy().astype(np.float64)
+        y = qerl.mxfp4_lora_linear_native(x.cuda(), pw, A.cuda(), B.cuda(), 1.0)
+        want = mx.mx_lora_linear_native(x.float().numpy(), codes, scales, A.float().numpy(), B.float().numpy(), 1.0)
+        check_linear(y, want, ("lora reads x", M))
+        d = y.float().cpu().numpy() - base
+        assert not d[:, [0, 1, 3, 4, 5]].any() and np.all(np.abs(d[:, 2] - 1.0625) < 2.0 ** -6)
+
+
+def test_native_lora_linear_rejects_what_it_cannot_run():
+    lib = qerl.load_library()
+    assert lib.mxfp4_lora_linear_native_workspace_bytes(8, 64, 128, 136) == 0
+    x, codes, scales, pw = _problem(4, 64, 128, 3)
+    A = torch.zeros((12, 128), dtype=torch.bfloat16).cuda(); B = torch.zeros((64, 12), dtype=torch.bfloat16).cuda()
+    ws = qerl.Workspace(lib.mxfp4_lora_linear_native_workspace_bytes(4, 64, 128, 16))
+    with pytest.raises(qerl.QerlError):
+        qerl.mxfp4_lora_linear_native(x.cuda(), pw, A, B, 1.0, workspace=ws)       # rank not a multiple of 8
+    small = qerl.Workspace(256)
+    with pytest.raises(qerl.QerlError):
+        qerl.mxfp4_lora_linear_native(x.cuda(), pw, workspace=small)
+
+
 def test_how_far_the_native_path_is_from_the_weight_only_result():
     """Not a parity claim: the measured cost of rounding activations to MXFP8 on Gaussian inputs, relative to
     each output row's root mean square (the weight-only result is what the paper's kernels compute)."""

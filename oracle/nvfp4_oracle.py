@@ -245,6 +245,34 @@ def nvfp4_lora_linear_backward(x, dy, codes, scales, tensor_scale, A=None, B=Non
     return dx + s * (u @ A), s * (u.T @ x), s * (dy.T @ t)
 
 
+def nvfp4_lora_linear_backward_group(x, members):
+    """Backward of several linears that read the same x (the q / k / v or gate / up projections of a block:
+    Section 3.3; Preliminary, "Low-rank Adaptation"): the loss sees x through every member, so
+
+        dx = sum_i [ dy_i W_hat_i + s_i (dy_i B_i) A_i ]        [M, K]
+
+    while each member's adapter gradients depend on its own dy_i only.  members: dicts with dy, codes, scales,
+    tensor_scale and optionally A, B, lora_scale.  float64, nothing rounded.  Returns (dx, [(dA_i, dB_i)]).
+    """
+    x64 = np.asarray(x, dtype=np.float32).astype(np.float64)
+    dx = np.zeros_like(x64)
+    grads = []
+    for mem in members:
+        dy = np.asarray(mem["dy"], dtype=np.float32).astype(np.float64)
+        dx += dy @ nvfp4_dequantize(mem["codes"], mem["scales"], mem["tensor_scale"]).astype(np.float64)
+        A, B = mem.get("A"), mem.get("B")
+        if A is None or B is None or np.asarray(A).shape[0] == 0:
+            grads.append((None, None))
+            continue
+        A = np.asarray(A, dtype=np.float32).astype(np.float64)
+        B = np.asarray(B, dtype=np.float32).astype(np.float64)
+        s = np.float64(mem.get("lora_scale", 0.0))
+        u = dy @ B
+        dx += s * (u @ A)
+        grads.append((s * (u.T @ x64), s * (dy.T @ (x64 @ A.T))))
+    return dx, grads
+
+
 def round_to_bf16(v):
     """fp64 -> nearest bf16 value (ties to even), returned as float64.  bf16 keeps the top 16 bits of an
     IEEE fp32; the inputs met here are far inside the fp32 range, so rounding the fp32 bit pattern is exact

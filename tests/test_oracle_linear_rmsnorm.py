@@ -257,3 +257,71 @@ def test_backward_entries_by_brute_force_and_special_cases():
     fd = (L(A + E) - L(A - E)) / (2 * float(h))
     yg = o.nvfp4_lora_linear_backward(x, y.astype(np.float32), codes, scales, ts, A, B, s)[1][1, 5]
     assert abs(fd - yg) <= 1e-4 * max(1.0, abs(fd))      # y was rounded to fp32 for the call: not bit-exact
+
+
+
+def _bwd_group(seed, M=3, K=32, Ns=(20, 8, 12), rs=(8, 0, 4)):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    members = []
+    for N, r in zip(Ns, rs):
+        W = (rng.standard_normal((N, K)) * rng.uniform(0.01, 0.1)).astype(np.float32)   # members with different tensor scales
+        codes, scales, ts = o.nvfp4_quantize(W)
+        mem = {"dy": rng.standard_normal((M, N)).astype(np.float32), "codes": codes, "scales": scales, "tensor_scale": ts}
+        if r:
+            mem.update(A=(rng.standard_normal((r, K)) / r).astype(np.float32), B=(rng.standard_normal((N, r)) * 0.1).astype(np.float32),
+                       lora_scale=float(rng.uniform(0.5, 2.0)))
+        members.append(mem)
+    return x, members
+
+
+def _group_forward(x, mem, A=None, B=None):
+    A = mem.get("A") if A is None else A
+    B = mem.get("B") if B is None else B
+    return o.nvfp4_lora_linear(x, mem["codes"], mem["scales"], mem["tensor_scale"], A, B, mem.get("lora_scale", 0.0))
+
+
+def test_group_backward_is_the_adjoint_of_the_stacked_forward_map():
+    """The group's forward map x -> (y_1, .., y_n) is linear in x: <(dy_i), J v> = <dx, v> with the pinned forward
+    linears, for several directions (a dropped member, a missing LoRA term or a wrong scale breaks it); each
+    member's dA_i, dB_i are the adjoints of its own (bi)linear maps; a loss through one member only (the other
+    dy_i zero) gives that member's single-linear dx."""
+    x, members = _bwd_group(5)
+    dx, grads = o.nvfp4_lora_linear_backward_group(x, members)
+    rng = np.random.default_rng(6)
+    for _ in range(3):
+        v = rng.standard_normal(x.shape).astype(np.float32)
+        lhs = sum(np.sum(m["dy"] * (_group_forward(v, m) - _group_forward(np.zeros_like(v), m))) for m in members)
+        assert np.isclose(lhs, np.sum(dx * v), rtol=1e-11)
+    for m, (dA, dB) in zip(members, grads):
+        if "A" not in m:
+            assert dA is None and dB is None
+            continue
+        vA = rng.standard_normal(m["A"].shape).astype(np.float32)
+        vB = rng.standard_normal(m["B"].shape).astype(np.float32)
+        dyi = m["dy"]
+        assert np.isclose(np.sum(dyi * (_group_forward(x, m, A=vA) - _group_forward(x, m, A=np.zeros_like(vA)))), np.sum(dA * vA), rtol=1e-11)
+        assert np.isclose(np.sum(dyi * (_group_forward(x, m, B=vB) - _group_forward(x, m, B=np.zeros_like(vB)))), np.sum(dB * vB), rtol=1e-11)
+    # one member's loss alone
+    for i, m in enumerate(members):
+        only = [dict(mm, dy=(mm["dy"] if j == i else np.zeros_like(mm["dy"]))) for j, mm in enumerate(members)]
+        dxi, gi = o.nvfp4_lora_linear_backward_group(x, only)
+        single = o.nvfp4_lora_linear_backward(x, m["dy"], m["codes"], m["scales"], m["tensor_scale"], m.get("A"), m.get("B"), m.get("lora_scale", 0.0))
+        assert np.allclose(dxi, single[0], rtol=1e-13, atol=1e-15)
+        for j, (a, b) in enumerate(gi):
+            if j != i and a is not None:
+                assert not a.any() and not b.any()
+
+
+def test_group_backward_entries_by_brute_force():
+    x, members = _bwd_group(8, M=2, K=16, Ns=(5, 3), rs=(3, 2))
+    dx, grads = o.nvfp4_lora_linear_backward_group(x, members)
+    Ws = [o.nvfp4_dequantize(m["codes"], m["scales"], m["tensor_scale"]).astype(np.float64) for m in members]
+    for mrow in range(x.shape[0]):
+        for k in range(x.shape[1]):
+            want = 0.0
+            for m, W in zip(members, Ws):
+                N, r = m["B"].shape
+                want += sum(float(m["dy"][mrow, n]) * (W[n, k] + m["lora_scale"] * sum(float(m["B"][n, j]) * float(m["A"][j, k]) for j in range(r)))
+                            for n in range(N))
+            assert abs(dx[mrow, k] - want) <= 1e-12 * max(1.0, abs(want))

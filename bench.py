@@ -21,6 +21,7 @@ configurations (one leg).
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -393,7 +394,7 @@ def backward_bench(args):
     """--backward: the backward pass (dX through the frozen weights, dA, dB) of every linear of a few layers at
     the configuration's prefill size; one JSON line in the same format, TFLOP/s on the dX flops."""
     cfg = qs.CONFIGS[args.config]
-    M = args.M or cfg["M"][0]
+    M = args.M or max(cfg["M"])      # a training batch: the configuration's prefill size
     n_layers = args.layers or 2
     gen = torch.Generator(device="cuda")
     gen.manual_seed(qs.seed_for(args.config, 1))
@@ -415,11 +416,38 @@ def backward_bench(args):
     ws = torch.empty((need + 256,), dtype=torch.uint8, device="cuda")
     scale = cfg["alpha"] / r
 
-    def step():
+    # linears that read the same x (q + k + v, gate + up) go through one grouped call: one GEMM forms their summed dX
+    calls, run = [], []
+    for e in lin + [None]:
+        if run and (e is None or e[0].K != run[0][0].K or e[0].name in ("q", "o", "gate", "down") or len(run) == 4):
+            calls.append(run)
+            run = []
+        if e is not None:
+            run.append(e)
+    for run in calls:
+        if len(run) > 1:
+            descs = (qerl.binding._BackwardDesc * len(run))()
+            for d, (shp, *_) in zip(descs, run):
+                d.N, d.r = shp.N, r
+            need = max(need, lib.nvfp4_lora_linear_backward_group_workspace_bytes(M, run[0][0].K, ctypes.cast(descs, ctypes.c_void_p), len(run)))
+    ws = torch.empty((need + 256,), dtype=torch.uint8, device="cuda")
+
+    def step_separate():
         for shp, pt, A, B in lin:
             qerl.nvfp4_lora_linear_backward(xs[shp.K], dys[shp.N], pt, A, B, scale, workspace=ws)
+
+    def step():
+        for run in calls:
+            if len(run) == 1:
+                shp, pt, A, B = run[0]
+                qerl.nvfp4_lora_linear_backward(xs[shp.K], dys[shp.N], pt, A, B, scale, workspace=ws)
+            else:
+                qerl.nvfp4_lora_linear_backward_group(xs[run[0][0].K], [dys[e[0].N] for e in run], [e[1] for e in run],
+                                                      [e[2] for e in run], [e[3] for e in run], [scale] * len(run), workspace=ws)
     for _ in range(args.warmup):
         step()
+        step_separate()
+    ms_separate = timed(step_separate, args.steps)
     ms = timed(step, args.steps)
     flops = sum(2 * M * s.N * s.K for s, *_ in lin)
     tflops = flops / (ms * 1e-3) / 1e12
@@ -435,7 +463,9 @@ def backward_bench(args):
         "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 x fp4(e2m1)*fp8(e4m3) -> fp32 accumulate", "data": "synthetic",
         "config": {"workload": f"config {args.config}: backward of {cfg['model']}-shaped decoder linears, {n_layers} layers, "
-                               f"M={M}, LoRA r={r} alpha={cfg['alpha']:g}; dX bf16, dA and dB fp32; eager launches"},
+                               f"M={M}, LoRA r={r} alpha={cfg['alpha']:g}; dX bf16, dA and dB fp32; eager launches; "
+                               f"q+k+v and gate+up as grouped calls (summed dX)",
+                   "ms_per_step_one_call_per_linear": round(ms_separate, 4)},
         "roofline": {"bound": "mfma", "achieved": round(fl / (us * 1e-6) / 1e12, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(fl / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
                      "kernel": "gemm32_kernel<.., true> (transposed operand)", "algorithmic_flops_per_launch": fl,

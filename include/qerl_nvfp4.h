@@ -334,6 +334,47 @@ QERL_API int nvfp4_lora_linear_backward(const void* x_bf16, const void* dy_bf16,
                                         float* dA_f32, float* dB_f32, void* workspace, size_t workspace_bytes,
                                         void* stream);
 
+/* ---------------------------------------------------------------------------
+ * nvfp4_lora_linear_backward_group -- the backward pass of up to 4 linears that
+ * read the same x (the q / k / v or the gate / up projections of a block:
+ * Section 3.3), each with its own upstream gradient dY_i [M, N_i]:
+ *   dX [M, lddx] bf16 = sum_i [ dY_i W_hat_i + s_i (dY_i B_i) A_i ]
+ *   dA_i, dB_i as in nvfp4_lora_linear_backward, from dY_i alone.
+ * dX is formed by one GEMM whose contraction runs over the members' rows one
+ * after the other: fp32 throughout (between members the running sums are
+ * rescaled from one tensor scale to the next, one fp32 rounding each), ONE
+ * rounding to bf16 -- where separate calls would round every member's dX and
+ * their sum.  The down-projections x A_i^T of all adapters share one launch.
+ * With one member the call is nvfp4_lora_linear_backward, bit for bit.
+ *   members: HOST array of n_members descriptors (read during the call only; the
+ *            pointers inside are device pointers), each as the arguments of the
+ *            same names of nvfp4_lora_linear_backward.  r_i == 0: that member
+ *            contributes dY_i W_hat_i only.
+ *   workspace: >= nvfp4_lora_linear_backward_group_workspace_bytes(M, K, members,
+ *            n_members) (0 for n_members outside 1..4), 256-byte aligned; needs
+ *            no initialisation.
+ * Errors: as nvfp4_lora_linear_backward; QERL_ERR_SHAPE for n_members outside 1..4.
+ */
+typedef struct {
+  const void* dy_bf16;         /* [M, lddy] upstream gradient of this member's output */
+  int64_t lddy;
+  int64_t N;                   /* N % 8 == 0 */
+  const void* packed_t;        /* nvfp4_prepack_t output for this member's [N, K] weight */
+  const float* tensor_scale;
+  const void* A_bf16;          /* [r, K] or NULL */
+  const void* B_bf16;          /* [N, r] or NULL */
+  int64_t r;                   /* r % 8 == 0, r <= 64 */
+  float lora_scale;
+  float* dA_f32;               /* [r, K] out (NULL when r == 0) */
+  float* dB_f32;               /* [N, r] out (NULL when r == 0) */
+} qerl_backward_desc;
+QERL_API size_t nvfp4_lora_linear_backward_group_workspace_bytes(int64_t M, int64_t K, const qerl_backward_desc* members,
+                                                                 int n_members);   /* host */
+QERL_API int nvfp4_lora_linear_backward_group(const void* x_bf16, int64_t M, int64_t K, int64_t ldx,
+                                              const qerl_backward_desc* members, int n_members,
+                                              void* dx_bf16, int64_t lddx,
+                                              void* workspace, size_t workspace_bytes, void* stream);
+
 /* Zero the control words of a linear workspace.  Call once after allocating
  * it (and again if a kernel using it was ever aborted). */
 QERL_API int qerl_workspace_init(void* workspace, size_t workspace_bytes, void* stream);

@@ -46,6 +46,8 @@ _SIGNATURES = {
     "nvfp4_prepack_t_bytes": (_c_sz, [_c_i64, _c_i64]),
     "nvfp4_prepack_t": (ctypes.c_int, [_c_p, _c_p, _c_i64, _c_i64, _c_p, _c_p]),
     "nvfp4_lora_linear_backward_workspace_bytes": (_c_sz, [_c_i64, _c_i64, _c_i64, _c_i64]),
+    "nvfp4_lora_linear_backward_group_workspace_bytes": (_c_sz, [_c_i64, _c_i64, _c_p, ctypes.c_int]),
+    "nvfp4_lora_linear_backward_group": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, ctypes.c_int, _c_p, _c_i64, _c_p, _c_sz, _c_p]),
     "nvfp4_lora_linear_backward": (ctypes.c_int, [_c_p, _c_p, _c_i64, _c_i64, _c_i64, _c_i64, _c_i64, _c_p, _c_p, _c_p, _c_p,
                                                   _c_i64, ctypes.c_float, _c_p, _c_i64, _c_p, _c_p, _c_p, _c_sz, _c_p]),
     "nvfp4_lora_linear_packed_group": (ctypes.c_int, [_c_p, _c_i64, _c_i64, _c_i64, _c_p, ctypes.c_int,
@@ -437,6 +439,55 @@ def nvfp4_lora_linear_backward(x, dy, w: PackedWeightT, A: Optional[torch.Tensor
         _dev(w.tensor_scale, torch.float32, "tensor_scale"), a_ptr, b_ptr, r, float(lora_scale),
         _dev(dx, torch.bfloat16, "dx"), K, da_ptr, db_ptr, ws_ptr, workspace.numel() - (ws_ptr - base), _stream()))
     return dx, dA, dB
+
+
+class _BackwardDesc(ctypes.Structure):
+    """Mirror of qerl_backward_desc in the header."""
+    _fields_ = [("dy", _c_p), ("lddy", _c_i64), ("N", _c_i64), ("packed_t", _c_p), ("tensor_scale", _c_p), ("A", _c_p), ("B", _c_p),
+                ("r", _c_i64), ("lora_scale", ctypes.c_float), ("dA", _c_p), ("dB", _c_p)]
+
+
+def nvfp4_lora_linear_backward_group(x, dys, weights, As=None, Bs=None, lora_scales=None, workspace: Optional[torch.Tensor] = None):
+    """Backward of several linears that read the same x: (dx bf16 [M, K] summed over the members, [(dA_i, dB_i)])."""
+    lib = load_library()
+    n = len(weights)
+    As = As if As is not None else [None] * n
+    Bs = Bs if Bs is not None else [None] * n
+    lora_scales = lora_scales if lora_scales is not None else [0.0] * n
+    M, K, ldx = _rows(x, "x")
+    descs = (_BackwardDesc * n)()
+    grads, keep = [], []
+    for i, (dy, w) in enumerate(zip(dys, weights)):
+        Mi, N, lddy = _rows(dy, "dy")
+        if Mi != M or N != w.N or w.K != K:
+            raise ValueError("every dy must be [M, N_i] and every member must have K columns")
+        d = descs[i]
+        d.dy, d.lddy, d.N = _dev(dy, torch.bfloat16, "dy"), lddy, N
+        d.packed_t, d.tensor_scale = _dev(w.packed, torch.uint8, "packed_t"), _dev(w.tensor_scale, torch.float32, "tensor_scale")
+        A, B = As[i], Bs[i]
+        dA = dB = None
+        if A is not None and B is not None and A.shape[0] > 0:
+            r = A.shape[0]
+            if tuple(A.shape) != (r, K) or tuple(B.shape) != (N, r) or not A.is_contiguous() or not B.is_contiguous():
+                raise ValueError("A must be contiguous [r, K] and B contiguous [N, r]")
+            dA = torch.empty((r, K), dtype=torch.float32, device=x.device)
+            dB = torch.empty((N, r), dtype=torch.float32, device=x.device)
+            d.A, d.B, d.r, d.lora_scale = _dev(A, torch.bfloat16, "A"), _dev(B, torch.bfloat16, "B"), r, float(lora_scales[i])
+            d.dA, d.dB = _dev(dA, torch.float32, "dA"), _dev(dB, torch.float32, "dB")
+        grads.append((dA, dB))
+        keep.append((dy, A, B))
+    dx = torch.empty((M, K), dtype=torch.bfloat16, device=x.device)
+    need = lib.nvfp4_lora_linear_backward_group_workspace_bytes(M, K, ctypes.cast(descs, _c_p), n)
+    if need == 0:
+        raise ValueError("a backward group has 1..4 members")
+    if workspace is None:
+        workspace = torch.empty((need + 256,), dtype=torch.uint8, device=x.device)
+    base = workspace.data_ptr()
+    ws_ptr = (base + 255) & ~255
+    _check("nvfp4_lora_linear_backward_group", lib.nvfp4_lora_linear_backward_group(
+        _dev(x, torch.bfloat16, "x"), M, K, ldx, ctypes.cast(descs, _c_p), n, _dev(dx, torch.bfloat16, "dx"), K,
+        ws_ptr, workspace.numel() - (ws_ptr - base), _stream()))
+    return dx, grads
 
 
 T_PARTS = 8   # QERL_T_PARTS in the header

@@ -130,6 +130,10 @@ struct GemmMember {
   uint16_t* y; int64_t ldy;
   int block_begin;                                                          // first column block of this member (set by the launcher)
 };
+struct GemmSeg {
+  const uint16_t* x; int64_t ldx; int64_t K; const uint8_t* packed; int64_t k_tiles; const float* tensor_scale;
+  const uint16_t* ts; int64_t ts_ld; int ext_stages; const uint16_t* B; int r;
+};
 struct GemmArgs {
   const uint16_t* x; int64_t ldx; int64_t M; int64_t K; int64_t N;
   const uint8_t* packed; int64_t k_tiles; const float* tensor_scale;        // kFmtNvfp4 weights
@@ -141,6 +145,11 @@ struct GemmArgs {
   int n_tiles; int n_blocks; int nblk_per_xcd;
   int m_n; GemmMember m[kMaxGroup];                                         // the main launch's members (m_n == 0: one, from the fields above)
   int transposed;                                                           // packed is in nvfp4_prepack_t's order: K counts rows of W, N its columns
+  // transposed launches only: the contraction runs over seg_n segments one after the other -- the members of a group
+  // of linears that read the same x, each with its own dY (x, ldx), rows (K), transposed tiles, tensor scale and LoRA
+  // columns (ts = three terms of lora_scale / S32 * dY B; B = A^T [N, r]).  seg_n == 0: one segment, from the
+  // fields above and m[0].
+  int seg_n; GemmSeg seg[kMaxGroup];
   uint32_t* ready;                                                          // LoRA down-projection inside another kernel's launch: workgroups that have written ts count themselves here (else null)
   uint32_t* tpart; uint32_t* counters;                                      // LoRA down-projection over several K-parts: partial sums, arrival counts (zero between calls); or null
   // LoRA down-projection of a group of adapters that read the same x (g_n > 0): grid.y runs over the 32-row

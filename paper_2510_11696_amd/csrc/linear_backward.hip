@@ -16,6 +16,9 @@
 // the forward pass with the roles of A and B exchanged (both transposed once per call: they change with every
 // optimiser step).  dA and dB are skinny products over the token dimension (MFMA, operands transposed through LDS),
 // tokens split over a few workgroups whose partial sums are added in order.
+// Several linears that read the same x (q / k / v, gate / up: Section 3.3) go through one call: dX is the sum of the
+// members' terms, formed by ONE launch of the transposed GEMM whose contraction runs over the members' rows one
+// after the other (fp32 throughout, one rounding), and the down-projections of x for all adapters share a launch.
 #include "linear.hpp"
 
 namespace qerl {
@@ -216,32 +219,162 @@ __global__ __launch_bounds__(256) void lora_grad_reduce_kernel(const float* __re
 }
 
 static size_t al256(size_t v) { return (v + 255) & ~(size_t)255; }
-struct BackwardLayout { size_t ctr_off, at_off, bt_off, tsu_off, tst_off, p_off, part_off, total; int64_t ts_ld; int ext_stages; int n_chunks; int64_t tokens_per_chunk; };
-static BackwardLayout backward_layout(int64_t M, int64_t N, int64_t K, int64_t r) {
+// Workspace of a backward call over n members that read the same x: the arrival counters of the K-split
+// down-projections, then per member A^T, B^T and the two three-term products, then one area that first holds the
+// down-projections' K-part sums and later the gradient products' partial sums.
+struct BackwardMemberLayout { size_t at_off, bt_off, tsu_off, tst_off; int64_t ts_ld; int ext_stages; };
+struct BackwardLayout { size_t ctr_off, part_off, total; int n_chunks; int64_t tokens_per_chunk; BackwardMemberLayout mem[kMaxGroup]; };
+static BackwardLayout backward_layout(int64_t M, int64_t K, const int64_t* Ns, const int64_t* rs, int n) {
   BackwardLayout L{};
-  const size_t m = (size_t)(M > 0 ? M : 1), n = (size_t)(N > 0 ? N : 1), k = (size_t)(K > 0 ? K : 1), rr = (size_t)(r > 0 ? r : 0);
-  L.ext_stages = (int)ceil_div(3 * (int64_t)rr, 64);
-  L.ts_ld = (int64_t)L.ext_stages * 64;
+  const size_t m = (size_t)(M > 0 ? M : 1), k = (size_t)(K > 0 ? K : 1);
   int64_t chunks = ceil_div((int64_t)m, 64);
   chunks = chunks > kGradChunksMax ? kGradChunksMax : chunks;
   L.n_chunks = (int)chunks;
   L.tokens_per_chunk = ceil_div((int64_t)m, chunks);
-  L.ctr_off = 0;                                   // arrival counters of the K-split down-projections (zeroed by every call)
-  L.at_off = al256(kDownMaxSlots * sizeof(uint32_t));
-  L.bt_off = L.at_off + al256(k * rr * 2);
-  L.tsu_off = L.bt_off + al256(n * rr * 2);
-  L.tst_off = L.tsu_off + al256(m * (size_t)L.ts_ld * 2);
-  L.p_off = L.tst_off + al256(m * (size_t)L.ts_ld * 2);
-  L.part_off = L.p_off;
-  size_t part = rr ? al256((size_t)chunks * (n > k ? n : k) * kGradRanks * sizeof(float)) : 0;
-  if (rr && part < kDownExchangeBytes) part = kDownExchangeBytes;   // the same area first holds the down-projections' K-part sums
+  L.ctr_off = 0;                                   // zeroed by every call
+  size_t off = al256(kDownMaxSlots * sizeof(uint32_t));
+  size_t widest = 0;
+  bool any = false;
+  for (int i = 0; i < n; ++i) {
+    const size_t nn = (size_t)(Ns[i] > 0 ? Ns[i] : 1), rr = (size_t)(rs[i] > 0 ? rs[i] : 0);
+    BackwardMemberLayout& b = L.mem[i];
+    b.ext_stages = (int)ceil_div(3 * (int64_t)rr, 64);
+    b.ts_ld = (int64_t)b.ext_stages * 64;
+    b.at_off = off;  off += al256(k * rr * 2);
+    b.bt_off = off;  off += al256(nn * rr * 2);
+    b.tsu_off = off; off += al256(m * (size_t)b.ts_ld * 2);
+    b.tst_off = off; off += al256(m * (size_t)b.ts_ld * 2);
+    if (rr) { any = true; widest = widest > nn ? widest : nn; }
+  }
+  L.part_off = off;
+  size_t part = 0;
+  if (any) {
+    widest = widest > k ? widest : k;
+    part = al256((size_t)chunks * widest * kGradRanks * sizeof(float));
+    if (part < kDownExchangeBytes) part = kDownExchangeBytes;
+  }
   L.total = L.part_off + part;
-  if (L.total == 0) L.total = 256;
   return L;
 }
 static int grid_for(int64_t items) {
   int64_t b = ceil_div(items, 256);
   return (int)(b < 1 ? 1 : (b > 8192 ? 8192 : b));
+}
+
+struct BackwardMember {
+  const uint16_t* dy; int64_t lddy; int64_t N; const uint8_t* packed_t; const float* tensor_scale;
+  const uint16_t* A; const uint16_t* B; int64_t r; float lora_scale; float* dA; float* dB;
+};
+
+static int backward_validate(const void* x, int64_t M, int64_t K, int64_t ldx, const BackwardMember* mem, int n, const void* dx, int64_t lddx) {
+  if (n < 1 || n > kMaxGroup) return QERL_ERR_SHAPE;
+  if (M < 0 || K < 0 || K % kBlock != 0 || ldx < K || lddx < K) return QERL_ERR_SHAPE;
+  bool any = false;
+  for (int i = 0; i < n; ++i) {
+    const BackwardMember& b = mem[i];
+    if (b.N < 0 || b.r < 0 || b.N % 8 != 0 || b.lddy < b.N || b.r > kGradRanks || b.r % 8 != 0) return QERL_ERR_SHAPE;
+    any = any || b.r > 0;
+  }
+  if (M == 0) return 1;   // nothing to do
+  if (K == 0) return QERL_ERR_SHAPE;
+  for (int i = 0; i < n; ++i) if (mem[i].N == 0) return QERL_ERR_SHAPE;
+  if (!dx) return QERL_ERR_NULL;
+  if (any && !x) return QERL_ERR_NULL;
+  for (int i = 0; i < n; ++i) {
+    const BackwardMember& b = mem[i];
+    if (!b.dy || !b.packed_t || !b.tensor_scale) return QERL_ERR_NULL;
+    if (b.r > 0 && (!b.A || !b.B || !b.dA || !b.dB)) return QERL_ERR_NULL;
+  }
+  if (!aligned(dx, 2)) return QERL_ERR_ALIGN;
+  if (any && (!aligned(x, 16) || ldx % 8 != 0)) return QERL_ERR_ALIGN;
+  for (int i = 0; i < n; ++i) {
+    const BackwardMember& b = mem[i];
+    if (!aligned(b.dy, 16) || b.lddy % 8 != 0 || !aligned(b.packed_t, 16)) return QERL_ERR_ALIGN;
+    if (b.r > 0 && (!aligned(b.A, 16) || !aligned(b.B, 16) || !aligned(b.dA, 4) || !aligned(b.dB, 4))) return QERL_ERR_ALIGN;
+  }
+  return QERL_OK;
+}
+
+// The members' launches: per member one that transposes its adapter, one down-projection of its own dY, and four
+// for its gradient products; shared by the group: the down-projections of x (one launch over all adapters) and dX,
+// ONE GEMM whose contraction runs over the members' rows one after the other, so that dX is summed in fp32 and
+// rounded once.
+static int backward_run(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const BackwardMember* mem, int n, uint16_t* dx, int64_t lddx,
+                        void* workspace, size_t workspace_bytes, hipStream_t st) {
+  int64_t Ns[kMaxGroup], rs[kMaxGroup];
+  for (int i = 0; i < n; ++i) { Ns[i] = mem[i].N; rs[i] = mem[i].r; }
+  const BackwardLayout L = backward_layout(M, K, Ns, rs, n);
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total) return QERL_ERR_WORKSPACE;
+  uint8_t* ws = (uint8_t*)workspace;
+  uint32_t* counters = (uint32_t*)(ws + L.ctr_off);
+  float* part = (float*)(ws + L.part_off);
+  int rc = QERL_OK;
+  GemmArgs down{};   // t_i = x A_i^T of all adapters, one launch
+  down.x = x; down.ldx = ldx; down.M = M; down.K = K; down.k_tiles = ceil_div(K, kPackTileK);
+  down.tpart = (uint32_t*)part; down.counters = counters;
+  int tiles = 0;
+  for (int i = 0; i < n; ++i) {
+    const BackwardMember& b = mem[i];
+    if (b.r == 0) continue;
+    const BackwardMemberLayout& l = L.mem[i];
+    uint16_t* AT = (uint16_t*)(ws + l.at_off);
+    uint16_t* BT = (uint16_t*)(ws + l.bt_off);
+    const int blocks_a = grid_for(b.r * K), blocks_b = grid_for(b.N * b.r);
+    backward_prepare_kernel<<<dim3((unsigned)(blocks_a + blocks_b + 1)), dim3(256), 0, st>>>(
+        b.A, b.r, K, AT, b.B, b.N, BT, blocks_a, blocks_b, counters, kDownMaxSlots);
+    if ((rc = launch_status()) != QERL_OK) return rc;
+    // U_i = dY_i B_i as three bf16 terms of (lora_scale / S32) times the product
+    GemmArgs d{};
+    d.x = b.dy; d.ldx = b.lddy; d.M = M; d.K = b.N; d.k_tiles = ceil_div(b.N, kPackTileK);
+    d.N = b.r; d.wbf16 = BT; d.n_tiles = (int)ceil_div(b.r, 32); d.ts = (const uint16_t*)(ws + l.tsu_off); d.ts_ld = l.ts_ld; d.ext_stages = l.ext_stages;
+    d.r = (int)b.r; d.lora_scale = b.lora_scale; d.tensor_scale = b.tensor_scale;
+    d.tpart = (uint32_t*)part; d.counters = counters;   // K split over workgroups while token blocks alone do not fill the chip
+    if ((rc = launch_lora_down_gemm(d, st)) != QERL_OK) return rc;
+    const int gi = down.g_n++;
+    down.g_tile0[gi] = tiles; down.g_A[gi] = b.A; down.g_ts[gi] = (const uint16_t*)(ws + l.tst_off); down.g_ts_ld[gi] = l.ts_ld;
+    down.g_r[gi] = (int)b.r; down.g_lora_scale[gi] = b.lora_scale; down.g_tensor_scale[gi] = b.tensor_scale;
+    tiles += (int)ceil_div(b.r, 32);
+  }
+  if (down.g_n > 0) {
+    down.g_tile0[down.g_n] = tiles;
+    if ((rc = launch_lora_down_gemm(down, st)) != QERL_OK) return rc;
+  }
+  {
+    GemmArgs g{};
+    g.M = M; g.N = K; g.n_tiles = (int)ceil_div(K, 32); g.y = dx; g.ldy = lddx; g.transposed = 1;
+    g.seg_n = n;
+    int64_t rows = 0;
+    for (int i = 0; i < n; ++i) {
+      const BackwardMember& b = mem[i];
+      const BackwardMemberLayout& l = L.mem[i];
+      GemmSeg& sgm = g.seg[i];
+      sgm.x = b.dy; sgm.ldx = b.lddy; sgm.K = b.N; sgm.packed = b.packed_t; sgm.k_tiles = ceil_div(b.N, kPackTileK);
+      sgm.tensor_scale = b.tensor_scale;
+      if (b.r > 0) {
+        sgm.ts = (const uint16_t*)(ws + l.tsu_off); sgm.ts_ld = l.ts_ld; sgm.ext_stages = l.ext_stages;
+        sgm.B = (const uint16_t*)(ws + l.at_off); sgm.r = (int)b.r;
+      }
+      rows += b.N;
+    }
+    // the launcher's own fields describe the first segment (it validates them; the kernel reads the segments)
+    g.x = g.seg[0].x; g.ldx = g.seg[0].ldx; g.K = rows; g.k_tiles = g.seg[0].k_tiles; g.packed = g.seg[0].packed; g.tensor_scale = g.seg[0].tensor_scale;
+    if ((rc = launch_gemm(g, st)) != QERL_OK) return rc;
+  }
+  for (int i = 0; i < n; ++i) {
+    const BackwardMember& b = mem[i];
+    if (b.r == 0) continue;
+    const BackwardMemberLayout& l = L.mem[i];
+    // the three-term values carry lora_scale / S32; the gradients want lora_scale: one multiplication by S32
+    const dim3 blk(256);
+    lora_grad_partial_kernel<true><<<dim3((unsigned)ceil_div(K, 128), (unsigned)L.n_chunks), blk, 0, st>>>(
+        (const uint16_t*)(ws + l.tsu_off), l.ts_ld, (int)b.r, x, ldx, M, K, L.tokens_per_chunk, part);
+    lora_grad_reduce_kernel<<<dim3((unsigned)grid_for(K * b.r)), blk, 0, st>>>(part, L.n_chunks, K, (int)b.r, b.tensor_scale, 1, b.dA);
+    lora_grad_partial_kernel<false><<<dim3((unsigned)ceil_div(b.N, 128), (unsigned)L.n_chunks), blk, 0, st>>>(
+        (const uint16_t*)(ws + l.tst_off), l.ts_ld, (int)b.r, b.dy, b.lddy, M, b.N, L.tokens_per_chunk, part);
+    lora_grad_reduce_kernel<<<dim3((unsigned)grid_for(b.N * b.r)), blk, 0, st>>>(part, L.n_chunks, b.N, (int)b.r, b.tensor_scale, 0, b.dB);
+    if ((rc = launch_status()) != QERL_OK) return rc;
+  }
+  return rc;
 }
 
 }  // namespace qerl
@@ -264,65 +397,39 @@ extern "C" int nvfp4_prepack_t(const uint8_t* codes, const uint8_t* scales, int6
 }
 
 extern "C" size_t nvfp4_lora_linear_backward_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t r) {
-  return backward_layout(M, N, K, r).total;
+  const size_t t = backward_layout(M, K, &N, &r, 1).total;
+  return t ? t : 256;
 }
 
 extern "C" int nvfp4_lora_linear_backward(const void* x, const void* dy, int64_t M, int64_t K, int64_t N, int64_t ldx, int64_t lddy,
                                           const void* packed_t, const float* tensor_scale, const void* A, const void* B,
                                           int64_t r, float lora_scale, void* dx, int64_t lddx, float* dA, float* dB,
                                           void* workspace, size_t workspace_bytes, void* stream) {
-  if (M < 0 || N < 0 || K < 0 || r < 0 || K % kBlock != 0 || N % 8 != 0 || ldx < K || lddy < N || lddx < K) return QERL_ERR_SHAPE;
-  if (r > kGradRanks || r % 8 != 0) return QERL_ERR_SHAPE;
-  if (M == 0 || N == 0 || K == 0) return M == 0 ? QERL_OK : QERL_ERR_SHAPE;
-  if (!dy || !dx || !packed_t || !tensor_scale) return QERL_ERR_NULL;
-  if (r > 0 && (!x || !A || !B || !dA || !dB)) return QERL_ERR_NULL;
-  if (!aligned(dy, 16) || lddy % 8 != 0 || !aligned(packed_t, 16) || !aligned(dx, 2)) return QERL_ERR_ALIGN;
-  if (r > 0 && (!aligned(x, 16) || ldx % 8 != 0 || !aligned(A, 16) || !aligned(B, 16) || !aligned(dA, 4) || !aligned(dB, 4)))
-    return QERL_ERR_ALIGN;
-  const BackwardLayout L = backward_layout(M, N, K, r);
-  if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total) return QERL_ERR_WORKSPACE;
-  uint8_t* ws = (uint8_t*)workspace;
-  hipStream_t st = (hipStream_t)stream;
-  uint16_t* AT = (uint16_t*)(ws + L.at_off);
-  uint16_t* BT = (uint16_t*)(ws + L.bt_off);
-  uint16_t* tsU = (uint16_t*)(ws + L.tsu_off);
-  uint16_t* tsT = (uint16_t*)(ws + L.tst_off);
-  float* part = (float*)(ws + L.part_off);
-  int rc = QERL_OK;
-  if (r > 0) {
-    const int blocks_a = grid_for(r * K), blocks_b = grid_for(N * r);
-    backward_prepare_kernel<<<dim3((unsigned)(blocks_a + blocks_b + 1)), dim3(256), 0, st>>>(
-        (const uint16_t*)A, r, K, AT, (const uint16_t*)B, N, BT, blocks_a, blocks_b, (uint32_t*)(ws + L.ctr_off), kDownMaxSlots);
-    if ((rc = launch_status()) != QERL_OK) return rc;
-    // U = dY B and t = x A^T, each as three bf16 terms of (lora_scale / S32) times the product
-    GemmArgs d{};
-    d.x = (const uint16_t*)dy; d.ldx = lddy; d.M = M; d.K = N; d.k_tiles = ceil_div(N, kPackTileK);
-    d.N = r; d.wbf16 = BT; d.n_tiles = (int)ceil_div(r, 32); d.ts = tsU; d.ts_ld = L.ts_ld; d.ext_stages = L.ext_stages;
-    d.r = (int)r; d.lora_scale = lora_scale; d.tensor_scale = tensor_scale;
-    d.tpart = (uint32_t*)part; d.counters = (uint32_t*)(ws + L.ctr_off);   // K split over workgroups while token blocks alone do not fill the chip
-    if ((rc = launch_lora_down_gemm(d, st)) != QERL_OK) return rc;
-    d.x = (const uint16_t*)x; d.ldx = ldx; d.K = K; d.k_tiles = ceil_div(K, kPackTileK); d.wbf16 = (const uint16_t*)A; d.ts = tsT;
-    if ((rc = launch_lora_down_gemm(d, st)) != QERL_OK) return rc;
+  const BackwardMember b{(const uint16_t*)dy, lddy, N, (const uint8_t*)packed_t, tensor_scale, (const uint16_t*)A, (const uint16_t*)B, r, lora_scale, dA, dB};
+  const int vr = backward_validate(x, M, K, ldx, &b, 1, dx, lddx);
+  if (vr != QERL_OK) return vr > 0 ? QERL_OK : vr;
+  return backward_run((const uint16_t*)x, M, K, ldx, &b, 1, (uint16_t*)dx, lddx, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+extern "C" size_t nvfp4_lora_linear_backward_group_workspace_bytes(int64_t M, int64_t K, const qerl_backward_desc* members, int n_members) {
+  if (!members || n_members < 1 || n_members > kMaxGroup) return 0;
+  int64_t Ns[kMaxGroup], rs[kMaxGroup];
+  for (int i = 0; i < n_members; ++i) { Ns[i] = members[i].N; rs[i] = members[i].r; }
+  const size_t t = backward_layout(M, K, Ns, rs, n_members).total;
+  return t ? t : 256;
+}
+
+extern "C" int nvfp4_lora_linear_backward_group(const void* x, int64_t M, int64_t K, int64_t ldx, const qerl_backward_desc* members,
+                                                int n_members, void* dx, int64_t lddx, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!members) return QERL_ERR_NULL;
+  if (n_members < 1 || n_members > kMaxGroup) return QERL_ERR_SHAPE;
+  BackwardMember b[kMaxGroup];
+  for (int i = 0; i < n_members; ++i) {
+    const qerl_backward_desc& d = members[i];
+    b[i] = BackwardMember{(const uint16_t*)d.dy_bf16, d.lddy, d.N, (const uint8_t*)d.packed_t, d.tensor_scale, (const uint16_t*)d.A_bf16,
+                          (const uint16_t*)d.B_bf16, d.r, d.lora_scale, d.dA_f32, d.dB_f32};
   }
-  {
-    GemmArgs g{};
-    g.x = (const uint16_t*)dy; g.ldx = lddy; g.M = M; g.K = N; g.k_tiles = ceil_div(N, kPackTileK);
-    g.N = K; g.packed = (const uint8_t*)packed_t; g.n_tiles = (int)ceil_div(K, 32); g.tensor_scale = tensor_scale;
-    g.ts = r > 0 ? tsU : nullptr; g.ts_ld = r > 0 ? L.ts_ld : 0; g.ext_stages = r > 0 ? L.ext_stages : 0;
-    g.B = r > 0 ? AT : nullptr; g.r = (int)r; g.lora_scale = lora_scale;
-    g.y = (uint16_t*)dx; g.ldy = lddx; g.transposed = 1;
-    if ((rc = launch_gemm(g, st)) != QERL_OK) return rc;
-  }
-  if (r > 0) {
-    // the three-term values carry lora_scale / S32; the gradients want lora_scale: one multiplication by S32
-    const dim3 blk(256);
-    lora_grad_partial_kernel<true><<<dim3((unsigned)ceil_div(K, 128), (unsigned)L.n_chunks), blk, 0, st>>>(
-        tsU, L.ts_ld, (int)r, (const uint16_t*)x, ldx, M, K, L.tokens_per_chunk, part);
-    lora_grad_reduce_kernel<<<dim3((unsigned)grid_for(K * r)), blk, 0, st>>>(part, L.n_chunks, K, (int)r, tensor_scale, 1, dA);
-    lora_grad_partial_kernel<false><<<dim3((unsigned)ceil_div(N, 128), (unsigned)L.n_chunks), blk, 0, st>>>(
-        tsT, L.ts_ld, (int)r, (const uint16_t*)dy, lddy, M, N, L.tokens_per_chunk, part);
-    lora_grad_reduce_kernel<<<dim3((unsigned)grid_for(N * r)), blk, 0, st>>>(part, L.n_chunks, N, (int)r, tensor_scale, 0, dB);
-    rc = launch_status();
-  }
-  return rc;
+  const int vr = backward_validate(x, M, K, ldx, b, n_members, dx, lddx);
+  if (vr != QERL_OK) return vr > 0 ? QERL_OK : vr;
+  return backward_run((const uint16_t*)x, M, K, ldx, b, n_members, (uint16_t*)dx, lddx, workspace, workspace_bytes, (hipStream_t)stream);
 }

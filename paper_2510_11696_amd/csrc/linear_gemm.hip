@@ -74,8 +74,15 @@ __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
   for (int i = 1; i < kMaxGroup; ++i) mi = (i < a.m_n && nb >= a.m[i].block_begin) ? i : mi;
   const GemmMember& mem = a.m[__builtin_amdgcn_readfirstlane(mi)];
   const int nt0 = ((nb - mem.block_begin) * W + wave) * NT;
-  const int64_t n_stages = ceil_div_dev(a.K, 64);
-  const int64_t s_begin = 0, s_end = n_stages;
+  // The contraction's source: the launch's x and the member's tiles, or (TR) one segment after the other
+  const uint16_t* sx = a.x;
+  int64_t sldx = a.ldx, sK = a.K, skt = a.k_tiles;
+  const uint8_t* spk = mem.packed;
+  const uint16_t* sts = mem.ts;
+  int64_t sts_ld = mem.ts_ld;
+  int sext = mem.ext_stages, sr = mem.r;
+  const uint16_t* sB = mem.B;
+  const float* sscale = mem.tensor_scale;
 
   f32x16 acc[MT][NT];
 #pragma unroll
@@ -112,7 +119,7 @@ __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
     for (int nt = 0; nt < NT; ++nt) {
       int tile = nt0 + nt;
       tile = tile < mem.n_tiles ? tile : mem.n_tiles - 1;
-      const uint8_t* base = mem.packed + ((int64_t)tile * a.k_tiles + (s >> 1)) * kPackTileBytes;
+      const uint8_t* base = spk + ((int64_t)tile * skt + (s >> 1)) * kPackTileBytes;
       const int plane = (int)(s & 1);
       wr.c[nt] = *reinterpret_cast<const u32x4*>(base + plane * 1024 + lane * 16);
       wr.sc[nt] = 0u;
@@ -126,7 +133,7 @@ __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
     if (tid < W * NT * 8) {
       int tile = (nb - mem.block_begin) * W * NT + sc_tl;
       tile = tile < mem.n_tiles ? tile : mem.n_tiles - 1;
-      const uint8_t* base = mem.packed + ((int64_t)tile * a.k_tiles + (s >> 1)) * kPackTileBytes;
+      const uint8_t* base = spk + ((int64_t)tile * skt + (s >> 1)) * kPackTileBytes;
       r = *reinterpret_cast<const u32x4*>(base + 2048 + (int)(s & 1) * 128 + sc_part * 16);
     }
   };
@@ -198,6 +205,14 @@ __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
   // per stage): a stage lasts a few hundred nanoseconds, a memory round trip several times that.  The loop is
   // unrolled over the ring so that every register index is a constant; requests past the end are redirected to
   // the last stage rather than branched around, which keeps the compiler's wait counts exact.
+  const int n_seg = TR ? a.seg_n : 1;
+  for (int sg = 0; sg < n_seg; ++sg) {
+  if constexpr (TR) {
+    const GemmSeg& g = a.seg[sg];                           // uniform index: scalar loads
+    sx = g.x; sldx = g.ldx; sK = g.K; skt = g.k_tiles; spk = g.packed;
+    sts = g.ts; sts_ld = g.ts_ld; sext = g.ext_stages; sr = g.r; sB = g.B; sscale = g.tensor_scale;
+  }
+  const int64_t s_begin = 0, s_end = ceil_div_dev(sK, 64);
   if (s_begin < s_end) {
     constexpr int R = kGemmRing, PX = kGemmXAhead;
     WeightRegs<NT> wring[R];
@@ -207,7 +222,7 @@ __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
     auto clamp_s = [&](int64_t s) { return s < s_last ? s : s_last; };
 #pragma unroll
     for (int p = 0; p < PX; ++p) {
-      gload_x(xring[p], a.x, a.ldx, a.K, clamp_s(s_begin + p));
+      gload_x(xring[p], sx, sldx, sK, clamp_s(s_begin + p));
       if constexpr (TR) gload_sc(scring[p], clamp_s(s_begin + p));
     }
 #pragma unroll
@@ -220,7 +235,7 @@ __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
     }
     __syncthreads();
     auto stage = [&](int64_t s, int u) {
-      gload_x(xring[u % PX], a.x, a.ldx, a.K, clamp_s(s + PX));
+      gload_x(xring[u % PX], sx, sldx, sK, clamp_s(s + PX));
       if constexpr (TR) gload_sc(scring[u % PX], clamp_s(s + PX));
       gload_w(wring[(u + R - 1) % R], clamp_s(s + R - 1));
       if constexpr (TR) compute_tr(u & 1, wring[u]);
@@ -245,9 +260,9 @@ main_done:
   {
     // ---- LoRA up-projection: 3r extra columns  [hi | mid | lo] . [B ; B ; B]^T.  ts already carries
     // the factor lora_scale / S32, so one multiplication by S32 at the end scales both branches.
-    for (int e = 0; e < mem.ext_stages; ++e) {
+    for (int e = 0; e < sext; ++e) {
       u32x4 xe[XL];
-      gload_x(xe, mem.ts, mem.ts_ld, mem.ts_ld, e);
+      gload_x(xe, sts, sts_ld, sts_ld, e);
       swrite_x(0, xe);
       __syncthreads();
 #pragma unroll
@@ -259,14 +274,29 @@ main_done:
           row = row < mem.N ? row : mem.N - 1;
           const int c = e * 64 + 16 * j + 8 * kg;
           u32x4 b = {0u, 0u, 0u, 0u};
-          if (c < 3 * mem.r) b = *reinterpret_cast<const u32x4*>(mem.B + row * mem.r + (c % mem.r));
+          if (c < 3 * sr) b = *reinterpret_cast<const u32x4*>(sB + row * sr + (c % sr));
           wf[nt] = __builtin_bit_cast(bf16x8, b);
         }
         mma_step(xs, j, wf);
       }
       __syncthreads();
     }
-    const float S32 = *mem.tensor_scale;
+    if constexpr (TR) {
+      // the sums so far are in units of this segment's tensor scale: put them into the next segment's
+      if (sg + 1 < n_seg) {
+        const float f = *sscale / *a.seg[sg + 1].tensor_scale;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mt][nt][i] *= f;
+      }
+    }
+  }
+  }   // segments
+  {
+    const float S32 = *sscale;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -567,6 +597,21 @@ int launch_gemm(const GemmArgs& a0, hipStream_t st) {
   };
   double t_single = 0;
   int best = best_cfg(a.m, a.m_n, t_single);
+  if (a.transposed) {
+    if (a.m_n != 1 || a.seg_n < 0 || a.seg_n > kMaxGroup) return QERL_ERR_SHAPE;
+    if (a.seg_n == 0) {   // one segment: the launch's x and the member's tiles
+      const GemmMember& m = a.m[0];
+      a.seg_n = 1;
+      a.seg[0] = GemmSeg{a.x, a.ldx, a.K, m.packed, a.k_tiles, m.tensor_scale, m.ts, m.ts_ld, m.ext_stages, m.B, m.r};
+    }
+    for (int i = 0; i < a.seg_n; ++i) {
+      const GemmSeg& g = a.seg[i];
+      if (!g.x || !g.packed || !g.tensor_scale || (g.r > 0 && (!g.ts || !g.B))) return QERL_ERR_NULL;
+      if (g.K < 8 || g.ldx < g.K || g.k_tiles < 1 || g.r < 0 || (g.r > 0 && g.ts_ld < 3 * g.r) || g.ext_stages * 64 < 3 * g.r ||
+          (int64_t)g.ext_stages * 64 > (g.r > 0 ? g.ts_ld : 0))
+        return QERL_ERR_SHAPE;
+    }
+  }
   if (a.transposed) return best == 5 ? launch_cfg<4, 1, 10, true>(a, st) : launch_cfg<4, 2, 8, true>(a, st);
   if (g_force_cfg >= 0) best = g_force_cfg;
   auto launch_one = [&](int c, const GemmArgs& b) -> int {

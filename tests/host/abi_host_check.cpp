@@ -28,8 +28,24 @@ int main() {
       bad += nvfp4_lora_linear_workspace_bytes(M, 27648, H, 64) == 0;
       bad += nvfp4_lora_linear_swiglu_workspace_bytes(M, H, 27648, 64) == 0;
       bad += nvfp4_lora_linear_backward_workspace_bytes(M, 27648, H, 64) == 0;
-      plans += 4;
+      bad += mxfp4_lora_linear_native_workspace_bytes(M, 27648, H, 64) < mxfp4_linear_native_workspace_bytes(M, 27648, H);
+      qerl_backward_desc bd[3] = {};
+      for (int i = 0; i < 3; ++i) { bd[i].N = Ns[i]; bd[i].r = 64; }
+      bad += nvfp4_lora_linear_backward_group_workspace_bytes(M, H, bd, 3) < nvfp4_lora_linear_backward_workspace_bytes(M, H, H, 64);
+      plans += 6;
     }
+  {
+    // the new entry points' validation: descriptors on the host, nothing launched
+    qerl_backward_desc bd[2] = {};
+    for (auto& d : bd) { d.dy_bf16 = fake; d.lddy = 32; d.N = 32; d.packed_t = fake; d.tensor_scale = (const float*)fake; d.r = 0; }
+    bad += nvfp4_lora_linear_backward_group(nullptr, 4, 64, 64, bd, 2, fake, 64, nullptr, 0, nullptr) != QERL_ERR_WORKSPACE;
+    bd[1].N = 30;
+    bad += nvfp4_lora_linear_backward_group(nullptr, 4, 64, 64, bd, 2, fake, 64, fake, 1 << 20, nullptr) != QERL_ERR_SHAPE;
+    bad += nvfp4_lora_linear_backward_group(nullptr, 4, 64, 64, bd, 5, fake, 64, fake, 1 << 20, nullptr) != QERL_ERR_SHAPE;
+    bad += mxfp4_lora_linear_native(fake, 4, 64, 64, fake, 8, fake, fake, 12, 1.f, nullptr, fake, 8, fake, 1 << 30, nullptr) != QERL_ERR_SHAPE;
+    bad += mxfp4_lora_linear_native(fake, 4, 64, 64, fake, 8, nullptr, fake, 8, 1.f, nullptr, fake, 8, fake, 1 << 30, nullptr) != QERL_ERR_NULL;
+    bad += mxfp4_lora_linear_native(fake, 4, 64, 64, fake, 8, nullptr, nullptr, 0, 0.f, nullptr, fake, 8, fake, 16, nullptr) != QERL_ERR_WORKSPACE;
+  }
   bad += nvfp4_prepack_bytes(27648, 5120) != (size_t)864 * 40 * 2304;
   printf("host check: %ld sizing calls, %d unexpected results\n", plans, bad);
   return bad != 0;

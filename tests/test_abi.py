@@ -230,6 +230,41 @@ def test_host_side_validation_of_the_fused_entry_points(lib):
     assert lib.nvfp4_prepack_t(None, fake, 4, 32, fake, None) == -1
     assert lib.nvfp4_lora_linear_backward_workspace_bytes(2048, 13824, 5120, 64) < 64 << 20
 
+    # the grouped form: a HOST array of descriptors
+    from paper_2510_11696_amd.binding import _BackwardDesc
+    bg = lib.nvfp4_lora_linear_backward_group
+
+    def group(n=2, M=4, K=64, ldx=64, lddx=64, x=fake, dx=fake, ws=fake, wsb=big, edit=None):
+        descs = (_BackwardDesc * max(n, 1))()
+        for d in descs:
+            d.dy, d.lddy, d.N, d.packed_t, d.tensor_scale = fake, 32, 32, fake, fake
+            d.A, d.B, d.r, d.lora_scale, d.dA, d.dB = fake, fake, 8, 1.0, fake, fake
+        if edit:
+            edit(descs)
+        return bg(x, M, K, ldx, ctypes.cast(descs, ctypes.c_void_p), n, dx, lddx, ws, wsb, None), descs
+    assert group(M=0)[0] == 0
+    assert group(n=0)[0] == -2 and group(n=5)[0] == -2
+    assert bg(fake, 4, 64, 64, None, 2, fake, 64, fake, big, None) == -1
+    assert group(K=40, ldx=40, lddx=40)[0] == -2 and group(lddx=32)[0] == -2
+    assert group(edit=lambda d: setattr(d[1], "N", 30))[0] == -2           # N % 8 of the second member
+    assert group(edit=lambda d: setattr(d[1], "r", 72))[0] == -2
+    assert group(edit=lambda d: setattr(d[1], "dy", None))[0] == -1 and group(edit=lambda d: setattr(d[0], "dB", None))[0] == -1
+    assert group(x=None)[0] == -1 and group(dx=None)[0] == -1
+    assert group(edit=lambda d: setattr(d[1], "A", fake + 8))[0] == -3 and group(edit=lambda d: setattr(d[1], "lddy", 36))[0] == -3
+    assert group(wsb=64)[0] == -4 and group(ws=fake + 16)[0] == -4
+
+    def no_adapters(d):
+        for e in d:
+            e.A = e.B = e.dA = e.dB = None
+            e.r = 0
+    assert group(x=None, ws=None, edit=no_adapters)[0] == -4                  # no adapter anywhere: x is not read; a workspace still is
+    _, descs = group()
+    gb = lib.nvfp4_lora_linear_backward_group_workspace_bytes
+    assert gb(4, 64, ctypes.cast(descs, ctypes.c_void_p), 0) == 0 and gb(4, 64, None, 2) == 0
+    one = gb(2048, 5120, ctypes.cast(descs, ctypes.c_void_p), 1)
+    assert one == lib.nvfp4_lora_linear_backward_workspace_bytes(2048, 32, 5120, 8)
+    assert one < gb(2048, 5120, ctypes.cast(descs, ctypes.c_void_p), 2) < 2 * one
+
     nd = lib.aqn_rmsnorm_lora_down
     A = (ctypes.c_void_p * 5)(*([fake] * 5)); T = (ctypes.c_void_p * 5)(*([fake] * 5))
     R = (ctypes.c_int64 * 5)(32, 32, 32, 32, 32)

@@ -114,3 +114,54 @@ def test_backward_of_one_hot_gradients_reads_dequantised_rows():
     What = oracle.nvfp4_dequantize(codes, scales, ts)
     want = torch.from_numpy(What[rows].astype(np.float32)).to(torch.bfloat16).float().numpy()
     assert np.array_equal(dx.float().cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("M,K,Ns,rs", [
+    (1, 64, (64, 8), (8, 8)),
+    (40, 320, (160, 96, 96), (16, 16, 0)),            # q / k / v shaped; one member without an adapter
+    (130, 2112, (1000, 1000), (32, 32)),              # gate / up shaped, ragged everywhere
+    (300, 512, (512, 128, 128), (32, 32, 32)),
+    (520, 1024, (520, 264, 8, 1024), (64, 8, 0, 24)),  # four members, the 64-token down-projection kernel, a contraction of eight rows
+    (2048, 3584, (3584, 512, 512), (32, 32, 32)),     # the 7B attention projections at a training batch
+])
+def test_group_backward_equals_oracle(M, K, Ns, rs):
+    """dX summed over the members in one GEMM (members with different tensor scales), every member's dA and dB; one
+    rounding of dX to bf16, so it is held to the linear's gate against the oracle's float64 sum."""
+    print("backward group case", M, K, Ns, rs, flush=True)
+    g = lambda a: torch.from_numpy(a).cuda()
+    x = qs.activations(M, K, 9200 + M)
+    members, weights, dys, As, Bs, scales_ = [], [], [], [], [], []
+    for i, (N, r) in enumerate(zip(Ns, rs)):
+        W = cases.gaussian(N, K, 9100 + M + i) * (1.0 + 3.0 * i)           # tensor scales differ from member to member
+        codes, scales, ts = oracle.nvfp4_quantize(W)
+        dy = qs.activations(M, N, 9300 + M + i, std=0.5)
+        mem = {"dy": dy.float().numpy(), "codes": codes, "scales": scales, "tensor_scale": ts}
+        A = B = None
+        if r:
+            A, B = qs.lora_pair(N, K, r, 9400 + M + i, b_std=0.05)
+            mem.update(A=A.float().numpy(), B=B.float().numpy(), lora_scale=1.0 + 0.5 * i)
+        members.append(mem)
+        weights.append(qerl.nvfp4_prepack_t(g(codes), g(scales), torch.tensor([ts], device="cuda")))
+        dys.append(dy.cuda()); As.append(A.cuda() if r else None); Bs.append(B.cuda() if r else None); scales_.append(1.0 + 0.5 * i)
+    dx_ref, grads_ref = oracle.nvfp4_lora_linear_backward_group(x.float().numpy(), members)
+    dx, grads = qerl.nvfp4_lora_linear_backward_group(x.cuda(), dys, weights, As, Bs, scales_)
+    torch.cuda.synchronize()
+    check_linear(dx, dx_ref, ("group dx", M, K, Ns, rs))
+    for i, ((dA, dB), (dA_ref, dB_ref)) in enumerate(zip(grads, grads_ref)):
+        if rs[i]:
+            _check_f32(dA, dA_ref, ("group dA", i, M, K, Ns, rs))
+            _check_f32(dB, dB_ref, ("group dB", i, M, K, Ns, rs))
+        else:
+            assert dA is None and dB is None
+    again = qerl.nvfp4_lora_linear_backward_group(x.cuda(), dys, weights, As, Bs, scales_)
+    assert torch.equal(dx, again[0])
+    for (a0, b0), (a1, b1) in zip(grads, again[1]):
+        assert (a0 is None and a1 is None) or (torch.equal(a0, a1) and torch.equal(b0, b1))
+    # a group of one is the single call, bit for bit; dA_i depends on dY_i B_i alone, which both calls compute alike
+    i = 0
+    single = qerl.nvfp4_lora_linear_backward(x.cuda(), dys[i], weights[i], As[i], Bs[i], scales_[i])
+    one = qerl.nvfp4_lora_linear_backward_group(x.cuda(), dys[:1], weights[:1], As[:1], Bs[:1], scales_[:1])
+    assert torch.equal(one[0], single[0])
+    if rs[i]:
+        assert torch.equal(one[1][0][0], single[1]) and torch.equal(one[1][0][1], single[2])
+        assert torch.equal(grads[i][0], single[1])

@@ -140,3 +140,49 @@ def test_mx_linear_launches_replay_like_eager(M):
         held["y"] = qerl.mxfp4_linear_native(x, pw)
 
     _replays_match(run, lambda: [held["y"]])
+
+
+@pytest.mark.parametrize("M", [8, 200])
+def test_mx_lora_linear_launches_replay_like_eager(M):
+    """The down-projection's K-parts count their arrivals in the workspace and leave the counters at zero: replays and
+    eager calls through the same workspace agree."""
+    print("graph case: mx lora linear, M =", M, flush=True)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(95 + M)
+    N, K, r = 1536, 2048, 32
+    codes = torch.randint(0, 256, (N, K // 2), device="cuda", dtype=torch.uint8, generator=gen)
+    scales = torch.randint(118, 126, (N, K // 32), device="cuda", dtype=torch.uint8, generator=gen)
+    pw = qerl.mxfp4_prepack(codes, scales)
+    x = torch.randn((M, K), device="cuda", generator=gen).to(torch.bfloat16)
+    A = (torch.randn((r, K), device="cuda", generator=gen) / r).to(torch.bfloat16)
+    B = (torch.randn((N, r), device="cuda", generator=gen) * 0.05).to(torch.bfloat16)
+    bias = torch.randn((N,), device="cuda", generator=gen).to(torch.bfloat16)
+    ws = qerl.Workspace(qerl.load_library().mxfp4_lora_linear_native_workspace_bytes(M, N, K, r))
+    y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+
+    def run():
+        qerl.mxfp4_lora_linear_native(x, pw, A, B, 2.0, bias, workspace=ws, out=y)
+
+    _replays_match(run, lambda: [y])
+
+
+@pytest.mark.parametrize("M", [24, 300])
+def test_group_backward_launches_replay_like_eager(M):
+    print("graph case: backward group, M =", M, flush=True)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(75 + M)
+    K, r = 1024, 32
+    members = [_weights(N, K, r, gen, transposed=True) for N in (1024, 256, 256)]
+    x = torch.randn((M, K), device="cuda", generator=gen).to(torch.bfloat16)
+    dys = [torch.randn((M, N), device="cuda", generator=gen).to(torch.bfloat16) for N in (1024, 256, 256)]
+    held = {}
+    first = qerl.nvfp4_lora_linear_backward_group(x, dys, [m[0] for m in members], [m[1] for m in members], [m[2] for m in members], [2.0] * 3)
+    need = 64 << 20
+    ws = torch.empty((need,), dtype=torch.uint8, device="cuda")
+
+    def run():
+        held["out"] = qerl.nvfp4_lora_linear_backward_group(x, dys, [m[0] for m in members], [m[1] for m in members],
+                                                            [m[2] for m in members], [2.0] * 3, workspace=ws)
+
+    _replays_match(run, lambda: [held["out"][0]] + [t for pair in held["out"][1] for t in pair])
+    assert torch.equal(first[0], held["out"][0])

@@ -56,6 +56,14 @@ static WorkspaceLayout workspace_layout(int64_t M, int64_t N, int64_t K, int64_t
     need = need > mid ? need : mid;
   }
   if (M > 128 && need < kDownExchangeBytes) need = kDownExchangeBytes;   // K-parts of the prefill path's LoRA down-projection
+  if (M > 16) {
+    // the GEMM path from g_gemm_min_tokens on: a down-projection launched by itself has the whole area for its K-part
+    // sums and is through with it when the GEMM starts; one that rides inside the GEMM launch needs the first
+    // kFusedDownBytes at most, and the GEMM's own K-parts start behind them
+    size_t g = kFusedDownBytes + gemm_split_bytes(M, N);
+    g = g > kDownExchangeBytes ? g : kDownExchangeBytes;
+    need = need > g ? need : g;
+  }
   L.total = L.partial_off + align256(need);
   return L;
 }
@@ -208,6 +216,7 @@ extern "C" int nvfp4_lora_linear(const void* x, int64_t M, int64_t K, int64_t ld
 
 namespace qerl {
 static bool g_use_stream = true;
+static int g_gemm_min_tokens = 96;   // from here on the prefill GEMM (K split over workgroups where the tiles alone would not fill the chip) beats the 17..128-token kernel
 static int64_t g_mid_gemm_min_rows = 16384;   // 65..128 tokens: groups with at least this many output rows go to the prefill GEMM
 static int64_t g_mid_producer_bytes = 24 << 20;   // 17..128 tokens: LoRA down-projections run inside the main launch when it streams at least this many packed bytes (long enough to hide them)
 
@@ -322,6 +331,28 @@ static int mid_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const
   }
   return launch_mid(g, st);
 }
+// The GEMM launch and the LoRA down-projections it depends on (dn: the group form, tiles rank tiles; g_n == 0: none).
+// launch_gemm either takes the down-projections into its own launch (few tokens) or runs them first; the scratch
+// serves the down-projection's K-parts from its front and the GEMM's own K-parts from kFusedDownBytes on (inside
+// one launch both are alive at once, and the down-projection stays below that mark).
+static int gemm_with_down(GemmArgs& g, GemmArgs& dn, int tiles, int64_t n_sum, uint8_t* ws, const WorkspaceLayout& L, hipStream_t st) {
+  if (dn.g_n > 0) {
+    dn.g_tile0[dn.g_n] = tiles;
+    g.g_n = dn.g_n;
+    for (int i = 0; i <= dn.g_n; ++i) g.g_tile0[i] = dn.g_tile0[i];
+    for (int i = 0; i < dn.g_n; ++i) {
+      g.g_A[i] = dn.g_A[i]; g.g_ts[i] = dn.g_ts[i]; g.g_ts_ld[i] = dn.g_ts_ld[i]; g.g_r[i] = dn.g_r[i];
+      g.g_lora_scale[i] = dn.g_lora_scale[i]; g.g_tensor_scale[i] = dn.g_tensor_scale[i];
+    }
+    g.tpart = (uint32_t*)(ws + L.partial_off); g.counters = (uint32_t*)ws + L.n_main_ctr;   // K-parts while token blocks alone do not fill the chip
+    g.ready = (uint32_t*)ws + L.n_main_ctr + L.n_down_ctr;                                   // the hand-over words (zero between calls)
+    g.done = g.ready + 2;
+    g.n_prod = -1;                                                                           // not run yet: the launcher's to place
+  }
+  g.kpartial = (float*)(ws + L.partial_off + kFusedDownBytes); g.kpartial_bytes = gemm_split_bytes(g.M, n_sum);
+  return launch_gemm(g, st);
+}
+
 // More tokens than mid_kernel takes: one launch of the LoRA down-projection for all adapters of the group, then
 // one GEMM launch whose column blocks run over all members (k and v alone would fill half the chip).
 static int gemm_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const qerl_linear_desc* d, int n,
@@ -347,13 +378,9 @@ static int gemm_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, cons
       tiles += (int)ceil_div(d[i].r, 32);
     }
   }
-  if (dn.g_n > 0) {
-    dn.g_tile0[dn.g_n] = tiles;
-    dn.tpart = (uint32_t*)(ws + L.partial_off); dn.counters = (uint32_t*)ws + L.n_main_ctr;   // K-parts while token blocks alone do not fill the chip
-    const int rc = launch_lora_down_gemm(dn, st);
-    if (rc != QERL_OK) return rc;
-  }
-  return launch_gemm(g, st);
+  int64_t n_sum = 0;
+  for (int i = 0; i < n; ++i) n_sum += d[i].N;
+  return gemm_with_down(g, dn, tiles, n_sum, ws, L, st);
 }
 }  // namespace qerl
 
@@ -361,6 +388,7 @@ static int gemm_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, cons
 extern "C" QERL_API void qerl_debug_use_stream(int on) { qerl::g_use_stream = on != 0; }
 extern "C" QERL_API void qerl_debug_mid_producer_bytes(long long b) { qerl::g_mid_producer_bytes = b; }
 extern "C" QERL_API void qerl_debug_mid_gemm_min_rows(long long n) { qerl::g_mid_gemm_min_rows = n; }
+extern "C" QERL_API void qerl_debug_gemm_min_tokens(int m) { qerl::g_gemm_min_tokens = m; }
 #endif  // QERL_TUNING_HOOKS
 
 static int packed_single(const void* x, int64_t M, int64_t K, int64_t ldx, const void* packed,
@@ -398,9 +426,10 @@ extern "C" int nvfp4_lora_linear_packed_group(const void* x, int64_t M, int64_t 
   // the chip with one block of tokens and multiplies faster than the weight-streaming kernel (115 against 181 us
   // for the 32B pair at 128 tokens); the workspace of such a shape holds the GEMM's areas
   const bool wide = M > 64 && n_sum >= g_mid_gemm_min_rows && mid_partial_bytes(M, n_sum) >= kDownExchangeBytes;
-  if (M > 16 && M <= g_mid_max_tokens && mid_ok && !(wide && n_members > 1))
+  const bool to_gemm = M >= g_gemm_min_tokens || M > g_mid_max_tokens || (wide && n_members > 1);
+  if (M > 16 && mid_ok && !to_gemm)
     return mid_group((const uint16_t*)x, M, K, ldx, members, n_members, (uint8_t*)workspace, L, (hipStream_t)stream);
-  if ((M > g_mid_max_tokens || wide) && mid_ok && n_members > 1)
+  if (to_gemm && mid_ok && n_members > 1)
     return gemm_group((const uint16_t*)x, M, K, ldx, members, n_members, (uint8_t*)workspace, L, (hipStream_t)stream);
   for (int i = 0; i < n_members; ++i) {   // general case: member by member
     const qerl_linear_desc& d = members[i];
@@ -484,7 +513,7 @@ static int packed_single(const void* x, int64_t M, int64_t K, int64_t ldx, const
   uint32_t* partial = (uint32_t*)(ws + L.partial_off);
 
   const bool lora_gemm_ok = r == 0 || (r % 8 == 0 && aligned(A, 16) && aligned(B, 16));
-  if (M > 16 && M <= g_mid_max_tokens && lora_gemm_ok) {
+  if (M > 16 && M <= g_mid_max_tokens && M < g_gemm_min_tokens && lora_gemm_ok) {
     qerl_linear_desc d{packed, tensor_scale, N, A, B, r, lora_scale, y, ldy, nullptr, bias};
     return mid_group(c.x, M, K, ldx, &d, 1, ws, L, c.st);
   }
@@ -495,16 +524,17 @@ static int packed_single(const void* x, int64_t M, int64_t K, int64_t ldx, const
     g.x = c.x; g.ldx = ldx; g.M = M; g.K = K; g.k_tiles = ceil_div(K, kPackTileK);
     g.ts = (const uint16_t*)(ws + L.t_off); g.ext_stages = (int)ceil_div(3 * r, 64); g.ts_ld = (int64_t)g.ext_stages * 64;
     g.r = (int)r; g.lora_scale = lora_scale; g.tensor_scale = tensor_scale;
+    GemmArgs dn{};
+    int tiles = 0;
     if (r > 0) {
-      GemmArgs d = g;
-      d.N = r; d.wbf16 = c.A; d.n_tiles = (int)ceil_div(r, 32);
-      d.tpart = partial; d.counters = (uint32_t*)ws + L.n_main_ctr;
-      const int rc = launch_lora_down_gemm(d, c.st);
-      if (rc != QERL_OK) return rc;
+      dn.g_n = 1;
+      dn.g_tile0[0] = 0; dn.g_A[0] = c.A; dn.g_ts[0] = g.ts; dn.g_ts_ld[0] = g.ts_ld; dn.g_r[0] = (int)r;
+      dn.g_lora_scale[0] = lora_scale; dn.g_tensor_scale[0] = tensor_scale;
+      tiles = (int)ceil_div(r, 32);
     }
     g.N = N; g.packed = (const uint8_t*)packed; g.n_tiles = (int)ceil_div(N, 32);
     g.B = c.B; g.y = c.y; g.ldy = ldy; g.bias = (const uint16_t*)bias;
-    return launch_gemm(g, c.st);
+    return gemm_with_down(g, dn, tiles, N, ws, L, c.st);
   }
 
   if (g_use_stream && M <= 16 && (r == 0 || (r <= 64 && r % 8 == 0 && aligned(A, 16) && aligned(B, 16)))) {

@@ -129,6 +129,7 @@ struct GemmMember {
   const uint16_t* bias;                                                     // [N] bf16 or null
   uint16_t* y; int64_t ldy;
   int block_begin;                                                          // first column block of this member (set by the launcher)
+  int64_t col0;                                                             // K split over workgroups: this member's first column in the partial outputs (set by the launcher)
 };
 struct GemmSeg {
   const uint16_t* x; int64_t ldx; int64_t K; const uint8_t* packed; int64_t k_tiles; const float* tensor_scale;
@@ -150,6 +151,17 @@ struct GemmArgs {
   // columns (ts = three terms of lora_scale / S32 * dY B; B = A^T [N, r]).  seg_n == 0: one segment, from the
   // fields above and m[0].
   int seg_n; GemmSeg seg[kMaxGroup];
+  // K split over workgroups (forward launches that would leave most of the chip idle): the caller offers kpartial,
+  // kpartial_bytes of scratch; the launcher decides on ksplit parts, whose sums (LoRA columns in part 0) go there as
+  // fp32 [ksplit][M][kp_ld] and are added in part order, with the bias, by a second small launch.
+  float* kpartial; size_t kpartial_bytes; int ksplit; int m_blocks; int64_t kp_ld;
+  // LoRA down-projections inside a forward launch of few tokens (n_prod > 0): the g_* fields, tpart, counters and
+  // ready describe them as for launch_lora_down_gemm; the first n_prod workgroups (a multiple of 8) compute ts as
+  // lora_down_block does -- token block x rank tile x K-part = p_tbs x p_tiles x p_parts of them, the rest idle --
+  // and the workgroups that carry the LoRA columns wait (bounded) until `ready` has counted p_tbs * p_tiles of
+  // them; every consumer counts itself in `done` when it leaves, the last one zeroes both words for the next call.
+  // The launcher may decline (a shape of ten waves, many tokens) and run the down-projection as a launch of its own.
+  int n_prod; int p_tbs; int p_tiles; int p_parts; uint32_t* done; int n_consumers;
   uint32_t* ready;                                                          // LoRA down-projection inside another kernel's launch: workgroups that have written ts count themselves here (else null)
   uint32_t* tpart; uint32_t* counters;                                      // LoRA down-projection over several K-parts: partial sums, arrival counts (zero between calls); or null
   // LoRA down-projection of a group of adapters that read the same x (g_n > 0): grid.y runs over the 32-row
@@ -158,6 +170,9 @@ struct GemmArgs {
   int g_r[kMaxGroup]; float g_lora_scale[kMaxGroup]; const float* g_tensor_scale[kMaxGroup];
 };
 int launch_gemm(const GemmArgs& a, hipStream_t st);
+constexpr size_t kGemmSplitCap = (size_t)24 << 20;
+constexpr size_t kFusedDownBytes = (size_t)1 << 20;   // K-part sums of down-projections that ride inside a GEMM launch: at most 64 workgroups of one 32 x 32 tile
+size_t gemm_split_bytes(int64_t M, int64_t N_total);   // scratch worth offering launch_gemm as kpartial for this shape (0: it would not split K)
 constexpr int kDownMaxSlots = 256;                                           // workgroups of a K-split LoRA down-projection
 constexpr size_t kDownExchangeBytes = (size_t)16 << 20;   // the K-parts' partial sums (32-token kernel: kDownMaxSlots workgroups of two 32 x 32 tiles; 64-token kernel: up to eight tiles per wave quartet)
 int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st);

@@ -30,6 +30,7 @@
 
 namespace qerl {
 
+constexpr uint32_t kGemmSpinLimit = 1u << 16;   // polls (of ~0.5 us) a workgroup spends on the producers of its launch before it gives up
 constexpr int kGemmRing = 4;    // stages of weights in registers per wave (even)
 constexpr int kGemmXAhead = 2;  // x slabs in registers (divides kGemmRing)
 
@@ -43,8 +44,11 @@ struct WeightRegs {      // one stage = 64 inputs (4 MFMA steps) of NT column ti
 // of W, so the eight weights of a lane and MFMA step carry eight different block scales; the scale bytes of a
 // stage (128 per column tile) ride along with the x slab through LDS.  Used by the backward pass
 // (dX = dY W_hat); everything around the dequantisation step is shared with the forward kernel.
-template <int MT, int NT, int W, bool TR = false>
+// SK: the forward launch of few tokens -- K split over workgroups and / or the LoRA down-projections as its first
+// workgroups; a variant of its own so that the prefill kernel carries none of it.
+template <int MT, int NT, int W, bool TR = false, bool SK = false>
 __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
+  static_assert(!(TR && SK), "the backward launch has no K split");
   constexpr int BM = MT * 32;
   constexpr int kThreads = W * 64;
   constexpr int kChunks = BM * 8;                          // 16-byte chunks of one x slab (BM x 64)
@@ -62,10 +66,27 @@ __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
   // its own L2), so XCD x = id % 8 gets a contiguous eighth of the column blocks and walks them fastest:
   // the ~32 workgroups an XCD runs at a time then share a few x slabs and each weight stripe stays in
   // one L2 instead of eight.
-  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-  const int nb_local = local % a.nblk_per_xcd, mb = local / a.nblk_per_xcd;
+  int bid = (int)blockIdx.x;
+  if constexpr (SK && W <= 8) {
+    if (bid < a.n_prod) {
+      // ---- a LoRA producer: one (token block, rank tile, K-part) of the down-projections; dispatched before
+      // every consumer, waits for nothing but its own loads
+      if (bid >= a.p_tbs * a.p_tiles * a.p_parts) return;
+      const int bx = bid % a.p_tbs, by = (bid / a.p_tbs) % a.p_tiles, bz = bid / (a.p_tbs * a.p_tiles);
+      lora_down_block<1, W>(a, bx, by, bz, a.p_parts, a.p_tbs, a.p_tiles, reinterpret_cast<float*>(xs));
+      return;
+    }
+    bid -= a.n_prod;
+  }
+  const int xcd = bid & 7, local = bid >> 3;
+  const int nb_local = local % a.nblk_per_xcd, mb_all = local / a.nblk_per_xcd;
   const int nb = xcd * a.nblk_per_xcd + nb_local;
   if (nb >= a.n_blocks) return;          // padding of the last XCD's share (uniform per workgroup)
+  // K split over workgroups (forward only): part ks of a.ksplit, token block mb
+  int mb = mb_all, ks = 0;
+  if constexpr (SK) {
+    if (a.ksplit > 1) { ks = mb_all / a.m_blocks; mb = mb_all - ks * a.m_blocks; }
+  }
   const int64_t m0 = (int64_t)mb * BM;
   // the member of the group this column block belongs to: a uniform index into the kernel arguments, so
   // its fields arrive by scalar loads
@@ -84,6 +105,7 @@ __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
   const uint16_t* sB = mem.B;
   const float* sscale = mem.tensor_scale;
 
+  bool poisoned = false;   // a bounded wait gave up: the outputs become NaN
   f32x16 acc[MT][NT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
@@ -212,7 +234,14 @@ __global__ __launch_bounds__(W * 64) void gemm32_kernel(const GemmArgs a) {
     sx = g.x; sldx = g.ldx; sK = g.K; skt = g.k_tiles; spk = g.packed;
     sts = g.ts; sts_ld = g.ts_ld; sext = g.ext_stages; sr = g.r; sB = g.B; sscale = g.tensor_scale;
   }
-  const int64_t s_begin = 0, s_end = ceil_div_dev(sK, 64);
+  int64_t s_begin = 0, s_end = ceil_div_dev(sK, 64);
+  if constexpr (SK) {
+    if (a.ksplit > 1) {                                     // the launcher leaves no part empty
+      const int64_t per = ceil_div_dev(s_end, a.ksplit);
+      s_begin = ks * per;
+      s_end = s_begin + per < s_end ? s_begin + per : s_end;
+    }
+  }
   if (s_begin < s_end) {
     constexpr int R = kGemmRing, PX = kGemmXAhead;
     WeightRegs<NT> wring[R];
@@ -260,7 +289,23 @@ main_done:
   {
     // ---- LoRA up-projection: 3r extra columns  [hi | mid | lo] . [B ; B ; B]^T.  ts already carries
     // the factor lora_scale / S32, so one multiplication by S32 at the end scales both branches.
-    for (int e = 0; e < sext; ++e) {
+    const int n_ext = (!SK || ks == 0) ? sext : 0;         // the LoRA columns belong to the first K-part
+    if constexpr (SK && W <= 8) {
+      if (a.n_prod > 0 && n_ext > 0) {
+        // ts comes from the producers of this launch: wait (bounded) until all of them have published it
+        uint32_t spins = 0;
+        while (__hip_atomic_load(a.ready, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (uint32_t)(a.p_tbs * a.p_tiles)) {
+          if (++spins > kGemmSpinLimit) {   // never reached unless a producer died or was kept off the chip: make it visible
+            poisoned = true;
+            if (tid == 0) __hip_atomic_fetch_or(a.ready + kCtlErr, 4u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            break;
+          }
+          __builtin_amdgcn_s_sleep(32);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      }
+    }
+    for (int e = 0; e < n_ext; ++e) {
       u32x4 xe[XL];
       gload_x(xe, sts, sts_ld, sts_ld, e);
       swrite_x(0, xe);
@@ -295,13 +340,33 @@ main_done:
     }
   }
   }   // segments
+  if constexpr (SK && W <= 8) {
+    if (a.n_prod > 0 && tid == 0) {
+      // the last consumer to leave re-arms the hand-over words (every waiting workgroup has passed its wait by then)
+      const uint32_t old = __hip_atomic_fetch_add(a.done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (old == (uint32_t)(a.n_consumers - 1) && __hip_atomic_load(a.ready + kCtlErr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {   // (not after a wait that gave up)
+        __hip_atomic_store(a.ready, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(a.done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+  }
   {
-    const float S32 = *sscale;
+    const float S32 = (SK && poisoned) ? __uint_as_float(0x7fc00000u) : *sscale;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
         const int64_t n = (int64_t)(nt0 + nt) * 32 + n32;
+        if constexpr (SK) {
+          if (a.ksplit > 1) {                               // this part's sums; gemm_split_reduce_kernel adds the parts and the bias
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int64_t m = m0 + mt * 32 + 8 * (i >> 2) + 4 * kg + (i & 3);
+              if (m < a.M && n < mem.N) a.kpartial[((int64_t)ks * a.M + m) * a.kp_ld + mem.col0 + n] = acc[mt][nt][i] * S32;
+            }
+            continue;
+          }
+        }
         const float bias = (mem.bias && n < mem.N) ? bf16_bits_to_f32(mem.bias[n]) : 0.f;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -462,22 +527,26 @@ __global__ __launch_bounds__(256) void lora_down64_kernel(const GemmArgs a, cons
     const uint32_t* all = a.tpart + (int64_t)tb * kWgFloats + wave * (TPW * 16 * 64) + lane;
 #pragma unroll
     for (int i = 0; i < TPW; ++i) {
-      uint32_t v[kDownMaxParts][16];
 #pragma unroll
-      for (int z = 0; z < kDownMaxParts; ++z)
+      for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+      for (int z0 = 0; z0 < P; z0 += kDownMaxParts) {   // in part order, eight parts requested together
+        uint32_t v[kDownMaxParts][16];
+#pragma unroll
+        for (int z = 0; z < kDownMaxParts; ++z)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            v[z][e] = 0u;
+            if (z0 + z < P) v[z][e] = __hip_atomic_load(all + (int64_t)(z0 + z) * part_stride + (i * 16 + e) * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          v[z][e] = 0u;
-          if (z < P) v[z][e] = __hip_atomic_load(all + (int64_t)z * part_stride + (i * 16 + e) * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          float sum = acc[i][e];
+#pragma unroll
+          for (int z = 0; z < kDownMaxParts; ++z) sum += __uint_as_float(v[z][e]);
+          acc[i][e] = sum;
         }
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        float sum = 0.f;
-#pragma unroll
-        for (int z = 0; z < kDownMaxParts; ++z) sum += __uint_as_float(v[z][e]);
-        acc[i][e] = sum;
+        __builtin_amdgcn_sched_barrier(0);   // one tile's 128 values at a time in registers
       }
-      __builtin_amdgcn_sched_barrier(0);   // one tile's 128 values at a time in registers
     }
     if (tid == 0) __hip_atomic_store(a.counters + tb, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
   }
@@ -526,6 +595,37 @@ __global__ __launch_bounds__(256) void lora_down64_kernel(const GemmArgs a, cons
   }
 }
 
+// ---- K split over workgroups: y = bf16(sum over parts, in part order, + bias) ------------------------------
+struct GemmReduceArgs {
+  const float* partial; int S; int64_t M, ld; int n;
+  int64_t col0[kMaxGroup], N[kMaxGroup], ldy[kMaxGroup]; uint16_t* y[kMaxGroup]; const uint16_t* bias[kMaxGroup];
+};
+// one thread per four consecutive columns of a row (every member's columns start at a multiple of four)
+__global__ __launch_bounds__(256) void gemm_split_reduce_kernel(const GemmReduceArgs a) {
+  const int64_t quads = a.ld / 4, total = a.M * quads;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t m = i / quads, c = (i - m * quads) * 4;
+    int mi = 0;
+#pragma unroll
+    for (int j = 1; j < kMaxGroup; ++j) mi = (j < a.n && c >= a.col0[j]) ? j : mi;
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    for (int z = 0; z < a.S; ++z) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(a.partial + ((int64_t)z * a.M + m) * a.ld + c);
+      sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
+    }
+    int64_t col0 = a.col0[0], N = a.N[0], ldy = a.ldy[0];
+    uint16_t* y = a.y[0];
+    const uint16_t* bias = a.bias[0];
+#pragma unroll
+    for (int j = 1; j < kMaxGroup; ++j)
+      if (mi == j) { col0 = a.col0[j]; N = a.N[j]; ldy = a.ldy[j]; y = a.y[j]; bias = a.bias[j]; }
+    const int64_t n0 = c - col0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (n0 + e < N) y[m * ldy + n0 + e] = (uint16_t)f32_to_bf16_bits(sum[e] + (bias ? bf16_bits_to_f32(bias[n0 + e]) : 0.f));
+  }
+}
+
 // ---- host ------------------------------------------------------------------------------------------
 
 struct GemmConfig { int MT, NT, W, wg_per_cu; float quality, quality_shared, quality_rounds; };
@@ -540,6 +640,24 @@ static const GemmConfig kConfigs[] = {
 };
 static int g_force_cfg = -1;
 static bool g_split = true;   // whole rounds and remainder as two launches when that is estimated faster
+static int g_force_ksplit = 0;   // tuning: K-parts of the forward launch (0 = automatic, 1 = never)
+static int g_fuse_max_tokens = 512;   // up to here the LoRA down-projections run inside the forward launch
+static int g_fuse_wgs = 256;          // producer workgroups aimed at (K-parts until there are that many)
+constexpr int kGemmMaxKsplit = 8;
+constexpr int kGemmMinSplitStages = 8;   // a K-part is at least 512 inputs
+
+// The partial outputs' row length: every member's columns padded to a multiple of four
+static int64_t split_ld(const GemmMember* m, int n) {
+  int64_t ld = 0;
+  for (int i = 0; i < n; ++i) ld += (m[i].N + 3) / 4 * 4;
+  return ld;
+}
+// Shapes worth a K split: fewer than two rounds of 128 x 128 tiles.  The bound covers any member count's padding.
+size_t gemm_split_bytes(int64_t M, int64_t N_total) {
+  if (M < 1 || N_total < 1 || ceil_div(M, 128) * ceil_div(N_total, 128) >= 512) return 0;
+  const size_t b = (size_t)kGemmMaxKsplit * (size_t)M * (size_t)(N_total + 4 * kMaxGroup) * sizeof(float);
+  return b < kGemmSplitCap ? (b + 255) & ~(size_t)255 : kGemmSplitCap;
+}
 
 template <int MT, int NT, int W, bool TR = false>
 static int launch_cfg(const GemmArgs& a, hipStream_t st) {
@@ -552,7 +670,27 @@ static int launch_cfg(const GemmArgs& a, hipStream_t st) {
   }
   b.nblk_per_xcd = (int)ceil_div(b.n_blocks, 8);
   const int64_t m_blocks = ceil_div(a.M, MT * 32);
-  gemm32_kernel<MT, NT, W, TR><<<dim3((unsigned)(8 * b.nblk_per_xcd * m_blocks)), W * 64, lds, st>>>(b);
+  b.m_blocks = (int)m_blocks;
+  if (TR || b.ksplit < 2) b.ksplit = 1;
+  if (TR || W > 8) b.n_prod = 0;   // (launch_gemm has run the down-projection by itself then)
+  b.n_consumers = (int)(b.n_blocks * m_blocks * b.ksplit);
+  const dim3 grid((unsigned)(b.n_prod + 8 * b.nblk_per_xcd * m_blocks * b.ksplit));
+  if constexpr (!TR) {
+    if (b.ksplit > 1 || b.n_prod > 0) gemm32_kernel<MT, NT, W, false, true><<<grid, W * 64, lds, st>>>(b);
+    else gemm32_kernel<MT, NT, W, false, false><<<grid, W * 64, lds, st>>>(b);
+  } else {
+    gemm32_kernel<MT, NT, W, true, false><<<grid, W * 64, lds, st>>>(b);
+  }
+  int rc = launch_status();
+  if (rc != QERL_OK || b.ksplit == 1) return rc;
+  GemmReduceArgs r{};
+  r.partial = b.kpartial; r.S = b.ksplit; r.M = b.M; r.ld = b.kp_ld; r.n = b.m_n;
+  for (int i = 0; i < b.m_n; ++i) {
+    r.col0[i] = b.m[i].col0; r.N[i] = b.m[i].N; r.ldy[i] = b.m[i].ldy; r.y[i] = b.m[i].y; r.bias[i] = b.m[i].bias;
+  }
+  int64_t blocks = ceil_div(b.M * (b.kp_ld / 4), 256);
+  blocks = blocks > 4096 ? 4096 : blocks;
+  gemm_split_reduce_kernel<<<dim3((unsigned)blocks), 256, 0, st>>>(r);
   return launch_status();
 }
 
@@ -574,22 +712,38 @@ int launch_gemm(const GemmArgs& a0, hipStream_t st) {
   // Estimated time of every eligible shape, in units of one output element's K-loop on a fully used chip at
   // quality 1: rounds x slots x tile area / quality.
   const int n_cfg = (int)(sizeof(kConfigs) / sizeof(kConfigs[0]));
-  auto cfg_time = [&](int c, const GemmMember* m, int n) {
+  // The LoRA down-projections of the launch (a.n_prod < 0: described by the g_* fields, not run yet): with few tokens
+  // they ride as the first workgroups of the main launch, hidden behind its K-loop; otherwise, and for the shape
+  // of ten waves, they get their launch here.
+  int64_t prod_wgs = 0;
+  const bool fuse_wanted = a.n_prod < 0 && !a.transposed && a.g_n > 0 && a.ready && a.done && a.M <= g_fuse_max_tokens;
+  if (fuse_wanted) {
+    a.p_tbs = (int)ceil_div(a.M, 32); a.p_tiles = a.g_tile0[a.g_n];
+    const int64_t base_wgs = (int64_t)a.p_tbs * a.p_tiles;
+    int64_t P = (a.tpart && a.counters && base_wgs < g_fuse_wgs) ? g_fuse_wgs / base_wgs : 1;
+    const int64_t p_max = ceil_div(a.K, 512);
+    P = P < p_max ? P : p_max;
+    P = P > kDownMaxPartsWide ? kDownMaxPartsWide : (P < 1 ? 1 : P);
+    a.p_parts = (int)P;
+    prod_wgs = ceil_div(base_wgs * P, 8) * 8;
+  }
+  auto cfg_time = [&](int c, const GemmMember* m, int n, int S = 1) {
     const GemmConfig& g = kConfigs[c];
     const int64_t bm = g.MT * 32, bn = (int64_t)g.W * g.NT * 32;
     int64_t col_blocks = 0;
     for (int i = 0; i < n; ++i) col_blocks += ceil_div(m[i].N, bn);
-    const int64_t wgs = ceil_div(a.M, bm) * col_blocks;
+    const int64_t wgs = ceil_div(a.M, bm) * col_blocks * S + prod_wgs;     // S K-parts: S times the workgroups, each 1 / S of the K-loop
     const bool alone = wgs <= 256;                              // every workgroup gets a CU of its own
     const int64_t slots = alone ? 256 : 256 * g.wg_per_cu;
     const int64_t rounds = ceil_div(wgs, slots);
     const float q = rounds > 1 ? g.quality_rounds : alone ? g.quality : g.quality_shared;
-    return (double)rounds * (double)slots * (double)bm * (double)bn / q;
+    return (double)rounds * (double)slots * (double)bm * (double)bn / q / (double)S;
   };
   auto best_cfg = [&](const GemmMember* m, int n, double& t_best) {
     int best = -1;
     for (int c = 0; c < n_cfg; ++c) {
       if (a.transposed && c != 2 && c != 5) continue;   // the backward pass is instantiated for two shapes
+      if (fuse_wanted && kConfigs[c].W > 8) continue;    // the producers' reduction needs LDS per wave
       const double t = cfg_time(c, m, n);
       if (best < 0 || t < t_best) { t_best = t; best = c; }
     }
@@ -614,6 +768,54 @@ int launch_gemm(const GemmArgs& a0, hipStream_t st) {
   }
   if (a.transposed) return best == 5 ? launch_cfg<4, 1, 10, true>(a, st) : launch_cfg<4, 2, 8, true>(a, st);
   if (g_force_cfg >= 0) best = g_force_cfg;
+  // K split over workgroups when the tiles alone leave most of the chip idle.  In the units above one microsecond is
+  // about 5.6e8 / K; a split costs every workgroup its pipeline fill once more per part, and the second launch.
+  a.ksplit = 1;
+  if (a.kpartial && g_force_ksplit != 1) {
+    const int64_t ld = split_ld(a.m, a.m_n), n_stages = ceil_div(a.K, 64);
+    const double us = 5.6e8 / (double)a.K;
+    double t_best = t_single;
+    for (int c = 0; c < n_cfg; ++c) {
+      if (g_force_cfg >= 0 && c != g_force_cfg) continue;
+      if (fuse_wanted && kConfigs[c].W > 8) continue;
+      for (int S = 2; S <= kGemmMaxKsplit; ++S) {
+        if (g_force_ksplit > 1 && S != g_force_ksplit) continue;
+        const int64_t per = ceil_div(n_stages, S);
+        if (per < kGemmMinSplitStages || per * (S - 1) >= n_stages) continue;       // parts too short, or an empty last part
+        const size_t bytes = (size_t)S * (size_t)a.M * (size_t)ld * sizeof(float);
+        if (bytes > a.kpartial_bytes) continue;
+        const double t = cfg_time(c, a.m, a.m_n, S) + (4.0 + (double)bytes / 3.0e6) * us +      // the second launch: its gap, S reads and one write
+                         2.0 * us * (double)(S - 1) / (double)S;
+        if (t < t_best || (g_force_ksplit > 1 && a.ksplit == 1)) { t_best = t; best = c; a.ksplit = S; }
+      }
+    }
+    if (a.ksplit > 1) {
+      a.kp_ld = ld;
+      int64_t col = 0;
+      for (int i = 0; i < a.m_n; ++i) { a.m[i].col0 = col; col += (a.m[i].N + 3) / 4 * 4; }
+    }
+  }
+  if (a.n_prod < 0) {
+    // measured on 32B shapes at 128 and 256 tokens: worth it where K is split because the tiles alone leave the chip
+    // idle (q + k + v 69 -> 49 us, o 45 -> 37, down 92 -> 82 at 128 tokens); a launch that fills the chip by itself
+    // (gate + up) only loses its first slots to the producers (193 -> 240 us at 256 tokens)
+    bool fuse = fuse_wanted && kConfigs[best].W <= 8 && a.ksplit > 1;
+    if (fuse) {   // everything resident at once: the consumers wait for the producers
+      const GemmConfig& g = kConfigs[best];
+      int64_t col_blocks = 0;
+      for (int i = 0; i < a.m_n; ++i) col_blocks += ceil_div(a.m[i].N, (int64_t)g.W * g.NT * 32);
+      fuse = ceil_div(a.M, g.MT * 32) * col_blocks * a.ksplit + prod_wgs <= 256 * (int64_t)g.wg_per_cu;
+    }
+    if (fuse) {
+      a.n_prod = (int)prod_wgs;
+    } else {
+      GemmArgs dn = a;
+      dn.ready = nullptr;
+      const int rc = launch_lora_down_gemm(dn, st);
+      if (rc != QERL_OK) return rc;
+      a.n_prod = 0;
+    }
+  }
   auto launch_one = [&](int c, const GemmArgs& b) -> int {
 #define QERL_GEMM_CASE(idx, mt, nt, w) \
     if (c == idx) return launch_cfg<mt, nt, w>(b, st);
@@ -626,7 +828,7 @@ int launch_gemm(const GemmArgs& a0, hipStream_t st) {
   // the remaining columns as a launch of their own in whatever shape suits them (smaller tiles fill the chip
   // where a part round of large ones would leave CUs idle).  A member cut by the boundary appears in both
   // launches; the second sees it from a row-tile offset on (the packed tiles of 32 rows are contiguous per row tile).
-  if (g_split && g_force_cfg < 0) {
+  if (g_split && g_force_cfg < 0 && a.ksplit == 1 && a.n_prod == 0) {
     // ~15 us in the units above: the gap between the launches, the second one's fill and drain
     const double overhead = 8.4e9 / (double)a.K;
     double t_split = 0.97 * t_single;   // what a pair of launches has to beat
@@ -707,14 +909,14 @@ static int launch_lora_down64(const GemmArgs& a0, hipStream_t st) {
   const int n_tiles = a.g_tile0[a.g_n];
   const int tpw = (n_tiles + 1) / 2;
   const int64_t tbs = ceil_div(a.M, 64);
-  // K-parts until the chip is full (twice over for a single adapter, whose parts exchange little): at most eight,
+  // K-parts until the chip is full (twice over for a single adapter, whose parts exchange little): at most 32,
   // at least 512 columns each, one arrival counter per token block, and the parts' sums must fit the exchange area
   int64_t P = 1;
   if (a.tpart && a.counters && tbs <= kDownMaxSlots) {
     P = (tpw == 1 ? 512 : 256) / tbs;
     const int64_t p_max = ceil_div(a.K, 512);
     P = P < p_max ? P : p_max;
-    P = P > kDownMaxParts ? kDownMaxParts : (P < 1 ? 1 : P);
+    P = P > kDownMaxPartsWide ? kDownMaxPartsWide : (P < 1 ? 1 : P);
     if (g_down64_parts > 0) P = g_down64_parts;
     while (P > 1 && (size_t)(tbs * P) * 4 * tpw * 16 * 64 * sizeof(float) > kDownExchangeBytes) --P;
   }
@@ -739,11 +941,11 @@ int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st) {
     if (a.M >= g_down64_min_tokens && tiles <= 8 && a.K % 8 == 0) return launch_lora_down64(a, st);
     int64_t P = 1;
     const int64_t base_wgs = ceil_div(a.M, 32) * tiles;
-    if (a.tpart && a.counters && base_wgs < 32) {
-      P = 64 / base_wgs;
-      const int64_t p_max = ceil_div(a.K, 512);
+    if (a.tpart && a.counters && base_wgs <= kDownMaxSlots / 2) {
+      P = (base_wgs < 2 ? 64 : kDownMaxSlots) / base_wgs;
+      const int64_t p_max = ceil_div(a.K, 256);
       P = P < p_max ? P : p_max;
-      P = P > kDownMaxParts ? kDownMaxParts : (P < 1 ? 1 : P);
+      P = P > kDownMaxPartsWide ? kDownMaxPartsWide : (P < 1 ? 1 : P);
     }
     lora_down32_kernel<1><<<dim3((unsigned)ceil_div(a.M, 32), (unsigned)tiles, (unsigned)P), 512, 0, st>>>(a);
     return launch_status();
@@ -752,15 +954,15 @@ int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st) {
   if (a.M < 1 || a.N < 1 || a.K < 8 || a.ts_ld < 3 * a.N) return QERL_ERR_SHAPE;
   const int tiles = (int)ceil_div(a.N, 32);
   if (a.M >= g_down64_min_tokens && tiles <= 8 && a.K % 8 == 0) return launch_lora_down64(a, st);
-  // While token blocks x rank tiles do not fill the chip, K is split over workgroups (up to eight parts, at
-  // least 512 columns each, at most kDownMaxSlots workgroups) when the caller provides the exchange area.
+  // While token blocks x rank tiles do not fill the chip, K is split over workgroups (up to 32 parts, at
+  // least 256 columns each, at most kDownMaxSlots workgroups) when the caller provides the exchange area.
   int64_t P = 1;
   const int64_t base_wgs = ceil_div(a.M, 32) * ceil_div(tiles, tiles >= 2 ? 2 : 1);
   if (a.tpart && a.counters && base_wgs <= kDownMaxSlots / 2) {
-    P = (base_wgs < 32 ? 64 : kDownMaxSlots) / base_wgs;   // a few dozen workgroups for a few tokens, one per CU otherwise
-    const int64_t p_max = ceil_div(a.K, 512);
+    P = (base_wgs < 2 ? 64 : kDownMaxSlots) / base_wgs;    // a few dozen workgroups for a handful of tokens, one per CU otherwise
+    const int64_t p_max = ceil_div(a.K, 256);
     P = P < p_max ? P : p_max;
-    P = P > kDownMaxParts ? kDownMaxParts : (P < 1 ? 1 : P);
+    P = P > kDownMaxPartsWide ? kDownMaxPartsWide : (P < 1 ? 1 : P);
   }
   const dim3 grid((unsigned)ceil_div(a.M, 32), (unsigned)ceil_div(tiles, tiles >= 2 ? 2 : 1), (unsigned)P);
   if (tiles >= 2) lora_down32_kernel<2><<<grid, 512, 0, st>>>(a);
@@ -774,6 +976,9 @@ int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st) {
 #ifdef QERL_TUNING_HOOKS   // built only for tuning sessions: they change process-wide state
 extern "C" QERL_API void qerl_debug_force_gemm(int cfg) { qerl::g_force_cfg = cfg; }
 extern "C" QERL_API void qerl_debug_gemm_split(int on) { qerl::g_split = on != 0; }
+extern "C" QERL_API void qerl_debug_gemm_ksplit(int s) { qerl::g_force_ksplit = s; }
+extern "C" QERL_API void qerl_debug_gemm_fuse_max_tokens(int m) { qerl::g_fuse_max_tokens = m; }
+extern "C" QERL_API void qerl_debug_gemm_fuse_wgs(int n) { qerl::g_fuse_wgs = n; }
 extern "C" QERL_API void qerl_debug_down64_min_tokens(int m) { qerl::g_down64_min_tokens = m; }
 extern "C" QERL_API void qerl_debug_down64_parts(int p) { qerl::g_down64_parts = p; }
 #endif  // QERL_TUNING_HOOKS

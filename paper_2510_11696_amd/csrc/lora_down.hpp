@@ -6,7 +6,8 @@
 
 namespace qerl {
 
-constexpr int kDownMaxParts = 8;   // K-parts of the LoRA down-projection when there are few token blocks
+constexpr int kDownMaxParts = 8;   // K-parts of the LoRA down-projection when there are few token blocks: summed eight at a time
+constexpr int kDownMaxPartsWide = 32;   // ... when it is a launch of its own and would otherwise leave most of the chip idle
 
 // One workgroup of WAVES waves: token block bx (32 tokens), rank tile(s) by, K-part bz of P; gx, gy: numbers of token
 // blocks and tile columns.  red: (WAVES - 1) * NT * 16 * 64 floats of LDS.  With a.ready set, the workgroup that writes
@@ -127,20 +128,24 @@ __device__ __forceinline__ void lora_down_block(const GemmArgs& a, int bx, int b
     const uint32_t* all = a.tpart + (int64_t)slot * (NT * 16 * 64) + lane;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-      uint32_t v[kDownMaxParts][16];        // one tile's values of all parts requested together
 #pragma unroll
-      for (int z = 0; z < kDownMaxParts; ++z)
+      for (int i = 0; i < 16; ++i) acc[nt][i] = 0.f;
+      for (int z0 = 0; z0 < P; z0 += kDownMaxParts) {   // in part order, eight parts requested together
+        uint32_t v[kDownMaxParts][16];
+#pragma unroll
+        for (int z = 0; z < kDownMaxParts; ++z)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            v[z][i] = 0u;
+            if (z0 + z < P) v[z][i] = __hip_atomic_load(all + (int64_t)(z0 + z) * part_stride + (nt * 16 + i) * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          v[z][i] = 0u;
-          if (z < P) v[z][i] = __hip_atomic_load(all + (int64_t)z * part_stride + (nt * 16 + i) * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          float sum = acc[nt][i];
+#pragma unroll
+          for (int z = 0; z < kDownMaxParts; ++z) sum += __uint_as_float(v[z][i]);
+          acc[nt][i] = sum;
         }
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        float sum = 0.f;
-#pragma unroll
-        for (int z = 0; z < kDownMaxParts; ++z) sum += __uint_as_float(v[z][i]);
-        acc[nt][i] = sum;
       }
     }
     if (lane == 0) __hip_atomic_store(a.counters + slot, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call

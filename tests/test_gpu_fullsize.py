@@ -157,9 +157,11 @@ def test_7b_mlp_at_a_few_dozen_tokens_as_the_benchmark_launches_it(mlp_7b, M):
 
 
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("M", [1, 16, 128])
+@pytest.mark.parametrize("M", [1, 16, 128, 300])
 def test_32b_mlp_as_the_benchmark_launches_it(block_32b, M):
-    """32B gate + up (2 x 27648 x 5120: 1728 row tiles) as one group and down (5120 x 27648), r = 64."""
+    """32B gate + up (2 x 27648 x 5120: 1728 row tiles) as one group and down (5120 x 27648), r = 64.  From 96 tokens
+    on the GEMM takes over: down's 40 column blocks split K over workgroups (partial sums added by a second launch)
+    and carry the LoRA down-projection as the launch's first workgroups; 300 tokens: three token blocks, the last ragged."""
     print("full-size 32B MLP,", M, "tokens", flush=True)
     g, u, d = block_32b["gate"], block_32b["up"], block_32b["down"]
     y, y_np, ts = _normed_input(M, 5120, 64000 + M, M <= 16, [g.A, u.A])
@@ -172,7 +174,7 @@ def test_32b_mlp_as_the_benchmark_launches_it(block_32b, M):
 
 
 @pytest.mark.timeout(600)
-@pytest.mark.parametrize("M", [1, 16, 128])
+@pytest.mark.parametrize("M", [1, 16, 128, 300])
 def test_32b_attention_projections_as_the_benchmark_launches_them(block_32b, M):
     """32B q + k + v (rank 64 each: six rank tiles for the fused norm) as one group, and a q-sized single
     linear standing in for o (same shape, its own input, in-launch LoRA producers)."""

@@ -941,11 +941,11 @@ int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st) {
     if (a.M >= g_down64_min_tokens && tiles <= 8 && a.K % 8 == 0) return launch_lora_down64(a, st);
     int64_t P = 1;
     const int64_t base_wgs = ceil_div(a.M, 32) * tiles;
-    if (a.tpart && a.counters && base_wgs <= kDownMaxSlots / 2) {
-      P = (base_wgs < 2 ? 64 : kDownMaxSlots) / base_wgs;
-      const int64_t p_max = ceil_div(a.K, 256);
+    if (a.tpart && a.counters && base_wgs < 32) {
+      P = 64 / base_wgs;
+      const int64_t p_max = ceil_div(a.K, 512);
       P = P < p_max ? P : p_max;
-      P = P > kDownMaxPartsWide ? kDownMaxPartsWide : (P < 1 ? 1 : P);
+      P = P > kDownMaxParts ? kDownMaxParts : (P < 1 ? 1 : P);
     }
     lora_down32_kernel<1><<<dim3((unsigned)ceil_div(a.M, 32), (unsigned)tiles, (unsigned)P), 512, 0, st>>>(a);
     return launch_status();
@@ -954,15 +954,17 @@ int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st) {
   if (a.M < 1 || a.N < 1 || a.K < 8 || a.ts_ld < 3 * a.N) return QERL_ERR_SHAPE;
   const int tiles = (int)ceil_div(a.N, 32);
   if (a.M >= g_down64_min_tokens && tiles <= 8 && a.K % 8 == 0) return launch_lora_down64(a, st);
-  // While token blocks x rank tiles do not fill the chip, K is split over workgroups (up to 32 parts, at
-  // least 256 columns each, at most kDownMaxSlots workgroups) when the caller provides the exchange area.
+  // While token blocks x rank tiles do not fill the chip, K is split over workgroups (up to eight parts, at
+  // least 512 columns each, at most kDownMaxSlots workgroups) when the caller provides the exchange area.
+  // (More and shorter parts were tried for 96..255 tokens: 41 -> 32 us for K = 27648, 19 -> 22 us for K = 5120, and
+  // 1 % lost on the 7B steps at 32 and 64 tokens; those shapes now carry the down-projection inside the GEMM launch.)
   int64_t P = 1;
   const int64_t base_wgs = ceil_div(a.M, 32) * ceil_div(tiles, tiles >= 2 ? 2 : 1);
   if (a.tpart && a.counters && base_wgs <= kDownMaxSlots / 2) {
-    P = (base_wgs < 2 ? 64 : kDownMaxSlots) / base_wgs;    // a few dozen workgroups for a handful of tokens, one per CU otherwise
-    const int64_t p_max = ceil_div(a.K, 256);
+    P = (base_wgs < 32 ? 64 : kDownMaxSlots) / base_wgs;   // a few dozen workgroups for a few tokens, one per CU otherwise
+    const int64_t p_max = ceil_div(a.K, 512);
     P = P < p_max ? P : p_max;
-    P = P > kDownMaxPartsWide ? kDownMaxPartsWide : (P < 1 ? 1 : P);
+    P = P > kDownMaxParts ? kDownMaxParts : (P < 1 ? 1 : P);
   }
   const dim3 grid((unsigned)ceil_div(a.M, 32), (unsigned)ceil_div(tiles, tiles >= 2 ? 2 : 1), (unsigned)P);
   if (tiles >= 2) lora_down32_kernel<2><<<grid, 512, 0, st>>>(a);

@@ -552,3 +552,47 @@ def test_down_projection_on_the_gated_input(M, K, N, r, fused_buffer):
     assert (d == 0).mean() >= 0.9, (d == 0).mean()
     again = qerl.nvfp4_lora_linear_packed_swiglu(gd, ud, pw, Ad, Bd, 2.0)
     assert torch.equal(y, again)
+
+
+@pytest.mark.parametrize("seed", [21, 22, 23])
+def test_random_shapes_where_the_gemm_splits_k(seed):
+    """Seeded random shapes from 96 tokens on with few output columns, where the GEMM splits K over workgroups, adds
+    the parts by a second launch and carries the LoRA down-projections as its first workgroups: ragged token blocks,
+    row tiles and K (any multiple of 16), ranks 0..64, one to three members, with and without bias; each call twice
+    through one workspace (arrival counters and hand-over words are left at zero), bit-equal."""
+    rng = np.random.default_rng(seed)
+    g = lambda a: torch.from_numpy(a).cuda()
+    for it in range(6):
+        M = int(rng.integers(96, 700))
+        K = 16 * int(rng.integers(40, 500))
+        n = int(rng.integers(1, 4))
+        Ns = [8 * int(rng.integers(4, 260)) for _ in range(n)]
+        rs = [int(rng.choice([0, 8, 16, 24, 32, 64])) for _ in range(n)]
+        with_bias = bool(rng.integers(0, 2))
+        print("random split-K case", seed, it, M, K, Ns, rs, with_bias, flush=True)
+        x = qs.activations(M, K, 9500 + seed * 10 + it)
+        ws_, As, Bs, biases, refs = [], [], [], [], []
+        for i, (N, r) in enumerate(zip(Ns, rs)):
+            W = cases.gaussian(N, K, 9600 + seed * 100 + it * 10 + i)
+            codes, scales, ts = oracle.nvfp4_quantize(W)
+            A = B = None
+            if r:
+                A, B = qs.lora_pair(N, K, r, 9700 + seed * 100 + it * 10 + i)
+            bias = (torch.randn(N, generator=torch.Generator().manual_seed(9800 + i)) * 0.5).to(torch.bfloat16) if with_bias else None
+            ws_.append(qerl.nvfp4_prepack(g(codes), g(scales), torch.tensor([ts], device="cuda")))
+            As.append(A.cuda() if r else None)
+            Bs.append(B.cuda() if r else None)
+            biases.append(bias.cuda() if with_bias else None)
+            refs.append(oracle.nvfp4_lora_linear(x.float().numpy(), codes, scales, ts, A.float().numpy() if r else None,
+                                                 B.float().numpy() if r else None, 2.0,
+                                                 bias=bias.float().numpy() if with_bias else None))
+        need = qerl.nvfp4_lora_linear_workspace_bytes(M, sum(Ns), K, sum(rs))
+        ws = qerl.Workspace(need)
+        outs = qerl.nvfp4_lora_linear_packed_group(x.cuda(), ws_, As, Bs, [2.0] * n, workspace=ws, biases=biases)
+        outs = [o.clone() for o in outs]
+        again = qerl.nvfp4_lora_linear_packed_group(x.cuda(), ws_, As, Bs, [2.0] * n, workspace=ws, biases=biases)
+        torch.cuda.synchronize()
+        assert qerl.workspace_status(ws) == 0
+        for i, (y, ref) in enumerate(zip(outs, refs)):
+            check_linear(y, ref, ("random split-K", seed, it, i, M, K, Ns, rs))
+            assert torch.equal(y, again[i])

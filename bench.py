@@ -379,8 +379,13 @@ def cpu_baseline(config_no: int, M: int, budget_s: float = 20.0):
     except AttributeError:
         cores = os.cpu_count()
     threads = min(cores, torch.get_num_threads())
+    flops_names = names
+    counts = {}
+    for n in names:
+        counts[n] = counts.get(n, 0) + 1
+    names = [n if c == 1 else f"{c} x {n}" for n, c in counts.items()]
     if M > 128:
-        flops = sum(2 * M * int(n.split("[")[1].split("x")[0]) * int(n.split("x")[1].rstrip("]")) for n in names)
+        flops = sum(2 * M * int(n.split("[")[1].split("x")[0]) * int(n.split("x")[1].rstrip("]")) for n in flops_names)
         return {"value": round(flops / t_total / 1e12, 5), "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
                 "sample": f"oracle nvfp4_lora_linear (dequantise + fp64 matmul + LoRA), M={M}, on "
                           + ", ".join(names) + f"; {t_total:.1f} s"}

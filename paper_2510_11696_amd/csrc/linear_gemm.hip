@@ -378,13 +378,12 @@ main_done:
 }
 
 // ---- LoRA down-projection for many tokens: ts = three bf16 terms of (lora_scale / S32) * x A^T --------
-// A skinny GEMM (r <= 64 output columns per block) that is bound by reading x once.  One workgroup owns
-// 32 tokens; its eight waves split K in interleaved 64-column chunks, read both operands straight from
-// global memory in MFMA operand layout (double buffered in registers), and are summed through LDS.
-template <int NT>
+// A skinny GEMM (32 output columns per block) that is bound by reading x once.  One workgroup owns 32 tokens and
+// one rank tile; its eight waves take the 64-column slabs of its K-part in turn (lora_down_block) and are summed
+// through LDS.
 __global__ __launch_bounds__(512) void lora_down32_kernel(const GemmArgs a) {
-  __shared__ float red[7 * NT * 16 * 64];
-  lora_down_block<NT, 8>(a, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z, (int)gridDim.z, (int)gridDim.x, (int)gridDim.y, red);
+  __shared__ __attribute__((aligned(16))) float red[kLoraDownLdsBytes(1, 8) / sizeof(float)];
+  lora_down_block<1, 8>(a, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z, (int)gridDim.z, (int)gridDim.x, (int)gridDim.y, red);
 }
 
 // ---- the same product for a few hundred tokens and more ----------------------------------------------
@@ -661,7 +660,9 @@ size_t gemm_split_bytes(int64_t M, int64_t N_total) {
 
 template <int MT, int NT, int W, bool TR = false>
 static int launch_cfg(const GemmArgs& a, hipStream_t st) {
-  constexpr size_t lds = 2 * (size_t)MT * 32 * 8 * sizeof(u32x4) + (TR ? 2 * (size_t)W * NT * 128 : 0);
+  constexpr size_t lds_tiles = 2 * (size_t)MT * 32 * 8 * sizeof(u32x4) + (TR ? 2 * (size_t)W * NT * 128 : 0);
+  constexpr size_t lds_prod = (TR || W > 8) ? 0 : kLoraDownLdsBytes(1, W);   // what a producer workgroup of the few-token variant needs
+  const size_t lds = (a.n_prod > 0 && lds_prod > lds_tiles) ? lds_prod : lds_tiles;
   GemmArgs b = a;
   b.n_blocks = 0;
   for (int i = 0; i < b.m_n; ++i) {
@@ -947,7 +948,7 @@ int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st) {
       P = P < p_max ? P : p_max;
       P = P > kDownMaxParts ? kDownMaxParts : (P < 1 ? 1 : P);
     }
-    lora_down32_kernel<1><<<dim3((unsigned)ceil_div(a.M, 32), (unsigned)tiles, (unsigned)P), 512, 0, st>>>(a);
+    lora_down32_kernel<<<dim3((unsigned)ceil_div(a.M, 32), (unsigned)tiles, (unsigned)P), 512, 0, st>>>(a);
     return launch_status();
   }
   if (!a.x || !a.wbf16 || !a.tensor_scale || !a.ts) return QERL_ERR_NULL;
@@ -959,16 +960,15 @@ int launch_lora_down_gemm(const GemmArgs& a, hipStream_t st) {
   // (More and shorter parts were tried for 96..255 tokens: 41 -> 32 us for K = 27648, 19 -> 22 us for K = 5120, and
   // 1 % lost on the 7B steps at 32 and 64 tokens; those shapes now carry the down-projection inside the GEMM launch.)
   int64_t P = 1;
-  const int64_t base_wgs = ceil_div(a.M, 32) * ceil_div(tiles, tiles >= 2 ? 2 : 1);
+  const int64_t base_wgs = ceil_div(a.M, 32) * tiles;
   if (a.tpart && a.counters && base_wgs <= kDownMaxSlots / 2) {
     P = (base_wgs < 32 ? 64 : kDownMaxSlots) / base_wgs;   // a few dozen workgroups for a few tokens, one per CU otherwise
     const int64_t p_max = ceil_div(a.K, 512);
     P = P < p_max ? P : p_max;
     P = P > kDownMaxParts ? kDownMaxParts : (P < 1 ? 1 : P);
   }
-  const dim3 grid((unsigned)ceil_div(a.M, 32), (unsigned)ceil_div(tiles, tiles >= 2 ? 2 : 1), (unsigned)P);
-  if (tiles >= 2) lora_down32_kernel<2><<<grid, 512, 0, st>>>(a);
-  else lora_down32_kernel<1><<<grid, 512, 0, st>>>(a);
+  const dim3 grid((unsigned)ceil_div(a.M, 32), (unsigned)tiles, (unsigned)P);
+  lora_down32_kernel<<<grid, 512, 0, st>>>(a);
   return launch_status();
 }
 

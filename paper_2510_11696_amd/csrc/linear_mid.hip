@@ -278,7 +278,8 @@ int g_mid_max_tokens = 128;   // token counts above this go to the prefill GEMM
 
 template <int MT, int W>
 static int launch_mid_t(const MidArgs& a, hipStream_t st) {
-  constexpr size_t lds = 2 * (size_t)MT * 32 * 16 * sizeof(u32x4);
+  constexpr size_t lds_tiles = 2 * (size_t)MT * 32 * 16 * sizeof(u32x4);
+  const size_t lds = (a.n_prod > 0 && kLoraDownLdsBytes(1, W) > lds_tiles) ? kLoraDownLdsBytes(1, W) : lds_tiles;
   const int64_t groups = ceil_div(a.n_blocks, 8);
   mid_kernel<MT, W><<<dim3((unsigned)(a.n_prod + groups * 8 * a.m_chunks * a.S)), dim3(W * 64), lds, st>>>(a);
   return launch_status();

@@ -10,8 +10,14 @@ constexpr int kDownMaxParts = 8;   // K-parts of the LoRA down-projection when t
 constexpr int kDownMaxPartsWide = 32;   // ... when it is a launch of its own and would otherwise leave most of the chip idle
 
 // One workgroup of WAVES waves: token block bx (32 tokens), rank tile(s) by, K-part bz of P; gx, gy: numbers of token
-// blocks and tile columns.  red: (WAVES - 1) * NT * 16 * 64 floats of LDS.  With a.ready set, the workgroup that writes
+// blocks and tile columns.  red: kLoraDownLdsBytes(NT, WAVES) of LDS.  With a.ready set, the workgroup that writes
 // ts makes it visible to the whole device and counts itself there.
+// The waves take the 64-column slabs of the K-part in turn.  A slab of x (32 tokens x 128 bytes) and of each rank
+// tile is fetched row-contiguously -- eight lanes per 128-byte row segment, two slabs ahead in registers -- and
+// reaches the MFMA operand layout (one row per lane) through a wave-private LDS area (row-XOR swizzle as in the
+// GEMM's x slab; no barrier: a wave's LDS operations complete in order).  Fetching in operand layout instead, 16
+// bytes of 64 different rows per instruction, is served at an eighth of the rate.
+constexpr size_t kLoraDownLdsBytes(int NT, int WAVES) { return (size_t)WAVES * (1 + NT) * 4096; }
 template <int NT, int WAVES>
 __device__ __forceinline__ void lora_down_block(const GemmArgs& a, int bx, int by, int bz, int P, int gx, int gy, float* red) {
   constexpr int kWaves = WAVES;
@@ -40,30 +46,60 @@ __device__ __forceinline__ void lora_down_block(const GemmArgs& a, int bx, int b
       }
     first_tile = nt0 == 0;
   }
-  int64_t mrow = m0 + n32;
-  mrow = mrow < a.M ? mrow : a.M - 1;
-  const uint16_t* xrow = a.x + mrow * a.ldx + 8 * kg;
 
   // K-part of this workgroup (P parts, whole 64-column chunks each)
   const int64_t part_cols = ceil_div_dev(ceil_div_dev(a.K, 64), P) * 64;
   const int64_t k_lo = (int64_t)bz * part_cols;
   const int64_t k_hi = k_lo + part_cols < a.K ? k_lo + part_cols : a.K;
 
-  struct Chunk { u32x4 x[4]; u32x4 w[NT][4]; };   // 64 columns = 4 MFMA steps
-  auto load = [&](Chunk& c, int64_t kb) {
+  struct Chunk { u32x4 x[4]; u32x4 w[NT][4]; };   // 64 columns = 4 MFMA steps: as requested (instruction i: row 8 i + lane / 8,
+                                                   // 16-byte segment lane % 8) or as operands (step j: row lane % 32, columns 16 j + 8 (lane / 32))
+  const int seg = lane & 7, rr = lane >> 3;
+  const uint16_t* xsrc[4];
+  const uint16_t* asrc[NT][4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int64_t k = kb + 16 * j + 8 * kg;
-      c.x[j] = u32x4{0u, 0u, 0u, 0u};
-      if (k < k_hi) c.x[j] = *reinterpret_cast<const u32x4*>(xrow + kb + 16 * j);
+  for (int i = 0; i < 4; ++i) {
+    int64_t m = m0 + 8 * i + rr;
+    m = m < a.M ? m : a.M - 1;
+    xsrc[i] = a.x + m * a.ldx + 8 * seg;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      int64_t row = (int64_t)(nt0 + nt) * 32 + 8 * i + rr;
+      row = row < rN ? row : rN - 1;
+      asrc[nt][i] = Aw + row * a.K + 8 * seg;
+    }
+  }
+  auto request = [&](Chunk& c, int64_t kb) {       // past the part's end: zeros, no access
+    const bool in = kb + 8 * seg < k_hi;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      c.x[i] = u32x4{0u, 0u, 0u, 0u};
+      if (in) c.x[i] = *reinterpret_cast<const u32x4*>(xsrc[i] + kb);
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
-        int64_t row = (int64_t)(nt0 + nt) * 32 + n32;
-        row = row < rN ? row : rN - 1;
-        c.w[nt][j] = u32x4{0u, 0u, 0u, 0u};
-        if (k < k_hi) c.w[nt][j] = *reinterpret_cast<const u32x4*>(Aw + row * a.K + k);
+        c.w[nt][i] = u32x4{0u, 0u, 0u, 0u};
+        if (in) c.w[nt][i] = *reinterpret_cast<const u32x4*>(asrc[nt][i] + kb);
       }
     }
+  };
+  u32x4* stage = reinterpret_cast<u32x4*>(red) + wave * (1 + NT) * 256;   // this wave's slabs: 256 chunks of 16 bytes each
+  auto to_operands = [&](Chunk& c) {               // in place: the requested slab becomes the MFMA fragments
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = 8 * i + rr, at = row * 8 + (seg ^ ((row >> 1) & 7));
+      stage[at] = c.x[i];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) stage[(1 + nt) * 256 + at] = c.w[nt][i];
+    }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int at = n32 * 8 + ((2 * j + kg) ^ ((n32 >> 1) & 7));
+      c.x[j] = stage[at];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) c.w[nt][j] = stage[(1 + nt) * 256 + at];
+    }
+    __builtin_amdgcn_wave_barrier();
   };
   f32x16 acc[NT];
 #pragma unroll
@@ -81,18 +117,23 @@ __device__ __forceinline__ void lora_down_block(const GemmArgs& a, int bx, int b
   Chunk c0, c1;
   const int64_t step = (int64_t)kWaves * 64;
   int64_t kb = k_lo + (int64_t)wave * 64;
-  if (kb < k_hi) load(c0, kb);
-  while (kb < k_hi) {
-    const bool has1 = kb + step < k_hi;
-    if (has1) load(c1, kb + step);
-    mma(c0);
-    if (!has1) break;
-    const bool has2 = kb + 2 * step < k_hi;
-    if (has2) load(c0, kb + 2 * step);
-    mma(c1);
-    kb += 2 * step;
-    if (!has2) break;
+  if (kb < k_hi) {
+    request(c0, kb);
+    request(c1, kb + step);
   }
+  while (kb < k_hi) {
+    Chunk f = c0;
+    request(c0, kb + 2 * step);
+    to_operands(f);
+    mma(f);
+    if (kb + step >= k_hi) break;
+    f = c1;
+    request(c1, kb + 3 * step);
+    to_operands(f);
+    mma(f);
+    kb += 2 * step;
+  }
+  __syncthreads();   // the staging areas become the reduction's
 
   if (wave > 0) {
 #pragma unroll

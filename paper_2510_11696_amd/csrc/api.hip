@@ -307,9 +307,11 @@ static int mid_group(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const
     dn.counters = (uint32_t*)ws + L.n_main_ctr;
     int64_t packed_bytes = 0;
     for (int i = 0; i < n; ++i) packed_bytes += (int64_t)g.mem[i].n_tiles * g.k_tiles * kPackTileBytes;
-    // measured on 7B shapes: above 64 tokens it always pays (7.5 against 8.2 ms per step at 128); below, only where the
-    // main launch runs long enough to hide producers of two or four waves (gate + up, down: 1-2 % of the step)
-    if (few && (M > 64 || packed_bytes >= g_mid_producer_bytes)) {
+    // measured on 7B shapes: above 64 tokens it always pays (7.5 against 8.2 ms per step at 128); below, where the
+    // main launch runs long enough to hide producers of two or four waves (gate + up, down: 1-2 % of the step), for
+    // a single adapter (o: 24.9 -> 24.6 us at 32 tokens, 29.9 -> 28.8 at 64; 32B 37.3 -> 32.8) and for groups from 33
+    // tokens on (q + k + v 34.8 -> 31.7 us at 64 tokens, but 30.1 -> 36.4 at 32)
+    if (few && (M > 32 || dn.g_n == 1 || packed_bytes >= g_mid_producer_bytes)) {
       // the down-projections run as the first workgroups of the main launch: token blocks x rank tiles x K-parts
       // (parts as the stand-alone launch would choose them: a few dozen workgroups, at least 512 columns each)
       const int64_t base_wgs = ceil_div(M, 32) * tiles;
